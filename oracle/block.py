@@ -1,0 +1,276 @@
+"""CPU oracle of the mixed-resolution denoising block: each image whole and unpatched.
+
+TEST INFRASTRUCTURE ONLY.  This is the slow, plain definition the HIP path is
+checked against.  It shares no code with the HIP path, is imported only by the
+tests, the smoke check and the CPU-baseline leg of the benchmark, and must never
+be used by the product path.
+
+The paper's claim is that running operators on a batch of equal patches of
+mixed-resolution images gives the result of running every image on its own
+(Patched Inference section; for the convolution-free model the evaluation table
+reports PSNR inf / SSIM 1.0 for every patch size).  The method therefore reaches,
+up to rounding order, a result with a plain definition, and the oracle is that
+definition written out: every function takes ONE image as a float64 array
+[C, H, W] and never forms patches, neighbour tables, halos or sequence offsets.
+A library matrix product (numpy.matmul) serves as a step; there is no blocking,
+fusion or reordering beyond splitting independent query rows into chunks to bound
+memory.
+
+Readings of points the paper leaves open (each also listed in the design notes):
+  * GroupNorm statistics are taken over the whole image (all its patches), biased
+    variance, eps = 1e-5, per-channel affine.
+  * "pad with 0 when a neighbour is absent" (Patch-Tailored Diffusion Operators)
+    == ordinary zero padding 1 at the true image border.
+  * attention: scale 1/sqrt(d), no mask, no positional term (Patch-based
+    Self-Attention Module: every query meets all keys of its own image).
+  * GELU is the exact erf form; the GEGLU value half comes first, the gate half second.
+  * cache reuse (Patch-aware Caching Strategy, steps 3-5): at each operator that
+    needs context the operand of a reused patch is the cached tensor of the
+    previous step; after the block the reused patches of the output are replaced by
+    the cached output; the cache then holds fresh values on computed patches.
+
+Pins (tests/test_oracle_pins.py): 7-loop direct convolution, delta and all-ones
+kernels (closed forms fix padding and tap orientation), GroupNorm moments and
+shift/scale invariance, three-pass softmax attention, uniform-attention special
+case, permutation equivariance, printed constants SiLU(1), GELU(1), and
+independent torch CPU library routines.  Absolute block outputs have no value
+printed in the paper: "parity unpinned" beyond these pins and the invariants
+one-patch == unpatched and patched == per-image.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+from scipy.special import erf as _erf
+
+F64 = np.float64
+
+
+# ----------------------------------------------------------------------------- pointwise
+def silu(u: np.ndarray) -> np.ndarray:
+    """SiLU(u) = u / (1 + exp(-u))."""
+    return u / (1.0 + np.exp(-u))
+
+
+def gelu(u: np.ndarray) -> np.ndarray:
+    """GELU(u) = u/2 * (1 + erf(u / sqrt 2)) (exact form)."""
+    return 0.5 * u * (1.0 + _erf(u / np.sqrt(2.0)))
+
+
+# ----------------------------------------------------------------------------- GroupNorm
+def group_norm(u: np.ndarray, gamma: np.ndarray, beta: np.ndarray, G: int, eps: float) -> np.ndarray:
+    """GroupNorm over one whole image u[C, H, W].
+
+    Group g holds channels g*C/G .. (g+1)*C/G-1; mean and biased variance run over
+    all H*W*C/G elements of the group (the whole image, not a patch).
+    """
+    C, H, W = u.shape
+    cg = C // G
+    out = np.empty_like(u, dtype=F64)
+    for g in range(G):
+        blk = u[g * cg:(g + 1) * cg].astype(F64)
+        mu = blk.mean()
+        var = ((blk - mu) ** 2).mean()
+        xh = (blk - mu) / np.sqrt(var + eps)
+        out[g * cg:(g + 1) * cg] = xh * gamma[g * cg:(g + 1) * cg, None, None] \
+            + beta[g * cg:(g + 1) * cg, None, None]
+    return out
+
+
+# ----------------------------------------------------------------------------- convolution
+def conv3(u: np.ndarray, W: np.ndarray, b: np.ndarray) -> np.ndarray:
+    """3x3 cross-correlation, stride 1, zero padding 1.
+
+    out[co, y, x] = b[co] + sum_{ci, ky, kx} u[ci, y+ky-1, x+kx-1] * W[co, ci, ky, kx],
+    with u taken as 0 outside the image.  One matrix product per tap.
+    """
+    Ci, H, Wd = u.shape
+    Co = W.shape[0]
+    up = np.zeros((Ci, H + 2, Wd + 2), dtype=F64)
+    up[:, 1:H + 1, 1:Wd + 1] = u
+    out = np.zeros((Co, H * Wd), dtype=F64)
+    for ky in range(3):
+        for kx in range(3):
+            window = up[:, ky:ky + H, kx:kx + Wd].reshape(Ci, H * Wd)
+            out += W[:, :, ky, kx].astype(F64) @ window
+    out += b.astype(F64)[:, None]
+    return out.reshape(Co, H, Wd)
+
+
+# ----------------------------------------------------------------------------- attention
+def attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, heads: int,
+              rows: Optional[np.ndarray] = None, chunk: int = 1024) -> np.ndarray:
+    """Multi-head softmax attention over one token set.
+
+    Q [Nq, C], K [Nk, C], V [Nk, C]; head h uses channel slice h*d .. (h+1)*d-1.
+    O_h = softmax_rows(Q_h K_h^T / sqrt(d)) V_h.  `rows` selects query rows (each
+    row is independent of the others); query rows are processed in chunks only to
+    bound memory.
+    """
+    if rows is not None:
+        Q = Q[rows]
+    Nq, C = Q.shape
+    d = C // heads
+    out = np.empty((Nq, C), dtype=F64)
+    for h in range(heads):
+        Kh = K[:, h * d:(h + 1) * d].astype(F64)
+        Vh = V[:, h * d:(h + 1) * d].astype(F64)
+        for r0 in range(0, Nq, chunk):
+            Qh = Q[r0:r0 + chunk, h * d:(h + 1) * d].astype(F64)
+            S = (Qh @ Kh.T) / np.sqrt(float(d))
+            S -= S.max(axis=1, keepdims=True)
+            E = np.exp(S)
+            A = E / E.sum(axis=1, keepdims=True)
+            out[r0:r0 + chunk, h * d:(h + 1) * d] = A @ Vh
+    return out
+
+
+def _tokens(u: np.ndarray) -> np.ndarray:
+    """[C, H, W] -> [H*W, C] (token n = y*W + x)."""
+    C, H, W = u.shape
+    return u.reshape(C, H * W).T
+
+
+def _image(t: np.ndarray, H: int, W: int) -> np.ndarray:
+    return t.T.reshape(t.shape[1], H, W)
+
+
+def _fill(fresh: np.ndarray, cached: Optional[np.ndarray], reuse_px: Optional[np.ndarray]) -> np.ndarray:
+    """Operand-fill rule: cached values on reused pixels, fresh values elsewhere ([C, H, W])."""
+    if reuse_px is None:
+        return fresh
+    return np.where(reuse_px[None, :, :], cached.astype(F64), fresh)
+
+
+# ----------------------------------------------------------------------------- stages
+def res1(x, p, G, eps):
+    """RES1(x) = x + conv3(SiLU(GN(x)))."""
+    return x + conv3(silu(group_norm(x, p["gn_g"], p["gn_b"], G, eps)), p["conv_w"], p["conv_b"])
+
+
+def res2(x, p, G, eps, reuse_px=None, cache=None, key="", new_cache=None):
+    """RES2(x) = x + conv3_b(SiLU(GN_b(h1))),  h1 = conv3_a(SiLU(GN_a(x))).
+
+    With reuse, h1 of reused patches is the cached h1 (it feeds GN_b statistics and
+    the halos of conv_b).
+    """
+    h1 = conv3(silu(group_norm(x, p["gn_a_g"], p["gn_a_b"], G, eps)), p["conv_a_w"], p["conv_a_b"])
+    if reuse_px is not None:
+        h1 = _fill(h1, cache[key + "h1"], reuse_px)
+        new_cache[key + "h1"] = h1
+    return x + conv3(silu(group_norm(h1, p["gn_b_g"], p["gn_b_b"], G, eps)), p["conv_b_w"], p["conv_b_b"])
+
+
+def sattn(x, p, G, heads, eps, reuse_px=None, cache=None, key="", new_cache=None, rows=None):
+    """SATTN(x) = x + concat_h(softmax(Q_h K_h^T / sqrt d) V_h) W_o + b_o, Q/K/V = GN(x) W_{q,k,v}.
+
+    With reuse, the stage input ("r"), K and V of reused patches come from the cache.
+    Returns tokens [N or len(rows), C] when rows is given, else an image [C, H, W].
+    """
+    C, H, W = x.shape
+    if reuse_px is not None:
+        x = _fill(x, cache[key + "r"], reuse_px)
+        new_cache[key + "r"] = x
+    u = _tokens(group_norm(x, p["gn_g"], p["gn_b"], G, eps))
+    Q = u @ p["wq"].astype(F64)
+    K = u @ p["wk"].astype(F64)
+    V = u @ p["wv"].astype(F64)
+    if reuse_px is not None:
+        K = _tokens(_fill(_image(K, H, W), cache[key + "K"], reuse_px))
+        V = _tokens(_fill(_image(V, H, W), cache[key + "V"], reuse_px))
+        new_cache[key + "K"] = _image(K, H, W)
+        new_cache[key + "V"] = _image(V, H, W)
+    O = attention(Q, K, V, heads, rows=rows)
+    xt = _tokens(x) if rows is None else _tokens(x)[rows]
+    yt = xt + O @ p["wo"].astype(F64) + p["bo"].astype(F64)
+    return yt if rows is not None else _image(yt, H, W)
+
+
+def xattn_tokens(xt, p, heads, ctx):
+    """XATTN on tokens [N, C]: queries from x, keys/values from the image's own text tokens."""
+    Q = xt @ p["wq"].astype(F64)
+    K = ctx.astype(F64) @ p["wk"].astype(F64)
+    V = ctx.astype(F64) @ p["wv"].astype(F64)
+    O = attention(Q, K, V, heads)
+    return xt + O @ p["wo"].astype(F64) + p["bo"].astype(F64)
+
+
+def ffn_tokens(xt, p):
+    """FFN(x) = x + (a * GELU(g)) W_2 + b_2, [a | g] = x W_1 + b_1 (value half first)."""
+    h = xt @ p["w1"].astype(F64) + p["b1"].astype(F64)
+    F = h.shape[1] // 2
+    return xt + (h[:, :F] * gelu(h[:, F:])) @ p["w2"].astype(F64) + p["b2"].astype(F64)
+
+
+# ----------------------------------------------------------------------------- whole block
+def block_forward(z: np.ndarray, stages: Sequence[str], params: List[Dict[str, np.ndarray]], *,
+                  G: int, heads: int, eps: float = 1e-5, ctx: Optional[np.ndarray] = None,
+                  reuse: Optional[np.ndarray] = None, cache: Optional[Dict[str, np.ndarray]] = None,
+                  rows: Optional[np.ndarray] = None):
+    """Run the stage list on ONE image z[C, H, W]; returns (out, new_cache).
+
+    reuse: bool [gh, gw] over the image's patch grid (True = reuse the cached
+    patch); cache: slot name -> [C, H, W] for this image ("<stage>.h1",
+    "<stage>.r", "<stage>.K", "<stage>.V", "y").  new_cache holds every slot after
+    the call (fresh on computed patches, unchanged on reused ones).
+    rows: optional token subset (n = y*W + x); allowed when every stage from the
+    last SATTN on acts per token; then out is [len(rows), C].
+    """
+    x = np.asarray(z, dtype=F64)
+    C, H, W = x.shape
+    reuse_px = None
+    new_cache: Dict[str, np.ndarray] = {}
+    if reuse is not None:
+        gh, gw = reuse.shape
+        reuse_px = np.repeat(np.repeat(np.asarray(reuse, dtype=bool), H // gh, axis=0), W // gw, axis=1)
+    tokens = None                      # set once only sampled rows are carried
+    if rows is not None:
+        last_ctx = max(i for i, s in enumerate(stages) if s in ("RES1", "RES2", "SATTN"))
+        assert stages[last_ctx] == "SATTN", "rows need a SATTN as the last context stage"
+    for si, (st, p) in enumerate(zip(stages, params)):
+        key = f"{si}."
+        if st == "RES1":
+            x = res1(x, p, G, eps)
+        elif st == "RES2":
+            x = res2(x, p, G, eps, reuse_px, cache, key, new_cache)
+        elif st == "SATTN":
+            if rows is not None and si == last_ctx:
+                tokens = sattn(x, p, G, heads, eps, reuse_px, cache, key, new_cache, rows=rows)
+            else:
+                x = sattn(x, p, G, heads, eps, reuse_px, cache, key, new_cache)
+        elif st == "XATTN":
+            if tokens is not None:
+                tokens = xattn_tokens(tokens, p, heads, ctx)
+            else:
+                x = _image(xattn_tokens(_tokens(x), p, heads, ctx), H, W)
+        elif st == "FFN":
+            if tokens is not None:
+                tokens = ffn_tokens(tokens, p)
+            else:
+                x = _image(ffn_tokens(_tokens(x), p), H, W)
+        else:
+            raise ValueError(st)
+    if tokens is not None:
+        if reuse_px is not None:
+            ry = _tokens(cache["y"].astype(F64))[rows]
+            m = reuse_px.reshape(-1)[rows]
+            tokens = np.where(m[:, None], ry, tokens)
+        return tokens, new_cache
+    if reuse_px is not None:
+        x = _fill(x, cache["y"], reuse_px)
+        new_cache["y"] = x
+    return x, new_cache
+
+
+def forward_batch(images, stages, params, *, G, heads, eps=1e-5, ctx=None, reuse=None, cache=None):
+    """Run block_forward on every image of a batch, one at a time (caller order)."""
+    outs, caches = [], []
+    for i, z in enumerate(images):
+        c_i = None if cache is None else {k: v[i] for k, v in cache.items()}
+        y, nc = block_forward(z, stages, params, G=G, heads=heads, eps=eps,
+                              ctx=None if ctx is None else ctx[i],
+                              reuse=None if reuse is None else reuse[i], cache=c_i)
+        outs.append(y)
+        caches.append(nc)
+    return outs, caches
