@@ -1,0 +1,183 @@
+/*
+ * pserve — one denoising block over a batch of mixed-resolution latents cut into
+ * equal patches (PatchedServe, arXiv 2501.09253, section "Patched Inference with
+ * Batching" and section "Exploiting Patch-Level Locality").
+ *
+ * C ABI of libpserve.so.  Every entry point is extern "C", takes plain pointers and
+ * sizes, returns an int status (0 = PSERVE_OK, negative = error) and never throws or
+ * aborts.  pserve_last_error() gives a thread-local description of the last failure.
+ *
+ * Conventions
+ *   - "device" pointers are HIP device memory of the current device; "host" pointers
+ *     are ordinary process memory.  `stream` is a hipStream_t passed as void*
+ *     (NULL = the default stream).  All device work is enqueued on `stream` and is
+ *     asynchronous; errors detectable on the host are returned synchronously.
+ *   - Per-request arrays (resolutions, images, text context) are in CALLER order.
+ *     Per-patch arrays (reuse mask, tables) are in PLAN order (requests sorted by
+ *     resolution; use the PERM / PATCH_OWNER / PATCH_RC tables to map).
+ *   - Activations are token-major, channels-last, patch-major: x[T][C] with token id
+ *     t = patch*ph*pw + y*pw + x.  dtype is PSERVE_F32 (float) or PSERVE_BF16
+ *     (bfloat16 storage, float accumulation); every tensor of a block, parameters
+ *     included, has the block's dtype.
+ *   - The caller owns x, y, images, parameters, ctx and masks.  The library owns plan
+ *     tables, packed weights and cache / scratch buffers; pserve_block_forward
+ *     allocates nothing.
+ */
+#ifndef PSERVE_H
+#define PSERVE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PSERVE_OK       0
+#define PSERVE_EINVAL  (-1)   /* bad argument (shape, divisibility, NULL, unsupported dtype/stage) */
+#define PSERVE_ENOMEM  (-2)   /* host or device allocation failed */
+#define PSERVE_EHIP    (-3)   /* a HIP runtime call failed */
+#define PSERVE_ESTATE  (-4)   /* object used in a state that does not allow the call */
+
+#define PSERVE_F32   0
+#define PSERVE_BF16  1
+
+/* stage kinds of the block grammar */
+#define PSERVE_RES1   1   /* x + conv3(SiLU(GN(x)))                                    params: gn_g gn_b conv_w conv_b */
+#define PSERVE_RES2   2   /* x + conv3_b(SiLU(GN_b(conv3_a(SiLU(GN_a(x))))))            params: gn_a_g gn_a_b conv_a_w conv_a_b gn_b_g gn_b_b conv_b_w conv_b_b */
+#define PSERVE_SATTN  3   /* x + MHA(GN(x))W_o + b_o, keys = all tokens of the own image params: gn_g gn_b wq wk wv wo bo */
+#define PSERVE_XATTN  4   /* x + MHA(x W_q; ctx W_k, ctx W_v)W_o + b_o                  params: wq wk wv wo bo */
+#define PSERVE_FFN    5   /* x + (a * GELU(g))W_2 + b_2, [a|g] = x W_1 + b_1            params: w1 b1 w2 b2 */
+
+#define PSERVE_MAX_STAGES 8
+#define PSERVE_MAX_PARAMS 8
+
+/* plan tables (int32) for pserve_plan_table */
+#define PSERVE_TAB_PERM            0   /* [n]      caller index of sorted slot s */
+#define PSERVE_TAB_REQUEST_OFFSET  1   /* [n+1]    first patch of sorted slot s (RequestOffset of the CSP format) */
+#define PSERVE_TAB_RES_OFFSET      2   /* [R+1]    first sorted slot of each distinct resolution */
+#define PSERVE_TAB_RES_HW          3   /* [R][2]   the distinct resolutions (H, W), ascending */
+#define PSERVE_TAB_PATCH_OWNER     4   /* [P]      sorted slot owning patch p (the per-patch request index) */
+#define PSERVE_TAB_PATCH_RC        5   /* [P][2]   (row, col) of patch p in its image's patch grid */
+#define PSERVE_TAB_NEIGHBOUR       6   /* [P][8]   patch ids NW N NE W E SW S SE, -1 = absent (zero fill) */
+#define PSERVE_TAB_HALO_SRC        7   /* [P][2(pw+2)+2ph] global token id of each ring pixel, -1 = outside the image;
+                                          ring order: top row x=-1..pw, bottom row x=-1..pw, left col y=0..ph-1, right col y=0..ph-1 */
+#define PSERVE_TAB_CU_SEQLENS      8   /* [n+1]    first token of sorted slot s */
+#define PSERVE_TAB_COUNT           9
+
+/* cache slots of a stage (pserve_cache_load / pserve_cache_read); stage = -1 addresses the block output slot */
+#define PSERVE_SLOT_H1  0   /* RES2: output of the first convolution */
+#define PSERVE_SLOT_R   1   /* SATTN: stage input */
+#define PSERVE_SLOT_K   2   /* SATTN: keys */
+#define PSERVE_SLOT_V   3   /* SATTN: values */
+#define PSERVE_SLOT_Y   4   /* block output (use stage = -1) */
+
+typedef struct pserve_plan_s pserve_plan_t;    /* CSP tables of one batch composition (host + device copies) */
+typedef struct pserve_block_s pserve_block_t;   /* block description + packed weights */
+typedef struct pserve_cache_s pserve_cache_t;   /* per (plan, block): cached operand tensors + scratch */
+
+typedef struct {
+    int32_t n;        /* requests */
+    int32_t R;        /* distinct resolutions */
+    int32_t P;        /* patches */
+    int32_t ph, pw;   /* patch height / width (latent pixels) */
+    int32_t ring;     /* 2(pw+2)+2ph, entries of HALO_SRC per patch */
+    int64_t T;        /* tokens = P*ph*pw */
+} pserve_plan_info_t;
+
+typedef struct {
+    int32_t n_stages;
+    int32_t stages[PSERVE_MAX_STAGES];   /* PSERVE_RES1 .. PSERVE_FFN, in execution order */
+    int32_t C;          /* channels */
+    int32_t G;          /* GroupNorm groups (C % G == 0) */
+    int32_t heads;      /* attention heads (C % heads == 0) */
+    int32_t dtype;      /* PSERVE_F32 | PSERVE_BF16 */
+    float   eps;        /* GroupNorm epsilon */
+    int32_t ctx_len;    /* text tokens per request (XATTN), else 0 */
+    int32_t ctx_dim;    /* width of a text token (XATTN), else 0 */
+    int32_t ffn_mult;   /* FFN hidden width = ffn_mult*C (W_1 is C x 2*ffn_mult*C) */
+} pserve_block_desc;
+
+/* Device pointers of the parameters of every stage, in the order listed beside the
+ * stage kinds above.  Layouts: conv weights W[Cout][Cin][3][3] (cross-correlation,
+ * zero padding 1); linear weights W[Cin][Cout] (y = x W); vectors [C]. */
+typedef struct {
+    const void* p[PSERVE_MAX_STAGES][PSERVE_MAX_PARAMS];
+} pserve_block_params;
+
+const char* pserve_last_error(void);
+
+/* ---- planner: Compressed Sparse Patch tables ("Compressed Sparse Patch Format") and
+ * per-patch neighbour metadata ("Patch-Tailored Diffusion Operators", patch-based
+ * convolution).  resolutions_hw: HOST int32 [n][2] = (H, W) in latent pixels, caller
+ * order.  ph = pw = 0 selects the greatest common divisor of all heights resp. widths
+ * (the paper's patch-size rule).  Requests are sorted ascending by (H, W), stable.
+ * The tables are built by device kernels on `stream`; the call returns after they are
+ * complete (it synchronises the stream once to mirror them on the host).
+ * Errors: EINVAL for n <= 0, non-positive sizes, H % ph != 0, W % pw != 0, or more
+ * than 2^31-1 tokens; ENOMEM; EHIP.  *out is owned by the caller until pserve_plan_free. */
+int  pserve_plan(const int32_t* resolutions_hw, int32_t n, int32_t ph, int32_t pw,
+                 void* stream, pserve_plan_t** out);
+void pserve_plan_free(pserve_plan_t* plan);
+int  pserve_plan_info(const pserve_plan_t* plan, pserve_plan_info_t* out);
+/* Borrowed pointer to a table (valid until pserve_plan_free): on_device != 0 gives the
+ * device copy, else the host mirror.  *count = number of int32 entries. */
+int  pserve_plan_table(const pserve_plan_t* plan, int which, int on_device,
+                       const int32_t** ptr, int64_t* count);
+
+/* ---- split / reassembly (patch splitting of "Compressed Sparse Patch Format";
+ * rebuilding full images from patches, "Patch-based Self-Attention Module").
+ * images: HOST array of n DEVICE pointers, image i is NCHW [C][H_i][W_i] in caller
+ * order; x / y: DEVICE [T][C].  Pure copies: bit-exact.  dtype as above. */
+int  pserve_split(const pserve_plan_t* plan, const void* const* images, int32_t C, int dtype,
+                  void* x, void* stream);
+int  pserve_reassemble(const pserve_plan_t* plan, const void* y, int32_t C, int dtype,
+                       void* const* images, void* stream);
+
+/* ---- block: description + weights.  Packs the weights into the layouts the kernels
+ * read (device copies owned by the block); the caller's parameter buffers are not
+ * referenced after the call returns (it synchronises `stream`).
+ * Errors: EINVAL for unknown stage kinds, C % G, C % heads, XATTN without ctx sizes,
+ * a NULL parameter; ENOMEM; EHIP. */
+int  pserve_block_create(const pserve_block_desc* desc, const pserve_block_params* params,
+                         void* stream, pserve_block_t** out);
+void pserve_block_free(pserve_block_t* block);
+
+/* ---- per (plan, block) activation store: the cached operand tensors of the patch-level
+ * cache ("Patch-aware Caching Strategy": operands of context operators and the block
+ * output of the previous step, per patch) plus all scratch the forward pass needs.
+ * with_slots = 0 allocates scratch only (then reuse_mask must be NULL). */
+int  pserve_cache_create(const pserve_plan_t* plan, const pserve_block_t* block, int with_slots,
+                         pserve_cache_t** out);
+void pserve_cache_free(pserve_cache_t* cache);
+/* Test / warm-start hooks: copy a [T][C] tensor (block dtype, token-major) into or out
+ * of a slot.  stage = index into desc.stages (or -1 with PSERVE_SLOT_Y). */
+int  pserve_cache_load(pserve_cache_t* cache, int stage, int slot, const void* src, void* stream);
+int  pserve_cache_read(const pserve_cache_t* cache, int stage, int slot, void* dst, void* stream);
+
+/* ---- the hot path: run the block on the patch batch.
+ *   x    DEVICE [T][C]   input tokens (fresh for every patch)
+ *   ctx  DEVICE [n][ctx_len][ctx_dim] text tokens per request, caller order (NULL if no XATTN)
+ *   reuse_mask DEVICE uint8 [P], plan order, 1 = reuse the cached patch (skip compute),
+ *        0 = compute; NULL = compute everything.
+ *   y    DEVICE [T][C]   output; must not alias x.
+ * Result: equal (up to rounding order) to running the block on every image on its own,
+ * unpatched ("Patched Inference with Batching").  With a mask (steps 3-5 of
+ * "Patch-aware Caching Strategy"): pixel-wise operators run on computed patches only;
+ * at every operator that needs context (GroupNorm statistics, convolution halos,
+ * attention keys/values) reused patches contribute their cached operand; afterwards
+ * y of reused patches is the cached output bit for bit, and every slot holds the fresh
+ * value on computed patches and keeps the old one on reused patches.
+ * Errors: EINVAL (NULL arguments, plan/block/cache mismatch, missing ctx), ESTATE (mask
+ * given but the cache has no slots or was never filled), EHIP. */
+int  pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* ctx,
+                          const pserve_block_t* weights, pserve_cache_t* cache,
+                          const uint8_t* reuse_mask, void* y, void* stream);
+
+/* Kernel selection for measurements and tests: 0 = fastest path available for the
+ * shapes (MFMA kernels where they apply), 1 = plain reference kernels only. */
+int  pserve_set_kernel_mode(int mode);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PSERVE_H */

@@ -1,0 +1,260 @@
+"""ctypes binding of the C ABI in include/pserve.h: argument marshalling only.
+
+Every step of the path runs in the HIP kernels of libpserve.so; torch is used for device
+memory and streams.  There is no CPU fallback: if the library is missing, loading fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+F32, BF16 = 0, 1
+STAGE_KIND = {"RES1": 1, "RES2": 2, "SATTN": 3, "XATTN": 4, "FFN": 5}
+TABLES = {"perm": 0, "request_offset": 1, "res_offset": 2, "res_hw": 3, "patch_owner": 4,
+          "patch_rc": 5, "neighbour": 6, "halo_src": 7, "cu_seqlens": 8}
+SLOT_H1, SLOT_R, SLOT_K, SLOT_V, SLOT_Y = 0, 1, 2, 3, 4
+MAX_STAGES, MAX_PARAMS = 8, 8
+
+# parameter order per stage kind (same as the header)
+PARAM_ORDER = {
+    "RES1": ["gn_g", "gn_b", "conv_w", "conv_b"],
+    "RES2": ["gn_a_g", "gn_a_b", "conv_a_w", "conv_a_b", "gn_b_g", "gn_b_b", "conv_b_w", "conv_b_b"],
+    "SATTN": ["gn_g", "gn_b", "wq", "wk", "wv", "wo", "bo"],
+    "XATTN": ["wq", "wk", "wv", "wo", "bo"],
+    "FFN": ["w1", "b1", "w2", "b2"],
+}
+
+
+class PserveError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"pserve status {status}: {msg}")
+        self.status = status
+
+
+class _PlanInfo(C.Structure):
+    _fields_ = [("n", C.c_int32), ("R", C.c_int32), ("P", C.c_int32), ("ph", C.c_int32), ("pw", C.c_int32),
+                ("ring", C.c_int32), ("T", C.c_int64)]
+
+
+class _BlockDesc(C.Structure):
+    _fields_ = [("n_stages", C.c_int32), ("stages", C.c_int32 * MAX_STAGES), ("C", C.c_int32), ("G", C.c_int32),
+                ("heads", C.c_int32), ("dtype", C.c_int32), ("eps", C.c_float), ("ctx_len", C.c_int32),
+                ("ctx_dim", C.c_int32), ("ffn_mult", C.c_int32)]
+
+
+class _BlockParams(C.Structure):
+    _fields_ = [("p", (C.c_void_p * MAX_PARAMS) * MAX_STAGES)]
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, "libpserve.so")
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libpserve.so (built by paper_2501_09253_amd.build); fails loudly if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} not found: build it with `python -m paper_2501_09253_amd.build` "
+                          "(there is no CPU fallback)")
+    L = C.CDLL(path)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    L.pserve_last_error.restype = C.c_char_p
+    L.pserve_last_error.argtypes = []
+    L.pserve_plan.argtypes = [C.POINTER(i32), i32, i32, i32, vp, C.POINTER(vp)]
+    L.pserve_plan_free.argtypes = [vp]
+    L.pserve_plan_free.restype = None
+    L.pserve_plan_info.argtypes = [vp, C.POINTER(_PlanInfo)]
+    L.pserve_plan_table.argtypes = [vp, C.c_int, C.c_int, C.POINTER(C.POINTER(i32)), C.POINTER(i64)]
+    L.pserve_split.argtypes = [vp, C.POINTER(vp), i32, C.c_int, vp, vp]
+    L.pserve_reassemble.argtypes = [vp, vp, i32, C.c_int, C.POINTER(vp), vp]
+    L.pserve_block_create.argtypes = [C.POINTER(_BlockDesc), C.POINTER(_BlockParams), vp, C.POINTER(vp)]
+    L.pserve_block_free.argtypes = [vp]
+    L.pserve_block_free.restype = None
+    L.pserve_cache_create.argtypes = [vp, vp, C.c_int, C.POINTER(vp)]
+    L.pserve_cache_free.argtypes = [vp]
+    L.pserve_cache_free.restype = None
+    L.pserve_cache_load.argtypes = [vp, C.c_int, C.c_int, vp, vp]
+    L.pserve_cache_read.argtypes = [vp, C.c_int, C.c_int, vp, vp]
+    L.pserve_block_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
+    L.pserve_set_kernel_mode.argtypes = [C.c_int]
+    _lib = L
+    return L
+
+
+def _check(status: int):
+    if status != 0:
+        raise PserveError(status, lib().pserve_last_error().decode())
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _torch_dtype(dtype: int):
+    import torch
+    return torch.bfloat16 if dtype == BF16 else torch.float32
+
+
+def set_kernel_mode(mode: int):
+    """0 = fastest kernels for the shapes, 1 = plain reference kernels only."""
+    _check(lib().pserve_set_kernel_mode(mode))
+
+
+class Plan:
+    """pserve_plan: Compressed Sparse Patch tables of one batch composition."""
+
+    def __init__(self, resolutions: Sequence[Sequence[int]], ph: int = 0, pw: int = 0):
+        res = np.ascontiguousarray(np.asarray(resolutions, dtype=np.int32).reshape(-1, 2))
+        self._h = C.c_void_p()
+        _check(lib().pserve_plan(res.ctypes.data_as(C.POINTER(C.c_int32)), res.shape[0], ph, pw, _stream(),
+                                 C.byref(self._h)))
+        info = _PlanInfo()
+        _check(lib().pserve_plan_info(self._h, C.byref(info)))
+        self.n, self.R, self.P, self.ph, self.pw, self.ring, self.T = (info.n, info.R, info.P, info.ph, info.pw,
+                                                                      info.ring, info.T)
+        self.resolutions = [tuple(int(v) for v in r) for r in res]
+
+    def table(self, name: str) -> np.ndarray:
+        """Host mirror of a table as a numpy int32 array (copy)."""
+        ptr = C.POINTER(C.c_int32)()
+        cnt = C.c_int64()
+        _check(lib().pserve_plan_table(self._h, TABLES[name], 0, C.byref(ptr), C.byref(cnt)))
+        a = np.ctypeslib.as_array(ptr, shape=(cnt.value,)).copy()
+        shape = {"res_hw": (-1, 2), "patch_rc": (-1, 2), "neighbour": (-1, 8), "halo_src": (self.P, -1)}.get(name)
+        return a.reshape(shape) if shape else a
+
+    def table_device_ptr(self, name: str) -> int:
+        ptr = C.POINTER(C.c_int32)()
+        cnt = C.c_int64()
+        _check(lib().pserve_plan_table(self._h, TABLES[name], 1, C.byref(ptr), C.byref(cnt)))
+        return C.cast(ptr, C.c_void_p).value
+
+    def split(self, images, out=None):
+        """Per-request NCHW device tensors (caller order) -> patch-major token matrix x[T, C]."""
+        import torch
+        Cc = images[0].shape[0]
+        dt = BF16 if images[0].dtype == torch.bfloat16 else F32
+        if out is None:
+            out = torch.empty((self.T, Cc), dtype=images[0].dtype, device=images[0].device)
+        ptrs = (C.c_void_p * self.n)(*[im.data_ptr() for im in images])
+        for im, (h, w) in zip(images, self.resolutions):
+            assert im.is_contiguous() and tuple(im.shape) == (Cc, h, w) and im.dtype == images[0].dtype
+        _check(lib().pserve_split(self._h, ptrs, Cc, dt, out.data_ptr(), _stream()))
+        return out
+
+    def reassemble(self, y, images=None):
+        """Patch-major y[T, C] -> per-request NCHW tensors in caller order."""
+        import torch
+        Cc = y.shape[1]
+        dt = BF16 if y.dtype == torch.bfloat16 else F32
+        assert y.is_contiguous() and y.shape[0] == self.T
+        if images is None:
+            images = [torch.empty((Cc, h, w), dtype=y.dtype, device=y.device) for h, w in self.resolutions]
+        ptrs = (C.c_void_p * self.n)(*[im.data_ptr() for im in images])
+        _check(lib().pserve_reassemble(self._h, y.data_ptr(), Cc, dt, ptrs, _stream()))
+        return images
+
+    def close(self):
+        if self._h:
+            lib().pserve_plan_free(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Block:
+    """pserve_block: block description + packed weights (params: per stage dict name -> device tensor)."""
+
+    def __init__(self, stages: Sequence[str], params: List[Dict[str, "object"]], *, C_: int, G: int, heads: int,
+                 dtype: int, eps: float = 1e-5, ctx_len: int = 0, ctx_dim: int = 0, ffn_mult: int = 4):
+        desc = _BlockDesc()
+        desc.n_stages = len(stages)
+        for i, s in enumerate(stages):
+            desc.stages[i] = STAGE_KIND[s]
+        desc.C, desc.G, desc.heads, desc.dtype, desc.eps = C_, G, heads, dtype, eps
+        desc.ctx_len, desc.ctx_dim, desc.ffn_mult = ctx_len, ctx_dim, ffn_mult
+        bp = _BlockParams()
+        keep = []
+        for i, (s, p) in enumerate(zip(stages, params)):
+            for k, name in enumerate(PARAM_ORDER[s]):
+                t = p[name]
+                assert t.is_contiguous() and t.dtype == _torch_dtype(dtype), (s, name, t.dtype)
+                keep.append(t)
+                bp.p[i][k] = t.data_ptr()
+        self._h = C.c_void_p()
+        _check(lib().pserve_block_create(C.byref(desc), C.byref(bp), _stream(), C.byref(self._h)))
+        self.stages, self.C, self.dtype = tuple(stages), C_, dtype
+
+    def close(self):
+        if self._h:
+            lib().pserve_block_free(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Cache:
+    """pserve_cache: cached operand tensors + scratch of one (plan, block) pair."""
+
+    def __init__(self, plan: Plan, block: Block, with_slots: bool = False):
+        self._h = C.c_void_p()
+        _check(lib().pserve_cache_create(plan._h, block._h, int(with_slots), C.byref(self._h)))
+        self.plan, self.block = plan, block
+
+    def load(self, stage: int, slot: int, src):
+        assert src.is_contiguous() and tuple(src.shape) == (self.plan.T, self.block.C)
+        _check(lib().pserve_cache_load(self._h, stage, slot, src.data_ptr(), _stream()))
+
+    def read(self, stage: int, slot: int):
+        import torch
+        dst = torch.empty((self.plan.T, self.block.C), dtype=_torch_dtype(self.block.dtype), device="cuda")
+        _check(lib().pserve_cache_read(self._h, stage, slot, dst.data_ptr(), _stream()))
+        return dst
+
+    def forward(self, x, ctx=None, reuse_mask=None, y=None):
+        """pserve_block_forward on the current torch stream; returns y[T, C]."""
+        import torch
+        assert x.is_contiguous() and tuple(x.shape) == (self.plan.T, self.block.C)
+        assert x.dtype == _torch_dtype(self.block.dtype)
+        if y is None:
+            y = torch.empty_like(x)
+        if ctx is not None:
+            assert ctx.is_contiguous() and ctx.dtype == x.dtype
+        if reuse_mask is not None:
+            assert reuse_mask.dtype == torch.uint8 and reuse_mask.numel() == self.plan.P and reuse_mask.is_contiguous()
+        _check(lib().pserve_block_forward(self.plan._h, x.data_ptr(), ctx.data_ptr() if ctx is not None else None,
+                                          self.block._h, self._h,
+                                          reuse_mask.data_ptr() if reuse_mask is not None else None,
+                                          y.data_ptr(), _stream()))
+        return y
+
+    def close(self):
+        if self._h:
+            lib().pserve_cache_free(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

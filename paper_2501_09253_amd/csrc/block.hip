@@ -1,0 +1,509 @@
+// Block executor: packs weights, owns the per (plan, block) activation store, and runs the
+// stage list of one denoising block over the patch batch with optional patch-level cache
+// reuse ("Patch-aware Caching Strategy": mask per patch before the block, pixel-wise
+// operators recompute only unmasked patches, context operators take the cached operand of
+// masked patches, masked outputs are replaced by the cache, the cache is then refreshed).
+//
+// Reuse without copies: the cached operand tensors ARE the working buffers.  A context
+// operator's producer writes only the computed patches into the slot, so after the write the
+// slot holds "fresh on computed, previous step on reused" — exactly the operand the
+// consumer needs and exactly the refreshed cache for the next step.
+#include "kernels.h"
+
+#include <algorithm>
+#include <new>
+
+using namespace pserve;
+
+namespace pserve {
+static int g_kernel_mode = 0;
+
+struct StageWeights {
+    void* gn_g[2] = {};      // raw copies, block dtype
+    void* gn_b[2] = {};
+    void* w[3] = {};         // packed [taps][N][K]
+    float* b[3] = {};        // packed biases (fp32)
+};
+
+// ---- small kernels ---------------------------------------------------------------------------------
+// Ordered compaction of the patches with mask == 0.
+__global__ void compact_mask_kernel(const uint8_t* __restrict__ mask, int32_t P, int32_t* __restrict__ active,
+                                    int32_t* __restrict__ count) {
+    __shared__ int32_t s_scan[1024];
+    __shared__ int32_t carry;
+    const int tid = threadIdx.x;
+    if (tid == 0) carry = 0;
+    __syncthreads();
+    for (int base = 0; base < P; base += 1024) {
+        const int p = base + tid;
+        const int32_t f = (p < P && mask[p] == 0) ? 1 : 0;
+        s_scan[tid] = f;
+        __syncthreads();
+        for (int off = 1; off < 1024; off <<= 1) {
+            int32_t v = 0;
+            if (tid >= off) v = s_scan[tid - off];
+            __syncthreads();
+            s_scan[tid] += v;
+            __syncthreads();
+        }
+        if (f) active[carry + s_scan[tid] - 1] = p;
+        __syncthreads();
+        if (tid == 1023) carry += s_scan[tid];
+        __syncthreads();
+    }
+    if (tid == 0) *count = carry;
+}
+
+// Copy whole patches ([S][C] rows) between token-major tensors, 16 bytes per thread.
+// which: 0 = all patches, 1 = patches with mask == 0 (computed), 2 = patches with mask == 1 (reused)
+__global__ void copy_patches_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int64_t vec_per_patch,
+                                    const uint8_t* __restrict__ mask, int which) {
+    const int p = blockIdx.x;
+    if (which && mask) {
+        const bool reused = mask[p] != 0;
+        if ((which == 1) == reused) return;
+    } else if (which == 2) {
+        return;
+    }
+    const uint4* s = src + (int64_t)p * vec_per_patch;
+    uint4* d = dst + (int64_t)p * vec_per_patch;
+    for (int64_t i = blockIdx.y * blockDim.x + threadIdx.x; i < vec_per_patch; i += (int64_t)gridDim.y * blockDim.x) d[i] = s[i];
+}
+
+// dst[c][t] = src[t][c] (or the reverse), used by the cache load/read hooks for the transposed V slot
+template <typename T>
+__global__ void transpose_tc_kernel(const T* __restrict__ src, T* __restrict__ dst, int64_t Tn, int32_t C, int to_ct) {
+    __shared__ T tile[32][33];
+    const int64_t t0 = (int64_t)blockIdx.x * 32;
+    const int c0 = blockIdx.y * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    if (to_ct) {
+        for (int r = ty; r < 32; r += 8)
+            if (t0 + r < Tn && c0 + tx < C) tile[r][tx] = src[(t0 + r) * C + c0 + tx];
+        __syncthreads();
+        for (int r = ty; r < 32; r += 8)
+            if (c0 + r < C && t0 + tx < Tn) dst[(int64_t)(c0 + r) * Tn + t0 + tx] = tile[tx][r];
+    } else {
+        for (int r = ty; r < 32; r += 8)
+            if (c0 + r < C && t0 + tx < Tn) tile[r][tx] = src[(int64_t)(c0 + r) * Tn + t0 + tx];
+        __syncthreads();
+        for (int r = ty; r < 32; r += 8)
+            if (t0 + r < Tn && c0 + tx < C) dst[(t0 + r) * C + c0 + tx] = tile[tx][r];
+    }
+}
+}  // namespace pserve
+
+struct pserve_block_s {
+    pserve_block_desc desc;
+    StageWeights sw[PSERVE_MAX_STAGES];
+    DevicePool pool;
+};
+
+struct pserve_cache_s {
+    const pserve_plan_t* plan = nullptr;
+    const pserve_block_t* block = nullptr;
+    bool with_slots = false, filled = false, v_transposed = false;
+    int32_t nsplit = 1, cross_ld = 0;
+    void* ping[2] = {};                       // [T][C] stage outputs
+    void* apad = nullptr;                     // [P][ph+2][pw+2][C]
+    float* partial = nullptr;
+    float* scale_shift = nullptr;
+    void* h1[PSERVE_MAX_STAGES] = {};         // RES2: first convolution output (slot H1)
+    void* r[PSERVE_MAX_STAGES] = {};          // SATTN: stage input (slot R), only with slots
+    void* k[PSERVE_MAX_STAGES] = {};          // SATTN: keys (slot K)
+    void* v[PSERVE_MAX_STAGES] = {};          // SATTN: values (slot V; [C][T] when v_transposed)
+    void* q = nullptr;                        // [T][C] scaled queries
+    void* o = nullptr;                        // [T][C] attention output
+    void* u = nullptr;                        // [T][C] normalised tokens
+    void* kc = nullptr;                       // [n*cross_ld][C] text keys
+    void* vc = nullptr;                       // [n*cross_ld][C] text values
+    void* hidden = nullptr;                   // [T][F]
+    void* yslot = nullptr;                    // [T][C] block output of the previous step (slot Y)
+    int32_t* active = nullptr;
+    int32_t* count = nullptr;
+    DevicePool pool;
+};
+
+static bool has_stage(const pserve_block_desc& d, int kind) {
+    for (int i = 0; i < d.n_stages; ++i)
+        if (d.stages[i] == kind) return true;
+    return false;
+}
+
+static int dup_param(DevicePool& pool, const void* src, size_t bytes, void** dst, hipStream_t st) {
+    PS_TRY(pool.alloc(dst, bytes));
+    PS_CHECK_HIP(hipMemcpyAsync(*dst, src, bytes, hipMemcpyDeviceToDevice, st));
+    return PSERVE_OK;
+}
+
+extern "C" {
+
+int pserve_set_kernel_mode(int mode) {
+    PS_REQUIRE(mode == 0 || mode == 1, "pserve_set_kernel_mode: mode must be 0 or 1");
+    g_kernel_mode = mode;
+    return PSERVE_OK;
+}
+
+int pserve_block_create(const pserve_block_desc* desc, const pserve_block_params* params, void* stream, pserve_block_t** out) {
+    PS_REQUIRE(out, "pserve_block_create: out is NULL");
+    *out = nullptr;
+    PS_REQUIRE(desc && params, "pserve_block_create: NULL argument");
+    const pserve_block_desc& d = *desc;
+    PS_REQUIRE(d.n_stages > 0 && d.n_stages <= PSERVE_MAX_STAGES, "pserve_block_create: n_stages=%d out of range", d.n_stages);
+    PS_REQUIRE(d.dtype == PSERVE_F32 || d.dtype == PSERVE_BF16, "pserve_block_create: unknown dtype %d", d.dtype);
+    PS_REQUIRE(d.C > 0 && d.G > 0 && d.C % d.G == 0, "pserve_block_create: C=%d must be a positive multiple of G=%d", d.C, d.G);
+    PS_REQUIRE(d.C % (d.dtype == PSERVE_BF16 ? 8 : 4) == 0, "pserve_block_create: C=%d must be a multiple of 16 bytes", d.C);
+    PS_REQUIRE(d.eps >= 0.f, "pserve_block_create: negative eps");
+    static const int nparams[6] = {0, 4, 8, 7, 5, 4};
+    for (int s = 0; s < d.n_stages; ++s) {
+        const int kind = d.stages[s];
+        PS_REQUIRE(kind >= PSERVE_RES1 && kind <= PSERVE_FFN, "pserve_block_create: stage %d has unknown kind %d", s, kind);
+        for (int k = 0; k < nparams[kind]; ++k) PS_REQUIRE(params->p[s][k], "pserve_block_create: stage %d parameter %d is NULL", s, k);
+        if (kind == PSERVE_SATTN || kind == PSERVE_XATTN)
+            PS_REQUIRE(d.heads > 0 && d.C % d.heads == 0 && d.C / d.heads <= 128,
+                       "pserve_block_create: heads=%d must divide C=%d with head dim <= 128", d.heads, d.C);
+        if (kind == PSERVE_XATTN)
+            PS_REQUIRE(d.ctx_len > 0 && d.ctx_dim > 0, "pserve_block_create: XATTN needs ctx_len and ctx_dim");
+        if (kind == PSERVE_FFN)
+            PS_REQUIRE(d.ffn_mult > 0 && (d.ffn_mult * d.C) % GEGLU_GROUP == 0,
+                       "pserve_block_create: FFN hidden width %d must be a multiple of %d", d.ffn_mult * d.C, GEGLU_GROUP);
+    }
+    pserve_block_t* b = new (std::nothrow) pserve_block_t();
+    if (!b) { set_error("pserve_block_create: out of host memory"); return PSERVE_ENOMEM; }
+    struct Guard { pserve_block_t* p; ~Guard() { delete p; } } guard{b};
+    b->desc = d;
+    hipStream_t st = (hipStream_t)stream;
+    const size_t es = dtype_size(d.dtype);
+    const int C = d.C;
+    for (int s = 0; s < d.n_stages; ++s) {
+        StageWeights& w = b->sw[s];
+        const void* const* p = params->p[s];
+        switch (d.stages[s]) {
+        case PSERVE_RES1:
+        case PSERVE_RES2: {
+            const int convs = d.stages[s] == PSERVE_RES1 ? 1 : 2;
+            for (int c = 0; c < convs; ++c) {
+                PS_TRY(dup_param(b->pool, p[4 * c + 0], es * C, &w.gn_g[c], st));
+                PS_TRY(dup_param(b->pool, p[4 * c + 1], es * C, &w.gn_b[c], st));
+                PS_TRY(b->pool.alloc(&w.w[c], es * 9 * C * C));
+                PS_TRY(pack_conv(p[4 * c + 2], w.w[c], C, C, d.dtype, st));
+                PS_TRY(b->pool.alloc_t(&w.b[c], C));
+                PS_TRY(pack_bias(p[4 * c + 3], w.b[c], C, d.dtype, st));
+            }
+            break;
+        }
+        case PSERVE_SATTN: {
+            PS_TRY(dup_param(b->pool, p[0], es * C, &w.gn_g[0], st));
+            PS_TRY(dup_param(b->pool, p[1], es * C, &w.gn_b[0], st));
+            PS_TRY(b->pool.alloc(&w.w[0], es * 3 * C * C));                       // fused [Wq | Wk | Wv]
+            for (int k = 0; k < 3; ++k) PS_TRY(pack_linear(p[2 + k], w.w[0], C, C, k * C, d.dtype, st));
+            PS_TRY(b->pool.alloc(&w.w[1], es * C * C));
+            PS_TRY(pack_linear(p[5], w.w[1], C, C, 0, d.dtype, st));
+            PS_TRY(b->pool.alloc_t(&w.b[1], C));
+            PS_TRY(pack_bias(p[6], w.b[1], C, d.dtype, st));
+            break;
+        }
+        case PSERVE_XATTN: {
+            const int D = d.ctx_dim;
+            PS_TRY(b->pool.alloc(&w.w[0], es * C * C));
+            PS_TRY(pack_linear(p[0], w.w[0], C, C, 0, d.dtype, st));
+            PS_TRY(b->pool.alloc(&w.w[2], es * 2 * C * D));                       // fused [Wk | Wv] on the text tokens
+            PS_TRY(pack_linear(p[1], w.w[2], D, C, 0, d.dtype, st));
+            PS_TRY(pack_linear(p[2], w.w[2], D, C, C, d.dtype, st));
+            PS_TRY(b->pool.alloc(&w.w[1], es * C * C));
+            PS_TRY(pack_linear(p[3], w.w[1], C, C, 0, d.dtype, st));
+            PS_TRY(b->pool.alloc_t(&w.b[1], C));
+            PS_TRY(pack_bias(p[4], w.b[1], C, d.dtype, st));
+            break;
+        }
+        case PSERVE_FFN: {
+            const int F = d.ffn_mult * C;
+            PS_TRY(b->pool.alloc(&w.w[0], es * 2 * F * C));
+            PS_TRY(b->pool.alloc_t(&w.b[0], 2 * F));
+            PS_TRY(pack_geglu(p[0], p[1], w.w[0], w.b[0], C, F, d.dtype, st));
+            PS_TRY(b->pool.alloc(&w.w[1], es * C * F));
+            PS_TRY(pack_linear(p[2], w.w[1], F, C, 0, d.dtype, st));
+            PS_TRY(b->pool.alloc_t(&w.b[1], C));
+            PS_TRY(pack_bias(p[3], w.b[1], C, d.dtype, st));
+            break;
+        }
+        }
+    }
+    PS_CHECK_HIP(hipStreamSynchronize(st));
+    guard.p = nullptr;
+    *out = b;
+    return PSERVE_OK;
+}
+
+void pserve_block_free(pserve_block_t* block) { delete block; }
+
+int pserve_cache_create(const pserve_plan_t* plan, const pserve_block_t* block, int with_slots, pserve_cache_t** out) {
+    PS_REQUIRE(out, "pserve_cache_create: out is NULL");
+    *out = nullptr;
+    PS_REQUIRE(plan && block, "pserve_cache_create: NULL argument");
+    const pserve_block_desc& d = block->desc;
+    if (with_slots)
+        for (int s = 1; s < d.n_stages; ++s)
+            PS_REQUIRE(d.stages[s] != PSERVE_RES1 && d.stages[s] != PSERVE_RES2,
+                       "pserve_cache_create: patch reuse needs residual-convolution stages at position 0 only "
+                       "(their input statistics and halos must be fresh on every patch)");
+    pserve_cache_t* c = new (std::nothrow) pserve_cache_t();
+    if (!c) { set_error("pserve_cache_create: out of host memory"); return PSERVE_ENOMEM; }
+    struct Guard { pserve_cache_t* p; ~Guard() { delete p; } } guard{c};
+    c->plan = plan;
+    c->block = block;
+    c->with_slots = with_slots != 0;
+    const size_t es = dtype_size(d.dtype);
+    const size_t TC = (size_t)plan->T * d.C * es;
+    const int head_dim = d.heads > 0 ? d.C / d.heads : 0;
+    c->v_transposed = d.dtype == PSERVE_BF16 && head_dim == 64 && g_kernel_mode == 0;
+    c->nsplit = (int)std::max<int64_t>(1, std::min<int64_t>(cdiv(2048, plan->P), std::max(1, plan->S / 16)));
+    PS_TRY(c->pool.alloc(&c->ping[0], TC));
+    PS_TRY(c->pool.alloc(&c->ping[1], TC));
+    const bool conv = has_stage(d, PSERVE_RES1) || has_stage(d, PSERVE_RES2);
+    const bool sattn = has_stage(d, PSERVE_SATTN), xattn = has_stage(d, PSERVE_XATTN), ffn = has_stage(d, PSERVE_FFN);
+    if (conv) PS_TRY(c->pool.alloc(&c->apad, (size_t)plan->P * (plan->ph + 2) * (plan->pw + 2) * d.C * es));
+    if (conv || sattn) {
+        PS_TRY(c->pool.alloc_t(&c->partial, (size_t)plan->P * c->nsplit * d.G * 2));
+        PS_TRY(c->pool.alloc_t(&c->scale_shift, (size_t)plan->n * d.C * 2));
+    }
+    for (int s = 0; s < d.n_stages; ++s) {
+        if (d.stages[s] == PSERVE_RES2) PS_TRY(c->pool.alloc(&c->h1[s], TC));
+        if (d.stages[s] == PSERVE_SATTN) {
+            if (with_slots) PS_TRY(c->pool.alloc(&c->r[s], TC));
+            PS_TRY(c->pool.alloc(&c->k[s], TC));
+            PS_TRY(c->pool.alloc(&c->v[s], TC));
+        }
+    }
+    if (sattn || xattn) {
+        PS_TRY(c->pool.alloc(&c->q, TC));
+        PS_TRY(c->pool.alloc(&c->o, TC));
+    }
+    if (sattn) PS_TRY(c->pool.alloc(&c->u, TC));
+    if (xattn) {
+        c->cross_ld = d.ctx_len;
+        PS_TRY(c->pool.alloc(&c->kc, (size_t)plan->n * c->cross_ld * d.C * es));
+        PS_TRY(c->pool.alloc(&c->vc, (size_t)plan->n * c->cross_ld * d.C * es));
+    }
+    if (ffn) PS_TRY(c->pool.alloc(&c->hidden, (size_t)plan->T * d.ffn_mult * d.C * es));
+    if (with_slots) PS_TRY(c->pool.alloc(&c->yslot, TC));
+    PS_TRY(c->pool.alloc_t(&c->active, (size_t)plan->P));
+    PS_TRY(c->pool.alloc_t(&c->count, 1));
+    guard.p = nullptr;
+    *out = c;
+    return PSERVE_OK;
+}
+
+void pserve_cache_free(pserve_cache_t* cache) { delete cache; }
+
+static int slot_ptr(const pserve_cache_t* c, int stage, int slot, void** ptr, bool* transposed) {
+    PS_REQUIRE(c, "cache slot: cache is NULL");
+    PS_REQUIRE(c->with_slots, "cache slot: this cache was created without slots");
+    const pserve_block_desc& d = c->block->desc;
+    *transposed = false;
+    if (slot == PSERVE_SLOT_Y) {
+        PS_REQUIRE(stage == -1, "cache slot: the output slot is addressed with stage = -1");
+        *ptr = c->yslot;
+        return PSERVE_OK;
+    }
+    PS_REQUIRE(stage >= 0 && stage < d.n_stages, "cache slot: stage %d out of range", stage);
+    void* p = nullptr;
+    if (slot == PSERVE_SLOT_H1 && d.stages[stage] == PSERVE_RES2) p = c->h1[stage];
+    else if (slot == PSERVE_SLOT_R && d.stages[stage] == PSERVE_SATTN) p = c->r[stage];
+    else if (slot == PSERVE_SLOT_K && d.stages[stage] == PSERVE_SATTN) p = c->k[stage];
+    else if (slot == PSERVE_SLOT_V && d.stages[stage] == PSERVE_SATTN) { p = c->v[stage]; *transposed = c->v_transposed; }
+    PS_REQUIRE(p, "cache slot: stage %d has no slot %d", stage, slot);
+    *ptr = p;
+    return PSERVE_OK;
+}
+
+static int slot_copy(const pserve_cache_t* c, void* slot, bool transposed, void* user, bool load, hipStream_t st) {
+    const pserve_block_desc& d = c->block->desc;
+    const size_t es = dtype_size(d.dtype);
+    const int64_t T = c->plan->T;
+    if (!transposed) {
+        PS_CHECK_HIP(hipMemcpyAsync(load ? slot : user, load ? user : slot, (size_t)T * d.C * es, hipMemcpyDeviceToDevice, st));
+        return PSERVE_OK;
+    }
+    dim3 grid((unsigned)cdiv(T, 32), (unsigned)cdiv(d.C, 32));
+    if (d.dtype == PSERVE_BF16)
+        transpose_tc_kernel<uint16_t><<<grid, 256, 0, st>>>((const uint16_t*)(load ? user : slot), (uint16_t*)(load ? slot : user), T, d.C, load ? 1 : 0);
+    else
+        transpose_tc_kernel<float><<<grid, 256, 0, st>>>((const float*)(load ? user : slot), (float*)(load ? slot : user), T, d.C, load ? 1 : 0);
+    return check_launch("transpose_tc_kernel");
+}
+
+int pserve_cache_load(pserve_cache_t* cache, int stage, int slot, const void* src, void* stream) {
+    void* p; bool tr;
+    PS_TRY(slot_ptr(cache, stage, slot, &p, &tr));
+    PS_REQUIRE(src, "pserve_cache_load: src is NULL");
+    PS_TRY(slot_copy(cache, p, tr, (void*)src, true, (hipStream_t)stream));
+    cache->filled = true;
+    return PSERVE_OK;
+}
+
+int pserve_cache_read(const pserve_cache_t* cache, int stage, int slot, void* dst, void* stream) {
+    void* p; bool tr;
+    PS_TRY(slot_ptr(cache, stage, slot, &p, &tr));
+    PS_REQUIRE(dst, "pserve_cache_read: dst is NULL");
+    return slot_copy(cache, p, tr, dst, false, (hipStream_t)stream);
+}
+
+int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* ctx, const pserve_block_t* block,
+                         pserve_cache_t* cache, const uint8_t* reuse_mask, void* y, void* stream) {
+    PS_REQUIRE(plan && x && block && cache && y, "pserve_block_forward: NULL argument");
+    PS_REQUIRE(x != y, "pserve_block_forward: x and y must not alias");
+    PS_REQUIRE(cache->plan == plan && cache->block == block, "pserve_block_forward: cache belongs to another plan or block");
+    const pserve_block_desc& d = block->desc;
+    PS_REQUIRE(ctx || !has_stage(d, PSERVE_XATTN), "pserve_block_forward: XATTN stage needs ctx");
+    if (reuse_mask) {
+        if (!cache->with_slots) { set_error("pserve_block_forward: reuse mask given but the cache has no slots"); return PSERVE_ESTATE; }
+        if (!cache->filled) { set_error("pserve_block_forward: reuse mask given but the cache was never filled"); return PSERVE_ESTATE; }
+    }
+    hipStream_t st = (hipStream_t)stream;
+    const int dt = d.dtype, mode = g_kernel_mode, C = d.C;
+    const size_t es = dtype_size(dt);
+    PatchGeom gm;
+    gm.P = plan->P; gm.S = plan->S; gm.ph = plan->ph; gm.pw = plan->pw;
+    gm.ppw = plan->pw + 2; gm.pS = (plan->ph + 2) * (plan->pw + 2);
+    const int32_t* request_offset = plan->d_tab[PSERVE_TAB_REQUEST_OFFSET];
+    const int32_t* owner = plan->d_tab[PSERVE_TAB_PATCH_OWNER];
+    const int64_t T = plan->T;
+    const int64_t vec_per_patch = (int64_t)plan->S * C * es / 16;
+    const dim3 copy_grid(plan->P, (unsigned)std::max<int64_t>(1, std::min<int64_t>(cdiv(vec_per_patch, 1024), 64)));
+
+    ActiveList act{nullptr, nullptr};
+    if (reuse_mask) {
+        compact_mask_kernel<<<1, 1024, 0, st>>>(reuse_mask, plan->P, cache->active, cache->count);
+        PS_TRY(check_launch("compact_mask_kernel"));
+        act.active = cache->active;
+        act.count = cache->count;
+    }
+    const ActiveList all{nullptr, nullptr};
+    const float qscale = 1.4426950408889634f / sqrtf((float)(d.heads > 0 ? C / d.heads : 1));
+
+    auto gn_args = [&](const void* in, const void* gamma, const void* beta) {
+        GroupNormArgs a;
+        a.x = in; a.gamma = gamma; a.beta = beta; a.C = C; a.G = d.G; a.n = plan->n; a.eps = d.eps;
+        a.nsplit = cache->nsplit; a.partial = cache->partial; a.scale_shift = cache->scale_shift;
+        a.request_offset = request_offset; a.owner = owner;
+        return a;
+    };
+    auto base_gemm = [&](const void* A, int64_t lda, int K, int N, const void* B, const float* bias) {
+        GemmArgs g{};
+        g.A = A; g.lda = lda; g.conv = 0; g.geom = gm; g.act = act; g.tokens_are_rows = 1; g.M = (int32_t)T;
+        g.N = N; g.K = K; g.taps = 1; g.B = B; g.bias = bias; g.res = nullptr; g.ldr = 0;
+        g.epi = EPI_ROUTE; g.seg_cols = N;
+        for (auto& s : g.seg) { s.ptr = nullptr; s.ld = 0; s.transposed = 0; s.scale = 1.f; }
+        return g;
+    };
+    // GroupNorm(+SiLU) of `in` into the padded buffer, halo ring, 3x3 convolution (+bias, +residual) into `out`
+    auto norm_conv = [&](const void* in, const StageWeights& w, int ci, const void* res, void* out) -> int {
+        GroupNormArgs ga = gn_args(in, w.gn_g[ci], w.gn_b[ci]);
+        PS_TRY(gn_stats(ga, gm, dt, st));
+        PS_TRY(gn_apply(ga, gm, dt, /*silu=*/true, /*padded=*/true, cache->apad, all, st));
+        PS_TRY(halo_gather(cache->apad, plan->d_tab[PSERVE_TAB_HALO_SRC], gm, C, plan->ring, dt, act, st));
+        GemmArgs g = base_gemm(cache->apad, C, C, C, w.w[ci], w.b[ci]);
+        g.conv = 1; g.taps = 9; g.res = res; g.ldr = C;
+        g.seg[0].ptr = out; g.seg[0].ld = C;
+        return gemm(g, dt, mode, st);
+    };
+
+    const void* cur = x;
+    for (int si = 0; si < d.n_stages; ++si) {
+        const StageWeights& w = block->sw[si];
+        const bool last = si == d.n_stages - 1;
+        void* out;
+        if (last) out = y;
+        else if (cache->with_slots && d.stages[si + 1] == PSERVE_SATTN) out = cache->r[si + 1];   // producer writes the slot
+        else out = (cur == cache->ping[0]) ? cache->ping[1] : cache->ping[0];
+
+        switch (d.stages[si]) {
+        case PSERVE_RES1:
+            PS_TRY(norm_conv(cur, w, 0, cur, out));
+            break;
+        case PSERVE_RES2:
+            PS_TRY(norm_conv(cur, w, 0, nullptr, cache->h1[si]));
+            PS_TRY(norm_conv(cache->h1[si], w, 1, cur, out));
+            break;
+        case PSERVE_SATTN: {
+            const void* rin = cur;
+            if (cache->with_slots && cur != cache->r[si]) {           // first stage: merge fresh input into the slot
+                copy_patches_kernel<<<copy_grid, 256, 0, st>>>((const uint4*)cur, (uint4*)cache->r[si], vec_per_patch,
+                                                               reuse_mask, reuse_mask ? 1 : 0);
+                PS_TRY(check_launch("copy_patches_kernel"));
+                rin = cache->r[si];
+            }
+            GroupNormArgs ga = gn_args(rin, w.gn_g[0], w.gn_b[0]);
+            PS_TRY(gn_stats(ga, gm, dt, st));
+            PS_TRY(gn_apply(ga, gm, dt, false, false, cache->u, act, st));
+            GemmArgs g = base_gemm(cache->u, C, C, 3 * C, w.w[0], nullptr);
+            g.seg_cols = C;
+            g.seg[0].ptr = cache->q; g.seg[0].ld = C; g.seg[0].scale = qscale;
+            g.seg[1].ptr = cache->k[si]; g.seg[1].ld = C;
+            g.seg[2].ptr = cache->v[si]; g.seg[2].ld = cache->v_transposed ? T : C; g.seg[2].transposed = cache->v_transposed;
+            PS_TRY(gemm(g, dt, mode, st));
+            AttnArgs aa{};
+            aa.Q = cache->q; aa.K = cache->k[si]; aa.V = cache->v[si];
+            aa.ldv = cache->v_transposed ? T : C; aa.v_transposed = cache->v_transposed;
+            aa.O = cache->o; aa.C = C; aa.heads = d.heads; aa.d = C / d.heads; aa.geom = gm; aa.act = act;
+            aa.owner = owner; aa.cu_seqlens = plan->d_tab[PSERVE_TAB_CU_SEQLENS]; aa.perm = plan->d_tab[PSERVE_TAB_PERM];
+            aa.cross_len = 0; aa.cross_ld = 0;
+            PS_TRY(attention(aa, dt, mode, st));
+            GemmArgs go = base_gemm(cache->o, C, C, C, w.w[1], w.b[1]);
+            go.res = rin; go.ldr = C;
+            go.seg[0].ptr = out; go.seg[0].ld = C;
+            PS_TRY(gemm(go, dt, mode, st));
+            break;
+        }
+        case PSERVE_XATTN: {
+            GemmArgs gk = base_gemm(ctx, d.ctx_dim, d.ctx_dim, 2 * C, w.w[2], nullptr);   // text keys / values of every request
+            gk.tokens_are_rows = 0; gk.act = all; gk.M = plan->n * d.ctx_len; gk.seg_cols = C;
+            gk.seg[0].ptr = cache->kc; gk.seg[0].ld = C;
+            gk.seg[1].ptr = cache->vc; gk.seg[1].ld = C;
+            PS_TRY(gemm(gk, dt, mode, st));
+            GemmArgs gq = base_gemm(cur, C, C, C, w.w[0], nullptr);
+            gq.seg[0].ptr = cache->q; gq.seg[0].ld = C; gq.seg[0].scale = qscale;
+            PS_TRY(gemm(gq, dt, mode, st));
+            AttnArgs aa{};
+            aa.Q = cache->q; aa.K = cache->kc; aa.V = cache->vc; aa.ldv = C; aa.v_transposed = 0;
+            aa.O = cache->o; aa.C = C; aa.heads = d.heads; aa.d = C / d.heads; aa.geom = gm; aa.act = act;
+            aa.owner = owner; aa.cu_seqlens = plan->d_tab[PSERVE_TAB_CU_SEQLENS]; aa.perm = plan->d_tab[PSERVE_TAB_PERM];
+            aa.cross_len = d.ctx_len; aa.cross_ld = cache->cross_ld;
+            PS_TRY(attention(aa, dt, mode, st));
+            GemmArgs go = base_gemm(cache->o, C, C, C, w.w[1], w.b[1]);
+            go.res = cur; go.ldr = C;
+            go.seg[0].ptr = out; go.seg[0].ld = C;
+            PS_TRY(gemm(go, dt, mode, st));
+            break;
+        }
+        case PSERVE_FFN: {
+            const int F = d.ffn_mult * C;
+            GemmArgs g1 = base_gemm(cur, C, C, 2 * F, w.w[0], w.b[0]);
+            g1.epi = EPI_GEGLU;
+            g1.seg[0].ptr = cache->hidden; g1.seg[0].ld = F;
+            PS_TRY(gemm(g1, dt, mode, st));
+            GemmArgs g2 = base_gemm(cache->hidden, F, F, C, w.w[1], w.b[1]);
+            g2.res = cur; g2.ldr = C;
+            g2.seg[0].ptr = out; g2.seg[0].ld = C;
+            PS_TRY(gemm(g2, dt, mode, st));
+            break;
+        }
+        }
+        cur = out;
+    }
+    if (cache->with_slots) {
+        // computed patches refresh the output slot; reused patches take the cached output
+        copy_patches_kernel<<<copy_grid, 256, 0, st>>>((const uint4*)y, (uint4*)cache->yslot, vec_per_patch, reuse_mask,
+                                                       reuse_mask ? 1 : 0);
+        PS_TRY(check_launch("copy_patches_kernel"));
+        if (reuse_mask) {
+            copy_patches_kernel<<<copy_grid, 256, 0, st>>>((const uint4*)cache->yslot, (uint4*)y, vec_per_patch, reuse_mask, 2);
+            PS_TRY(check_launch("copy_patches_kernel"));
+        }
+    }
+    cache->filled = true;
+    return PSERVE_OK;
+}
+
+}  // extern "C"

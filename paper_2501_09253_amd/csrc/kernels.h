@@ -1,0 +1,116 @@
+// Internal launch interface between the block executor and the kernel files.
+#pragma once
+
+#include "common.h"
+
+namespace pserve {
+
+// ---- element access helpers (device) ------------------------------------------------------
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {       // round to nearest even
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40);   // quiet NaN
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+template <typename T> __device__ __forceinline__ float ld_f(const T* p);
+template <> __device__ __forceinline__ float ld_f<float>(const float* p) { return *p; }
+template <> __device__ __forceinline__ float ld_f<uint16_t>(const uint16_t* p) { return bf16_bits_to_float(*p); }
+template <typename T> __device__ __forceinline__ void st_f(T* p, float v);
+template <> __device__ __forceinline__ void st_f<float>(float* p, float v) { *p = v; }
+template <> __device__ __forceinline__ void st_f<uint16_t>(uint16_t* p, float v) { *p = float_to_bf16_bits(v); }
+
+// Patch geometry shared by the kernels that walk tokens.
+struct PatchGeom {
+    int32_t P, S, ph, pw;      // patches, tokens per patch, patch height / width
+    int32_t ppw, pS;           // padded patch width (pw+2) and padded pixels per patch ((ph+2)*(pw+2))
+};
+
+// Optional compaction of the patches that are computed (reuse mask == 0).  active == nullptr means
+// "all patches, identity order".
+struct ActiveList {
+    const int32_t* active;     // [P] patch ids, first *count entries valid
+    const int32_t* count;      // device scalar
+};
+
+// ---- GroupNorm (norm.hip) -------------------------------------------------------------------
+struct GroupNormArgs {
+    const void* x;             // [T][C]
+    const void* gamma;         // [C] block dtype
+    const void* beta;          // [C]
+    int32_t C, G, n;
+    float eps;
+    int32_t nsplit;            // token chunks per patch used for the partial sums
+    float* partial;            // [P][nsplit][G][2] (sum, sum of squares)
+    float* scale_shift;        // [n][C][2]: y = x*scale + shift for sorted slot s
+    const int32_t* request_offset;   // [n+1]
+    const int32_t* owner;      // [P]
+};
+int gn_stats(const GroupNormArgs& a, const PatchGeom& g, int dtype, hipStream_t st);
+// y = x*scale+shift (then SiLU if silu).  padded: write into the interior of the padded patch buffer
+// [P][ph+2][pw+2][C]; else plain [T][C].  Only patches of `act` are written.
+int gn_apply(const GroupNormArgs& a, const PatchGeom& g, int dtype, bool silu, bool padded, void* out,
+             ActiveList act, hipStream_t st);
+// Fill the one-pixel ring of every active padded patch from the interiors of its neighbours (zeros outside the image).
+int halo_gather(void* apad, const int32_t* halo_src, const PatchGeom& g, int32_t C, int32_t ring, int dtype,
+                ActiveList act, hipStream_t st);
+
+// ---- GEMM / implicit-GEMM convolution (gemm.hip) -----------------------------------------------
+struct GemmSeg {
+    void* ptr;                 // output of this column segment
+    int64_t ld;                // row stride (elements); for transposed: stride between channels
+    int32_t transposed;        // 1: out[col][row] instead of out[row][col]
+    float scale;               // multiplies the result (after bias)
+};
+enum { EPI_ROUTE = 0, EPI_GEGLU = 1 };
+struct GemmArgs {
+    const void* A;             // linear: [rows][lda]; conv: padded patch buffer
+    int64_t lda;
+    int32_t conv;              // 1: rows are tokens read through the padded layout with 9 taps
+    PatchGeom geom;
+    ActiveList act;            // row compaction by patch (rows are tokens)
+    int32_t tokens_are_rows;   // 1: row ids are token ids (act applies); 0: plain row ids (M rows)
+    int32_t M;                 // number of rows (upper bound when act is used: P*S)
+    int32_t N, K;              // N packed output columns, K reduction length per tap
+    int32_t taps;              // 1 or 9
+    const void* B;             // packed weights [taps][N][K]
+    const float* bias;         // [N] packed order, or nullptr
+    const void* res;           // residual [rows][ldr] or nullptr (added after bias)
+    int64_t ldr;
+    int32_t epi;               // EPI_ROUTE: columns go to segment col / seg_cols; EPI_GEGLU: value*GELU(gate) pairs
+    int32_t seg_cols;
+    GemmSeg seg[3];
+};
+int gemm(const GemmArgs& a, int dtype, int mode, hipStream_t st);
+
+// weight packing into [taps][N][K] (K contiguous); all on device
+int pack_conv(const void* w, void* dst, int32_t Cout, int32_t Cin, int dtype, hipStream_t st);
+// linear W[K][Ncols] -> rows [row0, row0+Ncols) of dst[Ntotal][K]
+int pack_linear(const void* w, void* dst, int32_t K, int32_t Ncols, int32_t row0, int dtype, hipStream_t st);
+// GEGLU: W1[K][2F] -> dst[2F][K] with value / gate columns interleaved in groups of GEGLU_GROUP
+int pack_geglu(const void* w1, const void* b1, void* dst, float* bias_dst, int32_t K, int32_t F, int dtype, hipStream_t st);
+int pack_bias(const void* b, float* dst, int32_t N, int dtype, hipStream_t st);
+constexpr int GEGLU_GROUP = 64;
+
+// ---- attention (attn.hip) -------------------------------------------------------------------------
+struct AttnArgs {
+    const void* Q;             // [T][C], already multiplied by log2(e)/sqrt(d)
+    const void* K;             // self: [T][C]; cross: [n*L][C]
+    const void* V;             // [rows][C], or transposed [C][ldv] when v_transposed
+    int64_t ldv;
+    int32_t v_transposed;
+    void* O;                   // [T][C]
+    int32_t C, heads, d;
+    PatchGeom geom;
+    ActiveList act;
+    const int32_t* owner;      // [P] sorted slot of a patch
+    const int32_t* cu_seqlens; // self: [n+1] token range of slot s
+    const int32_t* perm;       // cross: caller index of slot s
+    int32_t cross_len;         // 0 = self-attention; else keys of slot s are rows perm[s]*cross_len .. +cross_len
+    int32_t cross_ld;          // cross: padded key rows per request (>= cross_len)
+};
+int attention(const AttnArgs& a, int dtype, int mode, hipStream_t st);
+
+// ---- reuse (block.hip) -------------------------------------------------------------------------------
+
+}  // namespace pserve

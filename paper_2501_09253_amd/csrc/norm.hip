@@ -1,0 +1,274 @@
+// Segmented GroupNorm over the patch batch and the 3x3 halo gather.
+//
+// GroupNorm statistics of a patch batch must be those of the whole image: mean and
+// variance of a group are reduced over ALL patches of the owning request (the patches of
+// request s are RequestOffset[s] .. RequestOffset[s+1], "Compressed Sparse Patch Format").
+// The halo gather is the pull form of the paper's edge stitching ("Patch Edge Stitcher"):
+// border pixels of same-image neighbour patches, zeros where the neighbour is absent
+// ("Patch-Tailored Diffusion Operators").
+//
+// Three kernels for the norm:
+//   gn_partial_kernel   per (patch, token chunk): per-group sum and sum of squares (fp32),
+//                       16-byte loads, per-thread channel accumulators, LDS tree to groups
+//   gn_finalize_kernel  per (request, group): wavefront-shuffle reduction of the partials in
+//                       fp64 -> mean, rstd -> per (request, channel) scale and shift
+//   gn_apply_kernel     y = x*scale + shift (+SiLU), written plain or into the interior of
+//                       the padded patch buffer the convolution reads
+// Reductions are deterministic (no float atomics).
+#include "kernels.h"
+
+namespace pserve {
+
+template <typename T> struct Vec;
+template <> struct Vec<float> { static constexpr int N = 4; };
+template <> struct Vec<uint16_t> { static constexpr int N = 8; };
+
+template <typename T>
+__device__ __forceinline__ void load_vec(const T* p, float (&v)[Vec<T>::N]);
+template <>
+__device__ __forceinline__ void load_vec<float>(const float* p, float (&v)[4]) {
+    const float4 q = *reinterpret_cast<const float4*>(p);
+    v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+}
+template <>
+__device__ __forceinline__ void load_vec<uint16_t>(const uint16_t* p, float (&v)[8]) {
+    const uint4 q = *reinterpret_cast<const uint4*>(p);
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        v[2 * i] = __uint_as_float(w[i] << 16);
+        v[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+    }
+}
+template <typename T>
+__device__ __forceinline__ void store_vec(T* p, const float (&v)[Vec<T>::N]);
+template <>
+__device__ __forceinline__ void store_vec<float>(float* p, const float (&v)[4]) {
+    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+}
+template <>
+__device__ __forceinline__ void store_vec<uint16_t>(uint16_t* p, const float (&v)[8]) {
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        w[i] = (uint32_t)float_to_bf16_bits(v[2 * i]) | ((uint32_t)float_to_bf16_bits(v[2 * i + 1]) << 16);
+    *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// thread (tl, cv): cv = channel vector (fixed channels for the whole kernel), tl = token lane
+template <typename T>
+__global__ void gn_partial_kernel(const T* __restrict__ x, int32_t C, int32_t G, int32_t S, int32_t nsplit,
+                                  int32_t TL, float* __restrict__ partial) {
+    constexpr int VN = Vec<T>::N;
+    extern __shared__ float red[];             // [2][TL][C]
+    const int CV = C / VN;
+    const int cv = threadIdx.x % CV, tl = threadIdx.x / CV;
+    const int p = blockIdx.x, sp = blockIdx.y;
+    const int chunk = (S + nsplit - 1) / nsplit;
+    const int t0 = sp * chunk, t1 = min(S, t0 + chunk);
+    float s1[VN], s2[VN];
+#pragma unroll
+    for (int e = 0; e < VN; ++e) { s1[e] = 0.f; s2[e] = 0.f; }
+    const T* base = x + ((int64_t)p * S) * C + cv * VN;
+    for (int t = t0 + tl; t < t1; t += TL) {
+        float v[VN];
+        load_vec<T>(base + (int64_t)t * C, v);
+#pragma unroll
+        for (int e = 0; e < VN; ++e) { s1[e] += v[e]; s2[e] = fmaf(v[e], v[e], s2[e]); }
+    }
+#pragma unroll
+    for (int e = 0; e < VN; ++e) {
+        red[tl * C + cv * VN + e] = s1[e];
+        red[(TL + tl) * C + cv * VN + e] = s2[e];
+    }
+    __syncthreads();
+    const int cg = C / G;
+    for (int g = threadIdx.x; g < G; g += blockDim.x) {
+        float a = 0.f, b = 0.f;
+        for (int l = 0; l < TL; ++l)
+            for (int c = g * cg; c < (g + 1) * cg; ++c) { a += red[l * C + c]; b += red[(TL + l) * C + c]; }
+        float* dst = partial + (((int64_t)p * nsplit + sp) * G + g) * 2;
+        dst[0] = a;
+        dst[1] = b;
+    }
+}
+
+// block = one wavefront per (request slot s, group g)
+template <typename T>
+__global__ void gn_finalize_kernel(const float* __restrict__ partial, const int32_t* __restrict__ request_offset,
+                                   const T* __restrict__ gamma, const T* __restrict__ beta, int32_t C, int32_t G,
+                                   int32_t S, int32_t nsplit, float eps, float* __restrict__ scale_shift) {
+    const int s = blockIdx.x, g = blockIdx.y;
+    const int p0 = request_offset[s], p1 = request_offset[s + 1];
+    const int items = (p1 - p0) * nsplit;
+    double a = 0.0, b = 0.0;
+    for (int i = threadIdx.x; i < items; i += 64) {
+        const float* src = partial + (((int64_t)p0 * nsplit + i) * G + g) * 2;
+        a += (double)src[0];
+        b += (double)src[1];
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        a += __shfl_down(a, off, 64);
+        b += __shfl_down(b, off, 64);
+    }
+    a = __shfl(a, 0, 64);
+    b = __shfl(b, 0, 64);
+    const int cg = C / G;
+    const double cnt = (double)(p1 - p0) * S * cg;
+    const double mean = a / cnt;
+    double var = b / cnt - mean * mean;
+    var = var > 0.0 ? var : 0.0;
+    const double rstd = 1.0 / sqrt(var + (double)eps);
+    for (int c = g * cg + threadIdx.x; c < (g + 1) * cg; c += 64) {
+        const double sc = rstd * (double)ld_f<T>(gamma + c);
+        float* dst = scale_shift + ((int64_t)s * C + c) * 2;
+        dst[0] = (float)sc;
+        dst[1] = (float)((double)ld_f<T>(beta + c) - mean * sc);
+    }
+}
+
+__device__ __forceinline__ float silu_f(float v) { return __fdividef(v, 1.f + __expf(-v)); }
+
+template <typename T, bool SILU, bool PADDED>
+__global__ void gn_apply_kernel(const T* __restrict__ x, const float* __restrict__ scale_shift,
+                                const int32_t* __restrict__ owner, PatchGeom gm, int32_t C, int32_t nsplit, int32_t TL,
+                                ActiveList act, T* __restrict__ out) {
+    constexpr int VN = Vec<T>::N;
+    int p = blockIdx.x;
+    if (act.active) {
+        if (p >= *act.count) return;
+        p = act.active[p];
+    }
+    const int CV = C / VN;
+    const int cv = threadIdx.x % CV, tl = threadIdx.x / CV;
+    const int sp = blockIdx.y;
+    const int chunk = (gm.S + nsplit - 1) / nsplit;
+    const int t0 = sp * chunk, t1 = min(gm.S, t0 + chunk);
+    const int s = owner[p];
+    float sc[VN], sh[VN];
+    const float* ss = scale_shift + ((int64_t)s * C + cv * VN) * 2;
+#pragma unroll
+    for (int e = 0; e < VN; ++e) { sc[e] = ss[2 * e]; sh[e] = ss[2 * e + 1]; }
+    const T* base = x + ((int64_t)p * gm.S) * C + cv * VN;
+    for (int t = t0 + tl; t < t1; t += TL) {
+        float v[VN];
+        load_vec<T>(base + (int64_t)t * C, v);
+#pragma unroll
+        for (int e = 0; e < VN; ++e) {
+            v[e] = fmaf(v[e], sc[e], sh[e]);
+            if (SILU) v[e] = silu_f(v[e]);
+        }
+        int64_t o;
+        if (PADDED) {
+            const int y = t / gm.pw, xx = t - y * gm.pw;
+            o = ((int64_t)p * gm.pS + (y + 1) * gm.ppw + xx + 1) * C;
+        } else {
+            o = ((int64_t)p * gm.S + t) * C;
+        }
+        store_vec<T>(out + o + cv * VN, v);
+    }
+}
+
+// one thread per (ring entry, channel vector) of an active patch
+template <typename T>
+__global__ void halo_gather_kernel(T* __restrict__ apad, const int32_t* __restrict__ halo_src, PatchGeom gm,
+                                   int32_t C, int32_t ring, ActiveList act) {
+    constexpr int VN = Vec<T>::N;
+    int p = blockIdx.x;
+    if (act.active) {
+        if (p >= *act.count) return;
+        p = act.active[p];
+    }
+    const int CV = C / VN;
+    const int items = ring * CV;
+    for (int i = blockIdx.y * blockDim.x + threadIdx.x; i < items; i += gridDim.y * blockDim.x) {
+        const int k = i / CV, cv = i - k * CV;
+        int y, x;                          // ring pixel relative to the patch origin
+        if (k < gm.pw + 2) { y = -1; x = k - 1; }
+        else if (k < 2 * (gm.pw + 2)) { y = gm.ph; x = k - (gm.pw + 2) - 1; }
+        else if (k < 2 * (gm.pw + 2) + gm.ph) { y = k - 2 * (gm.pw + 2); x = -1; }
+        else { y = k - 2 * (gm.pw + 2) - gm.ph; x = gm.pw; }
+        const int tok = halo_src[(int64_t)p * ring + k];
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (tok >= 0) {
+            const int q = tok / gm.S, r = tok - q * gm.S;
+            const int ys = r / gm.pw, xs = r - ys * gm.pw;
+            v = *reinterpret_cast<const uint4*>(apad + ((int64_t)q * gm.pS + (ys + 1) * gm.ppw + xs + 1) * C + cv * VN);
+        }
+        *reinterpret_cast<uint4*>(apad + ((int64_t)p * gm.pS + (y + 1) * gm.ppw + x + 1) * C + cv * VN) = v;
+    }
+}
+
+// ---- host side ---------------------------------------------------------------------------------
+static int norm_layout(int32_t C, int dtype, int* CV, int* TL) {
+    const int vn = dtype == PSERVE_BF16 ? 8 : 4;
+    PS_REQUIRE(C % vn == 0, "GroupNorm: C=%d must be a multiple of %d for this dtype", C, vn);
+    *CV = C / vn;
+    PS_REQUIRE(*CV <= 1024, "GroupNorm: C=%d too wide", C);
+    int tl = (256 + *CV / 2) / *CV;
+    if (tl < 1) tl = 1;
+    while (tl * *CV > 1024) --tl;
+    *TL = tl;
+    return PSERVE_OK;
+}
+
+int gn_stats(const GroupNormArgs& a, const PatchGeom& g, int dtype, hipStream_t st) {
+    int CV, TL;
+    PS_TRY(norm_layout(a.C, dtype, &CV, &TL));
+    PS_REQUIRE(a.C % a.G == 0, "GroupNorm: C %% G != 0");
+    const size_t lds = sizeof(float) * 2 * TL * a.C;
+    PS_REQUIRE(lds <= 64 * 1024, "GroupNorm: C=%d too wide for the reduction buffer", a.C);
+    dim3 grid(g.P, a.nsplit);
+    if (dtype == PSERVE_BF16)
+        gn_partial_kernel<uint16_t><<<grid, TL * CV, lds, st>>>((const uint16_t*)a.x, a.C, a.G, g.S, a.nsplit, TL, a.partial);
+    else
+        gn_partial_kernel<float><<<grid, TL * CV, lds, st>>>((const float*)a.x, a.C, a.G, g.S, a.nsplit, TL, a.partial);
+    PS_TRY(check_launch("gn_partial_kernel"));
+    dim3 fgrid(a.n, a.G);
+    if (dtype == PSERVE_BF16)
+        gn_finalize_kernel<uint16_t><<<fgrid, 64, 0, st>>>(a.partial, a.request_offset, (const uint16_t*)a.gamma,
+                                                           (const uint16_t*)a.beta, a.C, a.G, g.S, a.nsplit, a.eps, a.scale_shift);
+    else
+        gn_finalize_kernel<float><<<fgrid, 64, 0, st>>>(a.partial, a.request_offset, (const float*)a.gamma,
+                                                        (const float*)a.beta, a.C, a.G, g.S, a.nsplit, a.eps, a.scale_shift);
+    return check_launch("gn_finalize_kernel");
+}
+
+template <typename T>
+static void launch_apply(const GroupNormArgs& a, const PatchGeom& g, bool silu, bool padded, void* out, ActiveList act,
+                         int CV, int TL, hipStream_t st) {
+    dim3 grid(g.P, a.nsplit);
+    const int nt = TL * CV;
+#define PS_APPLY(SI, PA)                                                                                          \
+    gn_apply_kernel<T, SI, PA><<<grid, nt, 0, st>>>((const T*)a.x, a.scale_shift, a.owner, g, a.C, a.nsplit, TL, act, (T*)out)
+    if (silu && padded) PS_APPLY(true, true);
+    else if (silu) PS_APPLY(true, false);
+    else if (padded) PS_APPLY(false, true);
+    else PS_APPLY(false, false);
+#undef PS_APPLY
+}
+
+int gn_apply(const GroupNormArgs& a, const PatchGeom& g, int dtype, bool silu, bool padded, void* out, ActiveList act,
+             hipStream_t st) {
+    int CV, TL;
+    PS_TRY(norm_layout(a.C, dtype, &CV, &TL));
+    if (dtype == PSERVE_BF16) launch_apply<uint16_t>(a, g, silu, padded, out, act, CV, TL, st);
+    else launch_apply<float>(a, g, silu, padded, out, act, CV, TL, st);
+    return check_launch("gn_apply_kernel");
+}
+
+int halo_gather(void* apad, const int32_t* halo_src, const PatchGeom& g, int32_t C, int32_t ring, int dtype,
+                ActiveList act, hipStream_t st) {
+    int CV, TL;
+    PS_TRY(norm_layout(C, dtype, &CV, &TL));
+    const int items = ring * CV;
+    dim3 grid(g.P, (unsigned)std::max<int64_t>(1, std::min<int64_t>(cdiv(items, 256 * 4), 64)));
+    if (dtype == PSERVE_BF16)
+        halo_gather_kernel<uint16_t><<<grid, 256, 0, st>>>((uint16_t*)apad, halo_src, g, C, ring, act);
+    else
+        halo_gather_kernel<float><<<grid, 256, 0, st>>>((float*)apad, halo_src, g, C, ring, act);
+    return check_launch("halo_gather_kernel");
+}
+
+}  // namespace pserve
