@@ -92,6 +92,19 @@ def test_small_blocks(stages, dtype, mode):
         ps.set_kernel_mode(0)
 
 
+@pytest.mark.parametrize("C,res,patch", [(128, [(16, 16), (8, 24), (8, 8)], (8, 8)), (320, [(16, 32), (16, 16)], (16, 16)),
+                                         (64, [(12, 20), (4, 4)], (4, 4))])
+@pytest.mark.parametrize("stages", [(wl.RES2,), (wl.SATTN, wl.XATTN, wl.FFN), (wl.RES1, wl.SATTN)])
+def test_mfma_shapes_bf16(stages, C, res, patch):
+    """bf16 blocks whose widths take the MFMA kernels (C multiple of 64, head dim 64), ragged M tails included."""
+    cfg = wl.custom_config(res, patch, C=C, G=32, heads=C // 64, stages=stages, dtype="bf16", ctx_len=77, ctx_dim=128,
+                           seed=31)
+    w = wl.make_workload(cfg)
+    got = GpuRun(w).forward_images()
+    ref, _ = _oracle(w)
+    assert rel_err(got, ref) < 2e-2
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_one_patch_image_equals_unpatched_and_patched(dtype):
     """Invariant: patch = whole image (no halo from neighbours, one patch per request) and the 4x4 patching
