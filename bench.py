@@ -1,0 +1,201 @@
+"""Benchmark of the hot path: patch-tokens/s of one mixed-resolution denoising block on one MI355X.
+
+A step = one pass of the whole hot path over one resident batch: split (per-image NCHW -> patch
+batch), pserve_block_forward, reassembly (patch batch -> per-image NCHW), on a plan built once
+for the batch composition (planner time is reported separately).  Inputs are resident in HBM
+before the timed region.  One JSON line is printed.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+
+
+def kernel_work(cfg, n_active_tokens):
+    """Algorithmic work per LAUNCH of each kernel label: (flops, bytes).
+
+    Units: tokens T (all patches) or computed tokens Ta; b = bytes per element; C channels.
+      conv3x3      2*9*C*C flops per computed token; bytes 2*b*C per token (read a, write o) + 18*C*C weights
+      linear_*     2*Cin*Cout flops per token
+      attn_self    4*N_i*C flops per query token of image i
+      attn_cross   4*L*C flops per token
+      gn_stats     b*C bytes per token (one read)
+      gn_apply     2*b*C bytes per token (read + write)
+      halo_gather  2*b*C*ring bytes per patch (read + write of the ring)
+      reuse_copy   2*b*C bytes per token
+    """
+    b = 2 if cfg.dtype == "bf16" else 4
+    C, T, Ta = cfg.C, cfg.T, n_active_tokens
+    ph, pw = cfg.patch
+    ring = 2 * (pw + 2) + 2 * ph
+    Pa = Ta // (ph * pw)
+    frac = Ta / T
+    F = cfg.ffn_mult * C
+    attn = sum(4.0 * (h * w) * (h * w) * C for h, w in cfg.resolutions) * frac
+    return {
+        "conv3x3": (2.0 * 9 * C * C * Ta, 2.0 * b * C * Ta + 9.0 * b * C * C),
+        "linear_qkv": (2.0 * C * 3 * C * Ta, b * 4.0 * C * Ta),
+        "linear_out": (2.0 * C * C * Ta, b * 3.0 * C * Ta),
+        "linear_q": (2.0 * C * C * Ta, b * 2.0 * C * Ta),
+        "linear_ctx_kv": (2.0 * cfg.ctx_dim * 2 * C * cfg.n * cfg.ctx_len, 0.0),
+        "ffn_geglu": (2.0 * C * 2 * F * Ta, b * (C + F) * Ta),
+        "ffn_out": (2.0 * F * C * Ta, b * (F + 2 * C) * Ta),
+        "attn_self": (attn, b * 4.0 * C * Ta),
+        "attn_cross": (4.0 * cfg.ctx_len * C * Ta, b * 2.0 * C * Ta),
+        "gn_stats": (0.0, 1.0 * b * C * T),
+        "gn_apply": (0.0, 2.0 * b * C * T),
+        "halo_gather": (0.0, 2.0 * b * C * ring * Pa),
+        "reuse_copy": (0.0, 2.0 * b * C * T),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (default: 2, the SDXL ResNet block)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket kernels with HIP events")
+    ap.add_argument("--all-kernels", action="store_true", help="add every kernel's time and roofline fraction to the JSON")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2501_09253_amd as ps
+    import workloads as wl
+    from harness import GpuRun
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = wl.config(args.config)
+    w = wl.make_workload(cfg)
+    t0 = time.perf_counter()
+    run = GpuRun(w)
+    torch.cuda.synchronize()
+    mask = None
+    n_active = cfg.T
+    if w.reuse is not None:
+        run.load_cache()
+        mask = run.plan_mask(w.reuse)
+        n_active = int((mask == 0).sum().item()) * cfg.patch[0] * cfg.patch[1]
+    # planner time (one-off per batch composition)
+    tp = time.perf_counter()
+    for _ in range(5):
+        p = ps.Plan(cfg.resolutions, *cfg.patch)
+        p.close()
+    plan_us = (time.perf_counter() - tp) / 5 * 1e6
+
+    y = torch.empty_like(run.x)
+    outs = [torch.empty_like(im) for im in run.images]
+
+    def step():
+        run.plan.split(run.images, out=run.x)
+        run.cache.forward(run.x, run.ctx, mask, y=y)
+        run.plan.reassemble(y, outs)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = not args.no_kernel_events
+    ps.profile_enable(events)
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t1
+    prof = ps.profile_read() if events else {}
+    ps.profile_enable(False)
+    ms_per_step = dt / args.steps * 1e3
+
+    # block-only time on the same stream, for reference
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        run.cache.forward(run.x, run.ctx, mask, y=y)
+    e1.record()
+    torch.cuda.synchronize()
+    block_ms = e0.elapsed_time(e1) / args.steps
+
+    work = kernel_work(cfg, n_active)
+    kernels = {}
+    for name, rec in prof.items():
+        avg_ms = rec["total_ms"] / rec["calls"]
+        fl, by = work.get(name, (0.0, 0.0))
+        ent = {"calls_per_step": rec["calls"] / args.steps, "avg_us": avg_ms * 1e3}
+        if fl > 0:
+            ent["tflops"] = fl / (avg_ms * 1e-3) / 1e12
+            ent["frac_mfma"] = ent["tflops"] / PEAK_BF16_TFLOPS
+        elif by > 0:
+            ent["gbs"] = by / (avg_ms * 1e-3) / 1e9
+            ent["frac_hbm"] = ent["gbs"] / PEAK_HBM_GBS
+        kernels[name] = ent
+    roofline = None
+    if kernels:
+        dom = max(prof, key=lambda k: prof[k]["total_ms"])
+        ent = kernels[dom]
+        if "tflops" in ent:
+            roofline = {"kernel": dom, "bound": "mfma", "achieved": ent["tflops"], "peak": PEAK_BF16_TFLOPS,
+                        "unit": "TFLOP/s", "frac": ent["frac_mfma"], "traffic": None,
+                        "avg_us": ent["avg_us"]}
+        else:
+            roofline = {"kernel": dom, "bound": "hbm", "achieved": ent.get("gbs"), "peak": PEAK_HBM_GBS,
+                        "unit": "GB/s", "frac": ent.get("frac_hbm"), "traffic": None, "avg_us": ent["avg_us"]}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import block as ob
+        from threadpoolctl import threadpool_info
+        # bounded sample: whole images of the workload, smallest first, until ~20 s of oracle time
+        order = sorted(range(cfg.n), key=lambda i: cfg.resolutions[i][0] * cfg.resolutions[i][1])
+        done_tok, tc = 0, time.perf_counter()
+        used = []
+        for i in order:
+            H, W = cfg.resolutions[i]
+            if H * W > 16384 and used:
+                continue                      # a 65,536-token image alone is minutes of fp64 attention
+            c_i = None if w.cache is None else {k: v[i] for k, v in w.cache.items()}
+            ob.block_forward(w.images[i], cfg.stages, w.params, G=cfg.G, heads=cfg.heads, eps=cfg.eps,
+                             ctx=None if w.ctx is None else w.ctx[i],
+                             reuse=None if w.reuse is None else w.reuse[i], cache=c_i)
+            done_tok += H * W
+            used.append(i)
+            if time.perf_counter() - tc > 20.0:
+                break
+        cpu_s = time.perf_counter() - tc
+        threads = max([t.get("num_threads", 1) for t in threadpool_info()] + [1])
+        cpu = {"value": done_tok / cpu_s, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+               "sample": f"{len(used)} of {cfg.n} images ({done_tok} of {cfg.T} tokens), whole block, fp64 numpy, {cpu_s:.1f} s"}
+
+    out = {
+        "metric": "patch-tokens/sec per mixed-res denoising block", "value": cfg.T / (ms_per_step * 1e-3),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"config{cfg.cfg_id} {cfg.name}: latents {sorted(set(cfg.resolutions))} x{cfg.n}, "
+                               f"patch {cfg.patch[0]}x{cfg.patch[1]}, P={cfg.P}, T={cfg.T}, C={cfg.C}, stages={'+'.join(cfg.stages)}"
+                               + (f", reuse p={cfg.reuse_p} ({cfg.T - n_active} tokens reused)" if w.reuse is not None else ""),
+                   "step": "split + block_forward + reassemble"},
+        "block_forward_ms": block_ms, "block_tokens_per_s": cfg.T / (block_ms * 1e-3), "plan_us": plan_us,
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    if args.all_kernels:
+        out["kernels"] = kernels
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

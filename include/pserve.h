@@ -177,6 +177,19 @@ int  pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* 
  * shapes (MFMA kernels where they apply), 1 = plain reference kernels only. */
 int  pserve_set_kernel_mode(int mode);
 
+/* ---- per-kernel timing for measurements.  While enabled, pserve_block_forward brackets every
+ * kernel it launches with a pair of HIP events recorded on the call's stream (no host
+ * synchronisation).  pserve_profile_read waits for the recorded events, sums the elapsed time per
+ * kernel label, fills up to `max` entries, sets *count to the number of labels and clears the
+ * records.  Not thread-safe; meant for benchmarks. */
+typedef struct {
+    char    name[32];     /* kernel label, e.g. "conv3x3", "gn_stats", "attn_self" */
+    int32_t calls;        /* launches recorded */
+    float   total_ms;     /* summed device time of those launches */
+} pserve_prof_entry;
+int  pserve_profile_enable(int on);
+int  pserve_profile_read(pserve_prof_entry* out, int32_t max, int32_t* count);
+
 #ifdef __cplusplus
 }
 #endif

@@ -47,6 +47,10 @@ class _BlockDesc(C.Structure):
                 ("ctx_dim", C.c_int32), ("ffn_mult", C.c_int32)]
 
 
+class _ProfEntry(C.Structure):
+    _fields_ = [("name", C.c_char * 32), ("calls", C.c_int32), ("total_ms", C.c_float)]
+
+
 class _BlockParams(C.Structure):
     _fields_ = [("p", (C.c_void_p * MAX_PARAMS) * MAX_STAGES)]
 
@@ -88,6 +92,8 @@ def lib() -> C.CDLL:
     L.pserve_cache_read.argtypes = [vp, C.c_int, C.c_int, vp, vp]
     L.pserve_block_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
     L.pserve_set_kernel_mode.argtypes = [C.c_int]
+    L.pserve_profile_enable.argtypes = [C.c_int]
+    L.pserve_profile_read.argtypes = [C.POINTER(_ProfEntry), i32, C.POINTER(i32)]
     _lib = L
     return L
 
@@ -110,6 +116,20 @@ def _torch_dtype(dtype: int):
 def set_kernel_mode(mode: int):
     """0 = fastest kernels for the shapes, 1 = plain reference kernels only."""
     _check(lib().pserve_set_kernel_mode(mode))
+
+
+def profile_enable(on: bool):
+    """Bracket every kernel of pserve_block_forward with HIP events (pserve_profile_enable)."""
+    _check(lib().pserve_profile_enable(int(on)))
+
+
+def profile_read() -> Dict[str, Dict[str, float]]:
+    """Collect {kernel label: {"calls": n, "total_ms": t}} since the last read (pserve_profile_read)."""
+    buf = (_ProfEntry * 64)()
+    n = C.c_int32()
+    _check(lib().pserve_profile_read(buf, 64, C.byref(n)))
+    return {buf[i].name.decode(): {"calls": int(buf[i].calls), "total_ms": float(buf[i].total_ms)}
+            for i in range(n.value)}
 
 
 class Plan:

@@ -12,11 +12,42 @@
 
 #include <algorithm>
 #include <new>
+#include <string.h>
 
 using namespace pserve;
 
 namespace pserve {
 static int g_kernel_mode = 0;
+
+// ---- optional per-kernel event timing ---------------------------------------------------------
+struct ProfRecord { const char* name; hipEvent_t start, stop; };
+struct Profiler {
+    bool on = false;
+    std::vector<ProfRecord> recs;
+    std::vector<hipEvent_t> pool;
+    hipEvent_t get() {
+        if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+        hipEvent_t e = nullptr;
+        if (hipEventCreate(&e) != hipSuccess) return nullptr;
+        return e;
+    }
+};
+static Profiler g_prof;
+struct ProfScope {
+    hipStream_t st;
+    hipEvent_t stop = nullptr;
+    ProfScope(const char* name, hipStream_t s) : st(s) {
+        if (!g_prof.on) return;
+        hipEvent_t start = g_prof.get();
+        stop = g_prof.get();
+        if (!start || !stop) { stop = nullptr; return; }
+        (void)hipEventRecord(start, st);
+        g_prof.recs.push_back({name, start, stop});
+    }
+    ~ProfScope() {
+        if (stop) (void)hipEventRecord(stop, st);
+    }
+};
 
 struct StageWeights {
     void* gn_g[2] = {};      // raw copies, block dtype
@@ -141,6 +172,35 @@ extern "C" {
 int pserve_set_kernel_mode(int mode) {
     PS_REQUIRE(mode == 0 || mode == 1, "pserve_set_kernel_mode: mode must be 0 or 1");
     g_kernel_mode = mode;
+    return PSERVE_OK;
+}
+
+int pserve_profile_enable(int on) {
+    g_prof.on = on != 0;
+    return PSERVE_OK;
+}
+
+int pserve_profile_read(pserve_prof_entry* out, int32_t max, int32_t* count) {
+    PS_REQUIRE(out && count && max > 0, "pserve_profile_read: bad arguments");
+    int n = 0;
+    for (const ProfRecord& r : g_prof.recs) {
+        PS_CHECK_HIP(hipEventSynchronize(r.stop));
+        float ms = 0.f;
+        PS_CHECK_HIP(hipEventElapsedTime(&ms, r.start, r.stop));
+        int k = 0;
+        while (k < n && strncmp(out[k].name, r.name, sizeof(out[k].name)) != 0) ++k;
+        if (k == n) {
+            if (n == max) continue;
+            memset(&out[n], 0, sizeof(out[n]));
+            strncpy(out[n].name, r.name, sizeof(out[n].name) - 1);
+            ++n;
+        }
+        out[k].calls += 1;
+        out[k].total_ms += ms;
+    }
+    for (const ProfRecord& r : g_prof.recs) { g_prof.pool.push_back(r.start); g_prof.pool.push_back(r.stop); }
+    g_prof.recs.clear();
+    *count = n;
     return PSERVE_OK;
 }
 
@@ -374,6 +434,7 @@ int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* c
 
     ActiveList act{nullptr, nullptr};
     if (reuse_mask) {
+        ProfScope ps("mask_compact", st);
         compact_mask_kernel<<<1, 1024, 0, st>>>(reuse_mask, plan->P, cache->active, cache->count);
         PS_TRY(check_launch("compact_mask_kernel"));
         act.active = cache->active;
@@ -400,12 +461,14 @@ int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* c
     // GroupNorm(+SiLU) of `in` into the padded buffer, halo ring, 3x3 convolution (+bias, +residual) into `out`
     auto norm_conv = [&](const void* in, const StageWeights& w, int ci, const void* res, void* out) -> int {
         GroupNormArgs ga = gn_args(in, w.gn_g[ci], w.gn_b[ci]);
-        PS_TRY(gn_stats(ga, gm, dt, st));
-        PS_TRY(gn_apply(ga, gm, dt, /*silu=*/true, /*padded=*/true, cache->apad, all, st));
-        PS_TRY(halo_gather(cache->apad, plan->d_tab[PSERVE_TAB_HALO_SRC], gm, C, plan->ring, dt, act, st));
+        { ProfScope ps("gn_stats", st); PS_TRY(gn_stats(ga, gm, dt, st)); }
+        { ProfScope ps("gn_apply", st); PS_TRY(gn_apply(ga, gm, dt, /*silu=*/true, /*padded=*/true, cache->apad, all, st)); }
+        { ProfScope ps("halo_gather", st);
+          PS_TRY(halo_gather(cache->apad, plan->d_tab[PSERVE_TAB_HALO_SRC], gm, C, plan->ring, dt, act, st)); }
         GemmArgs g = base_gemm(cache->apad, C, C, C, w.w[ci], w.b[ci]);
         g.conv = 1; g.taps = 9; g.res = res; g.ldr = C;
         g.seg[0].ptr = out; g.seg[0].ld = C;
+        ProfScope ps("conv3x3", st);
         return gemm(g, dt, mode, st);
     };
 
@@ -429,31 +492,32 @@ int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* c
         case PSERVE_SATTN: {
             const void* rin = cur;
             if (cache->with_slots && cur != cache->r[si]) {           // first stage: merge fresh input into the slot
+                ProfScope ps("reuse_copy", st);
                 copy_patches_kernel<<<copy_grid, 256, 0, st>>>((const uint4*)cur, (uint4*)cache->r[si], vec_per_patch,
                                                                reuse_mask, reuse_mask ? 1 : 0);
                 PS_TRY(check_launch("copy_patches_kernel"));
                 rin = cache->r[si];
             }
             GroupNormArgs ga = gn_args(rin, w.gn_g[0], w.gn_b[0]);
-            PS_TRY(gn_stats(ga, gm, dt, st));
-            PS_TRY(gn_apply(ga, gm, dt, false, false, cache->u, act, st));
+            { ProfScope ps("gn_stats", st); PS_TRY(gn_stats(ga, gm, dt, st)); }
+            { ProfScope ps("gn_apply", st); PS_TRY(gn_apply(ga, gm, dt, false, false, cache->u, act, st)); }
             GemmArgs g = base_gemm(cache->u, C, C, 3 * C, w.w[0], nullptr);
             g.seg_cols = C;
             g.seg[0].ptr = cache->q; g.seg[0].ld = C; g.seg[0].scale = qscale;
             g.seg[1].ptr = cache->k[si]; g.seg[1].ld = C;
             g.seg[2].ptr = cache->v[si]; g.seg[2].ld = cache->v_transposed ? T : C; g.seg[2].transposed = cache->v_transposed;
-            PS_TRY(gemm(g, dt, mode, st));
+            { ProfScope ps("linear_qkv", st); PS_TRY(gemm(g, dt, mode, st)); }
             AttnArgs aa{};
             aa.Q = cache->q; aa.K = cache->k[si]; aa.V = cache->v[si];
             aa.ldv = cache->v_transposed ? T : C; aa.v_transposed = cache->v_transposed;
             aa.O = cache->o; aa.C = C; aa.heads = d.heads; aa.d = C / d.heads; aa.geom = gm; aa.act = act;
             aa.owner = owner; aa.cu_seqlens = plan->d_tab[PSERVE_TAB_CU_SEQLENS]; aa.perm = plan->d_tab[PSERVE_TAB_PERM];
             aa.cross_len = 0; aa.cross_ld = 0;
-            PS_TRY(attention(aa, dt, mode, st));
+            { ProfScope ps("attn_self", st); PS_TRY(attention(aa, dt, mode, st)); }
             GemmArgs go = base_gemm(cache->o, C, C, C, w.w[1], w.b[1]);
             go.res = rin; go.ldr = C;
             go.seg[0].ptr = out; go.seg[0].ld = C;
-            PS_TRY(gemm(go, dt, mode, st));
+            { ProfScope ps("linear_out", st); PS_TRY(gemm(go, dt, mode, st)); }
             break;
         }
         case PSERVE_XATTN: {
@@ -461,20 +525,20 @@ int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* c
             gk.tokens_are_rows = 0; gk.act = all; gk.M = plan->n * d.ctx_len; gk.seg_cols = C;
             gk.seg[0].ptr = cache->kc; gk.seg[0].ld = C;
             gk.seg[1].ptr = cache->vc; gk.seg[1].ld = C;
-            PS_TRY(gemm(gk, dt, mode, st));
+            { ProfScope ps("linear_ctx_kv", st); PS_TRY(gemm(gk, dt, mode, st)); }
             GemmArgs gq = base_gemm(cur, C, C, C, w.w[0], nullptr);
             gq.seg[0].ptr = cache->q; gq.seg[0].ld = C; gq.seg[0].scale = qscale;
-            PS_TRY(gemm(gq, dt, mode, st));
+            { ProfScope ps("linear_q", st); PS_TRY(gemm(gq, dt, mode, st)); }
             AttnArgs aa{};
             aa.Q = cache->q; aa.K = cache->kc; aa.V = cache->vc; aa.ldv = C; aa.v_transposed = 0;
             aa.O = cache->o; aa.C = C; aa.heads = d.heads; aa.d = C / d.heads; aa.geom = gm; aa.act = act;
             aa.owner = owner; aa.cu_seqlens = plan->d_tab[PSERVE_TAB_CU_SEQLENS]; aa.perm = plan->d_tab[PSERVE_TAB_PERM];
             aa.cross_len = d.ctx_len; aa.cross_ld = cache->cross_ld;
-            PS_TRY(attention(aa, dt, mode, st));
+            { ProfScope ps("attn_cross", st); PS_TRY(attention(aa, dt, mode, st)); }
             GemmArgs go = base_gemm(cache->o, C, C, C, w.w[1], w.b[1]);
             go.res = cur; go.ldr = C;
             go.seg[0].ptr = out; go.seg[0].ld = C;
-            PS_TRY(gemm(go, dt, mode, st));
+            { ProfScope ps("linear_out", st); PS_TRY(gemm(go, dt, mode, st)); }
             break;
         }
         case PSERVE_FFN: {
@@ -482,11 +546,11 @@ int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* c
             GemmArgs g1 = base_gemm(cur, C, C, 2 * F, w.w[0], w.b[0]);
             g1.epi = EPI_GEGLU;
             g1.seg[0].ptr = cache->hidden; g1.seg[0].ld = F;
-            PS_TRY(gemm(g1, dt, mode, st));
+            { ProfScope ps("ffn_geglu", st); PS_TRY(gemm(g1, dt, mode, st)); }
             GemmArgs g2 = base_gemm(cache->hidden, F, F, C, w.w[1], w.b[1]);
             g2.res = cur; g2.ldr = C;
             g2.seg[0].ptr = out; g2.seg[0].ld = C;
-            PS_TRY(gemm(g2, dt, mode, st));
+            { ProfScope ps("ffn_out", st); PS_TRY(gemm(g2, dt, mode, st)); }
             break;
         }
         }
@@ -494,6 +558,7 @@ int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* c
     }
     if (cache->with_slots) {
         // computed patches refresh the output slot; reused patches take the cached output
+        ProfScope ps("reuse_copy", st);
         copy_patches_kernel<<<copy_grid, 256, 0, st>>>((const uint4*)y, (uint4*)cache->yslot, vec_per_patch, reuse_mask,
                                                        reuse_mask ? 1 : 0);
         PS_TRY(check_launch("copy_patches_kernel"));

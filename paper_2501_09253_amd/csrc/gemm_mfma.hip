@@ -14,6 +14,8 @@ namespace pserve {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 __device__ __forceinline__ float gelu_erf(float v) { return 0.5f * v * (1.f + erff(v * 0.70710678118654752f)); }
 
@@ -28,8 +30,8 @@ gemm_mfma_kernel(GemmArgs a) {
     constexpr int B_LD = BN * CH / 256;
     static_assert(BM % 64 == 0 && BN % 64 == 0 && (BM * CH) % 256 == 0 && (BN * CH) % 256 == 0, "tile shape");
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    uint4* sA = reinterpret_cast<uint4*>(smem);                       // [2][BM*CH]
-    uint4* sB = sA + 2 * BM * CH;                                     // [2][BN*CH]
+    u32x4* sA = reinterpret_cast<u32x4*>(smem);                       // [2][BM*CH]
+    u32x4* sB = sA + 2 * BM * CH;                                     // [2][BN*CH]
     int32_t* s_tok = reinterpret_cast<int32_t*>(sB + 2 * BN * CH);    // [BM] token of each row, -1 = no row
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -72,29 +74,7 @@ gemm_mfma_kernel(GemmArgs a) {
 
     const int kchunks = a.K / BK;
     const int KT = a.taps * kchunks;
-
-    uint4 ra[A_LD], rb[B_LD];
-    auto load_global = [&](int kt) {
-        const int tap = kt / kchunks, kc = kt - tap * kchunks;
-        const int64_t a_off = (a.conv ? ((int64_t)(tap / 3) * a.geom.ppw + (tap % 3)) * a.lda : 0) + kc * BK;
-        const int64_t b_off = (int64_t)tap * a.N * a.K + kc * BK;
-#pragma unroll
-        for (int i = 0; i < A_LD; ++i) ra[i] = *reinterpret_cast<const uint4*>(a_ptr[i] + a_off);
-#pragma unroll
-        for (int i = 0; i < B_LD; ++i) rb[i] = *reinterpret_cast<const uint4*>(b_ptr[i] + b_off);
-    };
-    auto store_lds = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < A_LD; ++i) {
-            const int row = lr + i * (256 / CH);
-            sA[buf * BM * CH + row * CH + (lc ^ (row & 7))] = ra[i];
-        }
-#pragma unroll
-        for (int i = 0; i < B_LD; ++i) {
-            const int row = lr + i * (256 / CH);
-            sB[buf * BN * CH + row * CH + (lc ^ (row & 7))] = rb[i];
-        }
-    };
+    const int64_t b_tap_stride = (int64_t)a.N * a.K;
 
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -104,86 +84,186 @@ gemm_mfma_kernel(GemmArgs a) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    load_global(0);
-    store_lds(0);
+    // LDS slots this thread writes (row-dependent swizzle is loop invariant)
+    int sa_slot[A_LD], sb_slot[B_LD];
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i) {
+        const int row = lr + i * (256 / CH);
+        sa_slot[i] = row * CH + (lc ^ (row & 7));
+    }
+#pragma unroll
+    for (int i = 0; i < B_LD; ++i) {
+        const int row = lr + i * (256 / CH);
+        sb_slot[i] = row * CH + (lc ^ (row & 7));
+    }
+
+    u32x4 ra[A_LD], rb[B_LD];
+    // K step 0
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i) ra[i] = *reinterpret_cast<const u32x4*>(a_ptr[i]);
+#pragma unroll
+    for (int i = 0; i < B_LD; ++i) rb[i] = *reinterpret_cast<const u32x4*>(b_ptr[i]);
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i) sA[sa_slot[i]] = ra[i];
+#pragma unroll
+    for (int i = 0; i < B_LD; ++i) sB[sb_slot[i]] = rb[i];
     __syncthreads();
 
     const int fr = lane & 31, fh = lane >> 5;       // fragment row within a 32-row tile, k half
+    // LDS fragment slots of this lane for k sub-step ks: chunk c = 2*ks + fh, swizzled by the row
+    int fa_row[TM], fb_row[TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa_row[i] = wm * WM + i * 32 + fr;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb_row[j] = wn * WN + j * 32 + fr;
+
+    bf16x8 fa[2][TM], fb[2][TN];                    // register double buffer of the MFMA fragments
+#define PS_READ_FRAGS(dst, cA_, cB_, ks_)                                                        \
+    {                                                                                            \
+        const int c_ = (ks_) * 2 + fh;                                                           \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                         \
+            const u32x4 v_ = (cA_)[fa_row[i] * CH + (c_ ^ (fa_row[i] & 7))];                     \
+            fa[dst][i] = __builtin_bit_cast(bf16x8, v_);                                  \
+        }                                                                                        \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                         \
+            const u32x4 v_ = (cB_)[fb_row[j] * CH + (c_ ^ (fb_row[j] & 7))];                     \
+            fb[dst][j] = __builtin_bit_cast(bf16x8, v_);                                  \
+        }                                                                                        \
+    }
+    PS_READ_FRAGS(0, sA, sB, 0);
+
+    int tap = 0, kc = 0;                            // position of the NEXT K step to fetch
     for (int kt = 0; kt < KT; ++kt) {
         const int buf = kt & 1;
-        if (kt + 1 < KT) load_global(kt + 1);
-        const uint4* cA = sA + buf * BM * CH;
-        const uint4* cB = sB + buf * BN * CH;
+        // prefetch the next K step into registers (the last iteration re-fetches its own step; never used)
+        if (kt + 1 < KT) {
+            if (++kc == kchunks) { kc = 0; ++tap; }
+        }
+        {
+            const int ty = tap / 3, tx = tap - ty * 3;
+            const int64_t a_off = (a.conv ? ((int64_t)ty * a.geom.ppw + tx) * a.lda : 0) + kc * BK;
+            const int64_t b_off = tap * b_tap_stride + kc * BK;
+#pragma unroll
+            for (int i = 0; i < A_LD; ++i) ra[i] = *reinterpret_cast<const u32x4*>(a_ptr[i] + a_off);
+#pragma unroll
+            for (int i = 0; i < B_LD; ++i) rb[i] = *reinterpret_cast<const u32x4*>(b_ptr[i] + b_off);
+        }
+        __builtin_amdgcn_sched_barrier(0);          // keep the global loads ahead of the MFMA section
+        const u32x4* cA = sA + buf * BM * CH;
+        const u32x4* cB = sB + buf * BN * CH;
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
-            const int c = ks * 2 + fh;              // 16-byte chunk holding k = ks*16 + fh*8 .. +8
-            bf16x8 fa[TM], fb[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const int row = wm * WM + i * 32 + fr;
-                const uint4 v = cA[row * CH + (c ^ (row & 7))];
-                fa[i] = *reinterpret_cast<const bf16x8*>(&v);
-            }
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int row = wn * WN + j * 32 + fr;
-                const uint4 v = cB[row * CH + (c ^ (row & 7))];
-                fb[j] = *reinterpret_cast<const bf16x8*>(&v);
-            }
+            if (ks + 1 < BK / 16) PS_READ_FRAGS((ks + 1) & 1, cA, cB, ks + 1);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (kt + 1 < KT) store_lds(buf ^ 1);
+        // stage the prefetched step into the other LDS buffer (nobody reads it during this iteration)
+        u32x4* nA = sA + (buf ^ 1) * BM * CH;
+        u32x4* nB = sB + (buf ^ 1) * BN * CH;
+#pragma unroll
+        for (int i = 0; i < A_LD; ++i) nA[sa_slot[i]] = ra[i];
+#pragma unroll
+        for (int i = 0; i < B_LD; ++i) nB[sb_slot[i]] = rb[i];
         __syncthreads();
+        PS_READ_FRAGS(0, nA, nB, 0);
     }
+#undef PS_READ_FRAGS
 
-    // ---- epilogue: lane holds column (lane % 32) of each 32x32 tile, rows 8*(e/4) + 4*(lane/32) + e%4
-    if (GEGLU) {
-        static_assert(!GEGLU || (WN == 2 * GEGLU_GROUP), "GEGLU needs a wavefront tile of [GROUP values | GROUP gates]");
-        uint16_t* out = (uint16_t*)a.seg[0].ptr;
-        const int64_t ld = a.seg[0].ld;
+    // ---- epilogue.  A lane holds column (lane % 32) of each 32x32 tile and rows 8*(e/4) + 4*(lane/32) + e%4.
+    // One tile column (WM rows x 32 columns) at a time is finished in registers (bias, scale, GEGLU), staged
+    // as fp32 in this wavefront's private LDS region and read back row-wise, so that residual loads and
+    // output stores are 16 bytes per lane and 64 contiguous bytes per row.
+    constexpr int EP_LD = 36;                                       // floats per staged row (16-byte aligned, skewed banks)
+    static_assert((size_t)4 * WM * EP_LD * sizeof(float) <= (size_t)2 * (BM + BN) * CH * 16, "epilogue staging fits");
+    float* ep = reinterpret_cast<float*>(smem) + wave * (WM * EP_LD);
+    const int32_t* w_tok = s_tok + wm * WM;
+    constexpr int TNO = GEGLU ? TN / 2 : TN;                        // output tile columns per wavefront
+    static_assert(!GEGLU || (WN == 2 * GEGLU_GROUP), "GEGLU needs a wavefront tile of [GROUP values | GROUP gates]");
 #pragma unroll
-        for (int j = 0; j < TN / 2; ++j) {
-            const int pc = n0 + wn * WN + j * 32 + fr;                // packed value column; gate at + GROUP
-            const int oc = (n0 + wn * WN) / 2 + j * 32 + fr;          // output column
-            const float bv = a.bias ? a.bias[pc] : 0.f, bg = a.bias ? a.bias[pc + GEGLU_GROUP] : 0.f;
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int row = wm * WM + i * 32 + 8 * (e >> 2) + 4 * fh + (e & 3);
-                    const int tok = s_tok[row];
-                    if (tok < 0) continue;
-                    const float v = (acc[i][j][e] + bv) * gelu_erf(acc[i][j + TN / 2][e] + bg);
-                    out[(int64_t)tok * ld + oc] = float_to_bf16_bits(v);
-                }
-        }
-    } else {
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = n0 + wn * WN + j * 32 + fr;
-            const int sg = col / a.seg_cols, c = col - sg * a.seg_cols;
-            const GemmSeg sgm = a.seg[sg];
-            uint16_t* out = (uint16_t*)sgm.ptr;
-            const float bias = a.bias ? a.bias[col] : 0.f;
-            const uint16_t* res = (const uint16_t*)a.res;
+    for (int j = 0; j < TNO; ++j) {
+        const int pcol = n0 + wn * WN + j * 32;                     // first packed column of the tile
+        int ocol0;                                                  // first output column within its segment
+        GemmSeg sgm;
+        float vals[TM][16];
+        if (GEGLU) {
+            const float bv = a.bias ? a.bias[pcol + fr] : 0.f, bg = a.bias ? a.bias[pcol + fr + GEGLU_GROUP] : 0.f;
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int row = wm * WM + i * 32 + 8 * (e >> 2) + 4 * fh + (e & 3);
-                    const int tok = s_tok[row];
-                    if (tok < 0) continue;
-                    float v = acc[i][j][e] + bias;
-                    if (res) v += bf16_bits_to_float(res[(int64_t)tok * a.ldr + col]);
-                    v *= sgm.scale;
-                    if (sgm.transposed) out[(int64_t)c * sgm.ld + tok] = float_to_bf16_bits(v);
-                    else out[(int64_t)tok * sgm.ld + c] = float_to_bf16_bits(v);
-                }
+                for (int e = 0; e < 16; ++e) vals[i][e] = (acc[i][j][e] + bv) * gelu_erf(acc[i][j + TN / 2][e] + bg);
+            sgm = a.seg[0];
+            ocol0 = (n0 + wn * WN) / 2 + j * 32;
+        } else {
+            const int sg = pcol / a.seg_cols;
+            sgm = sg == 0 ? a.seg[0] : (sg == 1 ? a.seg[1] : a.seg[2]);
+            ocol0 = pcol - sg * a.seg_cols;
+            const float bias = a.bias ? a.bias[pcol + fr] : 0.f;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) vals[i][e] = acc[i][j][e] + bias;
         }
+        uint16_t* out = (uint16_t*)sgm.ptr;
+        if (sgm.transposed) {
+            // out[col][token]: the four rows e%4 of a lane are consecutive tokens -> one 8-byte store
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int eg = 0; eg < 4; ++eg) {
+                    const int row = i * 32 + 8 * eg + 4 * fh;
+                    const int t0 = w_tok[row], t3 = w_tok[row + 3];
+                    uint16_t* dst = out + (int64_t)(ocol0 + fr) * sgm.ld;
+                    if (t0 >= 0 && t3 == t0 + 3 && (t0 & 3) == 0 && (sgm.ld & 3) == 0) {
+                        const uint32_t lo = (uint32_t)float_to_bf16_bits(vals[i][4 * eg] * sgm.scale) |
+                                            ((uint32_t)float_to_bf16_bits(vals[i][4 * eg + 1] * sgm.scale) << 16);
+                        const uint32_t hi = (uint32_t)float_to_bf16_bits(vals[i][4 * eg + 2] * sgm.scale) |
+                                            ((uint32_t)float_to_bf16_bits(vals[i][4 * eg + 3] * sgm.scale) << 16);
+                        *reinterpret_cast<uint2*>(dst + t0) = make_uint2(lo, hi);
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const int t = w_tok[row + q];
+                            if (t >= 0) dst[t] = float_to_bf16_bits(vals[i][4 * eg + q] * sgm.scale);
+                        }
+                    }
+                }
+            continue;
+        }
+        // stage the tile column: ep[row][col]
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) ep[(i * 32 + 8 * (e >> 2) + 4 * fh + (e & 3)) * EP_LD + fr] = vals[i][e];
+        __builtin_amdgcn_wave_barrier();
+        const uint16_t* res = (const uint16_t*)a.res;
+#pragma unroll
+        for (int t = 0; t < WM * 4 / 64; ++t) {
+            const int item = t * 64 + lane;
+            const int row = item >> 2, ch = item & 3;
+            const int tok = w_tok[row];
+            const f32x4 lo = *reinterpret_cast<const f32x4*>(ep + row * EP_LD + ch * 8);
+            const f32x4 hi = *reinterpret_cast<const f32x4*>(ep + row * EP_LD + ch * 8 + 4);
+            const int64_t tk = tok < 0 ? 0 : tok;                   // rows past the end read row 0 and store nothing
+            float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            if (!GEGLU && res) {
+                const u32x4 r = *reinterpret_cast<const u32x4*>(res + tk * a.ldr + pcol + ch * 8);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    v[2 * q] += __uint_as_float(r[q] << 16);
+                    v[2 * q + 1] += __uint_as_float(r[q] & 0xFFFF0000u);
+                }
+            }
+            u32x4 o;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                o[q] = (uint32_t)float_to_bf16_bits(v[2 * q] * sgm.scale) | ((uint32_t)float_to_bf16_bits(v[2 * q + 1] * sgm.scale) << 16);
+            if (tok >= 0) *reinterpret_cast<u32x4*>(out + tk * sgm.ld + ocol0 + ch * 8) = o;
+        }
+        __builtin_amdgcn_wave_barrier();
     }
 }
 
