@@ -152,6 +152,9 @@ struct pserve_cache_s {
     void* yslot = nullptr;                    // [T][C] block output of the previous step (slot Y)
     int32_t* active = nullptr;
     int32_t* count = nullptr;
+    int32_t* act_off = nullptr;               // [n+1] attention: computed patches before slot s
+    int32_t* tile_off = nullptr;              // [n+1] attention: query tiles before slot s
+    int32_t max_tiles = 0;
     DevicePool pool;
 };
 
@@ -341,9 +344,19 @@ int pserve_cache_create(const pserve_plan_t* plan, const pserve_block_t* block, 
     }
     if (sattn) PS_TRY(c->pool.alloc(&c->u, TC));
     if (xattn) {
-        c->cross_ld = d.ctx_len;
-        PS_TRY(c->pool.alloc(&c->kc, (size_t)plan->n * c->cross_ld * d.C * es));
-        PS_TRY(c->pool.alloc(&c->vc, (size_t)plan->n * c->cross_ld * d.C * es));
+        // text keys / values: rows padded to a multiple of 8 per request and zero-filled once, so that the
+        // padding rows (never written) contribute exact zeros; values transposed like the self-attention V
+        c->cross_ld = c->v_transposed ? (d.ctx_len + 7) / 8 * 8 : d.ctx_len;
+        const size_t bytes = (size_t)plan->n * c->cross_ld * d.C * es;
+        PS_TRY(c->pool.alloc(&c->kc, bytes));
+        PS_TRY(c->pool.alloc(&c->vc, bytes));
+        PS_CHECK_HIP(hipMemset(c->kc, 0, bytes));
+        PS_CHECK_HIP(hipMemset(c->vc, 0, bytes));
+    }
+    if (sattn || xattn) {
+        PS_TRY(c->pool.alloc_t(&c->act_off, (size_t)plan->n + 1));
+        PS_TRY(c->pool.alloc_t(&c->tile_off, (size_t)plan->n + 1));
+        c->max_tiles = attention_max_tiles(plan);
     }
     if (ffn) PS_TRY(c->pool.alloc(&c->hidden, (size_t)plan->T * d.ffn_mult * d.C * es));
     if (with_slots) PS_TRY(c->pool.alloc(&c->yslot, TC));
@@ -440,6 +453,10 @@ int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* c
         act.active = cache->active;
         act.count = cache->count;
     }
+    if (cache->act_off) {
+        ProfScope ps("attn_tiles", st);
+        PS_TRY(attention_tiles(request_offset, reuse_mask, plan->n, plan->S, cache->act_off, cache->tile_off, st));
+    }
     const ActiveList all{nullptr, nullptr};
     const float qscale = 1.4426950408889634f / sqrtf((float)(d.heads > 0 ? C / d.heads : 1));
 
@@ -513,6 +530,7 @@ int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* c
             aa.O = cache->o; aa.C = C; aa.heads = d.heads; aa.d = C / d.heads; aa.geom = gm; aa.act = act;
             aa.owner = owner; aa.cu_seqlens = plan->d_tab[PSERVE_TAB_CU_SEQLENS]; aa.perm = plan->d_tab[PSERVE_TAB_PERM];
             aa.cross_len = 0; aa.cross_ld = 0;
+            aa.act_off = cache->act_off; aa.tile_off = cache->tile_off; aa.n = plan->n; aa.max_tiles = cache->max_tiles;
             { ProfScope ps("attn_self", st); PS_TRY(attention(aa, dt, mode, st)); }
             GemmArgs go = base_gemm(cache->o, C, C, C, w.w[1], w.b[1]);
             go.res = rin; go.ldr = C;
@@ -523,17 +541,21 @@ int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* c
         case PSERVE_XATTN: {
             GemmArgs gk = base_gemm(ctx, d.ctx_dim, d.ctx_dim, 2 * C, w.w[2], nullptr);   // text keys / values of every request
             gk.tokens_are_rows = 0; gk.act = all; gk.M = plan->n * d.ctx_len; gk.seg_cols = C;
+            gk.row_group = d.ctx_len; gk.row_group_pad = cache->cross_ld;
+            const int64_t ctx_rows = (int64_t)plan->n * cache->cross_ld;
             gk.seg[0].ptr = cache->kc; gk.seg[0].ld = C;
-            gk.seg[1].ptr = cache->vc; gk.seg[1].ld = C;
+            gk.seg[1].ptr = cache->vc; gk.seg[1].ld = cache->v_transposed ? ctx_rows : C; gk.seg[1].transposed = cache->v_transposed;
             { ProfScope ps("linear_ctx_kv", st); PS_TRY(gemm(gk, dt, mode, st)); }
             GemmArgs gq = base_gemm(cur, C, C, C, w.w[0], nullptr);
             gq.seg[0].ptr = cache->q; gq.seg[0].ld = C; gq.seg[0].scale = qscale;
             { ProfScope ps("linear_q", st); PS_TRY(gemm(gq, dt, mode, st)); }
             AttnArgs aa{};
-            aa.Q = cache->q; aa.K = cache->kc; aa.V = cache->vc; aa.ldv = C; aa.v_transposed = 0;
+            aa.Q = cache->q; aa.K = cache->kc; aa.V = cache->vc;
+            aa.ldv = cache->v_transposed ? (int64_t)plan->n * cache->cross_ld : C; aa.v_transposed = cache->v_transposed;
             aa.O = cache->o; aa.C = C; aa.heads = d.heads; aa.d = C / d.heads; aa.geom = gm; aa.act = act;
             aa.owner = owner; aa.cu_seqlens = plan->d_tab[PSERVE_TAB_CU_SEQLENS]; aa.perm = plan->d_tab[PSERVE_TAB_PERM];
             aa.cross_len = d.ctx_len; aa.cross_ld = cache->cross_ld;
+            aa.act_off = cache->act_off; aa.tile_off = cache->tile_off; aa.n = plan->n; aa.max_tiles = cache->max_tiles;
             { ProfScope ps("attn_cross", st); PS_TRY(attention(aa, dt, mode, st)); }
             GemmArgs go = base_gemm(cache->o, C, C, C, w.w[1], w.b[1]);
             go.res = cur; go.ldr = C;

@@ -16,7 +16,8 @@ namespace pserve {
 
 // ---- row / column addressing shared by the kernels ------------------------------------------------
 struct RowInfo {
-    int64_t tok;       // row id used for output / residual addressing
+    int64_t tok;       // input row id
+    int64_t out_row;   // row id used for output / residual addressing
     int64_t a_off;     // element offset of the row's first A element (tap 0)
     bool valid;
 };
@@ -34,6 +35,7 @@ __device__ __forceinline__ RowInfo row_info(const GemmArgs& a, int ri) {
         valid = ri < a.M;
         if (!valid) tok = 0;
     }
+    r.out_row = (!a.tokens_are_rows && a.row_group > 0) ? (tok / a.row_group) * a.row_group_pad + tok % a.row_group : tok;
     r.tok = tok;
     r.valid = valid;
     if (a.conv) {
@@ -76,7 +78,7 @@ gemm_simple_kernel(GemmArgs a) {
     if (tid < BM) {
         const RowInfo r = row_info(a, m0 + tid);
         s_aoff[tid] = r.a_off;
-        s_tok[tid] = r.tok;
+        s_tok[tid] = r.out_row;
         s_valid[tid] = r.valid;
     }
     __syncthreads();

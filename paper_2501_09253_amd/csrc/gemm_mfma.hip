@@ -66,7 +66,11 @@ gemm_mfma_kernel(GemmArgs a) {
             off = tok * a.lda;
         }
         a_ptr[i] = A + off + lc * 8;
-        if (lc == 0) s_tok[row] = valid ? (int32_t)tok : -1;
+        if (lc == 0) {
+            int64_t orow = tok;
+            if (!a.tokens_are_rows && a.row_group > 0) orow = (tok / a.row_group) * a.row_group_pad + tok % a.row_group;
+            s_tok[row] = valid ? (int32_t)orow : -1;
+        }
     }
     const uint16_t* b_ptr[B_LD];
 #pragma unroll
@@ -218,10 +222,8 @@ gemm_mfma_kernel(GemmArgs a) {
                     const int t0 = w_tok[row], t3 = w_tok[row + 3];
                     uint16_t* dst = out + (int64_t)(ocol0 + fr) * sgm.ld;
                     if (t0 >= 0 && t3 == t0 + 3 && (t0 & 3) == 0 && (sgm.ld & 3) == 0) {
-                        const uint32_t lo = (uint32_t)float_to_bf16_bits(vals[i][4 * eg] * sgm.scale) |
-                                            ((uint32_t)float_to_bf16_bits(vals[i][4 * eg + 1] * sgm.scale) << 16);
-                        const uint32_t hi = (uint32_t)float_to_bf16_bits(vals[i][4 * eg + 2] * sgm.scale) |
-                                            ((uint32_t)float_to_bf16_bits(vals[i][4 * eg + 3] * sgm.scale) << 16);
+                        const uint32_t lo = pack_bf16x2(vals[i][4 * eg] * sgm.scale, vals[i][4 * eg + 1] * sgm.scale);
+                        const uint32_t hi = pack_bf16x2(vals[i][4 * eg + 2] * sgm.scale, vals[i][4 * eg + 3] * sgm.scale);
                         *reinterpret_cast<uint2*>(dst + t0) = make_uint2(lo, hi);
                     } else {
 #pragma unroll
@@ -260,7 +262,7 @@ gemm_mfma_kernel(GemmArgs a) {
             u32x4 o;
 #pragma unroll
             for (int q = 0; q < 4; ++q)
-                o[q] = (uint32_t)float_to_bf16_bits(v[2 * q] * sgm.scale) | ((uint32_t)float_to_bf16_bits(v[2 * q + 1] * sgm.scale) << 16);
+                o[q] = pack_bf16x2(v[2 * q] * sgm.scale, v[2 * q + 1] * sgm.scale);
             if (tok >= 0) *reinterpret_cast<u32x4*>(out + tk * sgm.ld + ocol0 + ch * 8) = o;
         }
         __builtin_amdgcn_wave_barrier();

@@ -7,11 +7,14 @@ namespace pserve {
 
 // ---- element access helpers (device) ------------------------------------------------------
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
-__device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {       // round to nearest even
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40);   // quiet NaN
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {       // round to nearest even (v_cvt_pk_bf16_f32)
+    return __builtin_bit_cast(uint16_t, (__bf16)f);
+}
+// two floats -> packed bf16 pair (lo in bits 0..15), one v_cvt_pk_bf16_f32
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t));
 }
 template <typename T> __device__ __forceinline__ float ld_f(const T* p);
 template <> __device__ __forceinline__ float ld_f<float>(const float* p) { return *p; }
@@ -71,6 +74,7 @@ struct GemmArgs {
     ActiveList act;            // row compaction by patch (rows are tokens)
     int32_t tokens_are_rows;   // 1: row ids are token ids (act applies); 0: plain row ids (M rows)
     int32_t M;                 // number of rows (upper bound when act is used: P*S)
+    int32_t row_group, row_group_pad;   // plain rows only: output row = (r / row_group) * row_group_pad + r % row_group (0 = identity)
     int32_t N, K;              // N packed output columns, K reduction length per tap
     int32_t taps;              // 1 or 9
     const void* B;             // packed weights [taps][N][K]
@@ -108,7 +112,15 @@ struct AttnArgs {
     const int32_t* perm;       // cross: caller index of slot s
     int32_t cross_len;         // 0 = self-attention; else keys of slot s are rows perm[s]*cross_len .. +cross_len
     int32_t cross_ld;          // cross: padded key rows per request (>= cross_len)
+    // query tiling of the MFMA kernel (attention_tiles fills the two prefix tables)
+    const int32_t* act_off;    // [n+1] computed patches before slot s (== RequestOffset without a mask)
+    const int32_t* tile_off;   // [n+1] query tiles before slot s
+    int32_t n;                 // request slots
+    int32_t max_tiles;         // host upper bound of tile_off[n]
 };
+int attention_tiles(const int32_t* request_offset, const uint8_t* mask, int32_t n, int32_t S, int32_t* act_off,
+                    int32_t* tile_off, hipStream_t st);
+int attention_max_tiles(const pserve_plan_t* plan);
 int attention(const AttnArgs& a, int dtype, int mode, hipStream_t st);
 
 // ---- reuse (block.hip) -------------------------------------------------------------------------------
