@@ -19,6 +19,15 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 __device__ __forceinline__ float gelu_erf(float v) { return 0.5f * v * (1.f + erff(v * 0.70710678118654752f)); }
 
+typedef __attribute__((address_space(3))) void lds_void;
+
+// LDS bytes of one kernel instance: NS stages of (BM + BN) rows x 128 bytes, plus the row -> token table
+template <int BM, int BN> struct GemmCfg {
+    static constexpr int STAGE = (BM + BN) * 128;
+    static constexpr int NS = (3 * STAGE + BM * 4 <= 160 * 1024) ? 3 : 2;
+    static constexpr size_t LDS = (size_t)NS * STAGE + BM * sizeof(int32_t);
+};
+
 template <int BM, int BN, bool GEGLU>
 __global__ void __launch_bounds__(256)
 gemm_mfma_kernel(GemmArgs a) {
@@ -28,25 +37,29 @@ gemm_mfma_kernel(GemmArgs a) {
     constexpr int TM = WM / 32, TN = WN / 32;       // 32x32 MFMA tiles per wavefront
     constexpr int A_LD = BM * CH / 256;             // 16-byte loads per thread and K step
     constexpr int B_LD = BN * CH / 256;
+    constexpr int NS = GemmCfg<BM, BN>::NS;         // LDS ring depth
+    constexpr int STAGE_V = (BM + BN) * CH;         // 16-byte slots per stage: A rows then B rows
     static_assert(BM % 64 == 0 && BN % 64 == 0 && (BM * CH) % 256 == 0 && (BN * CH) % 256 == 0, "tile shape");
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    u32x4* sA = reinterpret_cast<u32x4*>(smem);                       // [2][BM*CH]
-    u32x4* sB = sA + 2 * BM * CH;                                     // [2][BN*CH]
-    int32_t* s_tok = reinterpret_cast<int32_t*>(sB + 2 * BN * CH);    // [BM] token of each row, -1 = no row
+    u32x4* ring = reinterpret_cast<u32x4*>(smem);                     // [NS][STAGE_V]
+    int32_t* s_tok = reinterpret_cast<int32_t*>(ring + NS * STAGE_V); // [BM] output row of each tile row, -1 = none
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
     if (a.tokens_are_rows && a.act.active && m0 >= *a.act.count * a.geom.S) return;
 
-    // rows this thread stages: chunk (tid % CH) of rows tid / CH + i * (256 / CH)
-    const int lc = tid % CH, lr = tid / CH;
+    // Staging by direct global -> LDS loads.  One wavefront instruction fills 64 consecutive 16-byte slots
+    // (8 rows x 8 chunk positions); the lane at (row, position pos) fetches global chunk pos ^ f(row),
+    // f(row) = (row >> 1) & 7, so the swizzle costs nothing.  Thread rows: lr + 32*i, position lc.
+    const int lc = lane & 7, lr = 8 * wave + (lane >> 3);
+    const int gc = lc ^ ((lr >> 1) & 7);            // global chunk this lane fetches (same for every i)
     const uint16_t* A = (const uint16_t*)a.A;
     const uint16_t* B = (const uint16_t*)a.B;
     const uint16_t* a_ptr[A_LD];
 #pragma unroll
     for (int i = 0; i < A_LD; ++i) {
-        const int row = lr + i * (256 / CH);
+        const int row = lr + i * 32;
         int64_t tok = m0 + row;
         bool valid;
         if (a.tokens_are_rows && a.act.active) {
@@ -65,16 +78,15 @@ gemm_mfma_kernel(GemmArgs a) {
         } else {
             off = tok * a.lda;
         }
-        a_ptr[i] = A + off + lc * 8;
+        a_ptr[i] = A + off + gc * 8;
         if (lc == 0) {
             int64_t orow = tok;
             if (!a.tokens_are_rows && a.row_group > 0) orow = (tok / a.row_group) * a.row_group_pad + tok % a.row_group;
             s_tok[row] = valid ? (int32_t)orow : -1;
         }
     }
-    const uint16_t* b_ptr[B_LD];
-#pragma unroll
-    for (int i = 0; i < B_LD; ++i) b_ptr[i] = B + (int64_t)(n0 + lr + i * (256 / CH)) * a.K + lc * 8;
+    const uint16_t* b_ptr = B + (int64_t)(n0 + lr) * a.K + gc * 8;
+    const int64_t b_row32 = (int64_t)32 * a.K;
 
     const int kchunks = a.K / BK;
     const int KT = a.taps * kchunks;
@@ -88,76 +100,59 @@ gemm_mfma_kernel(GemmArgs a) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    // LDS slots this thread writes (row-dependent swizzle is loop invariant)
-    int sa_slot[A_LD], sb_slot[B_LD];
-#pragma unroll
-    for (int i = 0; i < A_LD; ++i) {
-        const int row = lr + i * (256 / CH);
-        sa_slot[i] = row * CH + (lc ^ (row & 7));
-    }
-#pragma unroll
-    for (int i = 0; i < B_LD; ++i) {
-        const int row = lr + i * (256 / CH);
-        sb_slot[i] = row * CH + (lc ^ (row & 7));
+    // issue the loads of K step (tap_, kc_) into ring stage st_
+#define PS_ISSUE(st_, tap_, kc_)                                                                          \
+    {                                                                                                     \
+        const int ty_ = (tap_) / 3, tx_ = (tap_) - ty_ * 3;                                               \
+        const int64_t a_off_ = (a.conv ? ((int64_t)ty_ * a.geom.ppw + tx_) * a.lda : 0) + (kc_) * BK;     \
+        const int64_t b_off_ = (tap_) * b_tap_stride + (kc_) * BK;                                        \
+        u32x4* dst_ = ring + (st_) * STAGE_V + wave * 64;                                                 \
+        _Pragma("unroll") for (int i = 0; i < A_LD; ++i)                                                  \
+            __builtin_amdgcn_global_load_lds((const void*)(a_ptr[i] + a_off_), (lds_void*)(dst_ + i * 256), 16, 0, 0); \
+        _Pragma("unroll") for (int i = 0; i < B_LD; ++i)                                                  \
+            __builtin_amdgcn_global_load_lds((const void*)(b_ptr + i * b_row32 + b_off_),                 \
+                                             (lds_void*)(dst_ + BM * CH + i * 256), 16, 0, 0);            \
     }
 
-    u32x4 ra[A_LD], rb[B_LD];
-    // K step 0
+    int tap = 0, kc = 0;                            // K step that is issued next
 #pragma unroll
-    for (int i = 0; i < A_LD; ++i) ra[i] = *reinterpret_cast<const u32x4*>(a_ptr[i]);
-#pragma unroll
-    for (int i = 0; i < B_LD; ++i) rb[i] = *reinterpret_cast<const u32x4*>(b_ptr[i]);
-#pragma unroll
-    for (int i = 0; i < A_LD; ++i) sA[sa_slot[i]] = ra[i];
-#pragma unroll
-    for (int i = 0; i < B_LD; ++i) sB[sb_slot[i]] = rb[i];
-    __syncthreads();
+    for (int st = 0; st < NS - 1; ++st) {           // prologue: NS-1 stages in flight
+        PS_ISSUE(st, tap, kc);
+        if (st + 1 < KT) { if (++kc == kchunks) { kc = 0; ++tap; } }
+    }
 
     const int fr = lane & 31, fh = lane >> 5;       // fragment row within a 32-row tile, k half
-    // LDS fragment slots of this lane for k sub-step ks: chunk c = 2*ks + fh, swizzled by the row
-    int fa_row[TM], fb_row[TN];
+    // LDS fragment slots of this lane: row*CH + ((2*ks + fh) ^ f(row))
+    int fa_base[TM], fa_sw[TM], fb_base[TN], fb_sw[TN];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) fa_row[i] = wm * WM + i * 32 + fr;
+    for (int i = 0; i < TM; ++i) { const int r = wm * WM + i * 32 + fr; fa_base[i] = r * CH; fa_sw[i] = (r >> 1) & 7; }
 #pragma unroll
-    for (int j = 0; j < TN; ++j) fb_row[j] = wn * WN + j * 32 + fr;
+    for (int j = 0; j < TN; ++j) { const int r = wn * WN + j * 32 + fr; fb_base[j] = BM * CH + r * CH; fb_sw[j] = (r >> 1) & 7; }
 
     bf16x8 fa[2][TM], fb[2][TN];                    // register double buffer of the MFMA fragments
-#define PS_READ_FRAGS(dst, cA_, cB_, ks_)                                                        \
+#define PS_READ_FRAGS(dst, stage_, ks_)                                                          \
     {                                                                                            \
         const int c_ = (ks_) * 2 + fh;                                                           \
-        _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                         \
-            const u32x4 v_ = (cA_)[fa_row[i] * CH + (c_ ^ (fa_row[i] & 7))];                     \
-            fa[dst][i] = __builtin_bit_cast(bf16x8, v_);                                  \
-        }                                                                                        \
-        _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                         \
-            const u32x4 v_ = (cB_)[fb_row[j] * CH + (c_ ^ (fb_row[j] & 7))];                     \
-            fb[dst][j] = __builtin_bit_cast(bf16x8, v_);                                  \
-        }                                                                                        \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i)                                           \
+            fa[dst][i] = __builtin_bit_cast(bf16x8, (stage_)[fa_base[i] + (c_ ^ fa_sw[i])]);     \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j)                                           \
+            fb[dst][j] = __builtin_bit_cast(bf16x8, (stage_)[fb_base[j] + (c_ ^ fb_sw[j])]);     \
     }
-    PS_READ_FRAGS(0, sA, sB, 0);
 
-    int tap = 0, kc = 0;                            // position of the NEXT K step to fetch
+    int rd = 0, wr = NS - 1;                        // ring stage read now / written next
     for (int kt = 0; kt < KT; ++kt) {
-        const int buf = kt & 1;
-        // prefetch the next K step into registers (the last iteration re-fetches its own step; never used)
-        if (kt + 1 < KT) {
-            if (++kc == kchunks) { kc = 0; ++tap; }
-        }
-        {
-            const int ty = tap / 3, tx = tap - ty * 3;
-            const int64_t a_off = (a.conv ? ((int64_t)ty * a.geom.ppw + tx) * a.lda : 0) + kc * BK;
-            const int64_t b_off = tap * b_tap_stride + kc * BK;
-#pragma unroll
-            for (int i = 0; i < A_LD; ++i) ra[i] = *reinterpret_cast<const u32x4*>(a_ptr[i] + a_off);
-#pragma unroll
-            for (int i = 0; i < B_LD; ++i) rb[i] = *reinterpret_cast<const u32x4*>(b_ptr[i] + b_off);
-        }
-        __builtin_amdgcn_sched_barrier(0);          // keep the global loads ahead of the MFMA section
-        const u32x4* cA = sA + buf * BM * CH;
-        const u32x4* cB = sB + buf * BN * CH;
+        // own loads of stage kt have landed when at most (NS-2) later stages are still in flight
+        if (NS == 2) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * (A_LD + B_LD)) : "memory");
+        __syncthreads();                            // everyone's loads of stage kt visible; stage kt-1 is free
+        // refill the freed stage with K step kt + NS - 1 (past the end: re-fetch the last step, never read)
+        PS_ISSUE(wr, tap, kc);
+        if (kt + NS < KT) { if (++kc == kchunks) { kc = 0; ++tap; } }
+        const u32x4* cur = ring + rd * STAGE_V;
+        PS_READ_FRAGS(0, cur, 0);
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
-            if (ks + 1 < BK / 16) PS_READ_FRAGS((ks + 1) & 1, cA, cB, ks + 1);
+            if (ks + 1 < BK / 16) PS_READ_FRAGS((ks + 1) & 1, cur, ks + 1);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -165,24 +160,20 @@ gemm_mfma_kernel(GemmArgs a) {
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
-        // stage the prefetched step into the other LDS buffer (nobody reads it during this iteration)
-        u32x4* nA = sA + (buf ^ 1) * BM * CH;
-        u32x4* nB = sB + (buf ^ 1) * BN * CH;
-#pragma unroll
-        for (int i = 0; i < A_LD; ++i) nA[sa_slot[i]] = ra[i];
-#pragma unroll
-        for (int i = 0; i < B_LD; ++i) nB[sb_slot[i]] = rb[i];
-        __syncthreads();
-        PS_READ_FRAGS(0, nA, nB, 0);
+        rd = rd + 1 == NS ? 0 : rd + 1;
+        wr = wr + 1 == NS ? 0 : wr + 1;
     }
 #undef PS_READ_FRAGS
+#undef PS_ISSUE
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();                                // ring is reused by the epilogue
 
     // ---- epilogue.  A lane holds column (lane % 32) of each 32x32 tile and rows 8*(e/4) + 4*(lane/32) + e%4.
     // One tile column (WM rows x 32 columns) at a time is finished in registers (bias, scale, GEGLU), staged
     // as fp32 in this wavefront's private LDS region and read back row-wise, so that residual loads and
     // output stores are 16 bytes per lane and 64 contiguous bytes per row.
     constexpr int EP_LD = 36;                                       // floats per staged row (16-byte aligned, skewed banks)
-    static_assert((size_t)4 * WM * EP_LD * sizeof(float) <= (size_t)2 * (BM + BN) * CH * 16, "epilogue staging fits");
+    static_assert((size_t)4 * WM * EP_LD * sizeof(float) <= (size_t)NS * STAGE_V * 16, "epilogue staging fits");
     float* ep = reinterpret_cast<float*>(smem) + wave * (WM * EP_LD);
     const int32_t* w_tok = s_tok + wm * WM;
     constexpr int TNO = GEGLU ? TN / 2 : TN;                        // output tile columns per wavefront
@@ -271,7 +262,7 @@ gemm_mfma_kernel(GemmArgs a) {
 
 template <int BM, int BN, bool GEGLU>
 static int launch(const GemmArgs& a, hipStream_t st) {
-    constexpr size_t lds = (size_t)2 * (BM + BN) * 8 * 16 + BM * sizeof(int32_t);
+    constexpr size_t lds = GemmCfg<BM, BN>::LDS;
     static bool attr_set = false;
     if (!attr_set) {
         PS_CHECK_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<BM, BN, GEGLU>,
