@@ -163,7 +163,10 @@ def main():
         order = sorted(range(cfg.n), key=lambda i: cfg.resolutions[i][0] * cfg.resolutions[i][1])
         done_tok, tc = 0, time.perf_counter()
         used = []
-        for i in order:
+        passes = 0
+        while time.perf_counter() - tc < 10.0:          # repeat whole passes until about 10 s of oracle time
+          passes += 1
+          for i in order:
             H, W = cfg.resolutions[i]
             if H * W > 16384 and used:
                 continue                      # a 65,536-token image alone is minutes of fp64 attention
@@ -173,12 +176,13 @@ def main():
                              reuse=None if w.reuse is None else w.reuse[i], cache=c_i)
             done_tok += H * W
             used.append(i)
-            if time.perf_counter() - tc > 20.0:
+            if time.perf_counter() - tc > 25.0:
                 break
         cpu_s = time.perf_counter() - tc
         threads = max([t.get("num_threads", 1) for t in threadpool_info()] + [1])
         cpu = {"value": done_tok / cpu_s, "unit": "tokens/s", "cores": threads, "kind": "oracle",
-               "sample": f"{len(used)} of {cfg.n} images ({done_tok} of {cfg.T} tokens), whole block, fp64 numpy, {cpu_s:.1f} s"}
+               "sample": f"{passes} pass(es) over {len(set(used))} of {cfg.n} images ({done_tok} tokens in total), whole block, "
+                         f"fp64 numpy, {cpu_s:.1f} s"}
 
     out = {
         "metric": "patch-tokens/sec per mixed-res denoising block", "value": cfg.T / (ms_per_step * 1e-3),

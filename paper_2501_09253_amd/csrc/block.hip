@@ -320,7 +320,7 @@ int pserve_cache_create(const pserve_plan_t* plan, const pserve_block_t* block, 
     const size_t TC = (size_t)plan->T * d.C * es;
     const int head_dim = d.heads > 0 ? d.C / d.heads : 0;
     c->v_transposed = d.dtype == PSERVE_BF16 && head_dim == 64 && g_kernel_mode == 0;
-    c->nsplit = (int)std::max<int64_t>(1, std::min<int64_t>(cdiv(2048, plan->P), std::max(1, plan->S / 16)));
+    c->nsplit = (int)std::max<int64_t>(1, std::min<int64_t>(cdiv(768, plan->P), std::max(1, plan->S / 32)));
     PS_TRY(c->pool.alloc(&c->ping[0], TC));
     PS_TRY(c->pool.alloc(&c->ping[1], TC));
     const bool conv = has_stage(d, PSERVE_RES1) || has_stage(d, PSERVE_RES2);

@@ -19,6 +19,124 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 __device__ __forceinline__ float gelu_erf(float v) { return 0.5f * v * (1.f + erff(v * 0.70710678118654752f)); }
 
+// ---- epilogue shared by the kernels.  A lane holds column (lane % 32) of each 32x32 tile and rows
+// 8*(e/4) + 4*(lane/32) + e%4.  One tile column (WM rows x 32 columns) at a time is finished in registers (bias,
+// scale, GEGLU), staged as fp32 in this wavefront's private LDS region and read back row-wise, so that residual
+// loads and output stores are 16 bytes per lane and 64 contiguous bytes per row.  Residual loads of the next tile
+// column are issued before the current one is staged.  `smem` must be free (all staged operands consumed).
+template <int BM, int BN, bool GEGLU>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[BM / 64][BN / 64], uint8_t* smem,
+                                              const int32_t* s_tok, int n0) {
+    constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int fr = lane & 31, fh = lane >> 5;
+    constexpr int EP_LD = 36;                                       // floats per staged row (16-byte aligned, skewed banks)
+    float* ep = reinterpret_cast<float*>(smem) + wave * (WM * EP_LD);
+    const int32_t* w_tok = s_tok + wm * WM;
+    constexpr int TNO = GEGLU ? TN / 2 : TN;                        // output tile columns per wavefront
+    static_assert(!GEGLU || (WN == 2 * GEGLU_GROUP), "GEGLU needs a wavefront tile of [GROUP values | GROUP gates]");
+    // residual rows of this lane's read-back items (row = item / 4, 8-column chunk = item % 4)
+    constexpr int NIT = WM * 4 / 64;
+    const bool HAS_RES = !GEGLU && a.res != nullptr;
+    const uint16_t* res_row[NIT];
+    u32x4 rres[2][NIT];
+#pragma unroll
+    for (int t = 0; t < NIT; ++t) {
+        const int item = t * 64 + lane;
+        const int tok = w_tok[item >> 2];
+        res_row[t] = (const uint16_t*)a.res + (int64_t)(tok < 0 ? 0 : tok) * a.ldr + (item & 3) * 8;
+    }
+    if (HAS_RES) {
+#pragma unroll
+        for (int t = 0; t < NIT; ++t) rres[0][t] = *reinterpret_cast<const u32x4*>(res_row[t] + n0 + wn * WN);
+    }
+#pragma unroll
+    for (int j = 0; j < TNO; ++j) {
+        const int pcol = n0 + wn * WN + j * 32;                     // first packed column of the tile
+        int ocol0;                                                  // first output column within its segment
+        GemmSeg sgm;
+        float vals[TM][16];
+        if (GEGLU) {
+            const float bv = a.bias ? a.bias[pcol + fr] : 0.f, bg = a.bias ? a.bias[pcol + fr + GEGLU_GROUP] : 0.f;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) vals[i][e] = (acc[i][j][e] + bv) * gelu_erf(acc[i][j + TN / 2][e] + bg);
+            sgm = a.seg[0];
+            ocol0 = (n0 + wn * WN) / 2 + j * 32;
+        } else {
+            const int sg = pcol / a.seg_cols;
+            sgm = sg == 0 ? a.seg[0] : (sg == 1 ? a.seg[1] : a.seg[2]);
+            ocol0 = pcol - sg * a.seg_cols;
+            const float bias = a.bias ? a.bias[pcol + fr] : 0.f;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) vals[i][e] = acc[i][j][e] + bias;
+        }
+        uint16_t* out = (uint16_t*)sgm.ptr;
+        if (sgm.transposed) {
+            // out[col][token]: the four rows e%4 of a lane are consecutive tokens -> one 8-byte store
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int eg = 0; eg < 4; ++eg) {
+                    const int row = i * 32 + 8 * eg + 4 * fh;
+                    const int t0 = w_tok[row], t3 = w_tok[row + 3];
+                    uint16_t* dst = out + (int64_t)(ocol0 + fr) * sgm.ld;
+                    if (t0 >= 0 && t3 == t0 + 3 && (t0 & 3) == 0 && (sgm.ld & 3) == 0) {
+                        const uint32_t lo = pack_bf16x2(vals[i][4 * eg] * sgm.scale, vals[i][4 * eg + 1] * sgm.scale);
+                        const uint32_t hi = pack_bf16x2(vals[i][4 * eg + 2] * sgm.scale, vals[i][4 * eg + 3] * sgm.scale);
+                        *reinterpret_cast<uint2*>(dst + t0) = make_uint2(lo, hi);
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const int t = w_tok[row + q];
+                            if (t >= 0) dst[t] = float_to_bf16_bits(vals[i][4 * eg + q] * sgm.scale);
+                        }
+                    }
+                }
+            continue;
+        }
+        // stage the tile column: ep[row][col]
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) ep[(i * 32 + 8 * (e >> 2) + 4 * fh + (e & 3)) * EP_LD + fr] = vals[i][e];
+        __builtin_amdgcn_wave_barrier();
+        // prefetch the residual of the next tile column while this one is finished
+        if (HAS_RES && j + 1 < TNO) {
+#pragma unroll
+            for (int t = 0; t < NIT; ++t) rres[(j + 1) & 1][t] = *reinterpret_cast<const u32x4*>(res_row[t] + pcol + 32);
+        }
+#pragma unroll
+        for (int t = 0; t < NIT; ++t) {
+            const int item = t * 64 + lane;
+            const int row = item >> 2, ch = item & 3;
+            const int tok = w_tok[row];
+            const f32x4 lo = *reinterpret_cast<const f32x4*>(ep + row * EP_LD + ch * 8);
+            const f32x4 hi = *reinterpret_cast<const f32x4*>(ep + row * EP_LD + ch * 8 + 4);
+            const int64_t tk = tok < 0 ? 0 : tok;                   // rows past the end read row 0 and store nothing
+            float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            if (HAS_RES) {
+                const u32x4 r = rres[j & 1][t];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    v[2 * q] += __uint_as_float(r[q] << 16);
+                    v[2 * q + 1] += __uint_as_float(r[q] & 0xFFFF0000u);
+                }
+            }
+            u32x4 o;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                o[q] = pack_bf16x2(v[2 * q] * sgm.scale, v[2 * q + 1] * sgm.scale);
+            if (tok >= 0) *reinterpret_cast<u32x4*>(out + tk * sgm.ld + ocol0 + ch * 8) = o;
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
 typedef __attribute__((address_space(3))) void lds_void;
 
 // LDS bytes of one kernel instance: NS stages of (BM + BN) rows x 128 bytes, plus the row -> token table
@@ -168,96 +286,202 @@ gemm_mfma_kernel(GemmArgs a) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();                                // ring is reused by the epilogue
 
-    // ---- epilogue.  A lane holds column (lane % 32) of each 32x32 tile and rows 8*(e/4) + 4*(lane/32) + e%4.
-    // One tile column (WM rows x 32 columns) at a time is finished in registers (bias, scale, GEGLU), staged
-    // as fp32 in this wavefront's private LDS region and read back row-wise, so that residual loads and
-    // output stores are 16 bytes per lane and 64 contiguous bytes per row.
-    constexpr int EP_LD = 36;                                       // floats per staged row (16-byte aligned, skewed banks)
-    static_assert((size_t)4 * WM * EP_LD * sizeof(float) <= (size_t)NS * STAGE_V * 16, "epilogue staging fits");
-    float* ep = reinterpret_cast<float*>(smem) + wave * (WM * EP_LD);
-    const int32_t* w_tok = s_tok + wm * WM;
-    constexpr int TNO = GEGLU ? TN / 2 : TN;                        // output tile columns per wavefront
-    static_assert(!GEGLU || (WN == 2 * GEGLU_GROUP), "GEGLU needs a wavefront tile of [GROUP values | GROUP gates]");
-#pragma unroll
-    for (int j = 0; j < TNO; ++j) {
-        const int pcol = n0 + wn * WN + j * 32;                     // first packed column of the tile
-        int ocol0;                                                  // first output column within its segment
-        GemmSeg sgm;
-        float vals[TM][16];
-        if (GEGLU) {
-            const float bv = a.bias ? a.bias[pcol + fr] : 0.f, bg = a.bias ? a.bias[pcol + fr + GEGLU_GROUP] : 0.f;
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) vals[i][e] = (acc[i][j][e] + bv) * gelu_erf(acc[i][j + TN / 2][e] + bg);
-            sgm = a.seg[0];
-            ocol0 = (n0 + wn * WN) / 2 + j * 32;
+    gemm_epilogue<BM, BN, GEGLU>(a, acc, smem, s_tok, n0);
+}
+
+// ---- 3x3 convolution with the A operand kept in LDS across the nine taps -------------------------------------
+// The M tile is a set of segments, each `seg_rows` whole pixel rows of one patch.  For every 64-channel chunk
+// the haloed pixels of the segments ((seg_rows+2) x (pw+2) per segment, taken from the padded patch buffer) are
+// loaded into LDS ONCE and the nine taps read them as nine shifted views, so the activation traffic from L2 /
+// MALL is ~5x lower than re-loading a 128-row tile per tap.  Only the weights stream per (tap, chunk) step.
+// LDS: [2 weight stages][2 halo stages of CONV_APIX pixel slots][row -> token table].
+constexpr int CONV_APIX = 256;                      // halo pixel slots per stage
+struct ConvTile {
+    int32_t seg_rows, seg_tokens, nseg, seg_pix;    // seg_tokens = seg_rows*pw, seg_pix = (seg_rows+2)*(pw+2)
+};
+
+template <int BM, int BN>
+__global__ void __launch_bounds__(256)
+conv_mfma_kernel(GemmArgs a, ConvTile ct) {
+    constexpr int BK = 64, CH = 8;
+    constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
+    constexpr int B_LD = BN * CH / 256, A_LD = CONV_APIX * CH / 256;
+    constexpr int BSTAGE = BN * CH, ASTAGE = CONV_APIX * CH;       // 16-byte slots
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    u32x4* sB = reinterpret_cast<u32x4*>(smem);                    // [2][BSTAGE]
+    u32x4* sA = sB + 2 * BSTAGE;                                   // [2][ASTAGE]
+    int32_t* s_tok = reinterpret_cast<int32_t*>(sA + 2 * ASTAGE);  // [BM]
+    int32_t* s_seg = s_tok + BM;                                   // [nseg] padded-pixel index of each segment's halo origin
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+    if (a.act.active && m0 >= *a.act.count * a.geom.S) return;
+    const int S = a.geom.S, pw = a.geom.pw, hw = pw + 2;
+
+    // row -> token table and segment origins
+    if (tid < BM) {
+        const int ri = m0 + tid;
+        int64_t tok;
+        bool valid;
+        if (a.act.active) {
+            const int pi = ri / S;
+            valid = pi < *a.act.count;
+            tok = valid ? (int64_t)a.act.active[pi] * S + (ri - pi * S) : 0;
         } else {
-            const int sg = pcol / a.seg_cols;
-            sgm = sg == 0 ? a.seg[0] : (sg == 1 ? a.seg[1] : a.seg[2]);
-            ocol0 = pcol - sg * a.seg_cols;
-            const float bias = a.bias ? a.bias[pcol + fr] : 0.f;
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) vals[i][e] = acc[i][j][e] + bias;
+            valid = ri < a.M;
+            tok = valid ? ri : 0;
         }
-        uint16_t* out = (uint16_t*)sgm.ptr;
-        if (sgm.transposed) {
-            // out[col][token]: the four rows e%4 of a lane are consecutive tokens -> one 8-byte store
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int eg = 0; eg < 4; ++eg) {
-                    const int row = i * 32 + 8 * eg + 4 * fh;
-                    const int t0 = w_tok[row], t3 = w_tok[row + 3];
-                    uint16_t* dst = out + (int64_t)(ocol0 + fr) * sgm.ld;
-                    if (t0 >= 0 && t3 == t0 + 3 && (t0 & 3) == 0 && (sgm.ld & 3) == 0) {
-                        const uint32_t lo = pack_bf16x2(vals[i][4 * eg] * sgm.scale, vals[i][4 * eg + 1] * sgm.scale);
-                        const uint32_t hi = pack_bf16x2(vals[i][4 * eg + 2] * sgm.scale, vals[i][4 * eg + 3] * sgm.scale);
-                        *reinterpret_cast<uint2*>(dst + t0) = make_uint2(lo, hi);
-                    } else {
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const int t = w_tok[row + q];
-                            if (t >= 0) dst[t] = float_to_bf16_bits(vals[i][4 * eg + q] * sgm.scale);
-                        }
-                    }
-                }
-            continue;
+        s_tok[tid] = valid ? (int32_t)tok : -1;
+        if (tid % ct.seg_tokens == 0) {
+            const int p = (int)(tok / S), q = (int)(tok - (int64_t)p * S);
+            s_seg[tid / ct.seg_tokens] = p * a.geom.pS + (q / pw) * a.geom.ppw;    // padded pixel of halo (0, 0)
         }
-        // stage the tile column: ep[row][col]
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) ep[(i * 32 + 8 * (e >> 2) + 4 * fh + (e & 3)) * EP_LD + fr] = vals[i][e];
-        __builtin_amdgcn_wave_barrier();
-        const uint16_t* res = (const uint16_t*)a.res;
-#pragma unroll
-        for (int t = 0; t < WM * 4 / 64; ++t) {
-            const int item = t * 64 + lane;
-            const int row = item >> 2, ch = item & 3;
-            const int tok = w_tok[row];
-            const f32x4 lo = *reinterpret_cast<const f32x4*>(ep + row * EP_LD + ch * 8);
-            const f32x4 hi = *reinterpret_cast<const f32x4*>(ep + row * EP_LD + ch * 8 + 4);
-            const int64_t tk = tok < 0 ? 0 : tok;                   // rows past the end read row 0 and store nothing
-            float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-            if (!GEGLU && res) {
-                const u32x4 r = *reinterpret_cast<const u32x4*>(res + tk * a.ldr + pcol + ch * 8);
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    v[2 * q] += __uint_as_float(r[q] << 16);
-                    v[2 * q + 1] += __uint_as_float(r[q] & 0xFFFF0000u);
-                }
-            }
-            u32x4 o;
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                o[q] = pack_bf16x2(v[2 * q] * sgm.scale, v[2 * q + 1] * sgm.scale);
-            if (tok >= 0) *reinterpret_cast<u32x4*>(out + tk * sgm.ld + ocol0 + ch * 8) = o;
-        }
-        __builtin_amdgcn_wave_barrier();
     }
+    __syncthreads();
+
+    // halo staging: slot sl = lr + 32*i (pixel slot), chunk position lc; lane fetches global chunk lc ^ f(slot)
+    const int lc = lane & 7, lr = 8 * wave + (lane >> 3);
+    const int gc = lc ^ ((lr >> 1) & 7);
+    const uint16_t* A = (const uint16_t*)a.A;
+    const uint16_t* B = (const uint16_t*)a.B;
+    const uint16_t* a_ptr[A_LD];
+    const int apix = ct.nseg * ct.seg_pix;
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i) {
+        int sl = lr + 32 * i;
+        if (sl >= apix) sl = 0;                                    // unused slots re-read a valid pixel
+        const int g = sl / ct.seg_pix, l = sl - g * ct.seg_pix;
+        const int ly = l / hw, lx = l - ly * hw;
+        a_ptr[i] = A + ((int64_t)s_seg[g] + ly * a.geom.ppw + lx) * a.lda + gc * 8;
+    }
+    const uint16_t* b_ptr = B + (int64_t)(n0 + lr) * a.K + gc * 8;
+    const int64_t b_row32 = (int64_t)32 * a.K;
+    const int64_t b_tap_stride = (int64_t)a.N * a.K;
+    const int kchunks = a.K / BK;
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+#define PS_ISSUE_B(st_, tap_, kc_)                                                                            \
+    {                                                                                                         \
+        u32x4* dst_ = sB + (st_) * BSTAGE + wave * 64;                                                        \
+        const int64_t off_ = (tap_) * b_tap_stride + (kc_) * BK;                                              \
+        _Pragma("unroll") for (int i = 0; i < B_LD; ++i)                                                      \
+            __builtin_amdgcn_global_load_lds((const void*)(b_ptr + i * b_row32 + off_), (lds_void*)(dst_ + i * 256), 16, 0, 0); \
+    }
+#define PS_ISSUE_A(st_, kc_)                                                                                  \
+    {                                                                                                         \
+        u32x4* dst_ = sA + (st_) * ASTAGE + wave * 64;                                                        \
+        _Pragma("unroll") for (int i = 0; i < A_LD; ++i)                                                      \
+            __builtin_amdgcn_global_load_lds((const void*)(a_ptr[i] + (kc_) * BK), (lds_void*)(dst_ + i * 256), 16, 0, 0); \
+    }
+
+    const int fr = lane & 31, fh = lane >> 5;
+    // halo slot of each fragment row for tap (0, 0)
+    int fa_slot[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int r = wm * WM + i * 32 + fr;
+        const int g = r / ct.seg_tokens, rr = r - g * ct.seg_tokens;
+        const int ry = rr / pw, rx = rr - ry * pw;
+        fa_slot[i] = g * ct.seg_pix + ry * hw + rx;
+    }
+    int fb_base[TN], fb_sw[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) { const int r = wn * WN + j * 32 + fr; fb_base[j] = r * CH; fb_sw[j] = (r >> 1) & 7; }
+
+    bf16x8 fa[2][TM], fb[2][TN];
+#define PS_READ_FRAGS(dst, stA_, stB_, ks_)                                                      \
+    {                                                                                            \
+        const int c_ = (ks_) * 2 + fh;                                                           \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i)                                           \
+            fa[dst][i] = __builtin_bit_cast(bf16x8, (stA_)[fa_cur[i] * CH + (c_ ^ fa_sw[i])]);   \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j)                                           \
+            fb[dst][j] = __builtin_bit_cast(bf16x8, (stB_)[fb_base[j] + (c_ ^ fb_sw[j])]);       \
+    }
+
+    // prologue: halo of chunk 0 and weights of step (tap 0, chunk 0)
+    PS_ISSUE_A(0, 0);
+    PS_ISSUE_B(0, 0, 0);
+    int bst = 0;                                    // weight stage read by the current step
+    for (int kc = 0; kc < kchunks; ++kc) {
+        const u32x4* curA = sA + (kc & 1) * ASTAGE;
+#pragma unroll 1
+        for (int tap = 0; tap < 9; ++tap) {
+            // loads issued so far and still allowed in flight: only the next chunk's halo (issued after the
+            // weights of this step, during tap 0)
+            if (tap == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(A_LD) : "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();                        // this step's weights (and, at tap 0, this chunk's halo) visible;
+                                                    // the other weight stage (and, at tap 0, the other halo stage) is free
+            {                                       // weights of the next step
+                int ntap = tap + 1, nkc = kc;
+                if (ntap == 9) { ntap = 0; nkc = kc + 1 < kchunks ? kc + 1 : kc; }
+                PS_ISSUE_B(bst ^ 1, ntap, nkc);
+            }
+            if (tap == 0) {                         // halo of the next chunk (the last chunk re-fetches itself; never read)
+                const int nkc = kc + 1 < kchunks ? kc + 1 : kc;
+                PS_ISSUE_A((kc & 1) ^ 1, nkc);
+            }
+            const int ty = tap / 3, tx = tap - ty * 3;
+            int fa_cur[TM], fa_sw[TM];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) { fa_cur[i] = fa_slot[i] + ty * hw + tx; fa_sw[i] = (fa_cur[i] >> 1) & 7; }
+            const u32x4* curB = sB + bst * BSTAGE;
+            PS_READ_FRAGS(0, curA, curB, 0);
+#pragma unroll
+            for (int ks = 0; ks < BK / 16; ++ks) {
+                if (ks + 1 < BK / 16) PS_READ_FRAGS((ks + 1) & 1, curA, curB, ks + 1);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            bst ^= 1;
+        }
+    }
+#undef PS_READ_FRAGS
+#undef PS_ISSUE_A
+#undef PS_ISSUE_B
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    gemm_epilogue<BM, BN, false>(a, acc, smem, s_tok, n0);
+}
+
+template <int BM, int BN>
+static int launch_conv(const GemmArgs& a, const ConvTile& ct, hipStream_t st) {
+    constexpr size_t lds = (size_t)2 * (BN + CONV_APIX) * 128 + BM * sizeof(int32_t) + 64 * sizeof(int32_t);
+    static_assert(lds <= 160 * 1024, "conv LDS budget");
+    static bool attr_set = false;
+    if (!attr_set) {
+        PS_CHECK_HIP(hipFuncSetAttribute((const void*)conv_mfma_kernel<BM, BN>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_set = true;
+    }
+    dim3 grid((unsigned)cdiv(a.M, BM), (unsigned)(a.N / BN));
+    conv_mfma_kernel<BM, BN><<<grid, 256, lds, st>>>(a, ct);
+    return check_launch("conv_mfma_kernel");
+}
+
+// Tile geometry of the halo-in-LDS convolution; false if the patch shape does not fit it.
+static bool conv_tile(const GemmArgs& a, int BM, ConvTile* ct) {
+    const int pw = a.geom.pw, ph = a.geom.ph;
+    if (!a.conv || !a.tokens_are_rows || a.taps != 9 || BM % pw != 0) return false;
+    int R = BM / pw;
+    if (R > ph) R = ph;
+    if (ph % R != 0 || BM % (R * pw) != 0) return false;
+    ct->seg_rows = R;
+    ct->seg_tokens = R * pw;
+    ct->nseg = BM / ct->seg_tokens;
+    ct->seg_pix = (R + 2) * (pw + 2);
+    return ct->nseg * ct->seg_pix <= CONV_APIX && ct->nseg <= 64;
 }
 
 template <int BM, int BN, bool GEGLU>
@@ -283,6 +507,13 @@ int gemm_mfma_bf16(const GemmArgs& a, hipStream_t st, bool* handled) {
         return launch<128, 256, true>(a, st);
     }
     if (a.seg_cols % 32 != 0) return PSERVE_OK;      // a 32-column tile must not straddle output segments
+    ConvTile ct;
+    if (conv_tile(a, 128, &ct) && a.seg_cols == a.N && !a.seg[0].transposed) {
+        if (a.N % 320 == 0) { *handled = true; return launch_conv<128, 320>(a, ct, st); }
+        if (a.N % 256 == 0) { *handled = true; return launch_conv<128, 256>(a, ct, st); }
+        if (a.N % 128 == 0) { *handled = true; return launch_conv<128, 128>(a, ct, st); }
+        if (a.N % 64 == 0) { *handled = true; return launch_conv<128, 64>(a, ct, st); }
+    }
     if (a.N % 320 == 0) { *handled = true; return launch<128, 320, false>(a, st); }
     if (a.N % 256 == 0) { *handled = true; return launch<128, 256, false>(a, st); }
     if (a.N % 128 == 0) { *handled = true; return launch<128, 128, false>(a, st); }

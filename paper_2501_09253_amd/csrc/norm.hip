@@ -70,7 +70,17 @@ __global__ void gn_partial_kernel(const T* __restrict__ x, int32_t C, int32_t G,
 #pragma unroll
     for (int e = 0; e < VN; ++e) { s1[e] = 0.f; s2[e] = 0.f; }
     const T* base = x + ((int64_t)p * S) * C + cv * VN;
-    for (int t = t0 + tl; t < t1; t += TL) {
+    int t = t0 + tl;
+    for (; t + 3 * TL < t1; t += 4 * TL) {          // four independent 16-byte loads in flight
+        float v[4][VN];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) load_vec<T>(base + (int64_t)(t + u * TL) * C, v[u]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int e = 0; e < VN; ++e) { s1[e] += v[u][e]; s2[e] = fmaf(v[u][e], v[u][e], s2[e]); }
+    }
+    for (; t < t1; t += TL) {
         float v[VN];
         load_vec<T>(base + (int64_t)t * C, v);
 #pragma unroll
@@ -151,7 +161,29 @@ __global__ void gn_apply_kernel(const T* __restrict__ x, const float* __restrict
 #pragma unroll
     for (int e = 0; e < VN; ++e) { sc[e] = ss[2 * e]; sh[e] = ss[2 * e + 1]; }
     const T* base = x + ((int64_t)p * gm.S) * C + cv * VN;
-    for (int t = t0 + tl; t < t1; t += TL) {
+    auto out_off = [&](int t) -> int64_t {
+        if (PADDED) {
+            const int y = t / gm.pw, xx = t - y * gm.pw;
+            return ((int64_t)p * gm.pS + (y + 1) * gm.ppw + xx + 1) * C;
+        }
+        return ((int64_t)p * gm.S + t) * C;
+    };
+    int t = t0 + tl;
+    for (; t + 3 * TL < t1; t += 4 * TL) {          // four independent 16-byte loads in flight
+        float v[4][VN];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) load_vec<T>(base + (int64_t)(t + u * TL) * C, v[u]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+#pragma unroll
+            for (int e = 0; e < VN; ++e) {
+                v[u][e] = fmaf(v[u][e], sc[e], sh[e]);
+                if (SILU) v[u][e] = silu_f(v[u][e]);
+            }
+            store_vec<T>(out + out_off(t + u * TL) + cv * VN, v[u]);
+        }
+    }
+    for (; t < t1; t += TL) {
         float v[VN];
         load_vec<T>(base + (int64_t)t * C, v);
 #pragma unroll
@@ -159,14 +191,7 @@ __global__ void gn_apply_kernel(const T* __restrict__ x, const float* __restrict
             v[e] = fmaf(v[e], sc[e], sh[e]);
             if (SILU) v[e] = silu_f(v[e]);
         }
-        int64_t o;
-        if (PADDED) {
-            const int y = t / gm.pw, xx = t - y * gm.pw;
-            o = ((int64_t)p * gm.pS + (y + 1) * gm.ppw + xx + 1) * C;
-        } else {
-            o = ((int64_t)p * gm.S + t) * C;
-        }
-        store_vec<T>(out + o + cv * VN, v);
+        store_vec<T>(out + out_off(t) + cv * VN, v);
     }
 }
 
