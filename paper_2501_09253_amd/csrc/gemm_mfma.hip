@@ -24,12 +24,12 @@ __device__ __forceinline__ float gelu_erf(float v) { return 0.5f * v * (1.f + er
 // scale, GEGLU), staged as fp32 in this wavefront's private LDS region and read back row-wise, so that residual
 // loads and output stores are 16 bytes per lane and 64 contiguous bytes per row.  Residual loads of the next tile
 // column are issued before the current one is staged.  `smem` must be free (all staged operands consumed).
-template <int BM, int BN, bool GEGLU>
-__device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[BM / 64][BN / 64], uint8_t* smem,
+template <int BM, int BN, bool GEGLU, int WGM = 2, int WGN = 2>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32], uint8_t* smem,
                                               const int32_t* s_tok, int n0) {
-    constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
+    constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;     // WGM x WGN wavefront grid
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WGN, wn = wave % WGN;
     const int fr = lane & 31, fh = lane >> 5;
     constexpr int EP_LD = 36;                                       // floats per staged row (16-byte aligned, skewed banks)
     float* ep = reinterpret_cast<float*>(smem) + wave * (WM * EP_LD);
@@ -295,26 +295,29 @@ gemm_mfma_kernel(GemmArgs a) {
 // loaded into LDS ONCE and the nine taps read them as nine shifted views, so the activation traffic from L2 /
 // MALL is ~5x lower than re-loading a 128-row tile per tap.  Only the weights stream per (tap, chunk) step.
 // LDS: [2 weight stages][2 halo stages of CONV_APIX pixel slots][row -> token table].
-constexpr int CONV_APIX = 256;                      // halo pixel slots per stage
 struct ConvTile {
     int32_t seg_rows, seg_tokens, nseg, seg_pix;    // seg_tokens = seg_rows*pw, seg_pix = (seg_rows+2)*(pw+2)
 };
 
-template <int BM, int BN>
+// Template: block tile BM x BN, WGM x WGN wavefront grid (4 wavefronts), APIX halo pixel slots per stage
+// (multiple of 32), NSB weight stages.
+template <int BM, int BN, int WGM, int WGN, int APIX, int NSB>
 __global__ void __launch_bounds__(256)
 conv_mfma_kernel(GemmArgs a, ConvTile ct) {
     constexpr int BK = 64, CH = 8;
-    constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
-    constexpr int B_LD = BN * CH / 256, A_LD = CONV_APIX * CH / 256;
-    constexpr int BSTAGE = BN * CH, ASTAGE = CONV_APIX * CH;       // 16-byte slots
+    constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
+    constexpr int B_LD = BN * CH / 256, A_LD = APIX * CH / 256;
+    constexpr int BSTAGE = BN * CH, ASTAGE = APIX * CH;            // 16-byte slots
+    static_assert(WGM * WGN == 4 && (BN * CH) % 256 == 0 && (APIX * CH) % 256 == 0 && (NSB == 2 || NSB == 3), "conv tile");
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    u32x4* sB = reinterpret_cast<u32x4*>(smem);                    // [2][BSTAGE]
-    u32x4* sA = sB + 2 * BSTAGE;                                   // [2][ASTAGE]
+    u32x4* sB = reinterpret_cast<u32x4*>(smem);                    // [NSB][BSTAGE]
+    u32x4* sA = sB + NSB * BSTAGE;                                 // [2][ASTAGE]
     int32_t* s_tok = reinterpret_cast<int32_t*>(sA + 2 * ASTAGE);  // [BM]
     int32_t* s_seg = s_tok + BM;                                   // [nseg] padded-pixel index of each segment's halo origin
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // scalar: LDS destinations of the loads are SGPR math
+    const int wm = wave / WGN, wn = wave % WGN;
     const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
     if (a.act.active && m0 >= *a.act.count * a.geom.S) return;
     const int S = a.geom.S, pw = a.geom.pw, hw = pw + 2;
@@ -368,19 +371,11 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-#define PS_ISSUE_B(st_, tap_, kc_)                                                                            \
-    {                                                                                                         \
-        u32x4* dst_ = sB + (st_) * BSTAGE + wave * 64;                                                        \
-        const int64_t off_ = (tap_) * b_tap_stride + (kc_) * BK;                                              \
-        _Pragma("unroll") for (int i = 0; i < B_LD; ++i)                                                      \
-            __builtin_amdgcn_global_load_lds((const void*)(b_ptr + i * b_row32 + off_), (lds_void*)(dst_ + i * 256), 16, 0, 0); \
-    }
-#define PS_ISSUE_A(st_, kc_)                                                                                  \
-    {                                                                                                         \
-        u32x4* dst_ = sA + (st_) * ASTAGE + wave * 64;                                                        \
-        _Pragma("unroll") for (int i = 0; i < A_LD; ++i)                                                      \
-            __builtin_amdgcn_global_load_lds((const void*)(a_ptr[i] + (kc_) * BK), (lds_void*)(dst_ + i * 256), 16, 0, 0); \
-    }
+    // one direct global->LDS load (64 lanes x 16 bytes) of the weight / halo stage
+#define PS_LOAD_B(dstB_, off_, i_) \
+    __builtin_amdgcn_global_load_lds((const void*)(b_ptr + (i_) * b_row32 + (off_)), (lds_void*)((dstB_) + (i_) * 256), 16, 0, 0)
+#define PS_LOAD_A(dstA_, off_, i_) \
+    __builtin_amdgcn_global_load_lds((const void*)(a_ptr[i_] + (off_)), (lds_void*)((dstA_) + (i_) * 256), 16, 0, 0)
 
     const int fr = lane & 31, fh = lane >> 5;
     // halo slot of each fragment row for tap (0, 0)
@@ -406,72 +401,97 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
             fb[dst][j] = __builtin_bit_cast(bf16x8, (stB_)[fb_base[j] + (c_ ^ fb_sw[j])]);       \
     }
 
-    // prologue: halo of chunk 0 and weights of step (tap 0, chunk 0)
-    PS_ISSUE_A(0, 0);
-    PS_ISSUE_B(0, 0, 0);
-    int bst = 0;                                    // weight stage read by the current step
+    // prologue: halo of chunk 0 and the weights of the first NSB-1 steps
+    {
+        u32x4* dA = sA + wave * 64;
+#pragma unroll
+        for (int i = 0; i < A_LD; ++i) PS_LOAD_A(dA, 0, i);
+    }
+    int itap = 0, ikc = 0;                          // (tap, chunk) of the next weight stage to issue; clamps at the last step
+#pragma unroll
+    for (int t = 0; t < NSB - 1; ++t) {
+        u32x4* dB = sB + t * BSTAGE + wave * 64;
+        const int64_t off = itap * b_tap_stride + ikc * BK;
+#pragma unroll
+        for (int i = 0; i < B_LD; ++i) PS_LOAD_B(dB, off, i);
+        if (!(itap == 8 && ikc == kchunks - 1)) { if (++itap == 9) { itap = 0; ++ikc; } }
+    }
+    constexpr int NM = TM * TN;                     // MFMAs per 16-wide sub-step
+    constexpr int A_PER = (A_LD + 3 * NM - 1) / (3 * NM);   // halo loads slipped in per MFMA of sub-steps 1..3
+    static_assert(B_LD <= NM, "weight loads are interleaved one per MFMA");
+    int bst = 0, wst = NSB - 1;                     // weight stage read by the current step / refilled during it
     for (int kc = 0; kc < kchunks; ++kc) {
         const u32x4* curA = sA + (kc & 1) * ASTAGE;
+        const int nkc_a = kc + 1 < kchunks ? kc + 1 : kc;   // halo chunk fetched during tap 0 (last: itself, never read)
 #pragma unroll 1
         for (int tap = 0; tap < 9; ++tap) {
-            // loads issued so far and still allowed in flight: only the next chunk's halo (issued after the
-            // weights of this step, during tap 0)
-            if (tap == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(A_LD) : "memory");
-            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();                        // this step's weights (and, at tap 0, this chunk's halo) visible;
-                                                    // the other weight stage (and, at tap 0, the other halo stage) is free
-            {                                       // weights of the next step
-                int ntap = tap + 1, nkc = kc;
-                if (ntap == 9) { ntap = 0; nkc = kc + 1 < kchunks ? kc + 1 : kc; }
-                PS_ISSUE_B(bst ^ 1, ntap, nkc);
-            }
-            if (tap == 0) {                         // halo of the next chunk (the last chunk re-fetches itself; never read)
-                const int nkc = kc + 1 < kchunks ? kc + 1 : kc;
-                PS_ISSUE_A((kc & 1) ^ 1, nkc);
-            }
+            // Own loads of this step's weights must have landed.  Still allowed in flight: the NSB-2 later weight
+            // stages and a halo issued during one of the previous NSB-1 steps (taps 1 .. NSB-1 follow a tap 0).
+            if (tap >= 1 && tap <= NSB - 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSB - 2) * B_LD + A_LD) : "memory");
+            else asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSB - 2) * B_LD) : "memory");
+            __syncthreads();                        // everyone's loads of this step visible; the stage read last step is free
+            const int64_t b_off = itap * b_tap_stride + ikc * BK;
+            if (!(itap == 8 && ikc == kchunks - 1)) { if (++itap == 9) { itap = 0; ++ikc; } }
+            u32x4* dB = sB + wst * BSTAGE + wave * 64;
+            u32x4* dA = sA + ((kc & 1) ^ 1) * ASTAGE + wave * 64;
+            const int a_off = nkc_a * BK;
             const int ty = tap / 3, tx = tap - ty * 3;
             int fa_cur[TM], fa_sw[TM];
 #pragma unroll
             for (int i = 0; i < TM; ++i) { fa_cur[i] = fa_slot[i] + ty * hw + tx; fa_sw[i] = (fa_cur[i] >> 1) & 7; }
             const u32x4* curB = sB + bst * BSTAGE;
             PS_READ_FRAGS(0, curA, curB, 0);
+            // MFMAs first; the loads that refill the free stage are slipped in one per MFMA so that their address
+            // arithmetic and issue run in the shadow of the matrix pipe
 #pragma unroll
             for (int ks = 0; ks < BK / 16; ++ks) {
                 if (ks + 1 < BK / 16) PS_READ_FRAGS((ks + 1) & 1, curA, curB, ks + 1);
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
-                    for (int j = 0; j < TN; ++j)
+                    for (int j = 0; j < TN; ++j) {
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
+                        const int q = i * TN + j;
+                        if (ks == 0) {
+                            if (q < B_LD) PS_LOAD_B(dB, b_off, q);
+                        } else {
+#pragma unroll
+                            for (int u = 0; u < A_PER; ++u) {
+                                const int qa = ((ks - 1) * NM + q) * A_PER + u;
+                                if (qa < A_LD && tap == 0) PS_LOAD_A(dA, a_off, qa);
+                            }
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
             }
-            bst ^= 1;
+            bst = bst + 1 == NSB ? 0 : bst + 1;
+            wst = wst + 1 == NSB ? 0 : wst + 1;
         }
     }
 #undef PS_READ_FRAGS
-#undef PS_ISSUE_A
-#undef PS_ISSUE_B
+#undef PS_LOAD_A
+#undef PS_LOAD_B
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    gemm_epilogue<BM, BN, false>(a, acc, smem, s_tok, n0);
+    gemm_epilogue<BM, BN, false, WGM, WGN>(a, acc, smem, s_tok, n0);
 }
 
-template <int BM, int BN>
+template <int BM, int BN, int WGM, int WGN, int APIX, int NSB>
 static int launch_conv(const GemmArgs& a, const ConvTile& ct, hipStream_t st) {
-    constexpr size_t lds = (size_t)2 * (BN + CONV_APIX) * 128 + BM * sizeof(int32_t) + 64 * sizeof(int32_t);
+    constexpr size_t lds = (size_t)(NSB * BN + 2 * APIX) * 128 + BM * sizeof(int32_t) + 64 * sizeof(int32_t);
     static_assert(lds <= 160 * 1024, "conv LDS budget");
     static bool attr_set = false;
     if (!attr_set) {
-        PS_CHECK_HIP(hipFuncSetAttribute((const void*)conv_mfma_kernel<BM, BN>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        PS_CHECK_HIP(hipFuncSetAttribute((const void*)conv_mfma_kernel<BM, BN, WGM, WGN, APIX, NSB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set = true;
     }
     dim3 grid((unsigned)cdiv(a.M, BM), (unsigned)(a.N / BN));
-    conv_mfma_kernel<BM, BN><<<grid, 256, lds, st>>>(a, ct);
+    conv_mfma_kernel<BM, BN, WGM, WGN, APIX, NSB><<<grid, 256, lds, st>>>(a, ct);
     return check_launch("conv_mfma_kernel");
 }
 
 // Tile geometry of the halo-in-LDS convolution; false if the patch shape does not fit it.
-static bool conv_tile(const GemmArgs& a, int BM, ConvTile* ct) {
+static bool conv_tile(const GemmArgs& a, int BM, int apix_max, ConvTile* ct) {
     const int pw = a.geom.pw, ph = a.geom.ph;
     if (!a.conv || !a.tokens_are_rows || a.taps != 9 || BM % pw != 0) return false;
     int R = BM / pw;
@@ -481,7 +501,7 @@ static bool conv_tile(const GemmArgs& a, int BM, ConvTile* ct) {
     ct->seg_tokens = R * pw;
     ct->nseg = BM / ct->seg_tokens;
     ct->seg_pix = (R + 2) * (pw + 2);
-    return ct->nseg * ct->seg_pix <= CONV_APIX && ct->nseg <= 64;
+    return ct->nseg * ct->seg_pix <= apix_max && ct->nseg <= 64;
 }
 
 template <int BM, int BN, bool GEGLU>
@@ -508,11 +528,16 @@ int gemm_mfma_bf16(const GemmArgs& a, hipStream_t st, bool* handled) {
     }
     if (a.seg_cols % 32 != 0) return PSERVE_OK;      // a 32-column tile must not straddle output segments
     ConvTile ct;
-    if (conv_tile(a, 128, &ct) && a.seg_cols == a.N && !a.seg[0].transposed) {
-        if (a.N % 320 == 0) { *handled = true; return launch_conv<128, 320>(a, ct, st); }
-        if (a.N % 256 == 0) { *handled = true; return launch_conv<128, 256>(a, ct, st); }
-        if (a.N % 128 == 0) { *handled = true; return launch_conv<128, 128>(a, ct, st); }
-        if (a.N % 64 == 0) { *handled = true; return launch_conv<128, 64>(a, ct, st); }
+    if (a.seg_cols == a.N && !a.seg[0].transposed) {
+        // preferred: 256 x 160 tiles, four wavefronts stacked along M (each 64 x 160), three weight stages:
+        // half the weight bytes per MFMA of the 128 x 320 tile at the same accumulator shape
+        if (a.N % 160 == 0 && conv_tile(a, 256, 384, &ct)) { *handled = true; return launch_conv<256, 160, 4, 1, 384, 3>(a, ct, st); }
+        if (conv_tile(a, 128, 256, &ct)) {
+            if (a.N % 320 == 0) { *handled = true; return launch_conv<128, 320, 2, 2, 256, 2>(a, ct, st); }
+            if (a.N % 256 == 0) { *handled = true; return launch_conv<128, 256, 2, 2, 256, 2>(a, ct, st); }
+            if (a.N % 128 == 0) { *handled = true; return launch_conv<128, 128, 2, 2, 256, 2>(a, ct, st); }
+            if (a.N % 64 == 0) { *handled = true; return launch_conv<128, 64, 2, 2, 256, 2>(a, ct, st); }
+        }
     }
     if (a.N % 320 == 0) { *handled = true; return launch<128, 320, false>(a, st); }
     if (a.N % 256 == 0) { *handled = true; return launch<128, 256, false>(a, st); }
