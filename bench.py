@@ -30,7 +30,7 @@ def kernel_work(cfg, n_active_tokens):
       attn_self    4*N_i*C flops per query token of image i
       attn_cross   4*L*C flops per token
       gn_stats     b*C bytes per token (one read)
-      gn_apply     2*b*C bytes per token (read + write)
+      gn_apply     2*b*C bytes per token (read + write); gn_apply_stitch adds b*C*ring per patch (rim writes)
       halo_gather  2*b*C*ring bytes per patch (read + write of the ring)
       reuse_copy   2*b*C bytes per token
     """
@@ -54,6 +54,7 @@ def kernel_work(cfg, n_active_tokens):
         "attn_cross": (4.0 * cfg.ctx_len * C * Ta, b * 2.0 * C * Ta),
         "gn_stats": (0.0, 1.0 * b * C * T),
         "gn_apply": (0.0, 2.0 * b * C * T),
+        "gn_apply_stitch": (0.0, 2.0 * b * C * T + 1.0 * b * C * ring * cfg.P),
         "halo_gather": (0.0, 2.0 * b * C * ring * Pa),
         "reuse_copy": (0.0, 2.0 * b * C * T),
     }

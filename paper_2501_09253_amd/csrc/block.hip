@@ -464,7 +464,7 @@ int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* c
         GroupNormArgs a;
         a.x = in; a.gamma = gamma; a.beta = beta; a.C = C; a.G = d.G; a.n = plan->n; a.eps = d.eps;
         a.nsplit = cache->nsplit; a.partial = cache->partial; a.scale_shift = cache->scale_shift;
-        a.request_offset = request_offset; a.owner = owner;
+        a.request_offset = request_offset; a.owner = owner; a.neighbour = plan->d_tab[PSERVE_TAB_NEIGHBOUR];
         return a;
     };
     auto base_gemm = [&](const void* A, int64_t lda, int K, int N, const void* B, const float* bias) {
@@ -479,9 +479,14 @@ int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* c
     auto norm_conv = [&](const void* in, const StageWeights& w, int ci, const void* res, void* out) -> int {
         GroupNormArgs ga = gn_args(in, w.gn_g[ci], w.gn_b[ci]);
         { ProfScope ps("gn_stats", st); PS_TRY(gn_stats(ga, gm, dt, st)); }
-        { ProfScope ps("gn_apply", st); PS_TRY(gn_apply(ga, gm, dt, /*silu=*/true, /*padded=*/true, cache->apad, all, st)); }
-        { ProfScope ps("halo_gather", st);
-          PS_TRY(halo_gather(cache->apad, plan->d_tab[PSERVE_TAB_HALO_SRC], gm, C, plan->ring, dt, act, st)); }
+        if (mode == 0) {        // normalise + stitch in one pass (push); the reference path gathers rims afterwards (pull)
+            ProfScope ps("gn_apply_stitch", st);
+            PS_TRY(gn_apply(ga, gm, dt, /*silu=*/true, /*padded=*/true, /*stitch=*/true, cache->apad, all, st));
+        } else {
+            { ProfScope ps("gn_apply", st); PS_TRY(gn_apply(ga, gm, dt, true, true, false, cache->apad, all, st)); }
+            { ProfScope ps("halo_gather", st);
+              PS_TRY(halo_gather(cache->apad, plan->d_tab[PSERVE_TAB_HALO_SRC], gm, C, plan->ring, dt, act, st)); }
+        }
         GemmArgs g = base_gemm(cache->apad, C, C, C, w.w[ci], w.b[ci]);
         g.conv = 1; g.taps = 9; g.res = res; g.ldr = C;
         g.seg[0].ptr = out; g.seg[0].ld = C;
@@ -517,7 +522,7 @@ int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* c
             }
             GroupNormArgs ga = gn_args(rin, w.gn_g[0], w.gn_b[0]);
             { ProfScope ps("gn_stats", st); PS_TRY(gn_stats(ga, gm, dt, st)); }
-            { ProfScope ps("gn_apply", st); PS_TRY(gn_apply(ga, gm, dt, false, false, cache->u, act, st)); }
+            { ProfScope ps("gn_apply", st); PS_TRY(gn_apply(ga, gm, dt, false, false, false, cache->u, act, st)); }
             GemmArgs g = base_gemm(cache->u, C, C, 3 * C, w.w[0], nullptr);
             g.seg_cols = C;
             g.seg[0].ptr = cache->q; g.seg[0].ld = C; g.seg[0].scale = qscale;

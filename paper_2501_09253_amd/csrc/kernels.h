@@ -48,11 +48,13 @@ struct GroupNormArgs {
     float* scale_shift;        // [n][C][2]: y = x*scale + shift for sorted slot s
     const int32_t* request_offset;   // [n+1]
     const int32_t* owner;      // [P]
+    const int32_t* neighbour;  // [P][8] (stitching only)
 };
 int gn_stats(const GroupNormArgs& a, const PatchGeom& g, int dtype, hipStream_t st);
 // y = x*scale+shift (then SiLU if silu).  padded: write into the interior of the padded patch buffer
-// [P][ph+2][pw+2][C]; else plain [T][C].  Only patches of `act` are written.
-int gn_apply(const GroupNormArgs& a, const PatchGeom& g, int dtype, bool silu, bool padded, void* out,
+// [P][ph+2][pw+2][C]; else plain [T][C].  Only patches of `act` are written.  stitch (padded, all patches):
+// border tokens also fill the neighbours' ring slots / zero the own ring at image edges (no halo_gather needed).
+int gn_apply(const GroupNormArgs& a, const PatchGeom& g, int dtype, bool silu, bool padded, bool stitch, void* out,
              ActiveList act, hipStream_t st);
 // Fill the one-pixel ring of every active padded patch from the interiors of its neighbours (zeros outside the image).
 int halo_gather(void* apad, const int32_t* halo_src, const PatchGeom& g, int32_t C, int32_t ring, int dtype,

@@ -140,10 +140,39 @@ __global__ void gn_finalize_kernel(const float* __restrict__ partial, const int3
 
 __device__ __forceinline__ float silu_f(float v) { return __fdividef(v, 1.f + __expf(-v)); }
 
-template <typename T, bool SILU, bool PADDED>
+// Edge stitching fused into the normalisation (the push form of the paper's "Patch Edge Stitcher"): a border
+// token's normalised value is also written into the ring slot of every same-image neighbour patch that needs
+// it; where that neighbour is absent (image edge) the token zero-fills the matching ring slot of its OWN patch.
+// Every ring slot of every patch is written by exactly one thread, so there is no race and no extra pass.
+template <typename T>
+__device__ __forceinline__ void stitch_store(T* __restrict__ out, const int32_t* __restrict__ nb, const PatchGeom& gm,
+                                             int p, int y, int x, int C, int coff, const float (&v)[Vec<T>::N]) {
+    if (y != 0 && y != gm.ph - 1 && x != 0 && x != gm.pw - 1) return;
+    float z[Vec<T>::N];
+#pragma unroll
+    for (int e = 0; e < Vec<T>::N; ++e) z[e] = 0.f;
+    int k = 0;
+#pragma unroll
+    for (int dy = -1; dy <= 1; ++dy)
+#pragma unroll
+        for (int dx = -1; dx <= 1; ++dx) {
+            if (dy == 0 && dx == 0) continue;
+            const bool on = (dy == 0 || (dy < 0 ? y == 0 : y == gm.ph - 1)) && (dx == 0 || (dx < 0 ? x == 0 : x == gm.pw - 1));
+            if (on) {
+                const int q = nb[k];
+                if (q >= 0)
+                    store_vec<T>(out + ((int64_t)q * gm.pS + (y - dy * gm.ph + 1) * gm.ppw + (x - dx * gm.pw + 1)) * C + coff, v);
+                else
+                    store_vec<T>(out + ((int64_t)p * gm.pS + (y + dy + 1) * gm.ppw + (x + dx + 1)) * C + coff, z);
+            }
+            ++k;
+        }
+}
+
+template <typename T, bool SILU, bool PADDED, bool STITCH>
 __global__ void gn_apply_kernel(const T* __restrict__ x, const float* __restrict__ scale_shift,
-                                const int32_t* __restrict__ owner, PatchGeom gm, int32_t C, int32_t nsplit, int32_t TL,
-                                ActiveList act, T* __restrict__ out) {
+                                const int32_t* __restrict__ owner, const int32_t* __restrict__ neighbour, PatchGeom gm,
+                                int32_t C, int32_t nsplit, int32_t TL, ActiveList act, T* __restrict__ out) {
     constexpr int VN = Vec<T>::N;
     int p = blockIdx.x;
     if (act.active) {
@@ -181,6 +210,10 @@ __global__ void gn_apply_kernel(const T* __restrict__ x, const float* __restrict
                 if (SILU) v[u][e] = silu_f(v[u][e]);
             }
             store_vec<T>(out + out_off(t + u * TL) + cv * VN, v[u]);
+            if (PADDED && STITCH) {
+                const int tt = t + u * TL, y = tt / gm.pw;
+                stitch_store<T>(out, neighbour + 8 * p, gm, p, y, tt - y * gm.pw, C, cv * VN, v[u]);
+            }
         }
     }
     for (; t < t1; t += TL) {
@@ -192,6 +225,10 @@ __global__ void gn_apply_kernel(const T* __restrict__ x, const float* __restrict
             if (SILU) v[e] = silu_f(v[e]);
         }
         store_vec<T>(out + out_off(t) + cv * VN, v);
+        if (PADDED && STITCH) {
+            const int y = t / gm.pw;
+            stitch_store<T>(out, neighbour + 8 * p, gm, p, y, t - y * gm.pw, C, cv * VN, v);
+        }
     }
 }
 
@@ -261,25 +298,29 @@ int gn_stats(const GroupNormArgs& a, const PatchGeom& g, int dtype, hipStream_t 
 }
 
 template <typename T>
-static void launch_apply(const GroupNormArgs& a, const PatchGeom& g, bool silu, bool padded, void* out, ActiveList act,
-                         int CV, int TL, hipStream_t st) {
+static void launch_apply(const GroupNormArgs& a, const PatchGeom& g, bool silu, bool padded, bool stitch, void* out,
+                         ActiveList act, int CV, int TL, hipStream_t st) {
     dim3 grid(g.P, a.nsplit);
     const int nt = TL * CV;
-#define PS_APPLY(SI, PA)                                                                                          \
-    gn_apply_kernel<T, SI, PA><<<grid, nt, 0, st>>>((const T*)a.x, a.scale_shift, a.owner, g, a.C, a.nsplit, TL, act, (T*)out)
-    if (silu && padded) PS_APPLY(true, true);
-    else if (silu) PS_APPLY(true, false);
-    else if (padded) PS_APPLY(false, true);
-    else PS_APPLY(false, false);
+#define PS_APPLY(SI, PA, ST)                                                                                      \
+    gn_apply_kernel<T, SI, PA, ST><<<grid, nt, 0, st>>>((const T*)a.x, a.scale_shift, a.owner, a.neighbour, g, a.C, \
+                                                        a.nsplit, TL, act, (T*)out)
+    if (silu && padded && stitch) PS_APPLY(true, true, true);
+    else if (padded && stitch) PS_APPLY(false, true, true);
+    else if (silu && padded) PS_APPLY(true, true, false);
+    else if (silu) PS_APPLY(true, false, false);
+    else if (padded) PS_APPLY(false, true, false);
+    else PS_APPLY(false, false, false);
 #undef PS_APPLY
 }
 
-int gn_apply(const GroupNormArgs& a, const PatchGeom& g, int dtype, bool silu, bool padded, void* out, ActiveList act,
-             hipStream_t st) {
+int gn_apply(const GroupNormArgs& a, const PatchGeom& g, int dtype, bool silu, bool padded, bool stitch, void* out,
+             ActiveList act, hipStream_t st) {
     int CV, TL;
     PS_TRY(norm_layout(a.C, dtype, &CV, &TL));
-    if (dtype == PSERVE_BF16) launch_apply<uint16_t>(a, g, silu, padded, out, act, CV, TL, st);
-    else launch_apply<float>(a, g, silu, padded, out, act, CV, TL, st);
+    PS_REQUIRE(!stitch || (padded && a.neighbour && !act.active), "gn_apply: stitching needs the padded layout and all patches");
+    if (dtype == PSERVE_BF16) launch_apply<uint16_t>(a, g, silu, padded, stitch, out, act, CV, TL, st);
+    else launch_apply<float>(a, g, silu, padded, stitch, out, act, CV, TL, st);
     return check_launch("gn_apply_kernel");
 }
 
