@@ -102,6 +102,13 @@ def main():
 
     y = torch.empty_like(run.x)
     outs = [torch.empty_like(im) for im in run.images]
+    # one plain device copy of known size (256 MiB read + 256 MiB written): the reference that scales the
+    # FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this same command
+    cal_src = torch.ones(128 * 1024 * 1024, dtype=torch.bfloat16, device="cuda")
+    cal_dst = torch.empty_like(cal_src)
+    cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
 
     def step():
         run.plan.split(run.images, out=run.x)

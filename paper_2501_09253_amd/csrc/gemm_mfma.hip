@@ -177,7 +177,13 @@ gemm_mfma_kernel(GemmArgs a) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // scalar: LDS destinations of the loads are SGPR math
     const int wm = wave >> 1, wn = wave & 1;
-    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+    // XCD-aware tile order: block ids are dealt round-robin to the 8 XCDs, so all N tiles of one M tile get ids of
+    // the same residue mod 8 and consecutive slots: they run on one XCD back to back and share the A tile in its L2
+    const int n_tiles = a.N / BN, m_tiles = (a.M + BM - 1) / BM;
+    const int slot = blockIdx.x >> 3;
+    const int m_tile = (slot / n_tiles) * 8 + (blockIdx.x & 7);
+    if (m_tile >= m_tiles) return;
+    const int m0 = m_tile * BM, n0 = (slot % n_tiles) * BN;
     if (a.tokens_are_rows && a.act.active && m0 >= *a.act.count * a.geom.S) return;
 
     // Staging by direct global -> LDS loads.  One wavefront instruction fills 64 consecutive 16-byte slots
@@ -348,7 +354,13 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // scalar: LDS destinations of the loads are SGPR math
     const int wm = wave / WGN, wn = wave % WGN;
-    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+    // XCD-aware tile order: block ids are dealt round-robin to the 8 XCDs, so all N tiles of one M tile get ids of
+    // the same residue mod 8 and consecutive slots: they run on one XCD back to back and share the A tile in its L2
+    const int n_tiles = a.N / BN, m_tiles = (a.M + BM - 1) / BM;
+    const int slot = blockIdx.x >> 3;
+    const int m_tile = (slot / n_tiles) * 8 + (blockIdx.x & 7);
+    if (m_tile >= m_tiles) return;
+    const int m0 = m_tile * BM, n0 = (slot % n_tiles) * BN;
     if (a.act.active && m0 >= *a.act.count * a.geom.S) return;
     const int S = a.geom.S, pw = a.geom.pw, hw = pw + 2;
 
@@ -515,7 +527,7 @@ static int launch_conv(const GemmArgs& a, const ConvTile& ct, hipStream_t st) {
         PS_CHECK_HIP(hipFuncSetAttribute((const void*)conv_mfma_kernel<BM, BN, WGM, WGN, APIX, NSB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set = true;
     }
-    dim3 grid((unsigned)cdiv(a.M, BM), (unsigned)(a.N / BN));
+    const unsigned grid = (unsigned)(8 * cdiv(cdiv(a.M, BM), 8) * (a.N / BN));
     conv_mfma_kernel<BM, BN, WGM, WGN, APIX, NSB><<<grid, 256, lds, st>>>(a, ct);
     return check_launch("conv_mfma_kernel");
 }
@@ -543,7 +555,7 @@ static int launch(const GemmArgs& a, hipStream_t st) {
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set = true;
     }
-    dim3 grid((unsigned)cdiv(a.M, BM), (unsigned)(a.N / BN));
+    const unsigned grid = (unsigned)(8 * cdiv(cdiv(a.M, BM), 8) * (a.N / BN));
     gemm_mfma_kernel<BM, BN, GEGLU><<<grid, 256, lds, st>>>(a);
     return check_launch("gemm_mfma_kernel");
 }
