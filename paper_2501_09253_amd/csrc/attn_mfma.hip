@@ -29,6 +29,7 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 constexpr int ATT_BQ = 256;      // queries per block
 constexpr int ATT_BKV = 64;      // keys per step
 constexpr int ATT_D = 64;        // head dim
+constexpr float ATT_TAU = 8.f;   // the softmax reference moves when a shifted score exceeds this (p <= 2^8)
 
 // value of lane l^32 (v_permlane32_swap: upper half of the first operand <-> lower half of the second)
 __device__ __forceinline__ float other_half(float v) {
@@ -116,7 +117,7 @@ attn_mfma_kernel(AttnArgs a) {
         for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc_o[qt][dt][e] = 0.f;
-    float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+    float m_ref[2] = {0.f, 0.f}, l_run[2] = {0.f, 0.f};   // reference maximum (log2 domain) and partial row sums
 
     // step 0 into LDS
 #pragma unroll
@@ -148,14 +149,15 @@ attn_mfma_kernel(AttnArgs a) {
             rv[i] = vin ? *reinterpret_cast<const u32x4*>(vp + kvn + i * v_row32) : zero4;
         }
 
-        // ---- S^T = K Q^T : acc_s[qt][kt], lane: query fr, keys 32*kt + 8*(e/4) + 4*fh + e%4
+        // ---- S^T = K Q^T - m_ref : the accumulators start at minus the reference maximum of their query column,
+        // so the products come out already shifted.  lane: query fr, keys 32*kt + 8*(e/4) + 4*fh + e%4
         f32x16 acc_s[2][2];
 #pragma unroll
         for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) acc_s[qt][kt][e] = 0.f;
+                for (int e = 0; e < 16; ++e) acc_s[qt][kt][e] = -m_ref[qt];
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             bf16x8 fk[2];
@@ -180,26 +182,47 @@ attn_mfma_kernel(AttnArgs a) {
                 }
         }
 
-        // ---- online softmax per query column; P leaves as the B operand of the PV product
-        bf16x8 fp[2][4];
+        // ---- online softmax with a lazily updated reference maximum.  p = 2^(s - m_ref) is exact softmax
+        // numerator up to the common factor 2^(-m_ref); the reference only moves (and O, l are rescaled) when a
+        // column's shifted maximum exceeds ATT_TAU, i.e. before p could grow past 2^ATT_TAU.  The first step
+        // always anchors the reference at the true maximum.  The decision is wavefront-uniform.
+        float mx[2];
 #pragma unroll
         for (int qt = 0; qt < 2; ++qt) {
-            float mx = -INFINITY;
+            float m = -INFINITY;
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) mx = fmaxf(mx, acc_s[qt][kt][e]);
-            mx = half_swap_max(mx);
-            const float m_new = fmaxf(m_run[qt], mx);
-            const float corr = __builtin_amdgcn_exp2f(m_run[qt] - m_new);
-            m_run[qt] = m_new;
+                for (int e = 0; e < 16; ++e) m = fmaxf(m, acc_s[qt][kt][e]);
+            mx[qt] = half_swap_max(m);
+        }
+        if (st == 0 || __any(mx[0] > ATT_TAU || mx[1] > ATT_TAU)) {
+#pragma unroll
+            for (int qt = 0; qt < 2; ++qt) {
+                const float d = (st == 0 || mx[qt] > ATT_TAU) ? mx[qt] : 0.f;    // shift of this column's reference
+                const float corr = st == 0 ? 1.f : __builtin_amdgcn_exp2f(-d);   // O and l are still zero in step 0
+                m_ref[qt] += d;
+                l_run[qt] *= corr;
+#pragma unroll
+                for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acc_s[qt][kt][e] -= d;
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acc_o[qt][dt][e] *= corr;
+            }
+        }
+        bf16x8 fp[2][4];                           // P leaves as the B operand of the PV product
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) {
             float sum = 0.f;
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
                 float pv[8];
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    pv[i] = __builtin_amdgcn_exp2f(acc_s[qt][ks >> 1][8 * (ks & 1) + i] - m_new);
+                    pv[i] = __builtin_amdgcn_exp2f(acc_s[qt][ks >> 1][8 * (ks & 1) + i]);
                     sum += pv[i];
                 }
                 u32x4 pk;
@@ -207,11 +230,7 @@ attn_mfma_kernel(AttnArgs a) {
                 for (int i = 0; i < 4; ++i) pk[i] = pack_bf16x2(pv[2 * i], pv[2 * i + 1]);
                 fp[qt][ks] = __builtin_bit_cast(bf16x8, pk);
             }
-            l_run[qt] = l_run[qt] * corr + sum;
-#pragma unroll
-            for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) acc_o[qt][dt][e] *= corr;
+            l_run[qt] += sum;
         }
 
         // ---- O^T += V^T P^T : A operand = V^T rows (d), keys 16*ks + 8*(i/4) + 4*fh + i%4
