@@ -581,9 +581,15 @@ int gemm_mfma_bf16(const GemmArgs& a, hipStream_t st, bool* handled) {
             if (a.N % 64 == 0) { *handled = true; return launch_conv<128, 64, 2, 2, 256, 2>(a, ct, st); }
         }
     }
-    if (a.N % 320 == 0) { *handled = true; return launch<128, 320, false>(a, st); }
-    if (a.N % 256 == 0) { *handled = true; return launch<128, 256, false>(a, st); }
-    if (a.N % 128 == 0) { *handled = true; return launch<128, 128, false>(a, st); }
+    // Few rows (e.g. the text-token projections): wide tiles would leave most of the 256 CUs idle, so take the
+    // narrowest tile when the widest one gives fewer than one block per two CUs.
+    const int64_t m_tiles = cdiv(a.M, 128);
+    const bool small = a.N % 64 == 0 && m_tiles * cdiv(a.N, 320) < 128;
+    if (!small) {
+        if (a.N % 320 == 0) { *handled = true; return launch<128, 320, false>(a, st); }
+        if (a.N % 256 == 0) { *handled = true; return launch<128, 256, false>(a, st); }
+        if (a.N % 128 == 0) { *handled = true; return launch<128, 128, false>(a, st); }
+    }
     if (a.N % 64 == 0) { *handled = true; return launch<128, 64, false>(a, st); }
     return PSERVE_OK;
 }
