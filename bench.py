@@ -20,6 +20,14 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 
+# HBM bytes per launch of the dominant kernel, from the two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) of this
+# same command, each scaled by what the counter reads for bench.py's 256 MiB calibration copy (fetch x2.000,
+# write x1.000); see profiles/bench_config<N>_kernels_and_traffic.md.  (config id, kernel label) -> bytes.
+MEASURED_TRAFFIC = {
+    (2, "conv3x3"): 50.6e6 + 21.6e6,
+    (5, "attn_self"): 1462.6e6 + 100.9e6,
+}
+
 
 def kernel_work(cfg, n_active_tokens):
     """Algorithmic work per LAUNCH of each kernel label: (flops, bytes).
@@ -30,7 +38,7 @@ def kernel_work(cfg, n_active_tokens):
       attn_self    4*N_i*C flops per query token of image i
       attn_cross   4*L*C flops per token
       gn_stats     b*C bytes per token (one read)
-      gn_apply     2*b*C bytes per token (read + write); gn_apply_stitch adds b*C*ring per patch (rim writes)
+      gn_apply     2*b*C bytes per computed token (read + write); gn_apply_stitch (all tokens) adds b*C*ring per patch (rim writes)
       halo_gather  2*b*C*ring bytes per patch (read + write of the ring)
       reuse_copy   2*b*C bytes per token
     """
@@ -53,7 +61,7 @@ def kernel_work(cfg, n_active_tokens):
         "attn_self": (attn, b * 4.0 * C * Ta),
         "attn_cross": (4.0 * cfg.ctx_len * C * Ta, b * 2.0 * C * Ta),
         "gn_stats": (0.0, 1.0 * b * C * T),
-        "gn_apply": (0.0, 2.0 * b * C * T),
+        "gn_apply": (0.0, 2.0 * b * C * Ta),
         "gn_apply_stitch": (0.0, 2.0 * b * C * T + 1.0 * b * C * ring * cfg.P),
         "halo_gather": (0.0, 2.0 * b * C * ring * Pa),
         "reuse_copy": (0.0, 2.0 * b * C * T),
@@ -157,11 +165,12 @@ def main():
         ent = kernels[dom]
         if "tflops" in ent:
             roofline = {"kernel": dom, "bound": "mfma", "achieved": ent["tflops"], "peak": PEAK_BF16_TFLOPS,
-                        "unit": "TFLOP/s", "frac": ent["frac_mfma"], "traffic": None,
+                        "unit": "TFLOP/s", "frac": ent["frac_mfma"], "traffic": MEASURED_TRAFFIC.get((cfg.cfg_id, dom)),
                         "avg_us": ent["avg_us"]}
         else:
             roofline = {"kernel": dom, "bound": "hbm", "achieved": ent.get("gbs"), "peak": PEAK_HBM_GBS,
-                        "unit": "GB/s", "frac": ent.get("frac_hbm"), "traffic": None, "avg_us": ent["avg_us"]}
+                        "unit": "GB/s", "frac": ent.get("frac_hbm"), "traffic": MEASURED_TRAFFIC.get((cfg.cfg_id, dom)),
+                        "avg_us": ent["avg_us"]}
 
     cpu = None
     if not args.no_cpu_baseline:
