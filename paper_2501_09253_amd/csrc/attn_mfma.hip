@@ -40,12 +40,28 @@ __device__ __forceinline__ float other_half(float v) {
 }
 __device__ __forceinline__ float half_swap_max(float v) { return fmaxf(v, other_half(v)); }
 
+typedef __attribute__((address_space(3))) void lds_void;
+constexpr int ATT_NS = 4;        // K / V^T ring depth in 64-key tiles
+
+// MFMA tile row r of a score tile holds key kperm(r) (bits 2 and 3 swapped): with this order the eight scores a lane
+// owns for a 16-key MFMA step are eight CONSECUTIVE keys, so the matching V^T fragment is one 16-byte LDS read.
+__device__ __forceinline__ int kperm(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
+
+// Software pipeline over 32-key half tiles, per wavefront (64 queries = 2 query sub-tiles):
+//   half h issues, in one basic block, the 8 MFMAs of P(h-1) V and the 8 MFMAs of S(h+1) together with the softmax
+//   VALU work of S(h), so that the matrix pipe and the vector ALU of the same wavefront overlap; the two score
+//   accumulator sets and the two probability fragment sets alternate roles.
+// K / V^T tiles of 64 keys are staged by direct global->LDS loads into a ring of four stages: at the top of tile t the
+// barrier makes tile t+1 visible (S(t+1, first half) is issued during tile t), tile t-1 is still needed by the P V
+// product of its second half, and tile t+2 is being loaded.
 __global__ void __launch_bounds__(256, 2)
 attn_mfma_kernel(AttnArgs a) {
-    __shared__ __attribute__((aligned(16))) u32x4 sK[2][ATT_BKV * 8];      // [key][8 chunks of 16 B], chunk ^ ((key>>1)&7)
-    __shared__ __attribute__((aligned(16))) u32x2 sV[2][ATT_D * 16];       // [d][16 chunks of 8 B], chunk ^ g(d)
+    extern __shared__ __attribute__((aligned(16))) uint8_t att_smem[];
+    u32x4* sK = reinterpret_cast<u32x4*>(att_smem);            // [ATT_NS][64 keys][8 chunks], chunk ^ ((key>>1)&7)
+    u32x4* sV = sK + ATT_NS * 512;                             // [ATT_NS][64 d][8 chunks of 8 keys], chunk ^ ((d>>1)&7)
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int fr = lane & 31, fh = lane >> 5;
 
     // ---- which (head, query tile) ----------------------------------------------------------------
@@ -93,22 +109,28 @@ attn_mfma_kernel(AttnArgs a) {
         for (int ks = 0; ks < 4; ++ks) fq[qt][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qp + ks * 16));
     }
 
-    // ---- staging: thread loads 2 chunks of K and 2 chunks of V^T per step
-    const int lrow = tid >> 3, lc = tid & 7;                 // rows lrow and lrow + 32, 16-byte chunk lc
-    const uint16_t* kp = K + (k0 + lrow) * C + head * ATT_D + lc * 8;
-    const uint16_t* vp = V + (int64_t)(head * ATT_D + lrow) * a.ldv + k0 + lc * 8;
-    const int64_t k_row32 = (int64_t)32 * C, v_row32 = (int64_t)32 * a.ldv;
-    int sk_slot[2], sv_slot[2][2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int row = lrow + 32 * i;
-        sk_slot[i] = row * 8 + (lc ^ ((row >> 1) & 7));
-        const int g = ((row & 7) << 1) | ((row >> 3) & 1);
-        sv_slot[i][0] = row * 16 + ((2 * lc) ^ g);
-        sv_slot[i][1] = row * 16 + ((2 * lc + 1) ^ g);
+    // ---- staging by direct loads: a wavefront instruction fills 8 rows x 8 chunk positions; rows lr and lr + 32
+    const int lc = lane & 7, lr = 8 * wave + (lane >> 3);
+    const int gc = lc ^ ((lr >> 1) & 7);                     // global chunk fetched into position lc (same for both rows)
+    const uint16_t* k_base = K + k0 * C + head * ATT_D + gc * 8;
+    const uint16_t* v_base = V + (int64_t)(head * ATT_D + lr) * a.ldv + k0;
+    const int64_t v_row32 = (int64_t)32 * a.ldv;
+    const int steps = (nk + ATT_BKV - 1) / ATT_BKV;
+    // keys / chunks past the image are clamped to valid ones: their scores are masked, their P is zero
+#define PS_ISSUE_TILE(t_)                                                                                        \
+    {                                                                                                            \
+        const int tt_ = (t_) < steps ? (t_) : steps - 1;                                                         \
+        const int kv_ = tt_ * ATT_BKV;                                                                           \
+        u32x4* dk_ = sK + ((t_) & (ATT_NS - 1)) * 512 + wave * 64;                                               \
+        u32x4* dv_ = sV + ((t_) & (ATT_NS - 1)) * 512 + wave * 64;                                               \
+        _Pragma("unroll") for (int i = 0; i < 2; ++i) {                                                          \
+            const int key_ = min(kv_ + lr + 32 * i, nk - 1);                                                     \
+            __builtin_amdgcn_global_load_lds((const void*)(k_base + (int64_t)key_ * C), (lds_void*)(dk_ + i * 256), 16, 0, 0); \
+        }                                                                                                        \
+        const int vc_ = kv_ + gc * 8 < nk ? kv_ + gc * 8 : 0;                                                    \
+        _Pragma("unroll") for (int i = 0; i < 2; ++i)                                                            \
+            __builtin_amdgcn_global_load_lds((const void*)(v_base + i * v_row32 + vc_), (lds_void*)(dv_ + i * 256), 16, 0, 0); \
     }
-    u32x4 rk[2], rv[2];
-    const u32x4 zero4 = {0, 0, 0, 0};
 
     f32x16 acc_o[2][2];
 #pragma unroll
@@ -118,149 +140,129 @@ attn_mfma_kernel(AttnArgs a) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc_o[qt][dt][e] = 0.f;
     float m_ref[2] = {0.f, 0.f}, l_run[2] = {0.f, 0.f};   // reference maximum (log2 domain) and partial row sums
+    f32x16 acc_s[2][2];                                    // [set][query sub-tile]: scores of one 32-key half tile
+    bf16x8 fp[2][2][2];                                    // [set][query sub-tile][16-key step]: probabilities (B operand)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc_s[b][qt][e] = 0.f;
+#pragma unroll
+            for (int k2 = 0; k2 < 2; ++k2) fp[b][qt][k2] = __builtin_bit_cast(bf16x8, u32x4{0, 0, 0, 0});
+        }
 
-    // step 0 into LDS
+    // LDS rows of this lane's fragments
+    const int krow[2] = {kperm(fr), kperm(fr) + 32};        // key row of MFMA tile row fr in half 0 / 1
+    int ksw[2], vsw[2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const bool kin = lrow + 32 * i < nk;
-        rk[i] = kin ? *reinterpret_cast<const u32x4*>(kp + i * k_row32) : zero4;
-        const bool vin = lc * 8 < nk;
-        rv[i] = vin ? *reinterpret_cast<const u32x4*>(vp + i * v_row32) : zero4;
-    }
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        sK[0][sk_slot[i]] = rk[i];
-        sV[0][sv_slot[i][0]] = u32x2{rv[i][0], rv[i][1]};
-        sV[0][sv_slot[i][1]] = u32x2{rv[i][2], rv[i][3]};
-    }
+    for (int i = 0; i < 2; ++i) { ksw[i] = (krow[i] >> 1) & 7; vsw[i] = ((fr + 32 * i) >> 1) & 7; }
+
+    // the stage "before tile 0" is read by the (all-zero) first P V product: give it finite contents
+    sV[(ATT_NS - 1) * 512 + tid] = u32x4{0, 0, 0, 0};
+    sV[(ATT_NS - 1) * 512 + 256 + tid] = u32x4{0, 0, 0, 0};
+    PS_ISSUE_TILE(0);
+    PS_ISSUE_TILE(1);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
-    const int steps = (nk + ATT_BKV - 1) / ATT_BKV;
-    for (int st = 0; st < steps; ++st) {
-        const int buf = st & 1;
-        const int kv0 = st * ATT_BKV;
-        // prefetch the next step (the last iteration loads nothing)
-        const int kvn = kv0 + ATT_BKV;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const bool kin = kvn + lrow + 32 * i < nk;
-            rk[i] = kin ? *reinterpret_cast<const u32x4*>(kp + (int64_t)kvn * C + i * k_row32) : zero4;
-            const bool vin = kvn + lc * 8 < nk;
-            rv[i] = vin ? *reinterpret_cast<const u32x4*>(vp + kvn + i * v_row32) : zero4;
-        }
-
-        // ---- S^T = K Q^T - m_ref : the accumulators start at minus the reference maximum of their query column,
-        // so the products come out already shifted.  lane: query fr, keys 32*kt + 8*(e/4) + 4*fh + e%4
-        f32x16 acc_s[2][2];
-#pragma unroll
-        for (int qt = 0; qt < 2; ++qt)
-#pragma unroll
-            for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) acc_s[qt][kt][e] = -m_ref[qt];
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            bf16x8 fk[2];
-#pragma unroll
-            for (int kt = 0; kt < 2; ++kt) {
-                const int row = kt * 32 + fr;
-                fk[kt] = __builtin_bit_cast(bf16x8, sK[buf][row * 8 + ((2 * ks + fh) ^ ((row >> 1) & 7))]);
-            }
-#pragma unroll
-            for (int qt = 0; qt < 2; ++qt)
-#pragma unroll
-                for (int kt = 0; kt < 2; ++kt)
-                    acc_s[qt][kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk[kt], fq[qt][ks], acc_s[qt][kt], 0, 0, 0);
-        }
-        if (kv0 + ATT_BKV > nk) {                  // ragged last step: keys past the image get -inf
-#pragma unroll
-            for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int key = kv0 + 32 * kt + 8 * (e >> 2) + 4 * fh + (e & 3);
-                    if (key >= nk) { acc_s[0][kt][e] = -INFINITY; acc_s[1][kt][e] = -INFINITY; }
-                }
-        }
-
-        // ---- online softmax with a lazily updated reference maximum.  p = 2^(s - m_ref) is exact softmax
-        // numerator up to the common factor 2^(-m_ref); the reference only moves (and O, l are rescaled) when a
-        // column's shifted maximum exceeds ATT_TAU, i.e. before p could grow past 2^ATT_TAU.  The first step
-        // always anchors the reference at the true maximum.  The decision is wavefront-uniform.
-        float mx[2];
-#pragma unroll
-        for (int qt = 0; qt < 2; ++qt) {
-            float m = -INFINITY;
-#pragma unroll
-            for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) m = fmaxf(m, acc_s[qt][kt][e]);
-            mx[qt] = half_swap_max(m);
-        }
-        if (st == 0 || __any(mx[0] > ATT_TAU || mx[1] > ATT_TAU)) {
-#pragma unroll
-            for (int qt = 0; qt < 2; ++qt) {
-                const float d = (st == 0 || mx[qt] > ATT_TAU) ? mx[qt] : 0.f;    // shift of this column's reference
-                const float corr = st == 0 ? 1.f : __builtin_amdgcn_exp2f(-d);   // O and l are still zero in step 0
-                m_ref[qt] += d;
-                l_run[qt] *= corr;
-#pragma unroll
-                for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) acc_s[qt][kt][e] -= d;
-#pragma unroll
-                for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) acc_o[qt][dt][e] *= corr;
-            }
-        }
-        bf16x8 fp[2][4];                           // P leaves as the B operand of the PV product
-#pragma unroll
-        for (int qt = 0; qt < 2; ++qt) {
-            float sum = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                float pv[8];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    pv[i] = __builtin_amdgcn_exp2f(acc_s[qt][ks >> 1][8 * (ks & 1) + i]);
-                    sum += pv[i];
-                }
-                u32x4 pk;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) pk[i] = pack_bf16x2(pv[2 * i], pv[2 * i + 1]);
-                fp[qt][ks] = __builtin_bit_cast(bf16x8, pk);
-            }
-            l_run[qt] += sum;
-        }
-
-        // ---- O^T += V^T P^T : A operand = V^T rows (d), keys 16*ks + 8*(i/4) + 4*fh + i%4
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            bf16x8 fv[2];
-#pragma unroll
-            for (int dt = 0; dt < 2; ++dt) {
-                const int row = dt * 32 + fr;
-                const int g = ((row & 7) << 1) | ((row >> 3) & 1);
-                const u32x2 lo2 = sV[buf][row * 16 + ((4 * ks + fh) ^ g)];
-                const u32x2 hi2 = sV[buf][row * 16 + ((4 * ks + fh + 2) ^ g)];
-                fv[dt] = __builtin_bit_cast(bf16x8, u32x4{lo2[0], lo2[1], hi2[0], hi2[1]});
-            }
-#pragma unroll
-            for (int qt = 0; qt < 2; ++qt)
-#pragma unroll
-                for (int dt = 0; dt < 2; ++dt)
-                    acc_o[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv[dt], fp[qt][ks], acc_o[qt][dt], 0, 0, 0);
-        }
-
-        // ---- stage the prefetched step
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            sK[buf ^ 1][sk_slot[i]] = rk[i];
-            sV[buf ^ 1][sv_slot[i][0]] = u32x2{rv[i][0], rv[i][1]};
-            sV[buf ^ 1][sv_slot[i][1]] = u32x2{rv[i][2], rv[i][3]};
-        }
-        __syncthreads();
+    // S accumulate of half KT of the tile in stage ST into set B;  P V of half KT of stage ST from set B
+#define PS_S_MFMAS(B, ST, KT)                                                                                    \
+    _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {                                                           \
+        const bf16x8 fk_ = __builtin_bit_cast(bf16x8, sK[(ST) * 512 + krow[KT] * 8 + ((2 * ks + fh) ^ ksw[KT])]); \
+        _Pragma("unroll") for (int qt = 0; qt < 2; ++qt)                                                         \
+            acc_s[B][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk_, fq[qt][ks], acc_s[B][qt], 0, 0, 0);      \
     }
+#define PS_PV_MFMAS(B, ST, KT)                                                                                   \
+    _Pragma("unroll") for (int k2 = 0; k2 < 2; ++k2)                                                             \
+        _Pragma("unroll") for (int dt = 0; dt < 2; ++dt) {                                                       \
+            const bf16x8 fv_ = __builtin_bit_cast(bf16x8, sV[(ST) * 512 + (fr + 32 * dt) * 8 + ((4 * (KT) + 2 * k2 + fh) ^ vsw[dt])]); \
+            _Pragma("unroll") for (int qt = 0; qt < 2; ++qt)                                                     \
+                acc_o[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv_, fp[B][qt][k2], acc_o[qt][dt], 0, 0, 0); \
+        }
+    // mask (ragged last tile), column maxima and the rare move of the softmax reference for the scores in set B
+#define PS_PREPARE(B, KT, KV0, FIRST)                                                                            \
+    {                                                                                                            \
+        if ((KV0) + ATT_BKV > nk) {                                                                              \
+            _Pragma("unroll") for (int e = 0; e < 16; ++e) {                                                     \
+                const int key_ = (KV0) + 32 * (KT) + 16 * (e >> 3) + 8 * fh + (e & 7);                           \
+                if (key_ >= nk) { acc_s[B][0][e] = -INFINITY; acc_s[B][1][e] = -INFINITY; }                      \
+            }                                                                                                    \
+        }                                                                                                        \
+        float mx_[2];                                                                                            \
+        _Pragma("unroll") for (int qt = 0; qt < 2; ++qt) {                                                       \
+            float m_ = -INFINITY;                                                                                \
+            _Pragma("unroll") for (int e = 0; e < 16; ++e) m_ = fmaxf(m_, acc_s[B][qt][e]);                      \
+            mx_[qt] = half_swap_max(m_);                                                                         \
+        }                                                                                                        \
+        if ((FIRST) || __any(mx_[0] > ATT_TAU || mx_[1] > ATT_TAU)) {                                            \
+            _Pragma("unroll") for (int qt = 0; qt < 2; ++qt) {                                                   \
+                const float d_ = ((FIRST) || mx_[qt] > ATT_TAU) ? mx_[qt] : 0.f;                                 \
+                const float corr_ = (FIRST) ? 1.f : __builtin_amdgcn_exp2f(-d_);                                 \
+                m_ref[qt] += d_;                                                                                 \
+                l_run[qt] *= corr_;                                                                              \
+                _Pragma("unroll") for (int e = 0; e < 16; ++e) { acc_s[B][qt][e] -= d_; acc_s[1 - (B)][qt][e] -= d_; } \
+                _Pragma("unroll") for (int dt = 0; dt < 2; ++dt)                                                 \
+                    _Pragma("unroll") for (int e = 0; e < 16; ++e) acc_o[qt][dt][e] *= corr_;                    \
+            }                                                                                                    \
+        }                                                                                                        \
+    }
+    // probabilities of set B (exp2 of the shifted scores), row sums, bf16 pack; then the set restarts at -m_ref
+#define PS_SOFTMAX(B)                                                                                            \
+    _Pragma("unroll") for (int qt = 0; qt < 2; ++qt) {                                                           \
+        float sum_ = 0.f;                                                                                        \
+        _Pragma("unroll") for (int k2 = 0; k2 < 2; ++k2) {                                                       \
+            float pv_[8];                                                                                        \
+            _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                      \
+                pv_[i] = __builtin_amdgcn_exp2f(acc_s[B][qt][8 * k2 + i]);                                       \
+                sum_ += pv_[i];                                                                                  \
+            }                                                                                                    \
+            u32x4 pk_;                                                                                           \
+            _Pragma("unroll") for (int i = 0; i < 4; ++i) pk_[i] = pack_bf16x2(pv_[2 * i], pv_[2 * i + 1]);      \
+            fp[B][qt][k2] = __builtin_bit_cast(bf16x8, pk_);                                                     \
+        }                                                                                                        \
+        l_run[qt] += sum_;                                                                                       \
+        _Pragma("unroll") for (int e = 0; e < 16; ++e) acc_s[B][qt][e] = -m_ref[qt];                             \
+    }
+    // ask the scheduler to spread the 16 MFMAs of a half over its vector work
+#define PS_INTERLEAVE()                                                                                          \
+    _Pragma("unroll") for (int i_ = 0; i_ < 16; ++i_) {                                                          \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                       \
+        __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);                                                       \
+    }
+
+    PS_S_MFMAS(0, 0, 0);                                    // scores of the very first half tile
+    for (int t = 0; t < steps; ++t) {
+        if (t > 0) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // own loads of tile t+1 have landed
+            __syncthreads();                                    // tile t+1 visible to all; the stage of tile t-2 is free
+        }
+        PS_ISSUE_TILE(t + 2);
+        const int st = t & (ATT_NS - 1), sn = (t + 1) & (ATT_NS - 1), sp = (t + ATT_NS - 1) & (ATT_NS - 1);
+        const int kv0 = t * ATT_BKV;
+        // half 0: softmax of S(t, 0) [set 0] with P(t-1, 1) V [set 1] and S(t, 1) -> set 1
+        PS_PREPARE(0, 0, kv0, t == 0);
+        PS_PV_MFMAS(1, sp, 1);
+        PS_S_MFMAS(1, st, 1);
+        PS_SOFTMAX(0);
+        PS_INTERLEAVE();
+        __builtin_amdgcn_sched_barrier(0);
+        // half 1: softmax of S(t, 1) [set 1] with P(t, 0) V [set 0] and S(t+1, 0) -> set 0
+        PS_PREPARE(1, 1, kv0, false);
+        PS_PV_MFMAS(0, st, 0);
+        PS_S_MFMAS(0, sn, 0);
+        PS_SOFTMAX(1);
+        PS_INTERLEAVE();
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    PS_PV_MFMAS(1, (steps - 1) & (ATT_NS - 1), 1);          // P of the last half tile
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");        // no load may still target LDS when the block retires
+#undef PS_INTERLEAVE
+#undef PS_SOFTMAX
+#undef PS_PREPARE
+#undef PS_PV_MFMAS
+#undef PS_S_MFMAS
+#undef PS_ISSUE_TILE
 
     // ---- O[q][head*64 + d] = O^T / l ; lane holds d = 32*dt + 8*(e/4) + 4*fh + e%4 of query fr
     uint16_t* O = (uint16_t*)a.O;
@@ -341,7 +343,13 @@ int attention_mfma_bf16(const AttnArgs& a, hipStream_t st, bool* handled) {
     *handled = true;
     const int64_t items = (int64_t)a.max_tiles * a.heads;
     const unsigned grid = (unsigned)(8 * cdiv(items, 8));
-    attn_mfma_kernel<<<grid, 256, 0, st>>>(a);
+    constexpr int lds = ATT_NS * 2 * 512 * 16;
+    static bool attr_set = false;
+    if (!attr_set) {
+        PS_CHECK_HIP(hipFuncSetAttribute((const void*)attn_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+        attr_set = true;
+    }
+    attn_mfma_kernel<<<grid, 256, lds, st>>>(a);
     return check_launch("attn_mfma_kernel");
 }
 

@@ -5,7 +5,7 @@
 //                     by direct global -> LDS loads into a ring of 2-3 stages (one barrier per step);
 //                     linear layers (one tap) and the fallback form of the convolution (nine taps re-load A).
 //   conv_mfma_kernel  3x3 convolution with the haloed activation tile kept in LDS across the nine taps;
-//                     preferred tile 256 x 160 with four wavefronts stacked along M.
+//                     preferred tile 256 x 160 with four wavefronts stacked along M; every LDS read and global load rides behind an MFMA.
 // MFMA shape v_mfma_f32_32x32x16_bf16, fp32 accumulation.  LDS rows are 128 bytes (8 chunks of 16 bytes); chunk c of
 // row r sits at position c ^ ((r >> 1) & 7), which keeps the fragment reads (32 rows at one chunk position)
 // bank-conflict free; the swizzle is applied by choosing which global chunk each lane of a load fetches.
@@ -434,16 +434,19 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
     for (int j = 0; j < TN; ++j) { const int r = wn * WN + j * 32 + fr; fb_base[j] = r * CH; fb_sw[j] = (r >> 1) & 7; }
 
     bf16x8 fa[2][TM], fb[2][TN];
-#define PS_READ_FRAGS(dst, stA_, stB_, ks_)                                                      \
-    {                                                                                            \
-        const int c_ = (ks_) * 2 + fh;                                                           \
-        _Pragma("unroll") for (int i = 0; i < TM; ++i)                                           \
-            fa[dst][i] = __builtin_bit_cast(bf16x8, (stA_)[fa_cur[i] * CH + (c_ ^ fa_sw[i])]);   \
-        _Pragma("unroll") for (int j = 0; j < TN; ++j)                                           \
-            fb[dst][j] = __builtin_bit_cast(bf16x8, (stB_)[fb_base[j] + (c_ ^ fb_sw[j])]);       \
+    // one fragment read (16 bytes per lane) of K sub-step ks_ into register set dst; r_ = 0: A tile 0, 1 .. TN: B tiles,
+    // TN+1 ..: the remaining A tiles (the order in which the MFMAs of a sub-step first need them)
+#define PS_READ_ONE(dst, stA_, stB_, cur_, sw_, ks_, r_)                                                          \
+    {                                                                                                             \
+        const int c_ = (ks_) * 2 + fh;                                                                            \
+        const int jb_ = ((r_) >= 1 && (r_) <= TN) ? (r_) - 1 : 0;                                             \
+        const int ia_ = ((r_) > TN && (r_) < TM + TN) ? (r_) - TN : 0;                                        \
+        if ((r_) == 0) fa[dst][0] = __builtin_bit_cast(bf16x8, (stA_)[cur_[0] * CH + (c_ ^ sw_[0])]);             \
+        else if ((r_) <= TN) fb[dst][jb_] = __builtin_bit_cast(bf16x8, (stB_)[fb_base[jb_] + (c_ ^ fb_sw[jb_])]); \
+        else if ((r_) < TM + TN) fa[dst][ia_] = __builtin_bit_cast(bf16x8, (stA_)[cur_[ia_] * CH + (c_ ^ sw_[ia_])]); \
     }
 
-    // prologue: halo of chunk 0 and the weights of the first NSB-1 steps
+    // prologue: halo of chunk 0 and the weights of the first NSB steps
     {
         u32x4* dA = sA + wave * 64;
 #pragma unroll
@@ -451,7 +454,7 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
     }
     int itap = 0, ikc = 0;                          // (tap, chunk) of the next weight stage to issue; clamps at the last step
 #pragma unroll
-    for (int t = 0; t < NSB - 1; ++t) {
+    for (int t = 0; t < NSB; ++t) {
         u32x4* dB = sB + t * BSTAGE + wave * 64;
         const int64_t off = itap * b_tap_stride + ikc * BK;
 #pragma unroll
@@ -459,58 +462,82 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
         if (!(itap == 8 && ikc == kchunks - 1)) { if (++itap == 9) { itap = 0; ++ikc; } }
     }
     constexpr int NM = TM * TN;                     // MFMAs per 16-wide sub-step
-    constexpr int A_PER = (A_LD + 3 * NM - 1) / (3 * NM);   // halo loads slipped in per MFMA of sub-steps 1..3
+    constexpr int NR = TM + TN;                     // fragment reads per sub-step
+    constexpr int R_PER = (NR + NM - 1) / NM;       // fragment reads slipped in behind one MFMA
+    constexpr int A_PER = (A_LD + 3 * NM - 1) / (3 * NM);   // halo loads slipped in per MFMA of sub-steps 0..2
     static_assert(B_LD <= NM, "weight loads are interleaved one per MFMA");
-    int bst = 0, wst = NSB - 1;                     // weight stage read by the current step / refilled during it
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    int fa_cur[TM], fa_sw[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) { fa_cur[i] = fa_slot[i]; fa_sw[i] = (fa_cur[i] >> 1) & 7; }
+#pragma unroll
+    for (int r = 0; r < NR; ++r) PS_READ_ONE(0, sA, sB, fa_cur, fa_sw, 0, r);
+
+    // Step = (chunk kc, tap): 4 sub-steps of NM MFMAs.  Every memory instruction rides behind an MFMA: during
+    // sub-steps 0..2 the fragment reads of the next sub-step (and, in tap 0, the halo of the next chunk), during
+    // sub-step 3 the first fragments of the NEXT step and the refill of this step's weight stage.  The block barrier
+    // sits before sub-step 3: by then every wavefront has read all of this step's fragments (its stage is free) and
+    // has seen its own loads of the next step's weights land.
+    int bst = 0;                                    // weight stage of the current step
     for (int kc = 0; kc < kchunks; ++kc) {
         const u32x4* curA = sA + (kc & 1) * ASTAGE;
         const int nkc_a = kc + 1 < kchunks ? kc + 1 : kc;   // halo chunk fetched during tap 0 (last: itself, never read)
+        u32x4* dA = sA + ((kc & 1) ^ 1) * ASTAGE + wave * 64;
+        const int a_off = nkc_a * BK;
 #pragma unroll 1
         for (int tap = 0; tap < 9; ++tap) {
-            // Own loads of this step's weights must have landed.  Still allowed in flight: the NSB-2 later weight
-            // stages and a halo issued during one of the previous NSB-1 steps (taps 1 .. NSB-1 follow a tap 0).
-            if (tap >= 1 && tap <= NSB - 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSB - 2) * B_LD + A_LD) : "memory");
-            else asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSB - 2) * B_LD) : "memory");
-            __syncthreads();                        // everyone's loads of this step visible; the stage read last step is free
+            const u32x4* curB = sB + bst * BSTAGE;
+            const int nst = bst + 1 == NSB ? 0 : bst + 1;
+            const u32x4* nxtB = sB + nst * BSTAGE;
+            const int ntap = tap == 8 ? 0 : tap + 1;
+            const u32x4* nxtA = tap == 8 ? sA + ((kc & 1) ^ 1) * ASTAGE : curA;
+            const int nty = ntap / 3, ntx = ntap - nty * 3;
+            int nfa_cur[TM], nfa_sw[TM];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) { nfa_cur[i] = fa_slot[i] + nty * hw + ntx; nfa_sw[i] = (nfa_cur[i] >> 1) & 7; }
             const int64_t b_off = itap * b_tap_stride + ikc * BK;
             if (!(itap == 8 && ikc == kchunks - 1)) { if (++itap == 9) { itap = 0; ++ikc; } }
-            u32x4* dB = sB + wst * BSTAGE + wave * 64;
-            u32x4* dA = sA + ((kc & 1) ^ 1) * ASTAGE + wave * 64;
-            const int a_off = nkc_a * BK;
-            const int ty = tap / 3, tx = tap - ty * 3;
-            int fa_cur[TM], fa_sw[TM];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) { fa_cur[i] = fa_slot[i] + ty * hw + tx; fa_sw[i] = (fa_cur[i] >> 1) & 7; }
-            const u32x4* curB = sB + bst * BSTAGE;
-            PS_READ_FRAGS(0, curA, curB, 0);
-            // MFMAs first; the loads that refill the free stage are slipped in one per MFMA so that their address
-            // arithmetic and issue run in the shadow of the matrix pipe
+            u32x4* dB = sB + bst * BSTAGE + wave * 64;
 #pragma unroll
             for (int ks = 0; ks < BK / 16; ++ks) {
-                if (ks + 1 < BK / 16) PS_READ_FRAGS((ks + 1) & 1, curA, curB, ks + 1);
+                if (ks == BK / 16 - 1) {
+                    // own fragment reads of this step are complete; own loads of the next step's weights have landed.
+                    // Still allowed in flight: the NSB-2 later weight stages and a halo issued in this or a recent tap 0.
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                    if (tap < NSB - 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSB - 2) * B_LD + A_LD) : "memory");
+                    else asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSB - 2) * B_LD) : "memory");
+                    __syncthreads();
+                }
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < TN; ++j) {
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
                         const int q = i * TN + j;
-                        if (ks == 0) {
+#pragma unroll
+                        for (int u = 0; u < R_PER; ++u) {
+                            if (ks < BK / 16 - 1) { PS_READ_ONE((ks + 1) & 1, curA, curB, fa_cur, fa_sw, ks + 1, q * R_PER + u); }
+                            else { PS_READ_ONE(0, nxtA, nxtB, nfa_cur, nfa_sw, 0, q * R_PER + u); }
+                        }
+                        if (ks == BK / 16 - 1) {
                             if (q < B_LD) PS_LOAD_B(dB, b_off, q);
                         } else {
 #pragma unroll
                             for (int u = 0; u < A_PER; ++u) {
-                                const int qa = ((ks - 1) * NM + q) * A_PER + u;
+                                const int qa = (ks * NM + q) * A_PER + u;
                                 if (qa < A_LD && tap == 0) PS_LOAD_A(dA, a_off, qa);
                             }
                         }
                         __builtin_amdgcn_sched_barrier(0);
                     }
             }
-            bst = bst + 1 == NSB ? 0 : bst + 1;
-            wst = wst + 1 == NSB ? 0 : wst + 1;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) { fa_cur[i] = nfa_cur[i]; fa_sw[i] = nfa_sw[i]; }
+            bst = nst;
         }
     }
-#undef PS_READ_FRAGS
+#undef PS_READ_ONE
 #undef PS_LOAD_A
 #undef PS_LOAD_B
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
