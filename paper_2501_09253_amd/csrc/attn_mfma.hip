@@ -41,19 +41,24 @@ __device__ __forceinline__ float other_half(float v) {
 __device__ __forceinline__ float half_swap_max(float v) { return fmaxf(v, other_half(v)); }
 
 typedef __attribute__((address_space(3))) void lds_void;
-constexpr int ATT_NS = 4;        // K / V^T ring depth in 64-key tiles
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+constexpr int ATT_NS = 3;        // K / V^T ring depth in 64-key tiles
+constexpr float ATT_SUM_MAX = 4096.f;   // a lane's 16-key partial row sum above this moves the softmax reference
 
 // MFMA tile row r of a score tile holds key kperm(r) (bits 2 and 3 swapped): with this order the eight scores a lane
 // owns for a 16-key MFMA step are eight CONSECUTIVE keys, so the matching V^T fragment is one 16-byte LDS read.
 __device__ __forceinline__ int kperm(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
 
-// Software pipeline over 32-key half tiles, per wavefront (64 queries = 2 query sub-tiles):
-//   half h issues, in one basic block, the 8 MFMAs of P(h-1) V and the 8 MFMAs of S(h+1) together with the softmax
-//   VALU work of S(h), so that the matrix pipe and the vector ALU of the same wavefront overlap; the two score
-//   accumulator sets and the two probability fragment sets alternate roles.
-// K / V^T tiles of 64 keys are staged by direct global->LDS loads into a ring of four stages: at the top of tile t the
-// barrier makes tile t+1 visible (S(t+1, first half) is issued during tile t), tile t-1 is still needed by the P V
-// product of its second half, and tile t+2 is being loaded.
+// The vector ALU shares its issue slot with the matrix pipe, so the softmax is written for the fewest instructions
+// per score: one exp2, half a bf16 pack and half a packed dot-product for the row sum.
+//   * the scores come out of the MFMAs already shifted: the first MFMA of a 32-key half tile accumulates onto a
+//     register tile holding -m_ref of the lane's query (no reset, no subtraction);
+//   * no running maximum: the reference m_ref (log2 domain) is fixed by the first half tile and moves only when a
+//     lane's partial row sum shows that a shifted score got large (rare; the exact maximum is then taken, the
+//     accumulators are rescaled and the probabilities recomputed);
+//   * the row sum is taken over the bf16-rounded probabilities, i.e. of exactly what multiplies V.
+// K / V^T tiles of 64 keys are staged by direct global->LDS loads into a ring of three stages, two tiles ahead.
 __global__ void __launch_bounds__(256, 2)
 attn_mfma_kernel(AttnArgs a) {
     extern __shared__ __attribute__((aligned(16))) uint8_t att_smem[];
@@ -117,12 +122,12 @@ attn_mfma_kernel(AttnArgs a) {
     const int64_t v_row32 = (int64_t)32 * a.ldv;
     const int steps = (nk + ATT_BKV - 1) / ATT_BKV;
     // keys / chunks past the image are clamped to valid ones: their scores are masked, their P is zero
-#define PS_ISSUE_TILE(t_)                                                                                        \
+#define PS_ISSUE_TILE(t_, st_)                                                                                   \
     {                                                                                                            \
         const int tt_ = (t_) < steps ? (t_) : steps - 1;                                                         \
         const int kv_ = tt_ * ATT_BKV;                                                                           \
-        u32x4* dk_ = sK + ((t_) & (ATT_NS - 1)) * 512 + wave * 64;                                               \
-        u32x4* dv_ = sV + ((t_) & (ATT_NS - 1)) * 512 + wave * 64;                                               \
+        u32x4* dk_ = sK + (st_) * 512 + wave * 64;                                                               \
+        u32x4* dv_ = sV + (st_) * 512 + wave * 64;                                                               \
         _Pragma("unroll") for (int i = 0; i < 2; ++i) {                                                          \
             const int key_ = min(kv_ + lr + 32 * i, nk - 1);                                                     \
             __builtin_amdgcn_global_load_lds((const void*)(k_base + (int64_t)key_ * C), (lds_void*)(dk_ + i * 256), 16, 0, 0); \
@@ -140,17 +145,13 @@ attn_mfma_kernel(AttnArgs a) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc_o[qt][dt][e] = 0.f;
     float m_ref[2] = {0.f, 0.f}, l_run[2] = {0.f, 0.f};   // reference maximum (log2 domain) and partial row sums
-    f32x16 acc_s[2][2];                                    // [set][query sub-tile]: scores of one 32-key half tile
-    bf16x8 fp[2][2][2];                                    // [set][query sub-tile][16-key step]: probabilities (B operand)
+    f32x16 cinit[2];                                       // -m_ref of the lane's query in every element
+    f32x16 acc_s[2];                                       // shifted scores of one 32-key half tile, per query sub-tile
+    bf16x8 fp[2][2];                                       // [query sub-tile][16-key step]: probabilities (B operand)
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt) {
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc_s[b][qt][e] = 0.f;
-#pragma unroll
-            for (int k2 = 0; k2 < 2; ++k2) fp[b][qt][k2] = __builtin_bit_cast(bf16x8, u32x4{0, 0, 0, 0});
-        }
+        for (int e = 0; e < 16; ++e) cinit[qt][e] = 0.f;
 
     // LDS rows of this lane's fragments
     const int krow[2] = {kperm(fr), kperm(fr) + 32};        // key row of MFMA tile row fr in half 0 / 1
@@ -158,110 +159,84 @@ attn_mfma_kernel(AttnArgs a) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) { ksw[i] = (krow[i] >> 1) & 7; vsw[i] = ((fr + 32 * i) >> 1) & 7; }
 
-    // the stage "before tile 0" is read by the (all-zero) first P V product: give it finite contents
-    sV[(ATT_NS - 1) * 512 + tid] = u32x4{0, 0, 0, 0};
-    sV[(ATT_NS - 1) * 512 + 256 + tid] = u32x4{0, 0, 0, 0};
-    PS_ISSUE_TILE(0);
-    PS_ISSUE_TILE(1);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
+    PS_ISSUE_TILE(0, 0);
+    PS_ISSUE_TILE(1, 1);
 
-    // S accumulate of half KT of the tile in stage ST into set B;  P V of half KT of stage ST from set B
-#define PS_S_MFMAS(B, ST, KT)                                                                                    \
-    _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {                                                           \
-        const bf16x8 fk_ = __builtin_bit_cast(bf16x8, sK[(ST) * 512 + krow[KT] * 8 + ((2 * ks + fh) ^ ksw[KT])]); \
-        _Pragma("unroll") for (int qt = 0; qt < 2; ++qt)                                                         \
-            acc_s[B][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk_, fq[qt][ks], acc_s[B][qt], 0, 0, 0);      \
-    }
-#define PS_PV_MFMAS(B, ST, KT)                                                                                   \
-    _Pragma("unroll") for (int k2 = 0; k2 < 2; ++k2)                                                             \
-        _Pragma("unroll") for (int dt = 0; dt < 2; ++dt) {                                                       \
-            const bf16x8 fv_ = __builtin_bit_cast(bf16x8, sV[(ST) * 512 + (fr + 32 * dt) * 8 + ((4 * (KT) + 2 * k2 + fh) ^ vsw[dt])]); \
-            _Pragma("unroll") for (int qt = 0; qt < 2; ++qt)                                                     \
-                acc_o[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv_, fp[B][qt][k2], acc_o[qt][dt], 0, 0, 0); \
-        }
-    // mask (ragged last tile), column maxima and the rare move of the softmax reference for the scores in set B
-#define PS_PREPARE(B, KT, KV0, FIRST)                                                                            \
+    // probabilities of query sub-tile QT from its shifted scores minus SH_: exp2, bf16 pack, row sum of the packed values
+#define PS_PROBS(QT, SH_)                                                                                        \
     {                                                                                                            \
+        sum_ = 0.f;                                                                                              \
+        _Pragma("unroll") for (int k2 = 0; k2 < 2; ++k2) {                                                       \
+            uint32_t pk_[4];                                                                                     \
+            _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                      \
+                const f32x2 pf_ = {__builtin_amdgcn_exp2f(acc_s[QT][8 * k2 + 2 * i] - (SH_)),                    \
+                                   __builtin_amdgcn_exp2f(acc_s[QT][8 * k2 + 2 * i + 1] - (SH_))};               \
+                const bf16x2 pb_ = __builtin_convertvector(pf_, bf16x2);                                         \
+                sum_ = __builtin_amdgcn_fdot2_f32_bf16(pb_, bf16x2{(__bf16)1.f, (__bf16)1.f}, sum_, false);      \
+                pk_[i] = __builtin_bit_cast(uint32_t, pb_);                                                      \
+            }                                                                                                    \
+            fp[QT][k2] = __builtin_bit_cast(bf16x8, u32x4{pk_[0], pk_[1], pk_[2], pk_[3]});                      \
+        }                                                                                                        \
+    }
+    // one 32-key half tile (KT = 0 / 1 of the tile in stage ST): S^T = K Q^T - m_ref, P = 2^S, O^T += V^T P
+#define PS_HALF(ST, KT, KV0, FIRST)                                                                              \
+    {                                                                                                            \
+        __builtin_amdgcn_sched_barrier(0);                                                                       \
+        bf16x8 fk_[4], fv_[2][2];                                                                                \
+        _Pragma("unroll") for (int ks = 0; ks < 4; ++ks)                                                         \
+            fk_[ks] = __builtin_bit_cast(bf16x8, sK[(ST) * 512 + krow[KT] * 8 + ((2 * ks + fh) ^ ksw[KT])]);     \
+        _Pragma("unroll") for (int ks = 0; ks < 4; ++ks)                                                         \
+            _Pragma("unroll") for (int qt = 0; qt < 2; ++qt)                                                     \
+                acc_s[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk_[ks], fq[qt][ks], ks == 0 ? cinit[qt] : acc_s[qt], 0, 0, 0); \
+        __builtin_amdgcn_sched_barrier(0);                                                                       \
+        _Pragma("unroll") for (int k2 = 0; k2 < 2; ++k2)                                                         \
+            _Pragma("unroll") for (int dt = 0; dt < 2; ++dt)                                                     \
+                fv_[k2][dt] = __builtin_bit_cast(bf16x8, sV[(ST) * 512 + (fr + 32 * dt) * 8 + ((4 * (KT) + 2 * k2 + fh) ^ vsw[dt])]); \
+        __builtin_amdgcn_sched_barrier(0);                                                                       \
         if ((KV0) + ATT_BKV > nk) {                                                                              \
             _Pragma("unroll") for (int e = 0; e < 16; ++e) {                                                     \
                 const int key_ = (KV0) + 32 * (KT) + 16 * (e >> 3) + 8 * fh + (e & 7);                           \
-                if (key_ >= nk) { acc_s[B][0][e] = -INFINITY; acc_s[B][1][e] = -INFINITY; }                      \
+                if (key_ >= nk) { acc_s[0][e] = -INFINITY; acc_s[1][e] = -INFINITY; }                            \
             }                                                                                                    \
         }                                                                                                        \
-        float mx_[2];                                                                                            \
         _Pragma("unroll") for (int qt = 0; qt < 2; ++qt) {                                                       \
-            float m_ = -INFINITY;                                                                                \
-            _Pragma("unroll") for (int e = 0; e < 16; ++e) m_ = fmaxf(m_, acc_s[B][qt][e]);                      \
-            mx_[qt] = half_swap_max(m_);                                                                         \
-        }                                                                                                        \
-        if ((FIRST) || __any(mx_[0] > ATT_TAU || mx_[1] > ATT_TAU)) {                                            \
-            _Pragma("unroll") for (int qt = 0; qt < 2; ++qt) {                                                   \
-                const float d_ = ((FIRST) || mx_[qt] > ATT_TAU) ? mx_[qt] : 0.f;                                 \
+            float sum_;                                                                                          \
+            PS_PROBS(qt, 0.f);                                                                                   \
+            if ((FIRST) || __any(!(sum_ <= ATT_SUM_MAX))) {                                                      \
+                float m_ = -INFINITY;                                                                            \
+                _Pragma("unroll") for (int e = 0; e < 16; ++e) m_ = fmaxf(m_, acc_s[qt][e]);                     \
+                m_ = half_swap_max(m_);                                                                          \
+                const float d_ = ((FIRST) || m_ > 4.f) ? m_ : 0.f;                                               \
                 const float corr_ = (FIRST) ? 1.f : __builtin_amdgcn_exp2f(-d_);                                 \
                 m_ref[qt] += d_;                                                                                 \
                 l_run[qt] *= corr_;                                                                              \
-                _Pragma("unroll") for (int e = 0; e < 16; ++e) { acc_s[B][qt][e] -= d_; acc_s[1 - (B)][qt][e] -= d_; } \
                 _Pragma("unroll") for (int dt = 0; dt < 2; ++dt)                                                 \
                     _Pragma("unroll") for (int e = 0; e < 16; ++e) acc_o[qt][dt][e] *= corr_;                    \
+                _Pragma("unroll") for (int e = 0; e < 16; ++e) cinit[qt][e] = -m_ref[qt];                        \
+                PS_PROBS(qt, d_);                                                                                \
             }                                                                                                    \
+            l_run[qt] += sum_;                                                                                   \
+            _Pragma("unroll") for (int k2 = 0; k2 < 2; ++k2)                                                     \
+                _Pragma("unroll") for (int dt = 0; dt < 2; ++dt)                                                 \
+                    acc_o[qt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv_[k2][dt], fp[qt][k2], acc_o[qt][dt], 0, 0, 0); \
         }                                                                                                        \
-    }
-    // probabilities of set B (exp2 of the shifted scores), row sums, bf16 pack; then the set restarts at -m_ref
-#define PS_SOFTMAX(B)                                                                                            \
-    _Pragma("unroll") for (int qt = 0; qt < 2; ++qt) {                                                           \
-        float sum_ = 0.f;                                                                                        \
-        _Pragma("unroll") for (int k2 = 0; k2 < 2; ++k2) {                                                       \
-            float pv_[8];                                                                                        \
-            _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                      \
-                pv_[i] = __builtin_amdgcn_exp2f(acc_s[B][qt][8 * k2 + i]);                                       \
-                sum_ += pv_[i];                                                                                  \
-            }                                                                                                    \
-            u32x4 pk_;                                                                                           \
-            _Pragma("unroll") for (int i = 0; i < 4; ++i) pk_[i] = pack_bf16x2(pv_[2 * i], pv_[2 * i + 1]);      \
-            fp[B][qt][k2] = __builtin_bit_cast(bf16x8, pk_);                                                     \
-        }                                                                                                        \
-        l_run[qt] += sum_;                                                                                       \
-        _Pragma("unroll") for (int e = 0; e < 16; ++e) acc_s[B][qt][e] = -m_ref[qt];                             \
-    }
-    // ask the scheduler to spread the 16 MFMAs of a half over its vector work
-#define PS_INTERLEAVE()                                                                                          \
-    _Pragma("unroll") for (int i_ = 0; i_ < 16; ++i_) {                                                          \
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                       \
-        __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);                                                       \
     }
 
-    PS_S_MFMAS(0, 0, 0);                                    // scores of the very first half tile
+    int st = 0;
     for (int t = 0; t < steps; ++t) {
-        if (t > 0) {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // own loads of tile t+1 have landed
-            __syncthreads();                                    // tile t+1 visible to all; the stage of tile t-2 is free
-        }
-        PS_ISSUE_TILE(t + 2);
-        const int st = t & (ATT_NS - 1), sn = (t + 1) & (ATT_NS - 1), sp = (t + ATT_NS - 1) & (ATT_NS - 1);
+        asm volatile("s_waitcnt vmcnt(4)" ::: "memory");        // own loads of tile t have landed (tile t+1 may be in flight)
+        __syncthreads();                                        // tile t visible to all; the stage of tile t-1 is free
+        const int st2 = st == 0 ? ATT_NS - 1 : st - 1;          // stage of tile t-1 == stage of tile t+2
+        PS_ISSUE_TILE(t + 2, st2);
         const int kv0 = t * ATT_BKV;
-        // half 0: softmax of S(t, 0) [set 0] with P(t-1, 1) V [set 1] and S(t, 1) -> set 1
-        PS_PREPARE(0, 0, kv0, t == 0);
-        PS_PV_MFMAS(1, sp, 1);
-        PS_S_MFMAS(1, st, 1);
-        PS_SOFTMAX(0);
-        PS_INTERLEAVE();
-        __builtin_amdgcn_sched_barrier(0);
-        // half 1: softmax of S(t, 1) [set 1] with P(t, 0) V [set 0] and S(t+1, 0) -> set 0
-        PS_PREPARE(1, 1, kv0, false);
-        PS_PV_MFMAS(0, st, 0);
-        PS_S_MFMAS(0, sn, 0);
-        PS_SOFTMAX(1);
-        PS_INTERLEAVE();
-        __builtin_amdgcn_sched_barrier(0);
+        const bool first = t == 0;
+        PS_HALF(st, 0, kv0, first);
+        PS_HALF(st, 1, kv0, false);
+        st = st + 1 == ATT_NS ? 0 : st + 1;
     }
-    PS_PV_MFMAS(1, (steps - 1) & (ATT_NS - 1), 1);          // P of the last half tile
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");        // no load may still target LDS when the block retires
-#undef PS_INTERLEAVE
-#undef PS_SOFTMAX
-#undef PS_PREPARE
-#undef PS_PV_MFMAS
-#undef PS_S_MFMAS
+#undef PS_HALF
+#undef PS_PROBS
 #undef PS_ISSUE_TILE
 
     // ---- O[q][head*64 + d] = O^T / l ; lane holds d = 32*dt + 8*(e/4) + 4*fh + e%4 of query fr
