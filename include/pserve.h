@@ -188,6 +188,10 @@ typedef struct {
     float   total_ms;     /* summed device time of those launches */
 } pserve_prof_entry;
 int  pserve_profile_enable(int on);
+/* Restrict the timing to the kernels with this label (NULL or "": all kernels again).  Every event
+ * pair costs a few microseconds of stream time, so a throughput measurement that also wants one
+ * kernel's duration times only that kernel.  Errors: EINVAL (label of 32 characters or more). */
+int  pserve_profile_select(const char* label);
 int  pserve_profile_read(pserve_prof_entry* out, int32_t max, int32_t* count);
 
 #ifdef __cplusplus

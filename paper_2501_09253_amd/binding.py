@@ -93,6 +93,7 @@ def lib() -> C.CDLL:
     L.pserve_block_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
     L.pserve_set_kernel_mode.argtypes = [C.c_int]
     L.pserve_profile_enable.argtypes = [C.c_int]
+    L.pserve_profile_select.argtypes = [C.c_char_p]
     L.pserve_profile_read.argtypes = [C.POINTER(_ProfEntry), i32, C.POINTER(i32)]
     _lib = L
     return L
@@ -121,6 +122,11 @@ def set_kernel_mode(mode: int):
 def profile_enable(on: bool):
     """Bracket every kernel of pserve_block_forward with HIP events (pserve_profile_enable)."""
     _check(lib().pserve_profile_enable(int(on)))
+
+
+def profile_select(label: Optional[str]):
+    """Time only the kernels with this label; None = all kernels (pserve_profile_select)."""
+    _check(lib().pserve_profile_select(None if not label else label.encode()))
 
 
 def profile_read() -> Dict[str, Dict[str, float]]:

@@ -23,6 +23,7 @@ static int g_kernel_mode = 0;
 struct ProfRecord { const char* name; hipEvent_t start, stop; };
 struct Profiler {
     bool on = false;
+    char only[32] = {0};                 // when not empty: the one kernel label that is timed
     std::vector<ProfRecord> recs;
     std::vector<hipEvent_t> pool;
     hipEvent_t get() {
@@ -37,7 +38,7 @@ struct ProfScope {
     hipStream_t st;
     hipEvent_t stop = nullptr;
     ProfScope(const char* name, hipStream_t s) : st(s) {
-        if (!g_prof.on) return;
+        if (!g_prof.on || (g_prof.only[0] && strcmp(g_prof.only, name) != 0)) return;
         hipEvent_t start = g_prof.get();
         stop = g_prof.get();
         if (!start || !stop) { stop = nullptr; return; }
@@ -180,6 +181,15 @@ int pserve_set_kernel_mode(int mode) {
 
 int pserve_profile_enable(int on) {
     g_prof.on = on != 0;
+    return PSERVE_OK;
+}
+
+int pserve_profile_select(const char* label) {
+    memset(g_prof.only, 0, sizeof(g_prof.only));
+    if (label) {
+        PS_REQUIRE(strlen(label) < sizeof(g_prof.only), "pserve_profile_select: label too long");
+        strcpy(g_prof.only, label);
+    }
     return PSERVE_OK;
 }
 
