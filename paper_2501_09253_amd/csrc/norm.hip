@@ -10,7 +10,7 @@
 // Three kernels for the norm:
 //   gn_partial_kernel   per (patch, token chunk): per-group sum and sum of squares (fp32),
 //                       16-byte loads, per-thread channel accumulators, LDS tree to groups
-//   gn_finalize_kernel  per (request, group): wavefront-shuffle reduction of the partials in
+//   gn_finalize_kernel  per (request, group): shuffle + LDS reduction of the partials in
 //                       fp64 -> mean, rstd -> per (request, channel) scale and shift
 //   gn_apply_kernel     y = x*scale + shift (+SiLU), written plain or into the interior of
 //                       the padded patch buffer the convolution reads
@@ -55,6 +55,8 @@ __device__ __forceinline__ void store_vec<uint16_t>(uint16_t* p, const float (&v
     *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
+constexpr int GN_U = 8;     // token rows a thread keeps in flight
+
 // thread (tl, cv): cv = channel vector (fixed channels for the whole kernel), tl = token lane
 template <typename T>
 __global__ void gn_partial_kernel(const T* __restrict__ x, int32_t C, int32_t G, int32_t S, int32_t nsplit,
@@ -70,21 +72,18 @@ __global__ void gn_partial_kernel(const T* __restrict__ x, int32_t C, int32_t G,
 #pragma unroll
     for (int e = 0; e < VN; ++e) { s1[e] = 0.f; s2[e] = 0.f; }
     const T* base = x + ((int64_t)p * S) * C + cv * VN;
-    int t = t0 + tl;
-    for (; t + 3 * TL < t1; t += 4 * TL) {          // four independent 16-byte loads in flight
-        float v[4][VN];
+    // up to GN_U independent 16-byte loads in flight per thread; rows past the chunk re-read its last row and are skipped
+    for (int tb = t0 + tl; tb < t1; tb += GN_U * TL) {
+        float v[GN_U][VN];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) load_vec<T>(base + (int64_t)(t + u * TL) * C, v[u]);
+        for (int u = 0; u < GN_U; ++u) load_vec<T>(base + (int64_t)min(tb + u * TL, t1 - 1) * C, v[u]);
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < GN_U; ++u) {
+            if (tb + u * TL < t1) {
 #pragma unroll
-            for (int e = 0; e < VN; ++e) { s1[e] += v[u][e]; s2[e] = fmaf(v[u][e], v[u][e], s2[e]); }
-    }
-    for (; t < t1; t += TL) {
-        float v[VN];
-        load_vec<T>(base + (int64_t)t * C, v);
-#pragma unroll
-        for (int e = 0; e < VN; ++e) { s1[e] += v[e]; s2[e] = fmaf(v[e], v[e], s2[e]); }
+                for (int e = 0; e < VN; ++e) { s1[e] += v[u][e]; s2[e] = fmaf(v[u][e], v[u][e], s2[e]); }
+            }
+        }
     }
 #pragma unroll
     for (int e = 0; e < VN; ++e) {
@@ -103,7 +102,9 @@ __global__ void gn_partial_kernel(const T* __restrict__ x, int32_t C, int32_t G,
     }
 }
 
-// block = one wavefront per (request slot s, group g)
+constexpr int GN_FIN_THREADS = 256;
+
+// block = four wavefronts per (request slot s, group g)
 template <typename T>
 __global__ void gn_finalize_kernel(const float* __restrict__ partial, const int32_t* __restrict__ request_offset,
                                    const T* __restrict__ gamma, const T* __restrict__ beta, int32_t C, int32_t G,
@@ -112,7 +113,7 @@ __global__ void gn_finalize_kernel(const float* __restrict__ partial, const int3
     const int p0 = request_offset[s], p1 = request_offset[s + 1];
     const int items = (p1 - p0) * nsplit;
     double a = 0.0, b = 0.0;
-    for (int i = threadIdx.x; i < items; i += 64) {
+    for (int i = threadIdx.x; i < items; i += GN_FIN_THREADS) {
         const float* src = partial + (((int64_t)p0 * nsplit + i) * G + g) * 2;
         a += (double)src[0];
         b += (double)src[1];
@@ -122,15 +123,20 @@ __global__ void gn_finalize_kernel(const float* __restrict__ partial, const int3
         a += __shfl_down(a, off, 64);
         b += __shfl_down(b, off, 64);
     }
-    a = __shfl(a, 0, 64);
-    b = __shfl(b, 0, 64);
+    __shared__ double red[GN_FIN_THREADS / 64][2];
+    if ((threadIdx.x & 63) == 0) { red[threadIdx.x >> 6][0] = a; red[threadIdx.x >> 6][1] = b; }
+    __syncthreads();
+    a = 0.0;
+    b = 0.0;
+#pragma unroll
+    for (int w = 0; w < GN_FIN_THREADS / 64; ++w) { a += red[w][0]; b += red[w][1]; }    // fixed order: deterministic
     const int cg = C / G;
     const double cnt = (double)(p1 - p0) * S * cg;
     const double mean = a / cnt;
     double var = b / cnt - mean * mean;
     var = var > 0.0 ? var : 0.0;
     const double rstd = 1.0 / sqrt(var + (double)eps);
-    for (int c = g * cg + threadIdx.x; c < (g + 1) * cg; c += 64) {
+    for (int c = g * cg + threadIdx.x; c < (g + 1) * cg; c += GN_FIN_THREADS) {
         const double sc = rstd * (double)ld_f<T>(gamma + c);
         float* dst = scale_shift + ((int64_t)s * C + c) * 2;
         dst[0] = (float)sc;
@@ -197,37 +203,26 @@ __global__ void gn_apply_kernel(const T* __restrict__ x, const float* __restrict
         }
         return ((int64_t)p * gm.S + t) * C;
     };
-    int t = t0 + tl;
-    for (; t + 3 * TL < t1; t += 4 * TL) {          // four independent 16-byte loads in flight
-        float v[4][VN];
+    // up to GN_U independent 16-byte loads in flight per thread; rows past the chunk re-read its last row and are skipped
+    for (int tb = t0 + tl; tb < t1; tb += GN_U * TL) {
+        float v[GN_U][VN];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) load_vec<T>(base + (int64_t)(t + u * TL) * C, v[u]);
+        for (int u = 0; u < GN_U; ++u) load_vec<T>(base + (int64_t)min(tb + u * TL, t1 - 1) * C, v[u]);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < GN_U; ++u) {
+            const int t = tb + u * TL;
+            if (t < t1) {
 #pragma unroll
-            for (int e = 0; e < VN; ++e) {
-                v[u][e] = fmaf(v[u][e], sc[e], sh[e]);
-                if (SILU) v[u][e] = silu_f(v[u][e]);
+                for (int e = 0; e < VN; ++e) {
+                    v[u][e] = fmaf(v[u][e], sc[e], sh[e]);
+                    if (SILU) v[u][e] = silu_f(v[u][e]);
+                }
+                store_vec<T>(out + out_off(t) + cv * VN, v[u]);
+                if (PADDED && STITCH) {
+                    const int y = t / gm.pw;
+                    stitch_store<T>(out, neighbour + 8 * p, gm, p, y, t - y * gm.pw, C, cv * VN, v[u]);
+                }
             }
-            store_vec<T>(out + out_off(t + u * TL) + cv * VN, v[u]);
-            if (PADDED && STITCH) {
-                const int tt = t + u * TL, y = tt / gm.pw;
-                stitch_store<T>(out, neighbour + 8 * p, gm, p, y, tt - y * gm.pw, C, cv * VN, v[u]);
-            }
-        }
-    }
-    for (; t < t1; t += TL) {
-        float v[VN];
-        load_vec<T>(base + (int64_t)t * C, v);
-#pragma unroll
-        for (int e = 0; e < VN; ++e) {
-            v[e] = fmaf(v[e], sc[e], sh[e]);
-            if (SILU) v[e] = silu_f(v[e]);
-        }
-        store_vec<T>(out + out_off(t) + cv * VN, v);
-        if (PADDED && STITCH) {
-            const int y = t / gm.pw;
-            stitch_store<T>(out, neighbour + 8 * p, gm, p, y, t - y * gm.pw, C, cv * VN, v);
         }
     }
 }
@@ -289,10 +284,10 @@ int gn_stats(const GroupNormArgs& a, const PatchGeom& g, int dtype, hipStream_t 
     PS_TRY(check_launch("gn_partial_kernel"));
     dim3 fgrid(a.n, a.G);
     if (dtype == PSERVE_BF16)
-        gn_finalize_kernel<uint16_t><<<fgrid, 64, 0, st>>>(a.partial, a.request_offset, (const uint16_t*)a.gamma,
+        gn_finalize_kernel<uint16_t><<<fgrid, GN_FIN_THREADS, 0, st>>>(a.partial, a.request_offset, (const uint16_t*)a.gamma,
                                                            (const uint16_t*)a.beta, a.C, a.G, g.S, a.nsplit, a.eps, a.scale_shift);
     else
-        gn_finalize_kernel<float><<<fgrid, 64, 0, st>>>(a.partial, a.request_offset, (const float*)a.gamma,
+        gn_finalize_kernel<float><<<fgrid, GN_FIN_THREADS, 0, st>>>(a.partial, a.request_offset, (const float*)a.gamma,
                                                         (const float*)a.beta, a.C, a.G, g.S, a.nsplit, a.eps, a.scale_shift);
     return check_launch("gn_finalize_kernel");
 }
