@@ -175,6 +175,51 @@ split_kernel(ImagePtrs imgs, int slot0, int patch0, const int32_t* __restrict__ 
     }
 }
 
+// bf16 fast path: tile = 64 channels x 32 consecutive tokens of one patch, one 16-byte access per thread on each
+// side (8 pixels of one channel row in NCHW; 8 channels of one token in the patch-major layout), transposed in LDS.
+// Needs pw % 8 == 0, (ph*pw) % 32 == 0, C % 64 == 0, W % 8 == 0 and 16-byte aligned images.
+template <bool TO_PATCH>
+__global__ void __launch_bounds__(256)
+split_vec_kernel(ImagePtrs imgs, int slot0, int patch0, const int32_t* __restrict__ sorted_hw,
+                 const int32_t* __restrict__ owner, const int32_t* __restrict__ rc, int32_t ph, int32_t pw, int32_t C,
+                 uint16_t* __restrict__ x) {
+    __shared__ __attribute__((aligned(16))) uint16_t tile[32][72];      // [token][channel], rows padded to 144 bytes
+    const int S = ph * pw, tiles = S / 32;
+    const int p = patch0 + blockIdx.x / tiles;
+    const int t0 = (blockIdx.x % tiles) * 32;
+    const int c0 = blockIdx.y * 64;
+    const int s = owner[p];
+    const int H = sorted_hw[2 * s], W = sorted_hw[2 * s + 1];
+    uint16_t* img = (uint16_t*)imgs.p[s - slot0];
+    const int tid = threadIdx.x;
+    // image side: channel ich, 8 pixels starting at token t0 + 8*iq
+    const int ich = tid >> 2, iq = tid & 3;
+    const int it = t0 + 8 * iq, iy = it / pw, ix = it - iy * pw;
+    uint16_t* ip = img + ((int64_t)(c0 + ich) * H + rc[2 * p] * ph + iy) * W + rc[2 * p + 1] * pw + ix;
+    // patch side: token t0 + ptk, channels 8*pq .. +8
+    const int ptk = tid >> 3, pq = tid & 7;
+    uint16_t* xp = x + ((int64_t)p * S + t0 + ptk) * C + c0 + 8 * pq;
+    typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+    if (TO_PATCH) {
+        const u32x4 v = *reinterpret_cast<const u32x4*>(ip);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            tile[8 * iq + 2 * k][ich] = (uint16_t)(v[k] & 0xFFFFu);
+            tile[8 * iq + 2 * k + 1][ich] = (uint16_t)(v[k] >> 16);
+        }
+        __syncthreads();
+        *reinterpret_cast<u32x4*>(xp) = *reinterpret_cast<const u32x4*>(&tile[ptk][8 * pq]);
+    } else {
+        *reinterpret_cast<u32x4*>(&tile[ptk][8 * pq]) = *reinterpret_cast<const u32x4*>(xp);
+        __syncthreads();
+        u32x4 v;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            v[k] = (uint32_t)tile[8 * iq + 2 * k][ich] | ((uint32_t)tile[8 * iq + 2 * k + 1][ich] << 16);
+        *reinterpret_cast<u32x4*>(ip) = v;
+    }
+}
+
 template <bool TO_PATCH>
 static int run_split(const pserve_plan_t* plan, void* const* images, int32_t C, int dtype, void* x, hipStream_t st) {
     PS_REQUIRE(plan && images && x, "split/reassemble: NULL argument");
@@ -189,6 +234,16 @@ static int run_split(const pserve_plan_t* plan, void* const* images, int32_t C, 
         memset(&ip, 0, sizeof(ip));
         for (int s = s0; s < s1; ++s) ip.p[s - s0] = images[perm[s]];
         const int patch0 = ro[s0], npatch = ro[s1] - ro[s0];
+        bool vec = dtype == PSERVE_BF16 && plan->pw % 8 == 0 && plan->S % 32 == 0 && C % 64 == 0 && ((uintptr_t)x & 15) == 0;
+        for (int s = s0; s < s1 && vec; ++s)
+            vec = plan->h_sorted_hw[2 * s + 1] % 8 == 0 && ((uintptr_t)ip.p[s - s0] & 15) == 0;
+        if (vec) {
+            dim3 vgrid(npatch * (plan->S / 32), (unsigned)(C / 64));
+            split_vec_kernel<TO_PATCH><<<vgrid, 256, 0, st>>>(ip, s0, patch0, plan->d_sorted_hw,
+                plan->d_tab[PSERVE_TAB_PATCH_OWNER], plan->d_tab[PSERVE_TAB_PATCH_RC], plan->ph, plan->pw, C, (uint16_t*)x);
+            PS_TRY(check_launch("split_vec_kernel"));
+            continue;
+        }
         dim3 grid(npatch * plan->ph, (unsigned)cdiv(C, 64));
         if (dtype == PSERVE_BF16)
             split_kernel<uint16_t, TO_PATCH><<<grid, 256, 0, st>>>(ip, s0, patch0, plan->d_sorted_hw,

@@ -57,7 +57,8 @@ def test_plan_many_requests():
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("res,ph,pw,C", [([(16, 16), (24, 24)], 8, 8, 64), ([(4, 6), (2, 2), (4, 6)], 2, 2, 8),
-                                         ([(96, 64), (32, 32)], 32, 32, 72), ([(40, 40)], 40, 40, 16)])
+                                         ([(96, 64), (32, 32)], 32, 32, 72), ([(40, 40)], 40, 40, 16),
+                                         ([(32, 48), (16, 16)], 16, 16, 128), ([(8, 64), (16, 128)], 8, 64, 64)])
 def test_split_reassemble_bit_exact(res, ph, pw, C, dtype):
     imgs = [wl.bf16_round(wl.Stream(5, f"s{i}").normal((C, h, w))) for i, (h, w) in enumerate(res)]
     plan = ps.Plan(res, ph, pw)
