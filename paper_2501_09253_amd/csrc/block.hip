@@ -337,7 +337,7 @@ int pserve_cache_create(const pserve_plan_t* plan, const pserve_block_t* block, 
     const bool sattn = has_stage(d, PSERVE_SATTN), xattn = has_stage(d, PSERVE_XATTN), ffn = has_stage(d, PSERVE_FFN);
     if (conv) PS_TRY(c->pool.alloc(&c->apad, (size_t)plan->P * (plan->ph + 2) * (plan->pw + 2) * d.C * es));
     if (conv || sattn) {
-        PS_TRY(c->pool.alloc_t(&c->partial, (size_t)plan->P * c->nsplit * d.G * 2));
+        PS_TRY(c->pool.alloc_t(&c->partial, (size_t)plan->P * std::max<int64_t>(c->nsplit, plan->S / 64) * d.G * 2));
         PS_TRY(c->pool.alloc_t(&c->scale_shift, (size_t)plan->n * d.C * 2));
     }
     for (int s = 0; s < d.n_stages; ++s) {
@@ -486,9 +486,13 @@ int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* c
         return g;
     };
     // GroupNorm(+SiLU) of `in` into the padded buffer, halo ring, 3x3 convolution (+bias, +residual) into `out`
-    auto norm_conv = [&](const void* in, const StageWeights& w, int ci, const void* res, void* out) -> int {
+    // stats_next: the output feeds another norm, so the convolution may leave that norm's partial sums behind
+    bool have_partials = false;                     // cache->partial was filled by the previous convolution
+    auto norm_conv = [&](const void* in, const StageWeights& w, int ci, const void* res, void* out, bool stats_next) -> int {
         GroupNormArgs ga = gn_args(in, w.gn_g[ci], w.gn_b[ci]);
-        { ProfScope ps("gn_stats", st); PS_TRY(gn_stats(ga, gm, dt, st)); }
+        if (have_partials) { ProfScope ps("gn_stats", st); PS_TRY(gn_finalize(ga, gm, dt, plan->S / 64, st)); }
+        else { ProfScope ps("gn_stats", st); PS_TRY(gn_stats(ga, gm, dt, st)); }
+        have_partials = false;
         if (mode == 0) {        // normalise + stitch in one pass (push); the reference path gathers rims afterwards (pull)
             ProfScope ps("gn_apply_stitch", st);
             PS_TRY(gn_apply(ga, gm, dt, /*silu=*/true, /*padded=*/true, /*stitch=*/true, cache->apad, all, st));
@@ -500,6 +504,12 @@ int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* c
         GemmArgs g = base_gemm(cache->apad, C, C, C, w.w[ci], w.b[ci]);
         g.conv = 1; g.taps = 9; g.res = res; g.ldr = C;
         g.seg[0].ptr = out; g.seg[0].ld = C;
+        if (stats_next && !reuse_mask) {
+            // (with a mask the reused patches keep cached activations this convolution never sees: gn_stats reads them)
+            g.stats = cache->partial; g.stats_G = d.G; g.stats_slots = plan->S / 64;
+            if (gemm_emits_stats(g, dt, mode)) have_partials = true;
+            else { g.stats = nullptr; g.stats_G = 0; g.stats_slots = 0; }
+        }
         ProfScope ps("conv3x3", st);
         return gemm(g, dt, mode, st);
     };
@@ -515,11 +525,11 @@ int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* c
 
         switch (d.stages[si]) {
         case PSERVE_RES1:
-            PS_TRY(norm_conv(cur, w, 0, cur, out));
+            PS_TRY(norm_conv(cur, w, 0, cur, out, false));
             break;
         case PSERVE_RES2:
-            PS_TRY(norm_conv(cur, w, 0, nullptr, cache->h1[si]));
-            PS_TRY(norm_conv(cache->h1[si], w, 1, cur, out));
+            PS_TRY(norm_conv(cur, w, 0, nullptr, cache->h1[si], true));
+            PS_TRY(norm_conv(cache->h1[si], w, 1, cur, out, false));
             break;
         case PSERVE_SATTN: {
             const void* rin = cur;

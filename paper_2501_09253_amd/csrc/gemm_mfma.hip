@@ -31,6 +31,13 @@ __device__ __forceinline__ float gelu_erf(float v) {
     return 0.5f * v * (1.f + copysignf(e, v));
 }
 
+// value of lane l ^ 32 (v_permlane32_swap: upper half of the first operand <-> lower half of the second)
+__device__ __forceinline__ float other_half_f(float v) {
+    const uint32_t u = __float_as_uint(v);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __uint_as_float((threadIdx.x & 32) ? r[0] : r[1]);
+}
+
 // ---- epilogue shared by the kernels.  A lane holds column (lane % 32) of each 32x32 tile and rows
 // 8*(e/4) + 4*(lane/32) + e%4.  One tile column (WM rows x 32 columns) at a time is finished in registers (bias,
 // scale, GEGLU), staged as fp32 in this wavefront's private LDS region and read back row-wise, so that residual
@@ -63,6 +70,19 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[B
 #pragma unroll
         for (int t = 0; t < NIT; ++t) rres[0][t] = *reinterpret_cast<const u32x4*>(res_row[t] + n0 + wn * WN);
     }
+    // GroupNorm partial sums of the output (optional): column sums over this wavefront's 64 rows, which lie in one patch
+    const bool STATS = !GEGLU && a.stats != nullptr;
+    float* colsum = reinterpret_cast<float*>(smem) + WGM * WGN * (WM * EP_LD) + wave * (2 * WN);    // [WN][2]
+    uint32_t row_ok[TM];                                            // bit e: row 8*(e/4) + 4*fh + e%4 of tile i exists
+    const bool all_rows = STATS && w_tok[WM - 1] >= 0;              // existing rows are a prefix of the tile
+    if (STATS && !all_rows) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            row_ok[i] = 0;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) row_ok[i] |= (w_tok[i * 32 + 8 * (e >> 2) + 4 * fh + (e & 3)] >= 0 ? 1u : 0u) << e;
+        }
+    }
 #pragma unroll
     for (int j = 0; j < TNO; ++j) {
         const int pcol = n0 + wn * WN + j * 32;                     // first packed column of the tile
@@ -86,6 +106,27 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[B
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) vals[i][e] = acc[i][j][e] + bias;
+            if (STATS) {
+                float s1 = 0.f, s2 = 0.f;
+                if (all_rows) {
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) { s1 += vals[i][e]; s2 = fmaf(vals[i][e], vals[i][e], s2); }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) {
+                            const float v = (row_ok[i] >> e) & 1u ? vals[i][e] : 0.f;
+                            s1 += v;
+                            s2 = fmaf(v, v, s2);
+                        }
+                }
+                s1 += other_half_f(s1);
+                s2 += other_half_f(s2);
+                if (fh == 0) { colsum[2 * (j * 32 + fr)] = s1; colsum[2 * (j * 32 + fr) + 1] = s2; }
+            }
         }
         uint16_t* out = (uint16_t*)sgm.ptr;
         if (sgm.transposed) {
@@ -146,6 +187,19 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[B
             if (tok >= 0) *reinterpret_cast<u32x4*>(out + tk * sgm.ld + ocol0 + ch * 8) = o;
         }
         __builtin_amdgcn_wave_barrier();
+    }
+    if (STATS) {
+        __builtin_amdgcn_wave_barrier();
+        const int cg = a.N / a.stats_G;                             // channels per group (divides WN, see gemm_emits_stats)
+        const int tok0 = w_tok[0];
+        if (lane < WN / cg && tok0 >= 0) {
+            float s1 = 0.f, s2 = 0.f;
+            for (int c = lane * cg; c < (lane + 1) * cg; ++c) { s1 += colsum[2 * c]; s2 += colsum[2 * c + 1]; }
+            const int p = tok0 / a.geom.S, slot = (tok0 - p * a.geom.S) / WM;
+            float* dst = a.stats + (((int64_t)p * a.stats_slots + slot) * a.stats_G + (n0 + wn * WN) / cg + lane) * 2;
+            dst[0] = s1;
+            dst[1] = s2;
+        }
     }
 }
 
@@ -587,9 +641,42 @@ static int launch(const GemmArgs& a, hipStream_t st) {
     return check_launch("gemm_mfma_kernel");
 }
 
+// shapes the MFMA kernels take at all
+static bool mfma_eligible(const GemmArgs& a) {
+    return a.K % 64 == 0 && a.lda % 8 == 0 && !((uintptr_t)a.A & 15) && !((uintptr_t)a.B & 15);
+}
+
+// Which halo-in-LDS convolution kernel a problem takes (0: none) and the columns one wavefront of it covers.
+// Preferred: 256 x 160 tiles, four wavefronts stacked along M (each 64 x 160), three weight stages: half the weight
+// bytes per MFMA of the 128 x 320 tile at the same accumulator shape.
+static int conv_select(const GemmArgs& a, ConvTile* ct, int* wave_cols = nullptr) {
+    int wc = 0, sel = 0;
+    if (a.epi == EPI_ROUTE && a.seg_cols % 32 == 0 && a.seg_cols == a.N && !a.seg[0].transposed) {
+        if (a.N % 160 == 0 && conv_tile(a, 256, 384, ct)) { sel = 1; wc = 160; }
+        else if (conv_tile(a, 128, 256, ct)) {
+            if (a.N % 320 == 0) { sel = 2; wc = 160; }
+            else if (a.N % 256 == 0) { sel = 3; wc = 128; }
+            else if (a.N % 128 == 0) { sel = 4; wc = 64; }
+            else if (a.N % 64 == 0) { sel = 5; wc = 32; }
+        }
+    }
+    if (wave_cols) *wave_cols = wc;
+    return sel;
+}
+
+bool gemm_emits_stats(const GemmArgs& a, int dtype, int mode) {
+    if (mode != 0 || dtype != PSERVE_BF16 || !a.stats || a.stats_G <= 0 || !mfma_eligible(a)) return false;
+    ConvTile ct;
+    int wc = 0;
+    if (!conv_select(a, &ct, &wc)) return false;
+    // a wavefront's 64 rows must lie in one patch, and its columns must hold whole groups
+    return a.geom.S % 64 == 0 && a.stats_slots == a.geom.S / 64 && !a.act.active && a.N % a.stats_G == 0 &&
+           wc % (a.N / a.stats_G) == 0;
+}
+
 int gemm_mfma_bf16(const GemmArgs& a, hipStream_t st, bool* handled) {
     *handled = false;
-    if (a.K % 64 != 0 || a.lda % 8 != 0 || ((uintptr_t)a.A & 15) || ((uintptr_t)a.B & 15)) return PSERVE_OK;
+    if (!mfma_eligible(a)) return PSERVE_OK;
     if (a.epi == EPI_GEGLU) {
         if (a.N % 256 != 0) return PSERVE_OK;
         *handled = true;
@@ -597,16 +684,13 @@ int gemm_mfma_bf16(const GemmArgs& a, hipStream_t st, bool* handled) {
     }
     if (a.seg_cols % 32 != 0) return PSERVE_OK;      // a 32-column tile must not straddle output segments
     ConvTile ct;
-    if (a.seg_cols == a.N && !a.seg[0].transposed) {
-        // preferred: 256 x 160 tiles, four wavefronts stacked along M (each 64 x 160), three weight stages:
-        // half the weight bytes per MFMA of the 128 x 320 tile at the same accumulator shape
-        if (a.N % 160 == 0 && conv_tile(a, 256, 384, &ct)) { *handled = true; return launch_conv<256, 160, 4, 1, 384, 3>(a, ct, st); }
-        if (conv_tile(a, 128, 256, &ct)) {
-            if (a.N % 320 == 0) { *handled = true; return launch_conv<128, 320, 2, 2, 256, 2>(a, ct, st); }
-            if (a.N % 256 == 0) { *handled = true; return launch_conv<128, 256, 2, 2, 256, 2>(a, ct, st); }
-            if (a.N % 128 == 0) { *handled = true; return launch_conv<128, 128, 2, 2, 256, 2>(a, ct, st); }
-            if (a.N % 64 == 0) { *handled = true; return launch_conv<128, 64, 2, 2, 256, 2>(a, ct, st); }
-        }
+    switch (conv_select(a, &ct)) {
+    case 1: *handled = true; return launch_conv<256, 160, 4, 1, 384, 3>(a, ct, st);
+    case 2: *handled = true; return launch_conv<128, 320, 2, 2, 256, 2>(a, ct, st);
+    case 3: *handled = true; return launch_conv<128, 256, 2, 2, 256, 2>(a, ct, st);
+    case 4: *handled = true; return launch_conv<128, 128, 2, 2, 256, 2>(a, ct, st);
+    case 5: *handled = true; return launch_conv<128, 64, 2, 2, 256, 2>(a, ct, st);
+    default: break;
     }
     // Few rows (e.g. the text-token projections): wide tiles would leave most of the 256 CUs idle, so take the
     // narrowest tile when the widest one gives fewer than one block per two CUs.

@@ -51,6 +51,8 @@ struct GroupNormArgs {
     const int32_t* neighbour;  // [P][8] (stitching only)
 };
 int gn_stats(const GroupNormArgs& a, const PatchGeom& g, int dtype, hipStream_t st);
+// second half of gn_stats alone: a.partial already holds [P][slots][G][2] partial sums (filled by a convolution)
+int gn_finalize(const GroupNormArgs& a, const PatchGeom& g, int dtype, int32_t slots, hipStream_t st);
 // y = x*scale+shift (then SiLU if silu).  padded: write into the interior of the padded patch buffer
 // [P][ph+2][pw+2][C]; else plain [T][C].  Only patches of `act` are written.  stitch (padded, all patches):
 // border tokens also fill the neighbours' ring slots / zero the own ring at image edges (no halo_gather needed).
@@ -86,7 +88,14 @@ struct GemmArgs {
     int32_t epi;               // EPI_ROUTE: columns go to segment col / seg_cols; EPI_GEGLU: value*GELU(gate) pairs
     int32_t seg_cols;
     GemmSeg seg[3];
+    // Optional GroupNorm partial sums of the OUTPUT (bias included, before the residual), in the layout gn_finalize
+    // reads: stats[P][stats_slots][stats_G][2] = (sum, sum of squares) of 64 consecutive tokens of a patch
+    // (stats_slots = S / 64) and one group.  Only the kernels gemm_emits_stats() accepts fill it (plain stores).
+    float* stats;
+    int32_t stats_G, stats_slots;
 };
+// true if gemm(a, ...) will take a kernel that fills a.stats (the caller otherwise runs gn_stats on the output)
+bool gemm_emits_stats(const GemmArgs& a, int dtype, int mode);
 int gemm(const GemmArgs& a, int dtype, int mode, hipStream_t st);
 
 // weight packing into [taps][N][K] (K contiguous); all on device

@@ -282,13 +282,17 @@ int gn_stats(const GroupNormArgs& a, const PatchGeom& g, int dtype, hipStream_t 
     else
         gn_partial_kernel<float><<<grid, TL * CV, lds, st>>>((const float*)a.x, a.C, a.G, g.S, a.nsplit, TL, a.partial);
     PS_TRY(check_launch("gn_partial_kernel"));
+    return gn_finalize(a, g, dtype, a.nsplit, st);
+}
+
+int gn_finalize(const GroupNormArgs& a, const PatchGeom& g, int dtype, int32_t slots, hipStream_t st) {
     dim3 fgrid(a.n, a.G);
     if (dtype == PSERVE_BF16)
         gn_finalize_kernel<uint16_t><<<fgrid, GN_FIN_THREADS, 0, st>>>(a.partial, a.request_offset, (const uint16_t*)a.gamma,
-                                                           (const uint16_t*)a.beta, a.C, a.G, g.S, a.nsplit, a.eps, a.scale_shift);
+                                                                       (const uint16_t*)a.beta, a.C, a.G, g.S, slots, a.eps, a.scale_shift);
     else
         gn_finalize_kernel<float><<<fgrid, GN_FIN_THREADS, 0, st>>>(a.partial, a.request_offset, (const float*)a.gamma,
-                                                        (const float*)a.beta, a.C, a.G, g.S, a.nsplit, a.eps, a.scale_shift);
+                                                                    (const float*)a.beta, a.C, a.G, g.S, slots, a.eps, a.scale_shift);
     return check_launch("gn_finalize_kernel");
 }
 
