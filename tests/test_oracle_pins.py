@@ -16,6 +16,7 @@ import torch.nn.functional as F
 import workloads as wl
 from oracle import block as ob
 from oracle import plan as op
+from oracle import cache as oc
 
 RNG = np.random.default_rng(7)
 
@@ -436,3 +437,102 @@ def test_config_shapes():
     assert wl.config(2).T == 29696 and wl.config(5).T == 131072
     c3, c4 = wl.config(3), wl.config(4)
     assert c3.n == 8 and c4.n == 24 and 32 <= c3.P <= 128 and 96 <= c4.P <= 384
+
+
+# ----------------------------------------------------------------------------- cache manager pieces
+def _mse_images(seed, res, C):
+    return [wl.Stream(seed, f"m{i}").normal((C, h, w)).astype(np.float64) for i, (h, w) in enumerate(res)]
+
+
+def test_patch_mse_closed_forms_and_patch_localisation():
+    """Section "Patch-aware Caching Strategy", step 1 (input compared with the cache per patch; metric MSE)."""
+    res, ph, pw, C = [(8, 4), (4, 4), (8, 8)], 4, 2, 3
+    a = _mse_images(3, res, C)
+    assert np.array_equal(oc.patch_mse(a, a, ph, pw), np.zeros(2 * 2 + 1 * 2 + 2 * 4))          # identical -> 0
+    b = [x + 0.5 for x in a]
+    assert np.allclose(oc.patch_mse(a, b, ph, pw), 0.25, rtol=0, atol=1e-15)                      # constant offset c -> c^2
+    # one element changed by d: exactly one patch is non-zero, d^2 / (ph*pw*C), and it is the patch that the
+    # (independently pinned) planner tables place at that pixel
+    tabs = op.plan_tables(res, ph, pw)
+    for img, ch, Y, X in [(0, 1, 5, 3), (2, 0, 7, 0), (1, 2, 0, 3)]:
+        b = [x.copy() for x in a]
+        b[img][ch, Y, X] += 3.0
+        got = oc.patch_mse(a, b, ph, pw)
+        slot = list(tabs["perm"]).index(img)
+        want = [p for p in range(len(got)) if tabs["patch_owner"][p] == slot
+                and tuple(tabs["patch_rc"].reshape(-1, 2)[p]) == (Y // ph, X // pw)]
+        assert len(want) == 1
+        assert np.flatnonzero(got).tolist() == want
+        assert abs(got[want[0]] - 9.0 / (ph * pw * C)) < 1e-15
+
+
+def test_patch_mse_vs_plain_loops():
+    res, ph, pw, C = [(4, 6), (2, 2)], 2, 2, 2
+    a, b = _mse_images(5, res, C), _mse_images(6, res, C)
+    got = oc.patch_mse(a, b, ph, pw)
+    order = sorted(range(len(res)), key=lambda i: (res[i], i))
+    k = 0
+    for i in order:
+        for r in range(res[i][0] // ph):
+            for c in range(res[i][1] // pw):
+                acc = 0.0
+                for ch in range(C):
+                    for y in range(ph):
+                        for x in range(pw):
+                            d = float(a[i][ch, r * ph + y, c * pw + x]) - float(b[i][ch, r * ph + y, c * pw + x])
+                            acc += d * d
+                assert abs(got[k] - acc / (ph * pw * C)) < 1e-12
+                k += 1
+    assert k == len(got)
+
+
+def _read_sets_golden():
+    out = {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "cache_sets_tiny.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        key, *vals = line.split()
+        out[key] = [int(v) for v in vals]
+    return out
+
+
+def test_cache_sets_vs_hand_derived_example():
+    """Section "Batching Patches in Cache": Common / New / Expired sets."""
+    g = _read_sets_golden()
+    old_res = list(zip(g["old_res"][0::2], g["old_res"][1::2]))
+    new_res = list(zip(g["new_res"][0::2], g["new_res"][1::2]))
+    got = oc.cache_sets(old_res, g["old_ids"], new_res, g["new_ids"], 2, 2)
+    assert got["req_src"].tolist() == g["req_src"]
+    assert got["expired"].tolist() == g["expired"]
+    assert got["patch_src"].tolist() == g["patch_src"]
+
+
+def test_cache_sets_invariants():
+    rng = np.random.default_rng(1)
+    sizes = [(4, 4), (8, 4), (8, 8)]
+    old_ids = [int(v) for v in rng.permutation(40)[:9]]
+    old_res = [sizes[int(rng.integers(3))] for _ in old_ids]
+    keep = [i for i in range(9) if rng.random() < 0.6]
+    new_ids = [old_ids[i] for i in keep] + [100, 101, 102]
+    new_res = [old_res[i] for i in keep] + [sizes[0], sizes[2], sizes[1]]
+    order = rng.permutation(len(new_ids))
+    new_ids = [new_ids[i] for i in order]
+    new_res = [new_res[i] for i in order]
+    got = oc.cache_sets(old_res, old_ids, new_res, new_ids, 4, 4)
+    # same batch twice: everything is common and the patch table is the identity
+    same = oc.cache_sets(old_res, old_ids, old_res, old_ids, 4, 4)
+    assert same["patch_src"].tolist() == list(range(len(same["patch_src"]))) and not same["expired"].any()
+    # counts: common requests = kept ones; sources are distinct old patches; expired = not kept
+    assert int((got["req_src"] >= 0).sum()) == len(keep)
+    src = got["patch_src"][got["patch_src"] >= 0]
+    assert len(set(src.tolist())) == len(src)
+    assert got["expired"].tolist() == [0 if i in keep else 1 for i in range(9)]
+    # a migrated slot holds, for a common patch, the old patch's rows
+    S, C = 16, 2
+    old_slot = rng.standard_normal((len(same["patch_src"]) * S, C))
+    fill = np.zeros((len(got["patch_src"]) * S, C))
+    new_slot = oc.migrate(old_slot, got["patch_src"], S, fill)
+    for p, q in enumerate(got["patch_src"]):
+        want = old_slot[q * S:(q + 1) * S] if q >= 0 else 0.0
+        assert np.array_equal(new_slot[p * S:(p + 1) * S], want + np.zeros((S, C)))
