@@ -170,6 +170,33 @@ def main():
     torch.cuda.synchronize()
     block_ms = e0.elapsed_time(e1) / args.steps
 
+    # cache-manager pieces (outside the step): the predictor's per-patch MSE feature, and with slots the migration of
+    # every slot to a cache of the same batch (all requests common)
+    extras = {}
+    if args.all_kernels:
+        def timed(fn, reps=20):
+            fn()
+            a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a0.record()
+            for _ in range(reps):
+                fn()
+            a1.record()
+            torch.cuda.synchronize()
+            return a0.elapsed_time(a1) / reps * 1e3
+        es = 2 if cfg.dtype == "bf16" else 4
+        us = timed(lambda: run.plan.patch_mse(run.x, y))
+        gbs = 2.0 * cfg.T * cfg.C * es / (us * 1e-6) / 1e9
+        extras["patch_mse"] = {"avg_us": us, "gbs": gbs, "frac_hbm": gbs / PEAK_HBM_GBS}
+        if w.reuse is not None:
+            ids = list(range(cfg.n))
+            _, _, src = run.plan.cache_sets(ids, run.plan, ids)
+            twin = ps.Cache(run.plan, run.block, True)
+            us = timed(lambda: twin.migrate_from(run.cache, src), reps=5)
+            n_slots = 1 + sum({"RES2": 1, "SATTN": 3}.get(s, 0) for s in cfg.stages)
+            gbs = 2.0 * n_slots * cfg.T * cfg.C * es / (us * 1e-6) / 1e9
+            extras["cache_migrate"] = {"avg_us": us, "slots": n_slots, "gbs": gbs, "frac_hbm": gbs / PEAK_HBM_GBS}
+            twin.close()
+
     work = kernel_work(cfg, n_active)
     def entry(name, rec, steps_):
         avg_ms = rec["total_ms"] / rec["calls"]
@@ -241,6 +268,7 @@ def main():
     }
     if args.all_kernels:
         out["kernels"] = kernels
+        out["cache_manager"] = extras
     print(json.dumps(out))
 
 

@@ -173,6 +173,39 @@ int  pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* 
                           const pserve_block_t* weights, pserve_cache_t* cache,
                           const uint8_t* reuse_mask, void* y, void* stream);
 
+/* ---- cache manager pieces around the block ("Patch-aware Caching Strategy", "Batching Patches in Cache").
+ *
+ * pserve_patch_mse: the feature the cache reuse predictor compares per patch (step 1 of "Patch-aware
+ * Caching Strategy": the new input against the cache of the previous step; the similarity metric named
+ * in the implementation section is the mean squared error).  a, b: DEVICE [T][C] patch batches of the
+ * plan (dtype as above); out: DEVICE float [P], out[p] = mean over the S*C elements of patch p of
+ * (a - b)^2, accumulated in fp32 per thread and in a fixed order across threads (deterministic).
+ * Errors: EINVAL (NULL, C not a multiple of 8 (bf16) / 4 (fp32), C > 8192), EHIP.
+ *
+ * pserve_cache_sets: id bookkeeping when the batch composition changes between steps.  Every patch has
+ * the unique id (request id, patch row, patch column); comparing the ids of the new batch with the ids
+ * the cache holds gives the Common Set (in both), the New Set (only in the new batch) and the Expired
+ * Set (only in the cache).  old_ids / new_ids: HOST int64 [n], unique per batch, CALLER order of the
+ * respective plan.  Outputs: req_src HOST int32 [n_new] = caller index of the same request in the old
+ * batch or -1 (New Set); expired HOST uint8 [n_old] = 1 for the Expired Set; patch_src DEVICE int32
+ * [P_new] (plan order) = old plan's patch with the same id or -1.  Either host output may be NULL.
+ * The call synchronises `stream` (one small host->device copy).
+ * Errors: EINVAL (NULL, duplicate ids, different patch sizes, a common request with another resolution).
+ *
+ * pserve_cache_migrate: the coalesced insert of the Common Set into the cache of the new batch: every
+ * slot of new_cache takes, for each new patch p with patch_src[p] >= 0, the rows of old patch
+ * patch_src[p] of the same slot of old_cache (bit-exact copies, one launch per slot); other patches are
+ * left as they are and must be computed (mask 0) in the next pserve_block_forward.  valid: DEVICE uint8
+ * [P_new] or NULL, set to patch_src[p] >= 0.  Both caches must have slots and belong to the same block.
+ * Errors: EINVAL, ESTATE (old cache never filled). */
+int  pserve_patch_mse(const pserve_plan_t* plan, const void* a, const void* b, int32_t C, int dtype,
+                      float* out, void* stream);
+int  pserve_cache_sets(const pserve_plan_t* old_plan, const int64_t* old_ids, const pserve_plan_t* new_plan,
+                       const int64_t* new_ids, int32_t* req_src, uint8_t* expired, int32_t* patch_src,
+                       void* stream);
+int  pserve_cache_migrate(const pserve_cache_t* old_cache, pserve_cache_t* new_cache, const int32_t* patch_src,
+                          uint8_t* valid, void* stream);
+
 /* Kernel selection for measurements and tests: 0 = fastest path available for the
  * shapes (MFMA kernels where they apply), 1 = plain reference kernels only. */
 int  pserve_set_kernel_mode(int mode);

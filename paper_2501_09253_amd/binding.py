@@ -94,6 +94,10 @@ def lib() -> C.CDLL:
     L.pserve_set_kernel_mode.argtypes = [C.c_int]
     L.pserve_profile_enable.argtypes = [C.c_int]
     L.pserve_profile_select.argtypes = [C.c_char_p]
+    L.pserve_patch_mse.argtypes = [vp, vp, vp, i32, C.c_int, vp, vp]
+    L.pserve_cache_sets.argtypes = [vp, C.POINTER(C.c_int64), vp, C.POINTER(C.c_int64), C.POINTER(i32),
+                                    C.POINTER(C.c_uint8), vp, vp]
+    L.pserve_cache_migrate.argtypes = [vp, vp, vp, vp, vp]
     L.pserve_profile_read.argtypes = [C.POINTER(_ProfEntry), i32, C.POINTER(i32)]
     _lib = L
     return L
@@ -192,6 +196,30 @@ class Plan:
         _check(lib().pserve_reassemble(self._h, y.data_ptr(), Cc, dt, ptrs, _stream()))
         return images
 
+    def patch_mse(self, a, b):
+        """pserve_patch_mse: per-patch mean squared error of two patch batches [T, C] -> float32 [P] (plan order)."""
+        import torch
+        assert a.shape == b.shape and a.dtype == b.dtype and a.is_contiguous() and b.is_contiguous() and a.shape[0] == self.T
+        out = torch.empty(self.P, dtype=torch.float32, device=a.device)
+        dt = BF16 if a.dtype == torch.bfloat16 else F32
+        _check(lib().pserve_patch_mse(self._h, a.data_ptr(), b.data_ptr(), a.shape[1], dt, out.data_ptr(), _stream()))
+        return out
+
+    def cache_sets(self, ids, old_plan: "Plan", old_ids):
+        """pserve_cache_sets with this plan as the new batch: returns (req_src, expired, patch_src device tensor)."""
+        import torch
+        new_ids = np.ascontiguousarray(np.asarray(ids, dtype=np.int64))
+        prev_ids = np.ascontiguousarray(np.asarray(old_ids, dtype=np.int64))
+        assert new_ids.shape == (self.n,) and prev_ids.shape == (old_plan.n,)
+        req_src = np.empty(self.n, dtype=np.int32)
+        expired = np.empty(old_plan.n, dtype=np.uint8)
+        patch_src = torch.empty(self.P, dtype=torch.int32, device="cuda")
+        _check(lib().pserve_cache_sets(old_plan._h, prev_ids.ctypes.data_as(C.POINTER(C.c_int64)), self._h,
+                                       new_ids.ctypes.data_as(C.POINTER(C.c_int64)),
+                                       req_src.ctypes.data_as(C.POINTER(C.c_int32)),
+                                       expired.ctypes.data_as(C.POINTER(C.c_uint8)), patch_src.data_ptr(), _stream()))
+        return req_src, expired, patch_src
+
     def close(self):
         if self._h:
             lib().pserve_plan_free(self._h)
@@ -256,6 +284,14 @@ class Cache:
         dst = torch.empty((self.plan.T, self.block.C), dtype=_torch_dtype(self.block.dtype), device="cuda")
         _check(lib().pserve_cache_read(self._h, stage, slot, dst.data_ptr(), _stream()))
         return dst
+
+    def migrate_from(self, old_cache: "Cache", patch_src):
+        """pserve_cache_migrate: take the Common Set's slots from the cache of the previous batch; returns valid[P]."""
+        import torch
+        assert patch_src.dtype == torch.int32 and patch_src.numel() == self.plan.P and patch_src.is_contiguous()
+        valid = torch.empty(self.plan.P, dtype=torch.uint8, device="cuda")
+        _check(lib().pserve_cache_migrate(old_cache._h, self._h, patch_src.data_ptr(), valid.data_ptr(), _stream()))
+        return valid
 
     def forward(self, x, ctx=None, reuse_mask=None, y=None):
         """pserve_block_forward on the current torch stream; returns y[T, C]."""

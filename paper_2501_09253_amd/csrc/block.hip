@@ -102,6 +102,32 @@ __global__ void copy_patches_kernel(const uint4* __restrict__ src, uint4* __rest
     for (int64_t i = blockIdx.y * blockDim.x + threadIdx.x; i < vec_per_patch; i += (int64_t)gridDim.y * blockDim.x) d[i] = s[i];
 }
 
+// Coalesced insert of the Common Set into another batch's cache ("Batching Patches in Cache"): new patch p takes the
+// rows of old patch src_of[p] (token-major slot, 16 bytes per thread); patches with src_of[p] < 0 are left alone.
+__global__ void gather_patches_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int64_t vec_per_patch,
+                                      const int32_t* __restrict__ src_of) {
+    const int p = blockIdx.x, q = src_of[p];
+    if (q < 0) return;
+    const uint4* s = src + (int64_t)q * vec_per_patch;
+    uint4* d = dst + (int64_t)p * vec_per_patch;
+    for (int64_t i = blockIdx.y * blockDim.x + threadIdx.x; i < vec_per_patch; i += (int64_t)gridDim.y * blockDim.x) d[i] = s[i];
+}
+// The same for a channel-major slot (V^T [C][T]): per channel row, the S tokens of the patch are contiguous.
+template <typename T>
+__global__ void gather_patch_cols_kernel(const T* __restrict__ src, T* __restrict__ dst, int64_t T_old, int64_t T_new,
+                                         int32_t S, int32_t C, const int32_t* __restrict__ src_of) {
+    const int p = blockIdx.x, q = src_of[p];
+    if (q < 0) return;
+    for (int64_t i = blockIdx.y * blockDim.x + threadIdx.x; i < (int64_t)S * C; i += (int64_t)gridDim.y * blockDim.x) {
+        const int64_t c = i / S, t = i - c * S;
+        dst[c * T_new + (int64_t)p * S + t] = src[c * T_old + (int64_t)q * S + t];
+    }
+}
+__global__ void patch_valid_kernel(const int32_t* __restrict__ src_of, int32_t P, uint8_t* __restrict__ valid) {
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p < P) valid[p] = src_of[p] >= 0 ? 1 : 0;
+}
+
 // dst[c][t] = src[t][c] (or the reverse), used by the cache load/read hooks for the transposed V slot
 template <typename T>
 __global__ void transpose_tc_kernel(const T* __restrict__ src, T* __restrict__ dst, int64_t Tn, int32_t C, int to_ct) {
@@ -430,6 +456,54 @@ int pserve_cache_read(const pserve_cache_t* cache, int stage, int slot, void* ds
     PS_TRY(slot_ptr(cache, stage, slot, &p, &tr));
     PS_REQUIRE(dst, "pserve_cache_read: dst is NULL");
     return slot_copy(cache, p, tr, dst, false, (hipStream_t)stream);
+}
+
+int pserve_cache_migrate(const pserve_cache_t* old_cache, pserve_cache_t* new_cache, const int32_t* patch_src,
+                         uint8_t* valid, void* stream) {
+    PS_REQUIRE(old_cache && new_cache && patch_src, "pserve_cache_migrate: NULL argument");
+    PS_REQUIRE(old_cache != new_cache, "pserve_cache_migrate: old and new cache are the same object");
+    PS_REQUIRE(old_cache->with_slots && new_cache->with_slots, "pserve_cache_migrate: both caches need slots");
+    PS_REQUIRE(old_cache->block == new_cache->block, "pserve_cache_migrate: the caches belong to different blocks");
+    PS_REQUIRE(old_cache->plan->ph == new_cache->plan->ph && old_cache->plan->pw == new_cache->plan->pw,
+               "pserve_cache_migrate: the two plans use different patch sizes");
+    PS_REQUIRE(old_cache->v_transposed == new_cache->v_transposed, "pserve_cache_migrate: the caches use different value layouts");
+    if (!old_cache->filled) { set_error("pserve_cache_migrate: the old cache was never filled"); return PSERVE_ESTATE; }
+    const pserve_block_desc& d = new_cache->block->desc;
+    hipStream_t st = (hipStream_t)stream;
+    const pserve_plan_t* pn = new_cache->plan;
+    const size_t es = dtype_size(d.dtype);
+    const int64_t vec_per_patch = (int64_t)pn->S * d.C * es / 16;
+    PS_REQUIRE(((int64_t)pn->S * d.C * es) % 16 == 0, "pserve_cache_migrate: a patch must be a multiple of 16 bytes");
+    const dim3 grid(pn->P, (unsigned)std::max<int64_t>(1, std::min<int64_t>(cdiv(vec_per_patch, 1024), 64)));
+    auto rows = [&](const void* src, void* dst) -> int {
+        if (!src || !dst) return PSERVE_OK;
+        gather_patches_kernel<<<grid, 256, 0, st>>>((const uint4*)src, (uint4*)dst, vec_per_patch, patch_src);
+        return check_launch("gather_patches_kernel");
+    };
+    for (int s = 0; s < d.n_stages; ++s) {
+        PS_TRY(rows(old_cache->h1[s], new_cache->h1[s]));
+        PS_TRY(rows(old_cache->r[s], new_cache->r[s]));
+        PS_TRY(rows(old_cache->k[s], new_cache->k[s]));
+        if (old_cache->v[s] && new_cache->v[s]) {
+            if (!new_cache->v_transposed) PS_TRY(rows(old_cache->v[s], new_cache->v[s]));
+            else {
+                if (d.dtype == PSERVE_BF16)
+                    gather_patch_cols_kernel<uint16_t><<<grid, 256, 0, st>>>((const uint16_t*)old_cache->v[s], (uint16_t*)new_cache->v[s],
+                                                                             old_cache->plan->T, pn->T, pn->S, d.C, patch_src);
+                else
+                    gather_patch_cols_kernel<float><<<grid, 256, 0, st>>>((const float*)old_cache->v[s], (float*)new_cache->v[s],
+                                                                          old_cache->plan->T, pn->T, pn->S, d.C, patch_src);
+                PS_TRY(check_launch("gather_patch_cols_kernel"));
+            }
+        }
+    }
+    PS_TRY(rows(old_cache->yslot, new_cache->yslot));
+    if (valid) {
+        patch_valid_kernel<<<(unsigned)cdiv(pn->P, 256), 256, 0, st>>>(patch_src, pn->P, valid);
+        PS_TRY(check_launch("patch_valid_kernel"));
+    }
+    new_cache->filled = true;
+    return PSERVE_OK;
 }
 
 int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* ctx, const pserve_block_t* block,

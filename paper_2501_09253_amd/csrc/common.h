@@ -85,5 +85,6 @@ struct pserve_plan_s {
     int64_t tab_count[PSERVE_TAB_COUNT] = {};
     int32_t* d_sorted_hw = nullptr;             // [n][2] (H, W) of sorted slot s
     std::vector<int32_t> h_sorted_hw;
+    float* mse_partial = nullptr;               // [P][16] scratch of pserve_patch_mse
     pserve::DevicePool pool;
 };

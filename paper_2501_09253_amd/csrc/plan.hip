@@ -318,6 +318,7 @@ int pserve_plan(const int32_t* res, int32_t n, int32_t ph, int32_t pw, void* str
     cnt[PSERVE_TAB_CU_SEQLENS] = n + 1;
     for (int t = 0; t < PSERVE_TAB_COUNT; ++t) PS_TRY(pl->pool.alloc_t(&pl->d_tab[t], (size_t)cnt[t]));
     PS_TRY(pl->pool.alloc_t(&pl->d_sorted_hw, (size_t)2 * n));
+    PS_TRY(pl->pool.alloc_t(&pl->mse_partial, (size_t)P * 16));
 
     hipStream_t st = (hipStream_t)stream;
     PS_CHECK_HIP(hipMemcpyAsync(pl->d_sorted_hw, pl->h_sorted_hw.data(), sizeof(int32_t) * 2 * n, hipMemcpyHostToDevice, st));

@@ -1,0 +1,109 @@
+"""GPU parity of the cache-manager pieces (through the C ABI) against oracle/cache.py.
+
+Bars: id sets, patch source table and migrated slots bit-exact; per-patch MSE (fp32 accumulation against the
+fp64 oracle) within 2e-5 * max|ref|.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2501_09253_amd as ps
+import workloads as wl
+from oracle import cache as oc
+from oracle import plan as op
+from harness import GpuRun, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+def _images(seed, res, C, dtype):
+    imgs = [wl.Stream(seed, f"i{k}").normal((C, h, w)) for k, (h, w) in enumerate(res)]
+    return [wl.bf16_round(a) for a in imgs] if dtype == "bf16" else imgs
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("res,ph,pw,C", [([(16, 16), (8, 24), (8, 8)], 8, 8, 64),          # one wavefront row
+                                         ([(32, 32), (64, 32)], 32, 32, 320),              # 40 channel vectors: ragged block
+                                         ([(12, 20), (4, 4)], 4, 4, 8),                    # tiny patches, chunks of one token
+                                         ([(6, 10)], 6, 10, 1024)])                        # wide rows, odd token count
+def test_patch_mse(res, ph, pw, C, dtype):
+    a, b = _images(21, res, C, dtype), _images(22, res, C, dtype)
+    b[0][:, :ph, :pw] = a[0][:, :ph, :pw]                  # one patch identical: exactly 0
+    plan = ps.Plan(res, ph, pw)
+    xa, xb = plan.split([to_dev(t, dtype) for t in a]), plan.split([to_dev(t, dtype) for t in b])
+    got = plan.patch_mse(xa, xb).cpu().numpy().astype(np.float64)
+    ref = oc.patch_mse(a, b, ph, pw)
+    assert got.shape == ref.shape
+    assert np.abs(got - ref).max() <= 2e-5 * np.abs(ref).max()
+    zero = [p for p in range(plan.P) if ref[p] == 0.0]
+    assert len(zero) == 1 and got[zero[0]] == 0.0
+    again = plan.patch_mse(xa, xb).cpu().numpy()           # fixed summation order: bit-identical on a second call
+    assert np.array_equal(again.astype(np.float64), got)
+
+
+def test_patch_mse_config2_size():
+    cfg = wl.config(2)
+    a, b = _images(23, cfg.resolutions, cfg.C, "bf16"), _images(24, cfg.resolutions, cfg.C, "bf16")
+    plan = ps.Plan(cfg.resolutions, *cfg.patch)
+    got = plan.patch_mse(plan.split([to_dev(t, "bf16") for t in a]), plan.split([to_dev(t, "bf16") for t in b]))
+    ref = oc.patch_mse(a, b, *cfg.patch)
+    assert np.abs(got.cpu().numpy() - ref).max() <= 2e-5 * np.abs(ref).max()
+
+
+SETS_CASES = [
+    # (old resolutions, old ids, new resolutions, new ids)
+    ([(16, 16), (8, 8), (8, 16)], [7, 3, 9], [(8, 8), (16, 8), (16, 16)], [3, 5, 7]),
+    ([(8, 8)] * 5, [1, 2, 3, 4, 5], [(8, 8)] * 5, [5, 4, 3, 2, 1]),                        # same set, other arrival order
+    ([(16, 16), (8, 8)], [10, 11], [(8, 16), (24, 8)], [12, 13]),                           # nothing in common
+    ([(16, 8), (8, 8), (16, 8)], [2**40, -5, 0], [(16, 8), (16, 8), (8, 8), (8, 8)], [0, 2**40, 6, -5]),
+]
+
+
+@pytest.mark.parametrize("res_old,ids_old,res_new,ids_new", SETS_CASES)
+def test_cache_sets_bit_exact(res_old, ids_old, res_new, ids_new):
+    old, new = ps.Plan(res_old, 8, 8), ps.Plan(res_new, 8, 8)
+    req_src, expired, patch_src = new.cache_sets(ids_new, old, ids_old)
+    ref = oc.cache_sets(res_old, ids_old, res_new, ids_new, 8, 8)
+    assert np.array_equal(req_src, ref["req_src"])
+    assert np.array_equal(expired, ref["expired"])
+    assert np.array_equal(patch_src.cpu().numpy(), ref["patch_src"])
+
+
+def test_cache_sets_rejects_bad_input():
+    old, new = ps.Plan([(8, 8), (16, 8)], 8, 8), ps.Plan([(8, 8), (8, 8)], 8, 8)
+    with pytest.raises(ps.PserveError):
+        new.cache_sets([1, 1], old, [1, 2])                 # duplicate id
+    with pytest.raises(ps.PserveError):
+        new.cache_sets([2, 3], old, [1, 2])                 # id 2 was 16x8, now 8x8
+    other = ps.Plan([(8, 8), (8, 8)], 4, 4)
+    with pytest.raises(ps.PserveError):
+        other.cache_sets([1, 2], old, [1, 2])               # different patch size
+
+
+@pytest.mark.parametrize("dtype,heads", [("f32", 2), ("bf16", 1)])      # bf16 with head dim 64: V is kept transposed
+def test_cache_migrate_bit_exact(dtype, heads):
+    res_old, ids_old = [(16, 16), (8, 8), (8, 16)], [7, 3, 9]
+    res_new, ids_new = [(8, 8), (16, 8), (16, 16)], [3, 5, 7]
+    stages = (wl.RES2, wl.SATTN)
+    cfg_o = wl.custom_config(res_old, (8, 8), C=64, G=8, heads=heads, stages=stages, dtype=dtype, seed=5)
+    cfg_n = wl.custom_config(res_new, (8, 8), C=64, G=8, heads=heads, stages=stages, dtype=dtype, seed=5)
+    w_o, w_n = wl.make_workload(cfg_o), wl.make_workload(cfg_n)
+    run_o = GpuRun(w_o, with_slots=True)
+    cache_n = ps.Cache(ps.Plan(res_new, 8, 8), run_o.block, True)
+    plan_n = cache_n.plan
+    slots = [(0, ps.SLOT_H1), (1, ps.SLOT_R), (1, ps.SLOT_K), (1, ps.SLOT_V), (-1, ps.SLOT_Y)]
+    S, C = 64, 64
+    rnd = lambda seed, T: wl.bf16_round(wl.Stream(seed, "slot").normal((T, C)))
+    old_t, fill_t = {}, {}
+    for k, (st, sl) in enumerate(slots):
+        old_t[(st, sl)] = rnd(100 + k, run_o.plan.T)
+        fill_t[(st, sl)] = rnd(200 + k, plan_n.T)
+        run_o.cache.load(st, sl, to_dev(old_t[(st, sl)], dtype))
+        cache_n.load(st, sl, to_dev(fill_t[(st, sl)], dtype))
+    _, _, patch_src = plan_n.cache_sets(ids_new, run_o.plan, ids_old)
+    valid = cache_n.migrate_from(run_o.cache, patch_src)
+    ref = oc.cache_sets(res_old, ids_old, res_new, ids_new, 8, 8)
+    assert np.array_equal(valid.cpu().numpy(), (ref["patch_src"] >= 0).astype(np.uint8))
+    for key in slots:
+        got = to_host(cache_n.read(*key))
+        assert np.array_equal(got, oc.migrate(old_t[key], ref["patch_src"], S, fill_t[key])), key
