@@ -107,3 +107,49 @@ def test_cache_migrate_bit_exact(dtype, heads):
     for key in slots:
         got = to_host(cache_n.read(*key))
         assert np.array_equal(got, oc.migrate(old_t[key], ref["patch_src"], S, fill_t[key])), key
+
+
+@pytest.mark.parametrize("dtype,C,heads,G", [("f32", 32, 2, 4), ("bf16", 64, 1, 8)])
+def test_two_steps_across_a_batch_change(dtype, C, heads, G):
+    """Step 1 on one batch fills the cache; the batch changes (one request leaves, two arrive, order shuffled);
+    the Common Set's slots move to the new batch's cache; step 2 reuses some of those patches.  Against the
+    per-image oracle run on the same history."""
+    from oracle import block as ob
+    from harness import rel_err, tolerance
+    stages = (wl.RES2, wl.SATTN)
+    res_old, ids_old = [(16, 16), (8, 8), (8, 16)], [7, 3, 9]
+    res_new, ids_new = [(8, 8), (16, 8), (16, 16), (8, 8)], [3, 5, 7, 11]
+    cfg_o = wl.custom_config(res_old, (8, 8), C=C, G=G, heads=heads, stages=stages, dtype=dtype, seed=9)
+    w_o = wl.make_workload(cfg_o)
+    run_o = GpuRun(w_o, with_slots=True)
+    run_o.forward()                                                   # step 1: computes everything, fills every slot
+    # the oracle records its slots only on the reuse path: an all-compute mask over an (unused) empty cache
+    names = ["0.h1", "1.r", "1.K", "1.V", "y"]
+    none_1 = [np.zeros((h // 8, w // 8), dtype=bool) for h, w in res_old]
+    empty_1 = {k: [np.zeros((C, h, w)) for h, w in res_old] for k in names}
+    _, cache_1 = ob.forward_batch(w_o.images, stages, w_o.params, G=G, heads=heads, eps=cfg_o.eps, reuse=none_1,
+                                  cache=empty_1)
+
+    # step 2 inputs: fresh latents for every request of the new batch
+    imgs_n = _images(77, res_new, C, dtype)
+    plan_n = ps.Plan(res_new, 8, 8)
+    cache_n = ps.Cache(plan_n, run_o.block, True)
+    req_src, _, patch_src = plan_n.cache_sets(ids_new, run_o.plan, ids_old)
+    valid = cache_n.migrate_from(run_o.cache, patch_src)
+    rng = np.random.default_rng(3)
+    reuse, cache_2 = [], {k: [] for k in cache_1[0]}
+    for i, (h, w) in enumerate(res_new):
+        common = req_src[i] >= 0
+        reuse.append((rng.random((h // 8, w // 8)) < 0.5) if common else np.zeros((h // 8, w // 8), dtype=bool))
+        for k in cache_2:                                             # New requests: nothing cached, nothing reused
+            cache_2[k].append(cache_1[req_src[i]][k] if common else np.zeros((C, h, w)))
+    assert any(r.any() for r in reuse) and not all(r.all() for r in reuse)
+    # mask in plan order; it may only reuse patches the migration marked valid
+    owner, rc, perm = plan_n.table("patch_owner"), plan_n.table("patch_rc"), plan_n.table("perm")
+    mask = np.array([reuse[perm[owner[p]]][rc[p, 0], rc[p, 1]] for p in range(plan_n.P)], dtype=np.uint8)
+    assert not (mask & (1 - valid.cpu().numpy())).any()
+    x = plan_n.split([to_dev(t, dtype) for t in imgs_n])
+    y = cache_n.forward(x, None, torch.from_numpy(mask).cuda())
+    got = [to_host(t) for t in plan_n.reassemble(y)]
+    ref, _ = ob.forward_batch(imgs_n, stages, w_o.params, G=G, heads=heads, eps=cfg_o.eps, reuse=reuse, cache=cache_2)
+    assert rel_err(got, ref) < tolerance(dtype)
