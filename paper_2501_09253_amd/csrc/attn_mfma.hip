@@ -9,8 +9,8 @@
 // Scores are formed transposed, S^T = K Q^T, so that a lane owns one query column of each
 // 32x32 MFMA tile: the softmax row reductions are in-lane plus one exchange between the two
 // lane halves, and the probabilities leave the accumulators already in the layout of the
-// B operand of O^T = V^T P^T (keys of a 16-wide MFMA step are taken in the order the
-// accumulator holds them; V^T is read from LDS in the same order).  V is kept transposed in
+// B operand of O^T = V^T P^T (the MFMA rows are assigned to keys so that a lane's eight scores
+// of a 16-wide MFMA step are eight consecutive keys; V^T is read from LDS in the same order).  V is kept transposed in
 // memory ([C][tokens]) by the projection GEMM, so both K and V^T tiles are plain 128-byte
 // rows.  Online softmax in base 2 (logits pre-scaled by log2(e)/sqrt(d)), fp32 statistics.
 //
@@ -29,7 +29,6 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 constexpr int ATT_BQ = 256;      // queries per block
 constexpr int ATT_BKV = 64;      // keys per step
 constexpr int ATT_D = 64;        // head dim
-constexpr float ATT_TAU = 8.f;   // the softmax reference moves when a shifted score exceeds this (p <= 2^8)
 
 // value of lane l^32 (v_permlane32_swap: upper half of the first operand <-> lower half of the second)
 __device__ __forceinline__ float other_half(float v) {

@@ -5,7 +5,9 @@
 //                     by direct global -> LDS loads into a ring of 2-3 stages (one barrier per step);
 //                     linear layers (one tap) and the fallback form of the convolution (nine taps re-load A).
 //   conv_mfma_kernel  3x3 convolution with the haloed activation tile kept in LDS across the nine taps;
-//                     preferred tile 256 x 160 with four wavefronts stacked along M; every LDS read and global load rides behind an MFMA.
+//                     preferred tile 256 x 160 with four wavefronts stacked along M.
+// In both, every LDS fragment read and every global load is issued behind an MFMA (a wavefront issues in order,
+// and with one block per CU there is no other wavefront on the SIMD to fill a bubble).
 // MFMA shape v_mfma_f32_32x32x16_bf16, fp32 accumulation.  LDS rows are 128 bytes (8 chunks of 16 bytes); chunk c of
 // row r sits at position c ^ ((r >> 1) & 7), which keeps the fragment reads (32 rows at one chunk position)
 // bank-conflict free; the swizzle is applied by choosing which global chunk each lane of a load fetches.

@@ -151,7 +151,7 @@ __device__ __forceinline__ float silu_f(float v) { return __fdividef(v, 1.f + __
 // it; where that neighbour is absent (image edge) the token zero-fills the matching ring slot of its OWN patch.
 // Every ring slot of every patch is written by exactly one thread, so there is no race and no extra pass.
 template <typename T>
-__device__ __forceinline__ void stitch_store(T* __restrict__ out, const int32_t* __restrict__ nb, const PatchGeom& gm,
+__device__ __forceinline__ void stitch_store(T* __restrict__ out, const int32_t (&nb)[8], const PatchGeom& gm,
                                              int p, int y, int x, int C, int coff, const float (&v)[Vec<T>::N]) {
     if (y != 0 && y != gm.ph - 1 && x != 0 && x != gm.pw - 1) return;
     float z[Vec<T>::N];
@@ -195,6 +195,9 @@ __global__ void gn_apply_kernel(const T* __restrict__ x, const float* __restrict
     const float* ss = scale_shift + ((int64_t)s * C + cv * VN) * 2;
 #pragma unroll
     for (int e = 0; e < VN; ++e) { sc[e] = ss[2 * e]; sh[e] = ss[2 * e + 1]; }
+    int32_t nb[8];                              // neighbour patches, read once (no dependent loads behind the stores)
+#pragma unroll
+    for (int k = 0; k < 8; ++k) nb[k] = (PADDED && STITCH) ? neighbour[8 * p + k] : -1;
     const T* base = x + ((int64_t)p * gm.S) * C + cv * VN;
     auto out_off = [&](int t) -> int64_t {
         if (PADDED) {
@@ -220,7 +223,7 @@ __global__ void gn_apply_kernel(const T* __restrict__ x, const float* __restrict
                 store_vec<T>(out + out_off(t) + cv * VN, v[u]);
                 if (PADDED && STITCH) {
                     const int y = t / gm.pw;
-                    stitch_store<T>(out, neighbour + 8 * p, gm, p, y, t - y * gm.pw, C, cv * VN, v[u]);
+                    stitch_store<T>(out, nb, gm, p, y, t - y * gm.pw, C, cv * VN, v[u]);
                 }
             }
         }
