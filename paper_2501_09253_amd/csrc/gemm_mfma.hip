@@ -420,6 +420,31 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
     if (a.act.active && m0 >= *a.act.count * a.geom.S) return;
     const int S = a.geom.S, pw = a.geom.pw, hw = pw + 2;
 
+    // one direct global->LDS load (64 lanes x 16 bytes) of the weight / halo stage
+#define PS_LOAD_B(dstB_, off_, i_) \
+    __builtin_amdgcn_global_load_lds((const void*)(b_ptr + (i_) * b_row32 + (off_)), (lds_void*)((dstB_) + (i_) * 256), 16, 0, 0)
+#define PS_LOAD_A(dstA_, off_, i_) \
+    __builtin_amdgcn_global_load_lds((const void*)(a_ptr[i_] + (off_)), (lds_void*)((dstA_) + (i_) * 256), 16, 0, 0)
+
+    // The weights of the first NSB steps go first: they need no table, and the index arithmetic below runs while
+    // they are in flight.  Thread rows lr + 32*i, chunk position lc; the lane fetches global chunk lc ^ f(row).
+    const int lc = lane & 7, lr = 8 * wave + (lane >> 3);
+    const int gc = lc ^ ((lr >> 1) & 7);
+    const uint16_t* B = (const uint16_t*)a.B;
+    const uint16_t* b_ptr = B + (int64_t)(n0 + lr) * a.K + gc * 8;
+    const int64_t b_row32 = (int64_t)32 * a.K;
+    const int64_t b_tap_stride = (int64_t)a.N * a.K;
+    const int kchunks = a.K / BK;
+    int itap = 0, ikc = 0;                          // (tap, chunk) of the next weight stage to issue; clamps at the last step
+#pragma unroll
+    for (int t = 0; t < NSB; ++t) {
+        u32x4* dB = sB + t * BSTAGE + wave * 64;
+        const int64_t off = itap * b_tap_stride + ikc * BK;
+#pragma unroll
+        for (int i = 0; i < B_LD; ++i) PS_LOAD_B(dB, off, i);
+        if (!(itap == 8 && ikc == kchunks - 1)) { if (++itap == 9) { itap = 0; ++ikc; } }
+    }
+
     // row -> token table and segment origins
     if (tid < BM) {
         const int ri = m0 + tid;
@@ -442,10 +467,7 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
     __syncthreads();
 
     // halo staging: slot sl = lr + 32*i (pixel slot), chunk position lc; lane fetches global chunk lc ^ f(slot)
-    const int lc = lane & 7, lr = 8 * wave + (lane >> 3);
-    const int gc = lc ^ ((lr >> 1) & 7);
     const uint16_t* A = (const uint16_t*)a.A;
-    const uint16_t* B = (const uint16_t*)a.B;
     const uint16_t* a_ptr[A_LD];
     const int apix = ct.nseg * ct.seg_pix;
 #pragma unroll
@@ -456,11 +478,11 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
         const int ly = l / hw, lx = l - ly * hw;
         a_ptr[i] = A + ((int64_t)s_seg[g] + ly * a.geom.ppw + lx) * a.lda + gc * 8;
     }
-    const uint16_t* b_ptr = B + (int64_t)(n0 + lr) * a.K + gc * 8;
-    const int64_t b_row32 = (int64_t)32 * a.K;
-    const int64_t b_tap_stride = (int64_t)a.N * a.K;
-    const int kchunks = a.K / BK;
-
+    {                                               // halo of chunk 0: in flight during the rest of the set-up
+        u32x4* dA = sA + wave * 64;
+#pragma unroll
+        for (int i = 0; i < A_LD; ++i) PS_LOAD_A(dA, 0, i);
+    }
     f32x16 acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -469,11 +491,6 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    // one direct global->LDS load (64 lanes x 16 bytes) of the weight / halo stage
-#define PS_LOAD_B(dstB_, off_, i_) \
-    __builtin_amdgcn_global_load_lds((const void*)(b_ptr + (i_) * b_row32 + (off_)), (lds_void*)((dstB_) + (i_) * 256), 16, 0, 0)
-#define PS_LOAD_A(dstA_, off_, i_) \
-    __builtin_amdgcn_global_load_lds((const void*)(a_ptr[i_] + (off_)), (lds_void*)((dstA_) + (i_) * 256), 16, 0, 0)
 
     const int fr = lane & 31, fh = lane >> 5;
     // halo slot of each fragment row for tap (0, 0)
@@ -502,21 +519,6 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
         else if ((r_) < TM + TN) fa[dst][ia_] = __builtin_bit_cast(bf16x8, (stA_)[cur_[ia_] * CH + (c_ ^ sw_[ia_])]); \
     }
 
-    // prologue: halo of chunk 0 and the weights of the first NSB steps
-    {
-        u32x4* dA = sA + wave * 64;
-#pragma unroll
-        for (int i = 0; i < A_LD; ++i) PS_LOAD_A(dA, 0, i);
-    }
-    int itap = 0, ikc = 0;                          // (tap, chunk) of the next weight stage to issue; clamps at the last step
-#pragma unroll
-    for (int t = 0; t < NSB; ++t) {
-        u32x4* dB = sB + t * BSTAGE + wave * 64;
-        const int64_t off = itap * b_tap_stride + ikc * BK;
-#pragma unroll
-        for (int i = 0; i < B_LD; ++i) PS_LOAD_B(dB, off, i);
-        if (!(itap == 8 && ikc == kchunks - 1)) { if (++itap == 9) { itap = 0; ++ikc; } }
-    }
     constexpr int NM = TM * TN;                     // MFMAs per 16-wide sub-step
     constexpr int NR = TM + TN;                     // fragment reads per sub-step
     constexpr int R_PER = (NR + NM - 1) / NM;       // fragment reads slipped in behind one MFMA
