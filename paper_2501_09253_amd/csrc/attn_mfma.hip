@@ -184,9 +184,14 @@ attn_mfma_kernel(AttnArgs a) {
         bf16x8 fk_[4], fv_[2][2];                                                                                \
         _Pragma("unroll") for (int ks = 0; ks < 4; ++ks)                                                         \
             fk_[ks] = __builtin_bit_cast(bf16x8, sK[(ST) * 512 + krow[KT] * 8 + ((2 * ks + fh) ^ ksw[KT])]);     \
-        _Pragma("unroll") for (int ks = 0; ks < 4; ++ks)                                                         \
+        /* first step: D = K Q^T + (-m_ref) written as the three-address instruction, so that the -m_ref tile is */    \
+        /* read in place (the builtin form made the compiler copy it back and forth: 64 moves per key tile)      */    \
+        _Pragma("unroll") for (int qt = 0; qt < 2; ++qt)                                                         \
+            asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3"                                               \
+                         : "=&v"(acc_s[qt]) : "v"(fk_[0]), "v"(fq[qt][0]), "v"(cinit[qt]));                      \
+        _Pragma("unroll") for (int ks = 1; ks < 4; ++ks)                                                         \
             _Pragma("unroll") for (int qt = 0; qt < 2; ++qt)                                                     \
-                acc_s[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk_[ks], fq[qt][ks], ks == 0 ? cinit[qt] : acc_s[qt], 0, 0, 0); \
+                acc_s[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk_[ks], fq[qt][ks], acc_s[qt], 0, 0, 0);    \
         __builtin_amdgcn_sched_barrier(0);                                                                       \
         _Pragma("unroll") for (int k2 = 0; k2 < 2; ++k2)                                                         \
             _Pragma("unroll") for (int dt = 0; dt < 2; ++dt)                                                     \
