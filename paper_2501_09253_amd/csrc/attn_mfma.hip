@@ -216,7 +216,7 @@ attn_mfma_kernel(AttnArgs a) {
                 l_run[qt] *= corr_;                                                                              \
                 _Pragma("unroll") for (int dt = 0; dt < 2; ++dt)                                                 \
                     _Pragma("unroll") for (int e = 0; e < 16; ++e) acc_o[qt][dt][e] *= corr_;                    \
-                _Pragma("unroll") for (int e = 0; e < 16; ++e) cinit[qt][e] = -m_ref[qt];                        \
+                _Pragma("unroll") for (int e = 0; e < 16; ++e) cinit[qt][e] -= d_;    /* == -m_ref, in place */  \
                 PS_PROBS(qt, d_);                                                                                \
             }                                                                                                    \
             l_run[qt] += sum_;                                                                                   \
