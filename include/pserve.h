@@ -225,6 +225,9 @@ int  pserve_profile_enable(int on);
  * pair costs a few microseconds of stream time, so a throughput measurement that also wants one
  * kernel's duration times only that kernel.  Errors: EINVAL (label of 32 characters or more). */
 int  pserve_profile_select(const char* label);
+/* Time only every n-th pserve_block_forward call counted from this call (1 = every call): the sampled
+ * launches are bracketed exactly as above, the others run without events.  Errors: EINVAL (every < 1). */
+int  pserve_profile_sample(int every);
 int  pserve_profile_read(pserve_prof_entry* out, int32_t max, int32_t* count);
 
 #ifdef __cplusplus

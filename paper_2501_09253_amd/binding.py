@@ -94,6 +94,7 @@ def lib() -> C.CDLL:
     L.pserve_set_kernel_mode.argtypes = [C.c_int]
     L.pserve_profile_enable.argtypes = [C.c_int]
     L.pserve_profile_select.argtypes = [C.c_char_p]
+    L.pserve_profile_sample.argtypes = [C.c_int]
     L.pserve_patch_mse.argtypes = [vp, vp, vp, i32, C.c_int, vp, vp]
     L.pserve_cache_sets.argtypes = [vp, C.POINTER(C.c_int64), vp, C.POINTER(C.c_int64), C.POINTER(i32),
                                     C.POINTER(C.c_uint8), vp, vp]
@@ -131,6 +132,11 @@ def profile_enable(on: bool):
 def profile_select(label: Optional[str]):
     """Time only the kernels with this label; None = all kernels (pserve_profile_select)."""
     _check(lib().pserve_profile_select(None if not label else label.encode()))
+
+
+def profile_sample(every: int):
+    """Bracket the kernels of every n-th forward call only (pserve_profile_sample)."""
+    _check(lib().pserve_profile_sample(int(every)))
 
 
 def profile_read() -> Dict[str, Dict[str, float]]:

@@ -24,6 +24,8 @@ struct ProfRecord { const char* name; hipEvent_t start, stop; };
 struct Profiler {
     bool on = false;
     char only[32] = {0};                 // when not empty: the one kernel label that is timed
+    int every = 1;                       // time the kernels of every n-th pserve_block_forward call only
+    long tick = -1;                      // index of the current pserve_block_forward call
     std::vector<ProfRecord> recs;
     std::vector<hipEvent_t> pool;
     hipEvent_t get() {
@@ -39,6 +41,7 @@ struct ProfScope {
     hipEvent_t stop = nullptr;
     ProfScope(const char* name, hipStream_t s) : st(s) {
         if (!g_prof.on || (g_prof.only[0] && strcmp(g_prof.only, name) != 0)) return;
+        if (g_prof.every > 1 && g_prof.tick % g_prof.every != 0) return;
         hipEvent_t start = g_prof.get();
         stop = g_prof.get();
         if (!start || !stop) { stop = nullptr; return; }
@@ -207,6 +210,13 @@ int pserve_set_kernel_mode(int mode) {
 
 int pserve_profile_enable(int on) {
     g_prof.on = on != 0;
+    return PSERVE_OK;
+}
+
+int pserve_profile_sample(int every) {
+    PS_REQUIRE(every >= 1, "pserve_profile_sample: every must be at least 1");
+    g_prof.every = every;
+    g_prof.tick = -1;
     return PSERVE_OK;
 }
 
@@ -518,6 +528,7 @@ int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* c
         if (!cache->filled) { set_error("pserve_block_forward: reuse mask given but the cache was never filled"); return PSERVE_ESTATE; }
     }
     hipStream_t st = (hipStream_t)stream;
+    ++g_prof.tick;
     const int dt = d.dtype, mode = g_kernel_mode, C = d.C;
     const size_t es = dtype_size(dt);
     PatchGeom gm;
