@@ -268,6 +268,7 @@ def main():
                                + (f", reuse p={cfg.reuse_p} ({cfg.T - n_active} tokens reused)" if w.reuse is not None else ""),
                    "step": "split + block_forward + reassemble"},
         "block_forward_ms": block_ms, "block_tokens_per_s": cfg.T / (block_ms * 1e-3), "plan_us": plan_us,
+        "computed_tokens": n_active, "block_computed_tokens_per_s": n_active / (block_ms * 1e-3),
         "roofline": roofline, "cpu_baseline": cpu,
     }
     if args.all_kernels:
