@@ -30,7 +30,7 @@ MEASURED_TRAFFIC = {
 }
 
 
-def kernel_work(cfg, n_active_tokens):
+def kernel_work(cfg, n_active_tokens, patch=None):
     """Algorithmic work per LAUNCH of each kernel label: (flops, bytes).
 
     Units: tokens T (all patches) or computed tokens Ta; b = bytes per element; C channels.
@@ -45,9 +45,10 @@ def kernel_work(cfg, n_active_tokens):
     """
     b = 2 if cfg.dtype == "bf16" else 4
     C, T, Ta = cfg.C, cfg.T, n_active_tokens
-    ph, pw = cfg.patch
+    ph, pw = patch if patch is not None else cfg.patch
     ring = 2 * (pw + 2) + 2 * ph
     Pa = Ta // (ph * pw)
+    P = T // (ph * pw)
     frac = Ta / T
     F = cfg.ffn_mult * C
     attn = sum(4.0 * (h * w) * (h * w) * C for h, w in cfg.resolutions) * frac
@@ -63,7 +64,7 @@ def kernel_work(cfg, n_active_tokens):
         "attn_cross": (4.0 * cfg.ctx_len * C * Ta, b * 2.0 * C * Ta),
         "gn_stats": (0.0, 1.0 * b * C * T),
         "gn_apply": (0.0, 2.0 * b * C * Ta),
-        "gn_apply_stitch": (0.0, 2.0 * b * C * T + 1.0 * b * C * ring * cfg.P),
+        "gn_apply_stitch": (0.0, 2.0 * b * C * T + 1.0 * b * C * ring * P),
         "halo_gather": (0.0, 2.0 * b * C * ring * Pa),
         "reuse_copy": (0.0, 2.0 * b * C * T),
     }
@@ -75,6 +76,8 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (default: 2, the SDXL ResNet block)")
+    ap.add_argument("--patch", type=int, nargs=2, default=None, metavar=("PH", "PW"),
+                    help="patch size override for the patch-size sweep (not for reuse configs: the mask is per patch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket kernels with HIP events")
     ap.add_argument("--all-kernels", action="store_true", help="add every kernel's time and roofline fraction to the JSON")
@@ -94,18 +97,20 @@ def main():
     cfg = wl.config(args.config)
     w = wl.make_workload(cfg)
     t0 = time.perf_counter()
-    run = GpuRun(w)
+    assert args.patch is None or w.reuse is None, "--patch cannot be combined with a reuse mask"
+    run = GpuRun(w, patch=tuple(args.patch) if args.patch else None)
+    patch = (run.plan.ph, run.plan.pw)
     torch.cuda.synchronize()
     mask = None
     n_active = cfg.T
     if w.reuse is not None:
         run.load_cache()
         mask = run.plan_mask(w.reuse)
-        n_active = int((mask == 0).sum().item()) * cfg.patch[0] * cfg.patch[1]
+        n_active = int((mask == 0).sum().item()) * patch[0] * patch[1]
     # planner time (one-off per batch composition)
     tp = time.perf_counter()
     for _ in range(5):
-        p = ps.Plan(cfg.resolutions, *cfg.patch)
+        p = ps.Plan(cfg.resolutions, *patch)
         p.close()
     plan_us = (time.perf_counter() - tp) / 5 * 1e6
 
@@ -200,7 +205,7 @@ def main():
             extras["cache_migrate"] = {"avg_us": us, "slots": n_slots, "gbs": gbs, "frac_hbm": gbs / PEAK_HBM_GBS}
             twin.close()
 
-    work = kernel_work(cfg, n_active)
+    work = kernel_work(cfg, n_active, patch)
     def entry(name, rec, steps_):
         avg_ms = rec["total_ms"] / rec["calls"]
         fl, by = work.get(name, (0.0, 0.0))
@@ -264,7 +269,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"config{cfg.cfg_id} {cfg.name}: latents {sorted(set(cfg.resolutions))} x{cfg.n}, "
-                               f"patch {cfg.patch[0]}x{cfg.patch[1]}, P={cfg.P}, T={cfg.T}, C={cfg.C}, stages={'+'.join(cfg.stages)}"
+                               f"patch {patch[0]}x{patch[1]}, P={run.plan.P}, T={cfg.T}, C={cfg.C}, stages={'+'.join(cfg.stages)}"
                                + (f", reuse p={cfg.reuse_p} ({cfg.T - n_active} tokens reused)" if w.reuse is not None else ""),
                    "step": "split + block_forward + reassemble"},
         "block_forward_ms": block_ms, "block_tokens_per_s": cfg.T / (block_ms * 1e-3), "plan_us": plan_us,
