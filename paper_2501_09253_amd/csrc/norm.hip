@@ -55,6 +55,23 @@ __device__ __forceinline__ void store_vec<uint16_t>(uint16_t* p, const float (&v
     *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
+// 16 raw bytes of a row now, floats later: lets a kernel issue its row loads before loads it would otherwise wait for
+template <typename T>
+__device__ __forceinline__ void unpack_vec(const uint4& q, float (&v)[Vec<T>::N]);
+template <>
+__device__ __forceinline__ void unpack_vec<float>(const uint4& q, float (&v)[4]) {
+    v[0] = __uint_as_float(q.x); v[1] = __uint_as_float(q.y); v[2] = __uint_as_float(q.z); v[3] = __uint_as_float(q.w);
+}
+template <>
+__device__ __forceinline__ void unpack_vec<uint16_t>(const uint4& q, float (&v)[8]) {
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        v[2 * i] = __uint_as_float(w[i] << 16);
+        v[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+    }
+}
+
 constexpr int GN_U = 8;     // token rows a thread keeps in flight
 
 // thread (tl, cv): cv = channel vector (fixed channels for the whole kernel), tl = token lane
@@ -91,14 +108,21 @@ __global__ void gn_partial_kernel(const T* __restrict__ x, int32_t C, int32_t G,
         red[(TL + tl) * C + cv * VN + e] = s2[e];
     }
     __syncthreads();
+    // two short phases instead of one long serial loop per group: first the token lanes of every channel ...
+    for (int i = threadIdx.x; i < 2 * C; i += blockDim.x) {
+        const int which = i / C, c = i - which * C;
+        float a = 0.f;
+        for (int l = 0; l < TL; ++l) a += red[(which * TL + l) * C + c];
+        red[(which * TL) * C + c] = a;                  // lane 0's slot of this channel: no other thread touches it
+    }
+    __syncthreads();
+    // ... then the channels of every group (fixed order: deterministic)
     const int cg = C / G;
-    for (int g = threadIdx.x; g < G; g += blockDim.x) {
-        float a = 0.f, b = 0.f;
-        for (int l = 0; l < TL; ++l)
-            for (int c = g * cg; c < (g + 1) * cg; ++c) { a += red[l * C + c]; b += red[(TL + l) * C + c]; }
-        float* dst = partial + (((int64_t)p * nsplit + sp) * G + g) * 2;
-        dst[0] = a;
-        dst[1] = b;
+    for (int i = threadIdx.x; i < 2 * G; i += blockDim.x) {
+        const int g = i >> 1, which = i & 1;
+        float a = 0.f;
+        for (int c = g * cg; c < (g + 1) * cg; ++c) a += red[(which * TL) * C + c];
+        partial[(((int64_t)p * nsplit + sp) * G + g) * 2 + which] = a;
     }
 }
 
@@ -190,6 +214,16 @@ __global__ void gn_apply_kernel(const T* __restrict__ x, const float* __restrict
     const int sp = blockIdx.y;
     const int chunk = (gm.S + nsplit - 1) / nsplit;
     const int t0 = sp * chunk, t1 = min(gm.S, t0 + chunk);
+    // The row loads of the first batch go first: they depend on the patch only, while scale / shift hang on the
+    // owner table (two dependent loads).  Up to GN_U independent 16-byte loads in flight per thread; rows past the
+    // chunk re-read its last row and are skipped.
+    const T* base = x + ((int64_t)p * gm.S) * C + cv * VN;
+    uint4 raw[GN_U];
+    int tb = t0 + tl;
+    if (tb < t1) {
+#pragma unroll
+        for (int u = 0; u < GN_U; ++u) raw[u] = *reinterpret_cast<const uint4*>(base + (int64_t)min(tb + u * TL, t1 - 1) * C);
+    }
     const int s = owner[p];
     float sc[VN], sh[VN];
     const float* ss = scale_shift + ((int64_t)s * C + cv * VN) * 2;
@@ -198,7 +232,6 @@ __global__ void gn_apply_kernel(const T* __restrict__ x, const float* __restrict
     int32_t nb[8];                              // neighbour patches, read once (no dependent loads behind the stores)
 #pragma unroll
     for (int k = 0; k < 8; ++k) nb[k] = (PADDED && STITCH) ? neighbour[8 * p + k] : -1;
-    const T* base = x + ((int64_t)p * gm.S) * C + cv * VN;
     auto out_off = [&](int t) -> int64_t {
         if (PADDED) {
             const int y = t / gm.pw, xx = t - y * gm.pw;
@@ -206,11 +239,15 @@ __global__ void gn_apply_kernel(const T* __restrict__ x, const float* __restrict
         }
         return ((int64_t)p * gm.S + t) * C;
     };
-    // up to GN_U independent 16-byte loads in flight per thread; rows past the chunk re-read its last row and are skipped
-    for (int tb = t0 + tl; tb < t1; tb += GN_U * TL) {
+    for (; tb < t1; tb += GN_U * TL) {
         float v[GN_U][VN];
 #pragma unroll
-        for (int u = 0; u < GN_U; ++u) load_vec<T>(base + (int64_t)min(tb + u * TL, t1 - 1) * C, v[u]);
+        for (int u = 0; u < GN_U; ++u) unpack_vec<T>(raw[u], v[u]);
+        const int nxt = tb + GN_U * TL;
+        if (nxt < t1) {                         // next batch in flight while this one is finished
+#pragma unroll
+            for (int u = 0; u < GN_U; ++u) raw[u] = *reinterpret_cast<const uint4*>(base + (int64_t)min(nxt + u * TL, t1 - 1) * C);
+        }
 #pragma unroll
         for (int u = 0; u < GN_U; ++u) {
             const int t = tb + u * TL;
