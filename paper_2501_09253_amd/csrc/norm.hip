@@ -336,14 +336,20 @@ int gn_finalize(const GroupNormArgs& a, const PatchGeom& g, int dtype, int32_t s
     return check_launch("gn_finalize_kernel");
 }
 
+constexpr int APPLY_ROWS = 4;        // rows per thread of the apply pass (measured: 1-2 too many blocks, 6-8 too few)
+
 template <typename T>
 static void launch_apply(const GroupNormArgs& a, const PatchGeom& g, bool silu, bool padded, bool stitch, void* out,
                          ActiveList act, int CV, int TL, hipStream_t st) {
-    dim3 grid(g.P, a.nsplit);
+    // Own chunking (independent of the statistics pass): about APPLY_ROWS rows per thread.  Many short blocks are
+    // dispatched over time, so some load while others compute or store; with few long blocks every wavefront of
+    // the chip is in the same phase at once.
+    const int nsplit = (int)std::max<int64_t>(1, std::min<int64_t>(cdiv(g.S, (int64_t)APPLY_ROWS * TL), 65535));
+    dim3 grid(g.P, nsplit);
     const int nt = TL * CV;
 #define PS_APPLY(SI, PA, ST)                                                                                      \
     gn_apply_kernel<T, SI, PA, ST><<<grid, nt, 0, st>>>((const T*)a.x, a.scale_shift, a.owner, a.neighbour, g, a.C, \
-                                                        a.nsplit, TL, act, (T*)out)
+                                                        nsplit, TL, act, (T*)out)
     if (silu && padded && stitch) PS_APPLY(true, true, true);
     else if (padded && stitch) PS_APPLY(false, true, true);
     else if (silu && padded) PS_APPLY(true, true, false);
