@@ -94,7 +94,10 @@ def test_small_blocks(stages, dtype, mode):
 
 
 @pytest.mark.parametrize("C,res,patch", [(128, [(16, 16), (8, 24), (8, 8)], (8, 8)), (320, [(16, 32), (16, 16)], (16, 16)),
-                                         (64, [(12, 20), (4, 4)], (4, 4))])
+                                         (64, [(12, 20), (4, 4)], (4, 4)),
+                                         # ragged last M tile with 64-token patches (the convolution that also leaves the
+                                         # next norm's partial sums must skip the rows past the end): T = 192 and T = 320
+                                         (64, [(8, 8), (8, 16)], (8, 8)), (320, [(8, 8), (16, 16)], (8, 8))])
 @pytest.mark.parametrize("stages", [(wl.RES2,), (wl.SATTN, wl.XATTN, wl.FFN), (wl.RES1, wl.SATTN)])
 def test_mfma_shapes_bf16(stages, C, res, patch):
     """bf16 blocks whose widths take the MFMA kernels (C multiple of 64, head dim 64), ragged M tails included."""
