@@ -185,7 +185,17 @@ struct pserve_cache_s {
     int32_t* act_off = nullptr;               // [n+1] attention: computed patches before slot s
     int32_t* tile_off = nullptr;              // [n+1] attention: query tiles before slot s
     int32_t max_tiles = 0;
+    // The text key / value projection of the one cross-attention stage depends on ctx only: it runs on a stream of
+    // its own (default priority) beside the stages before it, forked and joined with events.
+    hipStream_t side = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    int side_stage = -1;
     DevicePool pool;
+    ~pserve_cache_s() {
+        if (ev_fork) (void)hipEventDestroy(ev_fork);
+        if (ev_join) (void)hipEventDestroy(ev_join);
+        if (side) (void)hipStreamDestroy(side);
+    }
 };
 
 static bool has_stage(const pserve_block_desc& d, int kind) {
@@ -408,6 +418,16 @@ int pserve_cache_create(const pserve_plan_t* plan, const pserve_block_t* block, 
     if (with_slots) PS_TRY(c->pool.alloc(&c->yslot, TC));
     PS_TRY(c->pool.alloc_t(&c->active, (size_t)plan->P));
     PS_TRY(c->pool.alloc_t(&c->count, 1));
+    {
+        int n_x = 0, at = -1;
+        for (int k = 0; k < d.n_stages; ++k) if (d.stages[k] == PSERVE_XATTN) { ++n_x; at = k; }
+        if (n_x == 1 && at > 0) {                  // something runs before it: worth a stream of its own
+            PS_CHECK_HIP(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
+            PS_CHECK_HIP(hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
+            PS_CHECK_HIP(hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming));
+            c->side_stage = at;
+        }
+    }
     guard.p = nullptr;
     *out = c;
     return PSERVE_OK;
@@ -599,6 +619,24 @@ int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* c
         return gemm(g, dt, mode, st);
     };
 
+    // text keys / values of every request (cross-attention): input ctx only
+    auto ctx_kv = [&](const StageWeights& w, hipStream_t s2) -> int {
+        GemmArgs gk = base_gemm(ctx, d.ctx_dim, d.ctx_dim, 2 * C, w.w[2], nullptr);
+        gk.tokens_are_rows = 0; gk.act = all; gk.M = plan->n * d.ctx_len; gk.seg_cols = C;
+        gk.row_group = d.ctx_len; gk.row_group_pad = cache->cross_ld;
+        const int64_t ctx_rows = (int64_t)plan->n * cache->cross_ld;
+        gk.seg[0].ptr = cache->kc; gk.seg[0].ld = C;
+        gk.seg[1].ptr = cache->vc; gk.seg[1].ld = cache->v_transposed ? ctx_rows : C; gk.seg[1].transposed = cache->v_transposed;
+        ProfScope ps("linear_ctx_kv", s2);
+        return gemm(gk, dt, mode, s2);
+    };
+    if (cache->side_stage >= 0) {                   // fork: the side stream starts where this call starts
+        PS_CHECK_HIP(hipEventRecord(cache->ev_fork, st));
+        PS_CHECK_HIP(hipStreamWaitEvent(cache->side, cache->ev_fork, 0));
+        PS_TRY(ctx_kv(block->sw[cache->side_stage], cache->side));
+        PS_CHECK_HIP(hipEventRecord(cache->ev_join, cache->side));
+    }
+
     const void* cur = x;
     for (int si = 0; si < d.n_stages; ++si) {
         const StageWeights& w = block->sw[si];
@@ -649,13 +687,8 @@ int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* c
             break;
         }
         case PSERVE_XATTN: {
-            GemmArgs gk = base_gemm(ctx, d.ctx_dim, d.ctx_dim, 2 * C, w.w[2], nullptr);   // text keys / values of every request
-            gk.tokens_are_rows = 0; gk.act = all; gk.M = plan->n * d.ctx_len; gk.seg_cols = C;
-            gk.row_group = d.ctx_len; gk.row_group_pad = cache->cross_ld;
-            const int64_t ctx_rows = (int64_t)plan->n * cache->cross_ld;
-            gk.seg[0].ptr = cache->kc; gk.seg[0].ld = C;
-            gk.seg[1].ptr = cache->vc; gk.seg[1].ld = cache->v_transposed ? ctx_rows : C; gk.seg[1].transposed = cache->v_transposed;
-            { ProfScope ps("linear_ctx_kv", st); PS_TRY(gemm(gk, dt, mode, st)); }
+            if (cache->side_stage == si) PS_CHECK_HIP(hipStreamWaitEvent(st, cache->ev_join, 0));     // join
+            else PS_TRY(ctx_kv(w, st));
             GemmArgs gq = base_gemm(cur, C, C, C, w.w[0], nullptr);
             gq.seg[0].ptr = cache->q; gq.seg[0].ld = C; gq.seg[0].scale = qscale;
             { ProfScope ps("linear_q", st); PS_TRY(gemm(gq, dt, mode, st)); }
