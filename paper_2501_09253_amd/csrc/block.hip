@@ -185,6 +185,7 @@ struct pserve_cache_s {
     int32_t* act_off = nullptr;               // [n+1] attention: computed patches before slot s
     int32_t* tile_off = nullptr;              // [n+1] attention: query tiles before slot s
     int32_t max_tiles = 0;
+    bool tiles_unmasked = false;              // act_off / tile_off hold the tiling of a call without mask
     // The text key / value projection of the one cross-attention stage depends on ctx only: it runs on a stream of
     // its own (default priority) beside the stages before it, forked and joined with events.
     hipStream_t side = nullptr;
@@ -568,9 +569,11 @@ int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* c
         act.active = cache->active;
         act.count = cache->count;
     }
-    if (cache->act_off) {
+    if (cache->act_off && (reuse_mask || !cache->tiles_unmasked)) {
+        // without a mask the query tiling depends on the plan only: built once and kept
         ProfScope ps("attn_tiles", st);
         PS_TRY(attention_tiles(request_offset, reuse_mask, plan->n, plan->S, cache->act_off, cache->tile_off, st));
+        cache->tiles_unmasked = reuse_mask == nullptr;
     }
     const ActiveList all{nullptr, nullptr};
     const float qscale = 1.4426950408889634f / sqrtf((float)(d.heads > 0 ? C / d.heads : 1));
