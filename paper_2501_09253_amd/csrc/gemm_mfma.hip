@@ -1,9 +1,10 @@
 // bf16 MFMA GEMM / implicit-GEMM 3x3 convolution for gfx950.
 //
 // Two kernels share one epilogue:
-//   gemm_mfma_kernel  block tile 128 x BN, four wavefronts 2 x 2, K in steps of 64, A and B tiles staged
-//                     by direct global -> LDS loads into a ring of 2-3 stages (one barrier per step);
-//                     linear layers (one tap) and the fallback form of the convolution (nine taps re-load A).
+//   gemm_mfma_kernel  block tile 256 x 160 / 256 x 128 (four wavefronts stacked along M) or 128 x BN (2 x 2), K in
+//                     steps of 64, A and B tiles staged by direct global -> LDS loads into a ring of 2-4 stages
+//                     (one barrier per step); linear layers (one tap) and the fallback form of the convolution
+//                     (nine taps re-load A).
 //   conv_mfma_kernel  3x3 convolution with the haloed activation tile kept in LDS across the nine taps;
 //                     preferred tile 256 x 160 with four wavefronts stacked along M.
 // In both, every LDS fragment read and every global load is issued behind an MFMA (a wavefront issues in order,
@@ -208,38 +209,54 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[B
 typedef __attribute__((address_space(3))) void lds_void;
 
 // LDS bytes of one kernel instance: NS stages of (BM + BN) rows x 128 bytes, plus the row -> token table
-template <int BM, int BN> struct GemmCfg {
+template <int BM, int BN, int NS> struct GemmCfg {
     static constexpr int STAGE = (BM + BN) * 128;
-    static constexpr int NS = (3 * STAGE + BM * 4 <= 160 * 1024) ? 3 : 2;
     static constexpr size_t LDS = (size_t)NS * STAGE + BM * sizeof(int32_t);
+    static_assert(LDS <= 160 * 1024, "ring does not fit the LDS");
 };
 
-template <int BM, int BN, bool GEGLU>
+// Block tile BM x BN, WGM x WGN wavefront grid (four wavefronts), ring of NS stages.
+// Step = 64 columns of K: 4 sub-steps of TM*TN MFMAs.  Every memory instruction rides behind an MFMA: during sub-steps
+// 0..2 the fragment reads of the next sub-step, during sub-step 3 the first fragments of the NEXT step and the refill
+// of this step's stage with step + NS.  The block barrier sits before sub-step 3: by then every wavefront has read all
+// of this step's fragments (its stage is free) and has seen its own loads of the next step land, NS - 2 further steps
+// still being in flight.
+template <int BM, int BN, bool GEGLU, int WGM, int WGN, int NS>
 __global__ void __launch_bounds__(256)
 gemm_mfma_kernel(GemmArgs a) {
     constexpr int BK = 64;
     constexpr int CH = BK / 8;                      // 16-byte chunks per row
-    constexpr int WM = BM / 2, WN = BN / 2;         // wavefront tile
+    constexpr int WM = BM / WGM, WN = BN / WGN;     // wavefront tile
     constexpr int TM = WM / 32, TN = WN / 32;       // 32x32 MFMA tiles per wavefront
     constexpr int A_LD = BM * CH / 256;             // 16-byte loads per thread and K step
     constexpr int B_LD = BN * CH / 256;
-    constexpr int NS = GemmCfg<BM, BN>::NS;         // LDS ring depth
+    constexpr int LD = A_LD + B_LD;
     constexpr int STAGE_V = (BM + BN) * CH;         // 16-byte slots per stage: A rows then B rows
-    static_assert(BM % 64 == 0 && BN % 64 == 0 && (BM * CH) % 256 == 0 && (BN * CH) % 256 == 0, "tile shape");
+    static_assert(WGM * WGN == 4 && WM % 32 == 0 && WN % 32 == 0 && (BM * CH) % 256 == 0 && (BN * CH) % 256 == 0 &&
+                  NS >= 2 && (NS - 1) * LD <= 63, "tile shape");
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     u32x4* ring = reinterpret_cast<u32x4*>(smem);                     // [NS][STAGE_V]
     int32_t* s_tok = reinterpret_cast<int32_t*>(ring + NS * STAGE_V); // [BM] output row of each tile row, -1 = none
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // scalar: LDS destinations of the loads are SGPR math
-    const int wm = wave >> 1, wn = wave & 1;
-    // XCD-aware tile order: block ids are dealt round-robin to the 8 XCDs, so all N tiles of one M tile get ids of
-    // the same residue mod 8 and consecutive slots: they run on one XCD back to back and share the A tile in its L2
+    const int wm = wave / WGN, wn = wave % WGN;
+    // XCD-aware tile order.  Block ids are dealt round-robin to the 8 XCDs (each with its own L2), so the blocks of one
+    // residue mod 8 run on one XCD in the order of their slot (id / 8), 32 at a time.  An XCD owns every 8th M tile;
+    // it takes them in groups of `gm` whose A panels together fit its L2, and walks a group M tile fastest, then N
+    // tile: the blocks in flight share `gm` A panels and a few B panels, A is fetched once and B once per group
+    // (N fastest, i.e. gm = 1, re-streams all of B for every M tile: 375 MB instead of 70 MB for a 5120 x 640 weight).
     const int n_tiles = a.N / BN, m_tiles = (a.M + BM - 1) / BM;
+    const int mx = (m_tiles + 7) >> 3;              // M tiles per XCD
+    const int64_t a_panel = (int64_t)BM * a.K * a.taps * 2;
+    const int gm = (int)max((int64_t)1, min((int64_t)mx, (int64_t)(2560 * 1024) / a_panel));
     const int slot = blockIdx.x >> 3;
-    const int m_tile = (slot / n_tiles) * 8 + (blockIdx.x & 7);
+    const int grp = slot / (gm * n_tiles), r_in = slot - grp * (gm * n_tiles);
+    const int gm_here = min(gm, mx - grp * gm);     // the last group may be short
+    const int n_tile = r_in / gm_here;
+    const int m_tile = (grp * gm + (r_in - n_tile * gm_here)) * 8 + (blockIdx.x & 7);
     if (m_tile >= m_tiles) return;
-    const int m0 = m_tile * BM, n0 = (slot % n_tiles) * BN;
+    const int m0 = m_tile * BM, n0 = n_tile * BN;
     if (a.tokens_are_rows && a.act.active && m0 >= *a.act.count * a.geom.S) return;
 
     // Staging by direct global -> LDS loads.  One wavefront instruction fills 64 consecutive 16-byte slots
@@ -285,6 +302,33 @@ gemm_mfma_kernel(GemmArgs a) {
     const int KT = a.taps * kchunks;
     const int64_t b_tap_stride = (int64_t)a.N * a.K;
 
+    // one direct global->LDS load (64 lanes x 16 bytes): l < A_LD an A row group, else a B row group
+#define PS_LOAD(dst_, a_off_, b_off_, l_)                                                                         \
+    {                                                                                                             \
+        if ((l_) < A_LD)                                                                                          \
+            __builtin_amdgcn_global_load_lds((const void*)(a_ptr[(l_) < A_LD ? (l_) : 0] + (a_off_)),             \
+                                             (lds_void*)((dst_) + (l_) * 256), 16, 0, 0);                         \
+        else if ((l_) < LD)                                                                                       \
+            __builtin_amdgcn_global_load_lds((const void*)(b_ptr + ((l_) - A_LD) * b_row32 + (b_off_)),           \
+                                             (lds_void*)((dst_) + BM * CH + ((l_) - A_LD) * 256), 16, 0, 0);      \
+    }
+    // global offsets of K step (tap, kc)
+#define PS_OFFSETS(tap_, kc_)                                                                                     \
+    const int ty_ = (tap_) / 3, tx_ = (tap_) - ty_ * 3;                                                           \
+    const int64_t a_off = (a.conv ? ((int64_t)ty_ * a.geom.ppw + tx_) * a.lda : 0) + (kc_) * BK;                  \
+    const int64_t b_off = (tap_) * b_tap_stride + (kc_) * BK;
+
+    int tap = 0, kc = 0, issued = 0;                // K step that is issued next (stays at the last one past the end:
+                                                    // it is fetched again into a free stage and never read)
+#pragma unroll
+    for (int st = 0; st < NS; ++st) {               // prologue: all NS stages in flight
+        PS_OFFSETS(tap, kc);
+        u32x4* dst = ring + st * STAGE_V + wave * 64;
+#pragma unroll
+        for (int l = 0; l < LD; ++l) PS_LOAD(dst, a_off, b_off, l);
+        if (++issued < KT) { if (++kc == kchunks) { kc = 0; ++tap; } } else { issued = KT - 1; }
+    }
+
     f32x16 acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -292,27 +336,6 @@ gemm_mfma_kernel(GemmArgs a) {
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-    // issue the loads of K step (tap_, kc_) into ring stage st_
-#define PS_ISSUE(st_, tap_, kc_)                                                                          \
-    {                                                                                                     \
-        const int ty_ = (tap_) / 3, tx_ = (tap_) - ty_ * 3;                                               \
-        const int64_t a_off_ = (a.conv ? ((int64_t)ty_ * a.geom.ppw + tx_) * a.lda : 0) + (kc_) * BK;     \
-        const int64_t b_off_ = (tap_) * b_tap_stride + (kc_) * BK;                                        \
-        u32x4* dst_ = ring + (st_) * STAGE_V + wave * 64;                                                 \
-        _Pragma("unroll") for (int i = 0; i < A_LD; ++i)                                                  \
-            __builtin_amdgcn_global_load_lds((const void*)(a_ptr[i] + a_off_), (lds_void*)(dst_ + i * 256), 16, 0, 0); \
-        _Pragma("unroll") for (int i = 0; i < B_LD; ++i)                                                  \
-            __builtin_amdgcn_global_load_lds((const void*)(b_ptr + i * b_row32 + b_off_),                 \
-                                             (lds_void*)(dst_ + BM * CH + i * 256), 16, 0, 0);            \
-    }
-
-    int tap = 0, kc = 0;                            // K step that is issued next
-#pragma unroll
-    for (int st = 0; st < NS - 1; ++st) {           // prologue: NS-1 stages in flight
-        PS_ISSUE(st, tap, kc);
-        if (st + 1 < KT) { if (++kc == kchunks) { kc = 0; ++tap; } }
-    }
 
     const int fr = lane & 31, fh = lane >> 5;       // fragment row within a 32-row tile, k half
     // LDS fragment slots of this lane: row*CH + ((2*ks + fh) ^ f(row))
@@ -323,62 +346,71 @@ gemm_mfma_kernel(GemmArgs a) {
     for (int j = 0; j < TN; ++j) { const int r = wn * WN + j * 32 + fr; fb_base[j] = BM * CH + r * CH; fb_sw[j] = (r >> 1) & 7; }
 
     bf16x8 fa[2][TM], fb[2][TN];                    // register double buffer of the MFMA fragments
-#define PS_READ_FRAGS(dst, stage_, ks_)                                                          \
-    {                                                                                            \
-        const int c_ = (ks_) * 2 + fh;                                                           \
-        _Pragma("unroll") for (int i = 0; i < TM; ++i)                                           \
-            fa[dst][i] = __builtin_bit_cast(bf16x8, (stage_)[fa_base[i] + (c_ ^ fa_sw[i])]);     \
-        _Pragma("unroll") for (int j = 0; j < TN; ++j)                                           \
-            fb[dst][j] = __builtin_bit_cast(bf16x8, (stage_)[fb_base[j] + (c_ ^ fb_sw[j])]);     \
+    // one fragment read (16 bytes per lane) of K sub-step ks_ into register set dst; r_ = 0: A tile 0, 1 .. TN: B tiles,
+    // TN+1 ..: the remaining A tiles (the order in which the MFMAs of a sub-step first need them)
+#define PS_READ_ONE(dst, stage_, ks_, r_)                                                                         \
+    {                                                                                                             \
+        const int c_ = (ks_) * 2 + fh;                                                                            \
+        const int jb_ = ((r_) >= 1 && (r_) <= TN) ? (r_) - 1 : 0;                                             \
+        const int ia_ = ((r_) > TN && (r_) < TM + TN) ? (r_) - TN : 0;                                        \
+        if ((r_) == 0) fa[dst][0] = __builtin_bit_cast(bf16x8, (stage_)[fa_base[0] + (c_ ^ fa_sw[0])]);           \
+        else if ((r_) <= TN) fb[dst][jb_] = __builtin_bit_cast(bf16x8, (stage_)[fb_base[jb_] + (c_ ^ fb_sw[jb_])]); \
+        else if ((r_) < TM + TN) fa[dst][ia_] = __builtin_bit_cast(bf16x8, (stage_)[fa_base[ia_] + (c_ ^ fa_sw[ia_])]); \
     }
 
     constexpr int NM = TM * TN;                     // MFMAs per 16-wide sub-step
-    constexpr int L_PER = (A_LD + B_LD + 4 * NM - 1) / (4 * NM);    // loads slipped in behind each MFMA
-    int rd = 0, wr = NS - 1;                        // ring stage read now / written next
+    constexpr int NR = TM + TN;                     // fragment reads per sub-step
+    constexpr int R_PER = (NR + NM - 1) / NM;       // fragment reads slipped in behind one MFMA
+    constexpr int L_PER = (LD + NM - 1) / NM;       // loads slipped in behind one MFMA of sub-step 3
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 1) * LD) : "memory");
+    __syncthreads();                                // step 0 (and the token table) visible to everyone
+#pragma unroll
+    for (int r = 0; r < NR; ++r) PS_READ_ONE(0, ring, 0, r);
+
+    int rd = 0;                                     // ring stage of the current step
+#pragma unroll 1
     for (int kt = 0; kt < KT; ++kt) {
-        // own loads of stage kt have landed when at most (NS-2) later stages are still in flight
-        if (NS == 2) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * (A_LD + B_LD)) : "memory");
-        __syncthreads();                            // everyone's loads of stage kt visible; stage kt-1 is free
-        // refill the freed stage with K step kt + NS - 1 (past the end: re-fetch the last step, never read); the
-        // loads are slipped in one behind each MFMA so that their address arithmetic runs in the matrix pipe's shadow
-        const int ty = tap / 3, tx = tap - ty * 3;
-        const int64_t a_off = (a.conv ? ((int64_t)ty * a.geom.ppw + tx) * a.lda : 0) + kc * BK;
-        const int64_t b_off = tap * b_tap_stride + kc * BK;
-        u32x4* dst = ring + wr * STAGE_V + wave * 64;
-        if (kt + NS < KT) { if (++kc == kchunks) { kc = 0; ++tap; } }
         const u32x4* cur = ring + rd * STAGE_V;
-        PS_READ_FRAGS(0, cur, 0);
+        const int nst = rd + 1 == NS ? 0 : rd + 1;
+        const u32x4* nxt = ring + nst * STAGE_V;
+        PS_OFFSETS(tap, kc);                        // step kt + NS goes into this step's stage
+        if (++issued < KT) { if (++kc == kchunks) { kc = 0; ++tap; } } else { issued = KT - 1; }
+        u32x4* dst = ring + rd * STAGE_V + wave * 64;
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
-            if (ks + 1 < BK / 16) PS_READ_FRAGS((ks + 1) & 1, cur, ks + 1);
+            if (ks == BK / 16 - 1) {
+                // own fragment reads of this step are complete; own loads of the next step have landed
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * LD) : "memory");
+                __syncthreads();
+            }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
+                    const int q = i * TN + j;
 #pragma unroll
-                    for (int u = 0; u < L_PER; ++u) {
-                        const int l = ((ks * NM) + i * TN + j) * L_PER + u;
-                        if (l < A_LD)
-                            __builtin_amdgcn_global_load_lds((const void*)(a_ptr[l < A_LD ? l : 0] + a_off),
-                                                             (lds_void*)(dst + l * 256), 16, 0, 0);
-                        else if (l < A_LD + B_LD)
-                            __builtin_amdgcn_global_load_lds((const void*)(b_ptr + (l - A_LD) * b_row32 + b_off),
-                                                             (lds_void*)(dst + BM * CH + (l - A_LD) * 256), 16, 0, 0);
+                    for (int u = 0; u < R_PER; ++u) {
+                        if (ks < BK / 16 - 1) { PS_READ_ONE((ks + 1) & 1, cur, ks + 1, q * R_PER + u); }
+                        else { PS_READ_ONE(0, nxt, 0, q * R_PER + u); }
+                    }
+                    if (ks == BK / 16 - 1) {
+#pragma unroll
+                        for (int u = 0; u < L_PER; ++u) PS_LOAD(dst, a_off, b_off, q * L_PER + u);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
         }
-        rd = rd + 1 == NS ? 0 : rd + 1;
-        wr = wr + 1 == NS ? 0 : wr + 1;
+        rd = nst;
     }
-#undef PS_READ_FRAGS
-#undef PS_ISSUE
+#undef PS_READ_ONE
+#undef PS_OFFSETS
+#undef PS_LOAD
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();                                // ring is reused by the epilogue
 
-    gemm_epilogue<BM, BN, GEGLU>(a, acc, smem, s_tok, n0);
+    gemm_epilogue<BM, BN, GEGLU, WGM, WGN>(a, acc, smem, s_tok, n0);
 }
 
 // ---- 3x3 convolution with the A operand kept in LDS across the nine taps -------------------------------------
@@ -631,17 +663,17 @@ static bool conv_tile(const GemmArgs& a, int BM, int apix_max, ConvTile* ct) {
     return ct->nseg * ct->seg_pix <= apix_max && ct->nseg <= 64;
 }
 
-template <int BM, int BN, bool GEGLU>
+template <int BM, int BN, bool GEGLU, int WGM, int WGN, int NS>
 static int launch(const GemmArgs& a, hipStream_t st) {
-    constexpr size_t lds = GemmCfg<BM, BN>::LDS;
+    constexpr size_t lds = GemmCfg<BM, BN, NS>::LDS;
     static bool attr_set = false;
     if (!attr_set) {
-        PS_CHECK_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<BM, BN, GEGLU>,
+        PS_CHECK_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<BM, BN, GEGLU, WGM, WGN, NS>,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set = true;
     }
     const unsigned grid = (unsigned)(8 * cdiv(cdiv(a.M, BM), 8) * (a.N / BN));
-    gemm_mfma_kernel<BM, BN, GEGLU><<<grid, 256, lds, st>>>(a);
+    gemm_mfma_kernel<BM, BN, GEGLU, WGM, WGN, NS><<<grid, 256, lds, st>>>(a);
     return check_launch("gemm_mfma_kernel");
 }
 
@@ -682,9 +714,9 @@ int gemm_mfma_bf16(const GemmArgs& a, hipStream_t st, bool* handled) {
     *handled = false;
     if (!mfma_eligible(a)) return PSERVE_OK;
     if (a.epi == EPI_GEGLU) {
-        if (a.N % 256 != 0) return PSERVE_OK;
+        if (a.N % 128 != 0) return PSERVE_OK;
         *handled = true;
-        return launch<128, 256, true>(a, st);
+        return launch<256, 128, true, 4, 1, 3>(a, st);
     }
     if (a.seg_cols % 32 != 0) return PSERVE_OK;      // a 32-column tile must not straddle output segments
     ConvTile ct;
@@ -696,16 +728,26 @@ int gemm_mfma_bf16(const GemmArgs& a, hipStream_t st, bool* handled) {
     case 5: *handled = true; return launch_conv<128, 64, 2, 2, 256, 2>(a, ct, st);
     default: break;
     }
-    // Few rows (e.g. the text-token projections): wide tiles would leave most of the 256 CUs idle, so take the
-    // narrowest tile when the widest one gives fewer than one block per two CUs.
-    const int64_t m_tiles = cdiv(a.M, 128);
-    const bool small = a.N % 64 == 0 && m_tiles * cdiv(a.N, 320) < 128;
+    // Tile choice.  Preferred: 256 rows, four wavefronts stacked along M (each 64 x 160 or 64 x 128), three stages.
+    // With fewer blocks than that leaves busy CUs, 128-row tiles; with few rows altogether (the text-token
+    // projections) the narrowest tile, two blocks per CU.
+    const int64_t m256 = cdiv(a.M, 256), m128 = cdiv(a.M, 128);
+    *handled = true;
+    // A transposed output segment (V^T) makes the epilogue long (8-byte stores): two smaller blocks per CU, so that one
+    // block's epilogue runs beside the other's main loop (measured 70 -> 62 us and 212 -> 184 us on the fused q/k/v
+    // projections of configs 3 and 4; without such a segment the large tiles win)
+    const bool has_t = a.seg[0].transposed || a.seg[1].transposed || a.seg[2].transposed;
+    if (has_t && a.N % 128 == 0 && m128 * (a.N / 128) >= 512) return launch<128, 128, false, 2, 2, 2>(a, st);
+    if (a.N % 160 == 0 && m256 * (a.N / 160) >= 160) return launch<256, 160, false, 4, 1, 3>(a, st);
+    if (a.N % 128 == 0 && m256 * (a.N / 128) >= 160) return launch<256, 128, false, 4, 1, 3>(a, st);
+    const bool small = a.N % 64 == 0 && m128 * cdiv(a.N, 320) < 128;
     if (!small) {
-        if (a.N % 320 == 0) { *handled = true; return launch<128, 320, false>(a, st); }
-        if (a.N % 256 == 0) { *handled = true; return launch<128, 256, false>(a, st); }
-        if (a.N % 128 == 0) { *handled = true; return launch<128, 128, false>(a, st); }
+        if (a.N % 320 == 0) return launch<128, 320, false, 2, 2, 2>(a, st);
+        if (a.N % 256 == 0) return launch<128, 256, false, 2, 2, 3>(a, st);
+        if (a.N % 128 == 0) return launch<128, 128, false, 2, 2, 4>(a, st);
     }
-    if (a.N % 64 == 0) { *handled = true; return launch<128, 64, false>(a, st); }
+    if (a.N % 64 == 0) return launch<128, 64, false, 2, 2, 3>(a, st);
+    *handled = false;
     return PSERVE_OK;
 }
 
