@@ -228,8 +228,9 @@ attn_mfma_kernel(AttnArgs a) {
 
     int st = 0;
     for (int t = 0; t < steps; ++t) {
-        asm volatile("s_waitcnt vmcnt(4)" ::: "memory");        // own loads of tile t have landed (tile t+1 may be in flight)
-        __syncthreads();                                        // tile t visible to all; the stage of tile t-1 is free
+        // own loads of tile t have landed (tile t+1 may be in flight); then tile t is visible to all and the stage of
+        // tile t-1 is free.  A bare s_barrier: __syncthreads() carries a fence that waits for ALL loads in flight.
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory");
         const int st2 = st == 0 ? ATT_NS - 1 : st - 1;          // stage of tile t-1 == stage of tile t+2
         PS_ISSUE_TILE(t + 2, st2);
         const int kv0 = t * ATT_BKV;

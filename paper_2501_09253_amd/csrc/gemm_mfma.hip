@@ -46,9 +46,11 @@ __device__ __forceinline__ float other_half_f(float v) {
 // scale, GEGLU), staged as fp32 in this wavefront's private LDS region and read back row-wise, so that residual
 // loads and output stores are 16 bytes per lane and 64 contiguous bytes per row.  Residual loads of the next tile
 // column are issued before the current one is staged.  `smem` must be free (all staged operands consumed).
-template <int BM, int BN, bool GEGLU, int WGM = 2, int WGN = 2>
+// bias_pre: the lane's bias of each of its TN tile columns, loaded by the caller (a kernel that has other loads in
+// flight reads it before issuing those: a wait for a later load waits for all earlier ones).
+template <int BM, int BN, bool GEGLU, int WGM = 2, int WGN = 2, bool MAY_STAT = true>
 __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32], uint8_t* smem,
-                                              const int32_t* s_tok, int n0) {
+                                              const int32_t* s_tok, int n0, const float* bias_pre = nullptr) {
     constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;     // WGM x WGN wavefront grid
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
@@ -74,7 +76,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[B
         for (int t = 0; t < NIT; ++t) rres[0][t] = *reinterpret_cast<const u32x4*>(res_row[t] + n0 + wn * WN);
     }
     // GroupNorm partial sums of the output (optional): column sums over this wavefront's 64 rows, which lie in one patch
-    const bool STATS = !GEGLU && a.stats != nullptr;
+    const bool STATS = MAY_STAT && !GEGLU && a.stats != nullptr;     // only the convolution kernels leave the sums behind
     float* colsum = reinterpret_cast<float*>(smem) + WGM * WGN * (WM * EP_LD) + wave * (2 * WN);    // [WN][2]
     uint32_t row_ok[TM];                                            // bit e: row 8*(e/4) + 4*fh + e%4 of tile i exists
     const bool all_rows = STATS && w_tok[WM - 1] >= 0;              // existing rows are a prefix of the tile
@@ -93,7 +95,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[B
         GemmSeg sgm;
         float vals[TM][16];
         if (GEGLU) {
-            const float bv = a.bias ? a.bias[pcol + fr] : 0.f, bg = a.bias ? a.bias[pcol + fr + GEGLU_GROUP] : 0.f;
+            const float bv = bias_pre ? bias_pre[j] : (a.bias ? a.bias[pcol + fr] : 0.f);
+            const float bg = bias_pre ? bias_pre[j + TN / 2] : (a.bias ? a.bias[pcol + fr + GEGLU_GROUP] : 0.f);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -104,7 +107,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[B
             const int sg = pcol / a.seg_cols;
             sgm = sg == 0 ? a.seg[0] : (sg == 1 ? a.seg[1] : a.seg[2]);
             ocol0 = pcol - sg * a.seg_cols;
-            const float bias = a.bias ? a.bias[pcol + fr] : 0.f;
+            const float bias = bias_pre ? bias_pre[j] : (a.bias ? a.bias[pcol + fr] : 0.f);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -208,11 +211,14 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[B
 
 typedef __attribute__((address_space(3))) void lds_void;
 
-// LDS bytes of one kernel instance: NS stages of (BM + BN) rows x 128 bytes, plus the row -> token table
-template <int BM, int BN, int NS> struct GemmCfg {
+// LDS bytes of one kernel instance: NS stages of (BM + BN) rows x 128 bytes, two row -> token tables and, with
+// OVERLAP, a staging region of the epilogue of its own (otherwise the epilogue stages in the drained ring)
+template <int BM, int BN, int NS, bool OVERLAP> struct GemmCfg {
     static constexpr int STAGE = (BM + BN) * 128;
-    static constexpr size_t LDS = (size_t)NS * STAGE + BM * sizeof(int32_t);
+    static constexpr int EPI = 4 * (BM / 4 >= 64 ? BM / 4 : 64) * 36 * 4;      // >= 4 wavefronts x WM rows x 36 floats
+    static constexpr size_t LDS = (size_t)NS * STAGE + 2 * BM * sizeof(int32_t) + (OVERLAP ? EPI : 0);
     static_assert(LDS <= 160 * 1024, "ring does not fit the LDS");
+    static_assert(OVERLAP || NS * STAGE >= EPI, "epilogue staging does not fit the ring");
 };
 
 // Block tile BM x BN, WGM x WGN wavefront grid (four wavefronts), ring of NS stages.
@@ -221,8 +227,11 @@ template <int BM, int BN, int NS> struct GemmCfg {
 // of this step's stage with step + NS.  The block barrier sits before sub-step 3: by then every wavefront has read all
 // of this step's fragments (its stage is free) and has seen its own loads of the next step land, NS - 2 further steps
 // still being in flight.
-template <int BM, int BN, bool GEGLU, int WGM, int WGN, int NS>
-__global__ void __launch_bounds__(256)
+// A block walks over tiles (grid = the blocks that fit the chip at once).  With OVERLAP the first NS steps of the next
+// tile are issued BEFORE the epilogue of the current one, so that the load latency of a tile start and the vector work
+// and stores of a tile end (about 4 us and 6 us of a 19 us tile at K = 640) run beside each other.
+template <int BM, int BN, bool GEGLU, int WGM, int WGN, int NS, bool OVERLAP>
+__global__ void __launch_bounds__(256, (GemmCfg<BM, BN, NS, OVERLAP>::LDS <= 80 * 1024 ? 2 : 1))
 gemm_mfma_kernel(GemmArgs a) {
     constexpr int BK = 64;
     constexpr int CH = BK / 8;                      // 16-byte chunks per row
@@ -234,30 +243,43 @@ gemm_mfma_kernel(GemmArgs a) {
     constexpr int STAGE_V = (BM + BN) * CH;         // 16-byte slots per stage: A rows then B rows
     static_assert(WGM * WGN == 4 && WM % 32 == 0 && WN % 32 == 0 && (BM * CH) % 256 == 0 && (BN * CH) % 256 == 0 &&
                   NS >= 2 && (NS - 1) * LD <= 63, "tile shape");
+    static_assert(4 * WM * 36 * 4 <= GemmCfg<BM, BN, NS, OVERLAP>::EPI, "epilogue staging size");
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     u32x4* ring = reinterpret_cast<u32x4*>(smem);                     // [NS][STAGE_V]
-    int32_t* s_tok = reinterpret_cast<int32_t*>(ring + NS * STAGE_V); // [BM] output row of each tile row, -1 = none
+    int32_t* s_tok2 = reinterpret_cast<int32_t*>(ring + NS * STAGE_V); // [2][BM] output row of each tile row, -1 = none
+    uint8_t* ep_smem = OVERLAP ? reinterpret_cast<uint8_t*>(s_tok2 + 2 * BM) : smem;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // scalar: LDS destinations of the loads are SGPR math
     const int wm = wave / WGN, wn = wave % WGN;
     // XCD-aware tile order.  Block ids are dealt round-robin to the 8 XCDs (each with its own L2), so the blocks of one
-    // residue mod 8 run on one XCD in the order of their slot (id / 8), 32 at a time.  An XCD owns every 8th M tile;
-    // it takes them in groups of `gm` whose A panels together fit its L2, and walks a group M tile fastest, then N
-    // tile: the blocks in flight share `gm` A panels and a few B panels, A is fetched once and B once per group
-    // (N fastest, i.e. gm = 1, re-streams all of B for every M tile: 375 MB instead of 70 MB for a 5120 x 640 weight).
+    // residue mod 8 run on one XCD; they take that XCD's slots in order, gridDim / 8 at a time.  An XCD owns every 8th
+    // M tile; it takes them in groups of `gm` whose A panels together fit its L2, and walks a group M tile fastest,
+    // then N tile: the blocks in flight share `gm` A panels and a few B panels, A is fetched once and B once per group
+    // (N fastest, i.e. gm = 1, re-streams all of B for every M tile: 375 MB instead of 145 MB for a 5120 x 640 weight).
     const int n_tiles = a.N / BN, m_tiles = (a.M + BM - 1) / BM;
     const int mx = (m_tiles + 7) >> 3;              // M tiles per XCD
     const int64_t a_panel = (int64_t)BM * a.K * a.taps * 2;
     const int gm = (int)max((int64_t)1, min((int64_t)mx, (int64_t)(2560 * 1024) / a_panel));
-    const int slot = blockIdx.x >> 3;
-    const int grp = slot / (gm * n_tiles), r_in = slot - grp * (gm * n_tiles);
-    const int gm_here = min(gm, mx - grp * gm);     // the last group may be short
-    const int n_tile = r_in / gm_here;
-    const int m_tile = (grp * gm + (r_in - n_tile * gm_here)) * 8 + (blockIdx.x & 7);
-    if (m_tile >= m_tiles) return;
-    const int m0 = m_tile * BM, n0 = n_tile * BN;
-    if (a.tokens_are_rows && a.act.active && m0 >= *a.act.count * a.geom.S) return;
+    const int slots = mx * n_tiles, slot_step = gridDim.x >> 3;
+    const int m_limit = (a.tokens_are_rows && a.act.active) ? *a.act.count * a.geom.S : a.M;   // rows that exist
+    // tile of a slot; false when it has no rows
+    auto decode = [&](int slot, int& m0, int& n0) -> bool {
+        const int grp = slot / (gm * n_tiles), r_in = slot - grp * (gm * n_tiles);
+        const int gm_here = min(gm, mx - grp * gm); // the last group may be short
+        const int n_tile = r_in / gm_here;
+        const int m_tile = (grp * gm + (r_in - n_tile * gm_here)) * 8 + (blockIdx.x & 7);
+        m0 = m_tile * BM;
+        n0 = n_tile * BN;
+        return m_tile < m_tiles && m0 < m_limit;
+    };
+    auto next_tile = [&](int slot, int& m0, int& n0) -> int {       // first slot >= `slot` of this block with rows
+        while (slot < slots && !decode(slot, m0, n0)) slot += slot_step;
+        return slot;
+    };
+    int m0 = 0, n0 = 0;
+    int slot = next_tile(blockIdx.x >> 3, m0, n0);
+    if (slot >= slots) return;
 
     // Staging by direct global -> LDS loads.  One wavefront instruction fills 64 consecutive 16-byte slots
     // (8 rows x 8 chunk positions); the lane at (row, position pos) fetches global chunk pos ^ f(row),
@@ -267,41 +289,47 @@ gemm_mfma_kernel(GemmArgs a) {
     const uint16_t* A = (const uint16_t*)a.A;
     const uint16_t* B = (const uint16_t*)a.B;
     const uint16_t* a_ptr[A_LD];
-#pragma unroll
-    for (int i = 0; i < A_LD; ++i) {
-        const int row = lr + i * 32;
-        int64_t tok = m0 + row;
-        bool valid;
-        if (a.tokens_are_rows && a.act.active) {
-            const int pi = (int)(tok / a.geom.S);
-            valid = pi < *a.act.count;
-            tok = valid ? (int64_t)a.act.active[pi] * a.geom.S + (tok - (int64_t)pi * a.geom.S) : 0;
-        } else {
-            valid = tok < a.M;
-            if (!valid) tok = 0;
-        }
-        int64_t off;
-        if (a.conv) {
-            const int p = (int)(tok / a.geom.S), q = (int)(tok - (int64_t)p * a.geom.S);
-            const int y = q / a.geom.pw, x = q - y * a.geom.pw;
-            off = ((int64_t)p * a.geom.pS + y * a.geom.ppw + x) * a.lda;
-        } else {
-            off = tok * a.lda;
-        }
-        a_ptr[i] = A + off + gc * 8;
-        if (lc == 0) {
-            int64_t orow = tok;
-            if (!a.tokens_are_rows && a.row_group > 0) orow = (tok / a.row_group) * a.row_group_pad + tok % a.row_group;
-            s_tok[row] = valid ? (int32_t)orow : -1;
-        }
-    }
-    const uint16_t* b_ptr = B + (int64_t)(n0 + lr) * a.K + gc * 8;
+    const uint16_t* b_ptr;
     const int64_t b_row32 = (int64_t)32 * a.K;
-
     const int kchunks = a.K / BK;
     const int KT = a.taps * kchunks;
     const int64_t b_tap_stride = (int64_t)a.N * a.K;
+    int tap, kc, issued;                            // K step that is issued next (stays at the last one past the end:
+                                                    // it is fetched again into a free stage and never read)
 
+    // operand pointers and the row -> token table `tok_tab` of tile (tm0, tn0)
+#define PS_SETUP(tm0, tn0, tok_tab)                                                                               \
+    {                                                                                                             \
+        _Pragma("unroll") for (int i = 0; i < A_LD; ++i) {                                                        \
+            const int row = lr + i * 32;                                                                          \
+            int64_t tok = (tm0) + row;                                                                            \
+            bool valid;                                                                                           \
+            if (a.tokens_are_rows && a.act.active) {                                                              \
+                const int pi = (int)(tok / a.geom.S);                                                             \
+                valid = pi < *a.act.count;                                                                        \
+                tok = valid ? (int64_t)a.act.active[pi] * a.geom.S + (tok - (int64_t)pi * a.geom.S) : 0;          \
+            } else {                                                                                              \
+                valid = tok < a.M;                                                                                \
+                if (!valid) tok = 0;                                                                              \
+            }                                                                                                     \
+            int64_t off;                                                                                          \
+            if (a.conv) {                                                                                         \
+                const int p = (int)(tok / a.geom.S), q = (int)(tok - (int64_t)p * a.geom.S);                      \
+                const int y = q / a.geom.pw, x = q - y * a.geom.pw;                                               \
+                off = ((int64_t)p * a.geom.pS + y * a.geom.ppw + x) * a.lda;                                      \
+            } else {                                                                                              \
+                off = tok * a.lda;                                                                                \
+            }                                                                                                     \
+            a_ptr[i] = A + off + gc * 8;                                                                          \
+            if (lc == 0) {                                                                                        \
+                int64_t orow = tok;                                                                               \
+                if (!a.tokens_are_rows && a.row_group > 0)                                                        \
+                    orow = (tok / a.row_group) * a.row_group_pad + tok % a.row_group;                             \
+                (tok_tab)[row] = valid ? (int32_t)orow : -1;                                                      \
+            }                                                                                                     \
+        }                                                                                                         \
+        b_ptr = B + (int64_t)((tn0) + lr) * a.K + gc * 8;                                                         \
+    }
     // one direct global->LDS load (64 lanes x 16 bytes): l < A_LD an A row group, else a B row group
 #define PS_LOAD(dst_, a_off_, b_off_, l_)                                                                         \
     {                                                                                                             \
@@ -317,25 +345,17 @@ gemm_mfma_kernel(GemmArgs a) {
     const int ty_ = (tap_) / 3, tx_ = (tap_) - ty_ * 3;                                                           \
     const int64_t a_off = (a.conv ? ((int64_t)ty_ * a.geom.ppw + tx_) * a.lda : 0) + (kc_) * BK;                  \
     const int64_t b_off = (tap_) * b_tap_stride + (kc_) * BK;
-
-    int tap = 0, kc = 0, issued = 0;                // K step that is issued next (stays at the last one past the end:
-                                                    // it is fetched again into a free stage and never read)
-#pragma unroll
-    for (int st = 0; st < NS; ++st) {               // prologue: all NS stages in flight
-        PS_OFFSETS(tap, kc);
-        u32x4* dst = ring + st * STAGE_V + wave * 64;
-#pragma unroll
-        for (int l = 0; l < LD; ++l) PS_LOAD(dst, a_off, b_off, l);
-        if (++issued < KT) { if (++kc == kchunks) { kc = 0; ++tap; } } else { issued = KT - 1; }
+    // the first NS steps of a tile: all stages in flight
+#define PS_PROLOGUE()                                                                                             \
+    {                                                                                                             \
+        tap = 0; kc = 0; issued = 0;                                                                              \
+        _Pragma("unroll") for (int st = 0; st < NS; ++st) {                                                       \
+            PS_OFFSETS(tap, kc);                                                                                  \
+            u32x4* dst = ring + st * STAGE_V + wave * 64;                                                         \
+            _Pragma("unroll") for (int l = 0; l < LD; ++l) PS_LOAD(dst, a_off, b_off, l);                         \
+            if (++issued < KT) { if (++kc == kchunks) { kc = 0; ++tap; } } else { issued = KT - 1; }              \
+        }                                                                                                         \
     }
-
-    f32x16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
     const int fr = lane & 31, fh = lane >> 5;       // fragment row within a 32-row tile, k half
     // LDS fragment slots of this lane: row*CH + ((2*ks + fh) ^ f(row))
@@ -357,60 +377,97 @@ gemm_mfma_kernel(GemmArgs a) {
         else if ((r_) <= TN) fb[dst][jb_] = __builtin_bit_cast(bf16x8, (stage_)[fb_base[jb_] + (c_ ^ fb_sw[jb_])]); \
         else if ((r_) < TM + TN) fa[dst][ia_] = __builtin_bit_cast(bf16x8, (stage_)[fa_base[ia_] + (c_ ^ fa_sw[ia_])]); \
     }
-
     constexpr int NM = TM * TN;                     // MFMAs per 16-wide sub-step
     constexpr int NR = TM + TN;                     // fragment reads per sub-step
     constexpr int R_PER = (NR + NM - 1) / NM;       // fragment reads slipped in behind one MFMA
     constexpr int L_PER = (LD + NM - 1) / NM;       // loads slipped in behind one MFMA of sub-step 3
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 1) * LD) : "memory");
-    __syncthreads();                                // step 0 (and the token table) visible to everyone
-#pragma unroll
-    for (int r = 0; r < NR; ++r) PS_READ_ONE(0, ring, 0, r);
 
-    int rd = 0;                                     // ring stage of the current step
+    int buf = 0;                                    // token table of the current tile
+    PS_SETUP(m0, n0, s_tok2);
+    PS_PROLOGUE();
 #pragma unroll 1
-    for (int kt = 0; kt < KT; ++kt) {
-        const u32x4* cur = ring + rd * STAGE_V;
-        const int nst = rd + 1 == NS ? 0 : rd + 1;
-        const u32x4* nxt = ring + nst * STAGE_V;
-        PS_OFFSETS(tap, kc);                        // step kt + NS goes into this step's stage
-        if (++issued < KT) { if (++kc == kchunks) { kc = 0; ++tap; } } else { issued = KT - 1; }
-        u32x4* dst = ring + rd * STAGE_V + wave * 64;
+    for (;;) {
+        f32x16 acc[TM][TN];
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            if (ks == BK / 16 - 1) {
-                // own fragment reads of this step are complete; own loads of the next step have landed
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * LD) : "memory");
-                __syncthreads();
-            }
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
-                    const int q = i * TN + j;
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+        // stage 0 has landed when at most the NS - 1 later stages (and nothing issued after them) are in flight
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 1) * LD) : "memory");
+        __syncthreads();                            // step 0 and the token table visible to everyone
 #pragma unroll
-                    for (int u = 0; u < R_PER; ++u) {
-                        if (ks < BK / 16 - 1) { PS_READ_ONE((ks + 1) & 1, cur, ks + 1, q * R_PER + u); }
-                        else { PS_READ_ONE(0, nxt, 0, q * R_PER + u); }
-                    }
-                    if (ks == BK / 16 - 1) {
+        for (int r = 0; r < NR; ++r) PS_READ_ONE(0, ring, 0, r);
+
+        int rd = 0;                                 // ring stage of the current step
+#pragma unroll 1
+        for (int kt = 0; kt < KT; ++kt) {
+            const u32x4* cur = ring + rd * STAGE_V;
+            const int nst = rd + 1 == NS ? 0 : rd + 1;
+            const u32x4* nxt = ring + nst * STAGE_V;
+            PS_OFFSETS(tap, kc);                    // step kt + NS goes into this step's stage
+            if (++issued < KT) { if (++kc == kchunks) { kc = 0; ++tap; } } else { issued = KT - 1; }
+            u32x4* dst = ring + rd * STAGE_V + wave * 64;
 #pragma unroll
-                        for (int u = 0; u < L_PER; ++u) PS_LOAD(dst, a_off, b_off, q * L_PER + u);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
+            for (int ks = 0; ks < BK / 16; ++ks) {
+                if (ks == BK / 16 - 1) {
+                    // own fragment reads of this step are complete; own loads of the next step have landed.  A bare
+                    // s_barrier: __syncthreads() carries a fence that waits for ALL loads in flight (vmcnt(0)), which
+                    // would cut the ring down to one step ahead whatever its depth.
+                    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((NS - 2) * LD) : "memory");
                 }
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
+                        const int q = i * TN + j;
+#pragma unroll
+                        for (int u = 0; u < R_PER; ++u) {
+                            if (ks < BK / 16 - 1) { PS_READ_ONE((ks + 1) & 1, cur, ks + 1, q * R_PER + u); }
+                            else { PS_READ_ONE(0, nxt, 0, q * R_PER + u); }
+                        }
+                        if (ks == BK / 16 - 1) {
+#pragma unroll
+                            for (int u = 0; u < L_PER; ++u) PS_LOAD(dst, a_off, b_off, q * L_PER + u);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+            }
+            rd = nst;
         }
-        rd = nst;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();                            // ring drained: free for the next tile (or the epilogue's staging)
+
+        int nm0 = 0, nn0 = 0;
+        const int nslot = next_tile(slot + slot_step, nm0, nn0);
+        const int32_t* tok_cur = s_tok2 + buf * BM;
+        const int n0_cur = n0;
+        // the bias is read before the next tile's loads are issued: a wait for a load waits for all loads issued
+        // before it, so a bias load behind them would stall the epilogue until the whole next tile start has landed
+        float bias_t[TN];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bias_t[j] = a.bias ? a.bias[n0_cur + wn * WN + j * 32 + fr] : 0.f;
+        asm volatile("" ::: "memory");              // keeps the compiler from sinking these loads below the next ones
+        if (OVERLAP && nslot < slots) {             // next tile's first steps in flight during this tile's epilogue
+            PS_SETUP(nm0, nn0, s_tok2 + (buf ^ 1) * BM);
+            PS_PROLOGUE();
+        }
+        gemm_epilogue<BM, BN, GEGLU, WGM, WGN, false>(a, acc, ep_smem, tok_cur, n0_cur, bias_t);
+        if (nslot >= slots) break;
+        if (!OVERLAP) {
+            __syncthreads();                        // every wavefront is done with its staging region in the ring
+            PS_SETUP(nm0, nn0, s_tok2 + (buf ^ 1) * BM);
+            PS_PROLOGUE();
+        }
+        slot = nslot; m0 = nm0; n0 = nn0; buf ^= 1;
     }
 #undef PS_READ_ONE
+#undef PS_PROLOGUE
 #undef PS_OFFSETS
 #undef PS_LOAD
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();                                // ring is reused by the epilogue
-
-    gemm_epilogue<BM, BN, GEGLU, WGM, WGN>(a, acc, smem, s_tok, n0);
+#undef PS_SETUP
 }
 
 // ---- 3x3 convolution with the A operand kept in LDS across the nine taps -------------------------------------
@@ -594,10 +651,12 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
                 if (ks == BK / 16 - 1) {
                     // own fragment reads of this step are complete; own loads of the next step's weights have landed.
                     // Still allowed in flight: the NSB-2 later weight stages and a halo issued in this or a recent tap 0.
-                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                    if (tap < NSB - 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSB - 2) * B_LD + A_LD) : "memory");
-                    else asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSB - 2) * B_LD) : "memory");
-                    __syncthreads();
+                    // A bare s_barrier: __syncthreads() carries a fence that waits for ALL loads in flight (vmcnt(0)),
+                    // which would cut the weight ring down to one step ahead whatever its depth.
+                    if (tap < NSB - 1)
+                        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((NSB - 2) * B_LD + A_LD) : "memory");
+                    else
+                        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((NSB - 2) * B_LD) : "memory");
                 }
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
@@ -663,17 +722,21 @@ static bool conv_tile(const GemmArgs& a, int BM, int apix_max, ConvTile* ct) {
     return ct->nseg * ct->seg_pix <= apix_max && ct->nseg <= 64;
 }
 
-template <int BM, int BN, bool GEGLU, int WGM, int WGN, int NS>
+template <int BM, int BN, bool GEGLU, int WGM, int WGN, int NS, bool OVERLAP>
 static int launch(const GemmArgs& a, hipStream_t st) {
-    constexpr size_t lds = GemmCfg<BM, BN, NS>::LDS;
+    constexpr size_t lds = GemmCfg<BM, BN, NS, OVERLAP>::LDS;
     static bool attr_set = false;
     if (!attr_set) {
-        PS_CHECK_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<BM, BN, GEGLU, WGM, WGN, NS>,
+        PS_CHECK_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<BM, BN, GEGLU, WGM, WGN, NS, OVERLAP>,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set = true;
     }
-    const unsigned grid = (unsigned)(8 * cdiv(cdiv(a.M, BM), 8) * (a.N / BN));
-    gemm_mfma_kernel<BM, BN, GEGLU, WGM, WGN, NS><<<grid, 256, lds, st>>>(a);
+    // all tiles, or as many blocks as run at once (256 CUs x the blocks of this LDS size per CU): each block then
+    // walks over several tiles
+    const int64_t all = 8 * cdiv(cdiv(a.M, BM), 8) * (a.N / BN);
+    const int64_t resident = 256 * (int64_t)std::max<size_t>(1, std::min<size_t>(2, (160 * 1024) / lds));
+    const unsigned grid = (unsigned)std::min(all, resident);
+    gemm_mfma_kernel<BM, BN, GEGLU, WGM, WGN, NS, OVERLAP><<<grid, 256, lds, st>>>(a);
     return check_launch("gemm_mfma_kernel");
 }
 
@@ -716,7 +779,7 @@ int gemm_mfma_bf16(const GemmArgs& a, hipStream_t st, bool* handled) {
     if (a.epi == EPI_GEGLU) {
         if (a.N % 128 != 0) return PSERVE_OK;
         *handled = true;
-        return launch<256, 128, true, 4, 1, 3>(a, st);
+        return launch<256, 128, true, 4, 1, 2, true>(a, st);
     }
     if (a.seg_cols % 32 != 0) return PSERVE_OK;      // a 32-column tile must not straddle output segments
     ConvTile ct;
@@ -737,16 +800,16 @@ int gemm_mfma_bf16(const GemmArgs& a, hipStream_t st, bool* handled) {
     // block's epilogue runs beside the other's main loop (measured 70 -> 62 us and 212 -> 184 us on the fused q/k/v
     // projections of configs 3 and 4; without such a segment the large tiles win)
     const bool has_t = a.seg[0].transposed || a.seg[1].transposed || a.seg[2].transposed;
-    if (has_t && a.N % 128 == 0 && m128 * (a.N / 128) >= 512) return launch<128, 128, false, 2, 2, 2>(a, st);
-    if (a.N % 160 == 0 && m256 * (a.N / 160) >= 160) return launch<256, 160, false, 4, 1, 3>(a, st);
-    if (a.N % 128 == 0 && m256 * (a.N / 128) >= 160) return launch<256, 128, false, 4, 1, 3>(a, st);
+    if (has_t && a.N % 128 == 0 && m128 * (a.N / 128) >= 512) return launch<128, 128, false, 2, 2, 2, false>(a, st);
+    if (a.N % 160 == 0 && m256 * (a.N / 160) >= 160) return launch<256, 160, false, 4, 1, 2, true>(a, st);
+    if (a.N % 128 == 0 && m256 * (a.N / 128) >= 160) return launch<256, 128, false, 4, 1, 2, true>(a, st);
     const bool small = a.N % 64 == 0 && m128 * cdiv(a.N, 320) < 128;
     if (!small) {
-        if (a.N % 320 == 0) return launch<128, 320, false, 2, 2, 2>(a, st);
-        if (a.N % 256 == 0) return launch<128, 256, false, 2, 2, 3>(a, st);
-        if (a.N % 128 == 0) return launch<128, 128, false, 2, 2, 4>(a, st);
+        if (a.N % 320 == 0) return launch<128, 320, false, 2, 2, 2, true>(a, st);
+        if (a.N % 256 == 0) return launch<128, 256, false, 2, 2, 2, true>(a, st);
+        if (a.N % 128 == 0) return launch<128, 128, false, 2, 2, 3, true>(a, st);
     }
-    if (a.N % 64 == 0) return launch<128, 64, false, 2, 2, 3>(a, st);
+    if (a.N % 64 == 0) return launch<128, 64, false, 2, 2, 3, false>(a, st);
     *handled = false;
     return PSERVE_OK;
 }
