@@ -168,7 +168,8 @@ __global__ void gn_finalize_kernel(const float* __restrict__ partial, const int3
     }
 }
 
-__device__ __forceinline__ float silu_f(float v) { return __fdividef(v, 1.f + __expf(-v)); }
+// v * sigmoid(v) with the hardware reciprocal (1 ulp): a true division expands to ten instructions per element
+__device__ __forceinline__ float silu_f(float v) { return v * __builtin_amdgcn_rcpf(1.f + __expf(-v)); }
 
 // Edge stitching fused into the normalisation (the push form of the paper's "Patch Edge Stitcher"): a border
 // token's normalised value is also written into the ring slot of every same-image neighbour patch that needs
@@ -214,15 +215,27 @@ __global__ void gn_apply_kernel(const T* __restrict__ x, const float* __restrict
     const int sp = blockIdx.y;
     const int chunk = (gm.S + nsplit - 1) / nsplit;
     const int t0 = sp * chunk, t1 = min(gm.S, t0 + chunk);
+    // Rows of this thread: t0 + tl + k*TL.  Their pixel coordinates and offsets advance by additions (a division and
+    // 64-bit multiplications per row were a third of the kernel's vector instructions).
+    const int pw = gm.pw;
+    const int dyy = TL / pw, dxx = TL - dyy * pw;                       // one row step in pixel rows / columns
+    const int step_in = TL * C;
+    const int step_out = PADDED ? (dyy * gm.ppw + dxx) * C : TL * C;
+    const int wrap_out = PADDED ? (gm.ppw - pw) * C : 0;                // extra when the column wraps into the next pixel row
+    int tb = t0 + tl;
+    int py = tb / pw, px = tb - py * pw;
+    const T* xin = x + ((int64_t)p * gm.S) * C + cv * VN;
+    T* po = out + ((int64_t)p * (PADDED ? gm.pS : gm.S)) * C + cv * VN;
+    int in_off = tb * C;
+    int out_off = (PADDED ? (py + 1) * gm.ppw + px + 1 : tb) * C;
+    const int last_in = (t1 - 1) * C;
     // The row loads of the first batch go first: they depend on the patch only, while scale / shift hang on the
     // owner table (two dependent loads).  Up to GN_U independent 16-byte loads in flight per thread; rows past the
     // chunk re-read its last row and are skipped.
-    const T* base = x + ((int64_t)p * gm.S) * C + cv * VN;
     uint4 raw[GN_U];
-    int tb = t0 + tl;
     if (tb < t1) {
 #pragma unroll
-        for (int u = 0; u < GN_U; ++u) raw[u] = *reinterpret_cast<const uint4*>(base + (int64_t)min(tb + u * TL, t1 - 1) * C);
+        for (int u = 0; u < GN_U; ++u) raw[u] = *reinterpret_cast<const uint4*>(xin + min(in_off + u * step_in, last_in));
     }
     const int s = owner[p];
     float sc[VN], sh[VN];
@@ -232,37 +245,31 @@ __global__ void gn_apply_kernel(const T* __restrict__ x, const float* __restrict
     int32_t nb[8];                              // neighbour patches, read once (no dependent loads behind the stores)
 #pragma unroll
     for (int k = 0; k < 8; ++k) nb[k] = (PADDED && STITCH) ? neighbour[8 * p + k] : -1;
-    auto out_off = [&](int t) -> int64_t {
-        if (PADDED) {
-            const int y = t / gm.pw, xx = t - y * gm.pw;
-            return ((int64_t)p * gm.pS + (y + 1) * gm.ppw + xx + 1) * C;
-        }
-        return ((int64_t)p * gm.S + t) * C;
-    };
     for (; tb < t1; tb += GN_U * TL) {
         float v[GN_U][VN];
 #pragma unroll
         for (int u = 0; u < GN_U; ++u) unpack_vec<T>(raw[u], v[u]);
-        const int nxt = tb + GN_U * TL;
-        if (nxt < t1) {                         // next batch in flight while this one is finished
+        in_off += GN_U * step_in;
+        if (tb + GN_U * TL < t1) {              // next batch in flight while this one is finished
 #pragma unroll
-            for (int u = 0; u < GN_U; ++u) raw[u] = *reinterpret_cast<const uint4*>(base + (int64_t)min(nxt + u * TL, t1 - 1) * C);
+            for (int u = 0; u < GN_U; ++u) raw[u] = *reinterpret_cast<const uint4*>(xin + min(in_off + u * step_in, last_in));
         }
 #pragma unroll
         for (int u = 0; u < GN_U; ++u) {
-            const int t = tb + u * TL;
-            if (t < t1) {
+            if (tb + u * TL < t1) {
 #pragma unroll
                 for (int e = 0; e < VN; ++e) {
                     v[u][e] = fmaf(v[u][e], sc[e], sh[e]);
                     if (SILU) v[u][e] = silu_f(v[u][e]);
                 }
-                store_vec<T>(out + out_off(t) + cv * VN, v[u]);
-                if (PADDED && STITCH) {
-                    const int y = t / gm.pw;
-                    stitch_store<T>(out, nb, gm, p, y, t - y * gm.pw, C, cv * VN, v[u]);
-                }
+                store_vec<T>(po + out_off, v[u]);
+                if (PADDED && STITCH) stitch_store<T>(out, nb, gm, p, py, px, C, cv * VN, v[u]);
             }
+            // next row of this thread
+            px += dxx;
+            py += dyy;
+            out_off += step_out;
+            if (px >= pw) { px -= pw; ++py; out_off += wrap_out; }
         }
     }
 }
