@@ -24,6 +24,12 @@ Readings of points the paper leaves open (each also listed in the design notes):
   * attention: scale 1/sqrt(d), no mask, no positional term (Patch-based
     Self-Attention Module: every query meets all keys of its own image).
   * GELU is the exact erf form; the GEGLU value half comes first, the gate half second.
+  * The L-stages (LSATTN, LXATTN, LFFN) are the attention / feed-forward stages with a
+    per-pixel LayerNorm over the channels in front (the transformer layer of the
+    paper's first model normalises each token before every sub-layer; the paper
+    lists such per-pixel operators among those that patching leaves untouched,
+    Patch-Tailored Diffusion Operators): biased variance, same eps, per-channel affine.
+    Nothing of a reused patch's input is needed by them, so only K and V are cached.
   * cache reuse (Patch-aware Caching Strategy, steps 3-5): at each operator that
     needs context the operand of a reused patch is the cached tensor of the
     previous step; after the block the reused patches of the output are replaced by
@@ -75,6 +81,19 @@ def group_norm(u: np.ndarray, gamma: np.ndarray, beta: np.ndarray, G: int, eps: 
         xh = (blk - mu) / np.sqrt(var + eps)
         out[g * cg:(g + 1) * cg] = xh * gamma[g * cg:(g + 1) * cg, None, None] \
             + beta[g * cg:(g + 1) * cg, None, None]
+    return out
+
+
+def layer_norm(u: np.ndarray, gamma: np.ndarray, beta: np.ndarray, eps: float) -> np.ndarray:
+    """LayerNorm of every pixel of u[C, H, W] over its C channels (mean and biased variance per pixel)."""
+    C, H, W = u.shape
+    out = np.empty((C, H, W), dtype=F64)
+    for y in range(H):
+        for x in range(W):
+            v = u[:, y, x].astype(F64)
+            mu = v.sum() / C
+            var = ((v - mu) ** 2).sum() / C
+            out[:, y, x] = (v - mu) / np.sqrt(var + eps) * gamma.astype(F64) + beta.astype(F64)
     return out
 
 
@@ -187,6 +206,30 @@ def sattn(x, p, G, heads, eps, reuse_px=None, cache=None, key="", new_cache=None
     return yt if rows is not None else _image(yt, H, W)
 
 
+def lsattn(x, p, heads, eps, reuse_px=None, cache=None, key="", new_cache=None, rows=None):
+    """LSATTN(x) = x + MHA(LN(x)) W_o + b_o.  With reuse, K and V of reused patches come from the cache (the
+    normalisation is per pixel, so the stage input of a reused patch is not needed)."""
+    C, H, W = x.shape
+    u = _tokens(layer_norm(x, p["ln_g"], p["ln_b"], eps))
+    Q = u @ p["wq"].astype(F64)
+    K = u @ p["wk"].astype(F64)
+    V = u @ p["wv"].astype(F64)
+    if reuse_px is not None:
+        K = _tokens(_fill(_image(K, H, W), cache[key + "K"], reuse_px))
+        V = _tokens(_fill(_image(V, H, W), cache[key + "V"], reuse_px))
+        new_cache[key + "K"] = _image(K, H, W)
+        new_cache[key + "V"] = _image(V, H, W)
+    O = attention(Q, K, V, heads, rows=rows)
+    xt = _tokens(x) if rows is None else _tokens(x)[rows]
+    yt = xt + O @ p["wo"].astype(F64) + p["bo"].astype(F64)
+    return yt if rows is not None else _image(yt, H, W)
+
+
+def _ln_tokens(xt, p, eps):
+    """LayerNorm of tokens [N, C] (each row on its own)."""
+    return _tokens(layer_norm(_image(xt, xt.shape[0], 1), p["ln_g"], p["ln_b"], eps))
+
+
 def xattn_tokens(xt, p, heads, ctx):
     """XATTN on tokens [N, C]: queries from x, keys/values from the image's own text tokens."""
     Q = xt @ p["wq"].astype(F64)
@@ -199,6 +242,21 @@ def xattn_tokens(xt, p, heads, ctx):
 def ffn_tokens(xt, p):
     """FFN(x) = x + (a * GELU(g)) W_2 + b_2, [a | g] = x W_1 + b_1 (value half first)."""
     h = xt @ p["w1"].astype(F64) + p["b1"].astype(F64)
+    F = h.shape[1] // 2
+    return xt + (h[:, :F] * gelu(h[:, F:])) @ p["w2"].astype(F64) + p["b2"].astype(F64)
+
+
+def lxattn_tokens(xt, p, heads, ctx, eps):
+    """LXATTN(x) = x + MHA(LN(x) W_q; ctx W_k, ctx W_v) W_o + b_o."""
+    Q = _ln_tokens(xt, p, eps) @ p["wq"].astype(F64)
+    K = ctx.astype(F64) @ p["wk"].astype(F64)
+    V = ctx.astype(F64) @ p["wv"].astype(F64)
+    return xt + attention(Q, K, V, heads) @ p["wo"].astype(F64) + p["bo"].astype(F64)
+
+
+def lffn_tokens(xt, p, eps):
+    """LFFN(x) = x + (a * GELU(g)) W_2 + b_2, [a | g] = LN(x) W_1 + b_1."""
+    h = _ln_tokens(xt, p, eps) @ p["w1"].astype(F64) + p["b1"].astype(F64)
     F = h.shape[1] // 2
     return xt + (h[:, :F] * gelu(h[:, F:])) @ p["w2"].astype(F64) + p["b2"].astype(F64)
 
@@ -226,8 +284,8 @@ def block_forward(z: np.ndarray, stages: Sequence[str], params: List[Dict[str, n
         reuse_px = np.repeat(np.repeat(np.asarray(reuse, dtype=bool), H // gh, axis=0), W // gw, axis=1)
     tokens = None                      # set once only sampled rows are carried
     if rows is not None:
-        last_ctx = max(i for i, s in enumerate(stages) if s in ("RES1", "RES2", "SATTN"))
-        assert stages[last_ctx] == "SATTN", "rows need a SATTN as the last context stage"
+        last_ctx = max(i for i, s in enumerate(stages) if s in ("RES1", "RES2", "SATTN", "LSATTN"))
+        assert stages[last_ctx] in ("SATTN", "LSATTN"), "rows need a self-attention as the last context stage"
     for si, (st, p) in enumerate(zip(stages, params)):
         key = f"{si}."
         if st == "RES1":
@@ -239,6 +297,17 @@ def block_forward(z: np.ndarray, stages: Sequence[str], params: List[Dict[str, n
                 tokens = sattn(x, p, G, heads, eps, reuse_px, cache, key, new_cache, rows=rows)
             else:
                 x = sattn(x, p, G, heads, eps, reuse_px, cache, key, new_cache)
+        elif st == "LSATTN":
+            if rows is not None and si == last_ctx:
+                tokens = lsattn(x, p, heads, eps, reuse_px, cache, key, new_cache, rows=rows)
+            else:
+                x = lsattn(x, p, heads, eps, reuse_px, cache, key, new_cache)
+        elif st in ("LXATTN", "LFFN"):
+            f = (lambda t: lxattn_tokens(t, p, heads, ctx, eps)) if st == "LXATTN" else (lambda t: lffn_tokens(t, p, eps))
+            if tokens is not None:
+                tokens = f(tokens)
+            else:
+                x = _image(f(_tokens(x)), H, W)
         elif st == "XATTN":
             if tokens is not None:
                 tokens = xattn_tokens(tokens, p, heads, ctx)

@@ -157,6 +157,83 @@ def _attn_three_pass(Q, K, V, heads):
     return out
 
 
+def test_layer_norm_closed_forms():
+    """Channels (1, 2, 3, 4): mean 5/2, biased variance 5/4, so with eps = 0 the result is (-3, -1, 1, 3) / sqrt 5;
+    a pixel whose channels are all equal gives beta exactly; each pixel is normalised on its own."""
+    u = np.zeros((4, 2, 3))
+    u[:, 0, 0] = [1, 2, 3, 4]
+    u[:, 1, 2] = 7.0
+    u[:, 0, 1] = [10, 20, 30, 40]                                   # a multiple: same normalised values
+    one, zero = np.ones(4), np.zeros(4)
+    y = ob.layer_norm(u, one, zero, 0.0 + 1e-300)
+    want = np.array([-3, -1, 1, 3]) / math.sqrt(5.0)
+    assert np.allclose(y[:, 0, 0], want, atol=1e-14) and np.allclose(y[:, 0, 1], want, atol=1e-14)
+    g, b = np.array([2.0, -1.0, 0.5, 3.0]), np.array([0.1, 0.2, 0.3, 0.4])
+    y = ob.layer_norm(u, g, b, 1e-5)
+    assert np.array_equal(y[:, 1, 2], b)                           # zero variance: only the shift is left
+    assert np.allclose(y[:, 0, 0], want * g * math.sqrt(1.25 / (1.25 + 1e-5)) + b, atol=1e-14)
+    # the channel axis is the one reduced: per-pixel mean 0 and variance var / (var + eps) before the affine map
+    z = wl.Stream(7, "ln").normal((6, 3, 5)).astype(np.float64)
+    n = ob.layer_norm(z, np.ones(6), np.zeros(6), 1e-5)
+    assert np.allclose(n.mean(axis=0), 0.0, atol=1e-14)
+    v = z.var(axis=0)
+    assert np.allclose(n.var(axis=0), v / (v + 1e-5), atol=1e-12)
+
+
+def test_layer_norm_vs_torch_library():
+    z = wl.Stream(8, "ln").normal((12, 4, 6)).astype(np.float64)
+    g, b = wl.Stream(8, "g").normal((12,)).astype(np.float64), wl.Stream(8, "b").normal((12,)).astype(np.float64)
+    ref = F.layer_norm(torch.from_numpy(z).permute(1, 2, 0), (12,), torch.from_numpy(g), torch.from_numpy(b), 1e-5)
+    assert np.allclose(ob.layer_norm(z, g, b, 1e-5), ref.permute(2, 0, 1).numpy(), atol=1e-12)
+
+
+def test_l_stages_act_per_pixel_where_they_should():
+    """LXATTN and LFFN see one pixel at a time: a crop of the input gives the crop of the output (so patching cannot
+    change them); LSATTN mixes the pixels of an image: the same crop test must fail for it."""
+    cfg = wl.custom_config([(6, 8)], (2, 2), C=16, G=4, heads=2, stages=(wl.LXATTN, wl.LFFN), ctx_len=5, ctx_dim=12, seed=17)
+    w = wl.make_workload(cfg)
+    z = w.images[0]
+    full, _ = ob.block_forward(z, cfg.stages, w.params, G=cfg.G, heads=cfg.heads, ctx=w.ctx[0])
+    crop, _ = ob.block_forward(z[:, 2:4, 3:7], cfg.stages, w.params, G=cfg.G, heads=cfg.heads, ctx=w.ctx[0])
+    assert np.allclose(crop, full[:, 2:4, 3:7], atol=1e-13)
+    cfg2 = wl.custom_config([(6, 8)], (2, 2), C=16, G=4, heads=2, stages=(wl.LSATTN,), seed=17)
+    w2 = wl.make_workload(cfg2)
+    full2, _ = ob.block_forward(z, cfg2.stages, w2.params, G=cfg2.G, heads=cfg2.heads)
+    crop2, _ = ob.block_forward(z[:, 2:4, 3:7], cfg2.stages, w2.params, G=cfg2.G, heads=cfg2.heads)
+    assert np.abs(crop2 - full2[:, 2:4, 3:7]).max() > 1e-3
+
+
+def test_lsattn_reuse_follows_operand_fill_rule():
+    """Mixed reuse through LSATTN with torch pieces: K and V of reused patches are the cached ones, queries and the
+    residual of computed patches are fresh, reused patches of the output are the cached output."""
+    cfg = wl.custom_config([(8, 8), (4, 8)], (4, 4), C=8, G=2, heads=2, stages=(wl.LSATTN, wl.LFFN), reuse_p=0.5, seed=3)
+    w = wl.make_workload(cfg)
+    assert set(w.cache) == {"0.K", "0.V", "y"}
+    y, nc = ob.forward_batch(w.images, cfg.stages, w.params, G=cfg.G, heads=cfg.heads, reuse=w.reuse, cache=w.cache)
+    t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    ph, pw = cfg.patch
+    for i, z in enumerate(w.images):
+        C, H, W = z.shape
+        m = t(np.kron(w.reuse[i].astype(np.float64), np.ones((ph, pw)))).bool()
+        mt = m.reshape(-1, 1)
+        p0, p1 = w.params
+        xt = t(z).flatten(1).T
+        u = F.layer_norm(xt, (C,), t(p0["ln_g"]), t(p0["ln_b"]), cfg.eps)
+        k = torch.where(mt, t(w.cache["0.K"][i]).flatten(1).T, u @ t(p0["wk"]))
+        v = torch.where(mt, t(w.cache["0.V"][i]).flatten(1).T, u @ t(p0["wv"]))
+        sp = lambda a: a.reshape(1, -1, cfg.heads, C // cfg.heads).transpose(1, 2)
+        o = F.scaled_dot_product_attention(sp(u @ t(p0["wq"])), sp(k), sp(v)).transpose(1, 2).reshape(-1, C)
+        r = xt + o @ t(p0["wo"]) + t(p0["bo"])
+        a, g = (F.layer_norm(r, (C,), t(p1["ln_g"]), t(p1["ln_b"]), cfg.eps) @ t(p1["w1"]) + t(p1["b1"])).chunk(2, dim=-1)
+        out = r + (a * F.gelu(g)) @ t(p1["w2"]) + t(p1["b2"])
+        out = torch.where(mt, t(w.cache["y"][i]).flatten(1).T, out).T.reshape(C, H, W).numpy()
+        mm = m.numpy()
+        # computed patches only: a reused patch's fresh values are never formed by the method
+        assert np.allclose(y[i][:, ~mm], out[:, ~mm], atol=1e-10)
+        assert np.array_equal(y[i][:, mm], w.cache["y"][i].astype(np.float64)[:, mm])
+        assert np.allclose(nc[i]["0.K"], k.T.reshape(C, H, W).numpy(), atol=1e-10)
+
+
 def test_attention_vs_three_pass_loops():
     Q, K, V = RNG.standard_normal((5, 6)), RNG.standard_normal((7, 6)), RNG.standard_normal((7, 6))
     assert np.allclose(ob.attention(Q, K, V, 2), _attn_three_pass(Q, K, V, 2), atol=1e-13)
@@ -226,11 +303,24 @@ def _torch_block(z, cfg, params, ctx):
             h = xt @ t(p["w1"]) + t(p["b1"])
             a, g = h.chunk(2, dim=-1)
             x = (xt + (a * F.gelu(g)) @ t(p["w2"]) + t(p["b2"])).transpose(1, 2).reshape(1, C, H, W)
+        elif st in (wl.LSATTN, wl.LXATTN, wl.LFFN):
+            xt = x.flatten(2).transpose(1, 2)
+            u = F.layer_norm(xt, (C,), t(p["ln_g"]), t(p["ln_b"]), cfg.eps)
+            if st == wl.LSATTN:
+                d = mha(u @ t(p["wq"]), u @ t(p["wk"]), u @ t(p["wv"])) @ t(p["wo"]) + t(p["bo"])
+            elif st == wl.LXATTN:
+                c = t(ctx)[None]
+                d = mha(u @ t(p["wq"]), c @ t(p["wk"]), c @ t(p["wv"])) @ t(p["wo"]) + t(p["bo"])
+            else:
+                a, g = (u @ t(p["w1"]) + t(p["b1"])).chunk(2, dim=-1)
+                d = (a * F.gelu(g)) @ t(p["w2"]) + t(p["b2"])
+            x = (xt + d).transpose(1, 2).reshape(1, C, H, W)
     return x[0].numpy()
 
 
 @pytest.mark.parametrize("stages", [
-    (wl.RES1, wl.SATTN), (wl.RES2,), (wl.SATTN, wl.XATTN, wl.FFN), (wl.RES2, wl.SATTN, wl.XATTN)])
+    (wl.RES1, wl.SATTN), (wl.RES2,), (wl.SATTN, wl.XATTN, wl.FFN), (wl.RES2, wl.SATTN, wl.XATTN),
+    (wl.LSATTN, wl.LXATTN, wl.LFFN), (wl.RES2, wl.LSATTN, wl.LFFN)])
 def test_block_vs_torch_composition(stages):
     cfg = wl.custom_config([(6, 8), (4, 4)], (2, 2), C=16, G=4, heads=2, stages=stages,
                            ctx_len=5, ctx_dim=12, seed=99)

@@ -113,6 +113,8 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
 
 # stage names of the block grammar
 RES1, RES2, SATTN, XATTN, FFN = "RES1", "RES2", "SATTN", "XATTN", "FFN"
+# the same three with a per-pixel LayerNorm in front (transformer layer of an SDXL level)
+LSATTN, LXATTN, LFFN = "LSATTN", "LXATTN", "LFFN"
 
 
 @dataclasses.dataclass
@@ -174,6 +176,9 @@ def config(cfg_id: int, seed: Optional[int] = None) -> Config:
     if cfg_id == 5:
         return Config(5, "skewed-reuse-c640", "bf16", [(256, 256)] + [(64, 64)] * 16, (32, 32),
                       640, 32, 10, 64, (RES2, SATTN), reuse_p=0.4, seed=s)
+    if cfg_id == 6:      # config 3 as a transformer layer with per-pixel LayerNorms (not a configuration of the baseline list)
+        return Config(6, "sdxl-transformer-ln-c640", "bf16", _draw_res(BASE_SEED + 3 if seed is None else seed, 8, (32, 48, 64)),
+                      (16, 16), 640, 32, 10, 64, (LSATTN, LXATTN, LFFN), ctx_len=77, ctx_dim=2048, seed=s)
     raise ValueError(f"unknown config {cfg_id}")
 
 
@@ -208,6 +213,11 @@ def stage_param_shapes(stage: str, cfg: Config) -> Dict[str, Tuple[Tuple[int, ..
     if stage == FFN:
         return {"w1": ((C, 2 * F), "w:%d" % C), "b1": ((2 * F,), "bias"),
                 "w2": ((F, C), "w:%d" % F), "b2": ((C,), "bias")}
+    if stage in (LSATTN, LXATTN, LFFN):
+        base = stage_param_shapes(stage[1:], cfg)
+        base.pop("gn_g", None)
+        base.pop("gn_b", None)
+        return {"ln_g": ((C,), "gamma"), "ln_b": ((C,), "beta"), **base}
     raise ValueError(stage)
 
 
@@ -217,6 +227,8 @@ def stage_cache_slots(stage: str) -> Tuple[str, ...]:
         return ("h1",)
     if stage == SATTN:
         return ("r", "K", "V")
+    if stage == LSATTN:
+        return ("K", "V")
     return ()
 
 
