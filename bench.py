@@ -42,6 +42,7 @@ def kernel_work(cfg, n_active_tokens, patch=None):
       gn_apply     2*b*C bytes per computed token (read + write); gn_apply_stitch (all tokens) adds b*C*ring per patch (rim writes)
       halo_gather  2*b*C*ring bytes per patch (read + write of the ring)
       reuse_copy   2*b*C bytes per token
+      layer_norm   2*b*C bytes per computed token (read + write)
     """
     b = 2 if cfg.dtype == "bf16" else 4
     C, T, Ta = cfg.C, cfg.T, n_active_tokens
@@ -67,6 +68,7 @@ def kernel_work(cfg, n_active_tokens, patch=None):
         "gn_apply_stitch": (0.0, 2.0 * b * C * T + 1.0 * b * C * ring * P),
         "halo_gather": (0.0, 2.0 * b * C * ring * Pa),
         "reuse_copy": (0.0, 2.0 * b * C * T),
+        "layer_norm": (0.0, 2.0 * b * C * Ta),
     }
 
 
@@ -75,7 +77,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (default: 2, the SDXL ResNet block)")
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5, or 6 = config 3 with per-token LayerNorms (default: 2, the SDXL ResNet block)")
     ap.add_argument("--patch", type=int, nargs=2, default=None, metavar=("PH", "PW"),
                     help="patch size override for the patch-size sweep (not for reuse configs: the mask is per patch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")

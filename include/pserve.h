@@ -47,6 +47,12 @@ extern "C" {
 #define PSERVE_SATTN  3   /* x + MHA(GN(x))W_o + b_o, keys = all tokens of the own image params: gn_g gn_b wq wk wv wo bo */
 #define PSERVE_XATTN  4   /* x + MHA(x W_q; ctx W_k, ctx W_v)W_o + b_o                  params: wq wk wv wo bo */
 #define PSERVE_FFN    5   /* x + (a * GELU(g))W_2 + b_2, [a|g] = x W_1 + b_1            params: w1 b1 w2 b2 */
+/* The three token stages with a per-token LayerNorm over the C channels in front (biased variance, desc.eps, affine):
+ * the transformer layer of an SDXL level.  A per-pixel operator needs nothing from other patches ("Patch-Tailored
+ * Diffusion Operators"), so LSATTN caches K and V only (no PSERVE_SLOT_R). */
+#define PSERVE_LSATTN 6   /* x + MHA(LN(x))W_o + b_o, keys = all tokens of the own image params: ln_g ln_b wq wk wv wo bo */
+#define PSERVE_LXATTN 7   /* x + MHA(LN(x) W_q; ctx W_k, ctx W_v)W_o + b_o              params: ln_g ln_b wq wk wv wo bo */
+#define PSERVE_LFFN   8   /* x + (a * GELU(g))W_2 + b_2, [a|g] = LN(x) W_1 + b_1        params: ln_g ln_b w1 b1 w2 b2 */
 
 #define PSERVE_MAX_STAGES 8
 #define PSERVE_MAX_PARAMS 8
@@ -67,8 +73,8 @@ extern "C" {
 /* cache slots of a stage (pserve_cache_load / pserve_cache_read); stage = -1 addresses the block output slot */
 #define PSERVE_SLOT_H1  0   /* RES2: output of the first convolution */
 #define PSERVE_SLOT_R   1   /* SATTN: stage input */
-#define PSERVE_SLOT_K   2   /* SATTN: keys */
-#define PSERVE_SLOT_V   3   /* SATTN: values */
+#define PSERVE_SLOT_K   2   /* SATTN, LSATTN: keys */
+#define PSERVE_SLOT_V   3   /* SATTN, LSATTN: values */
 #define PSERVE_SLOT_Y   4   /* block output (use stage = -1) */
 
 typedef struct pserve_plan_s pserve_plan_t;    /* CSP tables of one batch composition (host + device copies) */
@@ -86,12 +92,12 @@ typedef struct {
 
 typedef struct {
     int32_t n_stages;
-    int32_t stages[PSERVE_MAX_STAGES];   /* PSERVE_RES1 .. PSERVE_FFN, in execution order */
+    int32_t stages[PSERVE_MAX_STAGES];   /* PSERVE_RES1 .. PSERVE_LFFN, in execution order */
     int32_t C;          /* channels */
     int32_t G;          /* GroupNorm groups (C % G == 0) */
     int32_t heads;      /* attention heads (C % heads == 0) */
     int32_t dtype;      /* PSERVE_F32 | PSERVE_BF16 */
-    float   eps;        /* GroupNorm epsilon */
+    float   eps;        /* GroupNorm / LayerNorm epsilon */
     int32_t ctx_len;    /* text tokens per request (XATTN), else 0 */
     int32_t ctx_dim;    /* width of a text token (XATTN), else 0 */
     int32_t ffn_mult;   /* FFN hidden width = ffn_mult*C (W_1 is C x 2*ffn_mult*C) */

@@ -14,7 +14,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
 F32, BF16 = 0, 1
-STAGE_KIND = {"RES1": 1, "RES2": 2, "SATTN": 3, "XATTN": 4, "FFN": 5}
+STAGE_KIND = {"RES1": 1, "RES2": 2, "SATTN": 3, "XATTN": 4, "FFN": 5, "LSATTN": 6, "LXATTN": 7, "LFFN": 8}
 TABLES = {"perm": 0, "request_offset": 1, "res_offset": 2, "res_hw": 3, "patch_owner": 4,
           "patch_rc": 5, "neighbour": 6, "halo_src": 7, "cu_seqlens": 8}
 SLOT_H1, SLOT_R, SLOT_K, SLOT_V, SLOT_Y = 0, 1, 2, 3, 4
@@ -27,6 +27,9 @@ PARAM_ORDER = {
     "SATTN": ["gn_g", "gn_b", "wq", "wk", "wv", "wo", "bo"],
     "XATTN": ["wq", "wk", "wv", "wo", "bo"],
     "FFN": ["w1", "b1", "w2", "b2"],
+    "LSATTN": ["ln_g", "ln_b", "wq", "wk", "wv", "wo", "bo"],
+    "LXATTN": ["ln_g", "ln_b", "wq", "wk", "wv", "wo", "bo"],
+    "LFFN": ["ln_g", "ln_b", "w1", "b1", "w2", "b2"],
 }
 
 

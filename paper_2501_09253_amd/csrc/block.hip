@@ -204,6 +204,15 @@ static bool has_stage(const pserve_block_desc& d, int kind) {
         if (d.stages[i] == kind) return true;
     return false;
 }
+// stage families: the L-kinds are the token stages with a LayerNorm in front
+static bool is_sattn(int k) { return k == PSERVE_SATTN || k == PSERVE_LSATTN; }
+static bool is_xattn(int k) { return k == PSERVE_XATTN || k == PSERVE_LXATTN; }
+static bool is_ffn(int k) { return k == PSERVE_FFN || k == PSERVE_LFFN; }
+static bool has_ln(int k) { return k == PSERVE_LSATTN || k == PSERVE_LXATTN || k == PSERVE_LFFN; }
+template <typename F> static bool any_stage(const pserve_block_desc& d, F f) {
+    for (int s = 0; s < d.n_stages; ++s) if (f(d.stages[s])) return true;
+    return false;
+}
 
 static int dup_param(DevicePool& pool, const void* src, size_t bytes, void** dst, hipStream_t st) {
     PS_TRY(pool.alloc(dst, bytes));
@@ -274,17 +283,17 @@ int pserve_block_create(const pserve_block_desc* desc, const pserve_block_params
     PS_REQUIRE(d.C > 0 && d.G > 0 && d.C % d.G == 0, "pserve_block_create: C=%d must be a positive multiple of G=%d", d.C, d.G);
     PS_REQUIRE(d.C % (d.dtype == PSERVE_BF16 ? 8 : 4) == 0, "pserve_block_create: C=%d must be a multiple of 16 bytes", d.C);
     PS_REQUIRE(d.eps >= 0.f, "pserve_block_create: negative eps");
-    static const int nparams[6] = {0, 4, 8, 7, 5, 4};
+    static const int nparams[9] = {0, 4, 8, 7, 5, 4, 7, 7, 6};
     for (int s = 0; s < d.n_stages; ++s) {
         const int kind = d.stages[s];
-        PS_REQUIRE(kind >= PSERVE_RES1 && kind <= PSERVE_FFN, "pserve_block_create: stage %d has unknown kind %d", s, kind);
+        PS_REQUIRE(kind >= PSERVE_RES1 && kind <= PSERVE_LFFN, "pserve_block_create: stage %d has unknown kind %d", s, kind);
         for (int k = 0; k < nparams[kind]; ++k) PS_REQUIRE(params->p[s][k], "pserve_block_create: stage %d parameter %d is NULL", s, k);
-        if (kind == PSERVE_SATTN || kind == PSERVE_XATTN)
+        if (is_sattn(kind) || is_xattn(kind))
             PS_REQUIRE(d.heads > 0 && d.C % d.heads == 0 && d.C / d.heads <= 128,
                        "pserve_block_create: heads=%d must divide C=%d with head dim <= 128", d.heads, d.C);
-        if (kind == PSERVE_XATTN)
+        if (is_xattn(kind))
             PS_REQUIRE(d.ctx_len > 0 && d.ctx_dim > 0, "pserve_block_create: XATTN needs ctx_len and ctx_dim");
-        if (kind == PSERVE_FFN)
+        if (is_ffn(kind))
             PS_REQUIRE(d.ffn_mult > 0 && (d.ffn_mult * d.C) % GEGLU_GROUP == 0,
                        "pserve_block_create: FFN hidden width %d must be a multiple of %d", d.ffn_mult * d.C, GEGLU_GROUP);
     }
@@ -298,6 +307,11 @@ int pserve_block_create(const pserve_block_desc* desc, const pserve_block_params
     for (int s = 0; s < d.n_stages; ++s) {
         StageWeights& w = b->sw[s];
         const void* const* p = params->p[s];
+        if (d.stages[s] == PSERVE_LXATTN || d.stages[s] == PSERVE_LFFN) {     // ln_g ln_b, then the parameters of the plain kind
+            PS_TRY(dup_param(b->pool, p[0], es * C, &w.gn_g[0], st));
+            PS_TRY(dup_param(b->pool, p[1], es * C, &w.gn_b[0], st));
+            p += 2;
+        }
         switch (d.stages[s]) {
         case PSERVE_RES1:
         case PSERVE_RES2: {
@@ -312,7 +326,8 @@ int pserve_block_create(const pserve_block_desc* desc, const pserve_block_params
             }
             break;
         }
-        case PSERVE_SATTN: {
+        case PSERVE_SATTN:
+        case PSERVE_LSATTN: {                                                  // norm parameters first in both kinds
             PS_TRY(dup_param(b->pool, p[0], es * C, &w.gn_g[0], st));
             PS_TRY(dup_param(b->pool, p[1], es * C, &w.gn_b[0], st));
             PS_TRY(b->pool.alloc(&w.w[0], es * 3 * C * C));                       // fused [Wq | Wk | Wv]
@@ -323,7 +338,8 @@ int pserve_block_create(const pserve_block_desc* desc, const pserve_block_params
             PS_TRY(pack_bias(p[6], w.b[1], C, d.dtype, st));
             break;
         }
-        case PSERVE_XATTN: {
+        case PSERVE_XATTN:
+        case PSERVE_LXATTN: {
             const int D = d.ctx_dim;
             PS_TRY(b->pool.alloc(&w.w[0], es * C * C));
             PS_TRY(pack_linear(p[0], w.w[0], C, C, 0, d.dtype, st));
@@ -336,7 +352,8 @@ int pserve_block_create(const pserve_block_desc* desc, const pserve_block_params
             PS_TRY(pack_bias(p[4], w.b[1], C, d.dtype, st));
             break;
         }
-        case PSERVE_FFN: {
+        case PSERVE_FFN:
+        case PSERVE_LFFN: {
             const int F = d.ffn_mult * C;
             PS_TRY(b->pool.alloc(&w.w[0], es * 2 * F * C));
             PS_TRY(b->pool.alloc_t(&w.b[0], 2 * F));
@@ -381,16 +398,17 @@ int pserve_cache_create(const pserve_plan_t* plan, const pserve_block_t* block, 
     PS_TRY(c->pool.alloc(&c->ping[0], TC));
     PS_TRY(c->pool.alloc(&c->ping[1], TC));
     const bool conv = has_stage(d, PSERVE_RES1) || has_stage(d, PSERVE_RES2);
-    const bool sattn = has_stage(d, PSERVE_SATTN), xattn = has_stage(d, PSERVE_XATTN), ffn = has_stage(d, PSERVE_FFN);
+    const bool sattn = any_stage(d, is_sattn), xattn = any_stage(d, is_xattn), ffn = any_stage(d, is_ffn);
+    const bool gn_sattn = has_stage(d, PSERVE_SATTN);
     if (conv) PS_TRY(c->pool.alloc(&c->apad, (size_t)plan->P * (plan->ph + 2) * (plan->pw + 2) * d.C * es));
-    if (conv || sattn) {
+    if (conv || gn_sattn) {
         PS_TRY(c->pool.alloc_t(&c->partial, (size_t)plan->P * std::max<int64_t>(c->nsplit, plan->S / 64) * d.G * 2));
         PS_TRY(c->pool.alloc_t(&c->scale_shift, (size_t)plan->n * d.C * 2));
     }
     for (int s = 0; s < d.n_stages; ++s) {
         if (d.stages[s] == PSERVE_RES2) PS_TRY(c->pool.alloc(&c->h1[s], TC));
-        if (d.stages[s] == PSERVE_SATTN) {
-            if (with_slots) PS_TRY(c->pool.alloc(&c->r[s], TC));
+        if (is_sattn(d.stages[s])) {
+            if (with_slots && d.stages[s] == PSERVE_SATTN) PS_TRY(c->pool.alloc(&c->r[s], TC));
             PS_TRY(c->pool.alloc(&c->k[s], TC));
             PS_TRY(c->pool.alloc(&c->v[s], TC));
         }
@@ -399,7 +417,7 @@ int pserve_cache_create(const pserve_plan_t* plan, const pserve_block_t* block, 
         PS_TRY(c->pool.alloc(&c->q, TC));
         PS_TRY(c->pool.alloc(&c->o, TC));
     }
-    if (sattn) PS_TRY(c->pool.alloc(&c->u, TC));
+    if (sattn || any_stage(d, has_ln)) PS_TRY(c->pool.alloc(&c->u, TC));     // normalised stage input
     if (xattn) {
         // text keys / values: rows padded to a multiple of 8 per request and zero-filled once, so that the
         // padding rows (never written) contribute exact zeros; values transposed like the self-attention V
@@ -421,7 +439,7 @@ int pserve_cache_create(const pserve_plan_t* plan, const pserve_block_t* block, 
     PS_TRY(c->pool.alloc_t(&c->count, 1));
     {
         int n_x = 0, at = -1;
-        for (int k = 0; k < d.n_stages; ++k) if (d.stages[k] == PSERVE_XATTN) { ++n_x; at = k; }
+        for (int k = 0; k < d.n_stages; ++k) if (is_xattn(d.stages[k])) { ++n_x; at = k; }
         if (n_x == 1 && at > 0) {                  // something runs before it: worth a stream of its own
             PS_CHECK_HIP(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
             PS_CHECK_HIP(hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
@@ -450,8 +468,8 @@ static int slot_ptr(const pserve_cache_t* c, int stage, int slot, void** ptr, bo
     void* p = nullptr;
     if (slot == PSERVE_SLOT_H1 && d.stages[stage] == PSERVE_RES2) p = c->h1[stage];
     else if (slot == PSERVE_SLOT_R && d.stages[stage] == PSERVE_SATTN) p = c->r[stage];
-    else if (slot == PSERVE_SLOT_K && d.stages[stage] == PSERVE_SATTN) p = c->k[stage];
-    else if (slot == PSERVE_SLOT_V && d.stages[stage] == PSERVE_SATTN) { p = c->v[stage]; *transposed = c->v_transposed; }
+    else if (slot == PSERVE_SLOT_K && is_sattn(d.stages[stage])) p = c->k[stage];
+    else if (slot == PSERVE_SLOT_V && is_sattn(d.stages[stage])) { p = c->v[stage]; *transposed = c->v_transposed; }
     PS_REQUIRE(p, "cache slot: stage %d has no slot %d", stage, slot);
     *ptr = p;
     return PSERVE_OK;
@@ -543,7 +561,7 @@ int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* c
     PS_REQUIRE(x != y, "pserve_block_forward: x and y must not alias");
     PS_REQUIRE(cache->plan == plan && cache->block == block, "pserve_block_forward: cache belongs to another plan or block");
     const pserve_block_desc& d = block->desc;
-    PS_REQUIRE(ctx || !has_stage(d, PSERVE_XATTN), "pserve_block_forward: XATTN stage needs ctx");
+    PS_REQUIRE(ctx || !any_stage(d, is_xattn), "pserve_block_forward: XATTN stage needs ctx");
     if (reuse_mask) {
         if (!cache->with_slots) { set_error("pserve_block_forward: reuse mask given but the cache has no slots"); return PSERVE_ESTATE; }
         if (!cache->filled) { set_error("pserve_block_forward: reuse mask given but the cache was never filled"); return PSERVE_ESTATE; }
@@ -657,18 +675,25 @@ int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* c
             PS_TRY(norm_conv(cur, w, 0, nullptr, cache->h1[si], true));
             PS_TRY(norm_conv(cache->h1[si], w, 1, cur, out, false));
             break;
-        case PSERVE_SATTN: {
+        case PSERVE_SATTN:
+        case PSERVE_LSATTN: {
+            const bool ln = d.stages[si] == PSERVE_LSATTN;
             const void* rin = cur;
-            if (cache->with_slots && cur != cache->r[si]) {           // first stage: merge fresh input into the slot
+            if (!ln && cache->with_slots && cur != cache->r[si]) {    // first stage: merge fresh input into the slot
                 ProfScope ps("reuse_copy", st);
                 copy_patches_kernel<<<copy_grid, 256, 0, st>>>((const uint4*)cur, (uint4*)cache->r[si], vec_per_patch,
                                                                reuse_mask, reuse_mask ? 1 : 0);
                 PS_TRY(check_launch("copy_patches_kernel"));
                 rin = cache->r[si];
             }
-            GroupNormArgs ga = gn_args(rin, w.gn_g[0], w.gn_b[0]);
-            { ProfScope ps("gn_stats", st); PS_TRY(gn_stats(ga, gm, dt, st)); }
-            { ProfScope ps("gn_apply", st); PS_TRY(gn_apply(ga, gm, dt, false, false, false, cache->u, act, st)); }
+            if (ln) {                                                 // per token: nothing of the reused patches is needed
+                ProfScope ps("layer_norm", st);
+                PS_TRY(layer_norm(rin, w.gn_g[0], w.gn_b[0], C, d.eps, gm, dt, cache->u, act, st));
+            } else {
+                GroupNormArgs ga = gn_args(rin, w.gn_g[0], w.gn_b[0]);
+                { ProfScope ps("gn_stats", st); PS_TRY(gn_stats(ga, gm, dt, st)); }
+                { ProfScope ps("gn_apply", st); PS_TRY(gn_apply(ga, gm, dt, false, false, false, cache->u, act, st)); }
+            }
             GemmArgs g = base_gemm(cache->u, C, C, 3 * C, w.w[0], nullptr);
             g.seg_cols = C;
             g.seg[0].ptr = cache->q; g.seg[0].ld = C; g.seg[0].scale = qscale;
@@ -689,10 +714,17 @@ int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* c
             { ProfScope ps("linear_out", st); PS_TRY(gemm(go, dt, mode, st)); }
             break;
         }
-        case PSERVE_XATTN: {
+        case PSERVE_XATTN:
+        case PSERVE_LXATTN: {
             if (cache->side_stage == si) PS_CHECK_HIP(hipStreamWaitEvent(st, cache->ev_join, 0));     // join
             else PS_TRY(ctx_kv(w, st));
-            GemmArgs gq = base_gemm(cur, C, C, C, w.w[0], nullptr);
+            const void* qin = cur;
+            if (d.stages[si] == PSERVE_LXATTN) {
+                ProfScope ps("layer_norm", st);
+                PS_TRY(layer_norm(cur, w.gn_g[0], w.gn_b[0], C, d.eps, gm, dt, cache->u, act, st));
+                qin = cache->u;
+            }
+            GemmArgs gq = base_gemm(qin, C, C, C, w.w[0], nullptr);
             gq.seg[0].ptr = cache->q; gq.seg[0].ld = C; gq.seg[0].scale = qscale;
             { ProfScope ps("linear_q", st); PS_TRY(gemm(gq, dt, mode, st)); }
             AttnArgs aa{};
@@ -709,9 +741,16 @@ int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* c
             { ProfScope ps("linear_out", st); PS_TRY(gemm(go, dt, mode, st)); }
             break;
         }
-        case PSERVE_FFN: {
+        case PSERVE_FFN:
+        case PSERVE_LFFN: {
             const int F = d.ffn_mult * C;
-            GemmArgs g1 = base_gemm(cur, C, C, 2 * F, w.w[0], w.b[0]);
+            const void* fin = cur;
+            if (d.stages[si] == PSERVE_LFFN) {
+                ProfScope ps("layer_norm", st);
+                PS_TRY(layer_norm(cur, w.gn_g[0], w.gn_b[0], C, d.eps, gm, dt, cache->u, act, st));
+                fin = cache->u;
+            }
+            GemmArgs g1 = base_gemm(fin, C, C, 2 * F, w.w[0], w.b[0]);
             g1.epi = EPI_GEGLU;
             g1.seg[0].ptr = cache->hidden; g1.seg[0].ld = F;
             { ProfScope ps("ffn_geglu", st); PS_TRY(gemm(g1, dt, mode, st)); }

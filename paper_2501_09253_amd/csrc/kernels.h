@@ -58,6 +58,10 @@ int gn_finalize(const GroupNormArgs& a, const PatchGeom& g, int dtype, int32_t s
 // border tokens also fill the neighbours' ring slots / zero the own ring at image edges (no halo_gather needed).
 int gn_apply(const GroupNormArgs& a, const PatchGeom& g, int dtype, bool silu, bool padded, bool stitch, void* out,
              ActiveList act, hipStream_t st);
+// Per-token LayerNorm over the C channels (biased variance, affine gamma / beta of the block dtype) of the patches of
+// `act`; out [T][C] at the same token positions.
+int layer_norm(const void* x, const void* gamma, const void* beta, int32_t C, float eps, const PatchGeom& g, int dtype,
+               void* out, ActiveList act, hipStream_t st);
 // Fill the one-pixel ring of every active padded patch from the interiors of its neighbours (zeros outside the image).
 int halo_gather(void* apad, const int32_t* halo_src, const PatchGeom& g, int32_t C, int32_t ring, int dtype,
                 ActiveList act, hipStream_t st);

@@ -274,6 +274,70 @@ __global__ void gn_apply_kernel(const T* __restrict__ x, const float* __restrict
     }
 }
 
+// ---- per-token LayerNorm over the channels -------------------------------------------------------------------
+// LPT lanes (a power of two) share a token; lane `sub` holds the 16-byte vectors sub, sub + LPT, ... (VPL of them) of
+// the row in registers.  Mean, then variance around it (two passes over the registers), each reduced by a butterfly
+// over the LPT lanes; fp32 throughout.  One 16-byte load and one 16-byte store per vector: 2*b*C bytes per token.
+template <typename T, int VPL>
+__global__ void __launch_bounds__(256)
+layer_norm_kernel(const T* __restrict__ x, const T* __restrict__ gamma, const T* __restrict__ beta, int32_t C, int32_t S,
+                  int32_t LPT, float eps, ActiveList act, T* __restrict__ out) {
+    constexpr int VN = Vec<T>::N;
+    int p = blockIdx.x;
+    if (act.active) {
+        if (p >= *act.count) return;
+        p = act.active[p];
+    }
+    const int CV = C / VN;
+    const int sub = threadIdx.x % LPT, tl = threadIdx.x / LPT, tpb = blockDim.x / LPT;
+    uint4 graw[VPL], braw[VPL];
+#pragma unroll
+    for (int k = 0; k < VPL; ++k) {
+        const int cv = min(sub + k * LPT, CV - 1);
+        graw[k] = *reinterpret_cast<const uint4*>(gamma + cv * VN);
+        braw[k] = *reinterpret_cast<const uint4*>(beta + cv * VN);
+    }
+    const float inv_c = 1.f / (float)C;
+    for (int t = blockIdx.y * tpb + tl; t < S; t += gridDim.y * tpb) {
+        const int64_t row = ((int64_t)p * S + t) * C;
+        float v[VPL][VN];
+        float s1 = 0.f;
+#pragma unroll
+        for (int k = 0; k < VPL; ++k) {
+            const int cv = sub + k * LPT;
+            if (cv < CV) {
+                load_vec<T>(x + row + cv * VN, v[k]);
+#pragma unroll
+                for (int e = 0; e < VN; ++e) s1 += v[k][e];
+            }
+        }
+        for (int m = LPT >> 1; m > 0; m >>= 1) s1 += __shfl_xor(s1, m, 64);
+        const float mean = s1 * inv_c;
+        float s2 = 0.f;
+#pragma unroll
+        for (int k = 0; k < VPL; ++k) {
+            if (sub + k * LPT < CV) {
+#pragma unroll
+                for (int e = 0; e < VN; ++e) { v[k][e] -= mean; s2 = fmaf(v[k][e], v[k][e], s2); }
+            }
+        }
+        for (int m = LPT >> 1; m > 0; m >>= 1) s2 += __shfl_xor(s2, m, 64);
+        const float rstd = 1.f / sqrtf(s2 * inv_c + eps);
+#pragma unroll
+        for (int k = 0; k < VPL; ++k) {
+            const int cv = sub + k * LPT;
+            if (cv < CV) {
+                float g[VN], b[VN];
+                unpack_vec<T>(graw[k], g);
+                unpack_vec<T>(braw[k], b);
+#pragma unroll
+                for (int e = 0; e < VN; ++e) v[k][e] = fmaf(v[k][e] * rstd, g[e], b[e]);
+                store_vec<T>(out + row + cv * VN, v[k]);
+            }
+        }
+    }
+}
+
 // one thread per (ring entry, channel vector) of an active patch
 template <typename T>
 __global__ void halo_gather_kernel(T* __restrict__ apad, const int32_t* __restrict__ halo_src, PatchGeom gm,
@@ -374,6 +438,36 @@ int gn_apply(const GroupNormArgs& a, const PatchGeom& g, int dtype, bool silu, b
     if (dtype == PSERVE_BF16) launch_apply<uint16_t>(a, g, silu, padded, stitch, out, act, CV, TL, st);
     else launch_apply<float>(a, g, silu, padded, stitch, out, act, CV, TL, st);
     return check_launch("gn_apply_kernel");
+}
+
+template <typename T>
+static void launch_layer_norm(const void* x, const void* gamma, const void* beta, int32_t C, float eps, const PatchGeom& g,
+                              void* out, ActiveList act, int LPT, int VPL, hipStream_t st) {
+    const int tpb = 256 / LPT;
+    // one token per lane group while that gives at most ~16 blocks per CU, else more tokens per group
+    int64_t per = 1;
+    while (per < 8 && g.P * cdiv(g.S, tpb * per) > 4096) per *= 2;
+    dim3 grid(g.P, (unsigned)std::max<int64_t>(1, std::min<int64_t>(cdiv(g.S, tpb * per), 65535)));
+#define PS_LN(V) case V: layer_norm_kernel<T, V><<<grid, 256, 0, st>>>((const T*)x, (const T*)gamma, (const T*)beta, C, g.S, LPT, eps, act, (T*)out); break
+    switch (VPL) { PS_LN(1); PS_LN(2); PS_LN(3); PS_LN(4); PS_LN(5); PS_LN(6); PS_LN(7); PS_LN(8); }
+#undef PS_LN
+}
+
+int layer_norm(const void* x, const void* gamma, const void* beta, int32_t C, float eps, const PatchGeom& g, int dtype,
+               void* out, ActiveList act, hipStream_t st) {
+    const int vn = dtype == PSERVE_BF16 ? 8 : 4;
+    PS_REQUIRE(C % vn == 0, "LayerNorm: C=%d must be a multiple of %d for this dtype", C, vn);
+    const int CV = C / vn;
+    PS_REQUIRE(CV <= 512, "LayerNorm: C=%d too wide", C);
+    // lanes per token: the power of two that wastes the fewest vector slots (ties: more lanes)
+    int LPT = 64, VPL = (int)cdiv(CV, 64), waste = VPL * 64 - CV;
+    for (int l = 32; l >= 1; l >>= 1) {
+        const int v = (int)cdiv(CV, l);
+        if (v <= 8 && v * l - CV < waste) { LPT = l; VPL = v; waste = v * l - CV; }
+    }
+    if (dtype == PSERVE_BF16) launch_layer_norm<uint16_t>(x, gamma, beta, C, eps, g, out, act, LPT, VPL, st);
+    else launch_layer_norm<float>(x, gamma, beta, C, eps, g, out, act, LPT, VPL, st);
+    return check_launch("layer_norm_kernel");
 }
 
 int halo_gather(void* apad, const int32_t* halo_src, const PatchGeom& g, int32_t C, int32_t ring, int dtype,

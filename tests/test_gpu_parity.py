@@ -4,6 +4,8 @@ Bars: planner tables, split/reassembly and reused-patch outputs bit-exact; fp32 
 1e-4 * max|ref|; bf16 blocks within 2e-2 * max|ref| (both sides consume the same bf16-rounded
 inputs and weights; the oracle never rounds intermediates).
 """
+import math
+
 import numpy as np
 import pytest
 import torch
@@ -75,6 +77,9 @@ SMALL = [
     ((wl.RES1,), "f32"), ((wl.RES2,), "f32"), ((wl.SATTN,), "f32"), ((wl.XATTN,), "f32"), ((wl.FFN,), "f32"),
     ((wl.RES1, wl.SATTN), "f32"), ((wl.RES2, wl.SATTN, wl.XATTN, wl.FFN), "f32"),
     ((wl.RES2,), "bf16"), ((wl.SATTN, wl.XATTN, wl.FFN), "bf16"), ((wl.RES2, wl.SATTN, wl.XATTN), "bf16"),
+    # the token stages with a per-token LayerNorm in front
+    ((wl.LSATTN,), "f32"), ((wl.LXATTN,), "f32"), ((wl.LFFN,), "f32"), ((wl.RES2, wl.LSATTN, wl.LXATTN, wl.LFFN), "f32"),
+    ((wl.LSATTN, wl.LXATTN, wl.LFFN), "bf16"), ((wl.SATTN, wl.LFFN), "bf16"),
 ]
 
 
@@ -98,7 +103,8 @@ def test_small_blocks(stages, dtype, mode):
                                          # ragged last M tile with 64-token patches (the convolution that also leaves the
                                          # next norm's partial sums must skip the rows past the end): T = 192 and T = 320
                                          (64, [(8, 8), (8, 16)], (8, 8)), (320, [(8, 8), (16, 16)], (8, 8))])
-@pytest.mark.parametrize("stages", [(wl.RES2,), (wl.SATTN, wl.XATTN, wl.FFN), (wl.RES1, wl.SATTN)])
+@pytest.mark.parametrize("stages", [(wl.RES2,), (wl.SATTN, wl.XATTN, wl.FFN), (wl.RES1, wl.SATTN),
+                                    (wl.LSATTN, wl.LXATTN, wl.LFFN)])
 def test_mfma_shapes_bf16(stages, C, res, patch):
     """bf16 blocks whose widths take the MFMA kernels (C multiple of 64, head dim 64), ragged M tails included."""
     cfg = wl.custom_config(res, patch, C=C, G=32, heads=C // 64, stages=stages, dtype="bf16", ctx_len=77, ctx_dim=128,
@@ -132,9 +138,23 @@ def test_batch_independence_on_gpu():
     assert np.abs(full[1] - alone[0]).max() < 1e-5 * np.abs(alone[0]).max()
 
 
+@pytest.mark.parametrize("dtype,C", [("f32", 4), ("f32", 40), ("f32", 72), ("bf16", 8), ("bf16", 24), ("bf16", 320),
+                                     ("bf16", 1280), ("f32", 1280)])
+def test_layer_norm_widths(dtype, C):
+    """LayerNorm over 1 .. 160 vectors per token (every lanes-per-token / vectors-per-lane split), seen through LFFN."""
+    mult = 64 // math.gcd(C, 64)                      # hidden width a multiple of 64
+    cfg = wl.custom_config([(4, 12), (4, 4)], (4, 4), C=C, G=1, heads=1, stages=(wl.LFFN,), dtype=dtype, seed=41,
+                           ffn_mult=mult)
+    w = wl.make_workload(cfg)
+    got = GpuRun(w).forward_images()
+    ref, _ = _oracle(w)
+    assert rel_err(got, ref) < tolerance(dtype)
+
+
 # ----------------------------------------------------------------------------- reuse
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("stages", [(wl.RES2, wl.SATTN), (wl.SATTN,), (wl.RES2,), (wl.SATTN, wl.XATTN, wl.FFN)])
+@pytest.mark.parametrize("stages", [(wl.RES2, wl.SATTN), (wl.SATTN,), (wl.RES2,), (wl.SATTN, wl.XATTN, wl.FFN),
+                                    (wl.LSATTN, wl.LXATTN, wl.LFFN), (wl.RES2, wl.LSATTN)])
 def test_reuse_small(stages, dtype):
     cfg = wl.custom_config([(16, 16), (8, 8), (8, 16)], (4, 4), C=32, G=4, heads=2, stages=stages, dtype=dtype,
                            ctx_len=5, ctx_dim=16, reuse_p=0.4, seed=21)
@@ -206,7 +226,7 @@ def test_config1_fp32():
     assert rel_err(got, ref) < 1e-4
 
 
-@pytest.mark.parametrize("cfg_id", [2, 3, 4])
+@pytest.mark.parametrize("cfg_id", [2, 3, 4, 6])
 def test_config_bf16_full_size(cfg_id):
     w = wl.make_workload(wl.config(cfg_id))
     got = GpuRun(w).forward_images()
