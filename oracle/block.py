@@ -30,6 +30,10 @@ Readings of points the paper leaves open (each also listed in the design notes):
     lists such per-pixel operators among those that patching leaves untouched,
     Patch-Tailored Diffusion Operators): biased variance, same eps, per-channel affine.
     Nothing of a reused patch's input is needed by them, so only K and V are cached.
+  * RES2T is RES2 with the time embedding of the first model's residual block: the
+    request's embedding vector goes through SiLU and a linear layer, and the resulting
+    C values are added to every pixel of the first convolution's output (a per-pixel
+    operator with a per-request operand; the cached h1 of a reused patch includes it).
   * cache reuse (Patch-aware Caching Strategy, steps 3-5): at each operator that
     needs context the operand of a reused patch is the cached tensor of the
     previous step; after the block the reused patches of the output are replaced by
@@ -181,6 +185,19 @@ def res2(x, p, G, eps, reuse_px=None, cache=None, key="", new_cache=None):
     return x + conv3(silu(group_norm(h1, p["gn_b_g"], p["gn_b_b"], G, eps)), p["conv_b_w"], p["conv_b_b"])
 
 
+def res2t(x, p, G, eps, temb, reuse_px=None, cache=None, key="", new_cache=None):
+    """RES2T(x) = x + conv3_b(SiLU(GN_b(h1))),  h1 = conv3_a(SiLU(GN_a(x))) + (SiLU(temb) W_t + b_t)[:, None, None].
+
+    temb: the request's embedding vector [D].  With reuse, h1 of reused patches is the cached h1.
+    """
+    e = silu(np.asarray(temb, dtype=F64)) @ p["wt"].astype(F64) + p["bt"].astype(F64)
+    h1 = conv3(silu(group_norm(x, p["gn_a_g"], p["gn_a_b"], G, eps)), p["conv_a_w"], p["conv_a_b"]) + e[:, None, None]
+    if reuse_px is not None:
+        h1 = _fill(h1, cache[key + "h1"], reuse_px)
+        new_cache[key + "h1"] = h1
+    return x + conv3(silu(group_norm(h1, p["gn_b_g"], p["gn_b_b"], G, eps)), p["conv_b_w"], p["conv_b_b"])
+
+
 def sattn(x, p, G, heads, eps, reuse_px=None, cache=None, key="", new_cache=None, rows=None):
     """SATTN(x) = x + concat_h(softmax(Q_h K_h^T / sqrt d) V_h) W_o + b_o, Q/K/V = GN(x) W_{q,k,v}.
 
@@ -265,7 +282,7 @@ def lffn_tokens(xt, p, eps):
 def block_forward(z: np.ndarray, stages: Sequence[str], params: List[Dict[str, np.ndarray]], *,
                   G: int, heads: int, eps: float = 1e-5, ctx: Optional[np.ndarray] = None,
                   reuse: Optional[np.ndarray] = None, cache: Optional[Dict[str, np.ndarray]] = None,
-                  rows: Optional[np.ndarray] = None):
+                  rows: Optional[np.ndarray] = None, temb: Optional[np.ndarray] = None):
     """Run the stage list on ONE image z[C, H, W]; returns (out, new_cache).
 
     reuse: bool [gh, gw] over the image's patch grid (True = reuse the cached
@@ -284,7 +301,7 @@ def block_forward(z: np.ndarray, stages: Sequence[str], params: List[Dict[str, n
         reuse_px = np.repeat(np.repeat(np.asarray(reuse, dtype=bool), H // gh, axis=0), W // gw, axis=1)
     tokens = None                      # set once only sampled rows are carried
     if rows is not None:
-        last_ctx = max(i for i, s in enumerate(stages) if s in ("RES1", "RES2", "SATTN", "LSATTN"))
+        last_ctx = max(i for i, s in enumerate(stages) if s in ("RES1", "RES2", "RES2T", "SATTN", "LSATTN"))
         assert stages[last_ctx] in ("SATTN", "LSATTN"), "rows need a self-attention as the last context stage"
     for si, (st, p) in enumerate(zip(stages, params)):
         key = f"{si}."
@@ -292,6 +309,8 @@ def block_forward(z: np.ndarray, stages: Sequence[str], params: List[Dict[str, n
             x = res1(x, p, G, eps)
         elif st == "RES2":
             x = res2(x, p, G, eps, reuse_px, cache, key, new_cache)
+        elif st == "RES2T":
+            x = res2t(x, p, G, eps, temb, reuse_px, cache, key, new_cache)
         elif st == "SATTN":
             if rows is not None and si == last_ctx:
                 tokens = sattn(x, p, G, heads, eps, reuse_px, cache, key, new_cache, rows=rows)
@@ -332,14 +351,15 @@ def block_forward(z: np.ndarray, stages: Sequence[str], params: List[Dict[str, n
     return x, new_cache
 
 
-def forward_batch(images, stages, params, *, G, heads, eps=1e-5, ctx=None, reuse=None, cache=None):
+def forward_batch(images, stages, params, *, G, heads, eps=1e-5, ctx=None, reuse=None, cache=None, temb=None):
     """Run block_forward on every image of a batch, one at a time (caller order)."""
     outs, caches = [], []
     for i, z in enumerate(images):
         c_i = None if cache is None else {k: v[i] for k, v in cache.items()}
         y, nc = block_forward(z, stages, params, G=G, heads=heads, eps=eps,
                               ctx=None if ctx is None else ctx[i],
-                              reuse=None if reuse is None else reuse[i], cache=c_i)
+                              reuse=None if reuse is None else reuse[i], cache=c_i,
+                              temb=None if temb is None else temb[i])
         outs.append(y)
         caches.append(nc)
     return outs, caches

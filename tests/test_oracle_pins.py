@@ -234,6 +234,36 @@ def test_lsattn_reuse_follows_operand_fill_rule():
         assert np.allclose(nc[i]["0.K"], k.T.reshape(C, H, W).numpy(), atol=1e-10)
 
 
+def test_res2t_time_embedding_closed_forms():
+    """W_t = 0, b_t = 0 gives RES2; a zero embedding adds b_t alone (SiLU(0) = 0); the added term is the same for every
+    pixel of a request and differs between requests: with conv_a = 0 the first convolution's output is the term itself
+    (slot h1 under an all-compute mask), e = SiLU(temb) W_t + b_t computed here by a plain loop."""
+    cfg = wl.custom_config([(4, 6), (4, 4)], (2, 2), C=8, G=2, heads=1, stages=(wl.RES2T,), seed=12, temb_dim=5)
+    w = wl.make_workload(cfg)
+    p = dict(w.params[0])
+    kw = dict(G=cfg.G, heads=cfg.heads, eps=cfg.eps)
+    plain, _ = ob.forward_batch(w.images, (wl.RES2,), [p], **kw)
+    p0 = dict(p, wt=np.zeros_like(p["wt"]), bt=np.zeros_like(p["bt"]))
+    y0, _ = ob.forward_batch(w.images, cfg.stages, [p0], temb=w.temb, **kw)
+    for a, b in zip(plain, y0):
+        assert np.array_equal(a, b)
+    pz = dict(p, conv_a_w=np.zeros_like(p["conv_a_w"]), conv_a_b=np.zeros_like(p["conv_a_b"]))
+    none = [np.zeros((h // 2, w_ // 2), dtype=bool) for h, w_ in cfg.resolutions]
+    dummy = {"0.h1": [np.zeros_like(z) for z in w.images], "y": [np.zeros_like(z) for z in w.images]}
+    _, nc = ob.forward_batch(w.images, cfg.stages, [pz], temb=w.temb, reuse=none, cache=dummy, **kw)
+    for i in range(cfg.n):
+        e = np.zeros(8)
+        for c in range(8):
+            acc = float(p["bt"][c])
+            for k in range(5):
+                tk = float(w.temb[i][k])
+                acc += tk / (1.0 + math.exp(-tk)) * float(p["wt"][k, c])
+            e[c] = acc
+        assert np.allclose(nc[i]["0.h1"], np.broadcast_to(e[:, None, None], w.images[i].shape), atol=1e-13)
+    _, ncz = ob.forward_batch(w.images, cfg.stages, [pz], temb=np.zeros_like(w.temb), reuse=none, cache=dummy, **kw)
+    assert np.allclose(ncz[0]["0.h1"], np.broadcast_to(p["bt"].astype(np.float64)[:, None, None], w.images[0].shape), atol=1e-15)
+
+
 def test_attention_vs_three_pass_loops():
     Q, K, V = RNG.standard_normal((5, 6)), RNG.standard_normal((7, 6)), RNG.standard_normal((7, 6))
     assert np.allclose(ob.attention(Q, K, V, 2), _attn_three_pass(Q, K, V, 2), atol=1e-13)
@@ -267,7 +297,7 @@ def test_attention_vs_torch_library():
 
 
 # ----------------------------------------------------------------------------- whole block vs torch composition
-def _torch_block(z, cfg, params, ctx):
+def _torch_block(z, cfg, params, ctx, temb=None):
     """The block grammar composed from torch CPU library routines in float64 (independent of the oracle)."""
     x = torch.from_numpy(np.asarray(z, dtype=np.float64))[None]
     t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
@@ -287,6 +317,12 @@ def _torch_block(z, cfg, params, ctx):
         elif st == wl.RES2:
             h = F.conv2d(F.silu(F.group_norm(x, cfg.G, t(p["gn_a_g"]), t(p["gn_a_b"]), cfg.eps)),
                          t(p["conv_a_w"]), t(p["conv_a_b"]), padding=1)
+            x = x + F.conv2d(F.silu(F.group_norm(h, cfg.G, t(p["gn_b_g"]), t(p["gn_b_b"]), cfg.eps)),
+                             t(p["conv_b_w"]), t(p["conv_b_b"]), padding=1)
+        elif st == wl.RES2T:
+            e = F.linear(F.silu(t(temb)), t(p["wt"]).T, t(p["bt"]))
+            h = F.conv2d(F.silu(F.group_norm(x, cfg.G, t(p["gn_a_g"]), t(p["gn_a_b"]), cfg.eps)),
+                         t(p["conv_a_w"]), t(p["conv_a_b"]), padding=1) + e[None, :, None, None]
             x = x + F.conv2d(F.silu(F.group_norm(h, cfg.G, t(p["gn_b_g"]), t(p["gn_b_b"]), cfg.eps)),
                              t(p["conv_b_w"]), t(p["conv_b_b"]), padding=1)
         elif st == wl.SATTN:
@@ -320,14 +356,15 @@ def _torch_block(z, cfg, params, ctx):
 
 @pytest.mark.parametrize("stages", [
     (wl.RES1, wl.SATTN), (wl.RES2,), (wl.SATTN, wl.XATTN, wl.FFN), (wl.RES2, wl.SATTN, wl.XATTN),
-    (wl.LSATTN, wl.LXATTN, wl.LFFN), (wl.RES2, wl.LSATTN, wl.LFFN)])
+    (wl.LSATTN, wl.LXATTN, wl.LFFN), (wl.RES2, wl.LSATTN, wl.LFFN), (wl.RES2T, wl.LSATTN)])
 def test_block_vs_torch_composition(stages):
     cfg = wl.custom_config([(6, 8), (4, 4)], (2, 2), C=16, G=4, heads=2, stages=stages,
-                           ctx_len=5, ctx_dim=12, seed=99)
+                           ctx_len=5, ctx_dim=12, seed=99, temb_dim=10)
     w = wl.make_workload(cfg)
     for i, z in enumerate(w.images):
-        y, _ = ob.block_forward(z, cfg.stages, w.params, G=cfg.G, heads=cfg.heads, eps=cfg.eps, ctx=w.ctx[i])
-        ref = _torch_block(z, cfg, w.params, w.ctx[i])
+        y, _ = ob.block_forward(z, cfg.stages, w.params, G=cfg.G, heads=cfg.heads, eps=cfg.eps, ctx=w.ctx[i],
+                                temb=w.temb[i])
+        ref = _torch_block(z, cfg, w.params, w.ctx[i], w.temb[i])
         assert np.allclose(y, ref, atol=1e-10), np.abs(y - ref).max()
 
 

@@ -115,6 +115,8 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
 RES1, RES2, SATTN, XATTN, FFN = "RES1", "RES2", "SATTN", "XATTN", "FFN"
 # the same three with a per-pixel LayerNorm in front (transformer layer of an SDXL level)
 LSATTN, LXATTN, LFFN = "LSATTN", "LXATTN", "LFFN"
+# RES2 with the per-request time embedding added after the first convolution (residual block of an SDXL level)
+RES2T = "RES2T"
 
 
 @dataclasses.dataclass
@@ -135,6 +137,7 @@ class Config:
     reuse_p: float = 0.0
     eps: float = 1e-5
     seed: int = 0
+    temb_dim: int = 0                # width of the per-request time embedding (RES2T), else 0
 
     @property
     def n(self) -> int:
@@ -179,15 +182,18 @@ def config(cfg_id: int, seed: Optional[int] = None) -> Config:
     if cfg_id == 6:      # config 3 as a transformer layer with per-pixel LayerNorms (not a configuration of the baseline list)
         return Config(6, "sdxl-transformer-ln-c640", "bf16", _draw_res(BASE_SEED + 3 if seed is None else seed, 8, (32, 48, 64)),
                       (16, 16), 640, 32, 10, 64, (LSATTN, LXATTN, LFFN), ctx_len=77, ctx_dim=2048, seed=s)
+    if cfg_id == 7:      # config 2 with the time embedding (SDXL: 1280 wide); not a configuration of the baseline list
+        return Config(7, "sdxl-resnet-temb-c320", "bf16", [(64, 64), (96, 96), (128, 128)], (32, 32),
+                      320, 32, 5, 64, (RES2T,), seed=s, temb_dim=1280)
     raise ValueError(f"unknown config {cfg_id}")
 
 
 def custom_config(resolutions, patch, C, G, heads, stages, dtype="f32", ctx_len=0, ctx_dim=0,
-                  reuse_p=0.0, seed=1234, ffn_mult=4) -> Config:
+                  reuse_p=0.0, seed=1234, ffn_mult=4, temb_dim=0) -> Config:
     """A free-form configuration for edge-case tests."""
     return Config(0, "custom", dtype, [tuple(r) for r in resolutions], tuple(patch), C, G, heads,
                   C // heads, tuple(stages), ctx_len=ctx_len, ctx_dim=ctx_dim, reuse_p=reuse_p,
-                  seed=seed, ffn_mult=ffn_mult)
+                  seed=seed, ffn_mult=ffn_mult, temb_dim=temb_dim)
 
 
 # parameter shapes per stage type: name -> (shape builder, kind)
@@ -202,6 +208,9 @@ def stage_param_shapes(stage: str, cfg: Config) -> Dict[str, Tuple[Tuple[int, ..
                 "conv_a_w": ((C, C, 3, 3), "w:%d" % (9 * C)), "conv_a_b": ((C,), "bias"),
                 "gn_b_g": ((C,), "gamma"), "gn_b_b": ((C,), "beta"),
                 "conv_b_w": ((C, C, 3, 3), "w:%d" % (9 * C)), "conv_b_b": ((C,), "bias")}
+    if stage == RES2T:
+        D = cfg.temb_dim
+        return {**stage_param_shapes(RES2, cfg), "wt": ((D, C), "w:%d" % D), "bt": ((C,), "bias")}
     if stage == SATTN:
         return {"gn_g": ((C,), "gamma"), "gn_b": ((C,), "beta"),
                 "wq": ((C, C), "w:%d" % C), "wk": ((C, C), "w:%d" % C), "wv": ((C, C), "w:%d" % C),
@@ -223,7 +232,7 @@ def stage_param_shapes(stage: str, cfg: Config) -> Dict[str, Tuple[Tuple[int, ..
 
 def stage_cache_slots(stage: str) -> Tuple[str, ...]:
     """Names of the cached operand tensors a stage keeps for reused patches."""
-    if stage == RES2:
+    if stage in (RES2, RES2T):
         return ("h1",)
     if stage == SATTN:
         return ("r", "K", "V")
@@ -240,6 +249,7 @@ class Workload:
     ctx: Optional[np.ndarray]                 # [n, ctx_len, ctx_dim] float32 or None
     reuse: Optional[List[np.ndarray]]         # per request bool [gh, gw] (True = reuse) or None
     cache: Optional[Dict[str, List[np.ndarray]]]  # slot name -> per request [C, H, W] float32
+    temb: Optional[np.ndarray] = None         # [n, temb_dim] float32 or None
 
 
 def make_workload(cfg: Config) -> Workload:
@@ -276,4 +286,5 @@ def make_workload(cfg: Config) -> Workload:
         for nm in names + ["y"]:
             cache[nm] = [rd(Stream(seed, f"cache.{nm}.{i}").normal((cfg.C, h, w)))
                          for i, (h, w) in enumerate(cfg.resolutions)]
-    return Workload(cfg, images, params, ctx, reuse, cache)
+    temb = rd(Stream(seed, "temb").normal((cfg.n, cfg.temb_dim))) if cfg.temb_dim else None
+    return Workload(cfg, images, params, ctx, reuse, cache, temb)
