@@ -77,7 +77,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5, or 6 = config 3 with per-token LayerNorms (default: 2, the SDXL ResNet block)")
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5, 6 = config 3 with per-token LayerNorms, 7 = config 2 with the time embedding (default: 2, the SDXL ResNet block)")
     ap.add_argument("--patch", type=int, nargs=2, default=None, metavar=("PH", "PW"),
                     help="patch size override for the patch-size sweep (not for reuse configs: the mask is per patch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -128,7 +128,7 @@ def main():
 
     def step():
         run.plan.split(run.images, out=run.x)
-        run.cache.forward(run.x, run.ctx, mask, y=y)
+        run.cache.forward(run.x, run.ctx, mask, y=y, temb=run.temb)
         run.plan.reassemble(y, outs)
 
     # Warm-up; its last steps are timed kernel by kernel to find the dominant kernel.  In the timed region only THAT
@@ -175,7 +175,7 @@ def main():
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(args.steps):
-        run.cache.forward(run.x, run.ctx, mask, y=y)
+        run.cache.forward(run.x, run.ctx, mask, y=y, temb=run.temb)
     e1.record()
     torch.cuda.synchronize()
     block_ms = e0.elapsed_time(e1) / args.steps
@@ -254,7 +254,8 @@ def main():
             c_i = None if w.cache is None else {k: v[i] for k, v in w.cache.items()}
             ob.block_forward(w.images[i], cfg.stages, w.params, G=cfg.G, heads=cfg.heads, eps=cfg.eps,
                              ctx=None if w.ctx is None else w.ctx[i],
-                             reuse=None if w.reuse is None else w.reuse[i], cache=c_i)
+                             reuse=None if w.reuse is None else w.reuse[i], cache=c_i,
+                             temb=None if w.temb is None else w.temb[i])
             done_tok += H * W
             used.append(i)
             if time.perf_counter() - tc > 25.0:

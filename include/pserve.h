@@ -53,9 +53,14 @@ extern "C" {
 #define PSERVE_LSATTN 6   /* x + MHA(LN(x))W_o + b_o, keys = all tokens of the own image params: ln_g ln_b wq wk wv wo bo */
 #define PSERVE_LXATTN 7   /* x + MHA(LN(x) W_q; ctx W_k, ctx W_v)W_o + b_o              params: ln_g ln_b wq wk wv wo bo */
 #define PSERVE_LFFN   8   /* x + (a * GELU(g))W_2 + b_2, [a|g] = LN(x) W_1 + b_1        params: ln_g ln_b w1 b1 w2 b2 */
+/* RES2 with the time embedding of the residual block of an SDXL level: the request's embedding vector goes through
+ * SiLU and a linear layer and the C results are added to every pixel of the first convolution's output (a per-pixel
+ * operator with a per-request operand): h1 = conv3_a(SiLU(GN_a(x))) + SiLU(temb) W_t + b_t.  Needs desc.temb_dim and
+ * pserve_block_forward_temb.  params: the eight of RES2, then wt [temb_dim][C], bt [C] */
+#define PSERVE_RES2T  9
 
 #define PSERVE_MAX_STAGES 8
-#define PSERVE_MAX_PARAMS 8
+#define PSERVE_MAX_PARAMS 12
 
 /* plan tables (int32) for pserve_plan_table */
 #define PSERVE_TAB_PERM            0   /* [n]      caller index of sorted slot s */
@@ -71,7 +76,7 @@ extern "C" {
 #define PSERVE_TAB_COUNT           9
 
 /* cache slots of a stage (pserve_cache_load / pserve_cache_read); stage = -1 addresses the block output slot */
-#define PSERVE_SLOT_H1  0   /* RES2: output of the first convolution */
+#define PSERVE_SLOT_H1  0   /* RES2, RES2T: output of the first convolution (RES2T: time embedding included) */
 #define PSERVE_SLOT_R   1   /* SATTN: stage input */
 #define PSERVE_SLOT_K   2   /* SATTN, LSATTN: keys */
 #define PSERVE_SLOT_V   3   /* SATTN, LSATTN: values */
@@ -92,7 +97,7 @@ typedef struct {
 
 typedef struct {
     int32_t n_stages;
-    int32_t stages[PSERVE_MAX_STAGES];   /* PSERVE_RES1 .. PSERVE_LFFN, in execution order */
+    int32_t stages[PSERVE_MAX_STAGES];   /* PSERVE_RES1 .. PSERVE_RES2T, in execution order */
     int32_t C;          /* channels */
     int32_t G;          /* GroupNorm groups (C % G == 0) */
     int32_t heads;      /* attention heads (C % heads == 0) */
@@ -101,6 +106,7 @@ typedef struct {
     int32_t ctx_len;    /* text tokens per request (XATTN), else 0 */
     int32_t ctx_dim;    /* width of a text token (XATTN), else 0 */
     int32_t ffn_mult;   /* FFN hidden width = ffn_mult*C (W_1 is C x 2*ffn_mult*C) */
+    int32_t temb_dim;   /* width of the per-request time embedding (RES2T), else 0 */
 } pserve_block_desc;
 
 /* Device pointers of the parameters of every stage, in the order listed beside the
@@ -178,6 +184,12 @@ int  pserve_cache_read(const pserve_cache_t* cache, int stage, int slot, void* d
 int  pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* ctx,
                           const pserve_block_t* weights, pserve_cache_t* cache,
                           const uint8_t* reuse_mask, void* y, void* stream);
+/* The same with the time embedding of the RES2T stages: temb DEVICE [n][temb_dim] (block dtype), one vector per
+ * request, caller order; NULL if the block has no RES2T stage (then identical to pserve_block_forward, which is
+ * this call with temb = NULL).  Errors as above, EINVAL for a RES2T block without temb. */
+int  pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const void* ctx, const void* temb,
+                               const pserve_block_t* weights, pserve_cache_t* cache,
+                               const uint8_t* reuse_mask, void* y, void* stream);
 
 /* ---- cache manager pieces around the block ("Patch-aware Caching Strategy", "Batching Patches in Cache").
  *

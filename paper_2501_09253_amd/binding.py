@@ -14,11 +14,11 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
 F32, BF16 = 0, 1
-STAGE_KIND = {"RES1": 1, "RES2": 2, "SATTN": 3, "XATTN": 4, "FFN": 5, "LSATTN": 6, "LXATTN": 7, "LFFN": 8}
+STAGE_KIND = {"RES1": 1, "RES2": 2, "SATTN": 3, "XATTN": 4, "FFN": 5, "LSATTN": 6, "LXATTN": 7, "LFFN": 8, "RES2T": 9}
 TABLES = {"perm": 0, "request_offset": 1, "res_offset": 2, "res_hw": 3, "patch_owner": 4,
           "patch_rc": 5, "neighbour": 6, "halo_src": 7, "cu_seqlens": 8}
 SLOT_H1, SLOT_R, SLOT_K, SLOT_V, SLOT_Y = 0, 1, 2, 3, 4
-MAX_STAGES, MAX_PARAMS = 8, 8
+MAX_STAGES, MAX_PARAMS = 8, 12
 
 # parameter order per stage kind (same as the header)
 PARAM_ORDER = {
@@ -30,6 +30,7 @@ PARAM_ORDER = {
     "LSATTN": ["ln_g", "ln_b", "wq", "wk", "wv", "wo", "bo"],
     "LXATTN": ["ln_g", "ln_b", "wq", "wk", "wv", "wo", "bo"],
     "LFFN": ["ln_g", "ln_b", "w1", "b1", "w2", "b2"],
+    "RES2T": ["gn_a_g", "gn_a_b", "conv_a_w", "conv_a_b", "gn_b_g", "gn_b_b", "conv_b_w", "conv_b_b", "wt", "bt"],
 }
 
 
@@ -47,7 +48,7 @@ class _PlanInfo(C.Structure):
 class _BlockDesc(C.Structure):
     _fields_ = [("n_stages", C.c_int32), ("stages", C.c_int32 * MAX_STAGES), ("C", C.c_int32), ("G", C.c_int32),
                 ("heads", C.c_int32), ("dtype", C.c_int32), ("eps", C.c_float), ("ctx_len", C.c_int32),
-                ("ctx_dim", C.c_int32), ("ffn_mult", C.c_int32)]
+                ("ctx_dim", C.c_int32), ("ffn_mult", C.c_int32), ("temb_dim", C.c_int32)]
 
 
 class _ProfEntry(C.Structure):
@@ -94,6 +95,7 @@ def lib() -> C.CDLL:
     L.pserve_cache_load.argtypes = [vp, C.c_int, C.c_int, vp, vp]
     L.pserve_cache_read.argtypes = [vp, C.c_int, C.c_int, vp, vp]
     L.pserve_block_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
+    L.pserve_block_forward_temb.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.pserve_set_kernel_mode.argtypes = [C.c_int]
     L.pserve_profile_enable.argtypes = [C.c_int]
     L.pserve_profile_select.argtypes = [C.c_char_p]
@@ -245,13 +247,13 @@ class Block:
     """pserve_block: block description + packed weights (params: per stage dict name -> device tensor)."""
 
     def __init__(self, stages: Sequence[str], params: List[Dict[str, "object"]], *, C_: int, G: int, heads: int,
-                 dtype: int, eps: float = 1e-5, ctx_len: int = 0, ctx_dim: int = 0, ffn_mult: int = 4):
+                 dtype: int, eps: float = 1e-5, ctx_len: int = 0, ctx_dim: int = 0, ffn_mult: int = 4, temb_dim: int = 0):
         desc = _BlockDesc()
         desc.n_stages = len(stages)
         for i, s in enumerate(stages):
             desc.stages[i] = STAGE_KIND[s]
         desc.C, desc.G, desc.heads, desc.dtype, desc.eps = C_, G, heads, dtype, eps
-        desc.ctx_len, desc.ctx_dim, desc.ffn_mult = ctx_len, ctx_dim, ffn_mult
+        desc.ctx_len, desc.ctx_dim, desc.ffn_mult, desc.temb_dim = ctx_len, ctx_dim, ffn_mult, temb_dim
         bp = _BlockParams()
         keep = []
         for i, (s, p) in enumerate(zip(stages, params)):
@@ -302,8 +304,8 @@ class Cache:
         _check(lib().pserve_cache_migrate(old_cache._h, self._h, patch_src.data_ptr(), valid.data_ptr(), _stream()))
         return valid
 
-    def forward(self, x, ctx=None, reuse_mask=None, y=None):
-        """pserve_block_forward on the current torch stream; returns y[T, C]."""
+    def forward(self, x, ctx=None, reuse_mask=None, y=None, temb=None):
+        """pserve_block_forward (pserve_block_forward_temb when temb is given) on the current torch stream; returns y[T, C]."""
         import torch
         assert x.is_contiguous() and tuple(x.shape) == (self.plan.T, self.block.C)
         assert x.dtype == _torch_dtype(self.block.dtype)
@@ -313,10 +315,15 @@ class Cache:
             assert ctx.is_contiguous() and ctx.dtype == x.dtype
         if reuse_mask is not None:
             assert reuse_mask.dtype == torch.uint8 and reuse_mask.numel() == self.plan.P and reuse_mask.is_contiguous()
-        _check(lib().pserve_block_forward(self.plan._h, x.data_ptr(), ctx.data_ptr() if ctx is not None else None,
-                                          self.block._h, self._h,
-                                          reuse_mask.data_ptr() if reuse_mask is not None else None,
-                                          y.data_ptr(), _stream()))
+        mask_p = reuse_mask.data_ptr() if reuse_mask is not None else None
+        ctx_p = ctx.data_ptr() if ctx is not None else None
+        if temb is not None:
+            assert temb.is_contiguous() and temb.dtype == x.dtype
+            _check(lib().pserve_block_forward_temb(self.plan._h, x.data_ptr(), ctx_p, temb.data_ptr(), self.block._h,
+                                                   self._h, mask_p, y.data_ptr(), _stream()))
+        else:
+            _check(lib().pserve_block_forward(self.plan._h, x.data_ptr(), ctx_p, self.block._h, self._h, mask_p,
+                                              y.data_ptr(), _stream()))
         return y
 
     def close(self):

@@ -58,9 +58,54 @@ struct StageWeights {
     void* gn_b[2] = {};
     void* w[3] = {};         // packed [taps][N][K]
     float* b[3] = {};        // packed biases (fp32)
+    void* wt = nullptr;      // RES2T: time projection [temb_dim][C], block dtype (raw copy)
+    float* bt = nullptr;     // RES2T: its bias (fp32)
 };
 
 // ---- small kernels ---------------------------------------------------------------------------------
+// Time embedding of the RES2T stages: e[s][c] = bt[c] + sum_k SiLU(temb[perm[s]][k]) * wt[k][c] for request slot s
+// (sorted order).  One block of 1024 threads per (slot, 64 channels): 16 thread groups take every 16th k (the sum is a
+// chain of dependent loads otherwise: 94 us for 1280 terms), eight loads in flight each; SiLU(temb) is staged once in
+// LDS; the 16 partial sums are added in a fixed order.  fp32 accumulation.
+constexpr int TEMB_KG = 16;
+template <typename T>
+__global__ void __launch_bounds__(1024)
+temb_proj_kernel(const T* __restrict__ temb, const T* __restrict__ wt, const float* __restrict__ bt,
+                 const int32_t* __restrict__ perm, int32_t D, int32_t C, float* __restrict__ e) {
+    extern __shared__ float s_t[];                  // [D] SiLU(temb), then [TEMB_KG][64] partial sums
+    float* s_part = s_t + D;
+    const int s = blockIdx.x;
+    const T* tv = temb + (int64_t)perm[s] * D;
+    auto as_f = [](T v) -> float {
+        if constexpr (sizeof(T) == 2) return __uint_as_float((uint32_t)v << 16);
+        else return v;
+    };
+    for (int k = threadIdx.x; k < D; k += blockDim.x) {
+        const float v = as_f(tv[k]);
+        s_t[k] = v / (1.f + __expf(-v));
+    }
+    __syncthreads();
+    const int cl = threadIdx.x & 63, kg = threadIdx.x >> 6;
+    const int c = min(blockIdx.y * 64 + cl, C - 1);
+    float acc = 0.f;
+    int k = kg;
+    for (; k + 7 * TEMB_KG < D; k += 8 * TEMB_KG) {
+        float w[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) w[u] = as_f(wt[(int64_t)(k + u * TEMB_KG) * C + c]);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc = fmaf(s_t[k + u * TEMB_KG], w[u], acc);
+    }
+    for (; k < D; k += TEMB_KG) acc = fmaf(s_t[k], as_f(wt[(int64_t)k * C + c]), acc);
+    s_part[kg * 64 + cl] = acc;
+    __syncthreads();
+    if (kg == 0 && blockIdx.y * 64 + cl < C) {
+        float sum = bt[c];
+        for (int g = 0; g < TEMB_KG; ++g) sum += s_part[g * 64 + cl];
+        e[(int64_t)s * C + c] = sum;
+    }
+}
+
 // Ordered compaction of the patches with mask == 0.
 __global__ void compact_mask_kernel(const uint8_t* __restrict__ mask, int32_t P, int32_t* __restrict__ active,
                                     int32_t* __restrict__ count) {
@@ -180,6 +225,7 @@ struct pserve_cache_s {
     void* vc = nullptr;                       // [n*cross_ld][C] text values
     void* hidden = nullptr;                   // [T][F]
     void* yslot = nullptr;                    // [T][C] block output of the previous step (slot Y)
+    float* temb_e[PSERVE_MAX_STAGES] = {};    // RES2T: [n][C] projected time embedding per request slot
     int32_t* active = nullptr;
     int32_t* count = nullptr;
     int32_t* act_off = nullptr;               // [n+1] attention: computed patches before slot s
@@ -208,6 +254,7 @@ static bool has_stage(const pserve_block_desc& d, int kind) {
 static bool is_sattn(int k) { return k == PSERVE_SATTN || k == PSERVE_LSATTN; }
 static bool is_xattn(int k) { return k == PSERVE_XATTN || k == PSERVE_LXATTN; }
 static bool is_ffn(int k) { return k == PSERVE_FFN || k == PSERVE_LFFN; }
+static bool is_res2(int k) { return k == PSERVE_RES2 || k == PSERVE_RES2T; }
 static bool has_ln(int k) { return k == PSERVE_LSATTN || k == PSERVE_LXATTN || k == PSERVE_LFFN; }
 template <typename F> static bool any_stage(const pserve_block_desc& d, F f) {
     for (int s = 0; s < d.n_stages; ++s) if (f(d.stages[s])) return true;
@@ -283,14 +330,16 @@ int pserve_block_create(const pserve_block_desc* desc, const pserve_block_params
     PS_REQUIRE(d.C > 0 && d.G > 0 && d.C % d.G == 0, "pserve_block_create: C=%d must be a positive multiple of G=%d", d.C, d.G);
     PS_REQUIRE(d.C % (d.dtype == PSERVE_BF16 ? 8 : 4) == 0, "pserve_block_create: C=%d must be a multiple of 16 bytes", d.C);
     PS_REQUIRE(d.eps >= 0.f, "pserve_block_create: negative eps");
-    static const int nparams[9] = {0, 4, 8, 7, 5, 4, 7, 7, 6};
+    static const int nparams[10] = {0, 4, 8, 7, 5, 4, 7, 7, 6, 10};
     for (int s = 0; s < d.n_stages; ++s) {
         const int kind = d.stages[s];
-        PS_REQUIRE(kind >= PSERVE_RES1 && kind <= PSERVE_LFFN, "pserve_block_create: stage %d has unknown kind %d", s, kind);
+        PS_REQUIRE(kind >= PSERVE_RES1 && kind <= PSERVE_RES2T, "pserve_block_create: stage %d has unknown kind %d", s, kind);
         for (int k = 0; k < nparams[kind]; ++k) PS_REQUIRE(params->p[s][k], "pserve_block_create: stage %d parameter %d is NULL", s, k);
         if (is_sattn(kind) || is_xattn(kind))
             PS_REQUIRE(d.heads > 0 && d.C % d.heads == 0 && d.C / d.heads <= 128,
                        "pserve_block_create: heads=%d must divide C=%d with head dim <= 128", d.heads, d.C);
+        if (kind == PSERVE_RES2T)
+            PS_REQUIRE(d.temb_dim > 0 && d.temb_dim <= 8192, "pserve_block_create: RES2T needs temb_dim in 1..8192 (got %d)", d.temb_dim);
         if (is_xattn(kind))
             PS_REQUIRE(d.ctx_len > 0 && d.ctx_dim > 0, "pserve_block_create: XATTN needs ctx_len and ctx_dim");
         if (is_ffn(kind))
@@ -314,8 +363,14 @@ int pserve_block_create(const pserve_block_desc* desc, const pserve_block_params
         }
         switch (d.stages[s]) {
         case PSERVE_RES1:
-        case PSERVE_RES2: {
+        case PSERVE_RES2:
+        case PSERVE_RES2T: {
             const int convs = d.stages[s] == PSERVE_RES1 ? 1 : 2;
+            if (d.stages[s] == PSERVE_RES2T) {
+                PS_TRY(dup_param(b->pool, p[8], es * d.temb_dim * C, &w.wt, st));
+                PS_TRY(b->pool.alloc_t(&w.bt, C));
+                PS_TRY(pack_bias(p[9], w.bt, C, d.dtype, st));
+            }
             for (int c = 0; c < convs; ++c) {
                 PS_TRY(dup_param(b->pool, p[4 * c + 0], es * C, &w.gn_g[c], st));
                 PS_TRY(dup_param(b->pool, p[4 * c + 1], es * C, &w.gn_b[c], st));
@@ -381,7 +436,7 @@ int pserve_cache_create(const pserve_plan_t* plan, const pserve_block_t* block, 
     const pserve_block_desc& d = block->desc;
     if (with_slots)
         for (int s = 1; s < d.n_stages; ++s)
-            PS_REQUIRE(d.stages[s] != PSERVE_RES1 && d.stages[s] != PSERVE_RES2,
+            PS_REQUIRE(d.stages[s] != PSERVE_RES1 && !is_res2(d.stages[s]),
                        "pserve_cache_create: patch reuse needs residual-convolution stages at position 0 only "
                        "(their input statistics and halos must be fresh on every patch)");
     pserve_cache_t* c = new (std::nothrow) pserve_cache_t();
@@ -397,7 +452,7 @@ int pserve_cache_create(const pserve_plan_t* plan, const pserve_block_t* block, 
     c->nsplit = (int)std::max<int64_t>(1, std::min<int64_t>(cdiv(768, plan->P), std::max(1, plan->S / 32)));
     PS_TRY(c->pool.alloc(&c->ping[0], TC));
     PS_TRY(c->pool.alloc(&c->ping[1], TC));
-    const bool conv = has_stage(d, PSERVE_RES1) || has_stage(d, PSERVE_RES2);
+    const bool conv = has_stage(d, PSERVE_RES1) || any_stage(d, is_res2);
     const bool sattn = any_stage(d, is_sattn), xattn = any_stage(d, is_xattn), ffn = any_stage(d, is_ffn);
     const bool gn_sattn = has_stage(d, PSERVE_SATTN);
     if (conv) PS_TRY(c->pool.alloc(&c->apad, (size_t)plan->P * (plan->ph + 2) * (plan->pw + 2) * d.C * es));
@@ -406,7 +461,8 @@ int pserve_cache_create(const pserve_plan_t* plan, const pserve_block_t* block, 
         PS_TRY(c->pool.alloc_t(&c->scale_shift, (size_t)plan->n * d.C * 2));
     }
     for (int s = 0; s < d.n_stages; ++s) {
-        if (d.stages[s] == PSERVE_RES2) PS_TRY(c->pool.alloc(&c->h1[s], TC));
+        if (is_res2(d.stages[s])) PS_TRY(c->pool.alloc(&c->h1[s], TC));
+        if (d.stages[s] == PSERVE_RES2T) PS_TRY(c->pool.alloc_t(&c->temb_e[s], (size_t)plan->n * d.C));
         if (is_sattn(d.stages[s])) {
             if (with_slots && d.stages[s] == PSERVE_SATTN) PS_TRY(c->pool.alloc(&c->r[s], TC));
             PS_TRY(c->pool.alloc(&c->k[s], TC));
@@ -466,7 +522,7 @@ static int slot_ptr(const pserve_cache_t* c, int stage, int slot, void** ptr, bo
     }
     PS_REQUIRE(stage >= 0 && stage < d.n_stages, "cache slot: stage %d out of range", stage);
     void* p = nullptr;
-    if (slot == PSERVE_SLOT_H1 && d.stages[stage] == PSERVE_RES2) p = c->h1[stage];
+    if (slot == PSERVE_SLOT_H1 && is_res2(d.stages[stage])) p = c->h1[stage];
     else if (slot == PSERVE_SLOT_R && d.stages[stage] == PSERVE_SATTN) p = c->r[stage];
     else if (slot == PSERVE_SLOT_K && is_sattn(d.stages[stage])) p = c->k[stage];
     else if (slot == PSERVE_SLOT_V && is_sattn(d.stages[stage])) { p = c->v[stage]; *transposed = c->v_transposed; }
@@ -557,11 +613,18 @@ int pserve_cache_migrate(const pserve_cache_t* old_cache, pserve_cache_t* new_ca
 
 int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* ctx, const pserve_block_t* block,
                          pserve_cache_t* cache, const uint8_t* reuse_mask, void* y, void* stream) {
+    return pserve_block_forward_temb(plan, x, ctx, nullptr, block, cache, reuse_mask, y, stream);
+}
+
+int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const void* ctx, const void* temb,
+                              const pserve_block_t* block, pserve_cache_t* cache, const uint8_t* reuse_mask, void* y,
+                              void* stream) {
     PS_REQUIRE(plan && x && block && cache && y, "pserve_block_forward: NULL argument");
     PS_REQUIRE(x != y, "pserve_block_forward: x and y must not alias");
     PS_REQUIRE(cache->plan == plan && cache->block == block, "pserve_block_forward: cache belongs to another plan or block");
     const pserve_block_desc& d = block->desc;
     PS_REQUIRE(ctx || !any_stage(d, is_xattn), "pserve_block_forward: XATTN stage needs ctx");
+    PS_REQUIRE(temb || !has_stage(d, PSERVE_RES2T), "pserve_block_forward: RES2T stage needs temb (pserve_block_forward_temb)");
     if (reuse_mask) {
         if (!cache->with_slots) { set_error("pserve_block_forward: reuse mask given but the cache has no slots"); return PSERVE_ESTATE; }
         if (!cache->filled) { set_error("pserve_block_forward: reuse mask given but the cache was never filled"); return PSERVE_ESTATE; }
@@ -614,7 +677,8 @@ int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* c
     // GroupNorm(+SiLU) of `in` into the padded buffer, halo ring, 3x3 convolution (+bias, +residual) into `out`
     // stats_next: the output feeds another norm, so the convolution may leave that norm's partial sums behind
     bool have_partials = false;                     // cache->partial was filled by the previous convolution
-    auto norm_conv = [&](const void* in, const StageWeights& w, int ci, const void* res, void* out, bool stats_next) -> int {
+    auto norm_conv = [&](const void* in, const StageWeights& w, int ci, const void* res, void* out, bool stats_next,
+                         const float* rowbias = nullptr) -> int {
         GroupNormArgs ga = gn_args(in, w.gn_g[ci], w.gn_b[ci]);
         if (have_partials) { ProfScope ps("gn_stats", st); PS_TRY(gn_finalize(ga, gm, dt, plan->S / 64, st)); }
         else { ProfScope ps("gn_stats", st); PS_TRY(gn_stats(ga, gm, dt, st)); }
@@ -629,6 +693,7 @@ int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* c
         }
         GemmArgs g = base_gemm(cache->apad, C, C, C, w.w[ci], w.b[ci]);
         g.conv = 1; g.taps = 9; g.res = res; g.ldr = C;
+        g.rowbias = rowbias; g.row_owner = owner;
         g.seg[0].ptr = out; g.seg[0].ld = C;
         if (stats_next && !reuse_mask) {
             // (with a mask the reused patches keep cached activations this convolution never sees: gn_stats reads them)
@@ -675,6 +740,24 @@ int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* c
             PS_TRY(norm_conv(cur, w, 0, nullptr, cache->h1[si], true));
             PS_TRY(norm_conv(cache->h1[si], w, 1, cur, out, false));
             break;
+        case PSERVE_RES2T: {
+            {   // the projected embedding of every request; the first convolution adds it in its epilogue
+                ProfScope ps("temb_proj", st);
+                const dim3 grid(plan->n, (unsigned)cdiv(C, 64));
+                const size_t lds = sizeof(float) * (d.temb_dim + TEMB_KG * 64);
+                const int32_t* perm = plan->d_tab[PSERVE_TAB_PERM];
+                if (dt == PSERVE_BF16)
+                    temb_proj_kernel<uint16_t><<<grid, 1024, lds, st>>>((const uint16_t*)temb, (const uint16_t*)w.wt, w.bt, perm,
+                                                                       d.temb_dim, C, cache->temb_e[si]);
+                else
+                    temb_proj_kernel<float><<<grid, 1024, lds, st>>>((const float*)temb, (const float*)w.wt, w.bt, perm,
+                                                                    d.temb_dim, C, cache->temb_e[si]);
+                PS_TRY(check_launch("temb_proj_kernel"));
+            }
+            PS_TRY(norm_conv(cur, w, 0, nullptr, cache->h1[si], true, cache->temb_e[si]));
+            PS_TRY(norm_conv(cache->h1[si], w, 1, cur, out, false));
+            break;
+        }
         case PSERVE_SATTN:
         case PSERVE_LSATTN: {
             const bool ln = d.stages[si] == PSERVE_LSATTN;

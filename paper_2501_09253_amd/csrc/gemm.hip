@@ -143,6 +143,7 @@ gemm_simple_kernel(GemmArgs a) {
                 st_f<T>((T*)a.seg[0].ptr + tok * a.seg[0].ld + col, v);
             } else {
                 v = acc[0][i][j] + (a.bias ? a.bias[col] : 0.f);
+                if (a.rowbias) v += a.rowbias[(int64_t)a.row_owner[tok / a.geom.S] * a.N + col];
                 if (a.res) v += ld_f<T>((const T*)a.res + tok * a.ldr + col);
                 route_store<T>(a, tok, col, v);
             }

@@ -78,6 +78,17 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[B
 #pragma unroll
         for (int t = 0; t < NIT; ++t) rres[0][t] = *reinterpret_cast<const u32x4*>(res_row[t] + n0 + wn * WN);
     }
+    // per-request bias (time embedding): one value per column when all rows of the wavefront's tile belong to one
+    // request (rows are ordered by request, so first == last decides), else looked up per element
+    bool rb_uniform = false;
+    int rb_slot = 0;
+    if (!GEGLU && a.rowbias) {
+        const int t_first = w_tok[0], t_last = w_tok[WM - 1];
+        if (t_first >= 0 && t_last >= 0) {
+            rb_slot = a.row_owner[t_first / a.geom.S];
+            rb_uniform = rb_slot == a.row_owner[t_last / a.geom.S];
+        }
+    }
     // GroupNorm partial sums of the output (optional): column sums over this wavefront's 64 rows, which lie in one patch
     const bool STATS = MAY_STAT && !GEGLU && a.stats != nullptr;     // only the convolution kernels leave the sums behind
     float* colsum = reinterpret_cast<float*>(smem) + WGM * WGN * (WM * EP_LD) + wave * (2 * WN);    // [WN][2]
@@ -110,11 +121,21 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[B
             const int sg = pcol / a.seg_cols;
             sgm = sg == 0 ? a.seg[0] : (sg == 1 ? a.seg[1] : a.seg[2]);
             ocol0 = pcol - sg * a.seg_cols;
-            const float bias = bias_pre ? bias_pre[j] : (a.bias ? a.bias[pcol + fr] : 0.f);
+            float bias = bias_pre ? bias_pre[j] : (a.bias ? a.bias[pcol + fr] : 0.f);
+            if (rb_uniform) bias += a.rowbias[(int64_t)rb_slot * a.N + pcol + fr];
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) vals[i][e] = acc[i][j][e] + bias;
+            if (a.rowbias && !rb_uniform) {                     // rows of several requests in this wavefront's tile
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int tok = w_tok[i * 32 + 8 * (e >> 2) + 4 * fh + (e & 3)];
+                        if (tok >= 0) vals[i][e] += a.rowbias[(int64_t)a.row_owner[tok / a.geom.S] * a.N + pcol + fr];
+                    }
+            }
             if (STATS) {
                 float s1 = 0.f, s2 = 0.f;
                 if (all_rows) {

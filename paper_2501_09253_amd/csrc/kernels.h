@@ -87,6 +87,8 @@ struct GemmArgs {
     int32_t taps;              // 1 or 9
     const void* B;             // packed weights [taps][N][K]
     const float* bias;         // [N] packed order, or nullptr
+    const float* rowbias;      // optional [n][N]: row r also gets rowbias[row_owner[token / S]][col] (rows are tokens)
+    const int32_t* row_owner;  // [P] request slot of each patch (with rowbias)
     const void* res;           // residual [rows][ldr] or nullptr (added after bias)
     int64_t ldr;
     int32_t epi;               // EPI_ROUTE: columns go to segment col / seg_cols; EPI_GEGLU: value*GELU(gate) pairs

@@ -34,8 +34,10 @@ class GpuRun:
         self.images = [to_dev(im, cfg.dtype) for im in w.images]
         self.params = [{k: to_dev(v, cfg.dtype) for k, v in p.items()} for p in w.params]
         self.ctx = to_dev(w.ctx, cfg.dtype) if w.ctx is not None else None
+        self.temb = to_dev(w.temb, cfg.dtype) if w.temb is not None else None
         self.block = ps.Block(cfg.stages, self.params, C_=cfg.C, G=cfg.G, heads=cfg.heads, dtype=self.dtype,
-                              eps=cfg.eps, ctx_len=cfg.ctx_len, ctx_dim=cfg.ctx_dim, ffn_mult=cfg.ffn_mult)
+                              eps=cfg.eps, ctx_len=cfg.ctx_len, ctx_dim=cfg.ctx_dim, ffn_mult=cfg.ffn_mult,
+                              temb_dim=cfg.temb_dim)
         if with_slots is None:
             with_slots = w.cache is not None
         self.cache = ps.Cache(self.plan, self.block, with_slots)
@@ -72,7 +74,7 @@ class GpuRun:
 
     def forward(self, reuse=None):
         mask = self.plan_mask(reuse) if reuse is not None else None
-        y = self.cache.forward(self.x, self.ctx, mask)
+        y = self.cache.forward(self.x, self.ctx, mask, temb=self.temb)
         torch.cuda.synchronize()
         return y
 

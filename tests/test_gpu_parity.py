@@ -22,7 +22,7 @@ pytestmark = pytest.mark.gpu
 def _oracle(w, reuse=None, cache=None):
     cfg = w.cfg
     return ob.forward_batch(w.images, cfg.stages, w.params, G=cfg.G, heads=cfg.heads, eps=cfg.eps, ctx=w.ctx,
-                            reuse=reuse, cache=cache)
+                            reuse=reuse, cache=cache, temb=w.temb)
 
 
 # ----------------------------------------------------------------------------- planner, split
@@ -80,6 +80,8 @@ SMALL = [
     # the token stages with a per-token LayerNorm in front
     ((wl.LSATTN,), "f32"), ((wl.LXATTN,), "f32"), ((wl.LFFN,), "f32"), ((wl.RES2, wl.LSATTN, wl.LXATTN, wl.LFFN), "f32"),
     ((wl.LSATTN, wl.LXATTN, wl.LFFN), "bf16"), ((wl.SATTN, wl.LFFN), "bf16"),
+    # residual block with the per-request time embedding
+    ((wl.RES2T,), "f32"), ((wl.RES2T, wl.LSATTN), "f32"), ((wl.RES2T,), "bf16"),
 ]
 
 
@@ -89,7 +91,7 @@ def test_small_blocks(stages, dtype, mode):
     ps.set_kernel_mode(mode)
     try:
         cfg = wl.custom_config([(12, 8), (4, 4), (8, 12), (4, 4)], (4, 4), C=32, G=4, heads=2, stages=stages,
-                               dtype=dtype, ctx_len=7, ctx_dim=24, seed=11)
+                               dtype=dtype, ctx_len=7, ctx_dim=24, seed=11, temb_dim=20)
         w = wl.make_workload(cfg)
         got = GpuRun(w).forward_images()
         ref, _ = _oracle(w)
@@ -104,11 +106,11 @@ def test_small_blocks(stages, dtype, mode):
                                          # next norm's partial sums must skip the rows past the end): T = 192 and T = 320
                                          (64, [(8, 8), (8, 16)], (8, 8)), (320, [(8, 8), (16, 16)], (8, 8))])
 @pytest.mark.parametrize("stages", [(wl.RES2,), (wl.SATTN, wl.XATTN, wl.FFN), (wl.RES1, wl.SATTN),
-                                    (wl.LSATTN, wl.LXATTN, wl.LFFN)])
+                                    (wl.LSATTN, wl.LXATTN, wl.LFFN), (wl.RES2T,)])
 def test_mfma_shapes_bf16(stages, C, res, patch):
     """bf16 blocks whose widths take the MFMA kernels (C multiple of 64, head dim 64), ragged M tails included."""
     cfg = wl.custom_config(res, patch, C=C, G=32, heads=C // 64, stages=stages, dtype="bf16", ctx_len=77, ctx_dim=128,
-                           seed=31)
+                           seed=31, temb_dim=96)
     w = wl.make_workload(cfg)
     got = GpuRun(w).forward_images()
     ref, _ = _oracle(w)
@@ -154,10 +156,10 @@ def test_layer_norm_widths(dtype, C):
 # ----------------------------------------------------------------------------- reuse
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("stages", [(wl.RES2, wl.SATTN), (wl.SATTN,), (wl.RES2,), (wl.SATTN, wl.XATTN, wl.FFN),
-                                    (wl.LSATTN, wl.LXATTN, wl.LFFN), (wl.RES2, wl.LSATTN)])
+                                    (wl.LSATTN, wl.LXATTN, wl.LFFN), (wl.RES2, wl.LSATTN), (wl.RES2T, wl.SATTN)])
 def test_reuse_small(stages, dtype):
     cfg = wl.custom_config([(16, 16), (8, 8), (8, 16)], (4, 4), C=32, G=4, heads=2, stages=stages, dtype=dtype,
-                           ctx_len=5, ctx_dim=16, reuse_p=0.4, seed=21)
+                           ctx_len=5, ctx_dim=16, reuse_p=0.4, seed=21, temb_dim=12)
     w = wl.make_workload(cfg)
     run = GpuRun(w)
     run.load_cache()
@@ -226,7 +228,7 @@ def test_config1_fp32():
     assert rel_err(got, ref) < 1e-4
 
 
-@pytest.mark.parametrize("cfg_id", [2, 3, 4, 6])
+@pytest.mark.parametrize("cfg_id", [2, 3, 4, 6, 7])
 def test_config_bf16_full_size(cfg_id):
     w = wl.make_workload(wl.config(cfg_id))
     got = GpuRun(w).forward_images()
