@@ -17,6 +17,7 @@ import workloads as wl
 from oracle import block as ob
 from oracle import plan as op
 from oracle import cache as oc
+from oracle import resample as orr
 
 RNG = np.random.default_rng(7)
 
@@ -663,3 +664,71 @@ def test_cache_sets_invariants():
     for p, q in enumerate(got["patch_src"]):
         want = old_slot[q * S:(q + 1) * S] if q >= 0 else 0.0
         assert np.array_equal(new_slot[p * S:(p + 1) * S], want + np.zeros((S, C)))
+
+
+# ----------------------------------------------------------------------------- resolution changes
+def _rs_inputs(C=5, Co=3, H=6, W=8, seed=31):
+    u = wl.Stream(seed, "u").normal((C, H, W)).astype(np.float64)
+    k = wl.Stream(seed, "k").normal((Co, C, 3, 3)).astype(np.float64)
+    b = wl.Stream(seed, "b").normal((Co,)).astype(np.float64)
+    return u, k, b
+
+
+def test_down2_up2_vs_torch_library():
+    u, k, b = _rs_inputs()
+    t = torch.from_numpy
+    ref = F.conv2d(t(u)[None], t(k), t(b), stride=2, padding=1)[0].numpy()
+    assert np.allclose(orr.down2(u, k, b), ref, atol=1e-12)
+    ref = F.conv2d(F.interpolate(t(u)[None], scale_factor=2, mode="nearest"), t(k), t(b), padding=1)[0].numpy()
+    assert np.allclose(orr.up2(u, k, b), ref, atol=1e-12)
+
+
+def test_down2_closed_forms_fix_centre_stride_and_padding():
+    """Centre tap alone: plain subsampling of the even pixels; tap (0, 0) alone: pixel (2oy-1, 2ox-1), zero in the
+    first output row and column; all-ones kernel on an all-ones image: the number of taps inside the image."""
+    u, _, _ = _rs_inputs(C=2, Co=2)
+    eye = np.zeros((2, 2, 3, 3))
+    eye[0, 0, 1, 1] = eye[1, 1, 1, 1] = 1.0
+    assert np.array_equal(orr.down2(u, eye, np.zeros(2)), u[:, ::2, ::2])
+    k00 = np.zeros((2, 2, 3, 3))
+    k00[0, 1, 0, 0] = 1.0                                          # out channel 0 reads in channel 1
+    y = orr.down2(u, k00, np.zeros(2))
+    assert np.array_equal(y[0, 1:, 1:], u[1, 1:-1:2, 1:-1:2]) and not y[0, 0].any() and not y[0, :, 0].any() and not y[1].any()
+    ones = orr.down2(np.ones((1, 6, 8)), np.ones((1, 1, 3, 3)), np.array([0.5]))
+    want = np.full((3, 4), 9.0)
+    want[0, :] = 6.0
+    want[:, 0] = 6.0
+    want[0, 0] = 4.0                                               # only the top / left border loses taps (even sizes)
+    assert np.array_equal(ones[0], want + 0.5)
+
+
+def test_up2_closed_forms_and_plain_loops():
+    """Centre tap alone: every pixel repeated 2 x 2; and a 7-loop evaluation of the definition on a tiny case."""
+    u, k, b = _rs_inputs(C=2, Co=2, H=3, W=4)
+    eye = np.zeros((2, 2, 3, 3))
+    eye[0, 0, 1, 1] = eye[1, 1, 1, 1] = 1.0
+    assert np.array_equal(orr.up2(u, eye, np.zeros(2)), np.kron(u, np.ones((2, 2))))
+    got = orr.up2(u, k, b)
+    for co in range(2):
+        for oy in range(6):
+            for ox in range(8):
+                acc = b[co]
+                for ci in range(2):
+                    for ty in range(3):
+                        for tx in range(3):
+                            Y, X = oy + ty - 1, ox + tx - 1
+                            if 0 <= Y < 6 and 0 <= X < 8:
+                                acc += k[co, ci, ty, tx] * u[ci, Y // 2, X // 2]
+                assert abs(got[co, oy, ox] - acc) < 1e-12
+    got = orr.down2(u[:, :2, :], k, b)
+    for co in range(2):
+        for oy in range(1):
+            for ox in range(2):
+                acc = b[co]
+                for ci in range(2):
+                    for ty in range(3):
+                        for tx in range(3):
+                            Y, X = 2 * oy + ty - 1, 2 * ox + tx - 1
+                            if 0 <= Y < 2 and 0 <= X < 4:
+                                acc += k[co, ci, ty, tx] * u[ci, Y, X]
+                assert abs(got[co, oy, ox] - acc) < 1e-12
