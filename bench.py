@@ -197,6 +197,21 @@ def main():
         us = timed(lambda: run.plan.patch_mse(run.x, y))
         gbs = 2.0 * cfg.T * cfg.C * es / (us * 1e-6) / 1e9
         extras["patch_mse"] = {"avg_us": us, "gbs": gbs, "frac_hbm": gbs / PEAK_HBM_GBS}
+        if cfg.dtype == "bf16" and patch[0] % 2 == 0 and patch[1] % 2 == 0 and w.reuse is None:
+            # the level changes at this configuration's size: C -> C, down to half size and back up (random weights)
+            from harness import to_dev
+            import numpy as _np
+            wt = to_dev((wl.Stream(cfg.seed, "rs.w").normal((cfg.C, cfg.C, 3, 3)) / _np.sqrt(9.0 * cfg.C)).astype(_np.float32), "bf16")
+            bt = to_dev(_np.zeros(cfg.C, dtype=_np.float32), "bf16")
+            lo_plan = ps.Plan([(h // 2, w_ // 2) for h, w_ in cfg.resolutions], patch[0] // 2, patch[1] // 2)
+            down, up = ps.Resample(ps.DOWN2, wt, bt, ps.BF16), ps.Resample(ps.UP2, wt, bt, ps.BF16)
+            lo = down.forward(run.plan, lo_plan, run.x)
+            us = timed(lambda: down.forward(run.plan, lo_plan, run.x, y=lo))
+            tf = 2.0 * 9 * cfg.C * cfg.C * lo_plan.T / (us * 1e-6) / 1e12
+            extras["down2"] = {"avg_us": us, "tflops": tf, "frac_mfma": tf / PEAK_BF16_TFLOPS}
+            us = timed(lambda: up.forward(lo_plan, run.plan, lo, y=y))
+            tf = 2.0 * 16 * cfg.C * cfg.C * lo_plan.T / (us * 1e-6) / 1e12      # four merged taps per output pixel
+            extras["up2"] = {"avg_us": us, "tflops": tf, "frac_mfma": tf / PEAK_BF16_TFLOPS}
         if w.reuse is not None:
             ids = list(range(cfg.n))
             _, _, src = run.plan.cache_sets(ids, run.plan, ids)

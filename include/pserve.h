@@ -26,6 +26,7 @@
 #ifndef PSERVE_H
 #define PSERVE_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -223,6 +224,31 @@ int  pserve_cache_sets(const pserve_plan_t* old_plan, const int64_t* old_ids, co
                        void* stream);
 int  pserve_cache_migrate(const pserve_cache_t* old_cache, pserve_cache_t* new_cache, const int32_t* patch_src,
                           uint8_t* valid, void* stream);
+
+/* ---- resolution changes between two levels of the network (not part of the paper's block; its patch-size rule, the
+ * greatest common divisor of the resolutions, is what makes them keep the patch grid: a ph x pw patch becomes
+ * ph/2 x pw/2 resp. 2ph x 2pw, halos come from the neighbour patches as in "Patch-Tailored Diffusion Operators").
+ *   PSERVE_DOWN2  3x3 convolution, stride 2, zero padding 1: image [C_in][H][W] -> [C_out][H/2][W/2]; the taps of
+ *                 output pixel (oy, ox) are centred on input pixel (2oy, 2ox)
+ *   PSERVE_UP2    every pixel repeated 2 x 2 (nearest neighbour), then 3x3 convolution, zero padding 1:
+ *                 -> [C_out][2H][2W]
+ * pserve_resample_create: w DEVICE [C_out][C_in][3][3], b DEVICE [C_out] (dtype as given); packs them (for UP2 the nine
+ * taps are merged, in fp32, into four taps for each of the four output parities) and synchronises `stream`.
+ * pserve_resample_forward: x DEVICE [T_in][C_in] on plan_in, y DEVICE [T_out][C_out] on plan_out, where plan_out is
+ * the pserve_plan of the halved (doubled) resolutions, same caller order, with the halved (doubled) patch size;
+ * workspace DEVICE, at least pserve_resample_workspace bytes (the padded copy of x), owned by the caller; nothing is
+ * allocated.  Result: equal (up to rounding order) to the operator applied to every image on its own.
+ * Errors: EINVAL (NULL, widths not multiples of 16 bytes, plans that are not such a pair, odd patch size for DOWN2,
+ * workspace too small), ENOMEM, EHIP. */
+#define PSERVE_DOWN2 1
+#define PSERVE_UP2   2
+typedef struct pserve_resample_s pserve_resample_t;
+int  pserve_resample_create(int kind, int32_t C_in, int32_t C_out, int dtype, const void* w, const void* b,
+                            void* stream, pserve_resample_t** out);
+void pserve_resample_free(pserve_resample_t* op);
+int  pserve_resample_workspace(const pserve_resample_t* op, const pserve_plan_t* plan_in, size_t* bytes);
+int  pserve_resample_forward(const pserve_resample_t* op, const pserve_plan_t* plan_in, const pserve_plan_t* plan_out,
+                             const void* x, void* workspace, size_t workspace_bytes, void* y, void* stream);
 
 /* Kernel selection for measurements and tests: 0 = fastest path available for the
  * shapes (MFMA kernels where they apply), 1 = plain reference kernels only. */

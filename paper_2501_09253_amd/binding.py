@@ -105,6 +105,11 @@ def lib() -> C.CDLL:
                                     C.POINTER(C.c_uint8), vp, vp]
     L.pserve_cache_migrate.argtypes = [vp, vp, vp, vp, vp]
     L.pserve_profile_read.argtypes = [C.POINTER(_ProfEntry), i32, C.POINTER(i32)]
+    L.pserve_resample_create.argtypes = [C.c_int, i32, i32, C.c_int, vp, vp, vp, C.POINTER(vp)]
+    L.pserve_resample_free.argtypes = [vp]
+    L.pserve_resample_free.restype = None
+    L.pserve_resample_workspace.argtypes = [vp, vp, C.POINTER(C.c_size_t)]
+    L.pserve_resample_forward.argtypes = [vp, vp, vp, vp, vp, C.c_size_t, vp, vp]
     _lib = L
     return L
 
@@ -329,6 +334,51 @@ class Cache:
     def close(self):
         if self._h:
             lib().pserve_cache_free(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+DOWN2, UP2 = 1, 2
+
+
+class Resample:
+    """pserve_resample: stride-2 (DOWN2) or nearest-up (UP2) 3x3 convolution between two plans with the same patch grid."""
+
+    def __init__(self, kind: int, w, b, dtype: int):
+        assert w.is_contiguous() and b.is_contiguous() and w.dtype == _torch_dtype(dtype) and b.dtype == w.dtype
+        self.kind, self.dtype, self.C_out, self.C_in = kind, dtype, int(w.shape[0]), int(w.shape[1])
+        self._h = C.c_void_p()
+        _check(lib().pserve_resample_create(kind, self.C_in, self.C_out, dtype, w.data_ptr(), b.data_ptr(), _stream(),
+                                            C.byref(self._h)))
+        self._ws = None
+
+    def workspace_bytes(self, plan_in: "Plan") -> int:
+        n = C.c_size_t()
+        _check(lib().pserve_resample_workspace(self._h, plan_in._h, C.byref(n)))
+        return int(n.value)
+
+    def forward(self, plan_in: "Plan", plan_out: "Plan", x, y=None, workspace=None):
+        import torch
+        assert x.is_contiguous() and tuple(x.shape) == (plan_in.T, self.C_in) and x.dtype == _torch_dtype(self.dtype)
+        if workspace is None:
+            need = self.workspace_bytes(plan_in)
+            if self._ws is None or self._ws.numel() < need:
+                self._ws = torch.empty(need, dtype=torch.uint8, device=x.device)
+            workspace = self._ws
+        if y is None:
+            y = torch.empty((plan_out.T, self.C_out), dtype=x.dtype, device=x.device)
+        _check(lib().pserve_resample_forward(self._h, plan_in._h, plan_out._h, x.data_ptr(), workspace.data_ptr(),
+                                             workspace.numel() * workspace.element_size(), y.data_ptr(), _stream()))
+        return y
+
+    def close(self):
+        if self._h:
+            lib().pserve_resample_free(self._h)
             self._h = C.c_void_p()
 
     def __del__(self):

@@ -41,7 +41,9 @@ __device__ __forceinline__ RowInfo row_info(const GemmArgs& a, int ri) {
     if (a.conv) {
         const int p = (int)(tok / a.geom.S), q = (int)(tok - (int64_t)p * a.geom.S);
         const int y = q / a.geom.pw, x = q - y * a.geom.pw;
-        r.a_off = ((int64_t)p * a.geom.pS + y * a.geom.ppw + x) * a.lda;
+        const int am = a.a_mul ? a.a_mul : 1;
+        r.a_off = ((int64_t)p * a.geom.pS + (am * y + a.a_dy) * a.geom.ppw + am * x + a.a_dx) * a.lda;
+        if (a.o_mul) r.out_row = (int64_t)p * a.o_S + (a.o_mul * y + a.o_dy) * a.o_pw + a.o_mul * x + a.o_dx;
     } else {
         r.a_off = tok * a.lda;
     }
@@ -87,7 +89,8 @@ gemm_simple_kernel(GemmArgs a) {
     const int tx = tid & 15, ty = tid >> 4;
     float acc[NB][4][4] = {};
     for (int tap = 0; tap < a.taps; ++tap) {
-        const int64_t tap_off = a.conv ? ((int64_t)(tap / 3) * a.geom.ppw + (tap % 3)) * a.lda : 0;
+        const int tw = a.tap_w ? a.tap_w : 3;
+        const int64_t tap_off = a.conv ? ((int64_t)(tap / tw) * a.geom.ppw + (tap % tw)) * a.lda : 0;
         for (int k0 = 0; k0 < a.K; k0 += BK) {
             for (int i = tid; i < BM * BK; i += 256) {
                 const int m = i / BK, k = i - m * BK;
@@ -162,6 +165,24 @@ __global__ void pack_conv_kernel(const T* __restrict__ w, T* __restrict__ dst, i
     dst[i] = w[((int64_t)co * Cin + ci) * 9 + tap];
 }
 
+// four parity classes x four taps of the nearest-up convolution (see pack_conv_up2 in kernels.h)
+template <typename T>
+__global__ void pack_conv_up2_kernel(const T* __restrict__ w, T* __restrict__ dst, int32_t Cout, int32_t Cin) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;       // over dst [4][4][Cout][Cin]
+    if (i >= (int64_t)16 * Cout * Cin) return;
+    const int ci = (int)(i % Cin);
+    const int co = (int)((i / Cin) % Cout);
+    const int t = (int)(i / ((int64_t)Cin * Cout));
+    const int cls = t >> 2, a = cls >> 1, b = cls & 1, j = (t >> 1) & 1, ii = t & 1;
+    // 3x3 rows merged into 2x2 row j: a = 0: {0}, {1, 2};  a = 1: {0, 1}, {2}
+    const int y0 = a == 0 ? (j == 0 ? 0 : 1) : (j == 0 ? 0 : 2), y1 = a == 0 ? (j == 0 ? 0 : 2) : (j == 0 ? 1 : 2);
+    const int x0 = b == 0 ? (ii == 0 ? 0 : 1) : (ii == 0 ? 0 : 2), x1 = b == 0 ? (ii == 0 ? 0 : 2) : (ii == 0 ? 1 : 2);
+    float acc = 0.f;
+    for (int ty = y0; ty <= y1; ++ty)
+        for (int tx = x0; tx <= x1; ++tx) acc += ld_f<T>(w + ((int64_t)co * Cin + ci) * 9 + ty * 3 + tx);
+    st_f<T>(dst + i, acc);
+}
+
 // dst row (row0 + perm(n)) = column n of w[K][Ncols]; geglu_F > 0 applies the value/gate interleave
 template <typename T>
 __global__ void pack_linear_kernel(const T* __restrict__ w, T* __restrict__ dst, int32_t K, int32_t Ncols, int32_t row0,
@@ -203,6 +224,13 @@ int pack_conv(const void* w, void* dst, int32_t Cout, int32_t Cin, int dtype, hi
     if (dtype == PSERVE_BF16) pack_conv_kernel<uint16_t><<<grid, 256, 0, st>>>((const uint16_t*)w, (uint16_t*)dst, Cout, Cin);
     else pack_conv_kernel<float><<<grid, 256, 0, st>>>((const float*)w, (float*)dst, Cout, Cin);
     return check_launch("pack_conv_kernel");
+}
+
+int pack_conv_up2(const void* w, void* dst, int32_t Cout, int32_t Cin, int dtype, hipStream_t st) {
+    const unsigned grid = (unsigned)cdiv((int64_t)16 * Cout * Cin, 256);
+    if (dtype == PSERVE_BF16) pack_conv_up2_kernel<uint16_t><<<grid, 256, 0, st>>>((const uint16_t*)w, (uint16_t*)dst, Cout, Cin);
+    else pack_conv_up2_kernel<float><<<grid, 256, 0, st>>>((const float*)w, (float*)dst, Cout, Cin);
+    return check_launch("pack_conv_up2_kernel");
 }
 
 static int pack_linear_impl(const void* w, void* dst, int32_t K, int32_t Ncols, int32_t row0, int32_t gF, int dtype,

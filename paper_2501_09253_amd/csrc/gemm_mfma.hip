@@ -318,6 +318,7 @@ gemm_mfma_kernel(GemmArgs a) {
     const int kchunks = a.K / BK;
     const int KT = a.taps * kchunks;
     const int64_t b_tap_stride = (int64_t)a.N * a.K;
+    const int tap_w = a.tap_w ? a.tap_w : 3;
     int tap, kc, issued;                            // K step that is issued next (stays at the last one past the end:
                                                     // it is fetched again into a free stage and never read)
 
@@ -336,17 +337,18 @@ gemm_mfma_kernel(GemmArgs a) {
                 valid = tok < a.M;                                                                                \
                 if (!valid) tok = 0;                                                                              \
             }                                                                                                     \
-            int64_t off;                                                                                          \
+            int64_t off, orow = tok;                                                                              \
             if (a.conv) {                                                                                         \
                 const int p = (int)(tok / a.geom.S), q = (int)(tok - (int64_t)p * a.geom.S);                      \
                 const int y = q / a.geom.pw, x = q - y * a.geom.pw;                                               \
-                off = ((int64_t)p * a.geom.pS + y * a.geom.ppw + x) * a.lda;                                      \
+                const int am = a.a_mul ? a.a_mul : 1;                                                             \
+                off = ((int64_t)p * a.geom.pS + (am * y + a.a_dy) * a.geom.ppw + am * x + a.a_dx) * a.lda;        \
+                if (a.o_mul) orow = (int64_t)p * a.o_S + (a.o_mul * y + a.o_dy) * a.o_pw + a.o_mul * x + a.o_dx;  \
             } else {                                                                                              \
                 off = tok * a.lda;                                                                                \
             }                                                                                                     \
             a_ptr[i] = A + off + gc * 8;                                                                          \
             if (lc == 0) {                                                                                        \
-                int64_t orow = tok;                                                                               \
                 if (!a.tokens_are_rows && a.row_group > 0)                                                        \
                     orow = (tok / a.row_group) * a.row_group_pad + tok % a.row_group;                             \
                 (tok_tab)[row] = valid ? (int32_t)orow : -1;                                                      \
@@ -366,7 +368,7 @@ gemm_mfma_kernel(GemmArgs a) {
     }
     // global offsets of K step (tap, kc)
 #define PS_OFFSETS(tap_, kc_)                                                                                     \
-    const int ty_ = (tap_) / 3, tx_ = (tap_) - ty_ * 3;                                                           \
+    const int ty_ = (tap_) / tap_w, tx_ = (tap_) - ty_ * tap_w;                                                   \
     const int64_t a_off = (a.conv ? ((int64_t)ty_ * a.geom.ppw + tx_) * a.lda : 0) + (kc_) * BK;                  \
     const int64_t b_off = (tap_) * b_tap_stride + (kc_) * BK;
     // the first NS steps of a tile: all stages in flight
@@ -774,7 +776,8 @@ static bool mfma_eligible(const GemmArgs& a) {
 // bytes per MFMA of the 128 x 320 tile at the same accumulator shape.
 static int conv_select(const GemmArgs& a, ConvTile* ct, int* wave_cols = nullptr) {
     int wc = 0, sel = 0;
-    if (a.epi == EPI_ROUTE && a.seg_cols % 32 == 0 && a.seg_cols == a.N && !a.seg[0].transposed) {
+    const bool plain3x3 = a.taps == 9 && (a.tap_w == 0 || a.tap_w == 3) && a.a_mul <= 1 && !a.a_dy && !a.a_dx && !a.o_mul;
+    if (plain3x3 && a.epi == EPI_ROUTE && a.seg_cols % 32 == 0 && a.seg_cols == a.N && !a.seg[0].transposed) {
         if (a.N % 160 == 0 && conv_tile(a, 256, 384, ct)) { sel = 1; wc = 160; }
         else if (conv_tile(a, 128, 256, ct)) {
             if (a.N % 320 == 0) { sel = 2; wc = 160; }

@@ -77,7 +77,14 @@ enum { EPI_ROUTE = 0, EPI_GEGLU = 1 };
 struct GemmArgs {
     const void* A;             // linear: [rows][lda]; conv: padded patch buffer
     int64_t lda;
-    int32_t conv;              // 1: rows are tokens read through the padded layout with 9 taps
+    int32_t conv;              // 1: rows are tokens read through the padded layout with `taps` taps
+    // conv only (0 = the defaults 3 / 1 / identity): taps are laid out tap_w per pixel row; row token (p, y, x) reads
+    // the padded pixels (a_mul*y + a_dy + ty, a_mul*x + a_dx + tx) of patch p (a_mul = 2: stride-2 convolution whose
+    // rows are OUTPUT tokens of the half-size patch geometry in `geom.S / geom.pw`, while geom.ppw / geom.pS stay those
+    // of the input); with o_mul = 2 the result of row (p, y, x) goes to token p*o_S + (2y + o_dy)*o_pw + 2x + o_dx
+    // (one parity class of a nearest-up convolution, whose rows are INPUT tokens)
+    int32_t tap_w, a_mul, a_dy, a_dx;
+    int32_t o_mul, o_dy, o_dx, o_S, o_pw;
     PatchGeom geom;
     ActiveList act;            // row compaction by patch (rows are tokens)
     int32_t tokens_are_rows;   // 1: row ids are token ids (act applies); 0: plain row ids (M rows)
@@ -111,6 +118,10 @@ int pack_linear(const void* w, void* dst, int32_t K, int32_t Ncols, int32_t row0
 // GEGLU: W1[K][2F] -> dst[2F][K] with value / gate columns interleaved in groups of GEGLU_GROUP
 int pack_geglu(const void* w1, const void* b1, void* dst, float* bias_dst, int32_t K, int32_t F, int dtype, hipStream_t st);
 int pack_bias(const void* b, float* dst, int32_t N, int dtype, hipStream_t st);
+// Nearest-up 2x followed by a 3x3 convolution = four 2x2-tap convolutions on the input, one per output parity (a, b):
+// dst[(2a+b)][2j+i][Cout][Cin] = sum of the 3x3 taps (ty, tx) that fall on input pixel (y - 1 + a + j, x - 1 + b + i),
+// i.e. rows {0 | 1,2} for a = 0 and {0,1 | 2} for a = 1 (same for columns); summed in fp32, rounded once.
+int pack_conv_up2(const void* w, void* dst, int32_t Cout, int32_t Cin, int dtype, hipStream_t st);
 constexpr int GEGLU_GROUP = 64;
 
 // ---- attention (attn.hip) -------------------------------------------------------------------------

@@ -237,11 +237,16 @@ __global__ void gn_apply_kernel(const T* __restrict__ x, const float* __restrict
 #pragma unroll
         for (int u = 0; u < GN_U; ++u) raw[u] = *reinterpret_cast<const uint4*>(xin + min(in_off + u * step_in, last_in));
     }
-    const int s = owner[p];
     float sc[VN], sh[VN];
-    const float* ss = scale_shift + ((int64_t)s * C + cv * VN) * 2;
+    if (scale_shift) {
+        const int s = owner[p];
+        const float* ss = scale_shift + ((int64_t)s * C + cv * VN) * 2;
 #pragma unroll
-    for (int e = 0; e < VN; ++e) { sc[e] = ss[2 * e]; sh[e] = ss[2 * e + 1]; }
+        for (int e = 0; e < VN; ++e) { sc[e] = ss[2 * e]; sh[e] = ss[2 * e + 1]; }
+    } else {                                    // no table: plain copy into the padded layout (with the rims)
+#pragma unroll
+        for (int e = 0; e < VN; ++e) { sc[e] = 1.f; sh[e] = 0.f; }
+    }
     int32_t nb[8];                              // neighbour patches, read once (no dependent loads behind the stores)
 #pragma unroll
     for (int k = 0; k < 8; ++k) nb[k] = (PADDED && STITCH) ? neighbour[8 * p + k] : -1;

@@ -72,3 +72,11 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(binding, "library_path", lambda: "/nonexistent/libpserve.so")
     with pytest.raises(ImportError):
         binding.lib()
+
+
+def test_resample_argument_validation():
+    L = ps.lib()
+    out = C.c_void_p()
+    assert L.pserve_resample_create(3, 8, 8, 1, None, None, None, C.byref(out)) == -1       # unknown kind
+    assert L.pserve_resample_create(1, 8, 8, 1, None, None, None, C.byref(out)) == -1       # NULL parameters
+    assert L.pserve_resample_forward(None, None, None, None, None, 0, None, None) == -1
