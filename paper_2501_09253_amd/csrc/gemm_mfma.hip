@@ -818,7 +818,8 @@ int gemm_mfma_bf16(const GemmArgs& a, hipStream_t st, bool* handled) {
     case 5: *handled = true; return launch_conv<128, 64, 2, 2, 256, 2>(a, ct, st);
     default: break;
     }
-    // Tile choice.  Preferred: 256 rows, four wavefronts stacked along M (each 64 x 160 or 64 x 128), three stages.
+    // Tile choice.  Preferred: 256 rows, four wavefronts stacked along M (each 64 x 160 or 64 x 128), two stages and
+    // the next tile's first loads issued before the epilogue.
     // With fewer blocks than that leaves busy CUs, 128-row tiles; with few rows altogether (the text-token
     // projections) the narrowest tile, two blocks per CU.
     const int64_t m256 = cdiv(a.M, 256), m128 = cdiv(a.M, 128);
