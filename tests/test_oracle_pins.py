@@ -18,6 +18,7 @@ from oracle import block as ob
 from oracle import plan as op
 from oracle import cache as oc
 from oracle import resample as orr
+from oracle import sched as osc
 
 RNG = np.random.default_rng(7)
 
@@ -732,3 +733,54 @@ def test_up2_closed_forms_and_plain_loops():
                             if 0 <= Y < 2 and 0 <= X < 4:
                                 acc += k[co, ci, ty, tx] * u[ci, Y, X]
                 assert abs(got[co, oy, ox] - acc) < 1e-12
+
+
+# ----------------------------------------------------------------------------- scheduler pieces
+def _T(i, hw, steps, arrival, ddl, sa):
+    return osc.Task(i, hw, hw, steps, float(arrival), float(ddl), float(sa))
+
+
+def test_slack_and_latency_model_by_hand():
+    """Slack = (DDL - C - P) / SA with the numbers of the section's definition worked by hand; the model's features
+    for a 64x64 + 64x64 + 128x128 batch at 32x32 patches are 4 + 4 + 16 patches, 2 resolutions and
+    1e-6 (4096^2 + 4096^2 + 16384^2) = 301.989888."""
+    t = _T(1, 64, 10, 50, 200, 20)
+    assert osc.slack(t, 100.0, 3.5) == (200.0 - 50.0 - 35.0) / 20.0 == 5.75
+    assert not osc.time_out(t, 100.0, 3.5) and osc.time_out(t, 100.0, 15.1)         # 100 + 151 > 250
+    batch = [_T(1, 64, 1, 0, 1, 1), _T(2, 64, 1, 0, 1, 1), _T(3, 128, 1, 0, 1, 1)]
+    assert osc.features(batch, 32, 32) == (24.0, 2.0, 301.989888)
+    assert abs(osc.predict([2.0, 0.5, 3.0, 0.01], batch, 32, 32) - (2.0 + 12.0 + 6.0 + 3.01989888)) < 1e-12
+
+
+def test_latency_fit_recovers_a_linear_law():
+    rng = np.random.default_rng(5)
+    X = rng.uniform(1, 50, size=(40, 3))
+    w = np.array([1.5, 0.25, 2.0, 0.125])
+    y = w[0] + X @ w[1:]
+    assert np.allclose(osc.fit(X, y), w, atol=1e-9)
+
+
+def test_schedule_hand_derived_scenarios():
+    """Latency law 1 + 0.5 * patches (32x32 patches: 32^2 = 1, 64^2 = 4, 128^2 = 16 patches), now = 100.
+
+    A. active {64^2, 10 steps, arrival 0, DDL 300, SA 50}; waiting W0 {32^2, 10 steps, arr 50, DDL 200, SA 20},
+       W1 {128^2, 40 steps, arr 0, DDL 500, SA 200}, W2 {64^2, 5 steps, arr 90, DDL 100, SA 50}; relaxed slack 2.
+       Slacks in the batch each would join: W0 (200-50-35)/20 = 5.75, W1 (500-100-440)/200 = -0.2, W2 (100-10-25)/50 = 1.3.
+       W1 first: 100 + 40*11 = 540 > 500, discarded.  W2 next (1.3 <= 2: urgent mode): the active task ends at
+       100 + 10*5 = 150 <= 300, admitted.  W0 last (slack (200-50-55)/20 = 4.75 > 2: throughput mode, sole candidate);
+       most urgent active is W2 (1.3 against 3.0), 100 + 5*5.5 = 127.5 <= 190, admitted.  -> admitted [2, 0], discarded [1]
+    B. active {64^2, 20 steps, arr 0, DDL 165, SA 50} (alone: ends at 160); waiting {32^2, 2 steps}: with it the
+       active task would end at 100 + 20*3.5 = 170 > 165 -> stop, nothing admitted.
+    C. nothing active; waiting W0 {64^2, SA 50} slack (1000-100-30)/50 = 17.4, W1 {128^2, SA 10} slack
+       (1000-100-90)/10 = 81: least slack is W0 but 17.4 > 2, throughput mode: 4096/3 = 1365 against 16384/9 = 1820
+       tokens per ms -> W1 first, then W0.  -> admitted [1, 0]"""
+    w = [1.0, 0.5, 0.0, 0.0]
+    act = [_T(9, 64, 10, 0, 300, 50)]
+    wait = [_T(0, 32, 10, 50, 200, 20), _T(1, 128, 40, 0, 500, 200), _T(2, 64, 5, 90, 100, 50)]
+    assert osc.schedule(wait, act, 100.0, w, 32, 32, 2.0) == ([2, 0], [1])
+    act = [_T(9, 64, 20, 0, 165, 50)]
+    wait = [_T(0, 32, 2, 95, 100, 10)]
+    assert osc.schedule(wait, act, 100.0, w, 32, 32, 100.0) == ([], [])
+    wait = [_T(0, 64, 10, 0, 1000, 50), _T(1, 128, 10, 0, 1000, 10)]
+    assert osc.schedule(wait, [], 100.0, w, 32, 32, 2.0) == ([1, 0], [])
+    assert osc.schedule(wait, [], 100.0, w, 32, 32, 50.0) == ([0, 1], [])            # urgent mode: slack order
