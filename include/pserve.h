@@ -250,6 +250,40 @@ int  pserve_resample_workspace(const pserve_resample_t* op, const pserve_plan_t*
 int  pserve_resample_forward(const pserve_resample_t* op, const pserve_plan_t* plan_in, const pserve_plan_t* plan_out,
                              const void* x, void* workspace, size_t workspace_bytes, void* y, void* stream);
 
+/* ---- host-side scheduler pieces (section "SLO-Aware Scheduler").  All pointers HOST; no GPU work; times in ms.
+ *
+ * pserve_task: a request as the scheduler sees it.  ddl = its SLO budget counted from arrival (DDL_i), standalone =
+ * its latency when run alone (SA_i), steps_left = denoising steps still to run.
+ * pserve_slack: the slack score of "SLO-based Scheduling Algorithm": (DDL_i - C_i - P_i) / SA_i with C_i = now -
+ * arrival and P_i = steps_left * latency (the predicted per-step latency of the batch the task runs in).
+ * pserve_latency_model: stands in for the MLP of "Mixed-Resolution Throughput Analyzer" (which needs the authors'
+ * measurements); same inputs, reduced to three features of a batch at patch size ph x pw: per-step latency =
+ * w[0] + w[1] * total patches + w[2] * distinct resolutions + w[3] * 1e-6 * sum_i (H_i W_i)^2.
+ * pserve_latency_fit: ordinary least squares on m >= 4 samples, X [m][3] = the three features, y [m] = measured
+ * latency.  EINVAL if the samples do not determine the four coefficients.
+ * pserve_schedule: the scheduling loop of the section's algorithm.  Repeats: take the least-slack waiting task (slack
+ * with the latency of the batch it would join) and the least-slack active task; if the candidate would miss its
+ * deadline even so (now + steps_left * latency > arrival + ddl) it is discarded; if its slack exceeds relaxed_slack
+ * the candidate becomes the waiting task with the most batch tokens per predicted millisecond (among those that
+ * would meet their deadline); if the least-slack active task would miss its deadline with the candidate on board the
+ * loop stops, else the candidate is admitted and counts as active from then on.  Ties go to queue order.
+ * admitted / discarded: HOST int32 [n_wait] each, indices into `wait` in the order decided.
+ * Errors: EINVAL (NULL, resolutions that are not multiples of the patch, standalone <= 0). */
+typedef struct {
+    int64_t id;
+    int32_t H, W;
+    int32_t steps_left;
+    double  arrival, ddl, standalone;
+} pserve_task;
+typedef struct { double w[4]; } pserve_latency_model;
+int  pserve_latency_predict(const pserve_latency_model* model, const pserve_task* batch, int32_t n, int32_t ph,
+                            int32_t pw, double* latency);
+int  pserve_latency_fit(const double* X, const double* y, int32_t m, pserve_latency_model* model);
+int  pserve_slack(const pserve_task* task, double now, double latency, double* slack);
+int  pserve_schedule(const pserve_task* wait, int32_t n_wait, const pserve_task* active, int32_t n_active, double now,
+                     const pserve_latency_model* model, int32_t ph, int32_t pw, double relaxed_slack,
+                     int32_t* admitted, int32_t* n_admitted, int32_t* discarded, int32_t* n_discarded);
+
 /* Kernel selection for measurements and tests: 0 = fastest path available for the
  * shapes (MFMA kernels where they apply), 1 = plain reference kernels only. */
 int  pserve_set_kernel_mode(int mode);

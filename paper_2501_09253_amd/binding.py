@@ -55,6 +55,15 @@ class _ProfEntry(C.Structure):
     _fields_ = [("name", C.c_char * 32), ("calls", C.c_int32), ("total_ms", C.c_float)]
 
 
+class _Task(C.Structure):
+    _fields_ = [("id", C.c_int64), ("H", C.c_int32), ("W", C.c_int32), ("steps_left", C.c_int32),
+                ("arrival", C.c_double), ("ddl", C.c_double), ("standalone", C.c_double)]
+
+
+class _LatencyModel(C.Structure):
+    _fields_ = [("w", C.c_double * 4)]
+
+
 class _BlockParams(C.Structure):
     _fields_ = [("p", (C.c_void_p * MAX_PARAMS) * MAX_STAGES)]
 
@@ -105,6 +114,11 @@ def lib() -> C.CDLL:
                                     C.POINTER(C.c_uint8), vp, vp]
     L.pserve_cache_migrate.argtypes = [vp, vp, vp, vp, vp]
     L.pserve_profile_read.argtypes = [C.POINTER(_ProfEntry), i32, C.POINTER(i32)]
+    L.pserve_latency_predict.argtypes = [C.POINTER(_LatencyModel), C.POINTER(_Task), i32, i32, i32, C.POINTER(C.c_double)]
+    L.pserve_latency_fit.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double), i32, C.POINTER(_LatencyModel)]
+    L.pserve_slack.argtypes = [C.POINTER(_Task), C.c_double, C.c_double, C.POINTER(C.c_double)]
+    L.pserve_schedule.argtypes = [C.POINTER(_Task), i32, C.POINTER(_Task), i32, C.c_double, C.POINTER(_LatencyModel), i32, i32,
+                                  C.c_double, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
     L.pserve_resample_create.argtypes = [C.c_int, i32, i32, C.c_int, vp, vp, vp, C.POINTER(vp)]
     L.pserve_resample_free.argtypes = [vp]
     L.pserve_resample_free.restype = None
@@ -386,3 +400,50 @@ class Resample:
             self.close()
         except Exception:
             pass
+
+
+# ---- host-side scheduler pieces (tasks are tuples (id, H, W, steps_left, arrival, ddl, standalone), times in ms)
+def _tasks(ts):
+    arr = (_Task * max(1, len(ts)))()
+    for i, t in enumerate(ts):
+        arr[i] = _Task(*t)
+    return arr
+
+
+def _model(w):
+    m = _LatencyModel()
+    for i in range(4):
+        m.w[i] = float(w[i])
+    return m
+
+
+def latency_predict(w, batch, ph, pw) -> float:
+    out = C.c_double()
+    _check(lib().pserve_latency_predict(C.byref(_model(w)), _tasks(batch), len(batch), ph, pw, C.byref(out)))
+    return out.value
+
+
+def latency_fit(X, y):
+    import numpy as np
+    X = np.ascontiguousarray(X, dtype=np.float64)
+    y = np.ascontiguousarray(y, dtype=np.float64)
+    m = _LatencyModel()
+    _check(lib().pserve_latency_fit(X.ctypes.data_as(C.POINTER(C.c_double)), y.ctypes.data_as(C.POINTER(C.c_double)),
+                                    X.shape[0], C.byref(m)))
+    return [m.w[i] for i in range(4)]
+
+
+def slack(task, now, latency) -> float:
+    out = C.c_double()
+    _check(lib().pserve_slack(_tasks([task]), now, latency, C.byref(out)))
+    return out.value
+
+
+def schedule(wait, active, now, w, ph, pw, relaxed_slack):
+    """pserve_schedule: returns (admitted, discarded), indices into `wait` in the order decided."""
+    n = len(wait)
+    adm, dis = (C.c_int32 * max(1, n))(), (C.c_int32 * max(1, n))()
+    na, nd = C.c_int32(), C.c_int32()
+    _check(lib().pserve_schedule(_tasks(wait), n, _tasks(active), len(active), now, C.byref(_model(w)), ph, pw,
+                                 relaxed_slack, adm, C.byref(na), dis, C.byref(nd)))
+    return list(adm[:na.value]), list(dis[:nd.value])
