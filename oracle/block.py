@@ -30,6 +30,13 @@ Readings of points the paper leaves open (each also listed in the design notes):
     lists such per-pixel operators among those that patching leaves untouched,
     Patch-Tailored Diffusion Operators): biased variance, same eps, per-channel affine.
     Nothing of a reused patch's input is needed by them, so only K and V are cached.
+  * ASATTN and AMLP are the self-attention and feed-forward sub-layers of a block of the
+    paper's second model family (a diffusion transformer): the request's conditioning
+    vector c goes through SiLU and a linear layer to three C-vectors (shift, scale, gate);
+    the sub-layer sees LN0(x) * (1 + scale) + shift (LN0: LayerNorm without affine) and
+    its output is multiplied by gate before the residual add.  The feed-forward is
+    GELU(h W_1 + b_1) W_2 + b_2 with the tanh form of GELU (that model's choice).  The
+    joint text-image attention of that model is not part of these stages.
   * RES2T is RES2 with the time embedding of the first model's residual block: the
     request's embedding vector goes through SiLU and a linear layer, and the resulting
     C values are added to every pixel of the first convolution's output (a per-pixel
@@ -61,6 +68,11 @@ F64 = np.float64
 def silu(u: np.ndarray) -> np.ndarray:
     """SiLU(u) = u / (1 + exp(-u))."""
     return u / (1.0 + np.exp(-u))
+
+
+def gelu_tanh(u: np.ndarray) -> np.ndarray:
+    """GELU, tanh form: u/2 * (1 + tanh(sqrt(2/pi) * (u + 0.044715 u^3)))."""
+    return 0.5 * u * (1.0 + np.tanh(np.sqrt(2.0 / np.pi) * (u + 0.044715 * u ** 3)))
 
 
 def gelu(u: np.ndarray) -> np.ndarray:
@@ -242,6 +254,46 @@ def lsattn(x, p, heads, eps, reuse_px=None, cache=None, key="", new_cache=None, 
     return yt if rows is not None else _image(yt, H, W)
 
 
+def _modulation(cvec, p):
+    """(shift, scale, gate), each [C]: thirds of SiLU(c) W_m + b_m."""
+    m = silu(np.asarray(cvec, dtype=F64)) @ p["wm"].astype(F64) + p["bm"].astype(F64)
+    C = m.shape[0] // 3
+    return m[:C], m[C:2 * C], m[2 * C:]
+
+
+def _ln0_mod_tokens(xt, shift, scale, eps):
+    """LayerNorm without affine of every row of xt [N, C], then * (1 + scale) + shift."""
+    C = xt.shape[1]
+    xh = _tokens(layer_norm(_image(xt, xt.shape[0], 1), np.ones(C), np.zeros(C), eps))
+    return xh * (1.0 + scale) + shift
+
+
+def asattn(x, p, heads, eps, cvec, reuse_px=None, cache=None, key="", new_cache=None, rows=None):
+    """ASATTN(x) = x + gate * (MHA(h) W_o + b_o), h = LN0(x) * (1 + scale) + shift.  K, V cached like LSATTN."""
+    C, H, W = x.shape
+    shift, scale, gate = _modulation(cvec, p)
+    u = _ln0_mod_tokens(_tokens(x), shift, scale, eps)
+    Q = u @ p["wq"].astype(F64)
+    K = u @ p["wk"].astype(F64)
+    V = u @ p["wv"].astype(F64)
+    if reuse_px is not None:
+        K = _tokens(_fill(_image(K, H, W), cache[key + "K"], reuse_px))
+        V = _tokens(_fill(_image(V, H, W), cache[key + "V"], reuse_px))
+        new_cache[key + "K"] = _image(K, H, W)
+        new_cache[key + "V"] = _image(V, H, W)
+    O = attention(Q, K, V, heads, rows=rows)
+    xt = _tokens(x) if rows is None else _tokens(x)[rows]
+    yt = xt + gate * (O @ p["wo"].astype(F64) + p["bo"].astype(F64))
+    return yt if rows is not None else _image(yt, H, W)
+
+
+def amlp_tokens(xt, p, eps, cvec):
+    """AMLP(x) = x + gate * (GELU_tanh(h W_1 + b_1) W_2 + b_2), h = LN0(x) * (1 + scale) + shift."""
+    shift, scale, gate = _modulation(cvec, p)
+    h = _ln0_mod_tokens(xt, shift, scale, eps) @ p["w1"].astype(F64) + p["b1"].astype(F64)
+    return xt + gate * (gelu_tanh(h) @ p["w2"].astype(F64) + p["b2"].astype(F64))
+
+
 def _ln_tokens(xt, p, eps):
     """LayerNorm of tokens [N, C] (each row on its own)."""
     return _tokens(layer_norm(_image(xt, xt.shape[0], 1), p["ln_g"], p["ln_b"], eps))
@@ -301,8 +353,8 @@ def block_forward(z: np.ndarray, stages: Sequence[str], params: List[Dict[str, n
         reuse_px = np.repeat(np.repeat(np.asarray(reuse, dtype=bool), H // gh, axis=0), W // gw, axis=1)
     tokens = None                      # set once only sampled rows are carried
     if rows is not None:
-        last_ctx = max(i for i, s in enumerate(stages) if s in ("RES1", "RES2", "RES2T", "SATTN", "LSATTN"))
-        assert stages[last_ctx] in ("SATTN", "LSATTN"), "rows need a self-attention as the last context stage"
+        last_ctx = max(i for i, s in enumerate(stages) if s in ("RES1", "RES2", "RES2T", "SATTN", "LSATTN", "ASATTN"))
+        assert stages[last_ctx] in ("SATTN", "LSATTN", "ASATTN"), "rows need a self-attention as the last context stage"
     for si, (st, p) in enumerate(zip(stages, params)):
         key = f"{si}."
         if st == "RES1":
@@ -321,6 +373,16 @@ def block_forward(z: np.ndarray, stages: Sequence[str], params: List[Dict[str, n
                 tokens = lsattn(x, p, heads, eps, reuse_px, cache, key, new_cache, rows=rows)
             else:
                 x = lsattn(x, p, heads, eps, reuse_px, cache, key, new_cache)
+        elif st == "ASATTN":
+            if rows is not None and si == last_ctx:
+                tokens = asattn(x, p, heads, eps, temb, reuse_px, cache, key, new_cache, rows=rows)
+            else:
+                x = asattn(x, p, heads, eps, temb, reuse_px, cache, key, new_cache)
+        elif st == "AMLP":
+            if tokens is not None:
+                tokens = amlp_tokens(tokens, p, eps, temb)
+            else:
+                x = _image(amlp_tokens(_tokens(x), p, eps, temb), H, W)
         elif st in ("LXATTN", "LFFN"):
             f = (lambda t: lxattn_tokens(t, p, heads, ctx, eps)) if st == "LXATTN" else (lambda t: lffn_tokens(t, p, eps))
             if tokens is not None:

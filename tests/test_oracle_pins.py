@@ -266,6 +266,35 @@ def test_res2t_time_embedding_closed_forms():
     assert np.allclose(ncz[0]["0.h1"], np.broadcast_to(p["bt"].astype(np.float64)[:, None, None], w.images[0].shape), atol=1e-15)
 
 
+def test_adaln_closed_forms():
+    """W_m = 0 with b_m = (0, 0, gate): the modulation is the identity on LN0(x), the sub-layer output is scaled by the
+    gate; gate 0 returns x exactly (the zero-initialised form); GELU tanh form at 1: 0.5 (1 + tanh(sqrt(2/pi) 1.044715))."""
+    assert abs(float(ob.gelu_tanh(np.array(1.0))) - 0.5 * (1.0 + math.tanh(math.sqrt(2.0 / math.pi) * 1.044715))) < 1e-15
+    assert abs(float(ob.gelu_tanh(np.array(1.0))) - 0.8411919906082768) < 1e-12
+    cfg = wl.custom_config([(4, 6)], (2, 2), C=8, G=1, heads=2, stages=(wl.AMLP,), seed=14, temb_dim=5, ffn_mult=2)
+    w = wl.make_workload(cfg)
+    p = dict(w.params[0])
+    kw = dict(G=cfg.G, heads=cfg.heads, eps=cfg.eps)
+    z = w.images[0].astype(np.float64)
+    bm = np.zeros(24)
+    p0 = dict(p, wm=np.zeros_like(p["wm"]), bm=bm)
+    y0, _ = ob.block_forward(z, cfg.stages, [p0], temb=w.temb[0], **kw)
+    assert np.array_equal(y0, z)                                       # gate 0
+    bm1 = bm.copy()
+    bm1[16:] = 2.0
+    y1, _ = ob.block_forward(z, cfg.stages, [dict(p0, bm=bm1)], temb=w.temb[0], **kw)
+    xt = z.reshape(8, -1).T
+    xh = (xt - xt.mean(1, keepdims=True)) / np.sqrt(xt.var(1, keepdims=True) + cfg.eps)
+    d = ob.gelu_tanh(xh @ p["w1"].astype(np.float64) + p["b1"]) @ p["w2"].astype(np.float64) + p["b2"]
+    assert np.allclose(y1, (xt + 2.0 * d).T.reshape(z.shape), atol=1e-12)
+    bm2 = bm1.copy()
+    bm2[:8] = 0.5                                                      # shift 0.5
+    bm2[8:16] = 1.0                                                    # scale 1: h = 2 LN0(x) + 0.5
+    y2, _ = ob.block_forward(z, cfg.stages, [dict(p0, bm=bm2)], temb=w.temb[0], **kw)
+    d2 = ob.gelu_tanh((2.0 * xh + 0.5) @ p["w1"].astype(np.float64) + p["b1"]) @ p["w2"].astype(np.float64) + p["b2"]
+    assert np.allclose(y2, (xt + 2.0 * d2).T.reshape(z.shape), atol=1e-12)
+
+
 def test_attention_vs_three_pass_loops():
     Q, K, V = RNG.standard_normal((5, 6)), RNG.standard_normal((7, 6)), RNG.standard_normal((7, 6))
     assert np.allclose(ob.attention(Q, K, V, 2), _attn_three_pass(Q, K, V, 2), atol=1e-13)
@@ -341,6 +370,15 @@ def _torch_block(z, cfg, params, ctx, temb=None):
             h = xt @ t(p["w1"]) + t(p["b1"])
             a, g = h.chunk(2, dim=-1)
             x = (xt + (a * F.gelu(g)) @ t(p["w2"]) + t(p["b2"])).transpose(1, 2).reshape(1, C, H, W)
+        elif st in (wl.ASATTN, wl.AMLP):
+            xt = x.flatten(2).transpose(1, 2)
+            sh, sc, g = F.linear(F.silu(t(temb)), t(p["wm"]).T, t(p["bm"])).chunk(3)
+            u = F.layer_norm(xt, (C,), None, None, cfg.eps) * (1 + sc) + sh
+            if st == wl.ASATTN:
+                d = mha(u @ t(p["wq"]), u @ t(p["wk"]), u @ t(p["wv"])) @ t(p["wo"]) + t(p["bo"])
+            else:
+                d = F.gelu(u @ t(p["w1"]) + t(p["b1"]), approximate="tanh") @ t(p["w2"]) + t(p["b2"])
+            x = (xt + g * d).transpose(1, 2).reshape(1, C, H, W)
         elif st in (wl.LSATTN, wl.LXATTN, wl.LFFN):
             xt = x.flatten(2).transpose(1, 2)
             u = F.layer_norm(xt, (C,), t(p["ln_g"]), t(p["ln_b"]), cfg.eps)
@@ -358,7 +396,8 @@ def _torch_block(z, cfg, params, ctx, temb=None):
 
 @pytest.mark.parametrize("stages", [
     (wl.RES1, wl.SATTN), (wl.RES2,), (wl.SATTN, wl.XATTN, wl.FFN), (wl.RES2, wl.SATTN, wl.XATTN),
-    (wl.LSATTN, wl.LXATTN, wl.LFFN), (wl.RES2, wl.LSATTN, wl.LFFN), (wl.RES2T, wl.LSATTN)])
+    (wl.LSATTN, wl.LXATTN, wl.LFFN), (wl.RES2, wl.LSATTN, wl.LFFN), (wl.RES2T, wl.LSATTN),
+    (wl.ASATTN, wl.AMLP)])
 def test_block_vs_torch_composition(stages):
     cfg = wl.custom_config([(6, 8), (4, 4)], (2, 2), C=16, G=4, heads=2, stages=stages,
                            ctx_len=5, ctx_dim=12, seed=99, temb_dim=10)

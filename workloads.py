@@ -117,6 +117,8 @@ RES1, RES2, SATTN, XATTN, FFN = "RES1", "RES2", "SATTN", "XATTN", "FFN"
 LSATTN, LXATTN, LFFN = "LSATTN", "LXATTN", "LFFN"
 # RES2 with the per-request time embedding added after the first convolution (residual block of an SDXL level)
 RES2T = "RES2T"
+# sub-layers of a diffusion-transformer block: adaptive LayerNorm modulation from the per-request vector, gated residual
+ASATTN, AMLP = "ASATTN", "AMLP"
 
 
 @dataclasses.dataclass
@@ -182,6 +184,9 @@ def config(cfg_id: int, seed: Optional[int] = None) -> Config:
     if cfg_id == 6:      # config 3 as a transformer layer with per-pixel LayerNorms (not a configuration of the baseline list)
         return Config(6, "sdxl-transformer-ln-c640", "bf16", _draw_res(BASE_SEED + 3 if seed is None else seed, 8, (32, 48, 64)),
                       (16, 16), 640, 32, 10, 64, (LSATTN, LXATTN, LFFN), ctx_len=77, ctx_dim=2048, seed=s)
+    if cfg_id == 8:      # a diffusion-transformer block (adaLN sub-layers) at the second model's width; not in the baseline list
+        return Config(8, "dit-block-c1536", "bf16", [(32, 32), (48, 48), (64, 64), (64, 64)], (16, 16),
+                      1536, 32, 24, 64, (ASATTN, AMLP), seed=s, temb_dim=1536)
     if cfg_id == 7:      # config 2 with the time embedding (SDXL: 1280 wide); not a configuration of the baseline list
         return Config(7, "sdxl-resnet-temb-c320", "bf16", [(64, 64), (96, 96), (128, 128)], (32, 32),
                       320, 32, 5, 64, (RES2T,), seed=s, temb_dim=1280)
@@ -222,6 +227,15 @@ def stage_param_shapes(stage: str, cfg: Config) -> Dict[str, Tuple[Tuple[int, ..
     if stage == FFN:
         return {"w1": ((C, 2 * F), "w:%d" % C), "b1": ((2 * F,), "bias"),
                 "w2": ((F, C), "w:%d" % F), "b2": ((C,), "bias")}
+    if stage == ASATTN:
+        D = cfg.temb_dim
+        return {"wm": ((D, 3 * C), "w:%d" % D), "bm": ((3 * C,), "bias"),
+                "wq": ((C, C), "w:%d" % C), "wk": ((C, C), "w:%d" % C), "wv": ((C, C), "w:%d" % C),
+                "wo": ((C, C), "w:%d" % C), "bo": ((C,), "bias")}
+    if stage == AMLP:
+        D = cfg.temb_dim
+        return {"wm": ((D, 3 * C), "w:%d" % D), "bm": ((3 * C,), "bias"),
+                "w1": ((C, F), "w:%d" % C), "b1": ((F,), "bias"), "w2": ((F, C), "w:%d" % F), "b2": ((C,), "bias")}
     if stage in (LSATTN, LXATTN, LFFN):
         base = stage_param_shapes(stage[1:], cfg)
         base.pop("gn_g", None)
@@ -236,7 +250,7 @@ def stage_cache_slots(stage: str) -> Tuple[str, ...]:
         return ("h1",)
     if stage == SATTN:
         return ("r", "K", "V")
-    if stage == LSATTN:
+    if stage in (LSATTN, ASATTN):
         return ("K", "V")
     return ()
 
