@@ -69,6 +69,8 @@ def kernel_work(cfg, n_active_tokens, patch=None):
         "halo_gather": (0.0, 2.0 * b * C * ring * Pa),
         "reuse_copy": (0.0, 2.0 * b * C * T),
         "layer_norm": (0.0, 2.0 * b * C * Ta),
+        "mlp_in": (2.0 * C * F * Ta, b * (C + F) * Ta),
+        "mlp_out": (2.0 * F * C * Ta, b * (F + 2 * C) * Ta),
     }
 
 
@@ -77,7 +79,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5, 6 = config 3 with per-token LayerNorms, 7 = config 2 with the time embedding (default: 2, the SDXL ResNet block)")
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5, 6 = config 3 with per-token LayerNorms, 7 = config 2 with the time embedding, 8 = a diffusion-transformer block (default: 2, the SDXL ResNet block)")
     ap.add_argument("--patch", type=int, nargs=2, default=None, metavar=("PH", "PW"),
                     help="patch size override for the patch-size sweep (not for reuse configs: the mask is per patch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -59,6 +59,13 @@ extern "C" {
  * operator with a per-request operand): h1 = conv3_a(SiLU(GN_a(x))) + SiLU(temb) W_t + b_t.  Needs desc.temb_dim and
  * pserve_block_forward_temb.  params: the eight of RES2, then wt [temb_dim][C], bt [C] */
 #define PSERVE_RES2T  9
+/* Sub-layers of a block of the second model family (a diffusion transformer): the request's conditioning vector c (the
+ * `temb` argument of pserve_block_forward_temb, desc.temb_dim wide) gives (shift, scale, gate) = thirds of
+ * SiLU(c) W_m + b_m; the sub-layer sees h = LN0(x) * (1 + scale) + shift (LN0: LayerNorm over the channels without
+ * affine) and its output is multiplied by gate before the residual add.  Per-pixel operators with per-request
+ * operands; ASATTN caches K and V like LSATTN.  The joint text-image attention of that model is not part of them. */
+#define PSERVE_ASATTN 10  /* x + gate * (MHA(h) W_o + b_o)                              params: wm [temb_dim][3C] bm [3C] wq wk wv wo bo */
+#define PSERVE_AMLP   11  /* x + gate * (GELU_tanh(h W_1 + b_1) W_2 + b_2), W_1 [C][ffn_mult*C]  params: wm bm w1 b1 w2 b2 */
 
 #define PSERVE_MAX_STAGES 8
 #define PSERVE_MAX_PARAMS 12
@@ -79,8 +86,8 @@ extern "C" {
 /* cache slots of a stage (pserve_cache_load / pserve_cache_read); stage = -1 addresses the block output slot */
 #define PSERVE_SLOT_H1  0   /* RES2, RES2T: output of the first convolution (RES2T: time embedding included) */
 #define PSERVE_SLOT_R   1   /* SATTN: stage input */
-#define PSERVE_SLOT_K   2   /* SATTN, LSATTN: keys */
-#define PSERVE_SLOT_V   3   /* SATTN, LSATTN: values */
+#define PSERVE_SLOT_K   2   /* SATTN, LSATTN, ASATTN: keys */
+#define PSERVE_SLOT_V   3   /* SATTN, LSATTN, ASATTN: values */
 #define PSERVE_SLOT_Y   4   /* block output (use stage = -1) */
 
 typedef struct pserve_plan_s pserve_plan_t;    /* CSP tables of one batch composition (host + device copies) */
@@ -98,7 +105,7 @@ typedef struct {
 
 typedef struct {
     int32_t n_stages;
-    int32_t stages[PSERVE_MAX_STAGES];   /* PSERVE_RES1 .. PSERVE_RES2T, in execution order */
+    int32_t stages[PSERVE_MAX_STAGES];   /* PSERVE_RES1 .. PSERVE_AMLP, in execution order */
     int32_t C;          /* channels */
     int32_t G;          /* GroupNorm groups (C % G == 0) */
     int32_t heads;      /* attention heads (C % heads == 0) */
@@ -107,7 +114,7 @@ typedef struct {
     int32_t ctx_len;    /* text tokens per request (XATTN), else 0 */
     int32_t ctx_dim;    /* width of a text token (XATTN), else 0 */
     int32_t ffn_mult;   /* FFN hidden width = ffn_mult*C (W_1 is C x 2*ffn_mult*C) */
-    int32_t temb_dim;   /* width of the per-request time embedding (RES2T), else 0 */
+    int32_t temb_dim;   /* width of the per-request vector (RES2T: time embedding; ASATTN / AMLP: conditioning), else 0 */
 } pserve_block_desc;
 
 /* Device pointers of the parameters of every stage, in the order listed beside the
@@ -186,7 +193,7 @@ int  pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* 
                           const pserve_block_t* weights, pserve_cache_t* cache,
                           const uint8_t* reuse_mask, void* y, void* stream);
 /* The same with the time embedding of the RES2T stages: temb DEVICE [n][temb_dim] (block dtype), one vector per
- * request, caller order; NULL if the block has no RES2T stage (then identical to pserve_block_forward, which is
+ * request, caller order (also the conditioning vector of ASATTN / AMLP); NULL if the block has no such stage (then identical to pserve_block_forward, which is
  * this call with temb = NULL).  Errors as above, EINVAL for a RES2T block without temb. */
 int  pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const void* ctx, const void* temb,
                                const pserve_block_t* weights, pserve_cache_t* cache,

@@ -251,11 +251,13 @@ static bool has_stage(const pserve_block_desc& d, int kind) {
     return false;
 }
 // stage families: the L-kinds are the token stages with a LayerNorm in front
-static bool is_sattn(int k) { return k == PSERVE_SATTN || k == PSERVE_LSATTN; }
+static bool is_sattn(int k) { return k == PSERVE_SATTN || k == PSERVE_LSATTN || k == PSERVE_ASATTN; }
 static bool is_xattn(int k) { return k == PSERVE_XATTN || k == PSERVE_LXATTN; }
 static bool is_ffn(int k) { return k == PSERVE_FFN || k == PSERVE_LFFN; }
 static bool is_res2(int k) { return k == PSERVE_RES2 || k == PSERVE_RES2T; }
-static bool has_ln(int k) { return k == PSERVE_LSATTN || k == PSERVE_LXATTN || k == PSERVE_LFFN; }
+static bool has_ln(int k) { return k == PSERVE_LSATTN || k == PSERVE_LXATTN || k == PSERVE_LFFN || k == PSERVE_ASATTN || k == PSERVE_AMLP; }
+static bool has_mod(int k) { return k == PSERVE_ASATTN || k == PSERVE_AMLP; }
+static bool needs_temb(int k) { return k == PSERVE_RES2T || has_mod(k); }
 template <typename F> static bool any_stage(const pserve_block_desc& d, F f) {
     for (int s = 0; s < d.n_stages; ++s) if (f(d.stages[s])) return true;
     return false;
@@ -330,16 +332,18 @@ int pserve_block_create(const pserve_block_desc* desc, const pserve_block_params
     PS_REQUIRE(d.C > 0 && d.G > 0 && d.C % d.G == 0, "pserve_block_create: C=%d must be a positive multiple of G=%d", d.C, d.G);
     PS_REQUIRE(d.C % (d.dtype == PSERVE_BF16 ? 8 : 4) == 0, "pserve_block_create: C=%d must be a multiple of 16 bytes", d.C);
     PS_REQUIRE(d.eps >= 0.f, "pserve_block_create: negative eps");
-    static const int nparams[10] = {0, 4, 8, 7, 5, 4, 7, 7, 6, 10};
+    static const int nparams[12] = {0, 4, 8, 7, 5, 4, 7, 7, 6, 10, 7, 6};
     for (int s = 0; s < d.n_stages; ++s) {
         const int kind = d.stages[s];
-        PS_REQUIRE(kind >= PSERVE_RES1 && kind <= PSERVE_RES2T, "pserve_block_create: stage %d has unknown kind %d", s, kind);
+        PS_REQUIRE(kind >= PSERVE_RES1 && kind <= PSERVE_AMLP, "pserve_block_create: stage %d has unknown kind %d", s, kind);
         for (int k = 0; k < nparams[kind]; ++k) PS_REQUIRE(params->p[s][k], "pserve_block_create: stage %d parameter %d is NULL", s, k);
         if (is_sattn(kind) || is_xattn(kind))
             PS_REQUIRE(d.heads > 0 && d.C % d.heads == 0 && d.C / d.heads <= 128,
                        "pserve_block_create: heads=%d must divide C=%d with head dim <= 128", d.heads, d.C);
-        if (kind == PSERVE_RES2T)
-            PS_REQUIRE(d.temb_dim > 0 && d.temb_dim <= 8192, "pserve_block_create: RES2T needs temb_dim in 1..8192 (got %d)", d.temb_dim);
+        if (needs_temb(kind))
+            PS_REQUIRE(d.temb_dim > 0 && d.temb_dim <= 8192, "pserve_block_create: stage %d needs temb_dim in 1..8192 (got %d)", s, d.temb_dim);
+        if (kind == PSERVE_AMLP)
+            PS_REQUIRE(d.ffn_mult > 0, "pserve_block_create: AMLP needs ffn_mult > 0");
         if (is_xattn(kind))
             PS_REQUIRE(d.ctx_len > 0 && d.ctx_dim > 0, "pserve_block_create: XATTN needs ctx_len and ctx_dim");
         if (is_ffn(kind))
@@ -356,6 +360,12 @@ int pserve_block_create(const pserve_block_desc* desc, const pserve_block_params
     for (int s = 0; s < d.n_stages; ++s) {
         StageWeights& w = b->sw[s];
         const void* const* p = params->p[s];
+        if (has_mod(d.stages[s])) {                                            // wm bm, then the sub-layer's own parameters
+            PS_TRY(dup_param(b->pool, p[0], es * d.temb_dim * 3 * C, &w.wt, st));
+            PS_TRY(b->pool.alloc_t(&w.bt, 3 * C));
+            PS_TRY(pack_bias(p[1], w.bt, 3 * C, d.dtype, st));
+            p += 2;
+        }
         if (d.stages[s] == PSERVE_LXATTN || d.stages[s] == PSERVE_LFFN) {     // ln_g ln_b, then the parameters of the plain kind
             PS_TRY(dup_param(b->pool, p[0], es * C, &w.gn_g[0], st));
             PS_TRY(dup_param(b->pool, p[1], es * C, &w.gn_b[0], st));
@@ -382,15 +392,31 @@ int pserve_block_create(const pserve_block_desc* desc, const pserve_block_params
             break;
         }
         case PSERVE_SATTN:
-        case PSERVE_LSATTN: {                                                  // norm parameters first in both kinds
-            PS_TRY(dup_param(b->pool, p[0], es * C, &w.gn_g[0], st));
-            PS_TRY(dup_param(b->pool, p[1], es * C, &w.gn_b[0], st));
+        case PSERVE_LSATTN:                                                    // norm parameters first in both kinds
+        case PSERVE_ASATTN: {                                                  // (p already points behind wm bm)
+            const int o = d.stages[s] == PSERVE_ASATTN ? 0 : 2;
+            if (o) {
+                PS_TRY(dup_param(b->pool, p[0], es * C, &w.gn_g[0], st));
+                PS_TRY(dup_param(b->pool, p[1], es * C, &w.gn_b[0], st));
+            }
             PS_TRY(b->pool.alloc(&w.w[0], es * 3 * C * C));                       // fused [Wq | Wk | Wv]
-            for (int k = 0; k < 3; ++k) PS_TRY(pack_linear(p[2 + k], w.w[0], C, C, k * C, d.dtype, st));
+            for (int k = 0; k < 3; ++k) PS_TRY(pack_linear(p[o + k], w.w[0], C, C, k * C, d.dtype, st));
             PS_TRY(b->pool.alloc(&w.w[1], es * C * C));
-            PS_TRY(pack_linear(p[5], w.w[1], C, C, 0, d.dtype, st));
+            PS_TRY(pack_linear(p[o + 3], w.w[1], C, C, 0, d.dtype, st));
             PS_TRY(b->pool.alloc_t(&w.b[1], C));
-            PS_TRY(pack_bias(p[6], w.b[1], C, d.dtype, st));
+            PS_TRY(pack_bias(p[o + 4], w.b[1], C, d.dtype, st));
+            break;
+        }
+        case PSERVE_AMLP: {
+            const int F = d.ffn_mult * C;
+            PS_TRY(b->pool.alloc(&w.w[0], es * F * C));
+            PS_TRY(pack_linear(p[0], w.w[0], C, F, 0, d.dtype, st));
+            PS_TRY(b->pool.alloc_t(&w.b[0], F));
+            PS_TRY(pack_bias(p[1], w.b[0], F, d.dtype, st));
+            PS_TRY(b->pool.alloc(&w.w[1], es * C * F));
+            PS_TRY(pack_linear(p[2], w.w[1], F, C, 0, d.dtype, st));
+            PS_TRY(b->pool.alloc_t(&w.b[1], C));
+            PS_TRY(pack_bias(p[3], w.b[1], C, d.dtype, st));
             break;
         }
         case PSERVE_XATTN:
@@ -453,7 +479,8 @@ int pserve_cache_create(const pserve_plan_t* plan, const pserve_block_t* block, 
     PS_TRY(c->pool.alloc(&c->ping[0], TC));
     PS_TRY(c->pool.alloc(&c->ping[1], TC));
     const bool conv = has_stage(d, PSERVE_RES1) || any_stage(d, is_res2);
-    const bool sattn = any_stage(d, is_sattn), xattn = any_stage(d, is_xattn), ffn = any_stage(d, is_ffn);
+    const bool sattn = any_stage(d, is_sattn), xattn = any_stage(d, is_xattn);
+    const bool ffn = any_stage(d, is_ffn) || has_stage(d, PSERVE_AMLP);
     const bool gn_sattn = has_stage(d, PSERVE_SATTN);
     if (conv) PS_TRY(c->pool.alloc(&c->apad, (size_t)plan->P * (plan->ph + 2) * (plan->pw + 2) * d.C * es));
     if (conv || gn_sattn) {
@@ -463,6 +490,7 @@ int pserve_cache_create(const pserve_plan_t* plan, const pserve_block_t* block, 
     for (int s = 0; s < d.n_stages; ++s) {
         if (is_res2(d.stages[s])) PS_TRY(c->pool.alloc(&c->h1[s], TC));
         if (d.stages[s] == PSERVE_RES2T) PS_TRY(c->pool.alloc_t(&c->temb_e[s], (size_t)plan->n * d.C));
+        if (has_mod(d.stages[s])) PS_TRY(c->pool.alloc_t(&c->temb_e[s], (size_t)plan->n * 3 * d.C));
         if (is_sattn(d.stages[s])) {
             if (with_slots && d.stages[s] == PSERVE_SATTN) PS_TRY(c->pool.alloc(&c->r[s], TC));
             PS_TRY(c->pool.alloc(&c->k[s], TC));
@@ -624,7 +652,7 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
     PS_REQUIRE(cache->plan == plan && cache->block == block, "pserve_block_forward: cache belongs to another plan or block");
     const pserve_block_desc& d = block->desc;
     PS_REQUIRE(ctx || !any_stage(d, is_xattn), "pserve_block_forward: XATTN stage needs ctx");
-    PS_REQUIRE(temb || !has_stage(d, PSERVE_RES2T), "pserve_block_forward: RES2T stage needs temb (pserve_block_forward_temb)");
+    PS_REQUIRE(temb || !any_stage(d, needs_temb), "pserve_block_forward: a RES2T / ASATTN / AMLP stage needs temb (pserve_block_forward_temb)");
     if (reuse_mask) {
         if (!cache->with_slots) { set_error("pserve_block_forward: reuse mask given but the cache has no slots"); return PSERVE_ESTATE; }
         if (!cache->filled) { set_error("pserve_block_forward: reuse mask given but the cache was never filled"); return PSERVE_ESTATE; }
@@ -723,6 +751,21 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
         PS_CHECK_HIP(hipEventRecord(cache->ev_join, cache->side));
     }
 
+    // SiLU -> linear on the per-request vector: cache->temb_e[si] [n][width] in slot order
+    auto temb_proj = [&](const StageWeights& w, int si, int width) -> int {
+        ProfScope ps("temb_proj", st);
+        const dim3 grid(plan->n, (unsigned)cdiv(width, 64));
+        const size_t lds = sizeof(float) * (d.temb_dim + TEMB_KG * 64);
+        const int32_t* perm = plan->d_tab[PSERVE_TAB_PERM];
+        if (dt == PSERVE_BF16)
+            temb_proj_kernel<uint16_t><<<grid, 1024, lds, st>>>((const uint16_t*)temb, (const uint16_t*)w.wt, w.bt, perm,
+                                                               d.temb_dim, width, cache->temb_e[si]);
+        else
+            temb_proj_kernel<float><<<grid, 1024, lds, st>>>((const float*)temb, (const float*)w.wt, w.bt, perm,
+                                                            d.temb_dim, width, cache->temb_e[si]);
+        return check_launch("temb_proj_kernel");
+    };
+
     const void* cur = x;
     for (int si = 0; si < d.n_stages; ++si) {
         const StageWeights& w = block->sw[si];
@@ -741,26 +784,17 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
             PS_TRY(norm_conv(cache->h1[si], w, 1, cur, out, false));
             break;
         case PSERVE_RES2T: {
-            {   // the projected embedding of every request; the first convolution adds it in its epilogue
-                ProfScope ps("temb_proj", st);
-                const dim3 grid(plan->n, (unsigned)cdiv(C, 64));
-                const size_t lds = sizeof(float) * (d.temb_dim + TEMB_KG * 64);
-                const int32_t* perm = plan->d_tab[PSERVE_TAB_PERM];
-                if (dt == PSERVE_BF16)
-                    temb_proj_kernel<uint16_t><<<grid, 1024, lds, st>>>((const uint16_t*)temb, (const uint16_t*)w.wt, w.bt, perm,
-                                                                       d.temb_dim, C, cache->temb_e[si]);
-                else
-                    temb_proj_kernel<float><<<grid, 1024, lds, st>>>((const float*)temb, (const float*)w.wt, w.bt, perm,
-                                                                    d.temb_dim, C, cache->temb_e[si]);
-                PS_TRY(check_launch("temb_proj_kernel"));
-            }
+            PS_TRY(temb_proj(w, si, C));             // the first convolution adds it in its epilogue
             PS_TRY(norm_conv(cur, w, 0, nullptr, cache->h1[si], true, cache->temb_e[si]));
             PS_TRY(norm_conv(cache->h1[si], w, 1, cur, out, false));
             break;
         }
         case PSERVE_SATTN:
-        case PSERVE_LSATTN: {
-            const bool ln = d.stages[si] == PSERVE_LSATTN;
+        case PSERVE_LSATTN:
+        case PSERVE_ASATTN: {
+            const bool ada = d.stages[si] == PSERVE_ASATTN;
+            const bool ln = d.stages[si] == PSERVE_LSATTN || ada;
+            if (ada) PS_TRY(temb_proj(w, si, 3 * C));           // [shift | scale | gate] per request
             const void* rin = cur;
             if (!ln && cache->with_slots && cur != cache->r[si]) {    // first stage: merge fresh input into the slot
                 ProfScope ps("reuse_copy", st);
@@ -771,7 +805,8 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
             }
             if (ln) {                                                 // per token: nothing of the reused patches is needed
                 ProfScope ps("layer_norm", st);
-                PS_TRY(layer_norm(rin, w.gn_g[0], w.gn_b[0], C, d.eps, gm, dt, cache->u, act, st));
+                PS_TRY(layer_norm(rin, ada ? nullptr : w.gn_g[0], ada ? nullptr : w.gn_b[0], ada ? cache->temb_e[si] : nullptr,
+                                  3 * C, owner, C, d.eps, gm, dt, cache->u, act, st));
             } else {
                 GroupNormArgs ga = gn_args(rin, w.gn_g[0], w.gn_b[0]);
                 { ProfScope ps("gn_stats", st); PS_TRY(gn_stats(ga, gm, dt, st)); }
@@ -793,8 +828,25 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
             { ProfScope ps("attn_self", st); PS_TRY(attention(aa, dt, mode, st)); }
             GemmArgs go = base_gemm(cache->o, C, C, C, w.w[1], w.b[1]);
             go.res = rin; go.ldr = C;
+            if (ada) { go.rowscale = cache->temb_e[si] + 2 * C; go.rowscale_ld = 3 * C; go.row_owner = owner; }
             go.seg[0].ptr = out; go.seg[0].ld = C;
             { ProfScope ps("linear_out", st); PS_TRY(gemm(go, dt, mode, st)); }
+            break;
+        }
+        case PSERVE_AMLP: {
+            const int F = d.ffn_mult * C;
+            PS_TRY(temb_proj(w, si, 3 * C));
+            { ProfScope ps("layer_norm", st);
+              PS_TRY(layer_norm(cur, nullptr, nullptr, cache->temb_e[si], 3 * C, owner, C, d.eps, gm, dt, cache->u, act, st)); }
+            GemmArgs g1 = base_gemm(cache->u, C, C, F, w.w[0], w.b[0]);
+            g1.act_gelu = 1;
+            g1.seg[0].ptr = cache->hidden; g1.seg[0].ld = F;
+            { ProfScope ps("mlp_in", st); PS_TRY(gemm(g1, dt, mode, st)); }
+            GemmArgs g2 = base_gemm(cache->hidden, F, F, C, w.w[1], w.b[1]);
+            g2.res = cur; g2.ldr = C;
+            g2.rowscale = cache->temb_e[si] + 2 * C; g2.rowscale_ld = 3 * C; g2.row_owner = owner;
+            g2.seg[0].ptr = out; g2.seg[0].ld = C;
+            { ProfScope ps("mlp_out", st); PS_TRY(gemm(g2, dt, mode, st)); }
             break;
         }
         case PSERVE_XATTN:
@@ -804,7 +856,7 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
             const void* qin = cur;
             if (d.stages[si] == PSERVE_LXATTN) {
                 ProfScope ps("layer_norm", st);
-                PS_TRY(layer_norm(cur, w.gn_g[0], w.gn_b[0], C, d.eps, gm, dt, cache->u, act, st));
+                PS_TRY(layer_norm(cur, w.gn_g[0], w.gn_b[0], nullptr, 0, nullptr, C, d.eps, gm, dt, cache->u, act, st));
                 qin = cache->u;
             }
             GemmArgs gq = base_gemm(qin, C, C, C, w.w[0], nullptr);
@@ -830,7 +882,7 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
             const void* fin = cur;
             if (d.stages[si] == PSERVE_LFFN) {
                 ProfScope ps("layer_norm", st);
-                PS_TRY(layer_norm(cur, w.gn_g[0], w.gn_b[0], C, d.eps, gm, dt, cache->u, act, st));
+                PS_TRY(layer_norm(cur, w.gn_g[0], w.gn_b[0], nullptr, 0, nullptr, C, d.eps, gm, dt, cache->u, act, st));
                 fin = cache->u;
             }
             GemmArgs g1 = base_gemm(fin, C, C, 2 * F, w.w[0], w.b[0]);

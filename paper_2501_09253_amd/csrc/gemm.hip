@@ -50,6 +50,10 @@ __device__ __forceinline__ RowInfo row_info(const GemmArgs& a, int ri) {
     return r;
 }
 
+// tanh form: v/2 (1 + tanh(sqrt(2/pi) (v + 0.044715 v^3)))
+__device__ __forceinline__ float gelu_tanh_f(float v) {
+    return 0.5f * v * (1.f + tanhf(0.7978845608028654f * (v + 0.044715f * v * v * v)));
+}
 __device__ __forceinline__ float gelu_f(float v) { return 0.5f * v * (1.f + erff(v * 0.70710678118654752f)); }
 
 template <typename T>
@@ -147,6 +151,8 @@ gemm_simple_kernel(GemmArgs a) {
             } else {
                 v = acc[0][i][j] + (a.bias ? a.bias[col] : 0.f);
                 if (a.rowbias) v += a.rowbias[(int64_t)a.row_owner[tok / a.geom.S] * a.N + col];
+                if (a.act_gelu) v = gelu_tanh_f(v);
+                if (a.rowscale) v *= a.rowscale[(int64_t)a.row_owner[tok / a.geom.S] * a.rowscale_ld + col];
                 if (a.res) v += ld_f<T>((const T*)a.res + tok * a.ldr + col);
                 route_store<T>(a, tok, col, v);
             }

@@ -37,6 +37,12 @@ __device__ __forceinline__ float gelu_erf(float v) {
     return v >= 0.f ? v - r : r;
 }
 
+// GELU, tanh form: v/2 (1 + tanh(u)) = v / (1 + exp(-2u)), u = sqrt(2/pi) (v + 0.044715 v^3); hardware exp2 and reciprocal
+__device__ __forceinline__ float gelu_tanh(float v) {
+    const float u2 = v * fmaf(0.044715f * v, v, 1.f) * (-2.f * 0.7978845608028654f * 1.4426950408889634f);   // -2u log2(e)
+    return v * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(u2));
+}
+
 // value of lane l ^ 32 (v_permlane32_swap: upper half of the first operand <-> lower half of the second)
 __device__ __forceinline__ float other_half_f(float v) {
     const uint32_t u = __float_as_uint(v);
@@ -82,7 +88,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[B
     // request (rows are ordered by request, so first == last decides), else looked up per element
     bool rb_uniform = false;
     int rb_slot = 0;
-    if (!GEGLU && a.rowbias) {
+    if (!GEGLU && (a.rowbias || a.rowscale)) {
         const int t_first = w_tok[0], t_last = w_tok[WM - 1];
         if (t_first >= 0 && t_last >= 0) {
             rb_slot = a.row_owner[t_first / a.geom.S];
@@ -122,7 +128,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[B
             sgm = sg == 0 ? a.seg[0] : (sg == 1 ? a.seg[1] : a.seg[2]);
             ocol0 = pcol - sg * a.seg_cols;
             float bias = bias_pre ? bias_pre[j] : (a.bias ? a.bias[pcol + fr] : 0.f);
-            if (rb_uniform) bias += a.rowbias[(int64_t)rb_slot * a.N + pcol + fr];
+            if (rb_uniform && a.rowbias) bias += a.rowbias[(int64_t)rb_slot * a.N + pcol + fr];
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -135,6 +141,29 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[B
                         const int tok = w_tok[i * 32 + 8 * (e >> 2) + 4 * fh + (e & 3)];
                         if (tok >= 0) vals[i][e] += a.rowbias[(int64_t)a.row_owner[tok / a.geom.S] * a.N + pcol + fr];
                     }
+            }
+            if (a.act_gelu) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) vals[i][e] = gelu_tanh(vals[i][e]);
+            }
+            if (a.rowscale) {                                   // gate of the request, before the residual is added
+                if (rb_uniform) {
+                    const float gate = a.rowscale[(int64_t)rb_slot * a.rowscale_ld + pcol + fr];
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) vals[i][e] *= gate;
+                } else {
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) {
+                            const int tok = w_tok[i * 32 + 8 * (e >> 2) + 4 * fh + (e & 3)];
+                            if (tok >= 0) vals[i][e] *= a.rowscale[(int64_t)a.row_owner[tok / a.geom.S] * a.rowscale_ld + pcol + fr];
+                        }
+                }
             }
             if (STATS) {
                 float s1 = 0.f, s2 = 0.f;

@@ -58,10 +58,11 @@ int gn_finalize(const GroupNormArgs& a, const PatchGeom& g, int dtype, int32_t s
 // border tokens also fill the neighbours' ring slots / zero the own ring at image edges (no halo_gather needed).
 int gn_apply(const GroupNormArgs& a, const PatchGeom& g, int dtype, bool silu, bool padded, bool stitch, void* out,
              ActiveList act, hipStream_t st);
-// Per-token LayerNorm over the C channels (biased variance, affine gamma / beta of the block dtype) of the patches of
-// `act`; out [T][C] at the same token positions.
-int layer_norm(const void* x, const void* gamma, const void* beta, int32_t C, float eps, const PatchGeom& g, int dtype,
-               void* out, ActiveList act, hipStream_t st);
+// Per-token LayerNorm over the C channels (biased variance) of the patches of `act`; out [T][C] at the same token
+// positions.  Affine part: gamma / beta [C] of the block dtype, or (gamma == nullptr) the adaptive form
+// xhat * (1 + scale) + shift with shift = mod[slot * mod_ld + c], scale = mod[slot * mod_ld + C + c], slot = owner[patch].
+int layer_norm(const void* x, const void* gamma, const void* beta, const float* mod, int64_t mod_ld, const int32_t* owner,
+               int32_t C, float eps, const PatchGeom& g, int dtype, void* out, ActiveList act, hipStream_t st);
 // Fill the one-pixel ring of every active padded patch from the interiors of its neighbours (zeros outside the image).
 int halo_gather(void* apad, const int32_t* halo_src, const PatchGeom& g, int32_t C, int32_t ring, int dtype,
                 ActiveList act, hipStream_t st);
@@ -95,7 +96,10 @@ struct GemmArgs {
     const void* B;             // packed weights [taps][N][K]
     const float* bias;         // [N] packed order, or nullptr
     const float* rowbias;      // optional [n][N]: row r also gets rowbias[row_owner[token / S]][col] (rows are tokens)
-    const int32_t* row_owner;  // [P] request slot of each patch (with rowbias)
+    const int32_t* row_owner;  // [P] request slot of each patch (with rowbias / rowscale)
+    const float* rowscale;     // optional: (acc + bias [+ rowbias]) is multiplied by rowscale[slot * rowscale_ld + col]
+    int64_t rowscale_ld;       //           before the residual is added (gated residual of an adaLN sub-layer)
+    int32_t act_gelu;          // 1: tanh-form GELU of (acc + bias) (EPI_ROUTE only)
     const void* res;           // residual [rows][ldr] or nullptr (added after bias)
     int64_t ldr;
     int32_t epi;               // EPI_ROUTE: columns go to segment col / seg_cols; EPI_GEGLU: value*GELU(gate) pairs

@@ -285,7 +285,8 @@ __global__ void gn_apply_kernel(const T* __restrict__ x, const float* __restrict
 // over the LPT lanes; fp32 throughout.  One 16-byte load and one 16-byte store per vector: 2*b*C bytes per token.
 template <typename T, int VPL>
 __global__ void __launch_bounds__(256)
-layer_norm_kernel(const T* __restrict__ x, const T* __restrict__ gamma, const T* __restrict__ beta, int32_t C, int32_t S,
+layer_norm_kernel(const T* __restrict__ x, const T* __restrict__ gamma, const T* __restrict__ beta,
+                  const float* __restrict__ mod, int64_t mod_ld, const int32_t* __restrict__ owner, int32_t C, int32_t S,
                   int32_t LPT, float eps, ActiveList act, T* __restrict__ out) {
     constexpr int VN = Vec<T>::N;
     int p = blockIdx.x;
@@ -296,11 +297,14 @@ layer_norm_kernel(const T* __restrict__ x, const T* __restrict__ gamma, const T*
     const int CV = C / VN;
     const int sub = threadIdx.x % LPT, tl = threadIdx.x / LPT, tpb = blockDim.x / LPT;
     uint4 graw[VPL], braw[VPL];
+    const float* mrow = mod ? mod + (int64_t)owner[p] * mod_ld : nullptr;     // adaptive form: [shift | scale] of the request
+    if (!mod) {
 #pragma unroll
-    for (int k = 0; k < VPL; ++k) {
-        const int cv = min(sub + k * LPT, CV - 1);
-        graw[k] = *reinterpret_cast<const uint4*>(gamma + cv * VN);
-        braw[k] = *reinterpret_cast<const uint4*>(beta + cv * VN);
+        for (int k = 0; k < VPL; ++k) {
+            const int cv = min(sub + k * LPT, CV - 1);
+            graw[k] = *reinterpret_cast<const uint4*>(gamma + cv * VN);
+            braw[k] = *reinterpret_cast<const uint4*>(beta + cv * VN);
+        }
     }
     const float inv_c = 1.f / (float)C;
     for (int t = blockIdx.y * tpb + tl; t < S; t += gridDim.y * tpb) {
@@ -333,8 +337,13 @@ layer_norm_kernel(const T* __restrict__ x, const T* __restrict__ gamma, const T*
             const int cv = sub + k * LPT;
             if (cv < CV) {
                 float g[VN], b[VN];
-                unpack_vec<T>(graw[k], g);
-                unpack_vec<T>(braw[k], b);
+                if (mod) {
+#pragma unroll
+                    for (int e = 0; e < VN; ++e) { b[e] = mrow[cv * VN + e]; g[e] = 1.f + mrow[C + cv * VN + e]; }
+                } else {
+                    unpack_vec<T>(graw[k], g);
+                    unpack_vec<T>(braw[k], b);
+                }
 #pragma unroll
                 for (int e = 0; e < VN; ++e) v[k][e] = fmaf(v[k][e] * rstd, g[e], b[e]);
                 store_vec<T>(out + row + cv * VN, v[k]);
@@ -446,20 +455,23 @@ int gn_apply(const GroupNormArgs& a, const PatchGeom& g, int dtype, bool silu, b
 }
 
 template <typename T>
-static void launch_layer_norm(const void* x, const void* gamma, const void* beta, int32_t C, float eps, const PatchGeom& g,
-                              void* out, ActiveList act, int LPT, int VPL, hipStream_t st) {
+static void launch_layer_norm(const void* x, const void* gamma, const void* beta, const float* mod, int64_t mod_ld,
+                              const int32_t* owner, int32_t C, float eps, const PatchGeom& g, void* out, ActiveList act,
+                              int LPT, int VPL, hipStream_t st) {
     const int tpb = 256 / LPT;
     // one token per lane group while that gives at most ~16 blocks per CU, else more tokens per group
     int64_t per = 1;
     while (per < 8 && g.P * cdiv(g.S, tpb * per) > 4096) per *= 2;
     dim3 grid(g.P, (unsigned)std::max<int64_t>(1, std::min<int64_t>(cdiv(g.S, tpb * per), 65535)));
-#define PS_LN(V) case V: layer_norm_kernel<T, V><<<grid, 256, 0, st>>>((const T*)x, (const T*)gamma, (const T*)beta, C, g.S, LPT, eps, act, (T*)out); break
+#define PS_LN(V) case V: layer_norm_kernel<T, V><<<grid, 256, 0, st>>>((const T*)x, (const T*)gamma, (const T*)beta, mod, mod_ld, owner, C, g.S, LPT, eps, act, (T*)out); break
     switch (VPL) { PS_LN(1); PS_LN(2); PS_LN(3); PS_LN(4); PS_LN(5); PS_LN(6); PS_LN(7); PS_LN(8); }
 #undef PS_LN
 }
 
-int layer_norm(const void* x, const void* gamma, const void* beta, int32_t C, float eps, const PatchGeom& g, int dtype,
-               void* out, ActiveList act, hipStream_t st) {
+int layer_norm(const void* x, const void* gamma, const void* beta, const float* mod, int64_t mod_ld, const int32_t* owner,
+               int32_t C, float eps, const PatchGeom& g, int dtype, void* out, ActiveList act, hipStream_t st) {
+    PS_REQUIRE((gamma && beta) || (mod && owner), "LayerNorm: neither gamma / beta nor a modulation table");
+    if (gamma) mod = nullptr;
     const int vn = dtype == PSERVE_BF16 ? 8 : 4;
     PS_REQUIRE(C % vn == 0, "LayerNorm: C=%d must be a multiple of %d for this dtype", C, vn);
     const int CV = C / vn;
@@ -470,8 +482,8 @@ int layer_norm(const void* x, const void* gamma, const void* beta, int32_t C, fl
         const int v = (int)cdiv(CV, l);
         if (v <= 8 && v * l - CV < waste) { LPT = l; VPL = v; waste = v * l - CV; }
     }
-    if (dtype == PSERVE_BF16) launch_layer_norm<uint16_t>(x, gamma, beta, C, eps, g, out, act, LPT, VPL, st);
-    else launch_layer_norm<float>(x, gamma, beta, C, eps, g, out, act, LPT, VPL, st);
+    if (dtype == PSERVE_BF16) launch_layer_norm<uint16_t>(x, gamma, beta, mod, mod_ld, owner, C, eps, g, out, act, LPT, VPL, st);
+    else launch_layer_norm<float>(x, gamma, beta, mod, mod_ld, owner, C, eps, g, out, act, LPT, VPL, st);
     return check_launch("layer_norm_kernel");
 }
 

@@ -82,6 +82,8 @@ SMALL = [
     ((wl.LSATTN, wl.LXATTN, wl.LFFN), "bf16"), ((wl.SATTN, wl.LFFN), "bf16"),
     # residual block with the per-request time embedding
     ((wl.RES2T,), "f32"), ((wl.RES2T, wl.LSATTN), "f32"), ((wl.RES2T,), "bf16"),
+    # adaLN sub-layers of a diffusion-transformer block
+    ((wl.ASATTN,), "f32"), ((wl.AMLP,), "f32"), ((wl.RES2T, wl.ASATTN, wl.AMLP), "f32"), ((wl.ASATTN, wl.AMLP), "bf16"),
 ]
 
 
@@ -106,7 +108,7 @@ def test_small_blocks(stages, dtype, mode):
                                          # next norm's partial sums must skip the rows past the end): T = 192 and T = 320
                                          (64, [(8, 8), (8, 16)], (8, 8)), (320, [(8, 8), (16, 16)], (8, 8))])
 @pytest.mark.parametrize("stages", [(wl.RES2,), (wl.SATTN, wl.XATTN, wl.FFN), (wl.RES1, wl.SATTN),
-                                    (wl.LSATTN, wl.LXATTN, wl.LFFN), (wl.RES2T,)])
+                                    (wl.LSATTN, wl.LXATTN, wl.LFFN), (wl.RES2T,), (wl.ASATTN, wl.AMLP)])
 def test_mfma_shapes_bf16(stages, C, res, patch):
     """bf16 blocks whose widths take the MFMA kernels (C multiple of 64, head dim 64), ragged M tails included."""
     cfg = wl.custom_config(res, patch, C=C, G=32, heads=C // 64, stages=stages, dtype="bf16", ctx_len=77, ctx_dim=128,
@@ -156,7 +158,8 @@ def test_layer_norm_widths(dtype, C):
 # ----------------------------------------------------------------------------- reuse
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("stages", [(wl.RES2, wl.SATTN), (wl.SATTN,), (wl.RES2,), (wl.SATTN, wl.XATTN, wl.FFN),
-                                    (wl.LSATTN, wl.LXATTN, wl.LFFN), (wl.RES2, wl.LSATTN), (wl.RES2T, wl.SATTN)])
+                                    (wl.LSATTN, wl.LXATTN, wl.LFFN), (wl.RES2, wl.LSATTN), (wl.RES2T, wl.SATTN),
+                                    (wl.ASATTN, wl.AMLP)])
 def test_reuse_small(stages, dtype):
     cfg = wl.custom_config([(16, 16), (8, 8), (8, 16)], (4, 4), C=32, G=4, heads=2, stages=stages, dtype=dtype,
                            ctx_len=5, ctx_dim=16, reuse_p=0.4, seed=21, temb_dim=12)
@@ -228,7 +231,7 @@ def test_config1_fp32():
     assert rel_err(got, ref) < 1e-4
 
 
-@pytest.mark.parametrize("cfg_id", [2, 3, 4, 6, 7])
+@pytest.mark.parametrize("cfg_id", [2, 3, 4, 6, 7, 8])
 def test_config_bf16_full_size(cfg_id):
     w = wl.make_workload(wl.config(cfg_id))
     got = GpuRun(w).forward_images()
