@@ -236,11 +236,14 @@ struct pserve_cache_s {
     // its own (default priority) beside the stages before it, forked and joined with events.
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    hipEvent_t ev_temb[PSERVE_MAX_STAGES] = {};   // projection of the per-request vector of stage s is done (side stream)
+    bool side_temb = false;                       // the projections run on the side stream (else inline, at their stage)
     int side_stage = -1;
     DevicePool pool;
     ~pserve_cache_s() {
         if (ev_fork) (void)hipEventDestroy(ev_fork);
         if (ev_join) (void)hipEventDestroy(ev_join);
+        for (hipEvent_t e : ev_temb) if (e) (void)hipEventDestroy(e);
         if (side) (void)hipStreamDestroy(side);
     }
 };
@@ -524,11 +527,22 @@ int pserve_cache_create(const pserve_plan_t* plan, const pserve_block_t* block, 
     {
         int n_x = 0, at = -1;
         for (int k = 0; k < d.n_stages; ++k) if (is_xattn(d.stages[k])) { ++n_x; at = k; }
-        if (n_x == 1 && at > 0) {                  // something runs before it: worth a stream of its own
+        const bool side_kv = n_x == 1 && at > 0;   // something runs before it: worth a stream of its own
+        // The projections of the per-request vector depend on temb only.  A second stream costs a fork and a join
+        // (about 10 us of cross-stream waits): it pays for the adaLN projections of a wide block (2 x 20 us hidden at
+        // 1536 channels), not for the 5 us time-embedding projection of a 320-channel residual block.
+        int64_t macs = 0;
+        for (int k = 0; k < d.n_stages; ++k)
+            if (needs_temb(d.stages[k])) macs += (int64_t)plan->n * d.temb_dim * (d.stages[k] == PSERVE_RES2T ? d.C : 3 * d.C);
+        c->side_temb = macs >= (int64_t)8 << 20;
+        if (side_kv || c->side_temb) {
             PS_CHECK_HIP(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
             PS_CHECK_HIP(hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
             PS_CHECK_HIP(hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming));
-            c->side_stage = at;
+            for (int k = 0; k < d.n_stages; ++k)
+                if (c->side_temb && needs_temb(d.stages[k]))
+                    PS_CHECK_HIP(hipEventCreateWithFlags(&c->ev_temb[k], hipEventDisableTiming));
+            if (side_kv) c->side_stage = at;
         }
     }
     guard.p = nullptr;
@@ -706,7 +720,7 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
     // stats_next: the output feeds another norm, so the convolution may leave that norm's partial sums behind
     bool have_partials = false;                     // cache->partial was filled by the previous convolution
     auto norm_conv = [&](const void* in, const StageWeights& w, int ci, const void* res, void* out, bool stats_next,
-                         const float* rowbias = nullptr) -> int {
+                         const float* rowbias = nullptr, hipEvent_t rowbias_ready = nullptr) -> int {
         GroupNormArgs ga = gn_args(in, w.gn_g[ci], w.gn_b[ci]);
         if (have_partials) { ProfScope ps("gn_stats", st); PS_TRY(gn_finalize(ga, gm, dt, plan->S / 64, st)); }
         else { ProfScope ps("gn_stats", st); PS_TRY(gn_stats(ga, gm, dt, st)); }
@@ -729,6 +743,7 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
             if (gemm_emits_stats(g, dt, mode)) have_partials = true;
             else { g.stats = nullptr; g.stats_G = 0; g.stats_slots = 0; }
         }
+        if (rowbias_ready) PS_CHECK_HIP(hipStreamWaitEvent(st, rowbias_ready, 0));   // produced on the side stream
         ProfScope ps("conv3x3", st);
         return gemm(g, dt, mode, st);
     };
@@ -744,26 +759,38 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
         ProfScope ps("linear_ctx_kv", s2);
         return gemm(gk, dt, mode, s2);
     };
-    if (cache->side_stage >= 0) {                   // fork: the side stream starts where this call starts
-        PS_CHECK_HIP(hipEventRecord(cache->ev_fork, st));
-        PS_CHECK_HIP(hipStreamWaitEvent(cache->side, cache->ev_fork, 0));
-        PS_TRY(ctx_kv(block->sw[cache->side_stage], cache->side));
-        PS_CHECK_HIP(hipEventRecord(cache->ev_join, cache->side));
-    }
-
-    // SiLU -> linear on the per-request vector: cache->temb_e[si] [n][width] in slot order
-    auto temb_proj = [&](const StageWeights& w, int si, int width) -> int {
-        ProfScope ps("temb_proj", st);
+    // SiLU -> linear on the per-request vector of stage si: cache->temb_e[si] [n][width] in slot order
+    auto temb_proj = [&](const StageWeights& w, int si, int width, hipStream_t s2) -> int {
+        ProfScope ps("temb_proj", s2);
         const dim3 grid(plan->n, (unsigned)cdiv(width, 64));
         const size_t lds = sizeof(float) * (d.temb_dim + TEMB_KG * 64);
         const int32_t* perm = plan->d_tab[PSERVE_TAB_PERM];
         if (dt == PSERVE_BF16)
-            temb_proj_kernel<uint16_t><<<grid, 1024, lds, st>>>((const uint16_t*)temb, (const uint16_t*)w.wt, w.bt, perm,
+            temb_proj_kernel<uint16_t><<<grid, 1024, lds, s2>>>((const uint16_t*)temb, (const uint16_t*)w.wt, w.bt, perm,
                                                                d.temb_dim, width, cache->temb_e[si]);
         else
-            temb_proj_kernel<float><<<grid, 1024, lds, st>>>((const float*)temb, (const float*)w.wt, w.bt, perm,
+            temb_proj_kernel<float><<<grid, 1024, lds, s2>>>((const float*)temb, (const float*)w.wt, w.bt, perm,
                                                             d.temb_dim, width, cache->temb_e[si]);
         return check_launch("temb_proj_kernel");
+    };
+    if (cache->side) {                              // fork: the side stream starts where this call starts
+        PS_CHECK_HIP(hipEventRecord(cache->ev_fork, st));
+        PS_CHECK_HIP(hipStreamWaitEvent(cache->side, cache->ev_fork, 0));
+        for (int k = 0; k < d.n_stages; ++k)        // the short projections first: their consumers come early
+            if (cache->side_temb && needs_temb(d.stages[k])) {
+                PS_TRY(temb_proj(block->sw[k], k, d.stages[k] == PSERVE_RES2T ? C : 3 * C, cache->side));
+                PS_CHECK_HIP(hipEventRecord(cache->ev_temb[k], cache->side));
+            }
+        if (cache->side_stage >= 0) {
+            PS_TRY(ctx_kv(block->sw[cache->side_stage], cache->side));
+            PS_CHECK_HIP(hipEventRecord(cache->ev_join, cache->side));
+        }
+    }
+
+    // the projection of stage si as seen from the main stream: wait for the side stream, or run it here
+    auto temb_ready = [&](const StageWeights& w, int si, int width) -> int {
+        if (cache->side_temb) { PS_CHECK_HIP(hipStreamWaitEvent(st, cache->ev_temb[si], 0)); return PSERVE_OK; }
+        return temb_proj(w, si, width, st);
     };
 
     const void* cur = x;
@@ -784,8 +811,9 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
             PS_TRY(norm_conv(cache->h1[si], w, 1, cur, out, false));
             break;
         case PSERVE_RES2T: {
-            PS_TRY(temb_proj(w, si, C));             // the first convolution adds it in its epilogue
-            PS_TRY(norm_conv(cur, w, 0, nullptr, cache->h1[si], true, cache->temb_e[si]));
+            // the projected embedding comes from the side stream; the first convolution adds it in its epilogue
+            if (!cache->side_temb) PS_TRY(temb_proj(w, si, C, st));
+            PS_TRY(norm_conv(cur, w, 0, nullptr, cache->h1[si], true, cache->temb_e[si], cache->side_temb ? cache->ev_temb[si] : nullptr));
             PS_TRY(norm_conv(cache->h1[si], w, 1, cur, out, false));
             break;
         }
@@ -794,7 +822,7 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
         case PSERVE_ASATTN: {
             const bool ada = d.stages[si] == PSERVE_ASATTN;
             const bool ln = d.stages[si] == PSERVE_LSATTN || ada;
-            if (ada) PS_TRY(temb_proj(w, si, 3 * C));           // [shift | scale | gate] per request
+            if (ada) PS_TRY(temb_ready(w, si, 3 * C));          // [shift | scale | gate] per request
             const void* rin = cur;
             if (!ln && cache->with_slots && cur != cache->r[si]) {    // first stage: merge fresh input into the slot
                 ProfScope ps("reuse_copy", st);
@@ -835,7 +863,7 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
         }
         case PSERVE_AMLP: {
             const int F = d.ffn_mult * C;
-            PS_TRY(temb_proj(w, si, 3 * C));
+            PS_TRY(temb_ready(w, si, 3 * C));
             { ProfScope ps("layer_norm", st);
               PS_TRY(layer_norm(cur, nullptr, nullptr, cache->temb_e[si], 3 * C, owner, C, d.eps, gm, dt, cache->u, act, st)); }
             GemmArgs g1 = base_gemm(cache->u, C, C, F, w.w[0], w.b[0]);
