@@ -37,6 +37,9 @@ Readings of points the paper leaves open (each also listed in the design notes):
     its output is multiplied by gate before the residual add.  The feed-forward is
     GELU(h W_1 + b_1) W_2 + b_2 with the tanh form of GELU (that model's choice).  The
     joint text-image attention of that model is not part of these stages.
+  * MMDIT is a whole joint block of that model (function mmdit): two streams with their own
+    weights, one attention over the concatenated image and text tokens of a request.  It is
+    called on its own (block_forward carries images only), one request at a time.
   * RES2T is RES2 with the time embedding of the first model's residual block: the
     request's embedding vector goes through SiLU and a linear layer, and the resulting
     C values are added to every pixel of the first convolution's output (a per-pixel
@@ -328,6 +331,38 @@ def lffn_tokens(xt, p, eps):
     h = _ln_tokens(xt, p, eps) @ p["w1"].astype(F64) + p["b1"].astype(F64)
     F = h.shape[1] // 2
     return xt + (h[:, :F] * gelu(h[:, F:])) @ p["w2"].astype(F64) + p["b2"].astype(F64)
+
+
+def mmdit(x, txt, cvec, p, heads, eps):
+    """One joint block of the paper's second model on ONE request: image x [C, H, W] and its text tokens txt [L, C].
+
+    Each stream X in (img, txt) has its own weights p["X.*"]: six modulation vectors from the request's conditioning
+    vector, (sh1, sc1, g1, sh2, sc2, g2) = sixths of SiLU(c) W_m + b_m; q, k, v = h W_q, h W_k, h W_v with
+    h = LN0(x) (1 + sc1) + sh1; ONE softmax attention over the concatenated tokens of both streams (every token of the
+    request attends to all image and all text tokens of the same request); x += g1 * (o W_o + b_o);
+    x += g2 * (GELU_tanh(h2 W_1 + b_1) W_2 + b_2) with h2 = LN0(x) (1 + sc2) + sh2.  Returns (image, text)."""
+    C, H, W = x.shape
+    streams = {"img": _tokens(np.asarray(x, dtype=F64)), "txt": np.asarray(txt, dtype=F64)}
+    mod, q, k, v = {}, {}, {}, {}
+    for X, t in streams.items():
+        m = silu(np.asarray(cvec, dtype=F64)) @ p[X + ".wm"].astype(F64) + p[X + ".bm"].astype(F64)
+        mod[X] = [m[i * C:(i + 1) * C] for i in range(6)]
+        h = _ln0_mod_tokens(t, mod[X][0], mod[X][1], eps)
+        q[X], k[X], v[X] = (h @ p[X + "." + n].astype(F64) for n in ("wq", "wk", "wv"))
+    order = ("img", "txt")
+    O = attention(np.concatenate([q[X] for X in order]), np.concatenate([k[X] for X in order]),
+                  np.concatenate([v[X] for X in order]), heads)
+    out, at = {}, 0
+    for X in order:
+        t = streams[X]
+        o = O[at:at + t.shape[0]]
+        at += t.shape[0]
+        t = t + mod[X][2] * (o @ p[X + ".wo"].astype(F64) + p[X + ".bo"].astype(F64))
+        h2 = _ln0_mod_tokens(t, mod[X][3], mod[X][4], eps)
+        t = t + mod[X][5] * (gelu_tanh(h2 @ p[X + ".w1"].astype(F64) + p[X + ".b1"].astype(F64)) @ p[X + ".w2"].astype(F64)
+                             + p[X + ".b2"].astype(F64))
+        out[X] = t
+    return _image(out["img"], H, W), out["txt"]
 
 
 # ----------------------------------------------------------------------------- whole block

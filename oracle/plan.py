@@ -23,6 +23,11 @@ Readings where the paper is silent (figure of the worked example is not availabl
     right column y=0..ph-1; entries are global token ids, -1 = outside the image
   * token id = patch*ph*pw + y*pw + x
   * patch size (0, 0) means the greatest common divisor of all heights resp. widths
+  * text_len > 0 (joint text-image attention of the paper's second model, section "Patch-based Self-Attention
+    Module": every image token attends to its own request's tokens): the text tokens of a request ride along as
+    ceil(text_len / (ph*pw)) extra patches placed behind its image patches, grid position (-1, k), no neighbours,
+    no halo; seq_len[s] = H*W + text_len counts the valid tokens of slot s (the padding of the last text patch
+    lies behind them), so a request's key set is the token range [cu_seqlens[s], cu_seqlens[s] + seq_len[s])
 """
 from __future__ import annotations
 
@@ -35,7 +40,7 @@ import numpy as np
 NEIGHBOUR_ORDER = [(-1, -1), (-1, 0), (-1, 1), (0, -1), (0, 1), (1, -1), (1, 0), (1, 1)]
 
 
-def plan_tables(resolutions: Sequence[Tuple[int, int]], ph: int = 0, pw: int = 0) -> Dict[str, np.ndarray]:
+def plan_tables(resolutions: Sequence[Tuple[int, int]], ph: int = 0, pw: int = 0, text_len: int = 0) -> Dict[str, np.ndarray]:
     n = len(resolutions)
     if ph == 0 and pw == 0:
         ph = reduce(math.gcd, [h for h, _ in resolutions])
@@ -59,6 +64,9 @@ def plan_tables(resolutions: Sequence[Tuple[int, int]], ph: int = 0, pw: int = 0
                 for y in range(ph):
                     for x in range(pw):
                         token_at[(s, r * ph + y, c * pw + x)] = p * ph * pw + y * pw + x
+        for k in range(-(-text_len // (ph * pw))):              # text patches: off the grid, found by nobody
+            owner.append(s)
+            rc.append((-1, k))
         request_offset.append(len(owner))
     P = len(owner)
 
@@ -68,6 +76,8 @@ def plan_tables(resolutions: Sequence[Tuple[int, int]], ph: int = 0, pw: int = 0
     halo_src = np.full((P, len(ring)), -1, dtype=np.int32)
     for p in range(P):
         s, (r, c) = owner[p], rc[p]
+        if r < 0:
+            continue
         for k, (dy, dx) in enumerate(NEIGHBOUR_ORDER):
             neighbour[p, k] = patch_at.get((s, r + dy, c + dx), -1)
         for k, (y, x) in enumerate(ring):
@@ -91,6 +101,7 @@ def plan_tables(resolutions: Sequence[Tuple[int, int]], ph: int = 0, pw: int = 0
         "neighbour": neighbour,
         "halo_src": halo_src,
         "cu_seqlens": np.array(request_offset, dtype=np.int32) * (ph * pw),
+        "seq_len": np.array([H * W + text_len for H, W in res_sorted], dtype=np.int32),
     }
 
 
@@ -125,4 +136,31 @@ def reassemble(x: np.ndarray, resolutions: Sequence[Tuple[int, int]], ph: int, p
                 im[:, r * ph:(r + 1) * ph, c * pw:(c + 1) * pw] = x[t:t + ph * pw].T.reshape(C, ph, pw)
                 t += ph * pw
         out[i] = im
+    return out
+
+
+def text_scatter(x: np.ndarray, text: np.ndarray, resolutions: Sequence[Tuple[int, int]], ph: int, pw: int) -> np.ndarray:
+    """text [n, L, C] (caller order) into the text patches of the joint token matrix x[T, C] (copy returned); the
+    padding rows of the last text patch become zero."""
+    L = text.shape[1]
+    t = plan_tables(resolutions, ph, pw, L)
+    out = np.array(x, copy=True)
+    S = ph * pw
+    for s, i in enumerate(t["perm"]):
+        H, W = resolutions[i]
+        first = int(t["cu_seqlens"][s]) + H * W
+        end = int(t["cu_seqlens"][s + 1])
+        out[first:end] = 0
+        out[first:first + L] = text[i]
+    return out
+
+
+def text_gather(x: np.ndarray, L: int, resolutions: Sequence[Tuple[int, int]], ph: int, pw: int) -> np.ndarray:
+    """The text tokens of every request out of the joint token matrix: [n, L, C] in caller order."""
+    t = plan_tables(resolutions, ph, pw, L)
+    out = np.empty((len(resolutions), L, x.shape[1]), dtype=x.dtype)
+    for s, i in enumerate(t["perm"]):
+        H, W = resolutions[i]
+        first = int(t["cu_seqlens"][s]) + H * W
+        out[i] = x[first:first + L]
     return out

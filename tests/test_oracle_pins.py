@@ -823,3 +823,99 @@ def test_schedule_hand_derived_scenarios():
     wait = [_T(0, 64, 10, 0, 1000, 50), _T(1, 128, 10, 0, 1000, 10)]
     assert osc.schedule(wait, [], 100.0, w, 32, 32, 2.0) == ([1, 0], [])
     assert osc.schedule(wait, [], 100.0, w, 32, 32, 50.0) == ([0, 1], [])            # urgent mode: slack order
+
+
+# ----------------------------------------------------------------------------- joint text-image block
+def _mmdit_params(seed, C, D, F):
+    rd = lambda name, shape, scale: (wl.Stream(seed, name).normal(shape) * scale).astype(np.float64)
+    p = {}
+    for X in ("img", "txt"):
+        p[X + ".wm"], p[X + ".bm"] = rd(X + "wm", (D, 6 * C), D ** -0.5), rd(X + "bm", (6 * C,), 0.1)
+        for n in ("wq", "wk", "wv", "wo"):
+            p[X + "." + n] = rd(X + n, (C, C), C ** -0.5)
+        p[X + ".bo"] = rd(X + "bo", (C,), 0.1)
+        p[X + ".w1"], p[X + ".b1"] = rd(X + "w1", (C, F), C ** -0.5), rd(X + "b1", (F,), 0.1)
+        p[X + ".w2"], p[X + ".b2"] = rd(X + "w2", (F, C), F ** -0.5), rd(X + "b2", (C,), 0.1)
+    return p
+
+
+def test_mmdit_vs_torch_composition():
+    C, D, Fh, L, heads = 16, 10, 32, 7, 2
+    p = _mmdit_params(3, C, D, Fh)
+    z = wl.Stream(3, "z").normal((C, 4, 6)).astype(np.float64)
+    txt = wl.Stream(3, "t").normal((L, C)).astype(np.float64)
+    c = wl.Stream(3, "c").normal((D,)).astype(np.float64)
+    gi, gt = ob.mmdit(z, txt, c, p, heads, 1e-5)
+    t = torch.from_numpy
+    xs = {"img": t(z).flatten(1).T, "txt": t(txt)}
+    mod, qkv = {}, {}
+    for X in ("img", "txt"):
+        mod[X] = F_linear(F.silu(t(c)), t(p[X + ".wm"]), t(p[X + ".bm"])).chunk(6)
+        h = F.layer_norm(xs[X], (C,), None, None, 1e-5) * (1 + mod[X][1]) + mod[X][0]
+        qkv[X] = [h @ t(p[X + "." + n]) for n in ("wq", "wk", "wv")]
+    cat = [torch.cat([qkv["img"][i], qkv["txt"][i]]) for i in range(3)]
+    sp = lambda a: a.reshape(1, -1, heads, C // heads).transpose(1, 2)
+    o = F.scaled_dot_product_attention(sp(cat[0]), sp(cat[1]), sp(cat[2])).transpose(1, 2).reshape(-1, C)
+    outs, at = {}, 0
+    for X in ("img", "txt"):
+        n = xs[X].shape[0]
+        x1 = xs[X] + mod[X][2] * (o[at:at + n] @ t(p[X + ".wo"]) + t(p[X + ".bo"]))
+        at += n
+        h2 = F.layer_norm(x1, (C,), None, None, 1e-5) * (1 + mod[X][4]) + mod[X][3]
+        outs[X] = x1 + mod[X][5] * (F.gelu(h2 @ t(p[X + ".w1"]) + t(p[X + ".b1"]), approximate="tanh") @ t(p[X + ".w2"]) + t(p[X + ".b2"]))
+    assert np.allclose(gi, outs["img"].T.reshape(C, 4, 6).numpy(), atol=1e-10)
+    assert np.allclose(gt, outs["txt"].numpy(), atol=1e-10)
+
+
+def F_linear(x, w, b):
+    return x @ w + b
+
+
+def test_mmdit_without_text_is_the_adaln_block_and_text_order_is_free():
+    """No text tokens: the image stream is ASATTN followed by AMLP with the modulation split in two (both pinned
+    above).  With text: permuting the text tokens permutes the text output and leaves the image output alone."""
+    C, D, Fh, heads = 16, 10, 32, 2
+    p = _mmdit_params(4, C, D, Fh)
+    z = wl.Stream(4, "z").normal((C, 4, 6)).astype(np.float64)
+    c = wl.Stream(4, "c").normal((D,)).astype(np.float64)
+    gi, gt = ob.mmdit(z, np.zeros((0, C)), c, p, heads, 1e-5)
+    assert gt.shape == (0, C)
+    pa = {"wm": p["img.wm"][:, :3 * C], "bm": p["img.bm"][:3 * C], **{n: p["img." + n] for n in ("wq", "wk", "wv", "wo", "bo")}}
+    pm = {"wm": p["img.wm"][:, 3 * C:], "bm": p["img.bm"][3 * C:], **{n: p["img." + n] for n in ("w1", "b1", "w2", "b2")}}
+    ref, _ = ob.block_forward(z, ("ASATTN", "AMLP"), [pa, pm], G=1, heads=heads, eps=1e-5, temb=c)
+    assert np.allclose(gi, ref, atol=1e-12)
+    txt = wl.Stream(4, "t").normal((5, C)).astype(np.float64)
+    a_i, a_t = ob.mmdit(z, txt, c, p, heads, 1e-5)
+    perm = np.array([3, 0, 4, 1, 2])
+    b_i, b_t = ob.mmdit(z, txt[perm], c, p, heads, 1e-5)
+    assert np.allclose(a_i, b_i, atol=1e-12) and np.allclose(a_t[perm], b_t, atol=1e-12)
+    assert np.abs(a_i - gi).max() > 1e-3                           # the text does reach the image stream
+
+
+def test_plan_with_text_patches():
+    """Text patches sit behind the image patches of their request, off the grid: the image part of every table is the
+    plan without text, renumbered; seq_len = H*W + L; the scatter / gather pair round-trips and zero-fills the padding."""
+    res, ph, pw, L = [(8, 8), (4, 8), (8, 8)], 4, 4, 20
+    a, b = op.plan_tables(res, ph, pw), op.plan_tables(res, ph, pw, text_len=L)
+    tp = 2                                                         # ceil(20 / 16)
+    assert b["P"] == a["P"] + 3 * tp and b["T"] == b["P"] * 16
+    assert np.array_equal(b["perm"], a["perm"]) and np.array_equal(b["seq_len"], [32 + L, 64 + L, 64 + L])
+    assert np.array_equal(np.diff(b["request_offset"]), np.diff(a["request_offset"]) + tp)
+    img = [q for q in range(b["P"]) if b["patch_rc"][q, 0] >= 0]
+    new_id = {old: q for old, q in enumerate(img)}
+    assert np.array_equal(b["patch_rc"][img], a["patch_rc"]) and np.array_equal(b["patch_owner"][img], a["patch_owner"])
+    remap = lambda v, scale: np.where(v < 0, -1, np.vectorize(lambda u: new_id[u // scale] * scale + u % scale)(np.maximum(v, 0)))
+    assert np.array_equal(b["neighbour"][img], remap(a["neighbour"], 1))
+    assert np.array_equal(b["halo_src"][img], remap(a["halo_src"], 16))
+    txtp = [q for q in range(b["P"]) if b["patch_rc"][q, 0] < 0]
+    assert (b["neighbour"][txtp] == -1).all() and (b["halo_src"][txtp] == -1).all()
+    assert [tuple(b["patch_rc"][q]) for q in txtp] == [(-1, 0), (-1, 1)] * 3
+    x = wl.Stream(9, "x").normal((b["T"], 3))
+    text = wl.Stream(9, "t").normal((3, L, 3))
+    y = op.text_scatter(x, text, res, ph, pw)
+    assert np.array_equal(op.text_gather(y, L, res, ph, pw), text)
+    for s in range(3):
+        lo, hi = b["cu_seqlens"][s] + b["seq_len"][s], b["cu_seqlens"][s + 1]
+        assert hi - lo == tp * 16 - L and not y[lo:hi].any()
+        img_rows = slice(b["cu_seqlens"][s], b["cu_seqlens"][s] + b["seq_len"][s] - L)
+        assert np.array_equal(y[img_rows], x[img_rows])
