@@ -81,7 +81,8 @@ extern "C" {
 #define PSERVE_TAB_HALO_SRC        7   /* [P][2(pw+2)+2ph] global token id of each ring pixel, -1 = outside the image;
                                           ring order: top row x=-1..pw, bottom row x=-1..pw, left col y=0..ph-1, right col y=0..ph-1 */
 #define PSERVE_TAB_CU_SEQLENS      8   /* [n+1]    first token of sorted slot s */
-#define PSERVE_TAB_COUNT           9
+#define PSERVE_TAB_SEQ_LEN         9   /* [n]      valid tokens of sorted slot s: H*W, plus text_len in a joint plan */
+#define PSERVE_TAB_COUNT           10
 
 /* cache slots of a stage (pserve_cache_load / pserve_cache_read); stage = -1 addresses the block output slot */
 #define PSERVE_SLOT_H1  0   /* RES2, RES2T: output of the first convolution (RES2T: time embedding included) */
@@ -101,6 +102,8 @@ typedef struct {
     int32_t ph, pw;   /* patch height / width (latent pixels) */
     int32_t ring;     /* 2(pw+2)+2ph, entries of HALO_SRC per patch */
     int64_t T;        /* tokens = P*ph*pw */
+    int32_t text_len;      /* text tokens per request (pserve_plan_text), else 0 */
+    int32_t text_patches;  /* ceil(text_len / (ph*pw)): extra patches per request, counted in P and T */
 } pserve_plan_info_t;
 
 typedef struct {
@@ -137,6 +140,18 @@ const char* pserve_last_error(void);
  * than 2^31-1 tokens; ENOMEM; EHIP.  *out is owned by the caller until pserve_plan_free. */
 int  pserve_plan(const int32_t* resolutions_hw, int32_t n, int32_t ph, int32_t pw,
                  void* stream, pserve_plan_t** out);
+/* The same for the joint text-image attention of the paper's second model ("Patch-based Self-Attention Module":
+ * every token attends to the tokens of its own request): the text_len text tokens of a request ride along as
+ * ceil(text_len / (ph*pw)) extra patches behind its image patches (grid position (-1, k), no neighbours, no halo), so
+ * that per-token operators and the per-request attention take them in without a second code path.  SEQ_LEN[s] = H*W +
+ * text_len counts the valid tokens of slot s: its key set is the token range [CU_SEQLENS[s], CU_SEQLENS[s] +
+ * SEQ_LEN[s]); the padding rows of the last text patch lie behind it.  split / reassemble move image patches only;
+ * pserve_text_scatter copies text DEVICE [n][text_len][C] (caller order) into the text patches of x (padding rows
+ * zeroed), pserve_text_gather copies them back out.  text_len = 0 gives pserve_plan. */
+int  pserve_plan_text(const int32_t* resolutions_hw, int32_t n, int32_t ph, int32_t pw, int32_t text_len,
+                      void* stream, pserve_plan_t** out);
+int  pserve_text_scatter(const pserve_plan_t* plan, const void* text, int32_t C, int dtype, void* x, void* stream);
+int  pserve_text_gather(const pserve_plan_t* plan, const void* x, int32_t C, int dtype, void* text, void* stream);
 void pserve_plan_free(pserve_plan_t* plan);
 int  pserve_plan_info(const pserve_plan_t* plan, pserve_plan_info_t* out);
 /* Borrowed pointer to a table (valid until pserve_plan_free): on_device != 0 gives the

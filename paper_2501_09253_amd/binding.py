@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 F32, BF16 = 0, 1
 STAGE_KIND = {"RES1": 1, "RES2": 2, "SATTN": 3, "XATTN": 4, "FFN": 5, "LSATTN": 6, "LXATTN": 7, "LFFN": 8, "RES2T": 9, "ASATTN": 10, "AMLP": 11}
 TABLES = {"perm": 0, "request_offset": 1, "res_offset": 2, "res_hw": 3, "patch_owner": 4,
-          "patch_rc": 5, "neighbour": 6, "halo_src": 7, "cu_seqlens": 8}
+          "patch_rc": 5, "neighbour": 6, "halo_src": 7, "cu_seqlens": 8, "seq_len": 9}
 SLOT_H1, SLOT_R, SLOT_K, SLOT_V, SLOT_Y = 0, 1, 2, 3, 4
 MAX_STAGES, MAX_PARAMS = 8, 12
 
@@ -44,7 +44,7 @@ class PserveError(RuntimeError):
 
 class _PlanInfo(C.Structure):
     _fields_ = [("n", C.c_int32), ("R", C.c_int32), ("P", C.c_int32), ("ph", C.c_int32), ("pw", C.c_int32),
-                ("ring", C.c_int32), ("T", C.c_int64)]
+                ("ring", C.c_int32), ("T", C.c_int64), ("text_len", C.c_int32), ("text_patches", C.c_int32)]
 
 
 class _BlockDesc(C.Structure):
@@ -95,6 +95,9 @@ def lib() -> C.CDLL:
     L.pserve_plan_free.restype = None
     L.pserve_plan_info.argtypes = [vp, C.POINTER(_PlanInfo)]
     L.pserve_plan_table.argtypes = [vp, C.c_int, C.c_int, C.POINTER(C.POINTER(i32)), C.POINTER(i64)]
+    L.pserve_plan_text.argtypes = [C.POINTER(i32), i32, i32, i32, i32, vp, C.POINTER(vp)]
+    L.pserve_text_scatter.argtypes = [vp, vp, i32, C.c_int, vp, vp]
+    L.pserve_text_gather.argtypes = [vp, vp, i32, C.c_int, vp, vp]
     L.pserve_split.argtypes = [vp, C.POINTER(vp), i32, C.c_int, vp, vp]
     L.pserve_reassemble.argtypes = [vp, vp, i32, C.c_int, C.POINTER(vp), vp]
     L.pserve_block_create.argtypes = [C.POINTER(_BlockDesc), C.POINTER(_BlockParams), vp, C.POINTER(vp)]
@@ -177,16 +180,35 @@ def profile_read() -> Dict[str, Dict[str, float]]:
 class Plan:
     """pserve_plan: Compressed Sparse Patch tables of one batch composition."""
 
-    def __init__(self, resolutions: Sequence[Sequence[int]], ph: int = 0, pw: int = 0):
+    def __init__(self, resolutions: Sequence[Sequence[int]], ph: int = 0, pw: int = 0, text_len: int = 0):
         res = np.ascontiguousarray(np.asarray(resolutions, dtype=np.int32).reshape(-1, 2))
         self._h = C.c_void_p()
-        _check(lib().pserve_plan(res.ctypes.data_as(C.POINTER(C.c_int32)), res.shape[0], ph, pw, _stream(),
-                                 C.byref(self._h)))
+        _check(lib().pserve_plan_text(res.ctypes.data_as(C.POINTER(C.c_int32)), res.shape[0], ph, pw, text_len, _stream(),
+                                      C.byref(self._h)))
         info = _PlanInfo()
         _check(lib().pserve_plan_info(self._h, C.byref(info)))
         self.n, self.R, self.P, self.ph, self.pw, self.ring, self.T = (info.n, info.R, info.P, info.ph, info.pw,
                                                                       info.ring, info.T)
+        self.text_len, self.text_patches = info.text_len, info.text_patches
         self.resolutions = [tuple(int(v) for v in r) for r in res]
+
+    def text_scatter(self, text, x):
+        """pserve_text_scatter: text [n, text_len, C] (caller order) into the text patches of x[T, C] (in place)."""
+        assert text.is_contiguous() and x.is_contiguous() and text.dtype == x.dtype
+        assert tuple(text.shape) == (self.n, self.text_len, x.shape[1]) and x.shape[0] == self.T
+        import torch
+        dt = BF16 if x.dtype == torch.bfloat16 else F32
+        _check(lib().pserve_text_scatter(self._h, text.data_ptr(), x.shape[1], dt, x.data_ptr(), _stream()))
+        return x
+
+    def text_gather(self, x):
+        """pserve_text_gather: the text tokens of every request out of x[T, C]: [n, text_len, C] in caller order."""
+        import torch
+        assert x.is_contiguous() and x.shape[0] == self.T
+        out = torch.empty((self.n, self.text_len, x.shape[1]), dtype=x.dtype, device=x.device)
+        dt = BF16 if x.dtype == torch.bfloat16 else F32
+        _check(lib().pserve_text_gather(self._h, x.data_ptr(), x.shape[1], dt, out.data_ptr(), _stream()))
+        return out
 
     def table(self, name: str) -> np.ndarray:
         """Host mirror of a table as a numpy int32 array (copy)."""

@@ -43,7 +43,7 @@ attn_simple_kernel(AttnArgs a) {
     const int s = a.owner[p];
     int64_t k0, nk;
     if (a.cross_len) { k0 = (int64_t)a.perm[s] * a.cross_ld; nk = a.cross_len; }
-    else { k0 = a.cu_seqlens[s]; nk = a.cu_seqlens[s + 1] - k0; }
+    else { k0 = a.cu_seqlens[s]; nk = a.seq_len ? a.seq_len[s] : a.cu_seqlens[s + 1] - k0; }
 
     float m = -INFINITY, l = 0.f;
     float acc[DMAX];

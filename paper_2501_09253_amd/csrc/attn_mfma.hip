@@ -89,7 +89,7 @@ attn_mfma_kernel(AttnArgs a) {
     int64_t k0;
     int nk;
     if (a.cross_len) { k0 = (int64_t)a.perm[s] * a.cross_ld; nk = a.cross_len; }
-    else { k0 = a.cu_seqlens[s]; nk = a.cu_seqlens[s + 1] - a.cu_seqlens[s]; }
+    else { k0 = a.cu_seqlens[s]; nk = a.seq_len ? a.seq_len[s] : a.cu_seqlens[s + 1] - a.cu_seqlens[s]; }
 
     const uint16_t* Q = (const uint16_t*)a.Q;
     const uint16_t* K = (const uint16_t*)a.K;

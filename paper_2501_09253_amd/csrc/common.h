@@ -80,6 +80,7 @@ struct pserve_plan_s {
     int64_t T = 0;
     int32_t S = 0;                              // tokens per patch
     int32_t max_tokens_per_image = 0;
+    int32_t text_len = 0, text_patches = 0;     // joint plans: text tokens / text patches per request
     std::vector<int32_t> h_tab[PSERVE_TAB_COUNT];
     int32_t* d_tab[PSERVE_TAB_COUNT] = {};
     int64_t tab_count[PSERVE_TAB_COUNT] = {};

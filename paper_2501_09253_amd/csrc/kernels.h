@@ -141,6 +141,7 @@ struct AttnArgs {
     ActiveList act;
     const int32_t* owner;      // [P] sorted slot of a patch
     const int32_t* cu_seqlens; // self: [n+1] token range of slot s
+    const int32_t* seq_len;    // self: [n] valid tokens of slot s (keys cu_seqlens[s] .. + seq_len[s]); nullptr: the whole range
     const int32_t* perm;       // cross: caller index of slot s
     int32_t cross_len;         // 0 = self-attention; else keys of slot s are rows perm[s]*cross_len .. +cross_len
     int32_t cross_ld;          // cross: padded key rows per request (>= cross_len)

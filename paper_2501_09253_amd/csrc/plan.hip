@@ -28,8 +28,9 @@ void set_error(const char* fmt, ...) {
 // n is small (a serving batch), so a single wavefront-serial pass by thread 0 per 256-slot
 // chunk would do; a block-wide Hillis-Steele scan keeps it O(log n) deep anyway.
 __global__ void plan_offsets_kernel(const int32_t* __restrict__ sorted_hw, int32_t n, int32_t ph, int32_t pw,
-                                    int32_t* __restrict__ request_offset, int32_t* __restrict__ cu_seqlens,
-                                    int32_t* __restrict__ res_offset, int32_t* __restrict__ res_hw) {
+                                    int32_t tp, int32_t text_len, int32_t* __restrict__ request_offset,
+                                    int32_t* __restrict__ cu_seqlens, int32_t* __restrict__ res_offset,
+                                    int32_t* __restrict__ res_hw, int32_t* __restrict__ seq_len) {
     __shared__ int32_t s_cnt[1024];
     __shared__ int32_t s_flag[1024];
     __shared__ int32_t carry_cnt, carry_flag;
@@ -41,7 +42,8 @@ __global__ void plan_offsets_kernel(const int32_t* __restrict__ sorted_hw, int32
         int32_t cnt = 0, flag = 0;
         if (s < n) {
             const int32_t H = sorted_hw[2 * s], W = sorted_hw[2 * s + 1];
-            cnt = (H / ph) * (W / pw);
+            cnt = (H / ph) * (W / pw) + tp;               // tp text patches ride behind the image patches
+            seq_len[s] = H * W + text_len;                // valid tokens of the slot (padding of the last text patch excluded)
             flag = (s == 0) || sorted_hw[2 * s - 2] != H || sorted_hw[2 * s - 1] != W;   // first slot of a resolution run
         }
         s_cnt[tid] = cnt;
@@ -77,6 +79,7 @@ __global__ void plan_offsets_kernel(const int32_t* __restrict__ sorted_hw, int32
 __global__ void plan_patches_kernel(const int32_t* __restrict__ sorted_hw, const int32_t* __restrict__ request_offset,
                                     int32_t n, int32_t P, int32_t ph, int32_t pw, int32_t* __restrict__ owner,
                                     int32_t* __restrict__ rc, int32_t* __restrict__ neighbour) {
+    // (text patches: local index >= gh*gw; grid position (-1, k), no neighbours)
     const int p = blockIdx.x * blockDim.x + threadIdx.x;
     if (p >= P) return;
     int lo = 0, hi = n;                       // largest s with request_offset[s] <= p
@@ -87,8 +90,14 @@ __global__ void plan_patches_kernel(const int32_t* __restrict__ sorted_hw, const
     const int s = lo;
     const int gh = sorted_hw[2 * s] / ph, gw = sorted_hw[2 * s + 1] / pw;
     const int local = p - request_offset[s];
-    const int r = local / gw, c = local - r * gw;
     owner[p] = s;
+    if (local >= gh * gw) {
+        rc[2 * p] = -1;
+        rc[2 * p + 1] = local - gh * gw;
+        for (int k = 0; k < 8; ++k) neighbour[8 * p + k] = -1;
+        return;
+    }
+    const int r = local / gw, c = local - r * gw;
     rc[2 * p] = r;
     rc[2 * p + 1] = c;
     int k = 0;
@@ -117,7 +126,7 @@ __global__ void plan_halo_kernel(const int32_t* __restrict__ sorted_hw, const in
     const int H = sorted_hw[2 * s], W = sorted_hw[2 * s + 1], gw = W / pw;
     const int Y = rc[2 * p] * ph + y, X = rc[2 * p + 1] * pw + x;      // absolute pixel in the image
     int32_t tok = -1;
-    if (Y >= 0 && Y < H && X >= 0 && X < W) {
+    if (rc[2 * p] >= 0 && Y >= 0 && Y < H && X >= 0 && X < W) {
         const int q = request_offset[s] + (Y / ph) * gw + (X / pw);
         tok = q * ph * pw + (Y % ph) * pw + (X % pw);
     }
@@ -141,6 +150,7 @@ split_kernel(ImagePtrs imgs, int slot0, int patch0, const int32_t* __restrict__ 
     const int p = patch0 + blockIdx.x / ph;
     const int y = blockIdx.x % ph;
     const int c0 = blockIdx.y * 64;
+    if (rc[2 * p] < 0) return;                  // a text patch: not part of any image
     const int s = owner[p];
     const int H = sorted_hw[2 * s], W = sorted_hw[2 * s + 1];
     T* img = (T*)imgs.p[s - slot0];
@@ -188,6 +198,7 @@ split_vec_kernel(ImagePtrs imgs, int slot0, int patch0, const int32_t* __restric
     const int p = patch0 + blockIdx.x / tiles;
     const int t0 = (blockIdx.x % tiles) * 32;
     const int c0 = blockIdx.y * 64;
+    if (rc[2 * p] < 0) return;                  // a text patch: not part of any image
     const int s = owner[p];
     const int H = sorted_hw[2 * s], W = sorted_hw[2 * s + 1];
     uint16_t* img = (uint16_t*)imgs.p[s - slot0];
@@ -218,6 +229,36 @@ split_vec_kernel(ImagePtrs imgs, int slot0, int patch0, const int32_t* __restric
             v[k] = (uint32_t)tile[8 * iq + 2 * k][ich] | ((uint32_t)tile[8 * iq + 2 * k + 1][ich] << 16);
         *reinterpret_cast<u32x4*>(ip) = v;
     }
+}
+
+// Text tokens of every request <-> the text patches of the joint token matrix.  One thread per (slot, text row
+// incl. padding, 16-byte vector).  TO_PATCH: text [n][L][C] (caller order) -> x, padding rows zeroed; else x -> text.
+template <bool TO_PATCH>
+__global__ void text_rows_kernel(uint4* __restrict__ x, uint4* __restrict__ text, const int32_t* __restrict__ perm,
+                                 const int32_t* __restrict__ cu_seqlens, const int32_t* __restrict__ seq_len, int32_t n,
+                                 int32_t L, int32_t rows_pad, int32_t CV) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)n * rows_pad * CV) return;
+    const int cv = (int)(i % CV);
+    const int r = (int)((i / CV) % rows_pad);
+    const int s = (int)(i / ((int64_t)CV * rows_pad));
+    const int64_t xrow = (int64_t)cu_seqlens[s] + seq_len[s] - L + r;         // first text row sits behind the image tokens
+    if (TO_PATCH) x[xrow * CV + cv] = r < L ? text[((int64_t)perm[s] * L + r) * CV + cv] : make_uint4(0, 0, 0, 0);
+    else if (r < L) text[((int64_t)perm[s] * L + r) * CV + cv] = x[xrow * CV + cv];
+}
+
+template <bool TO_PATCH>
+static int run_text(const pserve_plan_t* plan, void* x, void* text, int32_t C, int dtype, hipStream_t st) {
+    PS_REQUIRE(plan && x && text, "text scatter/gather: NULL argument");
+    PS_REQUIRE(plan->text_len > 0, "text scatter/gather: the plan has no text patches (pserve_plan_text)");
+    PS_REQUIRE(dtype == PSERVE_F32 || dtype == PSERVE_BF16, "text scatter/gather: unknown dtype %d", dtype);
+    const int vn = dtype == PSERVE_BF16 ? 8 : 4;
+    PS_REQUIRE(C > 0 && C % vn == 0, "text scatter/gather: C=%d must be a multiple of 16 bytes", C);
+    const int rows_pad = plan->text_patches * plan->S, CV = C / vn;
+    const int64_t items = (int64_t)plan->n * rows_pad * CV;
+    text_rows_kernel<TO_PATCH><<<(unsigned)cdiv(items, 256), 256, 0, st>>>((uint4*)x, (uint4*)text, plan->d_tab[PSERVE_TAB_PERM],
+        plan->d_tab[PSERVE_TAB_CU_SEQLENS], plan->d_tab[PSERVE_TAB_SEQ_LEN], plan->n, plan->text_len, rows_pad, CV);
+    return check_launch("text_rows_kernel");
 }
 
 template <bool TO_PATCH>
@@ -265,7 +306,21 @@ extern "C" {
 const char* pserve_last_error(void) { return g_err; }
 
 int pserve_plan(const int32_t* res, int32_t n, int32_t ph, int32_t pw, void* stream, pserve_plan_t** out) {
+    return pserve_plan_text(res, n, ph, pw, 0, stream, out);
+}
+
+int pserve_text_scatter(const pserve_plan_t* plan, const void* text, int32_t C, int dtype, void* x, void* stream) {
+    return run_text<true>(plan, x, const_cast<void*>(text), C, dtype, (hipStream_t)stream);
+}
+
+int pserve_text_gather(const pserve_plan_t* plan, const void* x, int32_t C, int dtype, void* text, void* stream) {
+    return run_text<false>(plan, const_cast<void*>(x), text, C, dtype, (hipStream_t)stream);
+}
+
+int pserve_plan_text(const int32_t* res, int32_t n, int32_t ph, int32_t pw, int32_t text_len, void* stream,
+                     pserve_plan_t** out) {
     PS_REQUIRE(out, "pserve_plan: out is NULL");
+    PS_REQUIRE(text_len >= 0, "pserve_plan: negative text_len");
     *out = nullptr;
     PS_REQUIRE(res && n > 0, "pserve_plan: need n > 0 resolutions");
     PS_REQUIRE((ph == 0) == (pw == 0) && ph >= 0 && pw >= 0, "pserve_plan: patch must be (0,0) or both positive");
@@ -281,6 +336,9 @@ int pserve_plan(const int32_t* res, int32_t n, int32_t ph, int32_t pw, void* str
         P += (int64_t)(res[2 * i] / ph) * (res[2 * i + 1] / pw);
         max_tok = std::max<int64_t>(max_tok, (int64_t)res[2 * i] * res[2 * i + 1]);
     }
+    const int32_t tp = (int32_t)cdiv(text_len, (int64_t)ph * pw);     // text patches per request
+    P += (int64_t)n * tp;
+    max_tok += (int64_t)tp * ph * pw;
     const int64_t T = P * ph * pw;
     const int32_t ring = 2 * (pw + 2) + 2 * ph;
     PS_REQUIRE(T < (int64_t)1 << 31 && P * ring < (int64_t)1 << 31, "pserve_plan: batch too large (%lld tokens)", (long long)T);
@@ -305,6 +363,7 @@ int pserve_plan(const int32_t* res, int32_t n, int32_t ph, int32_t pw, void* str
     }
     pl->n = n; pl->R = R; pl->P = (int32_t)P; pl->ph = ph; pl->pw = pw; pl->ring = ring; pl->T = T; pl->S = ph * pw;
     pl->max_tokens_per_image = (int32_t)max_tok;
+    pl->text_len = text_len; pl->text_patches = tp;
 
     int64_t* cnt = pl->tab_count;
     cnt[PSERVE_TAB_PERM] = n;
@@ -316,6 +375,7 @@ int pserve_plan(const int32_t* res, int32_t n, int32_t ph, int32_t pw, void* str
     cnt[PSERVE_TAB_NEIGHBOUR] = 8 * P;
     cnt[PSERVE_TAB_HALO_SRC] = P * ring;
     cnt[PSERVE_TAB_CU_SEQLENS] = n + 1;
+    cnt[PSERVE_TAB_SEQ_LEN] = n;
     for (int t = 0; t < PSERVE_TAB_COUNT; ++t) PS_TRY(pl->pool.alloc_t(&pl->d_tab[t], (size_t)cnt[t]));
     PS_TRY(pl->pool.alloc_t(&pl->d_sorted_hw, (size_t)2 * n));
     PS_TRY(pl->pool.alloc_t(&pl->mse_partial, (size_t)P * 16));
@@ -323,9 +383,9 @@ int pserve_plan(const int32_t* res, int32_t n, int32_t ph, int32_t pw, void* str
     hipStream_t st = (hipStream_t)stream;
     PS_CHECK_HIP(hipMemcpyAsync(pl->d_sorted_hw, pl->h_sorted_hw.data(), sizeof(int32_t) * 2 * n, hipMemcpyHostToDevice, st));
     PS_CHECK_HIP(hipMemcpyAsync(pl->d_tab[PSERVE_TAB_PERM], perm.data(), sizeof(int32_t) * n, hipMemcpyHostToDevice, st));
-    plan_offsets_kernel<<<1, 1024, 0, st>>>(pl->d_sorted_hw, n, ph, pw, pl->d_tab[PSERVE_TAB_REQUEST_OFFSET],
+    plan_offsets_kernel<<<1, 1024, 0, st>>>(pl->d_sorted_hw, n, ph, pw, tp, text_len, pl->d_tab[PSERVE_TAB_REQUEST_OFFSET],
                                             pl->d_tab[PSERVE_TAB_CU_SEQLENS], pl->d_tab[PSERVE_TAB_RES_OFFSET],
-                                            pl->d_tab[PSERVE_TAB_RES_HW]);
+                                            pl->d_tab[PSERVE_TAB_RES_HW], pl->d_tab[PSERVE_TAB_SEQ_LEN]);
     PS_TRY(check_launch("plan_offsets_kernel"));
     plan_patches_kernel<<<(unsigned)cdiv(P, 256), 256, 0, st>>>(pl->d_sorted_hw, pl->d_tab[PSERVE_TAB_REQUEST_OFFSET], n, (int32_t)P,
                                                       ph, pw, pl->d_tab[PSERVE_TAB_PATCH_OWNER], pl->d_tab[PSERVE_TAB_PATCH_RC],
@@ -351,6 +411,7 @@ int pserve_plan_info(const pserve_plan_t* plan, pserve_plan_info_t* out) {
     PS_REQUIRE(plan && out, "pserve_plan_info: NULL argument");
     out->n = plan->n; out->R = plan->R; out->P = plan->P; out->ph = plan->ph; out->pw = plan->pw;
     out->ring = plan->ring; out->T = plan->T;
+    out->text_len = plan->text_len; out->text_patches = plan->text_patches;
     return PSERVE_OK;
 }
 

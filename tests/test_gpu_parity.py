@@ -48,6 +48,35 @@ def test_plan_tables_bit_exact(res, ph, pw):
         assert np.array_equal(plan.table(name).reshape(-1), ref[name].reshape(-1)), name
 
 
+@pytest.mark.parametrize("res,ph,pw,L", [([(8, 8), (4, 8), (8, 8)], 4, 4, 20), ([(32, 32), (16, 48)], 16, 16, 77),
+                                         ([(64, 64), (32, 32)], 16, 16, 256), ([(6, 10)], 6, 10, 1)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_joint_plan_and_text_rows_bit_exact(res, ph, pw, L, dtype):
+    """Plan with the text tokens as extra patches: every table, and the text scatter / gather copies."""
+    plan = ps.Plan(res, ph, pw, text_len=L)
+    ref = op.plan_tables(res, ph, pw, text_len=L)
+    assert (plan.P, plan.T, plan.text_len, plan.text_patches) == (ref["P"], ref["T"], L, -(-L // (ph * pw)))
+    for name in ps.TABLES:
+        assert np.array_equal(plan.table(name).reshape(-1), ref[name].reshape(-1)), name
+    C = 16
+    imgs = [wl.bf16_round(wl.Stream(5, f"s{i}").normal((C, h, w))) for i, (h, w) in enumerate(res)]
+    text = wl.bf16_round(wl.Stream(5, "t").normal((len(res), L, C)))
+    x = torch.full((plan.T, C), 7.0, device="cuda", dtype=torch.bfloat16 if dtype == "bf16" else torch.float32)
+    plan.split([to_dev(a, dtype) for a in imgs], out=x)           # image patches only: text patches keep the fill value
+    host = to_host(x)
+    img_rows = np.repeat(ref["patch_rc"][:, 0] >= 0, ph * pw)
+    joint = np.full((ref["T"], C), 7.0, dtype=np.float32)
+    joint[img_rows] = op.split(imgs, ph, pw)
+    assert np.array_equal(host, joint)
+    plan.text_scatter(to_dev(text, dtype), x)
+    want = op.text_scatter(joint, text, res, ph, pw)
+    assert np.array_equal(to_host(x), want)
+    assert np.array_equal(to_host(plan.text_gather(x)), text)
+    back = plan.reassemble(x)
+    for a, b in zip(back, imgs):
+        assert np.array_equal(to_host(a), b)
+
+
 def test_plan_many_requests():
     rng = np.random.default_rng(0)
     res = [(int(4 * rng.integers(1, 5)), int(4 * rng.integers(1, 5))) for _ in range(1500)]
