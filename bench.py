@@ -53,6 +53,12 @@ def kernel_work(cfg, n_active_tokens, patch=None):
     frac = Ta / T
     F = cfg.ffn_mult * C
     attn = sum(4.0 * (h * w) * (h * w) * C for h, w in cfg.resolutions) * frac
+    if "MMDIT" in cfg.stages:
+        # joint block: every linear kernel runs once per stream (image rows, text rows), one attention over both; the
+        # per-launch figures below are the mean of the two launches
+        L = cfg.ctx_len
+        attn = sum(4.0 * (h * w + L) * (h * w + L) * C for h, w in cfg.resolutions)
+        Ta = (T + cfg.n * L) / 2.0
     return {
         "conv3x3": (2.0 * 9 * C * C * Ta, 2.0 * b * C * Ta + 9.0 * b * C * C),
         "linear_qkv": (2.0 * C * 3 * C * Ta, b * 4.0 * C * Ta),
@@ -79,7 +85,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5, 6 = config 3 with per-token LayerNorms, 7 = config 2 with the time embedding, 8 = a diffusion-transformer block (default: 2, the SDXL ResNet block)")
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5, 6 = config 3 with per-token LayerNorms, 7 = config 2 with the time embedding, 8 = a diffusion-transformer block, 9 = a joint text-image block (default: 2, the SDXL ResNet block)")
     ap.add_argument("--patch", type=int, nargs=2, default=None, metavar=("PH", "PW"),
                     help="patch size override for the patch-size sweep (not for reuse configs: the mask is per patch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -130,7 +136,7 @@ def main():
 
     def step():
         run.plan.split(run.images, out=run.x)
-        run.cache.forward(run.x, run.ctx, mask, y=y, temb=run.temb)
+        run.cache.forward(run.x, None if run.joint else run.ctx, mask, y=y, temb=run.temb)
         run.plan.reassemble(y, outs)
 
     # Warm-up; its last steps are timed kernel by kernel to find the dominant kernel.  In the timed region only THAT
@@ -177,7 +183,7 @@ def main():
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(args.steps):
-        run.cache.forward(run.x, run.ctx, mask, y=y, temb=run.temb)
+        run.cache.forward(run.x, None if run.joint else run.ctx, mask, y=y, temb=run.temb)
     e1.record()
     torch.cuda.synchronize()
     block_ms = e0.elapsed_time(e1) / args.steps
@@ -199,7 +205,7 @@ def main():
         us = timed(lambda: run.plan.patch_mse(run.x, y))
         gbs = 2.0 * cfg.T * cfg.C * es / (us * 1e-6) / 1e9
         extras["patch_mse"] = {"avg_us": us, "gbs": gbs, "frac_hbm": gbs / PEAK_HBM_GBS}
-        if cfg.dtype == "bf16" and patch[0] % 2 == 0 and patch[1] % 2 == 0 and w.reuse is None:
+        if cfg.dtype == "bf16" and patch[0] % 2 == 0 and patch[1] % 2 == 0 and w.reuse is None and not run.joint:
             # the level changes at this configuration's size: C -> C, down to half size and back up (random weights)
             from harness import to_dev
             import numpy as _np
@@ -269,6 +275,13 @@ def main():
             if H * W > 16384 and used:
                 continue                      # a 65,536-token image alone is minutes of fp64 attention
             c_i = None if w.cache is None else {k: v[i] for k, v in w.cache.items()}
+            if "MMDIT" in cfg.stages:
+                ob.mmdit(w.images[i], w.ctx[i], w.temb[i], w.params[0], cfg.heads, cfg.eps)
+                done_tok += H * W
+                used.append(i)
+                if time.perf_counter() - tc > 25.0:
+                    break
+                continue
             ob.block_forward(w.images[i], cfg.stages, w.params, G=cfg.G, heads=cfg.heads, eps=cfg.eps,
                              ctx=None if w.ctx is None else w.ctx[i],
                              reuse=None if w.reuse is None else w.reuse[i], cache=c_i,

@@ -66,9 +66,17 @@ extern "C" {
  * operands; ASATTN caches K and V like LSATTN.  The joint text-image attention of that model is not part of them. */
 #define PSERVE_ASATTN 10  /* x + gate * (MHA(h) W_o + b_o)                              params: wm [temb_dim][3C] bm [3C] wq wk wv wo bo */
 #define PSERVE_AMLP   11  /* x + gate * (GELU_tanh(h W_1 + b_1) W_2 + b_2), W_1 [C][ffn_mult*C]  params: wm bm w1 b1 w2 b2 */
+/* One whole joint block of that model on a joint plan (pserve_plan_text; x holds image AND text patches).  Each of
+ * the two streams (image tokens, text tokens) has its own weights; (sh1, sc1, g1, sh2, sc2, g2) = sixths of
+ * SiLU(c) W_m + b_m per stream; q, k, v from h = LN0(x)(1 + sc1) + sh1; ONE attention per request over its image and
+ * text tokens together; x += g1 * (o W_o + b_o); x += g2 * (GELU_tanh(h2 W_1 + b_1) W_2 + b_2), h2 = LN0(x)(1 + sc2) + sh2.
+ * A block with a PSERVE_MMDIT stage holds only such stages, needs a joint plan, and has no cache slots (no reuse mask).
+ * params: image stream wm [temb_dim][6C] bm [6C] wq wk wv wo [C][C] bo [C] w1 [C][F] b1 [F] w2 [F][C] b2 [C]
+ * (F = ffn_mult*C), then the same eleven for the text stream. */
+#define PSERVE_MMDIT  12
 
 #define PSERVE_MAX_STAGES 8
-#define PSERVE_MAX_PARAMS 12
+#define PSERVE_MAX_PARAMS 24
 
 /* plan tables (int32) for pserve_plan_table */
 #define PSERVE_TAB_PERM            0   /* [n]      caller index of sorted slot s */
@@ -108,7 +116,7 @@ typedef struct {
 
 typedef struct {
     int32_t n_stages;
-    int32_t stages[PSERVE_MAX_STAGES];   /* PSERVE_RES1 .. PSERVE_AMLP, in execution order */
+    int32_t stages[PSERVE_MAX_STAGES];   /* PSERVE_RES1 .. PSERVE_MMDIT, in execution order */
     int32_t C;          /* channels */
     int32_t G;          /* GroupNorm groups (C % G == 0) */
     int32_t heads;      /* attention heads (C % heads == 0) */

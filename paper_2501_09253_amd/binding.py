@@ -14,11 +14,11 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
 F32, BF16 = 0, 1
-STAGE_KIND = {"RES1": 1, "RES2": 2, "SATTN": 3, "XATTN": 4, "FFN": 5, "LSATTN": 6, "LXATTN": 7, "LFFN": 8, "RES2T": 9, "ASATTN": 10, "AMLP": 11}
+STAGE_KIND = {"RES1": 1, "RES2": 2, "SATTN": 3, "XATTN": 4, "FFN": 5, "LSATTN": 6, "LXATTN": 7, "LFFN": 8, "RES2T": 9, "ASATTN": 10, "AMLP": 11, "MMDIT": 12}
 TABLES = {"perm": 0, "request_offset": 1, "res_offset": 2, "res_hw": 3, "patch_owner": 4,
           "patch_rc": 5, "neighbour": 6, "halo_src": 7, "cu_seqlens": 8, "seq_len": 9}
 SLOT_H1, SLOT_R, SLOT_K, SLOT_V, SLOT_Y = 0, 1, 2, 3, 4
-MAX_STAGES, MAX_PARAMS = 8, 12
+MAX_STAGES, MAX_PARAMS = 8, 24
 
 # parameter order per stage kind (same as the header)
 PARAM_ORDER = {
@@ -30,6 +30,7 @@ PARAM_ORDER = {
     "LSATTN": ["ln_g", "ln_b", "wq", "wk", "wv", "wo", "bo"],
     "LXATTN": ["ln_g", "ln_b", "wq", "wk", "wv", "wo", "bo"],
     "LFFN": ["ln_g", "ln_b", "w1", "b1", "w2", "b2"],
+    "MMDIT": [X + "." + n for X in ("img", "txt") for n in ("wm", "bm", "wq", "wk", "wv", "wo", "bo", "w1", "b1", "w2", "b2")],
     "ASATTN": ["wm", "bm", "wq", "wk", "wv", "wo", "bo"],
     "AMLP": ["wm", "bm", "w1", "b1", "w2", "b2"],
     "RES2T": ["gn_a_g", "gn_a_b", "conv_a_w", "conv_a_b", "gn_b_g", "gn_b_b", "conv_b_w", "conv_b_b", "wt", "bt"],

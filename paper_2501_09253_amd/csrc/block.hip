@@ -56,8 +56,8 @@ struct ProfScope {
 struct StageWeights {
     void* gn_g[2] = {};      // raw copies, block dtype
     void* gn_b[2] = {};
-    void* w[3] = {};         // packed [taps][N][K]
-    float* b[3] = {};        // packed biases (fp32)
+    void* w[5] = {};         // packed [taps][N][K]  (MMDIT: 0 qkv, 1 out, 3 mlp in, 4 mlp out)
+    float* b[5] = {};        // packed biases (fp32)
     void* wt = nullptr;      // RES2T: time projection [temb_dim][C], block dtype (raw copy)
     float* bt = nullptr;     // RES2T: its bias (fp32)
 };
@@ -202,6 +202,7 @@ __global__ void transpose_tc_kernel(const T* __restrict__ src, T* __restrict__ d
 struct pserve_block_s {
     pserve_block_desc desc;
     StageWeights sw[PSERVE_MAX_STAGES];
+    StageWeights sw_txt[PSERVE_MAX_STAGES];   // MMDIT: the text stream's weights (sw holds the image stream's)
     DevicePool pool;
 };
 
@@ -226,6 +227,9 @@ struct pserve_cache_s {
     void* hidden = nullptr;                   // [T][F]
     void* yslot = nullptr;                    // [T][C] block output of the previous step (slot Y)
     float* temb_e[PSERVE_MAX_STAGES] = {};    // RES2T: [n][C] projected time embedding per request slot
+    float* temb_e2[PSERVE_MAX_STAGES] = {};   // MMDIT: [n][6C] modulation of the text stream (temb_e: image stream)
+    int32_t* stream_list[2] = {};             // MMDIT: image patches / text patches of the joint plan (ascending)
+    int32_t* stream_count = nullptr;          // [2] their numbers
     int32_t* active = nullptr;
     int32_t* count = nullptr;
     int32_t* act_off = nullptr;               // [n+1] attention: computed patches before slot s
@@ -254,13 +258,13 @@ static bool has_stage(const pserve_block_desc& d, int kind) {
     return false;
 }
 // stage families: the L-kinds are the token stages with a LayerNorm in front
-static bool is_sattn(int k) { return k == PSERVE_SATTN || k == PSERVE_LSATTN || k == PSERVE_ASATTN; }
+static bool is_sattn(int k) { return k == PSERVE_SATTN || k == PSERVE_LSATTN || k == PSERVE_ASATTN || k == PSERVE_MMDIT; }
 static bool is_xattn(int k) { return k == PSERVE_XATTN || k == PSERVE_LXATTN; }
 static bool is_ffn(int k) { return k == PSERVE_FFN || k == PSERVE_LFFN; }
 static bool is_res2(int k) { return k == PSERVE_RES2 || k == PSERVE_RES2T; }
 static bool has_ln(int k) { return k == PSERVE_LSATTN || k == PSERVE_LXATTN || k == PSERVE_LFFN || k == PSERVE_ASATTN || k == PSERVE_AMLP; }
 static bool has_mod(int k) { return k == PSERVE_ASATTN || k == PSERVE_AMLP; }
-static bool needs_temb(int k) { return k == PSERVE_RES2T || has_mod(k); }
+static bool needs_temb(int k) { return k == PSERVE_RES2T || has_mod(k) || k == PSERVE_MMDIT; }
 template <typename F> static bool any_stage(const pserve_block_desc& d, F f) {
     for (int s = 0; s < d.n_stages; ++s) if (f(d.stages[s])) return true;
     return false;
@@ -335,18 +339,19 @@ int pserve_block_create(const pserve_block_desc* desc, const pserve_block_params
     PS_REQUIRE(d.C > 0 && d.G > 0 && d.C % d.G == 0, "pserve_block_create: C=%d must be a positive multiple of G=%d", d.C, d.G);
     PS_REQUIRE(d.C % (d.dtype == PSERVE_BF16 ? 8 : 4) == 0, "pserve_block_create: C=%d must be a multiple of 16 bytes", d.C);
     PS_REQUIRE(d.eps >= 0.f, "pserve_block_create: negative eps");
-    static const int nparams[12] = {0, 4, 8, 7, 5, 4, 7, 7, 6, 10, 7, 6};
+    static const int nparams[13] = {0, 4, 8, 7, 5, 4, 7, 7, 6, 10, 7, 6, 22};
     for (int s = 0; s < d.n_stages; ++s) {
         const int kind = d.stages[s];
-        PS_REQUIRE(kind >= PSERVE_RES1 && kind <= PSERVE_AMLP, "pserve_block_create: stage %d has unknown kind %d", s, kind);
+        PS_REQUIRE(kind >= PSERVE_RES1 && kind <= PSERVE_MMDIT, "pserve_block_create: stage %d has unknown kind %d", s, kind);
+        PS_REQUIRE((kind == PSERVE_MMDIT) == (d.stages[0] == PSERVE_MMDIT), "pserve_block_create: joint blocks hold PSERVE_MMDIT stages only");
         for (int k = 0; k < nparams[kind]; ++k) PS_REQUIRE(params->p[s][k], "pserve_block_create: stage %d parameter %d is NULL", s, k);
         if (is_sattn(kind) || is_xattn(kind))
             PS_REQUIRE(d.heads > 0 && d.C % d.heads == 0 && d.C / d.heads <= 128,
                        "pserve_block_create: heads=%d must divide C=%d with head dim <= 128", d.heads, d.C);
         if (needs_temb(kind))
             PS_REQUIRE(d.temb_dim > 0 && d.temb_dim <= 8192, "pserve_block_create: stage %d needs temb_dim in 1..8192 (got %d)", s, d.temb_dim);
-        if (kind == PSERVE_AMLP)
-            PS_REQUIRE(d.ffn_mult > 0, "pserve_block_create: AMLP needs ffn_mult > 0");
+        if (kind == PSERVE_AMLP || kind == PSERVE_MMDIT)
+            PS_REQUIRE(d.ffn_mult > 0, "pserve_block_create: AMLP / MMDIT need ffn_mult > 0");
         if (is_xattn(kind))
             PS_REQUIRE(d.ctx_len > 0 && d.ctx_dim > 0, "pserve_block_create: XATTN needs ctx_len and ctx_dim");
         if (is_ffn(kind))
@@ -410,6 +415,31 @@ int pserve_block_create(const pserve_block_desc* desc, const pserve_block_params
             PS_TRY(pack_bias(p[o + 4], w.b[1], C, d.dtype, st));
             break;
         }
+        case PSERVE_MMDIT: {
+            const int F = d.ffn_mult * C;
+            for (int x = 0; x < 2; ++x) {                                         // image stream, text stream
+                StageWeights& v = x == 0 ? b->sw[s] : b->sw_txt[s];
+                const void* const* q = p + 11 * x;
+                PS_TRY(dup_param(b->pool, q[0], es * d.temb_dim * 6 * C, &v.wt, st));
+                PS_TRY(b->pool.alloc_t(&v.bt, 6 * C));
+                PS_TRY(pack_bias(q[1], v.bt, 6 * C, d.dtype, st));
+                PS_TRY(b->pool.alloc(&v.w[0], es * 3 * C * C));
+                for (int k = 0; k < 3; ++k) PS_TRY(pack_linear(q[2 + k], v.w[0], C, C, k * C, d.dtype, st));
+                PS_TRY(b->pool.alloc(&v.w[1], es * C * C));
+                PS_TRY(pack_linear(q[5], v.w[1], C, C, 0, d.dtype, st));
+                PS_TRY(b->pool.alloc_t(&v.b[1], C));
+                PS_TRY(pack_bias(q[6], v.b[1], C, d.dtype, st));
+                PS_TRY(b->pool.alloc(&v.w[3], es * F * C));
+                PS_TRY(pack_linear(q[7], v.w[3], C, F, 0, d.dtype, st));
+                PS_TRY(b->pool.alloc_t(&v.b[3], F));
+                PS_TRY(pack_bias(q[8], v.b[3], F, d.dtype, st));
+                PS_TRY(b->pool.alloc(&v.w[4], es * C * F));
+                PS_TRY(pack_linear(q[9], v.w[4], F, C, 0, d.dtype, st));
+                PS_TRY(b->pool.alloc_t(&v.b[4], C));
+                PS_TRY(pack_bias(q[10], v.b[4], C, d.dtype, st));
+            }
+            break;
+        }
         case PSERVE_AMLP: {
             const int F = d.ffn_mult * C;
             PS_TRY(b->pool.alloc(&w.w[0], es * F * C));
@@ -468,6 +498,9 @@ int pserve_cache_create(const pserve_plan_t* plan, const pserve_block_t* block, 
             PS_REQUIRE(d.stages[s] != PSERVE_RES1 && !is_res2(d.stages[s]),
                        "pserve_cache_create: patch reuse needs residual-convolution stages at position 0 only "
                        "(their input statistics and halos must be fresh on every patch)");
+    const bool joint = has_stage(d, PSERVE_MMDIT);
+    PS_REQUIRE(joint == (plan->text_len > 0), "pserve_cache_create: PSERVE_MMDIT stages need a joint plan (pserve_plan_text), other stages a plain one");
+    PS_REQUIRE(!(joint && with_slots), "pserve_cache_create: joint blocks have no cache slots");
     pserve_cache_t* c = new (std::nothrow) pserve_cache_t();
     if (!c) { set_error("pserve_cache_create: out of host memory"); return PSERVE_ENOMEM; }
     struct Guard { pserve_cache_t* p; ~Guard() { delete p; } } guard{c};
@@ -483,7 +516,7 @@ int pserve_cache_create(const pserve_plan_t* plan, const pserve_block_t* block, 
     PS_TRY(c->pool.alloc(&c->ping[1], TC));
     const bool conv = has_stage(d, PSERVE_RES1) || any_stage(d, is_res2);
     const bool sattn = any_stage(d, is_sattn), xattn = any_stage(d, is_xattn);
-    const bool ffn = any_stage(d, is_ffn) || has_stage(d, PSERVE_AMLP);
+    const bool ffn = any_stage(d, is_ffn) || has_stage(d, PSERVE_AMLP) || joint;
     const bool gn_sattn = has_stage(d, PSERVE_SATTN);
     if (conv) PS_TRY(c->pool.alloc(&c->apad, (size_t)plan->P * (plan->ph + 2) * (plan->pw + 2) * d.C * es));
     if (conv || gn_sattn) {
@@ -494,6 +527,10 @@ int pserve_cache_create(const pserve_plan_t* plan, const pserve_block_t* block, 
         if (is_res2(d.stages[s])) PS_TRY(c->pool.alloc(&c->h1[s], TC));
         if (d.stages[s] == PSERVE_RES2T) PS_TRY(c->pool.alloc_t(&c->temb_e[s], (size_t)plan->n * d.C));
         if (has_mod(d.stages[s])) PS_TRY(c->pool.alloc_t(&c->temb_e[s], (size_t)plan->n * 3 * d.C));
+        if (d.stages[s] == PSERVE_MMDIT) {
+            PS_TRY(c->pool.alloc_t(&c->temb_e[s], (size_t)plan->n * 6 * d.C));
+            PS_TRY(c->pool.alloc_t(&c->temb_e2[s], (size_t)plan->n * 6 * d.C));
+        }
         if (is_sattn(d.stages[s])) {
             if (with_slots && d.stages[s] == PSERVE_SATTN) PS_TRY(c->pool.alloc(&c->r[s], TC));
             PS_TRY(c->pool.alloc(&c->k[s], TC));
@@ -524,6 +561,18 @@ int pserve_cache_create(const pserve_plan_t* plan, const pserve_block_t* block, 
     if (with_slots) PS_TRY(c->pool.alloc(&c->yslot, TC));
     PS_TRY(c->pool.alloc_t(&c->active, (size_t)plan->P));
     PS_TRY(c->pool.alloc_t(&c->count, 1));
+    if (joint) {                                    // the two streams as patch lists
+        std::vector<int32_t> lists[2];
+        const auto& rc = plan->h_tab[PSERVE_TAB_PATCH_RC];
+        for (int p = 0; p < plan->P; ++p) lists[rc[2 * p] < 0 ? 1 : 0].push_back(p);
+        const int32_t counts[2] = {(int32_t)lists[0].size(), (int32_t)lists[1].size()};
+        PS_TRY(c->pool.alloc_t(&c->stream_count, 2));
+        PS_CHECK_HIP(hipMemcpy(c->stream_count, counts, sizeof(counts), hipMemcpyHostToDevice));
+        for (int x = 0; x < 2; ++x) {
+            PS_TRY(c->pool.alloc_t(&c->stream_list[x], lists[x].size()));
+            PS_CHECK_HIP(hipMemcpy(c->stream_list[x], lists[x].data(), sizeof(int32_t) * lists[x].size(), hipMemcpyHostToDevice));
+        }
+    }
     {
         int n_x = 0, at = -1;
         for (int k = 0; k < d.n_stages; ++k) if (is_xattn(d.stages[k])) { ++n_x; at = k; }
@@ -533,7 +582,8 @@ int pserve_cache_create(const pserve_plan_t* plan, const pserve_block_t* block, 
         // 1536 channels), not for the 5 us time-embedding projection of a 320-channel residual block.
         int64_t macs = 0;
         for (int k = 0; k < d.n_stages; ++k)
-            if (needs_temb(d.stages[k])) macs += (int64_t)plan->n * d.temb_dim * (d.stages[k] == PSERVE_RES2T ? d.C : 3 * d.C);
+            if (needs_temb(d.stages[k]))
+                macs += (int64_t)plan->n * d.temb_dim * (d.stages[k] == PSERVE_RES2T ? d.C : d.stages[k] == PSERVE_MMDIT ? 12 * d.C : 3 * d.C);
         c->side_temb = macs >= (int64_t)8 << 20;
         if (side_kv || c->side_temb) {
             PS_CHECK_HIP(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
@@ -760,25 +810,34 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
         return gemm(gk, dt, mode, s2);
     };
     // SiLU -> linear on the per-request vector of stage si: cache->temb_e[si] [n][width] in slot order
-    auto temb_proj = [&](const StageWeights& w, int si, int width, hipStream_t s2) -> int {
+    auto temb_proj = [&](const StageWeights& w, int si, int width, hipStream_t s2, float* dst = nullptr) -> int {
+        if (!dst) dst = cache->temb_e[si];
         ProfScope ps("temb_proj", s2);
         const dim3 grid(plan->n, (unsigned)cdiv(width, 64));
         const size_t lds = sizeof(float) * (d.temb_dim + TEMB_KG * 64);
         const int32_t* perm = plan->d_tab[PSERVE_TAB_PERM];
         if (dt == PSERVE_BF16)
             temb_proj_kernel<uint16_t><<<grid, 1024, lds, s2>>>((const uint16_t*)temb, (const uint16_t*)w.wt, w.bt, perm,
-                                                               d.temb_dim, width, cache->temb_e[si]);
+                                                               d.temb_dim, width, dst);
         else
             temb_proj_kernel<float><<<grid, 1024, lds, s2>>>((const float*)temb, (const float*)w.wt, w.bt, perm,
-                                                            d.temb_dim, width, cache->temb_e[si]);
+                                                            d.temb_dim, width, dst);
         return check_launch("temb_proj_kernel");
+    };
+    // all projections of stage k (one for RES2T and the adaLN sub-layers, one per stream for a joint block)
+    auto temb_stage = [&](int k, hipStream_t s2) -> int {
+        if (d.stages[k] == PSERVE_MMDIT) {
+            PS_TRY(temb_proj(block->sw[k], k, 6 * C, s2, cache->temb_e[k]));
+            return temb_proj(block->sw_txt[k], k, 6 * C, s2, cache->temb_e2[k]);
+        }
+        return temb_proj(block->sw[k], k, d.stages[k] == PSERVE_RES2T ? C : 3 * C, s2);
     };
     if (cache->side) {                              // fork: the side stream starts where this call starts
         PS_CHECK_HIP(hipEventRecord(cache->ev_fork, st));
         PS_CHECK_HIP(hipStreamWaitEvent(cache->side, cache->ev_fork, 0));
         for (int k = 0; k < d.n_stages; ++k)        // the short projections first: their consumers come early
             if (cache->side_temb && needs_temb(d.stages[k])) {
-                PS_TRY(temb_proj(block->sw[k], k, d.stages[k] == PSERVE_RES2T ? C : 3 * C, cache->side));
+                PS_TRY(temb_stage(k, cache->side));
                 PS_CHECK_HIP(hipEventRecord(cache->ev_temb[k], cache->side));
             }
         if (cache->side_stage >= 0) {
@@ -788,9 +847,9 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
     }
 
     // the projection of stage si as seen from the main stream: wait for the side stream, or run it here
-    auto temb_ready = [&](const StageWeights& w, int si, int width) -> int {
+    auto temb_ready = [&](const StageWeights&, int si, int) -> int {
         if (cache->side_temb) { PS_CHECK_HIP(hipStreamWaitEvent(st, cache->ev_temb[si], 0)); return PSERVE_OK; }
-        return temb_proj(w, si, width, st);
+        return temb_stage(si, st);
     };
 
     const void* cur = x;
@@ -812,7 +871,7 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
             break;
         case PSERVE_RES2T: {
             // the projected embedding comes from the side stream; the first convolution adds it in its epilogue
-            if (!cache->side_temb) PS_TRY(temb_proj(w, si, C, st));
+            if (!cache->side_temb) PS_TRY(temb_stage(si, st));
             PS_TRY(norm_conv(cur, w, 0, nullptr, cache->h1[si], true, cache->temb_e[si], cache->side_temb ? cache->ev_temb[si] : nullptr));
             PS_TRY(norm_conv(cache->h1[si], w, 1, cur, out, false));
             break;
@@ -859,6 +918,63 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
             if (ada) { go.rowscale = cache->temb_e[si] + 2 * C; go.rowscale_ld = 3 * C; go.row_owner = owner; }
             go.seg[0].ptr = out; go.seg[0].ld = C;
             { ProfScope ps("linear_out", st); PS_TRY(gemm(go, dt, mode, st)); }
+            break;
+        }
+        case PSERVE_MMDIT: {
+            // Two streams (image patches, text patches) with their own weights, as two patch lists over the joint
+            // token matrix; one attention per request over all its tokens.
+            const int F = d.ffn_mult * C;
+            PS_TRY(temb_ready(w, si, 6 * C));
+            void* mid = (cur == cache->ping[0] || out == cache->ping[0]) ? ((cur == cache->ping[1] || out == cache->ping[1]) ? cache->q : cache->ping[1]) : cache->ping[0];
+            const int32_t* seq_len = plan->d_tab[PSERVE_TAB_SEQ_LEN];
+            for (int xs = 0; xs < 2; ++xs) {
+                const StageWeights& v = xs == 0 ? block->sw[si] : block->sw_txt[si];
+                const float* mod = xs == 0 ? cache->temb_e[si] : cache->temb_e2[si];
+                const ActiveList ax{cache->stream_list[xs], cache->stream_count + xs};
+                { ProfScope ps("layer_norm", st);
+                  PS_TRY(layer_norm(cur, nullptr, nullptr, mod, 6 * C, owner, C, d.eps, gm, dt, cache->u, ax, st)); }
+                GemmArgs g = base_gemm(cache->u, C, C, 3 * C, v.w[0], nullptr);
+                g.act = ax; g.seg_cols = C;
+                g.seg[0].ptr = cache->q; g.seg[0].ld = C; g.seg[0].scale = qscale;
+                g.seg[1].ptr = cache->k[si]; g.seg[1].ld = C;
+                g.seg[2].ptr = cache->v[si]; g.seg[2].ld = cache->v_transposed ? T : C; g.seg[2].transposed = cache->v_transposed;
+                { ProfScope ps("linear_qkv", st); PS_TRY(gemm(g, dt, mode, st)); }
+            }
+            AttnArgs aa{};
+            aa.Q = cache->q; aa.K = cache->k[si]; aa.V = cache->v[si];
+            aa.ldv = cache->v_transposed ? T : C; aa.v_transposed = cache->v_transposed;
+            aa.O = cache->o; aa.C = C; aa.heads = d.heads; aa.d = C / d.heads; aa.geom = gm; aa.act = all;
+            aa.owner = owner; aa.cu_seqlens = plan->d_tab[PSERVE_TAB_CU_SEQLENS]; aa.seq_len = seq_len;
+            aa.perm = plan->d_tab[PSERVE_TAB_PERM];
+            aa.cross_len = 0; aa.cross_ld = 0;
+            aa.act_off = cache->act_off; aa.tile_off = cache->tile_off; aa.n = plan->n; aa.max_tiles = cache->max_tiles;
+            { ProfScope ps("attn_self", st); PS_TRY(attention(aa, dt, mode, st)); }
+            for (int xs = 0; xs < 2; ++xs) {
+                const StageWeights& v = xs == 0 ? block->sw[si] : block->sw_txt[si];
+                const float* mod = xs == 0 ? cache->temb_e[si] : cache->temb_e2[si];
+                const ActiveList ax{cache->stream_list[xs], cache->stream_count + xs};
+                GemmArgs go = base_gemm(cache->o, C, C, C, v.w[1], v.b[1]);
+                go.act = ax; go.res = cur; go.ldr = C;
+                go.rowscale = mod + 2 * C; go.rowscale_ld = 6 * C; go.row_owner = owner;
+                go.seg[0].ptr = mid; go.seg[0].ld = C;
+                { ProfScope ps("linear_out", st); PS_TRY(gemm(go, dt, mode, st)); }
+            }
+            for (int xs = 0; xs < 2; ++xs) {
+                const StageWeights& v = xs == 0 ? block->sw[si] : block->sw_txt[si];
+                const float* mod = xs == 0 ? cache->temb_e[si] : cache->temb_e2[si];
+                const ActiveList ax{cache->stream_list[xs], cache->stream_count + xs};
+                { ProfScope ps("layer_norm", st);
+                  PS_TRY(layer_norm(mid, nullptr, nullptr, mod + 3 * C, 6 * C, owner, C, d.eps, gm, dt, cache->u, ax, st)); }
+                GemmArgs g1 = base_gemm(cache->u, C, C, F, v.w[3], v.b[3]);
+                g1.act = ax; g1.act_gelu = 1;
+                g1.seg[0].ptr = cache->hidden; g1.seg[0].ld = F;
+                { ProfScope ps("mlp_in", st); PS_TRY(gemm(g1, dt, mode, st)); }
+                GemmArgs g2 = base_gemm(cache->hidden, F, F, C, v.w[4], v.b[4]);
+                g2.act = ax; g2.res = mid; g2.ldr = C;
+                g2.rowscale = mod + 5 * C; g2.rowscale_ld = 6 * C; g2.row_owner = owner;
+                g2.seg[0].ptr = out; g2.seg[0].ld = C;
+                { ProfScope ps("mlp_out", st); PS_TRY(gemm(g2, dt, mode, st)); }
+            }
             break;
         }
         case PSERVE_AMLP: {

@@ -29,7 +29,8 @@ class GpuRun:
         cfg = w.cfg
         self.w, self.cfg = w, cfg
         ph, pw = patch if patch is not None else cfg.patch
-        self.plan = ps.Plan(cfg.resolutions, ph, pw)
+        self.joint = "MMDIT" in cfg.stages                     # text tokens ride along as extra patches
+        self.plan = ps.Plan(cfg.resolutions, ph, pw, text_len=cfg.ctx_len if self.joint else 0)
         self.dtype = ps.BF16 if cfg.dtype == "bf16" else ps.F32
         self.images = [to_dev(im, cfg.dtype) for im in w.images]
         self.params = [{k: to_dev(v, cfg.dtype) for k, v in p.items()} for p in w.params]
@@ -42,6 +43,9 @@ class GpuRun:
             with_slots = w.cache is not None
         self.cache = ps.Cache(self.plan, self.block, with_slots)
         self.x = self.plan.split(self.images)
+        if self.joint:
+            self.x[np.repeat(self.plan.table("patch_rc")[:, 0] < 0, self.plan.ph * self.plan.pw)] = 0
+            self.plan.text_scatter(self.ctx, self.x)
 
     def plan_mask(self, reuse) -> torch.Tensor:
         """Per-request [gh, gw] bool grids (caller order) -> uint8 [P] in plan order."""
@@ -74,7 +78,7 @@ class GpuRun:
 
     def forward(self, reuse=None):
         mask = self.plan_mask(reuse) if reuse is not None else None
-        y = self.cache.forward(self.x, self.ctx, mask, temb=self.temb)
+        y = self.cache.forward(self.x, None if self.joint else self.ctx, mask, temb=self.temb)
         torch.cuda.synchronize()
         return y
 

@@ -119,6 +119,8 @@ LSATTN, LXATTN, LFFN = "LSATTN", "LXATTN", "LFFN"
 RES2T = "RES2T"
 # sub-layers of a diffusion-transformer block: adaptive LayerNorm modulation from the per-request vector, gated residual
 ASATTN, AMLP = "ASATTN", "AMLP"
+# a whole joint text-image block of that model (needs a joint plan: ctx_len text tokens of width C per request)
+MMDIT = "MMDIT"
 
 
 @dataclasses.dataclass
@@ -184,6 +186,9 @@ def config(cfg_id: int, seed: Optional[int] = None) -> Config:
     if cfg_id == 6:      # config 3 as a transformer layer with per-pixel LayerNorms (not a configuration of the baseline list)
         return Config(6, "sdxl-transformer-ln-c640", "bf16", _draw_res(BASE_SEED + 3 if seed is None else seed, 8, (32, 48, 64)),
                       (16, 16), 640, 32, 10, 64, (LSATTN, LXATTN, LFFN), ctx_len=77, ctx_dim=2048, seed=s)
+    if cfg_id == 9:      # a joint text-image block at the second model's width, 154 text tokens per request; not in the baseline list
+        return Config(9, "mmdit-block-c1536", "bf16", [(32, 32), (48, 48), (64, 64), (64, 64)], (16, 16),
+                      1536, 32, 24, 64, (MMDIT,), ctx_len=154, ctx_dim=1536, seed=s, temb_dim=1536)
     if cfg_id == 8:      # a diffusion-transformer block (adaLN sub-layers) at the second model's width; not in the baseline list
         return Config(8, "dit-block-c1536", "bf16", [(32, 32), (48, 48), (64, 64), (64, 64)], (16, 16),
                       1536, 32, 24, 64, (ASATTN, AMLP), seed=s, temb_dim=1536)
@@ -227,6 +232,13 @@ def stage_param_shapes(stage: str, cfg: Config) -> Dict[str, Tuple[Tuple[int, ..
     if stage == FFN:
         return {"w1": ((C, 2 * F), "w:%d" % C), "b1": ((2 * F,), "bias"),
                 "w2": ((F, C), "w:%d" % F), "b2": ((C,), "bias")}
+    if stage == MMDIT:
+        D = cfg.temb_dim
+        one = {"wm": ((D, 6 * C), "w:%d" % D), "bm": ((6 * C,), "bias"),
+               "wq": ((C, C), "w:%d" % C), "wk": ((C, C), "w:%d" % C), "wv": ((C, C), "w:%d" % C),
+               "wo": ((C, C), "w:%d" % C), "bo": ((C,), "bias"),
+               "w1": ((C, F), "w:%d" % C), "b1": ((F,), "bias"), "w2": ((F, C), "w:%d" % F), "b2": ((C,), "bias")}
+        return {X + "." + k: v for X in ("img", "txt") for k, v in one.items()}
     if stage == ASATTN:
         D = cfg.temb_dim
         return {"wm": ((D, 3 * C), "w:%d" % D), "bm": ((3 * C,), "bias"),
