@@ -294,3 +294,39 @@ def test_config5_reuse_full_size_sampled():
         assert np.array_equal(got[i][:, m], w.cache["y"][i][:, m])
     print(f"config 5: rel err {worst:.3e}")
     assert worst < 2e-2
+
+
+# ----------------------------------------------------------------------------- random stage lists
+ALL_KINDS = [wl.RES1, wl.RES2, wl.RES2T, wl.SATTN, wl.XATTN, wl.FFN, wl.LSATTN, wl.LXATTN, wl.LFFN, wl.ASATTN, wl.AMLP]
+
+
+@pytest.mark.parametrize("seed", range(32))
+def test_random_stage_lists(seed):
+    """Seeded random blocks: stage list, widths, patch and batch composition drawn at random (small sizes), with and
+    without a reuse mask where the list allows one, against the per-image oracle."""
+    rng = np.random.default_rng(9000 + seed)
+    dtype = "bf16" if seed % 2 else "f32"
+    C = int(rng.choice([32, 64, 128] if dtype == "bf16" else [16, 32, 64]))
+    heads = int(rng.choice([h for h in (1, 2, 4) if C % h == 0 and C // h <= 128]))
+    G = int(rng.choice([g for g in (1, 4, 8) if C % g == 0]))
+    ph, pw = (int(v) for v in rng.choice([2, 4, 8], 2))
+    n = int(rng.integers(1, 5))
+    res = [(ph * int(rng.integers(1, 4)), pw * int(rng.integers(1, 4))) for _ in range(n)]
+    k = int(rng.integers(1, 5))
+    stages = [str(s) for s in rng.choice(ALL_KINDS, k)]
+    reuse_ok = all(s not in (wl.RES1, wl.RES2, wl.RES2T) for s in stages[1:])
+    use_reuse = reuse_ok and bool(rng.integers(0, 2))
+    cfg = wl.custom_config(res, (ph, pw), C=C, G=G, heads=heads, stages=tuple(stages), dtype=dtype, ctx_len=int(rng.integers(1, 9)),
+                           ctx_dim=int(8 * rng.integers(1, 5)), reuse_p=0.5 if use_reuse else 0.0, seed=100 + seed,
+                           ffn_mult=int(64 // math.gcd(C, 64) * rng.integers(1, 3)), temb_dim=int(rng.integers(1, 40)))
+    w = wl.make_workload(cfg)
+    run = GpuRun(w)
+    if use_reuse:
+        run.load_cache()
+        got = run.forward_images(reuse=w.reuse)
+        ref, _ = _oracle(w, reuse=w.reuse, cache=w.cache)
+    else:
+        got = run.forward_images()
+        ref, _ = _oracle(w)
+    err = rel_err(got, ref)
+    assert err < tolerance(dtype), (stages, res, (ph, pw), C, heads, G, use_reuse, err)
