@@ -182,8 +182,12 @@ attn_mfma_kernel(AttnArgs a) {
     {                                                                                                            \
         __builtin_amdgcn_sched_barrier(0);                                                                       \
         bf16x8 fk_[4], fv_[2][2];                                                                                \
-        _Pragma("unroll") for (int ks = 0; ks < 4; ++ks)                                                         \
-            fk_[ks] = __builtin_bit_cast(bf16x8, sK[(ST) * 512 + krow[KT] * 8 + ((2 * ks + fh) ^ ksw[KT])]);     \
+        if ((KT) == 0) {                                                                                         \
+            _Pragma("unroll") for (int ks = 0; ks < 4; ++ks)                                                     \
+                fk_[ks] = __builtin_bit_cast(bf16x8, sK[(ST) * 512 + krow[0] * 8 + ((2 * ks + fh) ^ ksw[0])]);   \
+        } else {                                /* read during the first half (behind its S MFMAs) */            \
+            _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) fk_[ks] = fkn_[ks];                                 \
+        }                                                                                                        \
         /* first step: D = K Q^T + (-m_ref) written as the three-address instruction, so that the -m_ref tile is */    \
         /* read in place (the builtin form made the compiler copy it back and forth: 64 moves per key tile)      */    \
         _Pragma("unroll") for (int qt = 0; qt < 2; ++qt)                                                         \
@@ -196,6 +200,10 @@ attn_mfma_kernel(AttnArgs a) {
         _Pragma("unroll") for (int k2 = 0; k2 < 2; ++k2)                                                         \
             _Pragma("unroll") for (int dt = 0; dt < 2; ++dt)                                                     \
                 fv_[k2][dt] = __builtin_bit_cast(bf16x8, sV[(ST) * 512 + (fr + 32 * dt) * 8 + ((4 * (KT) + 2 * k2 + fh) ^ vsw[dt])]); \
+        if ((KT) == 0) {                        /* the key fragments of the second half: their LDS latency hides here */ \
+            _Pragma("unroll") for (int ks = 0; ks < 4; ++ks)                                                     \
+                fkn_[ks] = __builtin_bit_cast(bf16x8, sK[(ST) * 512 + krow[1] * 8 + ((2 * ks + fh) ^ ksw[1])]);  \
+        }                                                                                                        \
         __builtin_amdgcn_sched_barrier(0);                                                                       \
         if ((KV0) + ATT_BKV > nk) {                                                                              \
             _Pragma("unroll") for (int e = 0; e < 16; ++e) {                                                     \
@@ -226,6 +234,7 @@ attn_mfma_kernel(AttnArgs a) {
         }                                                                                                        \
     }
 
+    bf16x8 fkn_[4];                                             // key fragments of the second half tile, read ahead
     int st = 0;
     for (int t = 0; t < steps; ++t) {
         // own loads of tile t have landed (tile t+1 may be in flight); then tile t is visible to all and the stage of
