@@ -26,7 +26,9 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
-constexpr int ATT_BQ = 256;      // queries per block
+// queries per block = 4 wavefronts x 32 * QT queries.  QT = 2 (256 queries, 222 registers, two blocks per CU): half the
+// K / V^T fragment reads per MFMA, best for long sequences.  QT = 1 (128 queries, 150 registers, three blocks per CU):
+// twice the blocks, which wins when a call has too few of them to fill the chip twice (short sequences, text keys).
 constexpr int ATT_BKV = 64;      // keys per step
 constexpr int ATT_D = 64;        // head dim
 
@@ -58,8 +60,10 @@ __device__ __forceinline__ int kperm(int r) { return (r & ~12) | ((r & 4) << 1) 
 //     accumulators are rescaled and the probabilities recomputed);
 //   * the row sum is taken over the bf16-rounded probabilities, i.e. of exactly what multiplies V.
 // K / V^T tiles of 64 keys are staged by direct global->LDS loads into a ring of three stages, two tiles ahead.
-__global__ void __launch_bounds__(256, 2)
+template <int ATT_QT>
+__global__ void __launch_bounds__(256, ATT_QT == 1 ? 3 : 2)
 attn_mfma_kernel(AttnArgs a) {
+    constexpr int ATT_BQ = 4 * 32 * ATT_QT;
     extern __shared__ __attribute__((aligned(16))) uint8_t att_smem[];
     u32x4* sK = reinterpret_cast<u32x4*>(att_smem);            // [ATT_NS][64 keys][8 chunks], chunk ^ ((key>>1)&7)
     u32x4* sV = sK + ATT_NS * 512;                             // [ATT_NS][64 d][8 chunks of 8 keys], chunk ^ ((d>>1)&7)
@@ -97,12 +101,12 @@ attn_mfma_kernel(AttnArgs a) {
     const int C = a.C;
 
     // ---- query fragments: lane holds Q[q][16*ks + 8*fh .. +8] of its query column, both query sub-tiles
-    int64_t q_tok[2];
-    bool q_ok[2];
-    bf16x8 fq[2][4];
+    int64_t q_tok[ATT_QT];
+    bool q_ok[ATT_QT];
+    bf16x8 fq[ATT_QT][4];
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
-        int r = r0 + wave * 64 + qt * 32 + fr;
+    for (int qt = 0; qt < ATT_QT; ++qt) {
+        int r = r0 + wave * (32 * ATT_QT) + qt * 32 + fr;
         q_ok[qt] = r < rows_s;
         if (!q_ok[qt]) r = rows_s - 1;
         const int pi = a.act_off[s] + r / S;
@@ -136,19 +140,19 @@ attn_mfma_kernel(AttnArgs a) {
             __builtin_amdgcn_global_load_lds((const void*)(v_base + i * v_row32 + vc_), (lds_void*)(dv_ + i * 256), 16, 0, 0); \
     }
 
-    f32x16 acc_o[2][2];
+    f32x16 acc_o[ATT_QT][2];
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt)
+    for (int qt = 0; qt < ATT_QT; ++qt)
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc_o[qt][dt][e] = 0.f;
-    float m_ref[2] = {0.f, 0.f}, l_run[2] = {0.f, 0.f};   // reference maximum (log2 domain) and partial row sums
-    f32x16 cinit[2];                                       // -m_ref of the lane's query in every element
-    f32x16 acc_s[2];                                       // shifted scores of one 32-key half tile, per query sub-tile
-    bf16x8 fp[2][2];                                       // [query sub-tile][16-key step]: probabilities (B operand)
+    float m_ref[ATT_QT] = {}, l_run[ATT_QT] = {};   // reference maximum (log2 domain) and partial row sums
+    f32x16 cinit[ATT_QT];                                       // -m_ref of the lane's query in every element
+    f32x16 acc_s[ATT_QT];                                       // shifted scores of one 32-key half tile, per query sub-tile
+    bf16x8 fp[ATT_QT][2];                                       // [query sub-tile][16-key step]: probabilities (B operand)
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt)
+    for (int qt = 0; qt < ATT_QT; ++qt)
 #pragma unroll
         for (int e = 0; e < 16; ++e) cinit[qt][e] = 0.f;
 
@@ -190,11 +194,11 @@ attn_mfma_kernel(AttnArgs a) {
         }                                                                                                        \
         /* first step: D = K Q^T + (-m_ref) written as the three-address instruction, so that the -m_ref tile is */    \
         /* read in place (the builtin form made the compiler copy it back and forth: 64 moves per key tile)      */    \
-        _Pragma("unroll") for (int qt = 0; qt < 2; ++qt)                                                         \
+        _Pragma("unroll") for (int qt = 0; qt < ATT_QT; ++qt)                                                         \
             asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3"                                               \
                          : "=&v"(acc_s[qt]) : "v"(fk_[0]), "v"(fq[qt][0]), "v"(cinit[qt]));                      \
         _Pragma("unroll") for (int ks = 1; ks < 4; ++ks)                                                         \
-            _Pragma("unroll") for (int qt = 0; qt < 2; ++qt)                                                     \
+            _Pragma("unroll") for (int qt = 0; qt < ATT_QT; ++qt)                                                     \
                 acc_s[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk_[ks], fq[qt][ks], acc_s[qt], 0, 0, 0);    \
         __builtin_amdgcn_sched_barrier(0);                                                                       \
         _Pragma("unroll") for (int k2 = 0; k2 < 2; ++k2)                                                         \
@@ -208,10 +212,10 @@ attn_mfma_kernel(AttnArgs a) {
         if ((KV0) + ATT_BKV > nk) {                                                                              \
             _Pragma("unroll") for (int e = 0; e < 16; ++e) {                                                     \
                 const int key_ = (KV0) + 32 * (KT) + 16 * (e >> 3) + 8 * fh + (e & 7);                           \
-                if (key_ >= nk) { acc_s[0][e] = -INFINITY; acc_s[1][e] = -INFINITY; }                            \
+                if (key_ >= nk) { _Pragma("unroll") for (int qt = 0; qt < ATT_QT; ++qt) acc_s[qt][e] = -INFINITY; }                            \
             }                                                                                                    \
         }                                                                                                        \
-        _Pragma("unroll") for (int qt = 0; qt < 2; ++qt) {                                                       \
+        _Pragma("unroll") for (int qt = 0; qt < ATT_QT; ++qt) {                                                       \
             float sum_;                                                                                          \
             PS_PROBS(qt, 0.f);                                                                                   \
             if ((FIRST) || __any(!(sum_ <= ATT_SUM_MAX))) {                                                      \
@@ -256,7 +260,7 @@ attn_mfma_kernel(AttnArgs a) {
     // ---- O[q][head*64 + d] = O^T / l ; lane holds d = 32*dt + 8*(e/4) + 4*fh + e%4 of query fr
     uint16_t* O = (uint16_t*)a.O;
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
+    for (int qt = 0; qt < ATT_QT; ++qt) {
         const float l = l_run[qt] + other_half(l_run[qt]);
         const float inv = 1.f / l;
         if (!q_ok[qt]) continue;
@@ -274,7 +278,7 @@ attn_mfma_kernel(AttnArgs a) {
 
 // One block: per request slot, number of computed patches and of query tiles (exclusive prefixes).
 __global__ void attn_tiles_kernel(const int32_t* __restrict__ request_offset, const uint8_t* __restrict__ mask, int32_t n,
-                                  int32_t S, int32_t* __restrict__ act_off, int32_t* __restrict__ tile_off) {
+                                  int32_t S, int32_t ATT_BQ, int32_t* __restrict__ act_off, int32_t* __restrict__ tile_off) {
     __shared__ int32_t s_cnt[1024], s_til[1024];
     __shared__ int32_t c_cnt, c_til;
     const int tid = threadIdx.x;
@@ -307,22 +311,22 @@ __global__ void attn_tiles_kernel(const int32_t* __restrict__ request_offset, co
     }
 }
 
-int attention_tiles(const int32_t* request_offset, const uint8_t* mask, int32_t n, int32_t S, int32_t* act_off,
+int attention_tiles(const int32_t* request_offset, const uint8_t* mask, int32_t n, int32_t S, int32_t qt, int32_t* act_off,
                     int32_t* tile_off, hipStream_t st) {
-    attn_tiles_kernel<<<1, 1024, 0, st>>>(request_offset, mask, n, S, act_off, tile_off);
+    attn_tiles_kernel<<<1, 1024, 0, st>>>(request_offset, mask, n, S, 128 * qt, act_off, tile_off);
     return check_launch("attn_tiles_kernel");
 }
 
-int attention_max_tiles(const pserve_plan_t* plan) {
+int attention_max_tiles(const pserve_plan_t* plan, int32_t qt) {
     int64_t t = 0;
     const auto& ro = plan->h_tab[PSERVE_TAB_REQUEST_OFFSET];
-    for (int s = 0; s < plan->n; ++s) t += cdiv((int64_t)(ro[s + 1] - ro[s]) * plan->S, ATT_BQ);
+    for (int s = 0; s < plan->n; ++s) t += cdiv((int64_t)(ro[s + 1] - ro[s]) * plan->S, 128 * qt);
     return (int)t;
 }
 
 int attention_mfma_bf16(const AttnArgs& a, hipStream_t st, bool* handled) {
     *handled = false;
-    if (a.d != ATT_D || !a.v_transposed || !a.tile_off || !a.act_off) return PSERVE_OK;
+    if (a.d != ATT_D || !a.v_transposed || !a.tile_off || !a.act_off || (a.qt != 1 && a.qt != 2)) return PSERVE_OK;
     if (a.C % 8 != 0 || a.ldv % 8 != 0) return PSERVE_OK;
     if (a.cross_len) {
         if (a.cross_ld % 8 != 0) return PSERVE_OK;
@@ -335,10 +339,12 @@ int attention_mfma_bf16(const AttnArgs& a, hipStream_t st, bool* handled) {
     constexpr int lds = ATT_NS * 2 * 512 * 16;
     static bool attr_set = false;
     if (!attr_set) {
-        PS_CHECK_HIP(hipFuncSetAttribute((const void*)attn_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+        PS_CHECK_HIP(hipFuncSetAttribute((const void*)attn_mfma_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+        PS_CHECK_HIP(hipFuncSetAttribute((const void*)attn_mfma_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
         attr_set = true;
     }
-    attn_mfma_kernel<<<grid, 256, lds, st>>>(a);
+    if (a.qt == 1) attn_mfma_kernel<1><<<grid, 256, lds, st>>>(a);
+    else attn_mfma_kernel<2><<<grid, 256, lds, st>>>(a);
     return check_launch("attn_mfma_kernel");
 }
 

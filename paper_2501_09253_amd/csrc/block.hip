@@ -235,6 +235,7 @@ struct pserve_cache_s {
     int32_t* act_off = nullptr;               // [n+1] attention: computed patches before slot s
     int32_t* tile_off = nullptr;              // [n+1] attention: query tiles before slot s
     int32_t max_tiles = 0;
+    int32_t att_qt = 2;                       // query tile of the MFMA attention: 128 * att_qt rows
     bool tiles_unmasked = false;              // act_off / tile_off hold the tiling of a call without mask
     // The text key / value projection of the one cross-attention stage depends on ctx only: it runs on a stream of
     // its own (default priority) beside the stages before it, forked and joined with events.
@@ -555,7 +556,9 @@ int pserve_cache_create(const pserve_plan_t* plan, const pserve_block_t* block, 
     if (sattn || xattn) {
         PS_TRY(c->pool.alloc_t(&c->act_off, (size_t)plan->n + 1));
         PS_TRY(c->pool.alloc_t(&c->tile_off, (size_t)plan->n + 1));
-        c->max_tiles = attention_max_tiles(plan);
+        // short batches: the smaller query tile, so that there are at least two rounds of blocks
+        c->att_qt = attention_max_tiles(plan, 2) * (int64_t)d.heads < 1024 ? 1 : 2;
+        c->max_tiles = attention_max_tiles(plan, c->att_qt);
     }
     if (ffn) PS_TRY(c->pool.alloc(&c->hidden, (size_t)plan->T * d.ffn_mult * d.C * es));
     if (with_slots) PS_TRY(c->pool.alloc(&c->yslot, TC));
@@ -745,7 +748,7 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
     if (cache->act_off && (reuse_mask || !cache->tiles_unmasked)) {
         // without a mask the query tiling depends on the plan only: built once and kept
         ProfScope ps("attn_tiles", st);
-        PS_TRY(attention_tiles(request_offset, reuse_mask, plan->n, plan->S, cache->act_off, cache->tile_off, st));
+        PS_TRY(attention_tiles(request_offset, reuse_mask, plan->n, plan->S, cache->att_qt, cache->act_off, cache->tile_off, st));
         cache->tiles_unmasked = reuse_mask == nullptr;
     }
     const ActiveList all{nullptr, nullptr};
@@ -911,7 +914,7 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
             aa.O = cache->o; aa.C = C; aa.heads = d.heads; aa.d = C / d.heads; aa.geom = gm; aa.act = act;
             aa.owner = owner; aa.cu_seqlens = plan->d_tab[PSERVE_TAB_CU_SEQLENS]; aa.perm = plan->d_tab[PSERVE_TAB_PERM];
             aa.cross_len = 0; aa.cross_ld = 0;
-            aa.act_off = cache->act_off; aa.tile_off = cache->tile_off; aa.n = plan->n; aa.max_tiles = cache->max_tiles;
+            aa.act_off = cache->act_off; aa.tile_off = cache->tile_off; aa.n = plan->n; aa.max_tiles = cache->max_tiles; aa.qt = cache->att_qt;
             { ProfScope ps("attn_self", st); PS_TRY(attention(aa, dt, mode, st)); }
             GemmArgs go = base_gemm(cache->o, C, C, C, w.w[1], w.b[1]);
             go.res = rin; go.ldr = C;
@@ -947,7 +950,7 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
             aa.owner = owner; aa.cu_seqlens = plan->d_tab[PSERVE_TAB_CU_SEQLENS]; aa.seq_len = seq_len;
             aa.perm = plan->d_tab[PSERVE_TAB_PERM];
             aa.cross_len = 0; aa.cross_ld = 0;
-            aa.act_off = cache->act_off; aa.tile_off = cache->tile_off; aa.n = plan->n; aa.max_tiles = cache->max_tiles;
+            aa.act_off = cache->act_off; aa.tile_off = cache->tile_off; aa.n = plan->n; aa.max_tiles = cache->max_tiles; aa.qt = cache->att_qt;
             { ProfScope ps("attn_self", st); PS_TRY(attention(aa, dt, mode, st)); }
             for (int xs = 0; xs < 2; ++xs) {
                 const StageWeights& v = xs == 0 ? block->sw[si] : block->sw_txt[si];
@@ -1012,7 +1015,7 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
             aa.O = cache->o; aa.C = C; aa.heads = d.heads; aa.d = C / d.heads; aa.geom = gm; aa.act = act;
             aa.owner = owner; aa.cu_seqlens = plan->d_tab[PSERVE_TAB_CU_SEQLENS]; aa.perm = plan->d_tab[PSERVE_TAB_PERM];
             aa.cross_len = d.ctx_len; aa.cross_ld = cache->cross_ld;
-            aa.act_off = cache->act_off; aa.tile_off = cache->tile_off; aa.n = plan->n; aa.max_tiles = cache->max_tiles;
+            aa.act_off = cache->act_off; aa.tile_off = cache->tile_off; aa.n = plan->n; aa.max_tiles = cache->max_tiles; aa.qt = cache->att_qt;
             { ProfScope ps("attn_cross", st); PS_TRY(attention(aa, dt, mode, st)); }
             GemmArgs go = base_gemm(cache->o, C, C, C, w.w[1], w.b[1]);
             go.res = cur; go.ldr = C;

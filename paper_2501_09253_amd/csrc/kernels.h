@@ -150,10 +150,11 @@ struct AttnArgs {
     const int32_t* tile_off;   // [n+1] query tiles before slot s
     int32_t n;                 // request slots
     int32_t max_tiles;         // host upper bound of tile_off[n]
+    int32_t qt;                // 1 or 2: the tables were built for query tiles of 128 * qt rows
 };
-int attention_tiles(const int32_t* request_offset, const uint8_t* mask, int32_t n, int32_t S, int32_t* act_off,
+int attention_tiles(const int32_t* request_offset, const uint8_t* mask, int32_t n, int32_t S, int32_t qt, int32_t* act_off,
                     int32_t* tile_off, hipStream_t st);
-int attention_max_tiles(const pserve_plan_t* plan);
+int attention_max_tiles(const pserve_plan_t* plan, int32_t qt);
 int attention(const AttnArgs& a, int dtype, int mode, hipStream_t st);
 
 // ---- reuse (block.hip) -------------------------------------------------------------------------------
