@@ -849,6 +849,35 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
         }
     }
 
+    // attention of the queries in cache->q over the keys / values of stage si (self; `joint`: key count from SEQ_LEN,
+    // all patches are queries) or over the text keys / values (cross), into cache->o
+    auto run_attention = [&](int si, bool cross, bool joint) -> int {
+        AttnArgs aa{};
+        aa.Q = cache->q; aa.O = cache->o; aa.C = C; aa.heads = d.heads; aa.d = C / d.heads; aa.geom = gm;
+        aa.K = cross ? cache->kc : cache->k[si];
+        aa.V = cross ? cache->vc : cache->v[si];
+        aa.v_transposed = cache->v_transposed;
+        aa.ldv = !cache->v_transposed ? C : cross ? (int64_t)plan->n * cache->cross_ld : T;
+        aa.act = joint ? all : act;
+        aa.owner = owner; aa.perm = plan->d_tab[PSERVE_TAB_PERM];
+        aa.cu_seqlens = plan->d_tab[PSERVE_TAB_CU_SEQLENS];
+        aa.seq_len = joint ? plan->d_tab[PSERVE_TAB_SEQ_LEN] : nullptr;
+        aa.cross_len = cross ? d.ctx_len : 0; aa.cross_ld = cross ? cache->cross_ld : 0;
+        aa.act_off = cache->act_off; aa.tile_off = cache->tile_off; aa.n = plan->n; aa.max_tiles = cache->max_tiles;
+        aa.qt = cache->att_qt;
+        ProfScope ps(cross ? "attn_cross" : "attn_self", st);
+        return attention(aa, dt, mode, st);
+    };
+    // fused q / k / v projection of `in` (rows of the patches in `rows`) into cache->q (scaled), k[si], v[si]
+    auto qkv_proj = [&](const void* in, const void* wqkv, int si, ActiveList rows) -> int {
+        GemmArgs g = base_gemm(in, C, C, 3 * C, wqkv, nullptr);
+        g.act = rows; g.seg_cols = C;
+        g.seg[0].ptr = cache->q; g.seg[0].ld = C; g.seg[0].scale = qscale;
+        g.seg[1].ptr = cache->k[si]; g.seg[1].ld = C;
+        g.seg[2].ptr = cache->v[si]; g.seg[2].ld = cache->v_transposed ? T : C; g.seg[2].transposed = cache->v_transposed;
+        ProfScope ps("linear_qkv", st);
+        return gemm(g, dt, mode, st);
+    };
     // the projection of stage si as seen from the main stream: wait for the side stream, or run it here
     auto temb_ready = [&](const StageWeights&, int si, int) -> int {
         if (cache->side_temb) { PS_CHECK_HIP(hipStreamWaitEvent(st, cache->ev_temb[si], 0)); return PSERVE_OK; }
@@ -902,20 +931,8 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
                 { ProfScope ps("gn_stats", st); PS_TRY(gn_stats(ga, gm, dt, st)); }
                 { ProfScope ps("gn_apply", st); PS_TRY(gn_apply(ga, gm, dt, false, false, false, cache->u, act, st)); }
             }
-            GemmArgs g = base_gemm(cache->u, C, C, 3 * C, w.w[0], nullptr);
-            g.seg_cols = C;
-            g.seg[0].ptr = cache->q; g.seg[0].ld = C; g.seg[0].scale = qscale;
-            g.seg[1].ptr = cache->k[si]; g.seg[1].ld = C;
-            g.seg[2].ptr = cache->v[si]; g.seg[2].ld = cache->v_transposed ? T : C; g.seg[2].transposed = cache->v_transposed;
-            { ProfScope ps("linear_qkv", st); PS_TRY(gemm(g, dt, mode, st)); }
-            AttnArgs aa{};
-            aa.Q = cache->q; aa.K = cache->k[si]; aa.V = cache->v[si];
-            aa.ldv = cache->v_transposed ? T : C; aa.v_transposed = cache->v_transposed;
-            aa.O = cache->o; aa.C = C; aa.heads = d.heads; aa.d = C / d.heads; aa.geom = gm; aa.act = act;
-            aa.owner = owner; aa.cu_seqlens = plan->d_tab[PSERVE_TAB_CU_SEQLENS]; aa.perm = plan->d_tab[PSERVE_TAB_PERM];
-            aa.cross_len = 0; aa.cross_ld = 0;
-            aa.act_off = cache->act_off; aa.tile_off = cache->tile_off; aa.n = plan->n; aa.max_tiles = cache->max_tiles; aa.qt = cache->att_qt;
-            { ProfScope ps("attn_self", st); PS_TRY(attention(aa, dt, mode, st)); }
+            PS_TRY(qkv_proj(cache->u, w.w[0], si, act));
+            PS_TRY(run_attention(si, /*cross=*/false, /*joint=*/false));
             GemmArgs go = base_gemm(cache->o, C, C, C, w.w[1], w.b[1]);
             go.res = rin; go.ldr = C;
             if (ada) { go.rowscale = cache->temb_e[si] + 2 * C; go.rowscale_ld = 3 * C; go.row_owner = owner; }
@@ -929,29 +946,15 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
             const int F = d.ffn_mult * C;
             PS_TRY(temb_ready(w, si, 6 * C));
             void* mid = (cur == cache->ping[0] || out == cache->ping[0]) ? ((cur == cache->ping[1] || out == cache->ping[1]) ? cache->q : cache->ping[1]) : cache->ping[0];
-            const int32_t* seq_len = plan->d_tab[PSERVE_TAB_SEQ_LEN];
             for (int xs = 0; xs < 2; ++xs) {
                 const StageWeights& v = xs == 0 ? block->sw[si] : block->sw_txt[si];
                 const float* mod = xs == 0 ? cache->temb_e[si] : cache->temb_e2[si];
                 const ActiveList ax{cache->stream_list[xs], cache->stream_count + xs};
                 { ProfScope ps("layer_norm", st);
                   PS_TRY(layer_norm(cur, nullptr, nullptr, mod, 6 * C, owner, C, d.eps, gm, dt, cache->u, ax, st)); }
-                GemmArgs g = base_gemm(cache->u, C, C, 3 * C, v.w[0], nullptr);
-                g.act = ax; g.seg_cols = C;
-                g.seg[0].ptr = cache->q; g.seg[0].ld = C; g.seg[0].scale = qscale;
-                g.seg[1].ptr = cache->k[si]; g.seg[1].ld = C;
-                g.seg[2].ptr = cache->v[si]; g.seg[2].ld = cache->v_transposed ? T : C; g.seg[2].transposed = cache->v_transposed;
-                { ProfScope ps("linear_qkv", st); PS_TRY(gemm(g, dt, mode, st)); }
+                PS_TRY(qkv_proj(cache->u, v.w[0], si, ax));
             }
-            AttnArgs aa{};
-            aa.Q = cache->q; aa.K = cache->k[si]; aa.V = cache->v[si];
-            aa.ldv = cache->v_transposed ? T : C; aa.v_transposed = cache->v_transposed;
-            aa.O = cache->o; aa.C = C; aa.heads = d.heads; aa.d = C / d.heads; aa.geom = gm; aa.act = all;
-            aa.owner = owner; aa.cu_seqlens = plan->d_tab[PSERVE_TAB_CU_SEQLENS]; aa.seq_len = seq_len;
-            aa.perm = plan->d_tab[PSERVE_TAB_PERM];
-            aa.cross_len = 0; aa.cross_ld = 0;
-            aa.act_off = cache->act_off; aa.tile_off = cache->tile_off; aa.n = plan->n; aa.max_tiles = cache->max_tiles; aa.qt = cache->att_qt;
-            { ProfScope ps("attn_self", st); PS_TRY(attention(aa, dt, mode, st)); }
+            PS_TRY(run_attention(si, /*cross=*/false, /*joint=*/true));
             for (int xs = 0; xs < 2; ++xs) {
                 const StageWeights& v = xs == 0 ? block->sw[si] : block->sw_txt[si];
                 const float* mod = xs == 0 ? cache->temb_e[si] : cache->temb_e2[si];
@@ -1009,14 +1012,7 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
             GemmArgs gq = base_gemm(qin, C, C, C, w.w[0], nullptr);
             gq.seg[0].ptr = cache->q; gq.seg[0].ld = C; gq.seg[0].scale = qscale;
             { ProfScope ps("linear_q", st); PS_TRY(gemm(gq, dt, mode, st)); }
-            AttnArgs aa{};
-            aa.Q = cache->q; aa.K = cache->kc; aa.V = cache->vc;
-            aa.ldv = cache->v_transposed ? (int64_t)plan->n * cache->cross_ld : C; aa.v_transposed = cache->v_transposed;
-            aa.O = cache->o; aa.C = C; aa.heads = d.heads; aa.d = C / d.heads; aa.geom = gm; aa.act = act;
-            aa.owner = owner; aa.cu_seqlens = plan->d_tab[PSERVE_TAB_CU_SEQLENS]; aa.perm = plan->d_tab[PSERVE_TAB_PERM];
-            aa.cross_len = d.ctx_len; aa.cross_ld = cache->cross_ld;
-            aa.act_off = cache->act_off; aa.tile_off = cache->tile_off; aa.n = plan->n; aa.max_tiles = cache->max_tiles; aa.qt = cache->att_qt;
-            { ProfScope ps("attn_cross", st); PS_TRY(attention(aa, dt, mode, st)); }
+            PS_TRY(run_attention(si, /*cross=*/true, /*joint=*/false));
             GemmArgs go = base_gemm(cache->o, C, C, C, w.w[1], w.b[1]);
             go.res = cur; go.ldr = C;
             go.seg[0].ptr = out; go.seg[0].ld = C;
