@@ -6,13 +6,15 @@
 //                     (one barrier per step); linear layers (one tap) and the fallback form of the convolution
 //                     (nine taps re-load A).
 //   conv_mfma_kernel  3x3 convolution with the haloed activation tile kept in LDS across the nine taps;
-//                     preferred tile 256 x 160 with four wavefronts stacked along M.
+//                     preferred tile 256 x 160 with four wavefronts stacked along M, each doubled by a second
+//                     wavefront that takes the other half of every K step (two wavefronts per SIMD).
 // In both, every LDS fragment read and every global load is issued behind an MFMA (a wavefront issues in order,
-// and with one block per CU there is no other wavefront on the SIMD to fill a bubble).
+// and with one block per CU and four wavefronts there is no other wavefront on the SIMD to fill a bubble).
 // MFMA shape v_mfma_f32_32x32x16_bf16, fp32 accumulation.  LDS rows are 128 bytes (8 chunks of 16 bytes); chunk c of
 // row r sits at position c ^ ((r >> 1) & 7), which keeps the fragment reads (32 rows at one chunk position)
 // bank-conflict free; the swizzle is applied by choosing which global chunk each lane of a load fetches.
 #include "kernels.h"
+#include <type_traits>
 
 namespace pserve {
 
@@ -537,14 +539,18 @@ struct ConvTile {
 
 // Template: block tile BM x BN, WGM x WGN wavefront grid (4 wavefronts), APIX halo pixel slots per stage
 // (multiple of 32), NSB weight stages.
-template <int BM, int BN, int WGM, int WGN, int APIX, int NSB>
-__global__ void __launch_bounds__(256)
+// KS = 2: eight wavefronts, two per SIMD.  Wavefronts w and w + 4 own the same output rows and split every 64-wide
+// K step (sub-steps 0, 1 / 2, 3); the first four fetch the weights, the last four the halo; the partial sums meet in
+// LDS before the epilogue, which the first four run.
+template <int BM, int BN, int WGM, int WGN, int APIX, int NSB, int KS>
+__global__ void __launch_bounds__(256 * KS)
 conv_mfma_kernel(GemmArgs a, ConvTile ct) {
     constexpr int BK = 64, CH = 8;
     constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
     constexpr int B_LD = BN * CH / 256, A_LD = APIX * CH / 256;
     constexpr int BSTAGE = BN * CH, ASTAGE = APIX * CH;            // 16-byte slots
     static_assert(WGM * WGN == 4 && (BN * CH) % 256 == 0 && (APIX * CH) % 256 == 0 && (NSB == 2 || NSB == 3), "conv tile");
+    static_assert(KS == 1 || KS == 2, "K split");
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     u32x4* sB = reinterpret_cast<u32x4*>(smem);                    // [NSB][BSTAGE]
     u32x4* sA = sB + NSB * BSTAGE;                                 // [2][ASTAGE]
@@ -552,7 +558,9 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
     int32_t* s_seg = s_tok + BM;                                   // [nseg] padded-pixel index of each segment's halo origin
 
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // scalar: LDS destinations of the loads are SGPR math
+    const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: LDS destinations of the loads are SGPR math
+    const int wave = wave_all & 3, kg = KS == 1 ? 0 : wave_all >> 2;    // place in the wavefront grid, K group
+    const bool pro_b = kg == 0, pro_a = kg == KS - 1;            // who issues the first weight stages / the first halo
     const int wm = wave / WGN, wn = wave % WGN;
     // XCD-aware tile order: block ids are dealt round-robin to the 8 XCDs, so all N tiles of one M tile get ids of
     // the same residue mod 8 and consecutive slots: they run on one XCD back to back and share the A tile in its L2
@@ -568,7 +576,7 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
 #define PS_LOAD_B(dstB_, off_, i_) \
     __builtin_amdgcn_global_load_lds((const void*)(b_ptr + (i_) * b_row32 + (off_)), (lds_void*)((dstB_) + (i_) * 256), 16, 0, 0)
 #define PS_LOAD_A(dstA_, off_, i_) \
-    __builtin_amdgcn_global_load_lds((const void*)(a_ptr[i_] + (off_)), (lds_void*)((dstA_) + (i_) * 256), 16, 0, 0)
+    __builtin_amdgcn_global_load_lds((const void*)(A + a_pos[i_] + (off_)), (lds_void*)((dstA_) + (i_) * 256), 16, 0, 0)
 
     // The weights of the first NSB steps go first: they need no table, and the index arithmetic below runs while
     // they are in flight.  Thread rows lr + 32*i, chunk position lc; the lane fetches global chunk lc ^ f(row).
@@ -584,8 +592,10 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
     for (int t = 0; t < NSB; ++t) {
         u32x4* dB = sB + t * BSTAGE + wave * 64;
         const int64_t off = itap * b_tap_stride + ikc * BK;
+        if (pro_b) {
 #pragma unroll
-        for (int i = 0; i < B_LD; ++i) PS_LOAD_B(dB, off, i);
+            for (int i = 0; i < B_LD; ++i) PS_LOAD_B(dB, off, i);
+        }
         if (!(itap == 8 && ikc == kchunks - 1)) { if (++itap == 9) { itap = 0; ++ikc; } }
     }
 
@@ -612,7 +622,7 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
 
     // halo staging: slot sl = lr + 32*i (pixel slot), chunk position lc; lane fetches global chunk lc ^ f(slot)
     const uint16_t* A = (const uint16_t*)a.A;
-    const uint16_t* a_ptr[A_LD];
+    int32_t a_pos[A_LD];                            // element offsets (the launch checks that the padded buffer stays below 2^31)
     const int apix = ct.nseg * ct.seg_pix;
 #pragma unroll
     for (int i = 0; i < A_LD; ++i) {
@@ -620,9 +630,9 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
         if (sl >= apix) sl = 0;                                    // unused slots re-read a valid pixel
         const int g = sl / ct.seg_pix, l = sl - g * ct.seg_pix;
         const int ly = l / hw, lx = l - ly * hw;
-        a_ptr[i] = A + ((int64_t)s_seg[g] + ly * a.geom.ppw + lx) * a.lda + gc * 8;
+        a_pos[i] = (s_seg[g] + ly * a.geom.ppw + lx) * (int32_t)a.lda + gc * 8;
     }
-    {                                               // halo of chunk 0: in flight during the rest of the set-up
+    if (pro_a) {                                    // halo of chunk 0: in flight during the rest of the set-up
         u32x4* dA = sA + wave * 64;
 #pragma unroll
         for (int i = 0; i < A_LD; ++i) PS_LOAD_A(dA, 0, i);
@@ -646,120 +656,182 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
         const int ry = rr / pw, rx = rr - ry * pw;
         fa_slot[i] = g * ct.seg_pix + ry * hw + rx;
     }
-    int fb_base[TN], fb_sw[TN];
-#pragma unroll
-    for (int j = 0; j < TN; ++j) { const int r = wn * WN + j * 32 + fr; fb_base[j] = r * CH; fb_sw[j] = (r >> 1) & 7; }
+    // weight fragment j: row wn*WN + 32*j + fr; the chunk swizzle (row >> 1) & 7 is the same for every j
+    const int fb_base0 = (wn * WN + fr) * CH, fb_sw0 = ((wn * WN + fr) >> 1) & 7;
 
-    bf16x8 fa[2][TM], fb[2][TN];
+    // fragment registers: two sets, filled one sub-step ahead.  With the K split (256 registers per wavefront) the
+    // weight fragments have one set: fb[j] is refilled right behind the last MFMA of the sub-step that reads it.
+    constexpr int FBS = KS == 1 ? 2 : 1;
+    bf16x8 fa[2][TM], fb[FBS][TN];
     // one fragment read (16 bytes per lane) of K sub-step ks_ into register set dst; r_ = 0: A tile 0, 1 .. TN: B tiles,
     // TN+1 ..: the remaining A tiles (the order in which the MFMAs of a sub-step first need them)
 #define PS_READ_ONE(dst, stA_, stB_, cur_, sw_, ks_, r_)                                                          \
     {                                                                                                             \
-        const int c_ = (ks_) * 2 + fh;                                                                            \
+        const int c_ = ((ks_) + koff) * 2 + fh;                                                                   \
         const int jb_ = ((r_) >= 1 && (r_) <= TN) ? (r_) - 1 : 0;                                             \
         const int ia_ = ((r_) > TN && (r_) < TM + TN) ? (r_) - TN : 0;                                        \
         if ((r_) == 0) fa[dst][0] = __builtin_bit_cast(bf16x8, (stA_)[cur_[0] * CH + (c_ ^ sw_[0])]);             \
-        else if ((r_) <= TN) fb[dst][jb_] = __builtin_bit_cast(bf16x8, (stB_)[fb_base[jb_] + (c_ ^ fb_sw[jb_])]); \
+        else if ((r_) <= TN) fb[(dst) & (FBS - 1)][jb_] = __builtin_bit_cast(bf16x8, (stB_)[fb_base0 + jb_ * 32 * CH + (c_ ^ fb_sw0)]); \
         else if ((r_) < TM + TN) fa[dst][ia_] = __builtin_bit_cast(bf16x8, (stA_)[cur_[ia_] * CH + (c_ ^ sw_[ia_])]); \
     }
 
     constexpr int NM = TM * TN;                     // MFMAs per 16-wide sub-step
     constexpr int NR = TM + TN;                     // fragment reads per sub-step
     constexpr int R_PER = (NR + NM - 1) / NM;       // fragment reads slipped in behind one MFMA
-    constexpr int A_PER = (A_LD + 3 * NM - 1) / (3 * NM);   // halo loads slipped in per MFMA of sub-steps 0..2
+    constexpr int SUB = BK / 16 / KS;               // sub-steps of a step one wavefront computes
+    constexpr int A_PER = (A_LD + (SUB - 1) * NM - 1) / ((SUB - 1) * NM);   // halo loads slipped in per MFMA before the last sub-step
     static_assert(B_LD <= NM, "weight loads are interleaved one per MFMA");
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    int fa_cur[TM], fa_sw[TM];
+    // The loop comes in three forms, chosen per wavefront: 0 = no K split (all sub-steps, both kinds of loads),
+    // 1 = first half of every step + the weight loads, 2 = second half + the halo loads.
+    auto main_loop = [&](auto role_c) {
+        constexpr int ROLE = decltype(role_c)::value;
+        constexpr bool issue_b = ROLE != 2, issue_a = ROLE != 1;
+        constexpr int koff = ROLE == 2 ? SUB : 0;       // first sub-step of this wavefront
+        int fa_cur[TM], fa_sw[TM];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) { fa_cur[i] = fa_slot[i]; fa_sw[i] = (fa_cur[i] >> 1) & 7; }
+        for (int i = 0; i < TM; ++i) { fa_cur[i] = fa_slot[i]; fa_sw[i] = (fa_cur[i] >> 1) & 7; }
 #pragma unroll
-    for (int r = 0; r < NR; ++r) PS_READ_ONE(0, sA, sB, fa_cur, fa_sw, 0, r);
+        for (int r = 0; r < NR; ++r) PS_READ_ONE(0, sA, sB, fa_cur, fa_sw, 0, r);
 
-    // Step = (chunk kc, tap): 4 sub-steps of NM MFMAs.  Every memory instruction rides behind an MFMA: during
-    // sub-steps 0..2 the fragment reads of the next sub-step (and, in tap 0, the halo of the next chunk), during
-    // sub-step 3 the first fragments of the NEXT step and the refill of this step's weight stage.  The block barrier
-    // sits before sub-step 3: by then every wavefront has read all of this step's fragments (its stage is free) and
-    // has seen its own loads of the next step's weights land.
-    int bst = 0;                                    // weight stage of the current step
-    for (int kc = 0; kc < kchunks; ++kc) {
-        const u32x4* curA = sA + (kc & 1) * ASTAGE;
-        const int nkc_a = kc + 1 < kchunks ? kc + 1 : kc;   // halo chunk fetched during tap 0 (last: itself, never read)
-        u32x4* dA = sA + ((kc & 1) ^ 1) * ASTAGE + wave * 64;
-        const int a_off = nkc_a * BK;
+        // Step = (chunk kc, tap): 4 sub-steps of NM MFMAs.  Every memory instruction rides behind an MFMA: during
+        // sub-steps 0..2 the fragment reads of the next sub-step (and, in tap 0, the halo of the next chunk), during
+        // sub-step 3 the first fragments of the NEXT step and the refill of this step's weight stage.  The block barrier
+        // sits before sub-step 3: by then every wavefront has read all of this step's fragments (its stage is free) and
+        // has seen its own loads of the next step's weights land.
+        int bst = 0;                                    // weight stage of the current step
+        for (int kc = 0; kc < kchunks; ++kc) {
+            const u32x4* curA = sA + (kc & 1) * ASTAGE;
+            const int nkc_a = kc + 1 < kchunks ? kc + 1 : kc;   // halo chunk fetched during tap 0 (last: itself, never read)
+            u32x4* dA = sA + ((kc & 1) ^ 1) * ASTAGE + wave * 64;
+            const int a_off = nkc_a * BK;
 #pragma unroll 1
-        for (int tap = 0; tap < 9; ++tap) {
-            const u32x4* curB = sB + bst * BSTAGE;
-            const int nst = bst + 1 == NSB ? 0 : bst + 1;
-            const u32x4* nxtB = sB + nst * BSTAGE;
-            const int ntap = tap == 8 ? 0 : tap + 1;
-            const u32x4* nxtA = tap == 8 ? sA + ((kc & 1) ^ 1) * ASTAGE : curA;
-            const int nty = ntap / 3, ntx = ntap - nty * 3;
-            int nfa_cur[TM], nfa_sw[TM];
+            for (int tap = 0; tap < 9; ++tap) {
+                const u32x4* curB = sB + bst * BSTAGE;
+                const int nst = bst + 1 == NSB ? 0 : bst + 1;
+                const u32x4* nxtB = sB + nst * BSTAGE;
+                const int ntap = tap == 8 ? 0 : tap + 1;
+                const u32x4* nxtA = tap == 8 ? sA + ((kc & 1) ^ 1) * ASTAGE : curA;
+                const int nty = ntap / 3, ntx = ntap - nty * 3;
+                int nfa_cur[TM], nfa_sw[TM];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) { nfa_cur[i] = fa_slot[i] + nty * hw + ntx; nfa_sw[i] = (nfa_cur[i] >> 1) & 7; }
-            const int64_t b_off = itap * b_tap_stride + ikc * BK;
-            if (!(itap == 8 && ikc == kchunks - 1)) { if (++itap == 9) { itap = 0; ++ikc; } }
-            u32x4* dB = sB + bst * BSTAGE + wave * 64;
+                for (int i = 0; i < TM; ++i) { nfa_cur[i] = fa_slot[i] + nty * hw + ntx; nfa_sw[i] = (nfa_cur[i] >> 1) & 7; }
+                const int64_t b_off = itap * b_tap_stride + ikc * BK;
+                if (!(itap == 8 && ikc == kchunks - 1)) { if (++itap == 9) { itap = 0; ++ikc; } }
+                u32x4* dB = sB + bst * BSTAGE + wave * 64;
 #pragma unroll
-            for (int ks = 0; ks < BK / 16; ++ks) {
-                if (ks == BK / 16 - 1) {
-                    // own fragment reads of this step are complete; own loads of the next step's weights have landed.
-                    // Still allowed in flight: the NSB-2 later weight stages and a halo issued in this or a recent tap 0.
-                    // A bare s_barrier: __syncthreads() carries a fence that waits for ALL loads in flight (vmcnt(0)),
-                    // which would cut the weight ring down to one step ahead whatever its depth.
-                    if (tap < NSB - 1)
-                        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((NSB - 2) * B_LD + A_LD) : "memory");
-                    else
-                        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((NSB - 2) * B_LD) : "memory");
+                for (int ks = 0; ks < SUB; ++ks) {
+                    if (ks == SUB - 1) {
+                        // own fragment reads of this step are complete; own loads of the next step's weights have landed.
+                        // Still allowed in flight: the NSB-2 later weight stages and a halo issued in this or a recent tap 0.
+                        // A bare s_barrier: __syncthreads() carries a fence that waits for ALL loads in flight (vmcnt(0)),
+                        // which would cut the weight ring down to one step ahead whatever its depth.
+                        // With the K split a wavefront waits for the kind it fetches: weights as above, or the halo (needed
+                        // from tap 8 on, issued in tap 0).
+                        if (KS == 1 ? tap < NSB - 1 : (!issue_b && tap == 0))
+                            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((KS == 1 ? (NSB - 2) * B_LD : 0) + A_LD) : "memory");
+                        else if (KS == 1 || issue_b)
+                            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((NSB - 2) * B_LD) : "memory");
+                        else
+                            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+                    }
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j) {
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & (FBS - 1)][j], acc[i][j], 0, 0, 0);
+                            const int q = i * TN + j;
+                            if (KS == 1) {
+#pragma unroll
+                                for (int u = 0; u < R_PER; ++u) {
+                                    if (ks < SUB - 1) { PS_READ_ONE((ks + 1) & 1, curA, curB, fa_cur, fa_sw, ks + 1, q * R_PER + u); }
+                                    else { PS_READ_ONE(0, nxtA, nxtB, nfa_cur, nfa_sw, 0, q * R_PER + u); }
+                                }
+                            } else {
+                                // A fragments of the next sub-step behind the first TM MFMAs (other register set), B fragment j
+                                // behind the last MFMA that reads the current one (i == TM - 1)
+                                const int r = q < TM ? (q == 0 ? 0 : TN + q) : (i == TM - 1 ? 1 + j : NR);
+                                if (ks < SUB - 1) { PS_READ_ONE((ks + 1) & 1, curA, curB, fa_cur, fa_sw, ks + 1, r); }
+                                else { PS_READ_ONE(0, nxtA, nxtB, nfa_cur, nfa_sw, 0, r); }
+                            }
+                            if (ks == SUB - 1) {
+                                if (q < B_LD && issue_b) PS_LOAD_B(dB, b_off, q);
+                            } else {
+#pragma unroll
+                                for (int u = 0; u < A_PER; ++u) {
+                                    const int qa = (ks * NM + q) * A_PER + u;
+                                    if (qa < A_LD && tap == 0 && issue_a) PS_LOAD_A(dA, a_off, qa);
+                                }
+                            }
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
                 }
 #pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) {
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
-                        const int q = i * TN + j;
-#pragma unroll
-                        for (int u = 0; u < R_PER; ++u) {
-                            if (ks < BK / 16 - 1) { PS_READ_ONE((ks + 1) & 1, curA, curB, fa_cur, fa_sw, ks + 1, q * R_PER + u); }
-                            else { PS_READ_ONE(0, nxtA, nxtB, nfa_cur, nfa_sw, 0, q * R_PER + u); }
-                        }
-                        if (ks == BK / 16 - 1) {
-                            if (q < B_LD) PS_LOAD_B(dB, b_off, q);
-                        } else {
-#pragma unroll
-                            for (int u = 0; u < A_PER; ++u) {
-                                const int qa = (ks * NM + q) * A_PER + u;
-                                if (qa < A_LD && tap == 0) PS_LOAD_A(dA, a_off, qa);
-                            }
-                        }
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
+                for (int i = 0; i < TM; ++i) { fa_cur[i] = nfa_cur[i]; fa_sw[i] = nfa_sw[i]; }
+                bst = nst;
             }
-#pragma unroll
-            for (int i = 0; i < TM; ++i) { fa_cur[i] = nfa_cur[i]; fa_sw[i] = nfa_sw[i]; }
-            bst = nst;
         }
-    }
+    };
+    if (KS == 1) main_loop(std::integral_constant<int, 0>{});
+    else if (kg == 0) main_loop(std::integral_constant<int, 1>{});
+    else main_loop(std::integral_constant<int, 2>{});
 #undef PS_READ_ONE
 #undef PS_LOAD_A
 #undef PS_LOAD_B
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+    if (KS == 2) {
+        // the partial sums of wavefront w + 4 go to wavefront w through the drained ring, half the tile columns at a
+        // time; the first four wavefronts then run the epilogue
+        constexpr int JH = (TN + 1) / 2;
+        static_assert(KS == 1 || 4 * JH * TM * 16 * 64 * 4 <= (NSB * BSTAGE + 2 * ASTAGE) * 16, "exchange does not fit the ring");
+        f32x4* xch = reinterpret_cast<f32x4*>(smem) + wave * (JH * TM * 4 * 64) + lane;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int j0 = h * JH, j1 = h ? TN : JH;
+            if (kg == 1) {
+#pragma unroll
+                for (int j = j0; j < j1; ++j)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                            xch[(((j - j0) * TM + i) * 4 + q) * 64] = v;
+                        }
+            }
+            __syncthreads();
+            if (kg == 0) {
+#pragma unroll
+                for (int j = j0; j < j1; ++j)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const f32x4 v = xch[(((j - j0) * TM + i) * 4 + q) * 64];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) acc[i][j][4 * q + e] += v[e];
+                        }
+            }
+            __syncthreads();
+        }
+        if (kg == 1) return;
+    }
     gemm_epilogue<BM, BN, false, WGM, WGN>(a, acc, smem, s_tok, n0);
 }
 
-template <int BM, int BN, int WGM, int WGN, int APIX, int NSB>
+template <int BM, int BN, int WGM, int WGN, int APIX, int NSB, int KS = 1>
 static int launch_conv(const GemmArgs& a, const ConvTile& ct, hipStream_t st) {
     constexpr size_t lds = (size_t)(NSB * BN + 2 * APIX) * 128 + BM * sizeof(int32_t) + 64 * sizeof(int32_t);
     static_assert(lds <= 160 * 1024, "conv LDS budget");
     static bool attr_set = false;
     if (!attr_set) {
-        PS_CHECK_HIP(hipFuncSetAttribute((const void*)conv_mfma_kernel<BM, BN, WGM, WGN, APIX, NSB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        PS_CHECK_HIP(hipFuncSetAttribute((const void*)conv_mfma_kernel<BM, BN, WGM, WGN, APIX, NSB, KS>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_set = true;
     }
     const unsigned grid = (unsigned)(8 * cdiv(cdiv(a.M, BM), 8) * (a.N / BN));
-    conv_mfma_kernel<BM, BN, WGM, WGN, APIX, NSB><<<grid, 256, lds, st>>>(a, ct);
+    conv_mfma_kernel<BM, BN, WGM, WGN, APIX, NSB, KS><<<grid, 256 * KS, lds, st>>>(a, ct);
     return check_launch("conv_mfma_kernel");
 }
 
@@ -802,11 +874,14 @@ static bool mfma_eligible(const GemmArgs& a) {
 
 // Which halo-in-LDS convolution kernel a problem takes (0: none) and the columns one wavefront of it covers.
 // Preferred: 256 x 160 tiles, four wavefronts stacked along M (each 64 x 160), three weight stages: half the weight
-// bytes per MFMA of the 128 x 320 tile at the same accumulator shape.
+// bytes per MFMA of the 128 x 320 tile at the same accumulator shape.  That tile runs with the K split (eight
+// wavefronts): 66 instead of 70 us at C = 320 / 29,696 tokens, 541 instead of 576 us at C = 640 / about 79,000 tokens.
 static int conv_select(const GemmArgs& a, ConvTile* ct, int* wave_cols = nullptr) {
     int wc = 0, sel = 0;
     const bool plain3x3 = a.taps == 9 && (a.tap_w == 0 || a.tap_w == 3) && a.a_mul <= 1 && !a.a_dy && !a.a_dx && !a.o_mul;
-    if (plain3x3 && a.epi == EPI_ROUTE && a.seg_cols % 32 == 0 && a.seg_cols == a.N && !a.seg[0].transposed) {
+    // the kernels address the padded patch buffer with 32-bit element offsets
+    const bool fits32 = (int64_t)a.geom.P * a.geom.pS * a.lda < ((int64_t)1 << 31);
+    if (plain3x3 && fits32 && a.epi == EPI_ROUTE && a.seg_cols % 32 == 0 && a.seg_cols == a.N && !a.seg[0].transposed) {
         if (a.N % 160 == 0 && conv_tile(a, 256, 384, ct)) { sel = 1; wc = 160; }
         else if (conv_tile(a, 128, 256, ct)) {
             if (a.N % 320 == 0) { sel = 2; wc = 160; }
@@ -840,7 +915,7 @@ int gemm_mfma_bf16(const GemmArgs& a, hipStream_t st, bool* handled) {
     if (a.seg_cols % 32 != 0) return PSERVE_OK;      // a 32-column tile must not straddle output segments
     ConvTile ct;
     switch (conv_select(a, &ct)) {
-    case 1: *handled = true; return launch_conv<256, 160, 4, 1, 384, 3>(a, ct, st);
+    case 1: *handled = true; return launch_conv<256, 160, 4, 1, 384, 3, 2>(a, ct, st);
     case 2: *handled = true; return launch_conv<128, 320, 2, 2, 256, 2>(a, ct, st);
     case 3: *handled = true; return launch_conv<128, 256, 2, 2, 256, 2>(a, ct, st);
     case 4: *handled = true; return launch_conv<128, 128, 2, 2, 256, 2>(a, ct, st);
