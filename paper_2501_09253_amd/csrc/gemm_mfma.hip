@@ -932,9 +932,26 @@ int gemm_mfma_bf16(const GemmArgs& a, hipStream_t st, bool* handled) {
     // block's epilogue runs beside the other's main loop (measured 70 -> 62 us and 212 -> 184 us on the fused q/k/v
     // projections of configs 3 and 4; without such a segment the large tiles win)
     const bool has_t = a.seg[0].transposed || a.seg[1].transposed || a.seg[2].transposed;
-    if (has_t && a.N % 128 == 0 && m128 * (a.N / 128) >= 512) return launch<128, 128, false, 2, 2, 2, false>(a, st);
-    if (a.N % 160 == 0 && m256 * (a.N / 160) >= 160) return launch<256, 160, false, 4, 1, 2, true>(a, st);
-    if (a.N % 128 == 0 && m256 * (a.N / 128) >= 160) return launch<256, 128, false, 4, 1, 2, true>(a, st);
+    const int64_t tiles128 = a.N % 128 == 0 ? m128 * (a.N / 128) : 0;
+    if (has_t && tiles128 >= 512) return launch<128, 128, false, 2, 2, 2, false>(a, st);
+    // Tile-count quantisation decides between the 256-row tiles (one block per CU: a started round of 256 tiles costs a
+    // whole round) and 128 x 128 with two blocks per CU (512 per round; a last round that is at most half full leaves
+    // one block per CU, which runs faster alone: about 0.65 of a round).  A full round of either does the same work
+    // in about the same time (measured at K = 1536 and 6144), so the cost is rounds x outputs per CU and round.
+    int bn_a = 0;
+    if (a.N % 160 == 0 && m256 * (a.N / 160) >= 160) bn_a = 160;
+    else if (a.N % 128 == 0 && m256 * (a.N / 128) >= 160) bn_a = 128;
+    if (bn_a) {
+        const int64_t tiles_a = m256 * (a.N / bn_a);
+        if (tiles128 >= 512) {
+            const double cost_a = (double)cdiv(tiles_a, 256) * 256 * bn_a;
+            const int64_t full = tiles128 / 512, rest = tiles128 % 512;
+            const double cost_b = ((double)full + (rest == 0 ? 0.0 : (rest <= 256 ? 0.65 : 1.0))) * 2 * 128 * 128;
+            if (cost_b < cost_a) return launch<128, 128, false, 2, 2, 2, false>(a, st);
+        }
+        if (bn_a == 160) return launch<256, 160, false, 4, 1, 2, true>(a, st);
+        return launch<256, 128, false, 4, 1, 2, true>(a, st);
+    }
     const bool small = a.N % 64 == 0 && m128 * cdiv(a.N, 320) < 128;
     if (!small) {
         if (a.N % 320 == 0) return launch<128, 320, false, 2, 2, 2, true>(a, st);
