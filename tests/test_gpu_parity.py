@@ -211,6 +211,22 @@ def test_reuse_small(stages, dtype):
             assert np.array_equal(per_image[i][:, m], w.cache[name][i][:, m]), name
 
 
+def test_reuse_mfma_convolution():
+    """Reuse mask on the bf16 residual block at a width and patch shape that take the halo-in-LDS convolution with
+    256-row tiles (active-patch list in the tile's row table, ragged last tile)."""
+    cfg = wl.custom_config([(32, 32), (16, 48), (16, 16)], (16, 16), C=320, G=32, heads=5, stages=(wl.RES2,), dtype="bf16",
+                           reuse_p=0.4, seed=23)
+    w = wl.make_workload(cfg)
+    run = GpuRun(w)
+    run.load_cache()
+    got = run.forward_images(reuse=w.reuse)
+    ref, _ = _oracle(w, reuse=w.reuse, cache=w.cache)
+    assert rel_err(got, ref) < 2e-2
+    for i in range(cfg.n):
+        m = np.kron(w.reuse[i], np.ones(cfg.patch)).astype(bool)
+        assert np.array_equal(got[i][:, m], w.cache["y"][i][:, m])
+
+
 def test_reuse_all_none_and_two_calls():
     cfg = wl.custom_config([(8, 8), (16, 8)], (4, 4), C=32, G=4, heads=2, stages=(wl.RES2, wl.SATTN), reuse_p=0.5, seed=8)
     w = wl.make_workload(cfg)
