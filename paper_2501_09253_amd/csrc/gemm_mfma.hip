@@ -910,6 +910,10 @@ int gemm_mfma_bf16(const GemmArgs& a, hipStream_t st, bool* handled) {
     if (a.epi == EPI_GEGLU) {
         if (a.N % 128 != 0) return PSERVE_OK;
         *handled = true;
+        // The epilogue (GELU of every gate) is as long as the main loop at K = 640: with at least a round of 128-row
+        // tiles, two blocks per CU, one block's epilogue runs beside the other's main loop (163 -> 142 us at
+        // 13,312 x 5,120 x 640); the wavefront tile is then 32 x 128 = [64 values | 64 gates]
+        if (cdiv(a.M, 128) * (a.N / 128) >= 512) return launch<128, 128, true, 4, 1, 2, false>(a, st);
         return launch<256, 128, true, 4, 1, 2, true>(a, st);
     }
     if (a.seg_cols % 32 != 0) return PSERVE_OK;      // a 32-column tile must not straddle output segments
