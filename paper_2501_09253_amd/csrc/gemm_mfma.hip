@@ -926,17 +926,20 @@ int gemm_mfma_bf16(const GemmArgs& a, hipStream_t st, bool* handled) {
     case 5: *handled = true; return launch_conv<128, 64, 2, 2, 256, 2>(a, ct, st);
     default: break;
     }
-    // Tile choice.  Preferred: 256 rows, four wavefronts stacked along M (each 64 x 160 or 64 x 128), two stages and
-    // the next tile's first loads issued before the epilogue.
-    // With fewer blocks than that leaves busy CUs, 128-row tiles; with few rows altogether (the text-token
-    // projections) the narrowest tile, two blocks per CU.
+    // Tile choice.  Two blocks of 128 rows per CU where they fit (one block's prologue and epilogue run beside the
+    // other's main loop), 256-row tiles with one block per CU (two stages, the next tile's first loads issued before
+    // the epilogue) where the rounds of tiles come out better, and for few rows altogether (the text-token
+    // projections) the narrowest tile.
     const int64_t m256 = cdiv(a.M, 256), m128 = cdiv(a.M, 128);
     *handled = true;
-    // A transposed output segment (V^T) makes the epilogue long (8-byte stores): two smaller blocks per CU, so that one
-    // block's epilogue runs beside the other's main loop (measured 70 -> 62 us and 212 -> 184 us on the fused q/k/v
-    // projections of configs 3 and 4; without such a segment the large tiles win)
     const bool has_t = a.seg[0].transposed || a.seg[1].transposed || a.seg[2].transposed;
+    // N a multiple of 160: 128 x 160 tiles, two blocks per CU (wavefront tile 32 x 160).  Against the 256 x 160 tile
+    // the rounds are the same: 34 -> 28 us (13,312 x 640 x 640), 68 -> 63 us (K = 2560), 80 -> 72 us
+    // (13.4 k x 1280 x 1280), 165 -> 137 us (79 k x 640 x 640).  The fused q/k/v projections (N = 1920, 3840, with the
+    // transposed V^T segment and its long epilogue of 8-byte stores) gain 6-11 % over 128 x 128 tiles as well.
+    if (a.N % 160 == 0 && m128 * (a.N / 160) >= 256) return launch<128, 160, false, 4, 1, 2, false>(a, st);
     const int64_t tiles128 = a.N % 128 == 0 ? m128 * (a.N / 128) : 0;
+    // a transposed segment otherwise: 128 x 128, two blocks per CU (70 -> 62 us and 212 -> 184 us against 256-row tiles)
     if (has_t && tiles128 >= 512) return launch<128, 128, false, 2, 2, 2, false>(a, st);
     // Tile-count quantisation decides between the 256-row tiles (one block per CU: a started round of 256 tiles costs a
     // whole round) and 128 x 128 with two blocks per CU (512 per round; a last round that is at most half full leaves
