@@ -106,6 +106,84 @@ temb_proj_kernel(const T* __restrict__ temb, const T* __restrict__ wt, const flo
     }
 }
 
+// The same for wide outputs (adaLN modulation: three or six rows of C per request): one block per (pair of request
+// slots, 2 * LPR channels); LPR lanes x two adjacent channels (4-byte loads of bf16 pairs) cover the channels, the
+// 1024 / LPR thread groups take every (1024 / LPR)-th k.  The weights are read once per pair of slots, and the launch
+// picks LPR = 32 or 64 so that the grid is close to one block per CU (the one-slot form ran more than a round of
+// 1,024-thread blocks: 24 -> 15 us at 4 x 4,608 x 1536, 29 -> 18 us at 4 x 9,216 x 1536).
+template <typename T, int LPR>
+__global__ void __launch_bounds__(1024)
+temb_proj_wide_kernel(const T* __restrict__ temb, const T* __restrict__ wt, const float* __restrict__ bt,
+                      const int32_t* __restrict__ perm, int32_t n, int32_t D, int32_t C, float* __restrict__ e) {
+    constexpr int TEMB_WKG = 1024 / LPR, CPB = 2 * LPR;     // k groups, channels per block
+    extern __shared__ float s_t[];                  // [2][D] SiLU(temb) of the two slots, then [TEMB_WKG][2][CPB] partial sums
+    float* s_part = s_t + 2 * D;
+    const int s0 = 2 * blockIdx.x, s1 = min(s0 + 1, n - 1);
+    auto as_f = [](T v) -> float {
+        if constexpr (sizeof(T) == 2) return __uint_as_float((uint32_t)v << 16);
+        else return v;
+    };
+    for (int k = threadIdx.x; k < 2 * D; k += blockDim.x) {
+        const int which = k >= D, kk = k - which * D;
+        const float v = as_f(temb[(int64_t)perm[which ? s1 : s0] * D + kk]);
+        s_t[k] = v / (1.f + __expf(-v));
+    }
+    __syncthreads();
+    const int cl = threadIdx.x % LPR, kg = threadIdx.x / LPR;
+    const int c = min(blockIdx.y * CPB + 2 * cl, C - 2);       // C is even (checked by the launch)
+    float acc[2][2] = {};
+    auto ld2 = [&](int k, float (&w)[2]) {
+        if constexpr (sizeof(T) == 2) {
+            const uint32_t r = *reinterpret_cast<const uint32_t*>(wt + (int64_t)k * C + c);
+            w[0] = __uint_as_float(r << 16);
+            w[1] = __uint_as_float(r & 0xFFFF0000u);
+        } else {
+            const float2 r = *reinterpret_cast<const float2*>(wt + (int64_t)k * C + c);
+            w[0] = r.x;
+            w[1] = r.y;
+        }
+    };
+    int k = kg;
+    for (; k + 7 * TEMB_WKG < D; k += 8 * TEMB_WKG) {
+        float w[8][2];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) ld2(k + u * TEMB_WKG, w[u]);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float t0 = s_t[k + u * TEMB_WKG], t1 = s_t[D + k + u * TEMB_WKG];
+            acc[0][0] = fmaf(t0, w[u][0], acc[0][0]);
+            acc[0][1] = fmaf(t0, w[u][1], acc[0][1]);
+            acc[1][0] = fmaf(t1, w[u][0], acc[1][0]);
+            acc[1][1] = fmaf(t1, w[u][1], acc[1][1]);
+        }
+    }
+    for (; k < D; k += TEMB_WKG) {
+        float w[2];
+        ld2(k, w);
+        const float t0 = s_t[k], t1 = s_t[D + k];
+        acc[0][0] = fmaf(t0, w[0], acc[0][0]);
+        acc[0][1] = fmaf(t0, w[1], acc[0][1]);
+        acc[1][0] = fmaf(t1, w[0], acc[1][0]);
+        acc[1][1] = fmaf(t1, w[1], acc[1][1]);
+    }
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) s_part[(kg * 2 + q) * CPB + 2 * cl + h] = acc[q][h];
+    __syncthreads();
+    // thread (q, channel): the partial sums of the k groups in a fixed order
+    if (threadIdx.x < 2 * CPB) {
+        const int q = threadIdx.x / CPB, ch = threadIdx.x % CPB;
+        const int cc = blockIdx.y * CPB + ch;
+        const int s = q ? s0 + 1 : s0;
+        if (cc < C && s < n) {
+            float sum = bt[cc];
+            for (int g = 0; g < TEMB_WKG; ++g) sum += s_part[(g * 2 + q) * CPB + ch];
+            e[(int64_t)s * C + cc] = sum;
+        }
+    }
+}
+
 // Ordered compaction of the patches with mask == 0.
 __global__ void compact_mask_kernel(const uint8_t* __restrict__ mask, int32_t P, int32_t* __restrict__ active,
                                     int32_t* __restrict__ count) {
@@ -816,9 +894,23 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
     auto temb_proj = [&](const StageWeights& w, int si, int width, hipStream_t s2, float* dst = nullptr) -> int {
         if (!dst) dst = cache->temb_e[si];
         ProfScope ps("temb_proj", s2);
+        const int32_t* perm = plan->d_tab[PSERVE_TAB_PERM];
+        if (plan->n >= 2 && width >= 2048 && width % 2 == 0) {      // wide: pairs of slots
+            const int64_t pairs = cdiv(plan->n, 2);
+            const int cpb = pairs * cdiv(width, 64) <= 256 ? 64 : 128;    // channels per block: at most ~one block per CU
+            const dim3 wgrid((unsigned)pairs, (unsigned)cdiv(width, cpb));
+            const size_t wlds = sizeof(float) * (2 * d.temb_dim + 2 * 1024 * 2);     // SiLU(temb) x 2, partial sums
+            if (wlds <= 64 * 1024) {
+#define PS_TW(TT, LPR_) temb_proj_wide_kernel<TT, LPR_><<<wgrid, 1024, wlds, s2>>>((const TT*)temb, (const TT*)w.wt, w.bt, perm, \
+                                                                                 plan->n, d.temb_dim, width, dst)
+                if (dt == PSERVE_BF16) { if (cpb == 64) PS_TW(uint16_t, 32); else PS_TW(uint16_t, 64); }
+                else { if (cpb == 64) PS_TW(float, 32); else PS_TW(float, 64); }
+#undef PS_TW
+                return check_launch("temb_proj_wide_kernel");
+            }
+        }
         const dim3 grid(plan->n, (unsigned)cdiv(width, 64));
         const size_t lds = sizeof(float) * (d.temb_dim + TEMB_KG * 64);
-        const int32_t* perm = plan->d_tab[PSERVE_TAB_PERM];
         if (dt == PSERVE_BF16)
             temb_proj_kernel<uint16_t><<<grid, 1024, lds, s2>>>((const uint16_t*)temb, (const uint16_t*)w.wt, w.bt, perm,
                                                                d.temb_dim, width, dst);

@@ -184,6 +184,17 @@ def test_layer_norm_widths(dtype, C):
     assert rel_err(got, ref) < tolerance(dtype)
 
 
+def test_wide_modulation_projection():
+    """adaLN sub-layers whose modulation rows (3 C = 2,112 values per request) take the wide form of the time-embedding
+    projection; three requests, so the last pair of request slots is half empty."""
+    cfg = wl.custom_config([(8, 8), (16, 8), (8, 16)], (8, 8), C=704, G=32, heads=11, stages=(wl.ASATTN, wl.AMLP),
+                           dtype="bf16", seed=41, temb_dim=200)
+    w = wl.make_workload(cfg)
+    got = GpuRun(w).forward_images()
+    ref, _ = _oracle(w)
+    assert rel_err(got, ref) < 2e-2
+
+
 # ----------------------------------------------------------------------------- reuse
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("stages", [(wl.RES2, wl.SATTN), (wl.SATTN,), (wl.RES2,), (wl.SATTN, wl.XATTN, wl.FFN),
