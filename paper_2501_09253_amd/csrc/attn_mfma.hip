@@ -124,20 +124,39 @@ attn_mfma_kernel(AttnArgs a) {
     const uint16_t* v_base = V + (int64_t)(head * ATT_D + lr) * a.ldv + k0;
     const int64_t v_row32 = (int64_t)32 * a.ldv;
     const int steps = (nk + ATT_BKV - 1) / ATT_BKV;
+    // A tile that lies inside the sequence is addressed as (uniform base of the tile) + (32-bit byte offset of the lane,
+    // the same for every tile), so that its four loads cost no vector arithmetic (a 64-bit multiply per load before:
+    // ~30 vector instructions per tile, two of them quarter-rate).  The launch checks that the offsets fit 32 bits.
+    const uint8_t* k_uni = reinterpret_cast<const uint8_t*>(K + k0 * C + head * ATT_D);
+    const uint8_t* v_uni = reinterpret_cast<const uint8_t*>(V + (int64_t)(head * ATT_D) * a.ldv + k0);
+    uint32_t k_lane[2], v_lane[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        k_lane[i] = (uint32_t)(((lr + 32 * i) * C + gc * 8) * 2);
+        v_lane[i] = (uint32_t)(((int64_t)(lr + 32 * i) * a.ldv + gc * 8) * 2);
+    }
     // keys / chunks past the image are clamped to valid ones: their scores are masked, their P is zero
 #define PS_ISSUE_TILE(t_, st_)                                                                                   \
     {                                                                                                            \
-        const int tt_ = (t_) < steps ? (t_) : steps - 1;                                                         \
-        const int kv_ = tt_ * ATT_BKV;                                                                           \
         u32x4* dk_ = sK + (st_) * 512 + wave * 64;                                                               \
         u32x4* dv_ = sV + (st_) * 512 + wave * 64;                                                               \
-        _Pragma("unroll") for (int i = 0; i < 2; ++i) {                                                          \
-            const int key_ = min(kv_ + lr + 32 * i, nk - 1);                                                     \
-            __builtin_amdgcn_global_load_lds((const void*)(k_base + (int64_t)key_ * C), (lds_void*)(dk_ + i * 256), 16, 0, 0); \
+        if ((t_) < steps - 1) {                                                                                  \
+            const uint8_t* kt_ = k_uni + (int64_t)(t_) * (ATT_BKV * 2) * C;                                      \
+            const uint8_t* vt_ = v_uni + (int64_t)(t_) * (ATT_BKV * 2);                                          \
+            _Pragma("unroll") for (int i = 0; i < 2; ++i)                                                        \
+                __builtin_amdgcn_global_load_lds((const void*)(kt_ + k_lane[i]), (lds_void*)(dk_ + i * 256), 16, 0, 0); \
+            _Pragma("unroll") for (int i = 0; i < 2; ++i)                                                        \
+                __builtin_amdgcn_global_load_lds((const void*)(vt_ + v_lane[i]), (lds_void*)(dv_ + i * 256), 16, 0, 0); \
+        } else {                                                                                                 \
+            const int kv_ = (steps - 1) * ATT_BKV;                                                               \
+            _Pragma("unroll") for (int i = 0; i < 2; ++i) {                                                      \
+                const int key_ = min(kv_ + lr + 32 * i, nk - 1);                                                 \
+                __builtin_amdgcn_global_load_lds((const void*)(k_base + (int64_t)key_ * C), (lds_void*)(dk_ + i * 256), 16, 0, 0); \
+            }                                                                                                    \
+            const int vc_ = kv_ + gc * 8 < nk ? kv_ + gc * 8 : 0;                                                \
+            _Pragma("unroll") for (int i = 0; i < 2; ++i)                                                        \
+                __builtin_amdgcn_global_load_lds((const void*)(v_base + i * v_row32 + vc_), (lds_void*)(dv_ + i * 256), 16, 0, 0); \
         }                                                                                                        \
-        const int vc_ = kv_ + gc * 8 < nk ? kv_ + gc * 8 : 0;                                                    \
-        _Pragma("unroll") for (int i = 0; i < 2; ++i)                                                            \
-            __builtin_amdgcn_global_load_lds((const void*)(v_base + i * v_row32 + vc_), (lds_void*)(dv_ + i * 256), 16, 0, 0); \
     }
 
     f32x16 acc_o[ATT_QT][2];
@@ -328,6 +347,7 @@ int attention_mfma_bf16(const AttnArgs& a, hipStream_t st, bool* handled) {
     *handled = false;
     if (a.d != ATT_D || !a.v_transposed || !a.tile_off || !a.act_off || (a.qt != 1 && a.qt != 2)) return PSERVE_OK;
     if (a.C % 8 != 0 || a.ldv % 8 != 0) return PSERVE_OK;
+    if ((int64_t)64 * a.ldv * 2 + 128 >= ((int64_t)1 << 32) || (int64_t)64 * a.C * 2 + 128 >= ((int64_t)1 << 32)) return PSERVE_OK;
     if (a.cross_len) {
         if (a.cross_ld % 8 != 0) return PSERVE_OK;
     } else if (a.geom.S % 8 != 0) {
