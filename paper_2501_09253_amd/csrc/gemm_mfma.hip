@@ -1,10 +1,10 @@
 // bf16 MFMA GEMM / implicit-GEMM 3x3 convolution for gfx950.
 //
 // Two kernels share one epilogue:
-//   gemm_mfma_kernel  block tile 256 x 160 / 256 x 128 (four wavefronts stacked along M) or 128 x BN (2 x 2), K in
-//                     steps of 64, A and B tiles staged by direct global -> LDS loads into a ring of 2-4 stages
-//                     (one barrier per step); linear layers (one tap) and the fallback form of the convolution
-//                     (nine taps re-load A).
+//   gemm_mfma_kernel  block tile 256 x 160 / 256 x 128 / 128 x 160 (four wavefronts stacked along M) or 128 x BN
+//                     (2 x 2), K in steps of 64, A and B tiles staged by direct global -> LDS loads into a ring of
+//                     2-4 stages (one barrier per step); linear layers (one tap) and the fallback form of the
+//                     convolution (nine taps re-load A).  The 128-row tiles with two stages run two blocks per CU.
 //   conv_mfma_kernel  3x3 convolution with the haloed activation tile kept in LDS across the nine taps;
 //                     preferred tile 256 x 160 with four wavefronts stacked along M, each doubled by a second
 //                     wavefront that takes the other half of every K step (two wavefronts per SIMD).
