@@ -80,3 +80,12 @@ def test_resample_argument_validation():
     assert L.pserve_resample_create(3, 8, 8, 1, None, None, None, C.byref(out)) == -1       # unknown kind
     assert L.pserve_resample_create(1, 8, 8, 1, None, None, None, C.byref(out)) == -1       # NULL parameters
     assert L.pserve_resample_forward(None, None, None, None, None, 0, None, None) == -1
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is a one-GPU program: any other count ends with a message and a non-zero status before touching a GPU."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=60)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
