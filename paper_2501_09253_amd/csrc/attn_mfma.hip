@@ -283,14 +283,25 @@ attn_mfma_kernel(AttnArgs a) {
         const float l = l_run[qt] + other_half(l_run[qt]);
         const float inv = 1.f / l;
         if (!q_ok[qt]) continue;
-        uint16_t* op = O + q_tok[qt] * C + head * ATT_D + 4 * fh;
+        // A lane holds four consecutive d (8 bytes) of its query per (dt, eg), lane ^ 32 the next four.  The two halves
+        // trade them so that the lower half owns the even eg chunks and the upper half the odd ones: 16-byte stores,
+        // two adjacent chunks of a row per instruction (half the stores of the 8-byte form).
+        uint16_t* op = O + q_tok[qt] * C + head * ATT_D + 8 * fh;
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
-            for (int eg = 0; eg < 4; ++eg) {
-                const uint32_t w0 = pack_bf16x2(acc_o[qt][dt][4 * eg] * inv, acc_o[qt][dt][4 * eg + 1] * inv);
-                const uint32_t w1 = pack_bf16x2(acc_o[qt][dt][4 * eg + 2] * inv, acc_o[qt][dt][4 * eg + 3] * inv);
-                *reinterpret_cast<u32x2*>(op + dt * 32 + eg * 8) = u32x2{w0, w1};
+            for (int eg = 0; eg < 4; eg += 2) {
+                uint32_t w[2][2];               // [eg parity][dword]
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    w[q][0] = pack_bf16x2(acc_o[qt][dt][4 * (eg + q)] * inv, acc_o[qt][dt][4 * (eg + q) + 1] * inv);
+                    w[q][1] = pack_bf16x2(acc_o[qt][dt][4 * (eg + q) + 2] * inv, acc_o[qt][dt][4 * (eg + q) + 3] * inv);
+                }
+                // swap(x = even chunk, y = odd chunk): r[0] = {lower: own even, upper: the lower half's odd},
+                // r[1] = {lower: the upper half's even, upper: own odd}
+                const auto r0 = __builtin_amdgcn_permlane32_swap(w[0][0], w[1][0], false, false);
+                const auto r1 = __builtin_amdgcn_permlane32_swap(w[0][1], w[1][1], false, false);
+                *reinterpret_cast<u32x4*>(op + dt * 32 + eg * 8) = u32x4{r0[0], r1[0], r0[1], r1[1]};
             }
     }
 }
