@@ -320,6 +320,7 @@ struct pserve_cache_s {
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     hipEvent_t ev_temb[PSERVE_MAX_STAGES] = {};   // projection of the per-request vector of stage s is done (side stream)
+    hipEvent_t ev_txt[4] = {};                    // joint block: fork / join of the text stream's kernels (side stream)
     bool side_temb = false;                       // the projections run on the side stream (else inline, at their stage)
     int side_stage = -1;
     DevicePool pool;
@@ -327,6 +328,7 @@ struct pserve_cache_s {
         if (ev_fork) (void)hipEventDestroy(ev_fork);
         if (ev_join) (void)hipEventDestroy(ev_join);
         for (hipEvent_t e : ev_temb) if (e) (void)hipEventDestroy(e);
+        for (hipEvent_t e : ev_txt) if (e) (void)hipEventDestroy(e);
         if (side) (void)hipStreamDestroy(side);
     }
 };
@@ -666,8 +668,12 @@ int pserve_cache_create(const pserve_plan_t* plan, const pserve_block_t* block, 
             if (needs_temb(d.stages[k]))
                 macs += (int64_t)plan->n * d.temb_dim * (d.stages[k] == PSERVE_RES2T ? d.C : d.stages[k] == PSERVE_MMDIT ? 12 * d.C : 3 * d.C);
         c->side_temb = macs >= (int64_t)8 << 20;
-        if (side_kv || c->side_temb) {
+        // A joint block runs the text stream's kernels (5 % of the rows, few tiles each: latency bound) on the side stream,
+        // beside the image stream's (config 9: the text kernels alone were 19 % of the block).
+        if (side_kv || c->side_temb || joint) {
             PS_CHECK_HIP(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
+            if (joint)
+                for (hipEvent_t& e : c->ev_txt) PS_CHECK_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
             PS_CHECK_HIP(hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
             PS_CHECK_HIP(hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming));
             for (int k = 0; k < d.n_stages; ++k)
@@ -961,14 +967,15 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
         return attention(aa, dt, mode, st);
     };
     // fused q / k / v projection of `in` (rows of the patches in `rows`) into cache->q (scaled), k[si], v[si]
-    auto qkv_proj = [&](const void* in, const void* wqkv, int si, ActiveList rows) -> int {
+    auto qkv_proj = [&](const void* in, const void* wqkv, int si, ActiveList rows, hipStream_t sq = nullptr) -> int {
+        if (!sq) sq = st;
         GemmArgs g = base_gemm(in, C, C, 3 * C, wqkv, nullptr);
         g.act = rows; g.seg_cols = C;
         g.seg[0].ptr = cache->q; g.seg[0].ld = C; g.seg[0].scale = qscale;
         g.seg[1].ptr = cache->k[si]; g.seg[1].ld = C;
         g.seg[2].ptr = cache->v[si]; g.seg[2].ld = cache->v_transposed ? T : C; g.seg[2].transposed = cache->v_transposed;
-        ProfScope ps("linear_qkv", st);
-        return gemm(g, dt, mode, st);
+        ProfScope ps("linear_qkv", sq);
+        return gemm(g, dt, mode, sq);
     };
     // the projection of stage si as seen from the main stream: wait for the side stream, or run it here
     auto temb_ready = [&](const StageWeights&, int si, int) -> int {
@@ -1038,41 +1045,56 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
             const int F = d.ffn_mult * C;
             PS_TRY(temb_ready(w, si, 6 * C));
             void* mid = (cur == cache->ping[0] || out == cache->ping[0]) ? ((cur == cache->ping[1] || out == cache->ping[1]) ? cache->q : cache->ping[1]) : cache->ping[0];
+            // The text stream's kernels go to the side stream: they touch the rows of the text patches only (every
+            // buffer is shared row-wise), so the two streams meet at the attention and at the end of the stage.
+            hipStream_t sx[2] = {st, cache->side ? cache->side : st};
+            auto fork_txt = [&](int e) -> int {           // the side stream continues from this point of the main one
+                if (sx[1] == st) return PSERVE_OK;
+                PS_CHECK_HIP(hipEventRecord(cache->ev_txt[e], st));
+                PS_CHECK_HIP(hipStreamWaitEvent(sx[1], cache->ev_txt[e], 0));
+                return PSERVE_OK;
+            };
+            auto join_txt = [&](int e) -> int {           // the main stream waits for what the side stream has queued
+                if (sx[1] == st) return PSERVE_OK;
+                PS_CHECK_HIP(hipEventRecord(cache->ev_txt[e], sx[1]));
+                PS_CHECK_HIP(hipStreamWaitEvent(st, cache->ev_txt[e], 0));
+                return PSERVE_OK;
+            };
+            PS_TRY(fork_txt(0));
             for (int xs = 0; xs < 2; ++xs) {
                 const StageWeights& v = xs == 0 ? block->sw[si] : block->sw_txt[si];
                 const float* mod = xs == 0 ? cache->temb_e[si] : cache->temb_e2[si];
                 const ActiveList ax{cache->stream_list[xs], cache->stream_count + xs};
-                { ProfScope ps("layer_norm", st);
-                  PS_TRY(layer_norm(cur, nullptr, nullptr, mod, 6 * C, owner, C, d.eps, gm, dt, cache->u, ax, st)); }
-                PS_TRY(qkv_proj(cache->u, v.w[0], si, ax));
+                { ProfScope ps("layer_norm", sx[xs]);
+                  PS_TRY(layer_norm(cur, nullptr, nullptr, mod, 6 * C, owner, C, d.eps, gm, dt, cache->u, ax, sx[xs])); }
+                PS_TRY(qkv_proj(cache->u, v.w[0], si, ax, sx[xs]));
             }
+            PS_TRY(join_txt(1));
             PS_TRY(run_attention(si, /*cross=*/false, /*joint=*/true));
+            PS_TRY(fork_txt(2));
             for (int xs = 0; xs < 2; ++xs) {
                 const StageWeights& v = xs == 0 ? block->sw[si] : block->sw_txt[si];
                 const float* mod = xs == 0 ? cache->temb_e[si] : cache->temb_e2[si];
                 const ActiveList ax{cache->stream_list[xs], cache->stream_count + xs};
+                hipStream_t s_ = sx[xs];
                 GemmArgs go = base_gemm(cache->o, C, C, C, v.w[1], v.b[1]);
                 go.act = ax; go.res = cur; go.ldr = C;
                 go.rowscale = mod + 2 * C; go.rowscale_ld = 6 * C; go.row_owner = owner;
                 go.seg[0].ptr = mid; go.seg[0].ld = C;
-                { ProfScope ps("linear_out", st); PS_TRY(gemm(go, dt, mode, st)); }
-            }
-            for (int xs = 0; xs < 2; ++xs) {
-                const StageWeights& v = xs == 0 ? block->sw[si] : block->sw_txt[si];
-                const float* mod = xs == 0 ? cache->temb_e[si] : cache->temb_e2[si];
-                const ActiveList ax{cache->stream_list[xs], cache->stream_count + xs};
-                { ProfScope ps("layer_norm", st);
-                  PS_TRY(layer_norm(mid, nullptr, nullptr, mod + 3 * C, 6 * C, owner, C, d.eps, gm, dt, cache->u, ax, st)); }
+                { ProfScope ps("linear_out", s_); PS_TRY(gemm(go, dt, mode, s_)); }
+                { ProfScope ps("layer_norm", s_);
+                  PS_TRY(layer_norm(mid, nullptr, nullptr, mod + 3 * C, 6 * C, owner, C, d.eps, gm, dt, cache->u, ax, s_)); }
                 GemmArgs g1 = base_gemm(cache->u, C, C, F, v.w[3], v.b[3]);
                 g1.act = ax; g1.act_gelu = 1;
                 g1.seg[0].ptr = cache->hidden; g1.seg[0].ld = F;
-                { ProfScope ps("mlp_in", st); PS_TRY(gemm(g1, dt, mode, st)); }
+                { ProfScope ps("mlp_in", s_); PS_TRY(gemm(g1, dt, mode, s_)); }
                 GemmArgs g2 = base_gemm(cache->hidden, F, F, C, v.w[4], v.b[4]);
                 g2.act = ax; g2.res = mid; g2.ldr = C;
                 g2.rowscale = mod + 5 * C; g2.rowscale_ld = 6 * C; g2.row_owner = owner;
                 g2.seg[0].ptr = out; g2.seg[0].ld = C;
-                { ProfScope ps("mlp_out", st); PS_TRY(gemm(g2, dt, mode, st)); }
+                { ProfScope ps("mlp_out", s_); PS_TRY(gemm(g2, dt, mode, s_)); }
             }
+            PS_TRY(join_txt(3));
             break;
         }
         case PSERVE_AMLP: {
