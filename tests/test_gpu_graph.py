@@ -59,3 +59,45 @@ def test_step_replayed_from_a_graph_equals_eager(stages, reuse):
         torch.cuda.synchronize()
         for o, r in zip(outs, ref):
             assert torch.equal(o, r), f"eager after replay {k}"
+
+
+def test_joint_block_replayed_from_a_graph_equals_eager():
+    """A joint text-image block: its text stream's kernels run on the library's side stream, forked from and joined to
+    the captured stream twice per stage; the capture must hold both streams' work."""
+    cfg = wl.custom_config([(32, 32), (16, 48), (16, 16)], (16, 16), C=128, G=32, heads=2, stages=(wl.MMDIT, wl.MMDIT),
+                           dtype="bf16", ctx_len=40, ctx_dim=128, seed=72, temb_dim=96)
+    w = wl.make_workload(cfg)
+    run = GpuRun(w)
+    ps.profile_enable(False)
+    x = run.x                                           # image rows from the split, text rows scattered in
+    y = torch.empty_like(x)
+    outs = [torch.empty_like(im) for im in run.images]
+
+    def step():
+        run.cache.forward(x, None, None, y=y, temb=run.temb)
+        run.plan.reassemble(y, images=outs)
+
+    step()
+    torch.cuda.synchronize()
+    ref = [o.clone() for o in outs]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step()
+        side.synchronize()
+        with torch.cuda.graph(g, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    for k in range(4):
+        for o in outs:
+            o.zero_()
+        y.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        for o, r in zip(outs, ref):
+            assert torch.equal(o, r), f"replay {k}"
+        step()
+        torch.cuda.synchronize()
+        for o, r in zip(outs, ref):
+            assert torch.equal(o, r), f"eager after replay {k}"
