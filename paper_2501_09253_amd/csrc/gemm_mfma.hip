@@ -535,7 +535,11 @@ gemm_mfma_kernel(GemmArgs a) {
 // LDS: [2 weight stages][2 halo stages of CONV_APIX pixel slots][row -> token table].
 struct ConvTile {
     int32_t seg_rows, seg_tokens, nseg, seg_pix;    // seg_tokens = seg_rows*pw, seg_pix = (seg_rows+2)*(pw+2)
+    // ceil(2^32 / d) for d = seg_pix, pw + 2, seg_tokens, pw: x / d == __umulhi(x, m) for the small x of the set-up
+    // (x * d < 2^32; a true integer division is ~40 instructions, and 28 of them sat in front of the first halo load)
+    uint32_t m_seg_pix, m_hw, m_seg_tokens, m_pw;
 };
+__device__ __forceinline__ int div_small(int x, uint32_t m, int d) { return d == 1 ? x : (int)__umulhi((uint32_t)x, m); }
 
 // Template: block tile BM x BN, WGM x WGN wavefront grid (4 wavefronts), APIX halo pixel slots per stage
 // (multiple of 32), NSB weight stages.
@@ -628,8 +632,8 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
     for (int i = 0; i < A_LD; ++i) {
         int sl = lr + 32 * i;
         if (sl >= apix) sl = 0;                                    // unused slots re-read a valid pixel
-        const int g = sl / ct.seg_pix, l = sl - g * ct.seg_pix;
-        const int ly = l / hw, lx = l - ly * hw;
+        const int g = div_small(sl, ct.m_seg_pix, ct.seg_pix), l = sl - g * ct.seg_pix;
+        const int ly = div_small(l, ct.m_hw, hw), lx = l - ly * hw;
         a_pos[i] = (s_seg[g] + ly * a.geom.ppw + lx) * (int32_t)a.lda + gc * 8;
     }
     if (pro_a) {                                    // halo of chunk 0: in flight during the rest of the set-up
@@ -652,8 +656,8 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int r = wm * WM + i * 32 + fr;
-        const int g = r / ct.seg_tokens, rr = r - g * ct.seg_tokens;
-        const int ry = rr / pw, rx = rr - ry * pw;
+        const int g = div_small(r, ct.m_seg_tokens, ct.seg_tokens), rr = r - g * ct.seg_tokens;
+        const int ry = div_small(rr, ct.m_pw, pw), rx = rr - ry * pw;
         fa_slot[i] = g * ct.seg_pix + ry * hw + rx;
     }
     // weight fragment j: row wn*WN + 32*j + fr; the chunk swizzle (row >> 1) & 7 is the same for every j
@@ -846,6 +850,11 @@ static bool conv_tile(const GemmArgs& a, int BM, int apix_max, ConvTile* ct) {
     ct->seg_tokens = R * pw;
     ct->nseg = BM / ct->seg_tokens;
     ct->seg_pix = (R + 2) * (pw + 2);
+    auto magic = [](int d) { return (uint32_t)((((uint64_t)1 << 32) + d - 1) / d); };      // d == 1 is handled apart
+    ct->m_seg_pix = magic(ct->seg_pix);
+    ct->m_hw = magic(pw + 2);
+    ct->m_seg_tokens = magic(ct->seg_tokens);
+    ct->m_pw = magic(pw);
     return ct->nseg * ct->seg_pix <= apix_max && ct->nseg <= 64;
 }
 
