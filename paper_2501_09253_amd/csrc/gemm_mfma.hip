@@ -59,7 +59,18 @@ __device__ __forceinline__ float other_half_f(float v) {
 // column are issued before the current one is staged.  `smem` must be free (all staged operands consumed).
 // bias_pre: the lane's bias of each of its TN tile columns, loaded by the caller (a kernel that has other loads in
 // flight reads it before issuing those: a wait for a later load waits for all earlier ones).
-template <int BM, int BN, bool GEGLU, int WGM = 2, int WGN = 2, bool MAY_STAT = true>
+// FEAT: which of the rarely taken paths are compiled in.  The epilogue is straight-line code that a block runs once per
+// tile, fully unrolled over the tile columns: every path that is present but skipped costs a jump to an instruction
+// line that is not in the cache (per-column timestamps showed 2 us per column, about five such jumps each, whatever
+// the memory traffic), so a kernel that can rule a path out by its launch conditions leaves it out.
+enum : int {
+    EPF_TRANS = 1,      // transposed output segments
+    EPF_GELU = 2,       // tanh GELU on the result
+    EPF_GATE = 4,       // per-request gate (rowscale)
+    EPF_MIXED = 8,      // rows of several requests in one wavefront tile: per-element look-ups of rowbias / rowscale
+    EPF_ALL = 15
+};
+template <int BM, int BN, bool GEGLU, int WGM = 2, int WGN = 2, bool MAY_STAT = true, int FEAT = EPF_ALL>
 __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32], uint8_t* smem,
                                               const int32_t* s_tok, int n0, const float* bias_pre = nullptr) {
     constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;     // WGM x WGN wavefront grid
@@ -90,7 +101,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[B
     // request (rows are ordered by request, so first == last decides), else looked up per element
     bool rb_uniform = false;
     int rb_slot = 0;
-    if (!GEGLU && (a.rowbias || a.rowscale)) {
+    if (!GEGLU && (a.rowbias || ((FEAT & EPF_GATE) && a.rowscale))) {
         const int t_first = w_tok[0], t_last = w_tok[WM - 1];
         if (t_first >= 0 && t_last >= 0) {
             rb_slot = a.row_owner[t_first / a.geom.S];
@@ -135,7 +146,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[B
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) vals[i][e] = acc[i][j][e] + bias;
-            if (a.rowbias && !rb_uniform) {                     // rows of several requests in this wavefront's tile
+            if ((FEAT & EPF_MIXED) && a.rowbias && !rb_uniform) {   // rows of several requests in this wavefront's tile
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -144,14 +155,14 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[B
                         if (tok >= 0) vals[i][e] += a.rowbias[(int64_t)a.row_owner[tok / a.geom.S] * a.N + pcol + fr];
                     }
             }
-            if (a.act_gelu) {
+            if ((FEAT & EPF_GELU) && a.act_gelu) {
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int e = 0; e < 16; ++e) vals[i][e] = gelu_tanh(vals[i][e]);
             }
-            if (a.rowscale) {                                   // gate of the request, before the residual is added
-                if (rb_uniform) {
+            if ((FEAT & EPF_GATE) && a.rowscale) {              // gate of the request, before the residual is added
+                if (rb_uniform || !(FEAT & EPF_MIXED)) {
                     const float gate = a.rowscale[(int64_t)rb_slot * a.rowscale_ld + pcol + fr];
 #pragma unroll
                     for (int i = 0; i < TM; ++i)
@@ -190,7 +201,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[B
             }
         }
         uint16_t* out = (uint16_t*)sgm.ptr;
-        if (sgm.transposed) {
+        if ((FEAT & EPF_TRANS) && sgm.transposed) {
             // out[col][token]: the four rows e%4 of a lane are consecutive tokens -> one 8-byte store
 #pragma unroll
             for (int i = 0; i < TM; ++i)
@@ -785,6 +796,12 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
 #undef PS_LOAD_B
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+    // The lane's bias of each tile column, loaded here in one batch: inside the epilogue the load of a column sits
+    // behind the staging of the previous one, and a memory round trip per column made the epilogue 2 us per column
+    // (10 us of a 60 us kernel, measured with per-column timestamps); here it hides behind the exchange.
+    float bias_t[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) bias_t[j] = a.bias ? a.bias[n0 + wn * WN + j * 32 + fr] : 0.f;
     if (KS == 2) {
         // the partial sums of wavefront w + 4 go to wavefront w through the drained ring, half the tile columns at a
         // time; the first four wavefronts then run the epilogue
@@ -822,7 +839,8 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
         }
         if (kg == 1) return;
     }
-    gemm_epilogue<BM, BN, false, WGM, WGN>(a, acc, smem, s_tok, n0);
+    // the launch conditions of these kernels rule the other paths out (conv_select)
+    gemm_epilogue<BM, BN, false, WGM, WGN, true, 0>(a, acc, smem, s_tok, n0, bias_t);
 }
 
 template <int BM, int BN, int WGM, int WGN, int APIX, int NSB, int KS = 1>
@@ -890,7 +908,10 @@ static int conv_select(const GemmArgs& a, ConvTile* ct, int* wave_cols = nullptr
     const bool plain3x3 = a.taps == 9 && (a.tap_w == 0 || a.tap_w == 3) && a.a_mul <= 1 && !a.a_dy && !a.a_dx && !a.o_mul;
     // the kernels address the padded patch buffer with 32-bit element offsets
     const bool fits32 = (int64_t)a.geom.P * a.geom.pS * a.lda < ((int64_t)1 << 31);
-    if (plain3x3 && fits32 && a.epi == EPI_ROUTE && a.seg_cols % 32 == 0 && a.seg_cols == a.N && !a.seg[0].transposed) {
+    // no gate, no GELU, no transposed segment; a per-request bias only where a wavefront's 64 rows lie in one patch (the
+    // kernels compile the epilogue without those paths)
+    const bool lean = !a.rowscale && !a.act_gelu && (!a.rowbias || (a.geom.S % 64 == 0 && a.geom.pw <= 64 && 64 % a.geom.pw == 0));
+    if (plain3x3 && fits32 && lean && a.epi == EPI_ROUTE && a.seg_cols % 32 == 0 && a.seg_cols == a.N && !a.seg[0].transposed) {
         if (a.N % 160 == 0 && conv_tile(a, 256, 384, ct)) { sel = 1; wc = 160; }
         else if (conv_tile(a, 128, 256, ct)) {
             if (a.N % 320 == 0) { sel = 2; wc = 160; }
