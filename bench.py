@@ -25,7 +25,7 @@ EVENT_EVERY = 4                # the timed region brackets the dominant kernel i
 # same command, each scaled by what the counter reads for bench.py's 256 MiB calibration copy (fetch x2.000,
 # write x1.000); see profiles/bench_config<N>_kernels_and_traffic.md.  (config id, kernel label) -> bytes.
 MEASURED_TRAFFIC = {
-    (2, "conv3x3"): 52.5e6 + 23.0e6,
+    (2, "conv3x3"): 52.0e6 + 23.1e6,
     (5, "attn_self"): 1475.2e6 + 100.9e6,
 }
 
