@@ -26,7 +26,7 @@ EVENT_EVERY = 4                # the timed region brackets the dominant kernel i
 # write x1.000); see profiles/bench_config<N>_kernels_and_traffic.md.  (config id, kernel label) -> bytes.
 MEASURED_TRAFFIC = {
     (2, "conv3x3"): 52.0e6 + 23.1e6,
-    (5, "attn_self"): 1475.2e6 + 100.9e6,
+    (5, "attn_self"): 1466.4e6 + 100.9e6,
 }
 
 
