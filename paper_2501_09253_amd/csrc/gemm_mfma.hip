@@ -68,7 +68,8 @@ enum : int {
     EPF_GELU = 2,       // tanh GELU on the result
     EPF_GATE = 4,       // per-request gate (rowscale)
     EPF_MIXED = 8,      // rows of several requests in one wavefront tile: per-element look-ups of rowbias / rowscale
-    EPF_ALL = 15
+    EPF_SCALE = 16,     // output segments with a scale other than 1 (the pre-multiplied Q)
+    EPF_ALL = 31
 };
 template <int BM, int BN, bool GEGLU, int WGM = 2, int WGN = 2, bool MAY_STAT = true, int FEAT = EPF_ALL>
 __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[BM / WGM / 32][BN / WGN / 32], uint8_t* smem,
@@ -255,7 +256,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[B
             u32x4 o;
 #pragma unroll
             for (int q = 0; q < 4; ++q)
-                o[q] = pack_bf16x2(v[2 * q] * sgm.scale, v[2 * q + 1] * sgm.scale);
+                o[q] = (FEAT & EPF_SCALE) ? pack_bf16x2(v[2 * q] * sgm.scale, v[2 * q + 1] * sgm.scale) : pack_bf16x2(v[2 * q], v[2 * q + 1]);
             if (tok >= 0) *reinterpret_cast<u32x4*>(out + tk * sgm.ld + ocol0 + ch * 8) = o;
         }
         __builtin_amdgcn_wave_barrier();
@@ -910,7 +911,7 @@ static int conv_select(const GemmArgs& a, ConvTile* ct, int* wave_cols = nullptr
     const bool fits32 = (int64_t)a.geom.P * a.geom.pS * a.lda < ((int64_t)1 << 31);
     // no gate, no GELU, no transposed segment; a per-request bias only where a wavefront's 64 rows lie in one patch (the
     // kernels compile the epilogue without those paths)
-    const bool lean = !a.rowscale && !a.act_gelu && (!a.rowbias || (a.geom.S % 64 == 0 && a.geom.pw <= 64 && 64 % a.geom.pw == 0));
+    const bool lean = a.seg[0].scale == 1.f && !a.rowscale && !a.act_gelu && (!a.rowbias || (a.geom.S % 64 == 0 && a.geom.pw <= 64 && 64 % a.geom.pw == 0));
     if (plain3x3 && fits32 && lean && a.epi == EPI_ROUTE && a.seg_cols % 32 == 0 && a.seg_cols == a.N && !a.seg[0].transposed) {
         if (a.N % 160 == 0 && conv_tile(a, 256, 384, ct)) { sel = 1; wc = 160; }
         else if (conv_tile(a, 128, 256, ct)) {
