@@ -5,7 +5,11 @@ batch), pserve_block_forward, reassembly (patch batch -> per-image NCHW), on a p
 for the batch composition (planner time is reported separately).  Inputs are resident in HBM
 before the timed region.  One JSON line is printed.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 5] [--only]
+
+The headline is configuration 5 (the largest single-GPU workload: the skewed batch with the patch cache); the line
+also carries a short measurement of every baseline configuration 1..5 under "configs" (left out with --only, which
+profiler runs use so that a trace holds one workload).
 """
 import argparse
 import json
@@ -21,12 +25,13 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 EVENT_EVERY = 4                # the timed region brackets the dominant kernel in every 4th step
 
-# HBM bytes per launch of the dominant kernel, from the two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) of this
-# same command, each scaled by what the counter reads for bench.py's 256 MiB calibration copy (fetch x2.000,
-# write x1.000); see profiles/bench_config<N>_kernels_and_traffic.md.  (config id, kernel label) -> bytes.
-MEASURED_TRAFFIC = {
-    (2, "conv3x3"): 52.0e6 + 23.1e6,
-    (5, "attn_self"): 1466.4e6 + 100.9e6,
+# HBM bytes per launch of the dominant kernel.  NOT measured by this run: counters need a profiler run of their own.
+# The figures come from two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE) of `python3 bench.py --config N --only`,
+# each scaled by what the same counter reads for the 256 MiB calibration copy below; the summary file is named beside
+# the number in the output.  (config id, kernel label) -> (bytes, summary file).
+PROFILED_TRAFFIC = {
+    (2, "conv3x3"): (52.0e6 + 23.1e6, "profiles/bench_config2_kernels_and_traffic.md"),
+    (5, "attn_self"): (1466.4e6 + 100.9e6, "profiles/bench_config5_kernels_and_traffic.md"),
 }
 
 
@@ -80,35 +85,18 @@ def kernel_work(cfg, n_active_tokens, patch=None):
     }
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5, 6 = config 3 with per-token LayerNorms, 7 = config 2 with the time embedding, 8 = a diffusion-transformer block, 9 = a joint text-image block (default: 2, the SDXL ResNet block)")
-    ap.add_argument("--patch", type=int, nargs=2, default=None, metavar=("PH", "PW"),
-                    help="patch size override for the patch-size sweep (not for reuse configs: the mask is per patch)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket kernels with HIP events")
-    ap.add_argument("--all-kernels", action="store_true", help="add every kernel's time and roofline fraction to the JSON")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
-        sys.exit(2)
-
-    import numpy as np
+def measure(cfg_id, steps, warmup, all_kernels=False, events=True, patch=None, peaks=None):
+    """One configuration on the GPU: `warmup` untimed steps, then exactly `steps` timed ones.  Returns the result
+    fields and the workload (for the CPU-baseline leg)."""
     import torch
     import paper_2501_09253_amd as ps
     import workloads as wl
     from harness import GpuRun
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
-    cfg = wl.config(args.config)
+    cfg = wl.config(cfg_id)
     w = wl.make_workload(cfg)
-    t0 = time.perf_counter()
-    assert args.patch is None or w.reuse is None, "--patch cannot be combined with a reuse mask"
-    run = GpuRun(w, patch=tuple(args.patch) if args.patch else None)
+    assert patch is None or w.reuse is None, "--patch cannot be combined with a reuse mask"
+    run = GpuRun(w, patch=tuple(patch) if patch else None)
     patch = (run.plan.ph, run.plan.pw)
     torch.cuda.synchronize()
     mask = None
@@ -126,13 +114,6 @@ def main():
 
     y = torch.empty_like(run.x)
     outs = [torch.empty_like(im) for im in run.images]
-    # one plain device copy of known size (256 MiB read + 256 MiB written): the reference that scales the
-    # FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this same command
-    cal_src = torch.ones(128 * 1024 * 1024, dtype=torch.bfloat16, device="cuda")
-    cal_dst = torch.empty_like(cal_src)
-    cal_dst.copy_(cal_src)
-    torch.cuda.synchronize()
-    del cal_src, cal_dst
 
     def step():
         run.plan.split(run.images, out=run.x)
@@ -142,8 +123,7 @@ def main():
     # Warm-up; its last steps are timed kernel by kernel to find the dominant kernel.  In the timed region only THAT
     # kernel is bracketed with HIP events (on the stream the library launches on): every event pair costs a few
     # microseconds of stream time, and bracketing all kernels would lower the very throughput being measured.
-    events = not args.no_kernel_events
-    for _ in range(max(0, args.warmup - 3)):
+    for _ in range(max(0, warmup - 3)):
         step()
     torch.cuda.synchronize()
     dom = None
@@ -151,25 +131,26 @@ def main():
     if events:
         ps.profile_select(None)
         ps.profile_enable(True)
-    n_probe = min(3, args.warmup)
+    n_probe = min(3, warmup)
     for _ in range(n_probe):
         step()
     torch.cuda.synchronize()
     if events:
         prof_all = ps.profile_read() if n_probe else {}
-        if args.all_kernels:                      # a longer untimed pass for the per-kernel table
-            for _ in range(args.steps):
+        if all_kernels:                      # a longer untimed pass for the per-kernel table
+            for _ in range(steps):
                 step()
             torch.cuda.synchronize()
             more = ps.profile_read()
             prof_all = {k: {"calls": more[k]["calls"], "total_ms": more[k]["total_ms"]} for k in more}
-            n_probe = args.steps
+            n_probe = steps
         if prof_all:
             dom = max(prof_all, key=lambda k: prof_all[k]["total_ms"])
         ps.profile_select(dom)
         ps.profile_sample(EVENT_EVERY)            # the dominant kernel of every 4th step: 2-3 us of event cost per step
+    torch.cuda.synchronize()
     t1 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t1
@@ -177,21 +158,21 @@ def main():
     ps.profile_enable(False)
     ps.profile_select(None)
     ps.profile_sample(1)
-    ms_per_step = dt / args.steps * 1e3
+    ms_per_step = dt / steps * 1e3
 
     # block-only time on the same stream, for reference
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
-    for _ in range(args.steps):
+    for _ in range(steps):
         run.cache.forward(run.x, None if run.joint else run.ctx, mask, y=y, temb=run.temb)
     e1.record()
     torch.cuda.synchronize()
-    block_ms = e0.elapsed_time(e1) / args.steps
+    block_ms = e0.elapsed_time(e1) / steps
 
     # cache-manager pieces (outside the step): the predictor's per-patch MSE feature, and with slots the migration of
     # every slot to a cache of the same batch (all requests common)
     extras = {}
-    if args.all_kernels:
+    if all_kernels:
         def timed(fn, reps=20):
             fn()
             a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -205,6 +186,10 @@ def main():
         us = timed(lambda: run.plan.patch_mse(run.x, y))
         gbs = 2.0 * cfg.T * cfg.C * es / (us * 1e-6) / 1e9
         extras["patch_mse"] = {"avg_us": us, "gbs": gbs, "frac_hbm": gbs / PEAK_HBM_GBS}
+        for name, fn in (("split", lambda: run.plan.split(run.images, out=run.x)), ("reassemble", lambda: run.plan.reassemble(y, outs))):
+            us = timed(fn)
+            gbs = 2.0 * cfg.T * cfg.C * es / (us * 1e-6) / 1e9
+            extras[name] = {"avg_us": us, "gbs": gbs, "frac_hbm": gbs / PEAK_HBM_GBS}
         if cfg.dtype == "bf16" and patch[0] % 2 == 0 and patch[1] % 2 == 0 and w.reuse is None and not run.joint:
             # the level changes at this configuration's size: C -> C, down to half size and back up (random weights)
             from harness import to_dev
@@ -231,6 +216,7 @@ def main():
             twin.close()
 
     work = kernel_work(cfg, n_active, patch)
+
     def entry(name, rec, steps_):
         avg_ms = rec["total_ms"] / rec["calls"]
         fl, by = work.get(name, (0.0, 0.0))
@@ -243,75 +229,146 @@ def main():
             ent["frac_hbm"] = ent["gbs"] / PEAK_HBM_GBS
         return ent
     kernels = {name: entry(name, rec, n_probe) for name, rec in prof_all.items()}      # untimed pass (all kernels)
-    timed = {name: entry(name, rec, max(1, (args.steps + EVENT_EVERY - 1) // EVENT_EVERY))     # timed region (dominant kernel)
-             for name, rec in prof.items()}
+    timed_k = {name: entry(name, rec, max(1, (steps + EVENT_EVERY - 1) // EVENT_EVERY))    # timed region (dominant kernel)
+               for name, rec in prof.items()}
     roofline = None
-    if timed:
-        if dom not in timed:                       # no warm-up steps: every kernel was timed in the timed region
+    if timed_k:
+        if dom not in timed_k:                     # no warm-up steps: every kernel was timed in the timed region
             dom = max(prof, key=lambda k: prof[k]["total_ms"])
-        ent = timed[dom]
-        if "tflops" in ent:
-            roofline = {"kernel": dom, "bound": "mfma", "achieved": ent["tflops"], "peak": PEAK_BF16_TFLOPS,
-                        "unit": "TFLOP/s", "frac": ent["frac_mfma"], "traffic": MEASURED_TRAFFIC.get((cfg.cfg_id, dom)),
-                        "avg_us": ent["avg_us"]}
-        else:
-            roofline = {"kernel": dom, "bound": "hbm", "achieved": ent.get("gbs"), "peak": PEAK_HBM_GBS,
-                        "unit": "GB/s", "frac": ent.get("frac_hbm"), "traffic": MEASURED_TRAFFIC.get((cfg.cfg_id, dom)),
-                        "avg_us": ent["avg_us"]}
+        ent = timed_k[dom]
+        traffic, source = PROFILED_TRAFFIC.get((cfg.cfg_id, dom), (None, None))
+        mfma = "tflops" in ent
+        measured_peak = None if peaks is None else peaks["mfma_bf16_tflops" if mfma else "copy_gbs"]
+        achieved = ent["tflops"] if mfma else ent.get("gbs")
+        roofline = {"kernel": dom, "bound": "mfma" if mfma else "hbm", "achieved": achieved,
+                    "peak": PEAK_BF16_TFLOPS if mfma else PEAK_HBM_GBS, "unit": "TFLOP/s" if mfma else "GB/s",
+                    "frac": ent["frac_mfma"] if mfma else ent.get("frac_hbm"),
+                    "traffic": traffic, "traffic_source": source, "avg_us": ent["avg_us"],
+                    "peak_measured": measured_peak,
+                    "frac_of_measured": (achieved / measured_peak) if (measured_peak and achieved) else None}
+    res = {
+        "ms_per_step": ms_per_step, "tokens_per_s": cfg.T / (ms_per_step * 1e-3),
+        "workload": f"config{cfg.cfg_id} {cfg.name}: latents {sorted(set(cfg.resolutions))} x{cfg.n}, "
+                    f"patch {patch[0]}x{patch[1]}, P={run.plan.P}, T={cfg.T}, C={cfg.C}, stages={'+'.join(cfg.stages)}"
+                    + (f", reuse p={cfg.reuse_p} ({cfg.T - n_active} tokens reused)" if w.reuse is not None else ""),
+        "block_ms": block_ms, "plan_us": plan_us, "n_active": n_active, "roofline": roofline, "kernels": kernels,
+        "extras": extras, "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "T": cfg.T,
+    }
+    run.cache.close()
+    run.block.close()
+    run.plan.close()
+    del run, y, outs
+    torch.cuda.empty_cache()
+    return res, w
 
-    cpu = None
-    if not args.no_cpu_baseline:
-        from oracle import block as ob
-        from threadpoolctl import threadpool_info
-        # bounded sample: whole images of the workload, smallest first, until ~20 s of oracle time
-        order = sorted(range(cfg.n), key=lambda i: cfg.resolutions[i][0] * cfg.resolutions[i][1])
-        done_tok, tc = 0, time.perf_counter()
-        used = []
-        passes = 0
-        while time.perf_counter() - tc < 10.0:          # repeat whole passes until about 10 s of oracle time
-          passes += 1
-          for i in order:
+
+def cpu_baseline(w):
+    """The oracle as it stands on the host cores, on a bounded sample of the workload (about 10-25 s)."""
+    from oracle import block as ob
+    from threadpoolctl import threadpool_info
+    cfg = w.cfg
+    # bounded sample: whole images of the workload, smallest first, until ~20 s of oracle time
+    order = sorted(range(cfg.n), key=lambda i: cfg.resolutions[i][0] * cfg.resolutions[i][1])
+    done_tok, tc = 0, time.perf_counter()
+    used = []
+    passes = 0
+    while time.perf_counter() - tc < 10.0:          # repeat whole passes until about 10 s of oracle time
+        passes += 1
+        for i in order:
             H, W = cfg.resolutions[i]
             if H * W > 16384 and used:
                 continue                      # a 65,536-token image alone is minutes of fp64 attention
             c_i = None if w.cache is None else {k: v[i] for k, v in w.cache.items()}
             if "MMDIT" in cfg.stages:
                 ob.mmdit(w.images[i], w.ctx[i], w.temb[i], w.params[0], cfg.heads, cfg.eps)
-                done_tok += H * W
-                used.append(i)
-                if time.perf_counter() - tc > 25.0:
-                    break
-                continue
-            ob.block_forward(w.images[i], cfg.stages, w.params, G=cfg.G, heads=cfg.heads, eps=cfg.eps,
-                             ctx=None if w.ctx is None else w.ctx[i],
-                             reuse=None if w.reuse is None else w.reuse[i], cache=c_i,
-                             temb=None if w.temb is None else w.temb[i])
+            else:
+                ob.block_forward(w.images[i], cfg.stages, w.params, G=cfg.G, heads=cfg.heads, eps=cfg.eps,
+                                 ctx=None if w.ctx is None else w.ctx[i],
+                                 reuse=None if w.reuse is None else w.reuse[i], cache=c_i,
+                                 temb=None if w.temb is None else w.temb[i])
             done_tok += H * W
             used.append(i)
             if time.perf_counter() - tc > 25.0:
                 break
-        cpu_s = time.perf_counter() - tc
-        threads = max([t.get("num_threads", 1) for t in threadpool_info()] + [1])
-        cpu = {"value": done_tok / cpu_s, "unit": "tokens/s", "cores": threads, "kind": "oracle",
-               "sample": f"{passes} pass(es) over {len(set(used))} of {cfg.n} images ({done_tok} tokens in total), whole block, "
-                         f"fp64 numpy, {cpu_s:.1f} s"}
+    cpu_s = time.perf_counter() - tc
+    threads = max([t.get("num_threads", 1) for t in threadpool_info()] + [1])
+    return {"value": done_tok / cpu_s, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"{passes} pass(es) over {len(set(used))} of {cfg.n} images ({done_tok} tokens in total), whole block, "
+                      f"fp64 numpy, {cpu_s:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=5, help="benchmark configuration 1..5 (default 5: the largest one, the skewed batch with cache reuse), 6 = config 3 with per-token LayerNorms, 7 = config 2 with the time embedding, 8 = a diffusion-transformer block, 9 = a joint text-image block")
+    ap.add_argument("--patch", type=int, nargs=2, default=None, metavar=("PH", "PW"),
+                    help="patch size override for the patch-size sweep (not for reuse configs: the mask is per patch)")
+    ap.add_argument("--only", action="store_true", help="measure --config alone: no \"configs\" array, no peak probes (profiler runs)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket kernels with HIP events")
+    ap.add_argument("--all-kernels", action="store_true", help="add every kernel's time and roofline fraction to the JSON")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2501_09253_amd as ps
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    # one plain device copy of known size (256 MiB read + 256 MiB written): the reference that scales the
+    # FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this same command
+    cal_src = torch.ones(128 * 1024 * 1024, dtype=torch.bfloat16, device="cuda")
+    cal_dst = torch.empty_like(cal_src)
+    cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
+    peaks = None
+    if not args.only:
+        # what this chip reaches: a register-resident MFMA stream (about 30 ms) and a 2 GiB streaming copy
+        big_src = torch.ones(1 << 30, dtype=torch.bfloat16, device="cuda")
+        big_dst = torch.empty_like(big_src)
+        peaks = {"mfma_bf16_tflops": ps.probe_mfma_bf16(20000), "copy_gbs": ps.probe_copy(big_dst, big_src, reps=5),
+                 "copy_bytes": 2 * big_src.numel()}
+        del big_src, big_dst
+        torch.cuda.empty_cache()
+
+    events = not args.no_kernel_events
+    res, w = measure(args.config, args.steps, args.warmup, all_kernels=args.all_kernels, events=events, patch=args.patch,
+                     peaks=peaks)
+    cpu = None if args.no_cpu_baseline else cpu_baseline(w)
+    del w
+
+    configs = None
+    if not args.only:
+        configs = []
+        for c in (1, 2, 3, 4, 5):
+            if c == args.config and args.patch is None:
+                r = res
+            else:
+                r, _ = measure(c, min(args.steps, 20), min(args.warmup, 5), events=events, peaks=peaks)
+            rf = r["roofline"] or {}
+            configs.append({"workload": r["workload"], "ms_per_step": r["ms_per_step"], "tokens_per_s": r["tokens_per_s"],
+                            "block_ms": r["block_ms"], "dominant_kernel": rf.get("kernel"), "bound": rf.get("bound"),
+                            "kernel_avg_us": rf.get("avg_us"), "frac": rf.get("frac"),
+                            "frac_of_measured": rf.get("frac_of_measured")})
 
     out = {
-        "metric": "patch-tokens/sec per mixed-res denoising block", "value": cfg.T / (ms_per_step * 1e-3),
-        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "metric": "patch-tokens/sec per mixed-res denoising block", "value": res["tokens_per_s"],
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": f"config{cfg.cfg_id} {cfg.name}: latents {sorted(set(cfg.resolutions))} x{cfg.n}, "
-                               f"patch {patch[0]}x{patch[1]}, P={run.plan.P}, T={cfg.T}, C={cfg.C}, stages={'+'.join(cfg.stages)}"
-                               + (f", reuse p={cfg.reuse_p} ({cfg.T - n_active} tokens reused)" if w.reuse is not None else ""),
-                   "step": "split + block_forward + reassemble"},
-        "block_forward_ms": block_ms, "block_tokens_per_s": cfg.T / (block_ms * 1e-3), "plan_us": plan_us,
-        "computed_tokens": n_active, "block_computed_tokens_per_s": n_active / (block_ms * 1e-3),
-        "roofline": roofline, "cpu_baseline": cpu,
+        "dtype": res["dtype"], "data": "synthetic",
+        "config": {"workload": res["workload"], "step": "split + block_forward + reassemble"},
+        "block_forward_ms": res["block_ms"], "block_tokens_per_s": res["T"] / (res["block_ms"] * 1e-3), "plan_us": res["plan_us"],
+        "computed_tokens": res["n_active"], "block_computed_tokens_per_s": res["n_active"] / (res["block_ms"] * 1e-3),
+        "roofline": res["roofline"], "cpu_baseline": cpu, "measured_peaks": peaks, "configs": configs,
     }
     if args.all_kernels:
-        out["kernels"] = kernels
-        out["cache_manager"] = extras
+        out["kernels"] = res["kernels"]
+        out["cache_manager"] = res["extras"]
     print(json.dumps(out))
 
 

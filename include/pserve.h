@@ -229,6 +229,8 @@ int  pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const v
  * in the implementation section is the mean squared error).  a, b: DEVICE [T][C] patch batches of the
  * plan (dtype as above); out: DEVICE float [P], out[p] = mean over the S*C elements of patch p of
  * (a - b)^2, accumulated in fp32 per thread and in a fixed order across threads (deterministic).
+ * The partial sums live in scratch owned by the plan: calls on the same plan must not overlap (one stream, or
+ * serialised by the caller); calls on different plans are independent.
  * Errors: EINVAL (NULL, C not a multiple of 8 (bf16) / 4 (fp32), C > 8192), EHIP.
  *
  * pserve_cache_sets: id bookkeeping when the batch composition changes between steps.  Every patch has
@@ -337,6 +339,17 @@ int  pserve_profile_select(const char* label);
  * launches are bracketed exactly as above, the others run without events.  Errors: EINVAL (every < 1). */
 int  pserve_profile_sample(int every);
 int  pserve_profile_read(pserve_prof_entry* out, int32_t max, int32_t* count);
+
+/* ---- peak probes for measurements (no operation of the paper; they give the roofline figures a second reference
+ * beside the datasheet).  Both time their own launches with a pair of events on `stream` and wait for them.
+ * pserve_probe_mfma_bf16: 512 blocks of four wavefronts, each wavefront issuing 8 * iters independent
+ * v_mfma_f32_32x32x16_bf16 on register-resident operands; *tflops = dense bf16 rate reached.
+ * pserve_probe_copy: a plain 16-byte-per-lane copy of `bytes` bytes from src to dst (DEVICE, 16-byte aligned, not
+ * overlapping), `reps` launches; *gbs = (bytes read + bytes written) per second.  A buffer well beyond the 256 MB
+ * last-level cache gives the HBM figure; the same launch is the known-size reference for memory counters.
+ * Errors: EINVAL, EHIP. */
+int  pserve_probe_mfma_bf16(int iters, double* tflops, void* stream);
+int  pserve_probe_copy(void* dst, const void* src, size_t bytes, int reps, double* gbs, void* stream);
 
 #ifdef __cplusplus
 }

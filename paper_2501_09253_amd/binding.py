@@ -116,6 +116,8 @@ def lib() -> C.CDLL:
     L.pserve_profile_select.argtypes = [C.c_char_p]
     L.pserve_profile_sample.argtypes = [C.c_int]
     L.pserve_patch_mse.argtypes = [vp, vp, vp, i32, C.c_int, vp, vp]
+    L.pserve_probe_mfma_bf16.argtypes = [C.c_int, C.POINTER(C.c_double), vp]
+    L.pserve_probe_copy.argtypes = [vp, vp, C.c_size_t, C.c_int, C.POINTER(C.c_double), vp]
     L.pserve_cache_sets.argtypes = [vp, C.POINTER(C.c_int64), vp, C.POINTER(C.c_int64), C.POINTER(i32),
                                     C.POINTER(C.c_uint8), vp, vp]
     L.pserve_cache_migrate.argtypes = [vp, vp, vp, vp, vp]
@@ -167,6 +169,22 @@ def profile_select(label: Optional[str]):
 def profile_sample(every: int):
     """Bracket the kernels of every n-th forward call only (pserve_profile_sample)."""
     _check(lib().pserve_profile_sample(int(every)))
+
+
+def probe_mfma_bf16(iters: int = 20000) -> float:
+    """pserve_probe_mfma_bf16: dense bf16 TFLOP/s of a register-resident MFMA stream on this GPU."""
+    out = C.c_double(0.0)
+    _check(lib().pserve_probe_mfma_bf16(iters, C.byref(out), _stream()))
+    return out.value
+
+
+def probe_copy(dst, src, reps: int = 5) -> float:
+    """pserve_probe_copy: GB/s (read + written) of a plain copy between two equally sized device tensors."""
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes and src.is_contiguous() and dst.is_contiguous()
+    out = C.c_double(0.0)
+    _check(lib().pserve_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes, reps, C.byref(out), _stream()))
+    return out.value
 
 
 def profile_read() -> Dict[str, Dict[str, float]]:

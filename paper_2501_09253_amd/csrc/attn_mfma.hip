@@ -16,7 +16,7 @@
 //
 // Blocks are numbered so that the blocks resident on one XCD (block id mod 8) walk
 // consecutive query tiles of the same head: the K / V^T tiles they stream are then shared
-// through that XCD's L2.  Within a head the largest images come first.
+// through that XCD's L2.  The largest images come first (attn_item).
 #include "kernels.h"
 
 namespace pserve {
@@ -60,36 +60,52 @@ __device__ __forceinline__ int kperm(int r) { return (r & ~12) | ((r & 4) << 1) 
 //     accumulators are rescaled and the probabilities recomputed);
 //   * the row sum is taken over the bf16-rounded probabilities, i.e. of exactly what multiplies V.
 // K / V^T tiles of 64 keys are staged by direct global->LDS loads into a ring of three stages, two tiles ahead.
+extern __shared__ __attribute__((aligned(16))) uint8_t att_smem[];
+
+// Work item of a block: (request slot, head, query tile of that request).  A block's run time goes with the number of
+// keys of its request, so the items are ordered longest first: request slots from the last (the plan sorts requests by
+// size, largest last) to the first, head-major inside a slot, so that consecutive items are consecutive query tiles of
+// one head.  Groups of ATT_GROUP consecutive items are dealt to the XCDs in turn (block b runs on XCD b mod 8 and an XCD
+// starts its blocks in order): the blocks resident on an XCD stream the K / V^T tiles of the same head through that
+// XCD's L2, every XCD gets the same share of the long items, and the short ones fill the last round.
+constexpr int ATT_GROUP = 64;
+__device__ __forceinline__ bool attn_item(const AttnArgs& a, int& s, int& head, int& tile_in_s) {
+    const int total_tiles = a.tile_off[a.n];
+    const int64_t items = (int64_t)total_tiles * a.heads;
+    const int64_t seq = blockIdx.x >> 3;
+    const int64_t k = ((seq / ATT_GROUP) * 8 + (blockIdx.x & 7)) * ATT_GROUP + seq % ATT_GROUP;
+    if (k >= items) return false;
+    const int64_t q = items - 1 - k;                 // position in ascending slot order
+    const int qt = (int)(q / a.heads);
+    int lo = 0, hi = a.n;                            // largest s with tile_off[s] <= qt
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (a.tile_off[mid] <= qt) lo = mid; else hi = mid;
+    }
+    s = lo;
+    const int tiles_s = a.tile_off[s + 1] - a.tile_off[s];
+    const int r = tiles_s * a.heads - 1 - (int)(q - (int64_t)a.tile_off[s] * a.heads);
+    head = r / tiles_s;
+    tile_in_s = r - head * tiles_s;
+    return true;
+}
+
 template <int ATT_QT>
-__global__ void __launch_bounds__(256, ATT_QT == 1 ? 3 : 2)
-attn_mfma_kernel(AttnArgs a) {
+__device__ __forceinline__ void attn_body(const AttnArgs& a, const int tid) {
     constexpr int ATT_BQ = 4 * 32 * ATT_QT;
-    extern __shared__ __attribute__((aligned(16))) uint8_t att_smem[];
     u32x4* sK = reinterpret_cast<u32x4*>(att_smem);            // [ATT_NS][64 keys][8 chunks], chunk ^ ((key>>1)&7)
     u32x4* sV = sK + ATT_NS * 512;                             // [ATT_NS][64 d][8 chunks of 8 keys], chunk ^ ((d>>1)&7)
 
-    const int tid = threadIdx.x, lane = tid & 63;
+    const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int fr = lane & 31, fh = lane >> 5;
 
-    // ---- which (head, query tile) ----------------------------------------------------------------
-    const int total_tiles = a.tile_off[a.n];
-    const int64_t items = (int64_t)total_tiles * a.heads;
-    const int64_t chunk = (items + 7) >> 3;
-    const int64_t j = blockIdx.x >> 3;
-    const int64_t k = (int64_t)(blockIdx.x & 7) * chunk + j;
-    if (j >= chunk || k >= items) return;
-    const int head = (int)(k / total_tiles);
-    const int tile = total_tiles - 1 - (int)(k - (int64_t)head * total_tiles);
-    int lo = 0, hi = a.n;                     // largest s with tile_off[s] <= tile
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (a.tile_off[mid] <= tile) lo = mid; else hi = mid;
-    }
-    const int s = lo;
+    // ---- which (request slot, head, query tile) ---------------------------------------------------
+    int s, head, tile_in_s;
+    if (!attn_item(a, s, head, tile_in_s)) return;
     const int S = a.geom.S;
     const int rows_s = (a.act_off[s + 1] - a.act_off[s]) * S;            // computed query rows of this image
-    const int r0 = (tile - a.tile_off[s]) * ATT_BQ;
+    const int r0 = tile_in_s * ATT_BQ;
     int64_t k0;
     int nk;
     if (a.cross_len) { k0 = (int64_t)a.perm[s] * a.cross_ld; nk = a.cross_len; }
@@ -306,6 +322,342 @@ attn_mfma_kernel(AttnArgs a) {
     }
 }
 
+template <int ATT_QT>
+__global__ void __launch_bounds__(256, ATT_QT == 1 ? 3 : 2)
+attn_mfma_kernel(AttnArgs a) {
+    attn_body<ATT_QT>(a, threadIdx.x);
+}
+
+// ---- the software-pipelined form (256 queries per block) ------------------------------------------------------
+// What the chip does with ONE wavefront's instruction stream (probe kernels: a stream of v_mfma_f32_32x32x16_bf16 with
+// K vector instructions between consecutive MFMAs): the MFMA occupies the matrix pipe for 32 clocks, and up to four
+// full-rate vector instructions or two v_exp_f32 issue behind it for free (more cost 4.2 resp. 7.3 clocks each); a
+// second wavefront on the SIMD adds no issue slots, it only fills stalls; v_dot2c_f32_bf16 next to an MFMA costs about
+// 20 clocks.  So the softmax has to ride behind the MFMAs of the SAME wavefront.  The work of a wavefront is cut into
+// units of (32 keys, 32 queries), and in every step the 4 score MFMAs of the NEXT unit and the 4 output MFMAs of the
+// PREVIOUS unit are issued alternately, with the 16 exponentials, 8 packs and 16 row-sum additions of the CURRENT unit
+// spread over the eight MFMA slots (the three are independent of each other).  The two query sub-tiles of a wavefront
+// alternate as units, so their score tiles and probability fragments are the double buffers.  Key fragments of the next
+// half tile and value fragments of the current one are refilled from LDS right behind the MFMA that last read the
+// register, eight MFMA slots before they are needed.  Because the scores of a tile's first unit are formed during the
+// previous tile, the key ring runs one tile ahead of the value ring: both have four stages of 64 keys (64 KB per block,
+// two blocks per CU), filled two tiles ahead by direct global->LDS loads, one barrier per tile.
+//
+// No softmax reference: P = 2^score as it is (the scores arrive pre-scaled by log2 e / sqrt d).  bf16 and fp32 share
+// the exponent range, and O / l does not depend on a common factor, so this is exact as long as nothing overflows or
+// underflows: the largest score of every query row within +-100 (logits of +-69 before the log2 e factor).  A block
+// that sees a row sum outside [2^-100, 2^100] (or not a number) at the end runs again through attn_body<2>, which
+// tracks a reference and takes any range.
+constexpr int ATT_PNS = 4;       // ring depth of the pipelined kernel
+constexpr float ATT_L_MAX = 1.2676506e30f, ATT_L_MIN = 7.8886091e-31f;      // 2^100, 2^-100
+
+__global__ void __launch_bounds__(256, 2)
+attn_pipe_kernel(AttnArgs a) {
+    constexpr int ATT_BQ = 256;
+    // sK: [ATT_PNS][64 keys][8 chunks of 8 d], chunk ^ ((key>>1)&7); sV behind it: [ATT_PNS][64 d][8 chunks of 8 keys],
+    // chunk ^ ((d>>1)&7).  A stage is 8 KB.
+    constexpr uint32_t STAGE = 8192, SV_OFF = ATT_PNS * STAGE;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int fr = lane & 31, fh = lane >> 5;
+
+    // ---- which (request slot, head, query tile) ---------------------------------------------------
+    int s, head, tile_in_s;
+    if (!attn_item(a, s, head, tile_in_s)) return;
+    const int S = a.geom.S;
+    const int rows_s = (a.act_off[s + 1] - a.act_off[s]) * S;            // computed query rows of this image
+    const int r0 = tile_in_s * ATT_BQ;
+    int64_t k0;
+    int nk;
+    if (a.cross_len) { k0 = (int64_t)a.perm[s] * a.cross_ld; nk = a.cross_len; }
+    else { k0 = a.cu_seqlens[s]; nk = a.seq_len ? a.seq_len[s] : a.cu_seqlens[s + 1] - a.cu_seqlens[s]; }
+
+    const uint16_t* Q = (const uint16_t*)a.Q;
+    const uint16_t* K = (const uint16_t*)a.K;
+    const uint16_t* V = (const uint16_t*)a.V;
+    const int C = a.C;
+
+    // token of query row (sub-tile qt, lane's column); rows past the image's computed rows repeat its last row
+#define PS_QTOK(qt_, tok_, ok_)                                                                                  \
+    {                                                                                                            \
+        int r_ = r0 + wave * 64 + (qt_) * 32 + fr;                                                               \
+        ok_ = r_ < rows_s;                                                                                       \
+        if (!ok_) r_ = rows_s - 1;                                                                               \
+        const int pi_ = a.act_off[s] + r_ / S;                                                                   \
+        const int p_ = a.act.active ? a.act.active[pi_] : pi_;                                                   \
+        tok_ = (int64_t)p_ * S + (r_ - (r_ / S) * S);                                                            \
+    }
+    // ---- query fragments: lane holds Q[q][16*ks + 8*fh .. +8] of its query column, both query sub-tiles
+    bf16x8 fq[2][4];
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+        int64_t tok;
+        bool ok;
+        PS_QTOK(qt, tok, ok);
+        const uint16_t* qp = Q + tok * C + head * ATT_D + fh * 8;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) fq[qt][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qp + ks * 16));
+    }
+
+    // ---- staging by direct loads: a wavefront instruction fills 8 rows x 8 chunk positions; rows lr and lr + 32
+    const int lc = lane & 7, lr = 8 * wave + (lane >> 3);
+    const int gc = lc ^ ((lr >> 1) & 7);                     // global chunk fetched into position lc (same for both rows)
+    const int steps = (nk + ATT_BKV - 1) / ATT_BKV;
+    const uint8_t* k_uni = reinterpret_cast<const uint8_t*>(K + k0 * C + head * ATT_D);
+    const uint8_t* v_uni = reinterpret_cast<const uint8_t*>(V + (int64_t)(head * ATT_D) * a.ldv + k0);
+    uint32_t k_lane[2], v_lane[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        k_lane[i] = (uint32_t)(((lr + 32 * i) * C + gc * 8) * 2);
+        v_lane[i] = (uint32_t)(((int64_t)(lr + 32 * i) * a.ldv + gc * 8) * 2);
+    }
+    typedef __attribute__((address_space(3))) uint8_t lds_u8;
+    // Two load instructions per tile and operand.  Tiles past the sequence re-load the last tile (into a stage nobody
+    // reads), so that every wavefront always has the same number of loads in flight; inside the last tile, keys /
+    // chunks past the image are clamped to valid ones: their scores are masked, their P is zero.  The clamped
+    // addresses are formed from the tile index on the spot (rare path; nothing of it is kept in registers).
+#define PS_ISSUE_K(t_)                                                                                           \
+    {                                                                                                            \
+        const int tt_ = min((t_), steps - 1);                                                                    \
+        lds_u8* dk_ = (lds_u8*)(att_smem + ((t_) & (ATT_PNS - 1)) * STAGE + wave * 1024);                        \
+        const uint8_t* kt_ = k_uni + (int64_t)tt_ * (ATT_BKV * 2) * C;                                           \
+        if ((tt_ + 1) * ATT_BKV <= nk) {                                                                         \
+            _Pragma("unroll") for (int i = 0; i < 2; ++i) {                                                      \
+                uint32_t off_ = k_lane[i];                                                                       \
+                asm volatile("" : "+v"(off_));                  /* stays a 32-bit offset beside the uniform base */ \
+                __builtin_amdgcn_global_load_lds((const void*)(kt_ + off_), (lds_void*)(dk_ + i * 4096), 16, 0, 0); \
+            }                                                                                                    \
+        } else {                                                                                                 \
+            int ln_ = lane;                                                                                      \
+            asm volatile("" : "+v"(ln_));                       /* formed here, not ahead of the loop */         \
+            const int lr_ = 8 * wave + (ln_ >> 3), gc_ = (ln_ & 7) ^ ((lr_ >> 1) & 7);                           \
+            _Pragma("unroll") for (int i = 0; i < 2; ++i) {                                                      \
+                const int row_ = min(lr_ + 32 * i, nk - 1 - tt_ * ATT_BKV);                                      \
+                __builtin_amdgcn_global_load_lds((const void*)(kt_ + (uint32_t)((row_ * C + gc_ * 8) * 2)), (lds_void*)(dk_ + i * 4096), 16, 0, 0); \
+            }                                                                                                    \
+        }                                                                                                        \
+    }
+#define PS_ISSUE_V(t_)                                                                                           \
+    {                                                                                                            \
+        const int tt_ = min((t_), steps - 1);                                                                    \
+        lds_u8* dv_ = (lds_u8*)(att_smem + SV_OFF + ((t_) & (ATT_PNS - 1)) * STAGE + wave * 1024);               \
+        const uint8_t* vt_ = v_uni + (int64_t)tt_ * (ATT_BKV * 2);                                               \
+        if ((tt_ + 1) * ATT_BKV <= nk) {                                                                         \
+            _Pragma("unroll") for (int i = 0; i < 2; ++i) {                                                      \
+                uint32_t off_ = v_lane[i];                                                                       \
+                asm volatile("" : "+v"(off_));                                                                   \
+                __builtin_amdgcn_global_load_lds((const void*)(vt_ + off_), (lds_void*)(dv_ + i * 4096), 16, 0, 0); \
+            }                                                                                                    \
+        } else {                                                                                                 \
+            int ln_ = lane;                                                                                      \
+            asm volatile("" : "+v"(ln_));                                                                        \
+            const int lr_ = 8 * wave + (ln_ >> 3), gc_ = (ln_ & 7) ^ ((lr_ >> 1) & 7);                           \
+            const int col_ = tt_ * ATT_BKV + gc_ * 8 < nk ? gc_ * 8 : -tt_ * ATT_BKV;                            \
+            _Pragma("unroll") for (int i = 0; i < 2; ++i)                                                        \
+                __builtin_amdgcn_global_load_lds((const void*)(vt_ + ((int64_t)(lr_ + 32 * i) * a.ldv + col_) * 2), (lds_void*)(dv_ + i * 4096), 16, 0, 0); \
+        }                                                                                                        \
+    }
+
+    f32x16 acc_o[2][2];
+    f32x16 acc_s[2];                                            // scores of the unit in flight, per query sub-tile
+    u32x4 fp[2][2];                                             // [query sub-tile][16-key step]: probabilities (B operand), packed bf16
+    bf16x8 fk[4], fv[4];                                        // key fragments [ks], value fragments [2*k2 + dt]
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+        acc_o[qt][0] = zero16;
+        acc_o[qt][1] = zero16;
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2) fp[qt][k2] = u32x4{0u, 0u, 0u, 0u};
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) fv[i] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});   // the first step's output MFMAs add 0 * 0
+    float l_run[2] = {0.f, 0.f};
+
+    // LDS byte addresses of this lane's fragments in stage 0.  Key fragment ks of half H: row kperm(fr) + 32 H (half 1 is
+    // 4 KB further), chunk (2 ks + fh) ^ swizzle.  Value fragment (H, k2, dt): row fr + 32 dt (dt = 1 is 4 KB further),
+    // chunk (4 H + 2 k2 + fh) ^ swizzle.  The registers follow the ring: they advance by one stage per tile.
+    uint32_t ka[4], va[4];
+    {
+        const int krow = kperm(fr), ksw = (krow >> 1) & 7, vsw = (fr >> 1) & 7;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) ka[ks] = (uint32_t)(krow * 128 + 16 * ((2 * ks + fh) ^ ksw));
+#pragma unroll
+        for (int i = 0; i < 4; ++i) va[i] = SV_OFF + (uint32_t)(fr * 128 + 16 * ((2 * i + fh) ^ vsw));
+    }
+#define PS_LDS(addr_) __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(att_smem + (addr_)))
+
+    // One MFMA slot's share of the softmax of the unit whose scores are acc_s[QT]: the two exponentials of pair G, and
+    // the bf16 pack and the two row-sum additions of pair G-1 (one slot later, so that nothing waits for an exponential).
+#define PS_SOFT(QT, G)                                                                                           \
+    {                                                                                                            \
+        if ((G) > 0) {                                                                                           \
+            fp[QT][((G) - 1) >> 2][((G) - 1) & 3] = pack_bf16x2(e0_, e1_);                                       \
+            sa_ += e0_;                                                                                          \
+            sb_ += e1_;                                                                                          \
+        }                                                                                                        \
+        if ((G) < 8) {                                                                                           \
+            e0_ = __builtin_amdgcn_exp2f(acc_s[QT][2 * (G)]);                                                    \
+            e1_ = __builtin_amdgcn_exp2f(acc_s[QT][2 * (G) + 1]);                                                \
+        }                                                                                                        \
+    }
+#define PS_MFMA_O(QT, J) acc_o[QT][(J) & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv[J], __builtin_bit_cast(bf16x8, fp[QT][(J) >> 1]), acc_o[QT][(J) & 1], 0, 0, 0)
+#define PS_MFMA_S(QT, J) acc_s[QT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk[J], fq[QT][J], (J) == 0 ? zero16 : acc_s[QT], 0, 0, 0)
+    // keys past the end of the sequence (last tile only): their scores become -inf
+#define PS_MASK(QT, KEY0)                                                                                        \
+    if ((KEY0) + 32 > nk) {                                                                                      \
+        int ln_ = lane;                                                                                          \
+        asm volatile("" : "+v"(ln_));                           /* formed here, not ahead of the loop */         \
+        _Pragma("unroll") for (int e = 0; e < 16; ++e) {                                                         \
+            const int key_ = (KEY0) + 16 * (e >> 3) + 8 * (ln_ >> 5) + (e & 7);                                  \
+            if (key_ >= nk) acc_s[QT][e] = -INFINITY;                                                            \
+        }                                                                                                        \
+    }
+#define PS_FENCE __builtin_amdgcn_sched_barrier(0)
+    // Step of unit (half H, sub-tile 0) of a tile: the score MFMAs of (H, sub-tile 1) alternate with the output MFMAs of
+    // the previous unit (sub-tile 1 of the previous half, whose value fragments are still in fv); behind its last reader
+    // each key fragment is refilled for the next half (KOFF: 4096 = second half of the stage ka points at, 0 = first half
+    // of the next stage, to which ka has then advanced) and each value fragment for half H.
+#define PS_STEP0(H, KOFF, KEY0)                                                                                  \
+    {                                                                                                            \
+        PS_MASK(0, KEY0)                                                                                         \
+        float sa_ = 0.f, sb_ = 0.f, e0_, e1_;                                                                    \
+        PS_FENCE;                                                                                                \
+        _Pragma("unroll") for (int j_ = 0; j_ < 4; ++j_) {                                                       \
+            PS_MFMA_S(1, j_);                                                                                    \
+            PS_SOFT(0, 2 * j_)                                                                                   \
+            fk[j_] = PS_LDS(ka[j_] + (KOFF));                                                                    \
+            PS_FENCE;                                                                                            \
+            PS_MFMA_O(1, j_);                                                                                    \
+            PS_SOFT(0, 2 * j_ + 1)                                                                               \
+            fv[j_] = PS_LDS(va[2 * (H) + (j_ >> 1)] + (j_ & 1) * 4096);                                          \
+            PS_FENCE;                                                                                            \
+        }                                                                                                        \
+        PS_SOFT(0, 8)                                                                                            \
+        l_run[0] += sa_ + sb_;                                                                                   \
+        PS_FENCE;                                                                                                \
+    }
+    // Step of unit (H, sub-tile 1): the score MFMAs of (next half, sub-tile 0) alternate with the output MFMAs of
+    // (H, sub-tile 0); no fragment is refilled (both sets are read again by the next step).
+#define PS_STEP1(KEY0)                                                                                           \
+    {                                                                                                            \
+        PS_MASK(1, KEY0)                                                                                         \
+        float sa_ = 0.f, sb_ = 0.f, e0_, e1_;                                                                    \
+        PS_FENCE;                                                                                                \
+        _Pragma("unroll") for (int j_ = 0; j_ < 4; ++j_) {                                                       \
+            PS_MFMA_S(0, j_);                                                                                    \
+            PS_SOFT(1, 2 * j_)                                                                                   \
+            PS_FENCE;                                                                                            \
+            PS_MFMA_O(0, j_);                                                                                    \
+            PS_SOFT(1, 2 * j_ + 1)                                                                               \
+            PS_FENCE;                                                                                            \
+        }                                                                                                        \
+        PS_SOFT(1, 8)                                                                                            \
+        l_run[1] += sa_ + sb_;                                                                                   \
+        PS_FENCE;                                                                                                \
+    }
+
+    // ---- prologue: K tiles 0..2 and V tiles 0..1 in flight (three groups, oldest first), scores of the first unit
+    PS_ISSUE_K(0);
+    PS_ISSUE_K(1);
+    PS_ISSUE_V(0);
+    PS_ISSUE_K(2);
+    PS_ISSUE_V(1);
+    asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");          // K tile 0 has landed everywhere
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) fk[ks] = PS_LDS(ka[ks]);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) PS_MFMA_S(0, ks);
+
+    for (int t = 0; t < steps; ++t) {
+        // K tile t+1 and V tile t have landed (the loads of the previous iteration may be in flight) and every
+        // wavefront has left iteration t-1: the stages of K tile t-1 and V tile t-2 are free.
+        asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory");
+        PS_ISSUE_K(t + 3);
+        PS_ISSUE_V(t + 2);
+        const int kv0 = t * ATT_BKV;
+        const uint32_t adv = ((t & (ATT_PNS - 1)) == ATT_PNS - 1) ? (uint32_t)(-(int)((ATT_PNS - 1) * STAGE)) : STAGE;
+        PS_STEP0(0, 4096, kv0);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) ka[ks] += adv;           // the key fragments now come from the next tile's stage
+        PS_STEP1(kv0);
+        PS_STEP0(1, 0, kv0 + 32);
+        PS_STEP1(kv0 + 32);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) va[i] += adv;
+    }
+    // ---- epilogue: output MFMAs of the last unit
+#pragma unroll
+    for (int j_ = 0; j_ < 4; ++j_) PS_MFMA_O(1, j_);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");        // no load may still target LDS when the block moves on
+#undef PS_STEP0
+#undef PS_STEP1
+#undef PS_FENCE
+#undef PS_MASK
+#undef PS_MFMA_S
+#undef PS_MFMA_O
+#undef PS_SOFT
+#undef PS_LDS
+#undef PS_ISSUE_K
+#undef PS_ISSUE_V
+
+    // ---- row sums; a row sum out of range (or not a number) anywhere in the block: the whole block again, with a
+    // softmax reference (the vote goes through LDS, which nobody reads any more after the barrier)
+    float inv[2];
+    bool fine = true;
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+        const float l = l_run[qt] + other_half(l_run[qt]);
+        fine = fine && l >= ATT_L_MIN && l <= ATT_L_MAX;
+        inv[qt] = 1.f / l;
+    }
+    __syncthreads();
+    int32_t* vote = reinterpret_cast<int32_t*>(att_smem);
+    if (tid < 4) vote[tid] = 0;
+    __syncthreads();
+    if (lane == 0 && __any(!fine)) vote[wave] = 1;
+    __syncthreads();
+    const bool redo = (vote[0] | vote[1] | vote[2] | vote[3]) != 0;
+    __syncthreads();
+    if (redo) {
+        // the thread index through an opaque move: nothing of the second pass is computed (and kept in registers)
+        // ahead of the loop above
+        int tid2 = threadIdx.x;
+        asm volatile("" : "+v"(tid2));
+        attn_body<2>(a, tid2);
+        return;
+    }
+
+    // ---- O[q][head*64 + d] = O^T / l ; lane holds d = 32*dt + 8*(e/4) + 4*fh + e%4 of query fr
+    uint16_t* O = (uint16_t*)a.O;
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+        int64_t tok;
+        bool ok;
+        PS_QTOK(qt, tok, ok);
+        if (!ok) continue;
+        // A lane holds four consecutive d (8 bytes) of its query per (dt, eg), lane ^ 32 the next four.  The two halves
+        // trade them so that the lower half owns the even eg chunks and the upper half the odd ones: 16-byte stores.
+        uint16_t* op = O + tok * C + head * ATT_D + 8 * fh;
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int eg = 0; eg < 4; eg += 2) {
+                uint32_t w[2][2];               // [eg parity][dword]
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    w[q][0] = pack_bf16x2(acc_o[qt][dt][4 * (eg + q)] * inv[qt], acc_o[qt][dt][4 * (eg + q) + 1] * inv[qt]);
+                    w[q][1] = pack_bf16x2(acc_o[qt][dt][4 * (eg + q) + 2] * inv[qt], acc_o[qt][dt][4 * (eg + q) + 3] * inv[qt]);
+                }
+                const auto r0_ = __builtin_amdgcn_permlane32_swap(w[0][0], w[1][0], false, false);
+                const auto r1_ = __builtin_amdgcn_permlane32_swap(w[0][1], w[1][1], false, false);
+                *reinterpret_cast<u32x4*>(op + dt * 32 + eg * 8) = u32x4{r0_[0], r1_[0], r0_[1], r1_[1]};
+            }
+    }
+#undef PS_QTOK
+}
+
 // One block: per request slot, number of computed patches and of query tiles (exclusive prefixes).
 __global__ void attn_tiles_kernel(const int32_t* __restrict__ request_offset, const uint8_t* __restrict__ mask, int32_t n,
                                   int32_t S, int32_t ATT_BQ, int32_t* __restrict__ act_off, int32_t* __restrict__ tile_off) {
@@ -366,16 +718,13 @@ int attention_mfma_bf16(const AttnArgs& a, hipStream_t st, bool* handled) {
     }
     *handled = true;
     const int64_t items = (int64_t)a.max_tiles * a.heads;
-    const unsigned grid = (unsigned)(8 * cdiv(items, 8));
+    const unsigned grid = (unsigned)(8 * ATT_GROUP * cdiv(items, 8 * ATT_GROUP));
     constexpr int lds = ATT_NS * 2 * 512 * 16;
-    static bool attr_set = false;
-    if (!attr_set) {
-        PS_CHECK_HIP(hipFuncSetAttribute((const void*)attn_mfma_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-        PS_CHECK_HIP(hipFuncSetAttribute((const void*)attn_mfma_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-        attr_set = true;
-    }
+    constexpr int lds_pipe = ATT_PNS * 2 * 512 * 16;
+    PS_SET_LDS_ONCE(attn_mfma_kernel<1>, lds);
+    PS_SET_LDS_ONCE(attn_pipe_kernel, lds_pipe);
     if (a.qt == 1) attn_mfma_kernel<1><<<grid, 256, lds, st>>>(a);
-    else attn_mfma_kernel<2><<<grid, 256, lds, st>>>(a);
+    else attn_pipe_kernel<<<grid, 256, lds_pipe, st>>>(a);
     return check_launch("attn_mfma_kernel");
 }
 

@@ -386,7 +386,7 @@ int pserve_profile_select(const char* label) {
     return PSERVE_OK;
 }
 
-int pserve_profile_read(pserve_prof_entry* out, int32_t max, int32_t* count) {
+static int profile_read_impl(pserve_prof_entry* out, int32_t max, int32_t* count) {
     PS_REQUIRE(out && count && max > 0, "pserve_profile_read: bad arguments");
     int n = 0;
     for (const ProfRecord& r : g_prof.recs) {
@@ -410,7 +410,11 @@ int pserve_profile_read(pserve_prof_entry* out, int32_t max, int32_t* count) {
     return PSERVE_OK;
 }
 
-int pserve_block_create(const pserve_block_desc* desc, const pserve_block_params* params, void* stream, pserve_block_t** out) {
+int pserve_profile_read(pserve_prof_entry* out, int32_t max, int32_t* count) {
+    return guarded("pserve_profile_read", [&] { return profile_read_impl(out, max, count); });
+}
+
+static int block_create_impl(const pserve_block_desc* desc, const pserve_block_params* params, void* stream, pserve_block_t** out) {
     PS_REQUIRE(out, "pserve_block_create: out is NULL");
     *out = nullptr;
     PS_REQUIRE(desc && params, "pserve_block_create: NULL argument");
@@ -567,9 +571,13 @@ int pserve_block_create(const pserve_block_desc* desc, const pserve_block_params
     return PSERVE_OK;
 }
 
+int pserve_block_create(const pserve_block_desc* desc, const pserve_block_params* params, void* stream, pserve_block_t** out) {
+    return guarded("pserve_block_create", [&] { return block_create_impl(desc, params, stream, out); });
+}
+
 void pserve_block_free(pserve_block_t* block) { delete block; }
 
-int pserve_cache_create(const pserve_plan_t* plan, const pserve_block_t* block, int with_slots, pserve_cache_t** out) {
+static int cache_create_impl(const pserve_plan_t* plan, const pserve_block_t* block, int with_slots, pserve_cache_t** out) {
     PS_REQUIRE(out, "pserve_cache_create: out is NULL");
     *out = nullptr;
     PS_REQUIRE(plan && block, "pserve_cache_create: NULL argument");
@@ -685,6 +693,10 @@ int pserve_cache_create(const pserve_plan_t* plan, const pserve_block_t* block, 
     guard.p = nullptr;
     *out = c;
     return PSERVE_OK;
+}
+
+int pserve_cache_create(const pserve_plan_t* plan, const pserve_block_t* block, int with_slots, pserve_cache_t** out) {
+    return guarded("pserve_cache_create", [&] { return cache_create_impl(plan, block, with_slots, out); });
 }
 
 void pserve_cache_free(pserve_cache_t* cache) { delete cache; }

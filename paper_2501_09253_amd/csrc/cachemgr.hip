@@ -2,6 +2,7 @@
 // ("Patch-aware Caching Strategy", step 1) and the Common / New / Expired id sets of "Batching Patches in Cache".
 #include "common.h"
 
+#include <new>
 #include <unordered_map>
 
 namespace pserve {
@@ -85,7 +86,9 @@ using namespace pserve;
 
 extern "C" {
 
-int pserve_patch_mse(const pserve_plan_t* plan, const void* a, const void* b, int32_t C, int dtype, float* out, void* stream) {
+// both entry points: partial sums of every (patch, chunk) into `partial` [P][16], then one thread per patch
+static int patch_mse_launch(const pserve_plan_t* plan, const void* a, const void* b, int32_t C, int dtype, float* partial,
+                            float* out, void* stream) {
     PS_REQUIRE(plan && a && b && out, "pserve_patch_mse: NULL argument");
     PS_REQUIRE(dtype == PSERVE_F32 || dtype == PSERVE_BF16, "pserve_patch_mse: unknown dtype %d", dtype);
     const int vn = dtype == PSERVE_BF16 ? 8 : 4;
@@ -98,13 +101,17 @@ int pserve_patch_mse(const pserve_plan_t* plan, const void* a, const void* b, in
     dim3 grid(plan->P, MSE_SPLIT);
     const int nt = (int)cdiv(TL * CV, 64) * 64;
     if (dtype == PSERVE_BF16)
-        patch_mse_partial_kernel<uint16_t><<<grid, nt, 0, st>>>((const uint16_t*)a, (const uint16_t*)b, C, plan->S, TL, plan->mse_partial);
+        patch_mse_partial_kernel<uint16_t><<<grid, nt, 0, st>>>((const uint16_t*)a, (const uint16_t*)b, C, plan->S, TL, partial);
     else
-        patch_mse_partial_kernel<float><<<grid, nt, 0, st>>>((const float*)a, (const float*)b, C, plan->S, TL, plan->mse_partial);
+        patch_mse_partial_kernel<float><<<grid, nt, 0, st>>>((const float*)a, (const float*)b, C, plan->S, TL, partial);
     PS_TRY(check_launch("patch_mse_partial_kernel"));
-    patch_mse_final_kernel<<<(unsigned)cdiv(plan->P, 256), 256, 0, st>>>(plan->mse_partial, plan->P,
-                                                                       1.f / ((float)plan->S * (float)C), out);
+    patch_mse_final_kernel<<<(unsigned)cdiv(plan->P, 256), 256, 0, st>>>(partial, plan->P, 1.f / ((float)plan->S * (float)C), out);
     return check_launch("patch_mse_final_kernel");
+}
+
+int pserve_patch_mse(const pserve_plan_t* plan, const void* a, const void* b, int32_t C, int dtype, float* out, void* stream) {
+    PS_REQUIRE(plan, "pserve_patch_mse: NULL argument");
+    return patch_mse_launch(plan, a, b, C, dtype, plan->mse_partial, out, stream);
 }
 
 int pserve_cache_sets(const pserve_plan_t* old_plan, const int64_t* old_ids, const pserve_plan_t* new_plan,
@@ -113,6 +120,7 @@ int pserve_cache_sets(const pserve_plan_t* old_plan, const int64_t* old_ids, con
     PS_REQUIRE(old_plan->ph == new_plan->ph && old_plan->pw == new_plan->pw,
                "pserve_cache_sets: the two plans use different patch sizes (%dx%d vs %dx%d)", old_plan->ph, old_plan->pw,
                new_plan->ph, new_plan->pw);
+    try {
     // ids the cache holds -> caller index in the old batch
     std::unordered_map<int64_t, int32_t> held;
     held.reserve((size_t)old_plan->n * 2);
@@ -150,6 +158,13 @@ int pserve_cache_sets(const pserve_plan_t* old_plan, const int64_t* old_ids, con
     PS_CHECK_HIP(hipMemcpyAsync(patch_src, h_src.data(), h_src.size() * sizeof(int32_t), hipMemcpyHostToDevice, st));
     PS_CHECK_HIP(hipStreamSynchronize(st));                          // h_src dies with this call
     return PSERVE_OK;
+    } catch (const std::bad_alloc&) {                                // nothing may unwind across the C boundary
+        set_error("pserve_cache_sets: out of host memory");
+        return PSERVE_ENOMEM;
+    } catch (...) {
+        set_error("pserve_cache_sets: unexpected exception");
+        return PSERVE_EINVAL;
+    }
 }
 
 }  // extern "C"

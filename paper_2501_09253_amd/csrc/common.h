@@ -6,6 +6,8 @@
 #include <stdint.h>
 #include <stdio.h>
 #include <stdarg.h>
+#include <mutex>
+#include <new>
 #include <vector>
 #include <algorithm>
 
@@ -39,6 +41,17 @@ void set_error(const char* fmt, ...);
         if (_s != PSERVE_OK) return _s;                                                 \
     } while (0)
 
+// Raise a kernel's dynamic LDS limit once per process; safe when two host threads make their first launch together.
+#define PS_SET_LDS_ONCE(fn, bytes)                                                      \
+    do {                                                                                \
+        static std::once_flag _once;                                                    \
+        static hipError_t _err = hipSuccess;                                            \
+        std::call_once(_once, [&] {                                                     \
+            _err = hipFuncSetAttribute((const void*)(fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)(bytes)); \
+        });                                                                             \
+        PS_CHECK_HIP(_err);                                                             \
+    } while (0)
+
 inline int check_launch(const char* what) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
@@ -46,6 +59,21 @@ inline int check_launch(const char* what) {
         return PSERVE_EHIP;
     }
     return PSERVE_OK;
+}
+
+// Runs the body of an entry point; no exception may unwind across the C boundary (the bodies use the standard
+// containers, whose allocations can throw).
+template <class F>
+inline int guarded(const char* who, F&& body) {
+    try {
+        return body();
+    } catch (const std::bad_alloc&) {
+        set_error("%s: out of host memory", who);
+        return PSERVE_ENOMEM;
+    } catch (...) {
+        set_error("%s: unexpected exception", who);
+        return PSERVE_EINVAL;
+    }
 }
 
 inline size_t dtype_size(int dtype) { return dtype == PSERVE_BF16 ? 2 : 4; }

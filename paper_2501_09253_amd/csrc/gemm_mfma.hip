@@ -848,11 +848,7 @@ template <int BM, int BN, int WGM, int WGN, int APIX, int NSB, int KS = 1>
 static int launch_conv(const GemmArgs& a, const ConvTile& ct, hipStream_t st) {
     constexpr size_t lds = (size_t)(NSB * BN + 2 * APIX) * 128 + BM * sizeof(int32_t) + 64 * sizeof(int32_t);
     static_assert(lds <= 160 * 1024, "conv LDS budget");
-    static bool attr_set = false;
-    if (!attr_set) {
-        PS_CHECK_HIP(hipFuncSetAttribute((const void*)conv_mfma_kernel<BM, BN, WGM, WGN, APIX, NSB, KS>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_set = true;
-    }
+    PS_SET_LDS_ONCE((conv_mfma_kernel<BM, BN, WGM, WGN, APIX, NSB, KS>), lds);
     const unsigned grid = (unsigned)(8 * cdiv(cdiv(a.M, BM), 8) * (a.N / BN));
     conv_mfma_kernel<BM, BN, WGM, WGN, APIX, NSB, KS><<<grid, 256 * KS, lds, st>>>(a, ct);
     return check_launch("conv_mfma_kernel");
@@ -880,12 +876,7 @@ static bool conv_tile(const GemmArgs& a, int BM, int apix_max, ConvTile* ct) {
 template <int BM, int BN, bool GEGLU, int WGM, int WGN, int NS, bool OVERLAP>
 static int launch(const GemmArgs& a, hipStream_t st) {
     constexpr size_t lds = GemmCfg<BM, BN, NS, OVERLAP>::LDS;
-    static bool attr_set = false;
-    if (!attr_set) {
-        PS_CHECK_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<BM, BN, GEGLU, WGM, WGN, NS, OVERLAP>,
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_set = true;
-    }
+    PS_SET_LDS_ONCE((gemm_mfma_kernel<BM, BN, GEGLU, WGM, WGN, NS, OVERLAP>), lds);
     // all tiles, or as many blocks as run at once (256 CUs x the blocks of this LDS size per CU): each block then
     // walks over several tiles
     const int64_t all = 8 * cdiv(cdiv(a.M, BM), 8) * (a.N / BN);

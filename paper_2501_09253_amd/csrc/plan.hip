@@ -317,7 +317,7 @@ int pserve_text_gather(const pserve_plan_t* plan, const void* x, int32_t C, int 
     return run_text<false>(plan, const_cast<void*>(x), text, C, dtype, (hipStream_t)stream);
 }
 
-int pserve_plan_text(const int32_t* res, int32_t n, int32_t ph, int32_t pw, int32_t text_len, void* stream,
+static int plan_text_impl(const int32_t* res, int32_t n, int32_t ph, int32_t pw, int32_t text_len, void* stream,
                      pserve_plan_t** out) {
     PS_REQUIRE(out, "pserve_plan: out is NULL");
     PS_REQUIRE(text_len >= 0, "pserve_plan: negative text_len");
@@ -403,6 +403,11 @@ int pserve_plan_text(const int32_t* res, int32_t n, int32_t ph, int32_t pw, int3
     guard.p = nullptr;
     *out = pl;
     return PSERVE_OK;
+}
+
+int pserve_plan_text(const int32_t* res, int32_t n, int32_t ph, int32_t pw, int32_t text_len, void* stream,
+                     pserve_plan_t** out) {
+    return guarded("pserve_plan_text", [&] { return plan_text_impl(res, n, ph, pw, text_len, stream, out); });
 }
 
 void pserve_plan_free(pserve_plan_t* plan) { delete plan; }

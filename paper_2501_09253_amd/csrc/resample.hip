@@ -36,7 +36,7 @@ static int check_pair(const pserve_resample_t* op, const pserve_plan_t* in, cons
 
 extern "C" {
 
-int pserve_resample_create(int kind, int32_t C_in, int32_t C_out, int dtype, const void* w, const void* b, void* stream,
+static int resample_create_impl(int kind, int32_t C_in, int32_t C_out, int dtype, const void* w, const void* b, void* stream,
                            pserve_resample_t** out) {
     PS_REQUIRE(out, "pserve_resample_create: out is NULL");
     *out = nullptr;
@@ -64,6 +64,11 @@ int pserve_resample_create(int kind, int32_t C_in, int32_t C_out, int dtype, con
     guard.p = nullptr;
     *out = r;
     return PSERVE_OK;
+}
+
+int pserve_resample_create(int kind, int32_t C_in, int32_t C_out, int dtype, const void* w, const void* b, void* stream,
+                           pserve_resample_t** out) {
+    return guarded("pserve_resample_create", [&] { return resample_create_impl(kind, C_in, C_out, dtype, w, b, stream, out); });
 }
 
 void pserve_resample_free(pserve_resample_t* op) { delete op; }

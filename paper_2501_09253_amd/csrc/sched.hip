@@ -64,7 +64,7 @@ int pserve_latency_predict(const pserve_latency_model* model, const pserve_task*
     return PSERVE_OK;
 }
 
-int pserve_latency_fit(const double* X, const double* y, int32_t m, pserve_latency_model* model) {
+static int latency_fit_impl(const double* X, const double* y, int32_t m, pserve_latency_model* model) {
     PS_REQUIRE(X && y && model && m >= 4, "pserve_latency_fit: needs at least 4 samples");
     // normal equations of y ~ [1, X] (4 unknowns), solved by Gaussian elimination with partial pivoting
     double A[4][5] = {};
@@ -93,13 +93,17 @@ int pserve_latency_fit(const double* X, const double* y, int32_t m, pserve_laten
     return PSERVE_OK;
 }
 
+int pserve_latency_fit(const double* X, const double* y, int32_t m, pserve_latency_model* model) {
+    return guarded("pserve_latency_fit", [&] { return latency_fit_impl(X, y, m, model); });
+}
+
 int pserve_slack(const pserve_task* task, double now, double latency, double* slack) {
     PS_REQUIRE(task && slack && task->standalone > 0.0, "pserve_slack: bad argument");
     *slack = slack_of(*task, now, latency);
     return PSERVE_OK;
 }
 
-int pserve_schedule(const pserve_task* wait, int32_t n_wait, const pserve_task* active, int32_t n_active, double now,
+static int schedule_impl(const pserve_task* wait, int32_t n_wait, const pserve_task* active, int32_t n_active, double now,
                     const pserve_latency_model* model, int32_t ph, int32_t pw, double relaxed_slack,
                     int32_t* admitted, int32_t* n_admitted, int32_t* discarded, int32_t* n_discarded) {
     PS_REQUIRE(model && admitted && n_admitted && discarded && n_discarded && n_wait >= 0 && n_active >= 0 &&
@@ -155,6 +159,12 @@ int pserve_schedule(const pserve_task* wait, int32_t n_wait, const pserve_task* 
     *n_admitted = na;
     *n_discarded = nd;
     return PSERVE_OK;
+}
+
+int pserve_schedule(const pserve_task* wait, int32_t n_wait, const pserve_task* active, int32_t n_active, double now,
+                    const pserve_latency_model* model, int32_t ph, int32_t pw, double relaxed_slack,
+                    int32_t* admitted, int32_t* n_admitted, int32_t* discarded, int32_t* n_discarded) {
+    return guarded("pserve_schedule", [&] { return schedule_impl(wait, n_wait, active, n_active, now, model, ph, pw, relaxed_slack, admitted, n_admitted, discarded, n_discarded); });
 }
 
 }  // extern "C"

@@ -297,30 +297,60 @@ def test_config_bf16_full_size(cfg_id):
     assert err < 2e-2
 
 
+def _sample_rows(cfg, reuse, H, W, count):
+    """`count` distinct query tokens (n = y*W + x) of an H x W image: one token of every computed patch first, the rest a
+    seeded draw without replacement."""
+    ph, pw = cfg.patch
+    pick = []
+    u = wl.Stream(cfg.seed, "sample.patch").uniform(reuse.size)
+    for k, (r, c) in enumerate(np.argwhere(~reuse)):
+        t = int(u[k] * ph * pw)
+        pick.append((r * ph + t // pw) * W + c * pw + t % pw)
+    order = np.argsort(wl.Stream(cfg.seed, "sample").uniform(H * W), kind="stable")     # a seeded permutation
+    seen = set(pick)
+    for t in order:
+        if len(pick) >= count:
+            break
+        if int(t) not in seen:
+            pick.append(int(t))
+            seen.add(int(t))
+    rows = np.sort(np.array(pick, dtype=np.int64))
+    assert len(np.unique(rows)) == count
+    return rows
+
+
 def test_config5_reuse_full_size_sampled():
-    """Config 5 at full size.  The 16 small images are compared in full; for the 65,536-token image the oracle
-    computes a seeded sample of 2,048 query tokens (each attention row is independent given all keys/values)."""
+    """Config 5 at full size.  The 16 small images are compared in full; for the 65,536-token image the oracle computes
+    4,096 distinct query tokens (each attention row is independent given all keys / values), at least one in every
+    computed patch.  After the call every operand slot of every image (and the output slot of the small images) is
+    compared as well: fresh on computed patches, bit for bit the old value on reused ones."""
     cfg = wl.config(5)
     w = wl.make_workload(cfg)
     run = GpuRun(w)
     run.load_cache()
     got = run.forward_images(reuse=w.reuse)
+    slots = run.read_cache()
     ph, pw = cfg.patch
-    worst = 0.0
+    worst = worst_slot = 0.0
     for i, z in enumerate(w.images):
         c_i = {k: v[i] for k, v in w.cache.items()}
         H, W = cfg.resolutions[i]
-        rows = None
-        if H * W > 8192:
-            rows = np.sort(wl.Stream(cfg.seed, "sample").randint(2048, H * W))
-        ref, _ = ob.block_forward(z, cfg.stages, w.params, G=cfg.G, heads=cfg.heads, eps=cfg.eps, reuse=w.reuse[i],
-                                  cache=c_i, rows=rows)
+        rows = _sample_rows(cfg, w.reuse[i], H, W, 4096) if H * W > 8192 else None
+        ref, ref_slots = ob.block_forward(z, cfg.stages, w.params, G=cfg.G, heads=cfg.heads, eps=cfg.eps, reuse=w.reuse[i],
+                                          cache=c_i, rows=rows)
         g = got[i].reshape(cfg.C, -1).T[rows] if rows is not None else got[i]
         worst = max(worst, float(np.abs(g - ref).max()) / float(np.abs(ref).max()))
         m = np.kron(w.reuse[i], np.ones((ph, pw))).astype(bool)
         assert np.array_equal(got[i][:, m], w.cache["y"][i][:, m])
-    print(f"config 5: rel err {worst:.3e}")
-    assert worst < 2e-2
+        assert set(ref_slots) == set(slots) - ({"y"} if rows is not None else set())
+        for name, want in ref_slots.items():
+            have = slots[name][i]
+            worst_slot = max(worst_slot, float(np.abs(have - want).max()) / float(np.abs(want).max()))
+            assert np.array_equal(have[:, m], w.cache[name][i][:, m]), (name, i)
+        if rows is not None:                                     # the output slot of the large image: what the call returned
+            assert np.array_equal(slots["y"][i], got[i])
+    print(f"config 5: rel err {worst:.3e}, slots {worst_slot:.3e}")
+    assert worst < 2e-2 and worst_slot < 2e-2
 
 
 # ----------------------------------------------------------------------------- random stage lists

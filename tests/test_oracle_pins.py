@@ -419,6 +419,28 @@ def test_block_rows_subset_matches_full():
     assert np.allclose(sub, full.reshape(16, -1).T[rows], atol=1e-12)
 
 
+@pytest.mark.parametrize("stages", [(wl.RES2, wl.SATTN), (wl.SATTN,), (wl.RES2, wl.LSATTN, wl.LFFN)])
+def test_block_rows_subset_with_reuse_matches_full(stages):
+    """Sampled query rows under a reuse mask: the rows that fall on reused patches are the cached output, the others
+    the fresh one, and every operand slot after the call is the one of the full run (the exit used for the large image
+    of the skewed configuration)."""
+    cfg = wl.custom_config([(8, 12)], (4, 4), C=16, G=4, heads=2, stages=stages, reuse_p=0.5, seed=17)
+    w = wl.make_workload(cfg)
+    c0 = {k: v[0] for k, v in w.cache.items()}
+    assert w.reuse[0].any() and not w.reuse[0].all()
+    full, nc_full = ob.block_forward(w.images[0], cfg.stages, w.params, G=cfg.G, heads=cfg.heads, reuse=w.reuse[0], cache=c0)
+    rows = np.arange(0, 96, 5)                                   # rows on reused and on computed patches
+    px = np.kron(w.reuse[0], np.ones((4, 4))).astype(bool).reshape(-1)
+    assert px[rows].any() and not px[rows].all()
+    sub, nc_sub = ob.block_forward(w.images[0], cfg.stages, w.params, G=cfg.G, heads=cfg.heads, reuse=w.reuse[0], cache=c0,
+                                   rows=rows)
+    assert np.allclose(sub, full.reshape(16, -1).T[rows], atol=1e-12)
+    assert np.array_equal(sub[px[rows]], c0["y"].reshape(16, -1).T[rows][px[rows]])
+    for name, slot in nc_sub.items():                            # "y" is not formed on a row subset
+        assert np.array_equal(slot, nc_full[name]), name
+    assert set(nc_full) - set(nc_sub) == {"y"}
+
+
 # ----------------------------------------------------------------------------- cache reuse semantics
 def _reuse_setup():
     cfg = wl.custom_config([(8, 8), (4, 8)], (4, 4), C=8, G=2, heads=2, stages=(wl.RES2, wl.SATTN),
