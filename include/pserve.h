@@ -251,6 +251,17 @@ int  pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const v
  * Errors: EINVAL, ESTATE (old cache never filled). */
 int  pserve_patch_mse(const pserve_plan_t* plan, const void* a, const void* b, int32_t C, int dtype,
                       float* out, void* stream);
+/* pserve_patch_mse for callers that cannot allocate device memory or own a plan-side scratch: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same result bit
+ * for bit; the partial sums go to a fixed array inside the library's device image (PSERVE_MSE_STATIC_MAX_PATCHES * 16
+ * floats = 1 MiB per GPU, held until the process ends) instead of the plan's scratch.  The call allocates nothing and
+ * frees nothing.  Every call on one GPU shares that array: calls that overlap on the same GPU (two streams, two
+ * threads) race; calls on different GPUs do not.  Nothing needs clearing between calls (every entry read is written
+ * first by the same call).
+ * Errors: as pserve_patch_mse, and EINVAL when the plan has more than PSERVE_MSE_STATIC_MAX_PATCHES patches. */
+#define PSERVE_MSE_STATIC_MAX_PATCHES 16384
+int  pserve_patch_mse_static(const pserve_plan_t* plan, const void* a, const void* b, int32_t C, int dtype,
+                             float* out, void* stream);
 int  pserve_cache_sets(const pserve_plan_t* old_plan, const int64_t* old_ids, const pserve_plan_t* new_plan,
                        const int64_t* new_ids, int32_t* req_src, uint8_t* expired, int32_t* patch_src,
                        void* stream);

@@ -14,6 +14,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
 F32, BF16 = 0, 1
+MSE_STATIC_MAX_PATCHES = 16384      # PSERVE_MSE_STATIC_MAX_PATCHES
 STAGE_KIND = {"RES1": 1, "RES2": 2, "SATTN": 3, "XATTN": 4, "FFN": 5, "LSATTN": 6, "LXATTN": 7, "LFFN": 8, "RES2T": 9, "ASATTN": 10, "AMLP": 11, "MMDIT": 12}
 TABLES = {"perm": 0, "request_offset": 1, "res_offset": 2, "res_hw": 3, "patch_owner": 4,
           "patch_rc": 5, "neighbour": 6, "halo_src": 7, "cu_seqlens": 8, "seq_len": 9}
@@ -116,6 +117,7 @@ def lib() -> C.CDLL:
     L.pserve_profile_select.argtypes = [C.c_char_p]
     L.pserve_profile_sample.argtypes = [C.c_int]
     L.pserve_patch_mse.argtypes = [vp, vp, vp, i32, C.c_int, vp, vp]
+    L.pserve_patch_mse_static.argtypes = [vp, vp, vp, i32, C.c_int, vp, vp]
     L.pserve_probe_mfma_bf16.argtypes = [C.c_int, C.POINTER(C.c_double), vp]
     L.pserve_probe_copy.argtypes = [vp, vp, C.c_size_t, C.c_int, C.POINTER(C.c_double), vp]
     L.pserve_cache_sets.argtypes = [vp, C.POINTER(C.c_int64), vp, C.POINTER(C.c_int64), C.POINTER(i32),
@@ -276,6 +278,17 @@ class Plan:
         out = torch.empty(self.P, dtype=torch.float32, device=a.device)
         dt = BF16 if a.dtype == torch.bfloat16 else F32
         _check(lib().pserve_patch_mse(self._h, a.data_ptr(), b.data_ptr(), a.shape[1], dt, out.data_ptr(), _stream()))
+        return out
+
+    def patch_mse_static(self, a, b, out=None):
+        """pserve_patch_mse_static: the same result through the library's fixed device scratch; allocates nothing when
+        `out` (float32 [P]) is given."""
+        import torch
+        assert a.shape == b.shape and a.dtype == b.dtype and a.is_contiguous() and b.is_contiguous() and a.shape[0] == self.T
+        if out is None:
+            out = torch.empty(self.P, dtype=torch.float32, device=a.device)
+        dt = BF16 if a.dtype == torch.bfloat16 else F32
+        _check(lib().pserve_patch_mse_static(self._h, a.data_ptr(), b.data_ptr(), a.shape[1], dt, out.data_ptr(), _stream()))
         return out
 
     def cache_sets(self, ids, old_plan: "Plan", old_ids):

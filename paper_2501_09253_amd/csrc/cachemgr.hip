@@ -2,10 +2,36 @@
 // ("Patch-aware Caching Strategy", step 1) and the Common / New / Expired id sets of "Batching Patches in Cache".
 #include "common.h"
 
+#include <mutex>
 #include <new>
 #include <unordered_map>
 
 namespace pserve {
+
+// Partial sums of pserve_patch_mse_static: a fixed array in device memory (one copy per GPU, held until the process
+// ends) for callers that may not allocate.  Host code never uses this name as an address: it asks the runtime for
+// the array's address on the current device once and passes that pointer on.
+constexpr int MSE_STATIC_MAX_PATCHES = PSERVE_MSE_STATIC_MAX_PATCHES;
+static __device__ __align__(256) float scratch[MSE_STATIC_MAX_PATCHES * 16];
+constexpr int MSE_MAX_DEVICES = 64;
+static float* g_scratch_ptr[MSE_MAX_DEVICES] = {};
+static std::mutex g_scratch_mutex;
+
+// address of `scratch` on the current device (looked up once per device, with that device current)
+static int static_scratch(float** out) {
+    int dev = -1;
+    PS_CHECK_HIP(hipGetDevice(&dev));
+    PS_REQUIRE(dev >= 0 && dev < MSE_MAX_DEVICES, "pserve_patch_mse_static: device index %d not supported", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        float* ptr = nullptr;
+        PS_CHECK_HIP(hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)));
+        PS_REQUIRE(ptr != nullptr, "pserve_patch_mse_static: no address for the scratch array on device %d", dev);
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return PSERVE_OK;
+}
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
@@ -112,6 +138,17 @@ static int patch_mse_launch(const pserve_plan_t* plan, const void* a, const void
 int pserve_patch_mse(const pserve_plan_t* plan, const void* a, const void* b, int32_t C, int dtype, float* out, void* stream) {
     PS_REQUIRE(plan, "pserve_patch_mse: NULL argument");
     return patch_mse_launch(plan, a, b, C, dtype, plan->mse_partial, out, stream);
+}
+
+int pserve_patch_mse_static(const pserve_plan_t* plan, const void* a, const void* b, int32_t C, int dtype, float* out,
+                            void* stream) {
+    PS_REQUIRE(plan, "pserve_patch_mse_static: NULL argument");
+    PS_REQUIRE(plan->P <= MSE_STATIC_MAX_PATCHES, "pserve_patch_mse_static: %d patches exceed the fixed scratch of %d patches",
+               plan->P, MSE_STATIC_MAX_PATCHES);
+    float* partial = nullptr;
+    PS_TRY(static_scratch(&partial));
+    // every (patch, chunk) entry the second kernel reads is written by the first one: nothing to clear between calls
+    return patch_mse_launch(plan, a, b, C, dtype, partial, out, stream);
 }
 
 int pserve_cache_sets(const pserve_plan_t* old_plan, const int64_t* old_ids, const pserve_plan_t* new_plan,
