@@ -354,12 +354,15 @@ int  pserve_profile_read(pserve_prof_entry* out, int32_t max, int32_t* count);
 /* ---- peak probes for measurements (no operation of the paper; they give the roofline figures a second reference
  * beside the datasheet).  Both time their own launches with a pair of events on `stream` and wait for them.
  * pserve_probe_mfma_bf16: 512 blocks of four wavefronts, each wavefront issuing 8 * iters independent
- * v_mfma_f32_32x32x16_bf16 on register-resident operands; *tflops = dense bf16 rate reached.
+ * v_mfma_f32_32x32x16_bf16 on register-resident operands: all 1.0 (random_operands = 0) or standard normals rounded to
+ * bf16 (random_operands = 1).  *tflops = dense bf16 rate reached; *mhz (may be NULL) = shader clock inside the timed
+ * loop (core cycles per tick of the 100 MHz wall clock).  The chip lowers its clock with the bit activity of the
+ * operands, so the second form is the rate a real workload's matrix products can reach.
  * pserve_probe_copy: a plain 16-byte-per-lane copy of `bytes` bytes from src to dst (DEVICE, 16-byte aligned, not
  * overlapping), `reps` launches; *gbs = (bytes read + bytes written) per second.  A buffer well beyond the 256 MB
  * last-level cache gives the HBM figure; the same launch is the known-size reference for memory counters.
  * Errors: EINVAL, EHIP. */
-int  pserve_probe_mfma_bf16(int iters, double* tflops, void* stream);
+int  pserve_probe_mfma_bf16(int iters, int random_operands, double* tflops, double* mhz, void* stream);
 int  pserve_probe_copy(void* dst, const void* src, size_t bytes, int reps, double* gbs, void* stream);
 
 #ifdef __cplusplus

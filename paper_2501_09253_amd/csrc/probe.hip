@@ -8,33 +8,72 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
-static __device__ float probe_sink;          // keeps the accumulators of the MFMA probe alive
+static __device__ long long probe_clk[2 * 512];   // per block: shader cycles and 100 MHz ticks of the timed loop
 
-constexpr int PROBE_ACC = 8;                 // independent accumulator tiles per wavefront
+constexpr int PROBE_ACC = 4;                 // independent accumulator tiles per wavefront
+constexpr int PROBE_FRAG = 4;                // distinct A and B fragments per wavefront
 
-// 4 wavefronts per block; every wavefront issues iters * PROBE_ACC independent v_mfma_f32_32x32x16_bf16
-__global__ void __launch_bounds__(256) probe_mfma_kernel(int iters) {
-    bf16x8 a, b;
+// a standard normal from a counter (hash -> two uniforms -> Box-Muller); only the distribution matters here
+__device__ __forceinline__ float probe_normal(uint32_t n) {
+    uint32_t x = n * 2654435761u + 12345u;
+    x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+    uint32_t y = x * 2246822519u + 977u;
+    y ^= y >> 15; y *= 0x2c1b3c6du; y ^= y >> 12;
+    const float u1 = ((float)(x >> 8) + 1.f) * (1.f / 16777217.f), u2 = (float)(y >> 8) * (1.f / 16777216.f);
+    return sqrtf(-2.f * __logf(u1)) * __cosf(6.2831853f * u2);
+}
+
+// 4 wavefronts per block, two blocks per CU; every wavefront issues 8 * iters v_mfma_f32_32x32x16_bf16 on register
+// operands: all 1.0 (RANDOM = false) or standard normals rounded to bf16 (RANDOM = true: the bit activity of real
+// activations, which is what the chip's power management reacts to)
+template <bool RANDOM>
+__global__ void __launch_bounds__(256, 2) probe_mfma_kernel(int iters) {
+    bf16x8 a[PROBE_FRAG], b[PROBE_FRAG];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) { a[i] = (__bf16)(0.001f * (float)(threadIdx.x & 7) + (float)i); b[i] = (__bf16)(0.5f * (float)i); }
+    for (int n = 0; n < PROBE_FRAG; ++n)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            a[n][i] = (__bf16)(RANDOM ? probe_normal((threadIdx.x * 64 + n * 16 + i) * 2u) : 1.f);
+            b[n][i] = (__bf16)(RANDOM ? probe_normal((threadIdx.x * 64 + n * 16 + i) * 2u + 1u) : 1.f);
+        }
     f32x16 acc[PROBE_ACC];
 #pragma unroll
     for (int n = 0; n < PROBE_ACC; ++n)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[n][e] = 0.f;
+    const long long c0 = clock64(), w0 = wall_clock64();
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int n = 0; n < PROBE_ACC; ++n) acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[n], 0, 0, 0);
+        for (int n = 0; n < 8; ++n)
+            acc[n % PROBE_ACC] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[n % PROBE_FRAG], b[(n / 2) % PROBE_FRAG], acc[n % PROBE_ACC], 0, 0, 0);
+        if ((it & 63) == 63) {                                   // keep the sums finite
+#pragma unroll
+            for (int n = 0; n < PROBE_ACC; ++n)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[n][e] *= 1e-3f;
+        }
     }
+    const long long c1 = clock64(), w1 = wall_clock64();
+    if (threadIdx.x == 0 && blockIdx.x < 512) { probe_clk[2 * blockIdx.x] = c1 - c0; probe_clk[2 * blockIdx.x + 1] = w1 - w0; }
     float s = 0.f;
 #pragma unroll
     for (int n = 0; n < PROBE_ACC; ++n) s += acc[n][0];
-    if (s == 12345.678f) probe_sink = s;
+    if (s == 12345.678f) probe_clk[0] = 0;              // keeps the accumulators alive
 }
 
+// four independent 16-byte loads in flight per lane, then the four stores
 __global__ void __launch_bounds__(256) probe_copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, int64_t n16) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const u32x4 v0 = __builtin_nontemporal_load(src + i), v1 = __builtin_nontemporal_load(src + i + stride);
+        const u32x4 v2 = __builtin_nontemporal_load(src + i + 2 * stride), v3 = __builtin_nontemporal_load(src + i + 3 * stride);
+        __builtin_nontemporal_store(v0, dst + i);
+        __builtin_nontemporal_store(v1, dst + i + stride);
+        __builtin_nontemporal_store(v2, dst + i + 2 * stride);
+        __builtin_nontemporal_store(v3, dst + i + 3 * stride);
+    }
+    for (; i < n16; i += stride) dst[i] = src[i];
 }
 
 // time `reps` launches with a pair of events on the stream; *ms = average per launch
@@ -66,17 +105,25 @@ using namespace pserve;
 
 extern "C" {
 
-int pserve_probe_mfma_bf16(int iters, double* tflops, void* stream) {
+int pserve_probe_mfma_bf16(int iters, int random_operands, double* tflops, double* mhz, void* stream) {
     PS_REQUIRE(tflops && iters > 0 && iters <= (1 << 22), "pserve_probe_mfma_bf16: need tflops and 0 < iters <= 2^22");
     hipStream_t st = (hipStream_t)stream;
     const int blocks = 512;                                   // two blocks of four wavefronts on each of the 256 CUs
     float ms = 0.f;
     PS_TRY(time_launches(st, 3, [&] {
-        probe_mfma_kernel<<<blocks, 256, 0, st>>>(iters);
+        if (random_operands) probe_mfma_kernel<true><<<blocks, 256, 0, st>>>(iters);
+        else probe_mfma_kernel<false><<<blocks, 256, 0, st>>>(iters);
         return check_launch("probe_mfma_kernel");
     }, &ms));
-    const double flops = (double)blocks * 4 * (double)iters * PROBE_ACC * (2.0 * 32 * 32 * 16);
+    const double flops = (double)blocks * 4 * (double)iters * 8 * (2.0 * 32 * 32 * 16);
     *tflops = flops / ((double)ms * 1e-3) / 1e12;
+    if (mhz) {
+        static long long h[2 * 512];
+        PS_CHECK_HIP(hipMemcpyFromSymbol(h, HIP_SYMBOL(probe_clk), sizeof(h)));
+        double cycles = 0.0, ticks = 0.0;
+        for (int i = 0; i < blocks; ++i) { cycles += (double)h[2 * i]; ticks += (double)h[2 * i + 1]; }
+        *mhz = ticks > 0.0 ? cycles / ticks * 100.0 : 0.0;
+    }
     return PSERVE_OK;
 }
 

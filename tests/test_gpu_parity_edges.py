@@ -3,6 +3,7 @@
 * attention logits with a wide range, so that the softmax reference of the MFMA kernel has to move after the first
   key tile (the rescale / recompute path), for image keys and for text keys, with both query-tile sizes and a ragged
   last key tile;
+* attention logits beyond +-100 (base 2), where the large-tile kernel has to fall back to its second pass;
 * GroupNorm inputs whose mean is far from zero (|mean| = 30 standard deviations): the statistics must not lose the
   variance to cancellation.
 Bars as everywhere: fp32 within 1e-4 * max|ref|, bf16 within 2e-2 * max|ref|.
@@ -80,6 +81,51 @@ def test_attention_wide_logits(name, res, stage):
     ref, _ = _oracle(w)
     err = rel_err(got, ref)
     print(f"wide logits ({name}, {stage}): {late} late maxima in two images, rel err {err:.3e}")
+    assert err < 2e-2
+
+
+@pytest.mark.parametrize("stage", [wl.SATTN, wl.XATTN])
+@pytest.mark.parametrize("name,res", WIDE, ids=[c[0] for c in WIDE])
+def test_attention_extreme_logits(name, res, stage):
+    """Logits far outside the range in which 2^logit can be formed without a softmax reference (the large query tile
+    then has to run its second pass): every logit of head 0 is shifted by about +185 and every logit of head 1 by about
+    -185 (base 2).  The shift is the same for all keys of a query, so the softmax, and with it the oracle's result, is
+    that of the unshifted problem, and bf16 rounding cannot turn it into a different one: the last eight dimensions of
+    every key are exactly 4, those of every query exactly +-32, and nothing else touches these dimensions.  (A constant
+    input channel does it: a GroupNorm group of constant channels gives beta, for the text keys a constant column.)"""
+    C, d = 128, 64
+    cfg = wl.custom_config(res, (4, 4), C=C, G=32, heads=2, stages=(stage,), dtype="bf16", ctx_len=77, ctx_dim=64, seed=79)
+    w = wl.make_workload(cfg)
+    p = w.params[0]
+    tail = np.concatenate([np.arange(56, 64), np.arange(64 + 56, 128)])              # last eight dimensions of both heads
+    p["wq"][:, tail] = 0.0
+    p["wk"][:, tail] = 0.0
+    p["wq"][0, 56:64] = 32.0
+    p["wq"][0, 64 + 56:128] = -32.0
+    p["wk"][0, tail] = 4.0
+    if stage == wl.SATTN:
+        for im in w.images:
+            im[0:4] = 1.0                                        # group 0 constant: normalised to exactly beta
+        p["gn_b"][0] = 1.0
+        p["gn_b"][1:4] = 0.0
+    else:
+        for im in w.images:
+            im[0] = 1.0                                          # the queries come from x itself
+        w.ctx[:, :, 0] = 1.0
+    # the shift, from the oracle's own logits
+    z = np.asarray(w.images[0], dtype=np.float64)
+    if stage == wl.SATTN:
+        ut = ob._tokens(ob.group_norm(z, p["gn_g"], p["gn_b"], cfg.G, cfg.eps))
+        Q, K = ut @ p["wq"].astype(np.float64), ut @ p["wk"].astype(np.float64)
+    else:
+        Q, K = ob._tokens(z) @ p["wq"].astype(np.float64), w.ctx[0].astype(np.float64) @ p["wk"].astype(np.float64)
+    for h, sign in ((0, 1.0), (1, -1.0)):
+        S2 = (Q[:, h * d:(h + 1) * d] @ K[:, h * d:(h + 1) * d].T) * (LOG2E / np.sqrt(d))
+        assert (sign * S2).min() > 150.0, (h, S2.min(), S2.max())
+    got = GpuRun(w).forward_images()
+    ref, _ = _oracle(w)
+    err = rel_err(got, ref)
+    print(f"extreme logits ({name}, {stage}): rel err {err:.3e}")
     assert err < 2e-2
 
 
