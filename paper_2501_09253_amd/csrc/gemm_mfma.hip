@@ -905,6 +905,9 @@ static int conv_select(const GemmArgs& a, ConvTile* ct, int* wave_cols = nullptr
     const bool lean = a.seg[0].scale == 1.f && !a.rowscale && !a.act_gelu && (!a.rowbias || (a.geom.S % 64 == 0 && a.geom.pw <= 64 && 64 % a.geom.pw == 0));
     if (plain3x3 && fits32 && lean && a.epi == EPI_ROUTE && a.seg_cols % 32 == 0 && a.seg_cols == a.N && !a.seg[0].transposed) {
         if (a.N % 160 == 0 && conv_tile(a, 256, 384, ct)) { sel = 1; wc = 160; }
+        // small patches (8 x 8: four segments of 10 x 10 pixels per 256 rows) need more halo slots than that tile's LDS
+        // has beside three weight stages; with two weight stages 416 slots fit
+        else if (a.N % 160 == 0 && conv_tile(a, 256, 416, ct)) { sel = 6; wc = 160; }
         else if (conv_tile(a, 128, 256, ct)) {
             if (a.N % 320 == 0) { sel = 2; wc = 160; }
             else if (a.N % 256 == 0) { sel = 3; wc = 128; }
@@ -946,6 +949,7 @@ int gemm_mfma_bf16(const GemmArgs& a, hipStream_t st, bool* handled) {
     case 3: *handled = true; return launch_conv<128, 256, 2, 2, 256, 2>(a, ct, st);
     case 4: *handled = true; return launch_conv<128, 128, 2, 2, 256, 2>(a, ct, st);
     case 5: *handled = true; return launch_conv<128, 64, 2, 2, 256, 2>(a, ct, st);
+    case 6: *handled = true; return launch_conv<256, 160, 4, 1, 416, 2, 2>(a, ct, st);
     default: break;
     }
     // Tile choice.  Two blocks of 128 rows per CU where they fit (one block's prologue and epilogue run beside the
