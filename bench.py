@@ -30,8 +30,8 @@ EVENT_EVERY = 4                # the timed region brackets the dominant kernel i
 # each scaled by what the same counter reads for the 256 MiB calibration copy below; the summary file is named beside
 # the number in the output.  (config id, kernel label) -> (bytes, summary file).
 PROFILED_TRAFFIC = {
-    (2, "conv3x3"): (52.0e6 + 23.1e6, "profiles/bench_config2_kernels_and_traffic.md"),
-    (5, "attn_self"): (1466.4e6 + 100.9e6, "profiles/bench_config5_kernels_and_traffic.md"),
+    (2, "conv3x3"): (52.1e6 + 23.2e6, "profiles/bench_config2_kernels_traffic_counters.md"),
+    (5, "attn_self"): (1208.1e6 + 107.2e6, "profiles/bench_config5_kernels_traffic_counters.md"),
 }
 
 
