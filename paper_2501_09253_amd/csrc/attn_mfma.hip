@@ -335,8 +335,8 @@ attn_mfma_kernel(AttnArgs a) {
 // second wavefront on the SIMD adds no issue slots, it only fills stalls; v_dot2c_f32_bf16 next to an MFMA costs about
 // 20 clocks.  So the softmax has to ride behind the MFMAs of the SAME wavefront.  The work of a wavefront is cut into
 // units of (32 keys, 32 queries), and in every step the 4 score MFMAs of the NEXT unit and the 4 output MFMAs of the
-// PREVIOUS unit are issued alternately, with the 16 exponentials, 8 packs and 16 row-sum additions of the CURRENT unit
-// spread over the eight MFMA slots (the three are independent of each other).  The two query sub-tiles of a wavefront
+// PREVIOUS unit are issued alternately, with the 16 exponentials and 8 packs of the CURRENT unit spread over the eight
+// MFMA slots (the three are independent of each other); the row sums are taken by four small MFMAs per unit.  The two query sub-tiles of a wavefront
 // alternate as units, so their score tiles and probability fragments are the double buffers.  Key fragments of the next
 // half tile and value fragments of the current one are refilled from LDS right behind the MFMA that last read the
 // register, eight MFMA slots before they are needed.  Because the scores of a tile's first unit are formed during the
@@ -473,7 +473,14 @@ attn_pipe_kernel(AttnArgs a) {
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) fv[i] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});   // the first step's output MFMAs add 0 * 0
-    float l_run[2] = {0.f, 0.f};
+    // Row sums by the matrix pipe: v_mfma_f32_4x4x4_16b_bf16 with an all-ones A operand adds up the four bf16 values
+    // a lane holds in its B operand (16 independent 4 x 4 x 4 products: D[i][j] = sum over k of B[k][j], every lane owning
+    // one column j of its block) and accumulates them onto acc_l; four such instructions (two passes each) per unit
+    // instead of 16 additions, and the sum is that of the rounded probabilities, i.e. of what multiplies V.
+    typedef __attribute__((ext_vector_type(4))) short s16x4;
+    typedef __attribute__((ext_vector_type(4))) float f32x4;
+    f32x4 acc_l[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+    const s16x4 ones4 = {0x3f80, 0x3f80, 0x3f80, 0x3f80};
 
     // LDS byte addresses of this lane's fragments in stage 0.  Key fragment ks of half H: row kperm(fr) + 32 H (half 1 is
     // 4 KB further), chunk (2 ks + fh) ^ swizzle.  Value fragment (H, k2, dt): row fr + 32 dt (dt = 1 is 4 KB further),
@@ -481,28 +488,29 @@ attn_pipe_kernel(AttnArgs a) {
     uint32_t ka[4], va[4];
     {
         const int krow = kperm(fr), ksw = (krow >> 1) & 7, vsw = (fr >> 1) & 7;
+        const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_u8*)att_smem;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) ka[ks] = (uint32_t)(krow * 128 + 16 * ((2 * ks + fh) ^ ksw));
+        for (int ks = 0; ks < 4; ++ks) ka[ks] = smem_base + (uint32_t)(krow * 128 + 16 * ((2 * ks + fh) ^ ksw));
 #pragma unroll
-        for (int i = 0; i < 4; ++i) va[i] = SV_OFF + (uint32_t)(fr * 128 + 16 * ((2 * i + fh) ^ vsw));
+        for (int i = 0; i < 4; ++i) va[i] = smem_base + SV_OFF + (uint32_t)(fr * 128 + 16 * ((2 * i + fh) ^ vsw));
     }
-#define PS_LDS(addr_) __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(att_smem + (addr_)))
+    // the fragment addresses are absolute LDS addresses (no base to add per read)
+    typedef const __attribute__((address_space(3))) u32x4* lds_frag;
+#define PS_LDS(addr_) __builtin_bit_cast(bf16x8, *(lds_frag)(uintptr_t)(addr_))
 
     // One MFMA slot's share of the softmax of the unit whose scores are acc_s[QT]: the two exponentials of pair G, and
-    // the bf16 pack and the two row-sum additions of pair G-1 (one slot later, so that nothing waits for an exponential).
+    // the bf16 pack of pair G-1 (one slot later, so that nothing waits for an exponential).
 #define PS_SOFT(QT, G)                                                                                           \
     {                                                                                                            \
-        if ((G) > 0) {                                                                                           \
-            fp[QT][((G) - 1) >> 2][((G) - 1) & 3] = pack_bf16x2(e0_, e1_);                                       \
-            sa_ += e0_;                                                                                          \
-            sb_ += e1_;                                                                                          \
-        }                                                                                                        \
+        if ((G) > 0) fp[QT][((G) - 1) >> 2][((G) - 1) & 3] = pack_bf16x2(e0_, e1_);                              \
         if ((G) < 8) {                                                                                           \
             e0_ = __builtin_amdgcn_exp2f(acc_s[QT][2 * (G)]);                                                    \
             e1_ = __builtin_amdgcn_exp2f(acc_s[QT][2 * (G) + 1]);                                                \
         }                                                                                                        \
     }
 #define PS_MFMA_O(QT, J) acc_o[QT][(J) & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv[J], __builtin_bit_cast(bf16x8, fp[QT][(J) >> 1]), acc_o[QT][(J) & 1], 0, 0, 0)
+#define PS_MFMA_L(QT, J)                                                                                         \
+    acc_l[QT] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(ones4, __builtin_bit_cast(s16x4, u32x2{fp[QT][(J) >> 1][2 * ((J) & 1)], fp[QT][(J) >> 1][2 * ((J) & 1) + 1]}), acc_l[QT], 0, 0, 0)
 #define PS_MFMA_S(QT, J) acc_s[QT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk[J], fq[QT][J], (J) == 0 ? zero16 : acc_s[QT], 0, 0, 0)
     // keys past the end of the sequence (last tile only): their scores become -inf
 #define PS_MASK(QT, KEY0)                                                                                        \
@@ -522,7 +530,7 @@ attn_pipe_kernel(AttnArgs a) {
 #define PS_STEP0(H, KOFF, KEY0)                                                                                  \
     {                                                                                                            \
         PS_MASK(0, KEY0)                                                                                         \
-        float sa_ = 0.f, sb_ = 0.f, e0_, e1_;                                                                    \
+        float e0_, e1_;                                                                                          \
         PS_FENCE;                                                                                                \
         _Pragma("unroll") for (int j_ = 0; j_ < 4; ++j_) {                                                       \
             PS_MFMA_S(1, j_);                                                                                    \
@@ -530,12 +538,12 @@ attn_pipe_kernel(AttnArgs a) {
             fk[j_] = PS_LDS(ka[j_] + (KOFF));                                                                    \
             PS_FENCE;                                                                                            \
             PS_MFMA_O(1, j_);                                                                                    \
+            PS_MFMA_L(1, j_);                                                                                    \
             PS_SOFT(0, 2 * j_ + 1)                                                                               \
             fv[j_] = PS_LDS(va[2 * (H) + (j_ >> 1)] + (j_ & 1) * 4096);                                          \
             PS_FENCE;                                                                                            \
         }                                                                                                        \
         PS_SOFT(0, 8)                                                                                            \
-        l_run[0] += sa_ + sb_;                                                                                   \
         PS_FENCE;                                                                                                \
     }
     // Step of unit (H, sub-tile 1): the score MFMAs of (next half, sub-tile 0) alternate with the output MFMAs of
@@ -543,18 +551,18 @@ attn_pipe_kernel(AttnArgs a) {
 #define PS_STEP1(KEY0)                                                                                           \
     {                                                                                                            \
         PS_MASK(1, KEY0)                                                                                         \
-        float sa_ = 0.f, sb_ = 0.f, e0_, e1_;                                                                    \
+        float e0_, e1_;                                                                                          \
         PS_FENCE;                                                                                                \
         _Pragma("unroll") for (int j_ = 0; j_ < 4; ++j_) {                                                       \
             PS_MFMA_S(0, j_);                                                                                    \
             PS_SOFT(1, 2 * j_)                                                                                   \
             PS_FENCE;                                                                                            \
             PS_MFMA_O(0, j_);                                                                                    \
+            PS_MFMA_L(0, j_);                                                                                    \
             PS_SOFT(1, 2 * j_ + 1)                                                                               \
             PS_FENCE;                                                                                            \
         }                                                                                                        \
         PS_SOFT(1, 8)                                                                                            \
-        l_run[1] += sa_ + sb_;                                                                                   \
         PS_FENCE;                                                                                                \
     }
 
@@ -589,13 +597,17 @@ attn_pipe_kernel(AttnArgs a) {
     }
     // ---- epilogue: output MFMAs of the last unit
 #pragma unroll
-    for (int j_ = 0; j_ < 4; ++j_) PS_MFMA_O(1, j_);
+    for (int j_ = 0; j_ < 4; ++j_) {
+        PS_MFMA_O(1, j_);
+        PS_MFMA_L(1, j_);
+    }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");        // no load may still target LDS when the block moves on
 #undef PS_STEP0
 #undef PS_STEP1
 #undef PS_FENCE
 #undef PS_MASK
 #undef PS_MFMA_S
+#undef PS_MFMA_L
 #undef PS_MFMA_O
 #undef PS_SOFT
 #undef PS_LDS
@@ -608,7 +620,7 @@ attn_pipe_kernel(AttnArgs a) {
     bool fine = true;
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt) {
-        const float l = l_run[qt] + other_half(l_run[qt]);
+        const float l = acc_l[qt][0] + other_half(acc_l[qt][0]);
         fine = fine && l >= ATT_L_MIN && l <= ATT_L_MAX;
         inv[qt] = 1.f / l;
     }
