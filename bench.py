@@ -85,7 +85,39 @@ def kernel_work(cfg, n_active_tokens, patch=None):
     }
 
 
-def measure(cfg_id, steps, warmup, all_kernels=False, events=True, patch=None, peaks=None):
+def big_workload(n_images):
+    """The stage list and mask rate of configuration 5 on n_images latents of 256 x 256 (84 MB each at C = 640, bf16):
+    tensors far beyond the 256 MB last-level cache, for the HBM-bound kernels.  Values from numpy's generator (the
+    seeded counter streams of workloads.py take minutes at this size; the kernels' time does not depend on the values)."""
+    import numpy as np
+    import workloads as wl
+    cfg = wl.custom_config([(256, 256)] * n_images, (32, 32), C=640, G=32, heads=10, stages=(wl.RES2, wl.SATTN),
+                           dtype="bf16", reuse_p=0.4, seed=55)
+    cfg.cfg_id, cfg.name = 0, f"hbm-sweep-{n_images}x256x256"
+    rng = np.random.default_rng(55)
+    draw = lambda shape: wl.bf16_round(rng.standard_normal(shape, dtype=np.float32))
+    images = [draw((cfg.C, 256, 256)) for _ in range(n_images)]
+    params = []
+    for st in cfg.stages:
+        d = {}
+        for name, (shape, kind) in wl.stage_param_shapes(st, cfg).items():
+            z = rng.standard_normal(shape, dtype=np.float32)
+            if kind == "gamma":
+                z = 1.0 + 0.1 * z
+            elif kind in ("beta", "bias"):
+                z = 0.1 * z
+            else:
+                z = z / np.float32(np.sqrt(float(kind.split(":")[1])))
+            d[name] = wl.bf16_round(z.astype(np.float32))
+        params.append(d)
+    reuse = [rng.random((8, 8)) < cfg.reuse_p for _ in range(n_images)]
+    names = [f"{si}.{sl}" for si, st in enumerate(cfg.stages) for sl in wl.stage_cache_slots(st)] + ["y"]
+    one = draw((cfg.C, 256, 256))                      # every slot of every image: the same values (they are only copied)
+    cache = {nm: [one for _ in range(n_images)] for nm in names}
+    return wl.Workload(cfg, images, params, None, reuse, cache)
+
+
+def measure(cfg_id, steps, warmup, all_kernels=False, events=True, patch=None, peaks=None, workload=None):
     """One configuration on the GPU: `warmup` untimed steps, then exactly `steps` timed ones.  Returns the result
     fields and the workload (for the CPU-baseline leg)."""
     import torch
@@ -93,8 +125,11 @@ def measure(cfg_id, steps, warmup, all_kernels=False, events=True, patch=None, p
     import workloads as wl
     from harness import GpuRun
 
-    cfg = wl.config(cfg_id)
-    w = wl.make_workload(cfg)
+    if workload is not None:
+        w, cfg = workload, workload.cfg
+    else:
+        cfg = wl.config(cfg_id)
+        w = wl.make_workload(cfg)
     assert patch is None or w.reuse is None, "--patch cannot be combined with a reuse mask"
     run = GpuRun(w, patch=tuple(patch) if patch else None)
     patch = (run.plan.ph, run.plan.pw)
@@ -306,6 +341,10 @@ def main():
     ap.add_argument("--patch", type=int, nargs=2, default=None, metavar=("PH", "PW"),
                     help="patch size override for the patch-size sweep (not for reuse configs: the mask is per patch)")
     ap.add_argument("--only", action="store_true", help="measure --config alone: no \"configs\" array, no peak probes (profiler runs)")
+    ap.add_argument("--hbm-sweep", type=int, nargs="+", default=None, metavar="N",
+                    help="instead of a configuration: the HBM-bound kernels on N latents of 256 x 256 at C = 640 (84 MB per tensor and "
+                         "latent), one JSON line per N with every kernel's effective GB/s")
+    ap.add_argument("--pull-stitch", action="store_true", help="edge stitching as a separate halo gather (kernel mode 2) instead of the push fused into the normalisation")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket kernels with HIP events")
     ap.add_argument("--all-kernels", action="store_true", help="add every kernel's time and roofline fraction to the JSON")
@@ -319,6 +358,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.pull_stitch:
+        ps.set_kernel_mode(2)
     # one plain device copy of known size (256 MiB read + 256 MiB written): the reference that scales the
     # FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this same command
     cal_src = torch.ones(128 * 1024 * 1024, dtype=torch.bfloat16, device="cuda")
@@ -340,6 +381,16 @@ def main():
                  "copy_bytes": 2 * big_src.numel()}
         del big_src, big_dst
         torch.cuda.empty_cache()
+
+    if args.hbm_sweep:
+        for n_images in args.hbm_sweep:
+            r, _ = measure(0, args.steps, args.warmup, all_kernels=True, peaks=peaks, workload=big_workload(n_images))
+            rows = {k: {"avg_us": v["avg_us"], "gbs": v["gbs"], "frac_hbm": v["frac_hbm"],
+                        "frac_of_copy": None if peaks is None else v["gbs"] / peaks["copy_gbs"]}
+                    for k, v in list(r["kernels"].items()) + list(r["extras"].items()) if "gbs" in v}
+            print(json.dumps({"hbm_sweep": r["workload"], "tensor_MB": r["T"] * 640 * 2 / 1e6, "ms_per_step": r["ms_per_step"],
+                              "copy_gbs": None if peaks is None else peaks["copy_gbs"], "kernels": rows}), flush=True)
+        return
 
     events = not args.no_kernel_events
     res, w = measure(args.config, args.steps, args.warmup, all_kernels=args.all_kernels, events=events, patch=args.patch,

@@ -328,7 +328,9 @@ int  pserve_schedule(const pserve_task* wait, int32_t n_wait, const pserve_task*
                      int32_t* admitted, int32_t* n_admitted, int32_t* discarded, int32_t* n_discarded);
 
 /* Kernel selection for measurements and tests: 0 = fastest path available for the
- * shapes (MFMA kernels where they apply), 1 = plain reference kernels only. */
+ * shapes (MFMA kernels where they apply; edge stitching pushed by the normalisation pass, the
+ * paper's "Patch Edge Stitcher"), 1 = plain reference kernels only (stitching as a separate gather),
+ * 2 = as 0 but with the separate gather (the two stitching forms side by side). */
 int  pserve_set_kernel_mode(int mode);
 
 /* ---- per-kernel timing for measurements.  While enabled, pserve_block_forward brackets every

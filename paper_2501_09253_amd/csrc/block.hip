@@ -360,7 +360,7 @@ static int dup_param(DevicePool& pool, const void* src, size_t bytes, void** dst
 extern "C" {
 
 int pserve_set_kernel_mode(int mode) {
-    PS_REQUIRE(mode == 0 || mode == 1, "pserve_set_kernel_mode: mode must be 0 or 1");
+    PS_REQUIRE(mode >= 0 && mode <= 2, "pserve_set_kernel_mode: mode must be 0, 1 or 2");
     g_kernel_mode = mode;
     return PSERVE_OK;
 }
@@ -599,7 +599,7 @@ static int cache_create_impl(const pserve_plan_t* plan, const pserve_block_t* bl
     const size_t es = dtype_size(d.dtype);
     const size_t TC = (size_t)plan->T * d.C * es;
     const int head_dim = d.heads > 0 ? d.C / d.heads : 0;
-    c->v_transposed = d.dtype == PSERVE_BF16 && head_dim == 64 && g_kernel_mode == 0;
+    c->v_transposed = d.dtype == PSERVE_BF16 && head_dim == 64 && g_kernel_mode != 1;
     c->nsplit = (int)std::max<int64_t>(1, std::min<int64_t>(cdiv(768, plan->P), std::max(1, plan->S / 32)));
     PS_TRY(c->pool.alloc(&c->ping[0], TC));
     PS_TRY(c->pool.alloc(&c->ping[1], TC));
@@ -822,7 +822,9 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
     }
     hipStream_t st = (hipStream_t)stream;
     ++g_prof.tick;
-    const int dt = d.dtype, mode = g_kernel_mode, C = d.C;
+    const int dt = d.dtype, C = d.C;
+    const int mode = g_kernel_mode == 1 ? 1 : 0;    // kernels: fastest available / plain reference
+    const bool push = g_kernel_mode == 0;           // edge stitching fused into the normalisation / separate gather
     const size_t es = dtype_size(dt);
     PatchGeom gm;
     gm.P = plan->P; gm.S = plan->S; gm.ph = plan->ph; gm.pw = plan->pw;
@@ -874,7 +876,7 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
         if (have_partials) { ProfScope ps("gn_stats", st); PS_TRY(gn_finalize(ga, gm, dt, plan->S / 64, st)); }
         else { ProfScope ps("gn_stats", st); PS_TRY(gn_stats(ga, gm, dt, st)); }
         have_partials = false;
-        if (mode == 0) {        // normalise + stitch in one pass (push); the reference path gathers rims afterwards (pull)
+        if (push) {             // normalise + stitch in one pass (push); otherwise the rims are gathered afterwards (pull)
             ProfScope ps("gn_apply_stitch", st);
             PS_TRY(gn_apply(ga, gm, dt, /*silu=*/true, /*padded=*/true, /*stitch=*/true, cache->apad, all, st));
         } else {
