@@ -111,7 +111,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[B
     }
     // GroupNorm partial sums of the output (optional): column sums over this wavefront's 64 rows, which lie in one patch
     const bool STATS = MAY_STAT && !GEGLU && a.stats != nullptr;     // only the convolution kernels leave the sums behind
-    float* colsum = reinterpret_cast<float*>(smem) + WGM * WGN * (WM * EP_LD) + wave * (2 * WN);    // [WN][2]
+    float* colsum = reinterpret_cast<float*>(smem) + WGM * WGN * (WM * EP_LD) + wave * (2 * WN + 2);    // [WN][2] + row count
     uint32_t row_ok[TM];                                            // bit e: row 8*(e/4) + 4*fh + e%4 of tile i exists
     const bool all_rows = STATS && w_tok[WM - 1] >= 0;              // existing rows are a prefix of the tile
     if (STATS && !all_rows) {
@@ -180,25 +180,38 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[B
                 }
             }
             if (STATS) {
-                float s1 = 0.f, s2 = 0.f;
+                // column moments over the wavefront's 64 rows, around the value of the column's first row (shifted sums:
+                // nothing is lost when the mean is far from zero); stored as (mean, M2) of the column
+                const float own0 = vals[0][0], oth0 = other_half_f(own0);
+                const float kc = fh == 0 ? own0 : oth0;             // both lane halves of a column use the lower half's value
+                float s1 = 0.f, s2 = 0.f, nr = 0.f;
                 if (all_rows) {
 #pragma unroll
                     for (int i = 0; i < TM; ++i)
 #pragma unroll
-                        for (int e = 0; e < 16; ++e) { s1 += vals[i][e]; s2 = fmaf(vals[i][e], vals[i][e], s2); }
+                        for (int e = 0; e < 16; ++e) { const float d = vals[i][e] - kc; s1 += d; s2 = fmaf(d, d, s2); }
+                    nr = (float)(TM * 16);
                 } else {
 #pragma unroll
                     for (int i = 0; i < TM; ++i)
 #pragma unroll
                         for (int e = 0; e < 16; ++e) {
-                            const float v = (row_ok[i] >> e) & 1u ? vals[i][e] : 0.f;
-                            s1 += v;
-                            s2 = fmaf(v, v, s2);
+                            const bool ok = (row_ok[i] >> e) & 1u;
+                            const float d = ok ? vals[i][e] - kc : 0.f;
+                            s1 += d;
+                            s2 = fmaf(d, d, s2);
+                            nr += ok ? 1.f : 0.f;
                         }
                 }
                 s1 += other_half_f(s1);
                 s2 += other_half_f(s2);
-                if (fh == 0) { colsum[2 * (j * 32 + fr)] = s1; colsum[2 * (j * 32 + fr) + 1] = s2; }
+                nr += other_half_f(nr);
+                if (fh == 0) {
+                    const float inv = nr > 0.f ? 1.f / nr : 0.f;
+                    colsum[2 * (j * 32 + fr)] = kc + s1 * inv;
+                    colsum[2 * (j * 32 + fr) + 1] = fmaxf(s2 - s1 * s1 * inv, 0.f);
+                    if (j == 0 && fr == 0) colsum[2 * WN] = nr;     // rows of this wavefront's tile that exist
+                }
             }
         }
         uint16_t* out = (uint16_t*)sgm.ptr;
@@ -266,12 +279,17 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[B
         const int cg = a.N / a.stats_G;                             // channels per group (divides WN, see gemm_emits_stats)
         const int tok0 = w_tok[0];
         if (lane < WN / cg && tok0 >= 0) {
-            float s1 = 0.f, s2 = 0.f;
-            for (int c = lane * cg; c < (lane + 1) * cg; ++c) { s1 += colsum[2 * c]; s2 += colsum[2 * c + 1]; }
+            // the group's columns cover the same rows: mean of the column means, M2 by the merge formula
+            const float nr = colsum[2 * WN];
+            float m = 0.f;
+            for (int c = lane * cg; c < (lane + 1) * cg; ++c) m += colsum[2 * c];
+            m /= (float)cg;
+            float m2 = 0.f;
+            for (int c = lane * cg; c < (lane + 1) * cg; ++c) { const float d = colsum[2 * c] - m; m2 += colsum[2 * c + 1] + nr * d * d; }
             const int p = tok0 / a.geom.S, slot = (tok0 - p * a.geom.S) / WM;
             float* dst = a.stats + (((int64_t)p * a.stats_slots + slot) * a.stats_G + (n0 + wn * WN) / cg + lane) * 2;
-            dst[0] = s1;
-            dst[1] = s2;
+            dst[0] = m;
+            dst[1] = m2;
         }
     }
 }

@@ -8,10 +8,11 @@
 // ("Patch-Tailored Diffusion Operators").
 //
 // Three kernels for the norm:
-//   gn_partial_kernel   per (patch, token chunk): per-group sum and sum of squares (fp32),
-//                       16-byte loads, per-thread channel accumulators, LDS tree to groups
-//   gn_finalize_kernel  per (request, group): shuffle + LDS reduction of the partials in
-//                       fp64 -> mean, rstd -> per (request, channel) scale and shift
+//   gn_partial_kernel   per (patch, token chunk): per-group mean and sum of squared deviations
+//                       (fp32, shifted sums), 16-byte loads, per-thread channel accumulators,
+//                       LDS tree to groups
+//   gn_finalize_kernel  per (request, group): the partial moments merged in fp64 (shuffles +
+//                       LDS) -> mean, rstd -> per (request, channel) scale and shift
 //   gn_apply_kernel     y = x*scale + shift (+SiLU), written plain or into the interior of
 //                       the padded patch buffer the convolution reads
 // Reductions are deterministic (no float atomics).
@@ -74,7 +75,11 @@ __device__ __forceinline__ void unpack_vec<uint16_t>(const uint4& q, float (&v)[
 
 constexpr int GN_U = 8;     // token rows a thread keeps in flight
 
-// thread (tl, cv): cv = channel vector (fixed channels for the whole kernel), tl = token lane
+// thread (tl, cv): cv = channel vector (fixed channels for the whole kernel), tl = token lane.
+// Moments that can be merged (Chan, Golub, LeVeque: combining the moments of two samples): a block leaves, per group,
+// the mean and the sum of squared deviations M2 of its n = (tokens of the chunk) x (channels per group) elements.  The
+// sums run over x - K with K = the channel's value in the chunk's first token, so that nothing is lost when the mean
+// is far from zero (sum of squares minus square of the sum would lose the variance at |mean| >> deviation).
 template <typename T>
 __global__ void gn_partial_kernel(const T* __restrict__ x, int32_t C, int32_t G, int32_t S, int32_t nsplit,
                                   int32_t TL, float* __restrict__ partial) {
@@ -85,10 +90,11 @@ __global__ void gn_partial_kernel(const T* __restrict__ x, int32_t C, int32_t G,
     const int p = blockIdx.x, sp = blockIdx.y;
     const int chunk = (S + nsplit - 1) / nsplit;
     const int t0 = sp * chunk, t1 = min(S, t0 + chunk);
-    float s1[VN], s2[VN];
+    float s1[VN], s2[VN], k0[VN];
 #pragma unroll
     for (int e = 0; e < VN; ++e) { s1[e] = 0.f; s2[e] = 0.f; }
     const T* base = x + ((int64_t)p * S) * C + cv * VN;
+    load_vec<T>(base + (int64_t)min(t0, S - 1) * C, k0);       // the shift: this channel vector in the chunk's first token
     // up to GN_U independent 16-byte loads in flight per thread; rows past the chunk re-read its last row and are skipped
     for (int tb = t0 + tl; tb < t1; tb += GN_U * TL) {
         float v[GN_U][VN];
@@ -98,7 +104,7 @@ __global__ void gn_partial_kernel(const T* __restrict__ x, int32_t C, int32_t G,
         for (int u = 0; u < GN_U; ++u) {
             if (tb + u * TL < t1) {
 #pragma unroll
-                for (int e = 0; e < VN; ++e) { s1[e] += v[u][e]; s2[e] = fmaf(v[u][e], v[u][e], s2[e]); }
+                for (int e = 0; e < VN; ++e) { const float d = v[u][e] - k0[e]; s1[e] += d; s2[e] = fmaf(d, d, s2[e]); }
             }
         }
     }
@@ -108,27 +114,38 @@ __global__ void gn_partial_kernel(const T* __restrict__ x, int32_t C, int32_t G,
         red[(TL + tl) * C + cv * VN + e] = s2[e];
     }
     __syncthreads();
-    // two short phases instead of one long serial loop per group: first the token lanes of every channel ...
-    for (int i = threadIdx.x; i < 2 * C; i += blockDim.x) {
-        const int which = i / C, c = i - which * C;
-        float a = 0.f;
-        for (int l = 0; l < TL; ++l) a += red[(which * TL + l) * C + c];
-        red[(which * TL) * C + c] = a;                  // lane 0's slot of this channel: no other thread touches it
+    // two short phases instead of one long serial loop per group: first the token lanes of every channel (plain sums:
+    // one shift per channel), which leave the channel's mean and M2 over the chunk ...
+    const float nt = (float)max(t1 - t0, 0);
+    for (int c = threadIdx.x; c < C; c += blockDim.x) {
+        float a = 0.f, b = 0.f;
+        for (int l = 0; l < TL; ++l) { a += red[l * C + c]; b += red[(TL + l) * C + c]; }
+        const float kc = ld_f<T>(x + ((int64_t)p * S + min(t0, S - 1)) * C + c);
+        const float inv = nt > 0.f ? 1.f / nt : 0.f;
+        red[c] = kc + a * inv;                          // mean of the channel over the chunk
+        red[TL * C + c] = fmaxf(b - a * a * inv, 0.f);  // M2 around it
     }
     __syncthreads();
-    // ... then the channels of every group (fixed order: deterministic)
+    // ... then the channels of every group (equal counts: mean of the means, M2 by the merge formula; fixed order)
     const int cg = C / G;
-    for (int i = threadIdx.x; i < 2 * G; i += blockDim.x) {
-        const int g = i >> 1, which = i & 1;
-        float a = 0.f;
-        for (int c = g * cg; c < (g + 1) * cg; ++c) a += red[(which * TL) * C + c];
-        partial[(((int64_t)p * nsplit + sp) * G + g) * 2 + which] = a;
+    for (int g = threadIdx.x; g < G; g += blockDim.x) {
+        float m = 0.f;
+        for (int c = g * cg; c < (g + 1) * cg; ++c) m += red[c];
+        m /= (float)cg;
+        float m2 = 0.f;
+        for (int c = g * cg; c < (g + 1) * cg; ++c) { const float d = red[c] - m; m2 += red[TL * C + c] + nt * d * d; }
+        float* dst = partial + (((int64_t)p * nsplit + sp) * G + g) * 2;
+        dst[0] = m;
+        dst[1] = m2;
     }
 }
 
 constexpr int GN_FIN_THREADS = 256;
 
-// block = four wavefronts per (request slot s, group g)
+// block = four wavefronts per (request slot s, group g): merges the moments of all partials of the request in fp64.
+// Partial i of a patch covers rows(i) = the tokens of chunk i (S split into `nsplit` chunks) times C/G channels;
+// sum n_i mean_i and sum (M2_i + n_i mean_i^2) in fp64 give the mean and the M2 of the whole request (the fp64 sums
+// carry 16 digits against the eight or so that |mean| / deviation can cost).
 template <typename T>
 __global__ void gn_finalize_kernel(const float* __restrict__ partial, const int32_t* __restrict__ request_offset,
                                    const T* __restrict__ gamma, const T* __restrict__ beta, int32_t C, int32_t G,
@@ -136,11 +153,16 @@ __global__ void gn_finalize_kernel(const float* __restrict__ partial, const int3
     const int s = blockIdx.x, g = blockIdx.y;
     const int p0 = request_offset[s], p1 = request_offset[s + 1];
     const int items = (p1 - p0) * nsplit;
+    const int cg = C / G;
+    const int chunk = (S + nsplit - 1) / nsplit;
     double a = 0.0, b = 0.0;
     for (int i = threadIdx.x; i < items; i += GN_FIN_THREADS) {
         const float* src = partial + (((int64_t)p0 * nsplit + i) * G + g) * 2;
-        a += (double)src[0];
-        b += (double)src[1];
+        const int sp = i % nsplit;
+        const double n = (double)max(min(S, (sp + 1) * chunk) - sp * chunk, 0) * cg;
+        const double m = (double)src[0];
+        a += n * m;
+        b += (double)src[1] + n * m * m;
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
@@ -154,7 +176,6 @@ __global__ void gn_finalize_kernel(const float* __restrict__ partial, const int3
     b = 0.0;
 #pragma unroll
     for (int w = 0; w < GN_FIN_THREADS / 64; ++w) { a += red[w][0]; b += red[w][1]; }    // fixed order: deterministic
-    const int cg = C / G;
     const double cnt = (double)(p1 - p0) * S * cg;
     const double mean = a / cnt;
     double var = b / cnt - mean * mean;
