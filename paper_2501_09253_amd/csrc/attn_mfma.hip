@@ -670,6 +670,164 @@ attn_pipe_kernel(AttnArgs a) {
 #undef PS_QTOK
 }
 
+// ---- few keys (the text tokens of cross-attention: at most 128 per request) ------------------------------------
+// With 77 keys a query tile is two key tiles of work behind a full prologue (query fragments, K / V^T staging), and
+// every 128 queries pay it again.  Here a block belongs to one (request, head): it stages that pair's keys and values in
+// LDS ONCE and then walks over query tiles of 128 rows (tile c, c + chunks, ...), the query fragments of the next tile
+// in flight while the current one is computed.  All scores of a query fit the registers (128 keys x 32 queries per
+// wavefront = 64 per lane), so the softmax is the plain three-pass form: exact row maximum, exponentials, sum.
+constexpr int ATT_XK = 128;      // keys the kernel takes at most
+
+__global__ void __launch_bounds__(256, 3)
+attn_cross_kernel(AttnArgs a, int chunks) {
+    u32x4* sK = reinterpret_cast<u32x4*>(att_smem);            // [2 tiles][64 keys][8 chunks], chunk ^ ((key>>1)&7)
+    u32x4* sV = sK + 2 * 512;                                  // [2 tiles][64 d][8 chunks of 8 keys], chunk ^ ((d>>1)&7)
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int fr = lane & 31, fh = lane >> 5;
+    // head fastest: the blocks that run at the same time read and write the same token rows (all heads of a row
+    // are one contiguous piece of memory), which keeps the DRAM pages they touch few
+    const int head = blockIdx.x % a.heads;
+    const int sc_ = blockIdx.x / a.heads;
+    const int c0 = sc_ % chunks, s = sc_ / chunks;
+    const int S = a.geom.S;
+    const int rows_s = (a.act_off[s + 1] - a.act_off[s]) * S;            // computed query rows of this request
+    const int tiles_s = (rows_s + 127) >> 7;
+    if (c0 >= tiles_s) return;
+    const int nk = a.cross_len;
+    const int64_t k0 = (int64_t)a.perm[s] * a.cross_ld;
+    const uint16_t* Q = (const uint16_t*)a.Q;
+    const uint16_t* K = (const uint16_t*)a.K;
+    const uint16_t* V = (const uint16_t*)a.V;
+    const int C = a.C;
+
+    // ---- keys and values of the pair: rows / chunks past the last key are clamped to valid ones (masked below)
+    {
+        const int lc = lane & 7, lr = 8 * wave + (lane >> 3);
+        const int gc = lc ^ ((lr >> 1) & 7);
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int key = min(t * 64 + lr + 32 * i, nk - 1);
+                __builtin_amdgcn_global_load_lds((const void*)(K + (k0 + key) * C + head * ATT_D + gc * 8),
+                                                 (lds_void*)(sK + t * 512 + wave * 64 + i * 256), 16, 0, 0);
+                const int vc = t * 64 + gc * 8 < nk ? t * 64 + gc * 8 : 0;
+                __builtin_amdgcn_global_load_lds((const void*)(V + (int64_t)(head * ATT_D + lr + 32 * i) * a.ldv + k0 + vc),
+                                                 (lds_void*)(sV + t * 512 + wave * 64 + i * 256), 16, 0, 0);
+            }
+    }
+    // query fragments of a tile: lane holds Q[q][16*ks + 8*fh .. +8] of its query column
+    auto query = [&](int tile, bf16x8 (&fq)[4], int64_t& tok, bool& ok) {
+        int r = tile * 128 + wave * 32 + fr;
+        ok = r < rows_s;
+        if (!ok) r = rows_s - 1;
+        const int pi = a.act_off[s] + r / S;
+        const int p = a.act.active ? a.act.active[pi] : pi;
+        tok = (int64_t)p * S + (r - (r / S) * S);
+        const uint16_t* qp = Q + tok * C + head * ATT_D + fh * 8;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) fq[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qp + ks * 16));
+    };
+    bf16x8 fq[4];
+    int64_t tok;
+    bool ok;
+    query(c0, fq, tok, ok);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();                                        // keys and values are in LDS for the rest of the block's life
+
+    const int krow[2] = {kperm(fr), kperm(fr) + 32};
+    const int ksw = (krow[0] >> 1) & 7, vsw = (fr >> 1) & 7;
+    const int nunit = (nk + 31) >> 5;                       // 32-key units that hold keys at all (1 .. 4)
+    uint16_t* O = (uint16_t*)a.O;
+    for (int tile = c0; tile < tiles_s; tile += chunks) {
+        // the next tile's query fragments travel while this tile is computed
+        bf16x8 fq_n[4];
+        int64_t tok_n = tok;
+        bool ok_n = false;
+        const bool more = tile + chunks < tiles_s;
+        if (more) query(tile + chunks, fq_n, tok_n, ok_n);
+        // scores: unit u = 2*t + h holds keys 64 t + 32 h + 16 (e >> 3) + 8 fh + (e & 7)
+        f32x16 sc[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) sc[u][e] = 0.f;
+            if (u < nunit) {
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {
+                    const bf16x8 fk = __builtin_bit_cast(bf16x8, sK[(u >> 1) * 512 + krow[u & 1] * 8 + ((2 * ks + fh) ^ ksw)]);
+                    sc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk, fq[ks], sc[u], 0, 0, 0);
+                }
+            }
+        }
+        float m = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int key = 32 * u + 16 * (e >> 3) + 8 * fh + (e & 7);
+                if (key >= nk) sc[u][e] = -INFINITY;
+                m = fmaxf(m, sc[u][e]);
+            }
+        m = half_swap_max(m);
+        float l = 0.f;
+        u32x4 fp[4][2];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                const float p0 = __builtin_amdgcn_exp2f(sc[u][2 * g] - m), p1 = __builtin_amdgcn_exp2f(sc[u][2 * g + 1] - m);
+                l += p0 + p1;
+                fp[u][g >> 2][g & 3] = pack_bf16x2(p0, p1);
+            }
+        l += other_half(l);
+        f32x16 acc_o[2];
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc_o[dt][e] = 0.f;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (u < nunit) {
+#pragma unroll
+                for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+                    for (int dt = 0; dt < 2; ++dt) {
+                        const bf16x8 fv = __builtin_bit_cast(bf16x8, sV[(u >> 1) * 512 + (fr + 32 * dt) * 8 + ((4 * (u & 1) + 2 * k2 + fh) ^ vsw)]);
+                        acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv, __builtin_bit_cast(bf16x8, fp[u][k2]), acc_o[dt], 0, 0, 0);
+                    }
+            }
+        }
+        // O[q][head*64 + d] = O^T / l; the lane halves trade pieces so that every store is 16 bytes (as in attn_body;
+        // the two lanes of an exchange hold the same query row, so they are in or out together)
+        if (ok) {
+            const float inv = 1.f / l;
+            uint16_t* op = O + tok * C + head * ATT_D + 8 * fh;
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                for (int eg = 0; eg < 4; eg += 2) {
+                    uint32_t w[2][2];
+#pragma unroll
+                    for (int q = 0; q < 2; ++q) {
+                        w[q][0] = pack_bf16x2(acc_o[dt][4 * (eg + q)] * inv, acc_o[dt][4 * (eg + q) + 1] * inv);
+                        w[q][1] = pack_bf16x2(acc_o[dt][4 * (eg + q) + 2] * inv, acc_o[dt][4 * (eg + q) + 3] * inv);
+                    }
+                    const auto r0_ = __builtin_amdgcn_permlane32_swap(w[0][0], w[1][0], false, false);
+                    const auto r1_ = __builtin_amdgcn_permlane32_swap(w[0][1], w[1][1], false, false);
+                    *reinterpret_cast<u32x4*>(op + dt * 32 + eg * 8) = u32x4{r0_[0], r1_[0], r0_[1], r1_[1]};
+                }
+        }
+        if (more) {
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) fq[ks] = fq_n[ks];
+            tok = tok_n;
+            ok = ok_n;
+        }
+    }
+}
+
 // One block: per request slot, number of computed patches and of query tiles (exclusive prefixes).
 __global__ void attn_tiles_kernel(const int32_t* __restrict__ request_offset, const uint8_t* __restrict__ mask, int32_t n,
                                   int32_t S, int32_t ATT_BQ, int32_t* __restrict__ act_off, int32_t* __restrict__ tile_off) {
@@ -729,6 +887,14 @@ int attention_mfma_bf16(const AttnArgs& a, hipStream_t st, bool* handled) {
         return PSERVE_OK;              // image token ranges must start on 16-byte boundaries of the V^T rows
     }
     *handled = true;
+    if (a.cross_len && a.cross_len <= ATT_XK) {
+        // one block per (request, head, chunk of its query tiles): about six blocks per CU in all (three run at once)
+        const int64_t pairs = (int64_t)a.n * a.heads;
+        const int tiles_max = (int)cdiv(a.max_rows, 128);
+        const int chunks = (int)std::max<int64_t>(1, std::min<int64_t>(tiles_max, cdiv(1536, pairs)));
+        attn_cross_kernel<<<(unsigned)(pairs * chunks), 256, 4 * 512 * 16, st>>>(a, chunks);
+        return check_launch("attn_cross_kernel");
+    }
     const int64_t items = (int64_t)a.max_tiles * a.heads;
     const unsigned grid = (unsigned)(8 * ATT_GROUP * cdiv(items, 8 * ATT_GROUP));
     constexpr int lds = ATT_NS * 2 * 512 * 16;

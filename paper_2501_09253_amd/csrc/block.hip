@@ -976,7 +976,7 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
         aa.seq_len = joint ? plan->d_tab[PSERVE_TAB_SEQ_LEN] : nullptr;
         aa.cross_len = cross ? d.ctx_len : 0; aa.cross_ld = cross ? cache->cross_ld : 0;
         aa.act_off = cache->act_off; aa.tile_off = cache->tile_off; aa.n = plan->n; aa.max_tiles = cache->max_tiles;
-        aa.qt = cache->att_qt;
+        aa.qt = cache->att_qt; aa.max_rows = plan->max_tokens_per_image;
         ProfScope ps(cross ? "attn_cross" : "attn_self", st);
         return attention(aa, dt, mode, st);
     };

@@ -151,6 +151,7 @@ struct AttnArgs {
     int32_t n;                 // request slots
     int32_t max_tiles;         // host upper bound of tile_off[n]
     int32_t qt;                // 1 or 2: the tables were built for query tiles of 128 * qt rows
+    int32_t max_rows;          // host upper bound of the query rows of one request (its tokens)
 };
 int attention_tiles(const int32_t* request_offset, const uint8_t* mask, int32_t n, int32_t S, int32_t qt, int32_t* act_off,
                     int32_t* tile_off, hipStream_t st);
