@@ -27,12 +27,32 @@ EVENT_EVERY = 4                # the timed region brackets the dominant kernel i
 
 # HBM bytes per launch of the dominant kernel.  NOT measured by this run: counters need a profiler run of their own.
 # The figures come from two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE) of `python3 bench.py --config N --only`,
-# each scaled by what the same counter reads for the 256 MiB calibration copy below; the summary file is named beside
-# the number in the output.  (config id, kernel label) -> (bytes, summary file).
-PROFILED_TRAFFIC = {
-    (2, "conv3x3"): (52.1e6 + 23.2e6, "profiles/bench_config2_kernels_traffic_counters.md"),
-    (5, "attn_self"): (1208.1e6 + 107.2e6, "profiles/bench_config5_kernels_traffic_counters.md"),
-}
+# each scaled by what the same counter reads for the 256 MiB calibration copy below; they are read from the committed
+# summary of those runs, which is named beside the number in the output.  Kernel label -> kernel name in the summary.
+PROFILE_KERNEL = {"conv3x3": "conv_mfma_kernel", "attn_self": "attn_pipe_kernel", "attn_cross": "attn_cross_kernel",
+                  "ffn_geglu": "gemm_mfma_kernel<128, 128, true", "gn_stats": "gn_partial_kernel"}
+
+
+def profiled_traffic(cfg_id, label):
+    """(HBM bytes per launch, summary file) of kernel `label` from the committed counter summary of configuration
+    cfg_id (the table "HBM traffic per launch": scaled read MB + scaled write MB of the first row whose kernel name
+    matches), or (None, None) when there is no summary or no such row."""
+    rel = f"profiles/bench_config{cfg_id}_kernels_traffic_counters.md"
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), rel)
+    name = PROFILE_KERNEL.get(label)
+    if name is None or not os.path.exists(path):
+        return None, None
+    in_table = False
+    for line in open(path):
+        if line.startswith("## "):
+            in_table = line.startswith("## HBM traffic per launch")
+        elif in_table and line.startswith("| pserve::" + name):
+            cells = [c.strip() for c in line.strip().strip("|").split("|")]
+            try:
+                return (float(cells[-2]) + float(cells[-1])) * 1e6, rel
+            except ValueError:
+                return None, None
+    return None, None
 
 
 def kernel_work(cfg, n_active_tokens, patch=None):
@@ -271,7 +291,7 @@ def measure(cfg_id, steps, warmup, all_kernels=False, events=True, patch=None, p
         if dom not in timed_k:                     # no warm-up steps: every kernel was timed in the timed region
             dom = max(prof, key=lambda k: prof[k]["total_ms"])
         ent = timed_k[dom]
-        traffic, source = PROFILED_TRAFFIC.get((cfg.cfg_id, dom), (None, None))
+        traffic, source = profiled_traffic(cfg.cfg_id, dom)
         mfma = "tflops" in ent
         measured_peak = None if peaks is None else peaks["mfma_bf16_tflops" if mfma else "copy_gbs"]
         achieved = ent["tflops"] if mfma else ent.get("gbs")
@@ -332,6 +352,65 @@ def cpu_baseline(w):
                       f"fp64 numpy, {cpu_s:.1f} s"}
 
 
+def library_gemm(steps, warmup):
+    """torch.matmul (the vendor library's tuned bf16 GEMM) on the shapes the block's MFMA kernels work on, with
+    standard-normal operands: what a plain GEMM of that shape reaches on this chip, without any of the fused work
+    (patch gather and halo of the convolution, bias / residual / GEGLU / transposed outputs of the linear layers).
+    M of the convolutions: computed tokens; K: nine taps x C."""
+    import torch
+    shapes = [("config 2 conv3x3", 29696, 2880, 320),
+              ("config 3 q/k/v", 13312, 640, 1920), ("config 3 attn out", 13312, 640, 640),
+              ("config 3 ffn in (GEGLU)", 13312, 640, 5120), ("config 3 ffn out", 13312, 2560, 640),
+              ("config 4 conv3x3", 13440, 11520, 1280), ("config 4 q/k/v", 13440, 1280, 3840), ("config 4 attn out", 13440, 1280, 1280),
+              ("config 5 conv3x3", 78848, 5760, 640), ("config 5 q/k/v", 131072, 640, 1920), ("config 5 attn out", 78848, 640, 640)]
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    rows = []
+    for name, M, K, N in shapes:
+        a = torch.randn(M, K, device="cuda", dtype=torch.bfloat16, generator=gen)
+        b = torch.randn(N, K, device="cuda", dtype=torch.bfloat16, generator=gen)
+        for _ in range(max(1, warmup)):
+            c = a @ b.t()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(steps):
+            c = a @ b.t()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / steps * 1e3
+        rows.append({"shape": name, "M": M, "K": K, "N": N, "avg_us": us, "tflops": 2.0 * M * K * N / us / 1e6,
+                     "frac": 2.0 * M * K * N / us / 1e6 / PEAK_BF16_TFLOPS})
+        del a, b, c
+    return rows
+
+
+def library_attention(steps, warmup):
+    """torch's fused attention (the vendor's flash-attention kernels) at head dimension 64, ten heads, on sequence
+    lengths of the configurations' images (all queries computed, no reuse mask): 256 tokens (16 x 16 latents of
+    configuration 3), 4,096 and 65,536 (the 64 x 64 and 256 x 256 latents of configuration 5)."""
+    import torch
+    import torch.nn.functional as F
+    gen = torch.Generator(device="cuda").manual_seed(6)
+    rows = []
+    for name, B, S in (("64 x 256 tokens", 64, 256), ("16 x 4,096 tokens", 16, 4096), ("4 x 16,384 tokens", 4, 16384),
+                       ("1 x 65,536 tokens", 1, 65536)):
+        q, k, v = (torch.randn(B, 10, S, 64, device="cuda", dtype=torch.bfloat16, generator=gen) for _ in range(3))
+        for _ in range(warmup):
+            o = F.scaled_dot_product_attention(q, k, v)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(steps):
+            o = F.scaled_dot_product_attention(q, k, v)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / steps * 1e3
+        fl = 4.0 * B * 10 * S * S * 64
+        rows.append({"shape": name, "heads": 10, "d": 64, "avg_us": us, "tflops": fl / us / 1e6, "frac": fl / us / 1e6 / PEAK_BF16_TFLOPS})
+        del q, k, v, o
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -345,6 +424,10 @@ def main():
                     help="instead of a configuration: the HBM-bound kernels on N latents of 256 x 256 at C = 640 (84 MB per tensor and "
                          "latent), one JSON line per N with every kernel's effective GB/s")
     ap.add_argument("--pull-stitch", action="store_true", help="edge stitching as a separate halo gather (kernel mode 2) instead of the push fused into the normalisation")
+    ap.add_argument("--library-yardstick", action="store_true",
+                    help="instead of a configuration: the vendor libraries' bf16 GEMM (torch.matmul) and fused attention "
+                         "(torch's scaled_dot_product_attention) on the shapes of configurations 2..5 with standard-normal operands, "
+                         "one JSON line: a yardstick for the MFMA kernels, not part of the path")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket kernels with HIP events")
     ap.add_argument("--all-kernels", action="store_true", help="add every kernel's time and roofline fraction to the JSON")
@@ -381,6 +464,12 @@ def main():
                  "copy_bytes": 2 * big_src.numel()}
         del big_src, big_dst
         torch.cuda.empty_cache()
+
+    if args.library_yardstick:
+        print(json.dumps({"library_gemm": library_gemm(args.steps, args.warmup),
+                          "library_attention": library_attention(min(args.steps, 5), min(max(1, args.warmup), 2)),
+                          "measured_peaks": peaks}), flush=True)
+        return
 
     if args.hbm_sweep:
         for n_images in args.hbm_sweep:
