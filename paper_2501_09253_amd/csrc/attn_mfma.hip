@@ -524,61 +524,20 @@ attn_pipe_kernel(AttnArgs a) {
         }                                                                                                        \
     }
 #define PS_FENCE __builtin_amdgcn_sched_barrier(0)
-    // Step of unit (half H, sub-tile 0) of a tile: the score MFMAs of (H, sub-tile 1) alternate with the output MFMAs of
-    // the previous unit (sub-tile 1 of the previous half, whose value fragments are still in fv); behind its last reader
-    // each key fragment is refilled for the next half (KOFF: 4096 = second half of the stage ka points at, 0 = first half
-    // of the next stage, to which ka has then advanced) and each value fragment for half H.
-#define PS_STEP0(H, KOFF, KEY0, HOOK)                                                                            \
-    {                                                                                                            \
-        PS_MASK(0, KEY0)                                                                                         \
-        float e0_, e1_;                                                                                          \
-        PS_FENCE;                                                                                                \
-        _Pragma("unroll") for (int j_ = 0; j_ < 4; ++j_) {                                                       \
-            PS_MFMA_S(1, j_);                                                                                    \
-            PS_SOFT(0, 2 * j_)                                                                                   \
-            fk[j_] = PS_LDS(ka[j_] + (KOFF));                                                                    \
-            if (j_ == 1) { HOOK; }                                                                               \
-            PS_FENCE;                                                                                            \
-            PS_MFMA_O(1, j_);                                                                                    \
-            PS_MFMA_L(1, j_);                                                                                    \
-            PS_SOFT(0, 2 * j_ + 1)                                                                               \
-            fv[j_] = PS_LDS(va[2 * (H) + (j_ >> 1)] + (j_ & 1) * 4096);                                          \
-            PS_FENCE;                                                                                            \
-        }                                                                                                        \
-        PS_SOFT(0, 8)                                                                                            \
-        PS_FENCE;                                                                                                \
-    }
-    // Step of unit (H, sub-tile 1): the score MFMAs of (next half, sub-tile 0) alternate with the output MFMAs of
+    // Step of unit (half H, sub-tile 0) of a tile (PS_STEP0): the score MFMAs of (H, sub-tile 1) alternate with the output
+    // MFMAs of the previous unit (sub-tile 1 of the previous half, whose value fragments are still in fv); behind its last
+    // reader each key fragment is refilled for the next half (KOFF: 4096 = second half of the stage ka points at, 0 =
+    // first half of the next stage, to which ka has then advanced) and each value fragment for half H.  Step of unit
+    // (H, sub-tile 1) (PS_STEP1): the score MFMAs of (next half, sub-tile 0) alternate with the output MFMAs of
     // (H, sub-tile 0); no fragment is refilled (both sets are read again by the next step).
-#define PS_STEP1(KEY0, HOOK)                                                                                     \
-    {                                                                                                            \
-        PS_MASK(1, KEY0)                                                                                         \
-        float e0_, e1_;                                                                                          \
-        PS_FENCE;                                                                                                \
-        _Pragma("unroll") for (int j_ = 0; j_ < 4; ++j_) {                                                       \
-            PS_MFMA_S(0, j_);                                                                                    \
-            PS_SOFT(1, 2 * j_)                                                                                   \
-            if (j_ == 1) { HOOK; }                                                                               \
-            PS_FENCE;                                                                                            \
-            PS_MFMA_O(0, j_);                                                                                    \
-            PS_MFMA_L(0, j_);                                                                                    \
-            PS_SOFT(1, 2 * j_ + 1)                                                                               \
-            PS_FENCE;                                                                                            \
-        }                                                                                                        \
-        PS_SOFT(1, 8)                                                                                            \
-        PS_FENCE;                                                                                                \
-    }
-
-    // The same two steps for tiles in the interior of the sequence (no key to mask, no load to clamp): one basic block
-    // per step, and the order inside it is prescribed slot by slot (sched_group_barrier: 0x8 matrix, 0x400
-    // transcendental, 0x2 other vector, 0x100 LDS read, 0x20 memory read).  Left to itself the compiler gathers the 16
-    // exponentials of a step in front of its MFMAs: the fences between the slots do not hold instructions without side
-    // effects in place.
+    // A step is one basic block, and the order inside it is prescribed slot by slot (sched_group_barrier: 0x8 matrix,
+    // 0x400 transcendental, 0x2 other vector, 0x100 LDS read).  Left to itself the compiler gathers the 16 exponentials
+    // of a step in front of its MFMAs: fences between the slots do not hold instructions without side effects in place.
 #define PS_SGB(mask_, n_) __builtin_amdgcn_sched_group_barrier((mask_), (n_), 0)
 #define PS_LOADS_K(t_)                                                                                           \
     {                                                                                                            \
         lds_u8* dk_ = (lds_u8*)(att_smem + ((t_) & (ATT_PNS - 1)) * STAGE + wave * 1024);                        \
-        const uint8_t* kt_ = k_uni + (int64_t)(t_) * (ATT_BKV * 2) * C;                                          \
+        const uint8_t* kt_ = k_uni + (int64_t)min((t_), steps - 1) * (ATT_BKV * 2) * C;                          \
         _Pragma("unroll") for (int i = 0; i < 2; ++i) {                                                          \
             uint32_t off_ = k_lane[i];                                                                           \
             asm volatile("" : "+v"(off_));                                                                       \
@@ -588,17 +547,17 @@ attn_pipe_kernel(AttnArgs a) {
 #define PS_LOADS_V(t_)                                                                                           \
     {                                                                                                            \
         lds_u8* dv_ = (lds_u8*)(att_smem + SV_OFF + ((t_) & (ATT_PNS - 1)) * STAGE + wave * 1024);               \
-        const uint8_t* vt_ = v_uni + (int64_t)(t_) * (ATT_BKV * 2);                                              \
+        const uint8_t* vt_ = v_uni + (int64_t)min((t_), steps - 1) * (ATT_BKV * 2);                              \
         _Pragma("unroll") for (int i = 0; i < 2; ++i) {                                                          \
             uint32_t off_ = v_lane[i];                                                                           \
             asm volatile("" : "+v"(off_));                                                                       \
             __builtin_amdgcn_global_load_lds((const void*)(vt_ + off_), (lds_void*)(dv_ + i * 4096), 16, 0, 0);  \
         }                                                                                                        \
     }
-#define PS_STEP0F(H, KOFF)                                                                                       \
+#define PS_STEP0(H, KOFF, LEAD)                                                                                  \
     {                                                                                                            \
         float e0_, e1_;                                                                                          \
-        PS_FENCE;                                                                                                \
+        LEAD;                                                                                                    \
         _Pragma("unroll") for (int j_ = 0; j_ < 4; ++j_) {                                                       \
             PS_MFMA_S(1, j_);                                                                                    \
             PS_SOFT(0, 2 * j_)                                                                                   \
@@ -622,10 +581,10 @@ attn_pipe_kernel(AttnArgs a) {
         PS_SGB(0x002, 1);                                                                                        \
         PS_FENCE;                                                                                                \
     }
-#define PS_STEP1F()                                                                                              \
+#define PS_STEP1(LEAD)                                                                                           \
     {                                                                                                            \
         float e0_, e1_;                                                                                          \
-        PS_FENCE;                                                                                                \
+        LEAD;                                                                                                    \
         _Pragma("unroll") for (int j_ = 0; j_ < 4; ++j_) {                                                       \
             PS_MFMA_S(0, j_);                                                                                    \
             PS_SOFT(1, 2 * j_)                                                                                   \
@@ -663,17 +622,20 @@ attn_pipe_kernel(AttnArgs a) {
     // of an iteration are issued behind MFMAs of its first two steps, not in front of them: right after the barrier all
     // wavefronts of the block would queue at the memory pipeline at once, each with idle matrix pipe behind it.
     int t = 0;
-    for (; (t + 4) * ATT_BKV <= nk; ++t) {                  // tile t whole, tiles t+2 and t+3 whole
+    // Interior iterations: tile t whole (nothing to mask) and the tiles loaded (t + 2, t + 3, or the last tile again
+    // once past the end) whole (nothing to clamp): every iteration of a sequence that is a multiple of the tile.
+    const int interior = (nk & (ATT_BKV - 1)) == 0 ? steps : steps - 4;
+    for (; t < interior; ++t) {
         asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory");
         const uint32_t adv = ((t & (ATT_PNS - 1)) == ATT_PNS - 1) ? (uint32_t)(-(int)((ATT_PNS - 1) * STAGE)) : STAGE;
-        PS_STEP0F(0, 4096);
+        PS_STEP0(0, 4096, PS_FENCE);
         PS_LOADS_K(t + 3);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) ka[ks] += adv;           // the key fragments now come from the next tile's stage
-        PS_STEP1F();
+        PS_STEP1(PS_FENCE);
         PS_LOADS_V(t + 2);
-        PS_STEP0F(1, 0);
-        PS_STEP1F();
+        PS_STEP0(1, 0, PS_FENCE);
+        PS_STEP1(PS_FENCE);
 #pragma unroll
         for (int i = 0; i < 4; ++i) va[i] += adv;
     }
@@ -681,12 +643,18 @@ attn_pipe_kernel(AttnArgs a) {
         asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory");
         const int kv0 = t * ATT_BKV;
         const uint32_t adv = ((t & (ATT_PNS - 1)) == ATT_PNS - 1) ? (uint32_t)(-(int)((ATT_PNS - 1) * STAGE)) : STAGE;
-        PS_STEP0(0, 4096, kv0, PS_ISSUE_K(t + 3));
+        PS_MASK(0, kv0)
+        PS_STEP0(0, 4096, );
+        PS_ISSUE_K(t + 3);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) ka[ks] += adv;
-        PS_STEP1(kv0, PS_ISSUE_V(t + 2));
-        PS_STEP0(1, 0, kv0 + 32, );
-        PS_STEP1(kv0 + 32, );
+        PS_MASK(1, kv0)
+        PS_STEP1();
+        PS_ISSUE_V(t + 2);
+        PS_MASK(0, kv0 + 32)
+        PS_STEP0(1, 0, );
+        PS_MASK(1, kv0 + 32)
+        PS_STEP1();
 #pragma unroll
         for (int i = 0; i < 4; ++i) va[i] += adv;
     }
@@ -699,8 +667,6 @@ attn_pipe_kernel(AttnArgs a) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");        // no load may still target LDS when the block moves on
 #undef PS_STEP0
 #undef PS_STEP1
-#undef PS_STEP0F
-#undef PS_STEP1F
 #undef PS_LOADS_K
 #undef PS_LOADS_V
 #undef PS_SGB
