@@ -570,13 +570,14 @@ attn_pipe_kernel(AttnArgs a) {
         PS_SOFT(0, 8)                                                                                            \
         _Pragma("unroll") for (int j_ = 0; j_ < 4; ++j_) {                                                       \
             PS_SGB(0x008, 1);                                                                                    \
+            PS_SGB(0x100, 1);                                                                                    \
             PS_SGB(0x400, 2);                                                                                    \
             if (j_ > 0) PS_SGB(0x002, 1);                                                                        \
+            PS_SGB(0x008, 1);                                                                                    \
             PS_SGB(0x100, 1);                                                                                    \
-            PS_SGB(0x008, 2);                                                                                    \
+            PS_SGB(0x008, 1);                                                                                    \
             PS_SGB(0x400, 2);                                                                                    \
             PS_SGB(0x002, 1);                                                                                    \
-            PS_SGB(0x100, 1);                                                                                    \
         }                                                                                                        \
         PS_SGB(0x002, 1);                                                                                        \
         PS_FENCE;                                                                                                \
