@@ -644,8 +644,10 @@ static int cache_create_impl(const pserve_plan_t* plan, const pserve_block_t* bl
     if (sattn || xattn) {
         PS_TRY(c->pool.alloc_t(&c->act_off, (size_t)plan->n + 1));
         PS_TRY(c->pool.alloc_t(&c->tile_off, (size_t)plan->n + 1));
-        // short batches: the smaller query tile, so that there are at least two rounds of blocks
-        c->att_qt = attention_max_tiles(plan, 2) * (int64_t)d.heads < 1024 ? 1 : 2;
+        // The software-pipelined kernel (256-row query tile) as soon as its blocks cover the chip once (256 CUs): with
+        // 520 blocks (8 latents of 32^2 / 48^2, 10 heads) it ran in 82 us against 99 us for the 128-row kernel with
+        // twice the blocks.  Below that the smaller tile, which gives twice as many blocks to spread.
+        c->att_qt = attention_max_tiles(plan, 2) * (int64_t)d.heads < 256 ? 1 : 2;
         c->max_tiles = attention_max_tiles(plan, c->att_qt);
     }
     if (ffn) PS_TRY(c->pool.alloc(&c->hidden, (size_t)plan->T * d.ffn_mult * d.C * es));

@@ -329,6 +329,11 @@ gemm_mfma_kernel(GemmArgs a) {
     static_assert(WGM * WGN == 4 && WM % 32 == 0 && WN % 32 == 0 && (BM * CH) % 256 == 0 && (BN * CH) % 256 == 0 &&
                   NS >= 2 && (NS - 1) * LD <= 63, "tile shape");
     static_assert(4 * WM * 36 * 4 <= GemmCfg<BM, BN, NS, OVERLAP>::EPI, "epilogue staging size");
+    // Without a staging region of its own the epilogue stages in the drained ring.  Where the stages behind the first
+    // hold that staging (4 wavefronts x WM rows x 36 floats), the first step of the next tile is loaded into stage 0
+    // BEFORE the epilogue and the remaining stages after it: the load latency of a tile start (the long part of the
+    // ~4 us a tile start costs at K = 640) passes beside the epilogue's vector work and stores.
+    constexpr bool HALF = !OVERLAP && (NS - 1) * (BM + BN) * 128 >= 4 * WM * 36 * 4;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     u32x4* ring = reinterpret_cast<u32x4*>(smem);                     // [NS][STAGE_V]
     int32_t* s_tok2 = reinterpret_cast<int32_t*>(ring + NS * STAGE_V); // [2][BM] output row of each tile row, -1 = none
@@ -433,16 +438,17 @@ gemm_mfma_kernel(GemmArgs a) {
     const int64_t a_off = (a.conv ? ((int64_t)ty_ * a.geom.ppw + tx_) * a.lda : 0) + (kc_) * BK;                  \
     const int64_t b_off = (tap_) * b_tap_stride + (kc_) * BK;
     // the first NS steps of a tile: all stages in flight
-#define PS_PROLOGUE()                                                                                             \
+#define PS_PROLOGUE_STAGES(st0_, st1_)                                                                            \
     {                                                                                                             \
-        tap = 0; kc = 0; issued = 0;                                                                              \
-        _Pragma("unroll") for (int st = 0; st < NS; ++st) {                                                       \
+        if ((st0_) == 0) { tap = 0; kc = 0; issued = 0; }                                                         \
+        _Pragma("unroll") for (int st = (st0_); st < (st1_); ++st) {                                              \
             PS_OFFSETS(tap, kc);                                                                                  \
             u32x4* dst = ring + st * STAGE_V + wave * 64;                                                         \
             _Pragma("unroll") for (int l = 0; l < LD; ++l) PS_LOAD(dst, a_off, b_off, l);                         \
             if (++issued < KT) { if (++kc == kchunks) { kc = 0; ++tap; } } else { issued = KT - 1; }              \
         }                                                                                                         \
     }
+#define PS_PROLOGUE() PS_PROLOGUE_STAGES(0, NS)
 
     const int fr = lane & 31, fh = lane >> 5;       // fragment row within a 32-row tile, k half
     // LDS fragment slots of this lane: row*CH + ((2*ks + fh) ^ f(row))
@@ -540,18 +546,26 @@ gemm_mfma_kernel(GemmArgs a) {
         if (OVERLAP && nslot < slots) {             // next tile's first steps in flight during this tile's epilogue
             PS_SETUP(nm0, nn0, s_tok2 + (buf ^ 1) * BM);
             PS_PROLOGUE();
+        } else if (HALF && nslot < slots) {         // its first step only: the epilogue stages in the stages behind it
+            PS_SETUP(nm0, nn0, s_tok2 + (buf ^ 1) * BM);
+            PS_PROLOGUE_STAGES(0, 1);
         }
-        gemm_epilogue<BM, BN, GEGLU, WGM, WGN, false>(a, acc, ep_smem, tok_cur, n0_cur, bias_t);
+        gemm_epilogue<BM, BN, GEGLU, WGM, WGN, false>(a, acc, HALF ? smem + STAGE_V * 16 : ep_smem, tok_cur, n0_cur, bias_t);
         if (nslot >= slots) break;
         if (!OVERLAP) {
             __syncthreads();                        // every wavefront is done with its staging region in the ring
-            PS_SETUP(nm0, nn0, s_tok2 + (buf ^ 1) * BM);
-            PS_PROLOGUE();
+            if (HALF) {
+                PS_PROLOGUE_STAGES(1, NS);
+            } else {
+                PS_SETUP(nm0, nn0, s_tok2 + (buf ^ 1) * BM);
+                PS_PROLOGUE();
+            }
         }
         slot = nslot; m0 = nm0; n0 = nn0; buf ^= 1;
     }
 #undef PS_READ_ONE
 #undef PS_PROLOGUE
+#undef PS_PROLOGUE_STAGES
 #undef PS_OFFSETS
 #undef PS_LOAD
 #undef PS_SETUP
