@@ -301,6 +301,11 @@ def measure(cfg_id, steps, warmup, all_kernels=False, events=True, patch=None, p
                     "traffic": traffic, "traffic_source": source, "avg_us": ent["avg_us"],
                     "peak_measured": measured_peak,
                     "frac_of_measured": (achieved / measured_peak) if (measured_peak and achieved) else None}
+        # the rate of a synthetic stream with this kernel's instruction mix (no memory, no barriers), where probed
+        mix_peak = None if peaks is None else peaks.get({"attn_self": "attention_mix_tflops", "conv3x3": "conv_mix_tflops"}.get(dom))
+        if mix_peak and achieved:
+            roofline["peak_same_mix"] = mix_peak
+            roofline["frac_of_same_mix"] = achieved / mix_peak
     res = {
         "ms_per_step": ms_per_step, "tokens_per_s": cfg.T / (ms_per_step * 1e-3),
         "workload": f"config{cfg.cfg_id} {cfg.name}: latents {sorted(set(cfg.resolutions))} x{cfg.n}, "
@@ -459,9 +464,14 @@ def main():
         # chip lowers its clock with the bit activity of the data, so the second is what a real workload can reach
         const_tf, const_mhz = ps.probe_mfma_bf16(20000, False)
         rand_tf, rand_mhz = ps.probe_mfma_bf16(20000, True)
+        # the same stream with the other instructions of a kernel's inner loop between the MFMAs (softmax work, LDS
+        # fragment reads, row-sum MFMAs): the clock follows the power drawn, so this is the ceiling of that mix
+        attn_tf, attn_mhz = ps.probe_mfma_mix(7, 20000)
+        conv_tf, conv_mhz = ps.probe_mfma_mix(8, 20000)
         peaks = {"mfma_bf16_tflops": rand_tf, "mfma_bf16_mhz": rand_mhz, "mfma_bf16_constant_operands_tflops": const_tf,
-                 "mfma_bf16_constant_operands_mhz": const_mhz, "copy_gbs": ps.probe_copy(big_dst, big_src, reps=5),
-                 "copy_bytes": 2 * big_src.numel()}
+                 "mfma_bf16_constant_operands_mhz": const_mhz, "attention_mix_tflops": attn_tf, "attention_mix_mhz": attn_mhz,
+                 "conv_mix_tflops": conv_tf, "conv_mix_mhz": conv_mhz,
+                 "copy_gbs": ps.probe_copy(big_dst, big_src, reps=5), "copy_bytes": 2 * big_src.numel()}
         del big_src, big_dst
         torch.cuda.empty_cache()
 

@@ -354,17 +354,24 @@ int  pserve_profile_sample(int every);
 int  pserve_profile_read(pserve_prof_entry* out, int32_t max, int32_t* count);
 
 /* ---- peak probes for measurements (no operation of the paper; they give the roofline figures a second reference
- * beside the datasheet).  Both time their own launches with a pair of events on `stream` and wait for them.
+ * beside the datasheet).  All time their own launches with a pair of events on `stream` and wait for them.
  * pserve_probe_mfma_bf16: 512 blocks of four wavefronts, each wavefront issuing 8 * iters independent
  * v_mfma_f32_32x32x16_bf16 on register-resident operands: all 1.0 (random_operands = 0) or standard normals rounded to
  * bf16 (random_operands = 1).  *tflops = dense bf16 rate reached; *mhz (may be NULL) = shader clock inside the timed
  * loop (core cycles per tick of the 100 MHz wall clock).  The chip lowers its clock with the bit activity of the
  * operands, so the second form is the rate a real workload's matrix products can reach.
+ * pserve_probe_mfma_mix: the same stream on standard-normal operands with the other instructions of a kernel's inner
+ * loop between the MFMAs, everything in registers or LDS (no global memory, no barriers): the rate a kernel with that
+ * instruction mix can reach at best on this chip.  `mix` is a sum of 1 (two v_exp_f32 and one v_cvt_pk_bf16_f32 per
+ * MFMA: a softmax), 2 (one 16-byte LDS fragment read per two MFMAs), 4 (one v_mfma_f32_4x4x4_16b_bf16 per two MFMAs:
+ * row sums), so 7 is the inner loop of the self-attention kernel; or 8 alone (seven fragment reads per ten MFMAs: a
+ * 64 x 160 wavefront tile of the convolution / GEMM).  *tflops counts the 32 x 32 x 16 MFMAs only.
  * pserve_probe_copy: a plain 16-byte-per-lane copy of `bytes` bytes from src to dst (DEVICE, 16-byte aligned, not
  * overlapping), `reps` launches; *gbs = (bytes read + bytes written) per second.  A buffer well beyond the 256 MB
  * last-level cache gives the HBM figure; the same launch is the known-size reference for memory counters.
  * Errors: EINVAL, EHIP. */
 int  pserve_probe_mfma_bf16(int iters, int random_operands, double* tflops, double* mhz, void* stream);
+int  pserve_probe_mfma_mix(int iters, int mix, double* tflops, double* mhz, void* stream);
 int  pserve_probe_copy(void* dst, const void* src, size_t bytes, int reps, double* gbs, void* stream);
 
 #ifdef __cplusplus

@@ -119,6 +119,7 @@ def lib() -> C.CDLL:
     L.pserve_patch_mse.argtypes = [vp, vp, vp, i32, C.c_int, vp, vp]
     L.pserve_patch_mse_static.argtypes = [vp, vp, vp, i32, C.c_int, vp, vp]
     L.pserve_probe_mfma_bf16.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double), vp]
+    L.pserve_probe_mfma_mix.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double), vp]
     L.pserve_probe_copy.argtypes = [vp, vp, C.c_size_t, C.c_int, C.POINTER(C.c_double), vp]
     L.pserve_cache_sets.argtypes = [vp, C.POINTER(C.c_int64), vp, C.POINTER(C.c_int64), C.POINTER(i32),
                                     C.POINTER(C.c_uint8), vp, vp]
@@ -177,6 +178,14 @@ def probe_mfma_bf16(iters: int = 20000, random_operands: bool = False):
     """pserve_probe_mfma_bf16: (dense bf16 TFLOP/s of a register-resident MFMA stream, shader clock in MHz inside it)."""
     out, mhz = C.c_double(0.0), C.c_double(0.0)
     _check(lib().pserve_probe_mfma_bf16(iters, 1 if random_operands else 0, C.byref(out), C.byref(mhz), _stream()))
+    return out.value, mhz.value
+
+
+def probe_mfma_mix(mix: int, iters: int = 20000):
+    """pserve_probe_mfma_mix: (bf16 TFLOP/s of the 32 x 32 x 16 MFMAs, shader clock in MHz) of an MFMA stream on
+    standard-normal operands with the instruction mix `mix` between the MFMAs (7: attention inner loop, 8: convolution)."""
+    out, mhz = C.c_double(0.0), C.c_double(0.0)
+    _check(lib().pserve_probe_mfma_mix(iters, int(mix), C.byref(out), C.byref(mhz), _stream()))
     return out.value, mhz.value
 
 

@@ -61,6 +61,84 @@ __global__ void __launch_bounds__(256, 2) probe_mfma_kernel(int iters) {
     if (s == 12345.678f) probe_clk[0] = 0;              // keeps the accumulators alive
 }
 
+// The same stream with other work between the MFMAs, on standard-normal operands: what a kernel with that instruction
+// mix can reach at best on this chip (no global memory, no barriers, every operand in registers or LDS).  The clock
+// follows the power drawn, so an added instruction costs issue time or energy; the probe shows the sum.  MIX bits:
+//   1  two v_exp_f32 and one v_cvt_pk_bf16_f32 per MFMA (the softmax of 32 scores per lane and MFMA pair)
+//   2  one 16-byte LDS fragment read per two MFMAs, into the A operands (they change as in a real kernel)
+//   4  one v_mfma_f32_4x4x4_16b_bf16 per two MFMAs (the row sums)
+//   8  seven 16-byte LDS fragment reads per ten MFMAs instead of bit 2 (a 64 x 160 wavefront tile of a GEMM)
+// 7 is the inner loop of the self-attention kernel, 8 that of the convolution.
+template <int MIX>
+__global__ void __launch_bounds__(256, 2) probe_mix_kernel(int iters) {
+    __shared__ __attribute__((aligned(16))) uint8_t frag[16384];
+    for (int i = threadIdx.x; i < 4096; i += 256) {
+        const __bf16 lo = (__bf16)probe_normal((blockIdx.x * 4096 + i) * 2u), hi = (__bf16)probe_normal((blockIdx.x * 4096 + i) * 2u + 1u);
+        reinterpret_cast<uint32_t*>(frag)[i] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
+    }
+    __syncthreads();
+    bf16x8 a[PROBE_FRAG], b[PROBE_FRAG];
+#pragma unroll
+    for (int n = 0; n < PROBE_FRAG; ++n)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            a[n][i] = (__bf16)probe_normal((threadIdx.x * 64 + n * 16 + i) * 2u);
+            b[n][i] = (__bf16)probe_normal((threadIdx.x * 64 + n * 16 + i) * 2u + 1u);
+        }
+    f32x16 acc[PROBE_ACC];
+#pragma unroll
+    for (int n = 0; n < PROBE_ACC; ++n)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[n][e] = 0.f;
+    typedef __attribute__((ext_vector_type(4))) float f32x4;
+    typedef __attribute__((ext_vector_type(4))) short s16x4;
+    f32x4 accl = {0.f, 0.f, 0.f, 0.f};
+    const s16x4 ones = {0x3f80, 0x3f80, 0x3f80, 0x3f80};
+    float ex[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) ex[i] = probe_normal(threadIdx.x * 8 + i);
+    uint32_t pk[4] = {0u, 0u, 0u, 0u};
+    const int lane = threadIdx.x & 63;
+    // fragment address: row lane % 32 of a 128-byte-row tile, chunk swizzled as in the kernels (no bank conflicts)
+    uint32_t addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)frag + (lane & 31) * 128 +
+                    16 * ((lane >> 5) ^ (((lane & 31) >> 1) & 7));
+    const long long c0 = clock64(), w0 = wall_clock64();
+    for (int it = 0; it < iters; ++it) {
+        constexpr int NM = (MIX & 8) ? 10 : 8;
+#pragma unroll
+        for (int j = 0; j < NM; ++j) {
+            asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc[j & 3]) : "v"(a[j & 3]), "v"(b[(j >> 1) & 3]));
+            if (MIX & 1) {
+                asm volatile("v_exp_f32 %0, %1" : "=v"(ex[j & 7]) : "v"(acc[(j + 1) & 3][j]));
+                asm volatile("v_exp_f32 %0, %1" : "=v"(ex[(j + 4) & 7]) : "v"(acc[(j + 1) & 3][(j + 8) & 15]));
+                asm volatile("s_nop 0\n\tv_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(pk[j & 3]) : "v"(ex[j & 7]), "v"(ex[(j + 3) & 7]));
+            }
+            if (((MIX & 2) && (j & 1)) || ((MIX & 8) && j < 7))
+                asm volatile("ds_read_b128 %0, %1" : "=v"(a[(j + 2) & 3]) : "v"(addr));
+            if ((MIX & 4) && !(j & 1)) {
+                const s16x4 p4 = {(short)pk[j & 2], (short)(pk[j & 2] >> 16), (short)pk[(j & 2) + 1], (short)(pk[(j & 2) + 1] >> 16)};
+                asm volatile("v_mfma_f32_4x4x4_16b_bf16 %0, %1, %2, %0" : "+v"(accl) : "v"(ones), "v"(p4));
+            }
+        }
+        addr ^= 4096u << (it & 1);                              // other fragments next time
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        if ((it & 63) == 63) {
+#pragma unroll
+            for (int n = 0; n < PROBE_ACC; ++n)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[n][e] *= 1e-3f;
+        }
+    }
+    const long long c1 = clock64(), w1 = wall_clock64();
+    if (threadIdx.x == 0 && blockIdx.x < 512) { probe_clk[2 * blockIdx.x] = c1 - c0; probe_clk[2 * blockIdx.x + 1] = w1 - w0; }
+    float s = accl[0];
+#pragma unroll
+    for (int n = 0; n < PROBE_ACC; ++n) s += acc[n][0] + __uint_as_float(pk[n]);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s += ex[i];
+    if (s == 12345.678f) probe_clk[0] = 0;
+}
+
 // four independent 16-byte loads in flight per lane, then the four stores
 __global__ void __launch_bounds__(256) probe_copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, int64_t n16) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -116,6 +194,39 @@ int pserve_probe_mfma_bf16(int iters, int random_operands, double* tflops, doubl
         return check_launch("probe_mfma_kernel");
     }, &ms));
     const double flops = (double)blocks * 4 * (double)iters * 8 * (2.0 * 32 * 32 * 16);
+    *tflops = flops / ((double)ms * 1e-3) / 1e12;
+    if (mhz) {
+        static long long h[2 * 512];
+        PS_CHECK_HIP(hipMemcpyFromSymbol(h, HIP_SYMBOL(probe_clk), sizeof(h)));
+        double cycles = 0.0, ticks = 0.0;
+        for (int i = 0; i < blocks; ++i) { cycles += (double)h[2 * i]; ticks += (double)h[2 * i + 1]; }
+        *mhz = ticks > 0.0 ? cycles / ticks * 100.0 : 0.0;
+    }
+    return PSERVE_OK;
+}
+
+int pserve_probe_mfma_mix(int iters, int mix, double* tflops, double* mhz, void* stream) {
+    PS_REQUIRE(tflops && iters > 0 && iters <= (1 << 22), "pserve_probe_mfma_mix: need tflops and 0 < iters <= 2^22");
+    PS_REQUIRE(mix == 0 || mix == 1 || mix == 2 || mix == 3 || mix == 4 || mix == 5 || mix == 6 || mix == 7 || mix == 8,
+               "pserve_probe_mfma_mix: mix is 0..7 or 8");
+    hipStream_t st = (hipStream_t)stream;
+    const int blocks = 512;
+    float ms = 0.f;
+    PS_TRY(time_launches(st, 3, [&] {
+        switch (mix) {
+        case 0: probe_mix_kernel<0><<<blocks, 256, 0, st>>>(iters); break;
+        case 1: probe_mix_kernel<1><<<blocks, 256, 0, st>>>(iters); break;
+        case 2: probe_mix_kernel<2><<<blocks, 256, 0, st>>>(iters); break;
+        case 3: probe_mix_kernel<3><<<blocks, 256, 0, st>>>(iters); break;
+        case 4: probe_mix_kernel<4><<<blocks, 256, 0, st>>>(iters); break;
+        case 5: probe_mix_kernel<5><<<blocks, 256, 0, st>>>(iters); break;
+        case 6: probe_mix_kernel<6><<<blocks, 256, 0, st>>>(iters); break;
+        case 7: probe_mix_kernel<7><<<blocks, 256, 0, st>>>(iters); break;
+        default: probe_mix_kernel<8><<<blocks, 256, 0, st>>>(iters); break;
+        }
+        return check_launch("probe_mix_kernel");
+    }, &ms));
+    const double flops = (double)blocks * 4 * (double)iters * (mix == 8 ? 10 : 8) * (2.0 * 32 * 32 * 16);   // the 32 x 32 x 16 MFMAs only
     *tflops = flops / ((double)ms * 1e-3) / 1e12;
     if (mhz) {
         static long long h[2 * 512];
