@@ -336,7 +336,7 @@ attn_mfma_kernel(AttnArgs a) {
 // 20 clocks.  So the softmax has to ride behind the MFMAs of the SAME wavefront.  The work of a wavefront is cut into
 // units of (32 keys, 32 queries), and in every step the 4 score MFMAs of the NEXT unit and the 4 output MFMAs of the
 // PREVIOUS unit are issued alternately, with the 16 exponentials and 8 packs of the CURRENT unit spread over the eight
-// MFMA slots (the three are independent of each other); the row sums are taken by four small MFMAs per unit.  The two query sub-tiles of a wavefront
+// MFMA slots (the three are independent of each other); the row sums are two running fp32 additions per pair of exponentials.  The two query sub-tiles of a wavefront
 // alternate as units, so their score tiles and probability fragments are the double buffers.  Key fragments of the next
 // half tile and value fragments of the current one are refilled from LDS right behind the MFMA that last read the
 // register, eight MFMA slots before they are needed.  Because the scores of a tile's first unit are formed during the
@@ -473,15 +473,12 @@ attn_pipe_kernel(AttnArgs a) {
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) fv[i] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});   // the first step's output MFMAs add 0 * 0
-    // Row sums by the matrix pipe: v_mfma_f32_4x4x4_16b_bf16 with an all-ones A operand adds up the four bf16 values
-    // a lane holds in its B operand (16 independent 4 x 4 x 4 products: D[i][j] = sum over k of B[k][j], every lane owning
-    // one column j of its block) and accumulates them onto acc_l; four such instructions (two passes each) per unit
-    // instead of 16 additions, and the sum is that of the rounded probabilities, i.e. of what multiplies V.
-    typedef __attribute__((ext_vector_type(4))) short s16x4;
-    typedef __attribute__((ext_vector_type(4))) float f32x4;
-    f32x4 acc_l[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-    s16x4 ones4 = {0x3f80, 0x3f80, 0x3f80, 0x3f80};
-    asm volatile("" : "+v"(ones4));                             // kept in registers: not formed again inside the loop
+    // Row sums on the vector unit: every exponential is added to one of two running sums per query sub-tile (fp32, before
+    // the rounding to bf16; the rounding errors of the probabilities that multiply V are unbiased).  Four
+    // v_mfma_f32_4x4x4_16b_bf16 per unit with an all-ones operand did the same on the matrix pipe; a register-resident
+    // stream with this loop's instruction mix is 5 % faster with the additions (the small MFMAs hold the pipe for two
+    // passes each), the kernel 2.7 %.
+    float lsum[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
 
     // LDS byte addresses of this lane's fragments in stage 0.  Key fragment ks of half H: row kperm(fr) + 32 H (half 1 is
     // 4 KB further), chunk (2 ks + fh) ^ swizzle.  Value fragment (H, k2, dt): row fr + 32 dt (dt = 1 is 4 KB further),
@@ -500,18 +497,32 @@ attn_pipe_kernel(AttnArgs a) {
 #define PS_LDS(addr_) __builtin_bit_cast(bf16x8, *(lds_frag)(uintptr_t)(addr_))
 
     // One MFMA slot's share of the softmax of the unit whose scores are acc_s[QT]: the two exponentials of pair G, and
-    // the bf16 pack of pair G-1 (one slot later, so that nothing waits for an exponential).
-#define PS_SOFT(QT, G)                                                                                           \
+    // the bf16 pack and the two row-sum additions of pair G-1 (one slot later, so that nothing waits for an
+    // exponential).  Pack and additions are one block of assembly: as separate instructions the compiler's scheduler no
+    // longer keeps the slot order (with 16 more vector instructions per step it falls back into clumps of
+    // exponentials), and a block that nothing ties down sinks to the end of the step.  Two operands that pass through
+    // the block untouched tie it down: PIN, an accumulator element that this slot's MFMA has just written (the block
+    // follows that MFMA), and the first score of pair G (the block precedes that pair's exponentials).  The pack comes
+    // LAST in the block: its result may be given the register of one of the block's inputs (an output that is not
+    // marked early-clobber), and the additions read those inputs.  The s_nop is the wait state a vector instruction
+    // needs behind the transcendental whose result it reads, should the two ever end up next to each other; nothing
+    // else in the block can meet a hazard the compiler does not see: it writes only its own results (never a register
+    // an MFMA in flight reads as its addend or writes) and reads only exponentials of an earlier slot.
+#define PS_SOFT(QT, G, PIN)                                                                                      \
     {                                                                                                            \
-        if ((G) > 0) fp[QT][((G) - 1) >> 2][((G) - 1) & 3] = pack_bf16x2(e0_, e1_);                              \
+        if ((G) > 0) {                                                                                           \
+            uint32_t pk_;                                                                                        \
+            asm("s_nop 0\n\tv_add_f32 %[l0], %[l0], %[e0]\n\tv_add_f32 %[l1], %[l1], %[e1]\n\tv_cvt_pk_bf16_f32 %[pk], %[e0], %[e1]" \
+                : [pk] "=v"(pk_), [l0] "+v"(lsum[QT][0]), [l1] "+v"(lsum[QT][1]), "+v"(acc_s[QT][(G) < 8 ? 2 * (G) : 0]), "+v"(PIN) \
+                : [e0] "v"(e0_), [e1] "v"(e1_));                                                                 \
+            fp[QT][((G) - 1) >> 2][((G) - 1) & 3] = pk_;                                                         \
+        }                                                                                                        \
         if ((G) < 8) {                                                                                           \
             e0_ = __builtin_amdgcn_exp2f(acc_s[QT][2 * (G)]);                                                    \
             e1_ = __builtin_amdgcn_exp2f(acc_s[QT][2 * (G) + 1]);                                                \
         }                                                                                                        \
     }
 #define PS_MFMA_O(QT, J) acc_o[QT][(J) & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv[J], __builtin_bit_cast(bf16x8, fp[QT][(J) >> 1]), acc_o[QT][(J) & 1], 0, 0, 0)
-#define PS_MFMA_L(QT, J)                                                                                         \
-    acc_l[QT] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(ones4, __builtin_bit_cast(s16x4, u32x2{fp[QT][(J) >> 1][2 * ((J) & 1)], fp[QT][(J) >> 1][2 * ((J) & 1) + 1]}), acc_l[QT], 0, 0, 0)
 #define PS_MFMA_S(QT, J) acc_s[QT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk[J], fq[QT][J], (J) == 0 ? zero16 : acc_s[QT], 0, 0, 0)
     // keys past the end of the sequence (last tile only): their scores become -inf
 #define PS_MASK(QT, KEY0)                                                                                        \
@@ -560,26 +571,21 @@ attn_pipe_kernel(AttnArgs a) {
         LEAD;                                                                                                    \
         _Pragma("unroll") for (int j_ = 0; j_ < 4; ++j_) {                                                       \
             PS_MFMA_S(1, j_);                                                                                    \
-            PS_SOFT(0, 2 * j_)                                                                                   \
+            PS_SOFT(0, 2 * j_, acc_s[1][0])                                                                                   \
             fk[j_] = PS_LDS(ka[j_] + (KOFF));                                                                    \
             PS_MFMA_O(1, j_);                                                                                    \
-            PS_MFMA_L(1, j_);                                                                                    \
-            PS_SOFT(0, 2 * j_ + 1)                                                                               \
+            PS_SOFT(0, 2 * j_ + 1, acc_o[1][j_ & 1][0])                                                                               \
             fv[j_] = PS_LDS(va[2 * (H) + (j_ >> 1)] + (j_ & 1) * 4096);                                          \
         }                                                                                                        \
-        PS_SOFT(0, 8)                                                                                            \
+        PS_SOFT(0, 8, acc_o[1][1][1])                                                                                            \
         _Pragma("unroll") for (int j_ = 0; j_ < 4; ++j_) {                                                       \
             PS_SGB(0x008, 1);                                                                                    \
             PS_SGB(0x100, 1);                                                                                    \
             PS_SGB(0x400, 2);                                                                                    \
-            if (j_ > 0) PS_SGB(0x002, 1);                                                                        \
             PS_SGB(0x008, 1);                                                                                    \
             PS_SGB(0x100, 1);                                                                                    \
-            PS_SGB(0x008, 1);                                                                                    \
             PS_SGB(0x400, 2);                                                                                    \
-            PS_SGB(0x002, 1);                                                                                    \
         }                                                                                                        \
-        PS_SGB(0x002, 1);                                                                                        \
         PS_FENCE;                                                                                                \
     }
 #define PS_STEP1(LEAD)                                                                                           \
@@ -588,21 +594,17 @@ attn_pipe_kernel(AttnArgs a) {
         LEAD;                                                                                                    \
         _Pragma("unroll") for (int j_ = 0; j_ < 4; ++j_) {                                                       \
             PS_MFMA_S(0, j_);                                                                                    \
-            PS_SOFT(1, 2 * j_)                                                                                   \
+            PS_SOFT(1, 2 * j_, acc_s[0][0])                                                                                   \
             PS_MFMA_O(0, j_);                                                                                    \
-            PS_MFMA_L(0, j_);                                                                                    \
-            PS_SOFT(1, 2 * j_ + 1)                                                                               \
+            PS_SOFT(1, 2 * j_ + 1, acc_o[0][j_ & 1][0])                                                                               \
         }                                                                                                        \
-        PS_SOFT(1, 8)                                                                                            \
+        PS_SOFT(1, 8, acc_o[0][1][1])                                                                                            \
         _Pragma("unroll") for (int j_ = 0; j_ < 4; ++j_) {                                                       \
             PS_SGB(0x008, 1);                                                                                    \
             PS_SGB(0x400, 2);                                                                                    \
-            if (j_ > 0) PS_SGB(0x002, 1);                                                                        \
-            PS_SGB(0x008, 2);                                                                                    \
+            PS_SGB(0x008, 1);                                                                                    \
             PS_SGB(0x400, 2);                                                                                    \
-            PS_SGB(0x002, 1);                                                                                    \
         }                                                                                                        \
-        PS_SGB(0x002, 1);                                                                                        \
         PS_FENCE;                                                                                                \
     }
 
@@ -663,7 +665,6 @@ attn_pipe_kernel(AttnArgs a) {
 #pragma unroll
     for (int j_ = 0; j_ < 4; ++j_) {
         PS_MFMA_O(1, j_);
-        PS_MFMA_L(1, j_);
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");        // no load may still target LDS when the block moves on
 #undef PS_STEP0
@@ -674,7 +675,6 @@ attn_pipe_kernel(AttnArgs a) {
 #undef PS_FENCE
 #undef PS_MASK
 #undef PS_MFMA_S
-#undef PS_MFMA_L
 #undef PS_MFMA_O
 #undef PS_SOFT
 #undef PS_LDS
@@ -687,7 +687,8 @@ attn_pipe_kernel(AttnArgs a) {
     bool fine = true;
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt) {
-        const float l = acc_l[qt][0] + other_half(acc_l[qt][0]);
+        const float lown = lsum[qt][0] + lsum[qt][1];
+        const float l = lown + other_half(lown);
         fine = fine && l >= ATT_L_MIN && l <= ATT_L_MAX;
         inv[qt] = 1.f / l;
     }
