@@ -466,7 +466,7 @@ def main():
         rand_tf, rand_mhz = ps.probe_mfma_bf16(20000, True)
         # the same stream with the other instructions of a kernel's inner loop between the MFMAs (softmax work, LDS
         # fragment reads, row-sum MFMAs): the clock follows the power drawn, so this is the ceiling of that mix
-        attn_tf, attn_mhz = ps.probe_mfma_mix(7, 20000)
+        attn_tf, attn_mhz = ps.probe_mfma_mix(19, 20000)
         conv_tf, conv_mhz = ps.probe_mfma_mix(8, 20000)
         peaks = {"mfma_bf16_tflops": rand_tf, "mfma_bf16_mhz": rand_mhz, "mfma_bf16_constant_operands_tflops": const_tf,
                  "mfma_bf16_constant_operands_mhz": const_mhz, "attention_mix_tflops": attn_tf, "attention_mix_mhz": attn_mhz,

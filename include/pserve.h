@@ -364,8 +364,9 @@ int  pserve_profile_read(pserve_prof_entry* out, int32_t max, int32_t* count);
  * loop between the MFMAs, everything in registers or LDS (no global memory, no barriers): the rate a kernel with that
  * instruction mix can reach at best on this chip.  `mix` is a sum of 1 (two v_exp_f32 and one v_cvt_pk_bf16_f32 per
  * MFMA: a softmax), 2 (one 16-byte LDS fragment read per two MFMAs), 4 (one v_mfma_f32_4x4x4_16b_bf16 per two MFMAs:
- * row sums), so 7 is the inner loop of the self-attention kernel; or 8 alone (seven fragment reads per ten MFMAs: a
- * 64 x 160 wavefront tile of the convolution / GEMM).  *tflops counts the 32 x 32 x 16 MFMAs only.
+ * row sums on the matrix pipe), 16 (two v_add_f32 per MFMA: row sums on the vector unit), so 19 is the inner loop of the
+ * self-attention kernel; or 8 alone (seven fragment reads per ten MFMAs: a 64 x 160 wavefront tile of the convolution /
+ * GEMM).  *tflops counts the 32 x 32 x 16 MFMAs only.
  * pserve_probe_copy: a plain 16-byte-per-lane copy of `bytes` bytes from src to dst (DEVICE, 16-byte aligned, not
  * overlapping), `reps` launches; *gbs = (bytes read + bytes written) per second.  A buffer well beyond the 256 MB
  * last-level cache gives the HBM figure; the same launch is the known-size reference for memory counters.

@@ -183,7 +183,7 @@ def probe_mfma_bf16(iters: int = 20000, random_operands: bool = False):
 
 def probe_mfma_mix(mix: int, iters: int = 20000):
     """pserve_probe_mfma_mix: (bf16 TFLOP/s of the 32 x 32 x 16 MFMAs, shader clock in MHz) of an MFMA stream on
-    standard-normal operands with the instruction mix `mix` between the MFMAs (7: attention inner loop, 8: convolution)."""
+    standard-normal operands with the instruction mix `mix` between the MFMAs (19: attention inner loop, 8: convolution)."""
     out, mhz = C.c_double(0.0), C.c_double(0.0)
     _check(lib().pserve_probe_mfma_mix(iters, int(mix), C.byref(out), C.byref(mhz), _stream()))
     return out.value, mhz.value

@@ -68,7 +68,8 @@ __global__ void __launch_bounds__(256, 2) probe_mfma_kernel(int iters) {
 //   2  one 16-byte LDS fragment read per two MFMAs, into the A operands (they change as in a real kernel)
 //   4  one v_mfma_f32_4x4x4_16b_bf16 per two MFMAs (the row sums)
 //   8  seven 16-byte LDS fragment reads per ten MFMAs instead of bit 2 (a 64 x 160 wavefront tile of a GEMM)
-// 7 is the inner loop of the self-attention kernel, 8 that of the convolution.
+//  16  two v_add_f32 per MFMA (the row sums on the vector unit)
+// 19 is the inner loop of the self-attention kernel (7 with the row sums it had before), 8 that of the convolution.
 template <int MIX>
 __global__ void __launch_bounds__(256, 2) probe_mix_kernel(int iters) {
     __shared__ __attribute__((aligned(16))) uint8_t frag[16384];
@@ -115,6 +116,10 @@ __global__ void __launch_bounds__(256, 2) probe_mix_kernel(int iters) {
             }
             if (((MIX & 2) && (j & 1)) || ((MIX & 8) && j < 7))
                 asm volatile("ds_read_b128 %0, %1" : "=v"(a[(j + 2) & 3]) : "v"(addr));
+            if (MIX & 16) {
+                asm volatile("v_add_f32 %0, %0, %1" : "+v"(accl[0]) : "v"(ex[(j + 2) & 7]));
+                asm volatile("v_add_f32 %0, %0, %1" : "+v"(accl[1]) : "v"(ex[(j + 6) & 7]));
+            }
             if ((MIX & 4) && !(j & 1)) {
                 const s16x4 p4 = {(short)pk[j & 2], (short)(pk[j & 2] >> 16), (short)pk[(j & 2) + 1], (short)(pk[(j & 2) + 1] >> 16)};
                 asm volatile("v_mfma_f32_4x4x4_16b_bf16 %0, %1, %2, %0" : "+v"(accl) : "v"(ones), "v"(p4));
@@ -207,25 +212,21 @@ int pserve_probe_mfma_bf16(int iters, int random_operands, double* tflops, doubl
 
 int pserve_probe_mfma_mix(int iters, int mix, double* tflops, double* mhz, void* stream) {
     PS_REQUIRE(tflops && iters > 0 && iters <= (1 << 22), "pserve_probe_mfma_mix: need tflops and 0 < iters <= 2^22");
-    PS_REQUIRE(mix == 0 || mix == 1 || mix == 2 || mix == 3 || mix == 4 || mix == 5 || mix == 6 || mix == 7 || mix == 8,
-               "pserve_probe_mfma_mix: mix is 0..7 or 8");
+    PS_REQUIRE(mix == 8 || (mix >= 0 && mix < 32 && !(mix & 8)), "pserve_probe_mfma_mix: mix is a sum of 1, 2, 4, 16, or 8 alone");
     hipStream_t st = (hipStream_t)stream;
     const int blocks = 512;
     float ms = 0.f;
-    PS_TRY(time_launches(st, 3, [&] {
+#define PS_MIX_CASE(m_) case m_: probe_mix_kernel<m_><<<blocks, 256, 0, st>>>(iters); break;
+    auto launch = [&] {
         switch (mix) {
-        case 0: probe_mix_kernel<0><<<blocks, 256, 0, st>>>(iters); break;
-        case 1: probe_mix_kernel<1><<<blocks, 256, 0, st>>>(iters); break;
-        case 2: probe_mix_kernel<2><<<blocks, 256, 0, st>>>(iters); break;
-        case 3: probe_mix_kernel<3><<<blocks, 256, 0, st>>>(iters); break;
-        case 4: probe_mix_kernel<4><<<blocks, 256, 0, st>>>(iters); break;
-        case 5: probe_mix_kernel<5><<<blocks, 256, 0, st>>>(iters); break;
-        case 6: probe_mix_kernel<6><<<blocks, 256, 0, st>>>(iters); break;
-        case 7: probe_mix_kernel<7><<<blocks, 256, 0, st>>>(iters); break;
+        PS_MIX_CASE(0) PS_MIX_CASE(1) PS_MIX_CASE(2) PS_MIX_CASE(3) PS_MIX_CASE(4) PS_MIX_CASE(5) PS_MIX_CASE(6) PS_MIX_CASE(7)
+        PS_MIX_CASE(16) PS_MIX_CASE(17) PS_MIX_CASE(18) PS_MIX_CASE(19) PS_MIX_CASE(20) PS_MIX_CASE(21) PS_MIX_CASE(22) PS_MIX_CASE(23)
         default: probe_mix_kernel<8><<<blocks, 256, 0, st>>>(iters); break;
         }
         return check_launch("probe_mix_kernel");
-    }, &ms));
+    };
+#undef PS_MIX_CASE
+    PS_TRY(time_launches(st, 3, launch, &ms));
     const double flops = (double)blocks * 4 * (double)iters * (mix == 8 ? 10 : 8) * (2.0 * 32 * 32 * 16);   // the 32 x 32 x 16 MFMAs only
     *tflops = flops / ((double)ms * 1e-3) / 1e12;
     if (mhz) {
