@@ -737,6 +737,16 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
         constexpr int ROLE = decltype(role_c)::value;
         constexpr bool issue_b = ROLE != 2, issue_a = ROLE != 1;
         constexpr int koff = ROLE == 2 ? SUB : 0;       // first sub-step of this wavefront
+        // MFMAs of a step's last sub-step that a wavefront issues IN FRONT of the block barrier (K split only).  With the
+        // barrier at the head of the sub-step every wavefront reaches it right behind its last fragment reads and
+        // waits out their LDS latency there, all eight at the same time and with nothing in the matrix pipe.  A few
+        // MFMAs later the reads have landed: those MFMAs take fragments read a sub-step earlier, and everything that
+        // must follow the barrier (the next step's first fragments, the refill of this step's weight stage) moves
+        // behind the remaining MFMAs.  Different slots for the two K groups also keep the two wavefronts of a SIMD
+        // from reaching their sub-step boundaries together.  Measured (both groups must move; one alone gains
+        // nothing): 513 -> 498 us at C = 640 on 79 k rows, 384 -> 374 us at C = 1280, 62.6 -> 60.7 us at C = 320.
+        constexpr int QB = KS == 1 ? 0 : (ROLE == 1 ? 2 : 5);
+        static_assert(QB + B_LD <= NM && QB + TM <= NM && QB <= NM - TN, "barrier slot");
         int fa_cur[TM], fa_sw[TM];
 #pragma unroll
         for (int i = 0; i < TM; ++i) { fa_cur[i] = fa_slot[i]; fa_sw[i] = (fa_cur[i] >> 1) & 7; }
@@ -746,8 +756,8 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
         // Step = (chunk kc, tap): 4 sub-steps of NM MFMAs.  Every memory instruction rides behind an MFMA: during
         // sub-steps 0..2 the fragment reads of the next sub-step (and, in tap 0, the halo of the next chunk), during
         // sub-step 3 the first fragments of the NEXT step and the refill of this step's weight stage.  The block barrier
-        // sits before sub-step 3: by then every wavefront has read all of this step's fragments (its stage is free) and
-        // has seen its own loads of the next step's weights land.
+        // sits in sub-step 3 (at its head, or QB MFMAs into it): by then every wavefront has read all of this step's
+        // fragments (its stage is free) and has seen its own loads of the next step's weights land.
         int bst = 0;                                    // weight stage of the current step
         for (int kc = 0; kc < kchunks; ++kc) {
             const u32x4* curA = sA + (kc & 1) * ASTAGE;
@@ -770,7 +780,7 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
                 u32x4* dB = sB + bst * BSTAGE + wave * 64;
 #pragma unroll
                 for (int ks = 0; ks < SUB; ++ks) {
-                    if (ks == SUB - 1) {
+                    auto step_barrier = [&] {
                         // own fragment reads of this step are complete; own loads of the next step's weights have landed.
                         // Still allowed in flight: the NSB-2 later weight stages and a halo issued in this or a recent tap 0.
                         // A bare s_barrier: __syncthreads() carries a fence that waits for ALL loads in flight (vmcnt(0)),
@@ -783,13 +793,14 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
                             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((NSB - 2) * B_LD) : "memory");
                         else
                             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-                    }
+                    };
 #pragma unroll
                     for (int i = 0; i < TM; ++i)
 #pragma unroll
                         for (int j = 0; j < TN; ++j) {
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & (FBS - 1)][j], acc[i][j], 0, 0, 0);
                             const int q = i * TN + j;
+                            if (ks == SUB - 1 && q == QB) step_barrier();
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & (FBS - 1)][j], acc[i][j], 0, 0, 0);
                             if (KS == 1) {
 #pragma unroll
                                 for (int u = 0; u < R_PER; ++u) {
@@ -801,10 +812,17 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
                                 // behind the last MFMA that reads the current one (i == TM - 1)
                                 const int r = q < TM ? (q == 0 ? 0 : TN + q) : (i == TM - 1 ? 1 + j : NR);
                                 if (ks < SUB - 1) { PS_READ_ONE((ks + 1) & 1, curA, curB, fa_cur, fa_sw, ks + 1, r); }
-                                else { PS_READ_ONE(0, nxtA, nxtB, nfa_cur, nfa_sw, 0, r); }
+                                else {
+                                    // behind the barrier only: the A fragments from slot QB on, B fragment j where it was
+                                    const int qa = q - QB;
+                                    const int ra = (qa >= 0 && qa < TM) ? (qa == 0 ? 0 : TN + qa) : NR;
+                                    const int rb = i == TM - 1 ? 1 + j : NR;
+                                    PS_READ_ONE(0, nxtA, nxtB, nfa_cur, nfa_sw, 0, ra);
+                                    PS_READ_ONE(0, nxtA, nxtB, nfa_cur, nfa_sw, 0, rb);
+                                }
                             }
                             if (ks == SUB - 1) {
-                                if (q < B_LD && issue_b) PS_LOAD_B(dB, b_off, q);
+                                if (q >= QB && q < QB + B_LD && issue_b) PS_LOAD_B(dB, b_off, q - QB);
                             } else {
 #pragma unroll
                                 for (int u = 0; u < A_PER; ++u) {
