@@ -621,17 +621,29 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
     const int S = a.geom.S, pw = a.geom.pw, hw = pw + 2;
 
     // one direct global->LDS load (64 lanes x 16 bytes) of the weight / halo stage
+    // Buffer loads into LDS rather than global loads into LDS: behind a flat-class load the compiler takes the LDS
+    // counter for out of order and turns every wait for ONE fragment into a wait for all reads in flight
+    // (lgkmcnt(0)), the read issued an instruction earlier included; behind buffer loads it counts (lgkmcnt(4..0)
+    // down a row of MFMAs): 498 -> 487 us at C = 640 on 79 k rows, 374 -> 358 us at C = 1280.  Offsets are 32-bit
+    // byte offsets from the tensor's base (the launch checks that both tensors stay below 2^31 bytes).
+#if defined(__HIP_DEVICE_COMPILE__)
+    const __amdgpu_buffer_rsrc_t b_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)a.B, 0, 0x7fffffff, 0x00020000);
+    const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)a.A, 0, 0x7fffffff, 0x00020000);
 #define PS_LOAD_B(dstB_, off_, i_) \
-    __builtin_amdgcn_global_load_lds((const void*)(b_ptr + (i_) * b_row32 + (off_)), (lds_void*)((dstB_) + (i_) * 256), 16, 0, 0)
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rsrc, (lds_void*)((dstB_) + (i_) * 256), 16, b_lane, (int)(((i_) * b_row32 + (off_)) * 2), 0, 0)
 #define PS_LOAD_A(dstA_, off_, i_) \
-    __builtin_amdgcn_global_load_lds((const void*)(A + a_pos[i_] + (off_)), (lds_void*)((dstA_) + (i_) * 256), 16, 0, 0)
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (lds_void*)((dstA_) + (i_) * 256), 16, a_pos[i_], (int)((off_) * 2), 0, 0)
+#else       // the host pass only needs the kernel's stub
+#define PS_LOAD_B(dstB_, off_, i_) (void)0
+#define PS_LOAD_A(dstA_, off_, i_) (void)0
+#endif
 
     // The weights of the first NSB steps go first: they need no table, and the index arithmetic below runs while
     // they are in flight.  Thread rows lr + 32*i, chunk position lc; the lane fetches global chunk lc ^ f(row).
     const int lc = lane & 7, lr = 8 * wave + (lane >> 3);
     const int gc = lc ^ ((lr >> 1) & 7);
     const uint16_t* B = (const uint16_t*)a.B;
-    const uint16_t* b_ptr = B + (int64_t)(n0 + lr) * a.K + gc * 8;
+    const int b_lane = (int)(((int64_t)(n0 + lr) * a.K + gc * 8) * 2);   // byte offset of this lane's first weight row
     const int64_t b_row32 = (int64_t)32 * a.K;
     const int64_t b_tap_stride = (int64_t)a.N * a.K;
     const int kchunks = a.K / BK;
@@ -670,7 +682,7 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
 
     // halo staging: slot sl = lr + 32*i (pixel slot), chunk position lc; lane fetches global chunk lc ^ f(slot)
     const uint16_t* A = (const uint16_t*)a.A;
-    int32_t a_pos[A_LD];                            // element offsets (the launch checks that the padded buffer stays below 2^31)
+    int32_t a_pos[A_LD];                            // byte offsets (the launch checks that the padded buffer stays below 2^31 bytes)
     const int apix = ct.nseg * ct.seg_pix;
 #pragma unroll
     for (int i = 0; i < A_LD; ++i) {
@@ -678,7 +690,7 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
         if (sl >= apix) sl = 0;                                    // unused slots re-read a valid pixel
         const int g = div_small(sl, ct.m_seg_pix, ct.seg_pix), l = sl - g * ct.seg_pix;
         const int ly = div_small(l, ct.m_hw, hw), lx = l - ly * hw;
-        a_pos[i] = (s_seg[g] + ly * a.geom.ppw + lx) * (int32_t)a.lda + gc * 8;
+        a_pos[i] = ((s_seg[g] + ly * a.geom.ppw + lx) * (int32_t)a.lda + gc * 8) * 2;
     }
     if (pro_a) {                                    // halo of chunk 0: in flight during the rest of the set-up
         u32x4* dA = sA + wave * 64;
@@ -738,13 +750,12 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
         constexpr bool issue_b = ROLE != 2, issue_a = ROLE != 1;
         constexpr int koff = ROLE == 2 ? SUB : 0;       // first sub-step of this wavefront
         // MFMAs of a step's last sub-step that a wavefront issues IN FRONT of the block barrier (K split only).  With the
-        // barrier at the head of the sub-step every wavefront reaches it right behind its last fragment reads and
-        // waits out their LDS latency there, all eight at the same time and with nothing in the matrix pipe.  A few
-        // MFMAs later the reads have landed: those MFMAs take fragments read a sub-step earlier, and everything that
-        // must follow the barrier (the next step's first fragments, the refill of this step's weight stage) moves
-        // behind the remaining MFMAs.  Different slots for the two K groups also keep the two wavefronts of a SIMD
-        // from reaching their sub-step boundaries together.  Measured (both groups must move; one alone gains
-        // nothing): 513 -> 498 us at C = 640 on 79 k rows, 384 -> 374 us at C = 1280, 62.6 -> 60.7 us at C = 320.
+        // barrier at the head of the sub-step a wavefront reaches it right behind its last fragment reads and waits out
+        // their LDS latency there.  A few MFMAs later the reads have landed: those MFMAs take fragments read a
+        // sub-step earlier, and everything that must follow the barrier (the next step's first fragments, the refill
+        // of this step's weight stage) moves behind the remaining MFMAs.  Different slots for the two K groups keep the
+        // two wavefronts of a SIMD from reaching their sub-step boundaries together.  Worth 3 % while every wait for a
+        // fragment was a wait for all reads in flight (see the loads above), about 1 % since.
         constexpr int QB = KS == 1 ? 0 : (ROLE == 1 ? 2 : 5);
         static_assert(QB + B_LD <= NM && QB + TM <= NM && QB <= NM - TN, "barrier slot");
         int fa_cur[TM], fa_sw[TM];
@@ -759,6 +770,11 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
         // sits in sub-step 3 (at its head, or QB MFMAs into it): by then every wavefront has read all of this step's
         // fragments (its stage is free) and has seen its own loads of the next step's weights land.
         int bst = 0;                                    // weight stage of the current step
+        // The two wavefronts of a SIMD compete for the matrix pipe, and the older one (the first K group) wins every
+        // time both have an MFMA ready: it runs ahead to the barrier and waits there a third of the loop's time
+        // (timestamps of a work build) while the second group finishes the step on its own.  With the second group
+        // at the higher priority the first one fills the gaps instead: 1-2 % (347 -> 339 us at C = 1280).
+        if (ROLE == 2) asm volatile("s_setprio 2" ::: "memory");
         for (int kc = 0; kc < kchunks; ++kc) {
             const u32x4* curA = sA + (kc & 1) * ASTAGE;
             const int nkc_a = kc + 1 < kchunks ? kc + 1 : kc;   // halo chunk fetched during tap 0 (last: itself, never read)
@@ -948,8 +964,9 @@ static bool mfma_eligible(const GemmArgs& a) {
 static int conv_select(const GemmArgs& a, ConvTile* ct, int* wave_cols = nullptr) {
     int wc = 0, sel = 0;
     const bool plain3x3 = a.taps == 9 && (a.tap_w == 0 || a.tap_w == 3) && a.a_mul <= 1 && !a.a_dy && !a.a_dx && !a.o_mul;
-    // the kernels address the padded patch buffer with 32-bit element offsets
-    const bool fits32 = (int64_t)a.geom.P * a.geom.pS * a.lda < ((int64_t)1 << 31);
+    // the kernels address the padded patch buffer and the weights with 32-bit byte offsets below 2^31
+    const bool fits32 = (int64_t)a.geom.P * a.geom.pS * a.lda < ((int64_t)1 << 30) &&
+                        (int64_t)a.taps * a.N * a.K < ((int64_t)1 << 30);
     // no gate, no GELU, no transposed segment; a per-request bias only where a wavefront's 64 rows lie in one patch (the
     // kernels compile the epilogue without those paths)
     const bool lean = a.seg[0].scale == 1.f && !a.rowscale && !a.act_gelu && (!a.rowbias || (a.geom.S % 64 == 0 && a.geom.pw <= 64 && 64 % a.geom.pw == 0));
