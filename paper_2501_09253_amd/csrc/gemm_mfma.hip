@@ -376,10 +376,7 @@ gemm_mfma_kernel(GemmArgs a) {
     // f(row) = (row >> 1) & 7, so the swizzle costs nothing.  Thread rows: lr + 32*i, position lc.
     const int lc = lane & 7, lr = 8 * wave + (lane >> 3);
     const int gc = lc ^ ((lr >> 1) & 7);            // global chunk this lane fetches (same for every i)
-    const uint16_t* A = (const uint16_t*)a.A;
-    const uint16_t* B = (const uint16_t*)a.B;
-    const uint16_t* a_ptr[A_LD];
-    const uint16_t* b_ptr;
+    int a_lane[A_LD], b_lane;                       // byte offsets of this lane's rows from the tensors' bases
     const int64_t b_row32 = (int64_t)32 * a.K;
     const int kchunks = a.K / BK;
     const int KT = a.taps * kchunks;
@@ -413,25 +410,33 @@ gemm_mfma_kernel(GemmArgs a) {
             } else {                                                                                              \
                 off = tok * a.lda;                                                                                \
             }                                                                                                     \
-            a_ptr[i] = A + off + gc * 8;                                                                          \
+            a_lane[i] = (int)((off + gc * 8) * 2);                                                                \
             if (lc == 0) {                                                                                        \
                 if (!a.tokens_are_rows && a.row_group > 0)                                                        \
                     orow = (tok / a.row_group) * a.row_group_pad + tok % a.row_group;                             \
                 (tok_tab)[row] = valid ? (int32_t)orow : -1;                                                      \
             }                                                                                                     \
         }                                                                                                         \
-        b_ptr = B + (int64_t)((tn0) + lr) * a.K + gc * 8;                                                         \
+        b_lane = (int)(((int64_t)((tn0) + lr) * a.K + gc * 8) * 2);                                               \
     }
     // one direct global->LDS load (64 lanes x 16 bytes): l < A_LD an A row group, else a B row group
+    // (buffer loads rather than global loads into LDS: behind a flat-class load the compiler turns every wait for one
+    // fragment into a wait for all LDS reads in flight; 2-4 % on every linear layer)
+#if defined(__HIP_DEVICE_COMPILE__)
+    const __amdgpu_buffer_rsrc_t ga_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)a.A, 0, 0x7fffffff, 0x00020000);
+    const __amdgpu_buffer_rsrc_t gb_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)a.B, 0, 0x7fffffff, 0x00020000);
 #define PS_LOAD(dst_, a_off_, b_off_, l_)                                                                         \
     {                                                                                                             \
         if ((l_) < A_LD)                                                                                          \
-            __builtin_amdgcn_global_load_lds((const void*)(a_ptr[(l_) < A_LD ? (l_) : 0] + (a_off_)),             \
-                                             (lds_void*)((dst_) + (l_) * 256), 16, 0, 0);                         \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(ga_rsrc, (lds_void*)((dst_) + (l_) * 256), 16,               \
+                                                     a_lane[(l_) < A_LD ? (l_) : 0], (int)((a_off_) * 2), 0, 0);  \
         else if ((l_) < LD)                                                                                       \
-            __builtin_amdgcn_global_load_lds((const void*)(b_ptr + ((l_) - A_LD) * b_row32 + (b_off_)),           \
-                                             (lds_void*)((dst_) + BM * CH + ((l_) - A_LD) * 256), 16, 0, 0);      \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(gb_rsrc, (lds_void*)((dst_) + BM * CH + ((l_) - A_LD) * 256), 16, \
+                                                     b_lane, (int)((((l_) - A_LD) * b_row32 + (b_off_)) * 2), 0, 0); \
     }
+#else       // the host pass only needs the kernel's stub
+#define PS_LOAD(dst_, a_off_, b_off_, l_) (void)0
+#endif
     // global offsets of K step (tap, kc)
 #define PS_OFFSETS(tap_, kc_)                                                                                     \
     const int ty_ = (tap_) / tap_w, tx_ = (tap_) - ty_ * tap_w;                                                   \
@@ -642,7 +647,6 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
     // they are in flight.  Thread rows lr + 32*i, chunk position lc; the lane fetches global chunk lc ^ f(row).
     const int lc = lane & 7, lr = 8 * wave + (lane >> 3);
     const int gc = lc ^ ((lr >> 1) & 7);
-    const uint16_t* B = (const uint16_t*)a.B;
     const int b_lane = (int)(((int64_t)(n0 + lr) * a.K + gc * 8) * 2);   // byte offset of this lane's first weight row
     const int64_t b_row32 = (int64_t)32 * a.K;
     const int64_t b_tap_stride = (int64_t)a.N * a.K;
@@ -680,7 +684,6 @@ conv_mfma_kernel(GemmArgs a, ConvTile ct) {
     }
     __syncthreads();
 
-    // halo staging: slot sl = lr + 32*i (pixel slot), chunk position lc; lane fetches global chunk lc ^ f(slot)
     const uint16_t* A = (const uint16_t*)a.A;
     int32_t a_pos[A_LD];                            // byte offsets (the launch checks that the padded buffer stays below 2^31 bytes)
     const int apix = ct.nseg * ct.seg_pix;
@@ -954,7 +957,10 @@ static int launch(const GemmArgs& a, hipStream_t st) {
 
 // shapes the MFMA kernels take at all
 static bool mfma_eligible(const GemmArgs& a) {
-    return a.K % 64 == 0 && a.lda % 8 == 0 && !((uintptr_t)a.A & 15) && !((uintptr_t)a.B & 15);
+    // the kernels stage both operands by buffer loads with 32-bit byte offsets from the tensors' bases
+    const int64_t a_rows = a.conv ? (int64_t)a.geom.P * a.geom.pS : (int64_t)a.M;
+    const bool fits = a_rows * a.lda < ((int64_t)1 << 30) && (int64_t)a.taps * a.N * a.K < ((int64_t)1 << 30);
+    return a.K % 64 == 0 && a.lda % 8 == 0 && !((uintptr_t)a.A & 15) && !((uintptr_t)a.B & 15) && fits;
 }
 
 // Which halo-in-LDS convolution kernel a problem takes (0: none) and the columns one wavefront of it covers.
