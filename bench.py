@@ -171,7 +171,7 @@ def measure(cfg_id, steps, warmup, all_kernels=False, events=True, patch=None, p
     outs = [torch.empty_like(im) for im in run.images]
 
     def step():
-        run.plan.split(run.images, out=run.x)
+        run.plan.split(run.images, out=run.x, cache=run.cache)      # also takes the first norm's statistics where it can
         run.cache.forward(run.x, None if run.joint else run.ctx, mask, y=y, temb=run.temb)
         run.plan.reassemble(y, outs)
 

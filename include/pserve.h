@@ -175,6 +175,18 @@ int  pserve_split(const pserve_plan_t* plan, const void* const* images, int32_t 
                   void* x, void* stream);
 int  pserve_reassemble(const pserve_plan_t* plan, const void* y, int32_t C, int dtype,
                        void* const* images, void* stream);
+/* pserve_split that also takes the statistics of the block's first normalisation while the
+ * data passes through ("Patch-Tailored Diffusion Operators": the group statistics of a
+ * request are those of all its patches): same x, bit for bit; per (patch, token chunk,
+ * channel) the mean and the sum of squared deviations go into scratch of `cache` (a cache
+ * of this plan), and the NEXT pserve_block_forward call of that cache on this x merges them
+ * instead of reading x once more.  Single use: any other forward call, or a later change of
+ * x, needs a new split.  Call it on the stream of that forward call (or order the two).
+ * Where the fast path does not apply (fp32, channel counts or patch shapes it does not
+ * cover, reference kernel mode, joint plans) it is pserve_split and the forward call takes
+ * its own statistics.  Errors: EINVAL for NULL arguments or a cache of another plan. */
+int  pserve_split_stats(const pserve_plan_t* plan, const void* const* images, int32_t C, int dtype,
+                        void* x, pserve_cache_t* cache, void* stream);
 
 /* ---- block: description + weights.  Packs the weights into the layouts the kernels
  * read (device copies owned by the block); the caller's parameter buffers are not

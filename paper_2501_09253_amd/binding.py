@@ -101,6 +101,7 @@ def lib() -> C.CDLL:
     L.pserve_text_scatter.argtypes = [vp, vp, i32, C.c_int, vp, vp]
     L.pserve_text_gather.argtypes = [vp, vp, i32, C.c_int, vp, vp]
     L.pserve_split.argtypes = [vp, C.POINTER(vp), i32, C.c_int, vp, vp]
+    L.pserve_split_stats.argtypes = [vp, C.POINTER(vp), i32, C.c_int, vp, vp, vp]
     L.pserve_reassemble.argtypes = [vp, vp, i32, C.c_int, C.POINTER(vp), vp]
     L.pserve_block_create.argtypes = [C.POINTER(_BlockDesc), C.POINTER(_BlockParams), vp, C.POINTER(vp)]
     L.pserve_block_free.argtypes = [vp]
@@ -255,8 +256,10 @@ class Plan:
         _check(lib().pserve_plan_table(self._h, TABLES[name], 1, C.byref(ptr), C.byref(cnt)))
         return C.cast(ptr, C.c_void_p).value
 
-    def split(self, images, out=None):
-        """Per-request NCHW device tensors (caller order) -> patch-major token matrix x[T, C]."""
+    def split(self, images, out=None, cache=None):
+        """Per-request NCHW device tensors (caller order) -> patch-major token matrix x[T, C].  With `cache` (a Cache of
+        this plan) the pass also leaves the input's GroupNorm moments behind for the cache's next forward call on x
+        (pserve_split_stats)."""
         import torch
         Cc = images[0].shape[0]
         dt = BF16 if images[0].dtype == torch.bfloat16 else F32
@@ -265,7 +268,10 @@ class Plan:
         ptrs = (C.c_void_p * self.n)(*[im.data_ptr() for im in images])
         for im, (h, w) in zip(images, self.resolutions):
             assert im.is_contiguous() and tuple(im.shape) == (Cc, h, w) and im.dtype == images[0].dtype
-        _check(lib().pserve_split(self._h, ptrs, Cc, dt, out.data_ptr(), _stream()))
+        if cache is not None:
+            _check(lib().pserve_split_stats(self._h, ptrs, Cc, dt, out.data_ptr(), cache._h, _stream()))
+        else:
+            _check(lib().pserve_split(self._h, ptrs, Cc, dt, out.data_ptr(), _stream()))
         return out
 
     def reassemble(self, y, images=None):

@@ -293,6 +293,11 @@ struct pserve_cache_s {
     void* apad = nullptr;                     // [P][ph+2][pw+2][C]
     float* partial = nullptr;
     float* scale_shift = nullptr;
+    // per-channel moments of the block input left behind by pserve_split_stats: [P][in_nch][C][2]; in_stats_x = the x
+    // they were taken from (the next forward call on that x uses them once instead of a statistics pass)
+    float* in_partial = nullptr;
+    int32_t in_nch = 0;
+    const void* in_stats_x = nullptr;
     void* h1[PSERVE_MAX_STAGES] = {};         // RES2: first convolution output (slot H1)
     void* r[PSERVE_MAX_STAGES] = {};          // SATTN: stage input (slot R), only with slots
     void* k[PSERVE_MAX_STAGES] = {};          // SATTN: keys (slot K)
@@ -611,6 +616,14 @@ static int cache_create_impl(const pserve_plan_t* plan, const pserve_block_t* bl
     if (conv || gn_sattn) {
         PS_TRY(c->pool.alloc_t(&c->partial, (size_t)plan->P * std::max<int64_t>(c->nsplit, plan->S / 64) * d.G * 2));
         PS_TRY(c->pool.alloc_t(&c->scale_shift, (size_t)plan->n * d.C * 2));
+        // token chunks per patch of the split pass that also takes the input's moments: enough blocks to fill the
+        // chip (x C / 64 channel slabs), a divisor of the patch's 32-token tiles
+        if (d.dtype == PSERVE_BF16 && plan->S % 32 == 0 && d.C % 64 == 0) {
+            int nch = 8;
+            while (nch > 1 && (plan->S / 32) % nch != 0) nch >>= 1;
+            c->in_nch = nch;
+            PS_TRY(c->pool.alloc_t(&c->in_partial, (size_t)plan->P * nch * d.C * 2));
+        }
     }
     for (int s = 0; s < d.n_stages; ++s) {
         if (is_res2(d.stages[s])) PS_TRY(c->pool.alloc(&c->h1[s], TC));
@@ -804,6 +817,20 @@ int pserve_cache_migrate(const pserve_cache_t* old_cache, pserve_cache_t* new_ca
     return PSERVE_OK;
 }
 
+int pserve_split_stats(const pserve_plan_t* plan, const void* const* images, int32_t C, int dtype, void* x,
+                       pserve_cache_t* cache, void* stream) {
+    PS_REQUIRE(plan && images && x && cache, "pserve_split_stats: NULL argument");
+    PS_REQUIRE(cache->plan == plan, "pserve_split_stats: cache belongs to another plan");
+    cache->in_stats_x = nullptr;
+    bool done = false;
+    if (cache->in_partial && dtype == PSERVE_BF16 && cache->block->desc.dtype == PSERVE_BF16 && C == cache->block->desc.C &&
+        g_kernel_mode != 1)
+        PS_TRY(split_with_stats(plan, images, C, x, cache->in_partial, cache->in_nch, (hipStream_t)stream, &done));
+    if (!done) return pserve_split(plan, images, C, dtype, x, stream);
+    cache->in_stats_x = x;
+    return PSERVE_OK;
+}
+
 int pserve_block_forward(const pserve_plan_t* plan, const void* x, const void* ctx, const pserve_block_t* block,
                          pserve_cache_t* cache, const uint8_t* reuse_mask, void* y, void* stream) {
     return pserve_block_forward_temb(plan, x, ctx, nullptr, block, cache, reuse_mask, y, stream);
@@ -825,6 +852,9 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
     hipStream_t st = (hipStream_t)stream;
     ++g_prof.tick;
     const int dt = d.dtype, C = d.C;
+    // moments of this x taken while it was split (single use: later calls on the buffer may see other contents)
+    const bool in_stats = cache->in_stats_x == x && cache->in_partial;
+    cache->in_stats_x = nullptr;
     const int mode = g_kernel_mode == 1 ? 1 : 0;    // kernels: fastest available / plain reference
     const bool push = g_kernel_mode == 0;           // edge stitching fused into the normalisation / separate gather
     const size_t es = dtype_size(dt);
@@ -876,6 +906,12 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
                          const float* rowbias = nullptr, hipEvent_t rowbias_ready = nullptr) -> int {
         GroupNormArgs ga = gn_args(in, w.gn_g[ci], w.gn_b[ci]);
         if (have_partials) { ProfScope ps("gn_stats", st); PS_TRY(gn_finalize(ga, gm, dt, plan->S / 64, st)); }
+        else if (in_stats && in == x) {             // the block input: its moments came with the split
+            GroupNormArgs gi = ga;
+            gi.partial = cache->in_partial;
+            ProfScope ps("gn_stats", st);
+            PS_TRY(gn_finalize(gi, gm, dt, cache->in_nch, st, /*per_channel=*/true));
+        }
         else { ProfScope ps("gn_stats", st); PS_TRY(gn_stats(ga, gm, dt, st)); }
         have_partials = false;
         if (push) {             // normalise + stitch in one pass (push); otherwise the rims are gathered afterwards (pull)
@@ -1043,7 +1079,12 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
                                   3 * C, owner, C, d.eps, gm, dt, cache->u, act, st));
             } else {
                 GroupNormArgs ga = gn_args(rin, w.gn_g[0], w.gn_b[0]);
-                { ProfScope ps("gn_stats", st); PS_TRY(gn_stats(ga, gm, dt, st)); }
+                if (in_stats && rin == x) {         // the block input itself (not the slot that mixes in cached patches)
+                    GroupNormArgs gi = ga;
+                    gi.partial = cache->in_partial;
+                    ProfScope ps("gn_stats", st);
+                    PS_TRY(gn_finalize(gi, gm, dt, cache->in_nch, st, /*per_channel=*/true));
+                } else { ProfScope ps("gn_stats", st); PS_TRY(gn_stats(ga, gm, dt, st)); }
                 { ProfScope ps("gn_apply", st); PS_TRY(gn_apply(ga, gm, dt, false, false, false, cache->u, act, st)); }
             }
             PS_TRY(qkv_proj(cache->u, w.w[0], si, act));

@@ -52,7 +52,11 @@ struct GroupNormArgs {
 };
 int gn_stats(const GroupNormArgs& a, const PatchGeom& g, int dtype, hipStream_t st);
 // second half of gn_stats alone: a.partial already holds [P][slots][G][2] partial sums (filled by a convolution)
-int gn_finalize(const GroupNormArgs& a, const PatchGeom& g, int dtype, int32_t slots, hipStream_t st);
+int gn_finalize(const GroupNormArgs& a, const PatchGeom& g, int dtype, int32_t slots, hipStream_t st, bool per_channel = false);
+// bf16 split that also leaves per-channel moments stats[P][nch][C][2] behind (plan.hip); *done = false where its
+// fast path does not apply (nothing is written then)
+int split_with_stats(const pserve_plan_t* plan, const void* const* images, int32_t C, void* x, float* stats, int32_t nch,
+                     hipStream_t st, bool* done);
 // y = x*scale+shift (then SiLU if silu).  padded: write into the interior of the padded patch buffer
 // [P][ph+2][pw+2][C]; else plain [T][C].  Only patches of `act` are written.  stitch (padded, all patches):
 // border tokens also fill the neighbours' ring slots / zero the own ring at image edges (no halo_gather needed).

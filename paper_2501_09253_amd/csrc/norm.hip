@@ -146,20 +146,23 @@ constexpr int GN_FIN_THREADS = 256;
 // Partial i of a patch covers rows(i) = the tokens of chunk i (S split into `nsplit` chunks) times C/G channels;
 // sum n_i mean_i and sum (M2_i + n_i mean_i^2) in fp64 give the mean and the M2 of the whole request (the fp64 sums
 // carry 16 digits against the eight or so that |mean| / deviation can cost).
+// epg = entries per group in a partial row: 1 (moments of whole groups) or C/G (moments of single channels, as the
+// split pass leaves them: partial[p][chunk][C][2]).
 template <typename T>
 __global__ void gn_finalize_kernel(const float* __restrict__ partial, const int32_t* __restrict__ request_offset,
                                    const T* __restrict__ gamma, const T* __restrict__ beta, int32_t C, int32_t G,
-                                   int32_t S, int32_t nsplit, float eps, float* __restrict__ scale_shift) {
+                                   int32_t S, int32_t nsplit, int32_t epg, float eps, float* __restrict__ scale_shift) {
     const int s = blockIdx.x, g = blockIdx.y;
     const int p0 = request_offset[s], p1 = request_offset[s + 1];
-    const int items = (p1 - p0) * nsplit;
+    const int items = (p1 - p0) * nsplit * epg;
     const int cg = C / G;
     const int chunk = (S + nsplit - 1) / nsplit;
     double a = 0.0, b = 0.0;
     for (int i = threadIdx.x; i < items; i += GN_FIN_THREADS) {
-        const float* src = partial + (((int64_t)p0 * nsplit + i) * G + g) * 2;
-        const int sp = i % nsplit;
-        const double n = (double)max(min(S, (sp + 1) * chunk) - sp * chunk, 0) * cg;
+        const int row = i / epg, e = i - row * epg;
+        const float* src = partial + (((int64_t)p0 * nsplit + row) * G * epg + g * epg + e) * 2;
+        const int sp = row % nsplit;
+        const double n = (double)max(min(S, (sp + 1) * chunk) - sp * chunk, 0) * (cg / epg);
         const double m = (double)src[0];
         a += n * m;
         b += (double)src[1] + n * m * m;
@@ -428,17 +431,18 @@ int gn_stats(const GroupNormArgs& a, const PatchGeom& g, int dtype, hipStream_t 
     else
         gn_partial_kernel<float><<<grid, TL * CV, lds, st>>>((const float*)a.x, a.C, a.G, g.S, a.nsplit, TL, a.partial);
     PS_TRY(check_launch("gn_partial_kernel"));
-    return gn_finalize(a, g, dtype, a.nsplit, st);
+    return gn_finalize(a, g, dtype, a.nsplit, st, false);
 }
 
-int gn_finalize(const GroupNormArgs& a, const PatchGeom& g, int dtype, int32_t slots, hipStream_t st) {
+int gn_finalize(const GroupNormArgs& a, const PatchGeom& g, int dtype, int32_t slots, hipStream_t st, bool per_channel) {
     dim3 fgrid(a.n, a.G);
+    const int epg = per_channel ? a.C / a.G : 1;
     if (dtype == PSERVE_BF16)
         gn_finalize_kernel<uint16_t><<<fgrid, GN_FIN_THREADS, 0, st>>>(a.partial, a.request_offset, (const uint16_t*)a.gamma,
-                                                                       (const uint16_t*)a.beta, a.C, a.G, g.S, slots, a.eps, a.scale_shift);
+                                                                       (const uint16_t*)a.beta, a.C, a.G, g.S, slots, epg, a.eps, a.scale_shift);
     else
         gn_finalize_kernel<float><<<fgrid, GN_FIN_THREADS, 0, st>>>(a.partial, a.request_offset, (const float*)a.gamma,
-                                                                    (const float*)a.beta, a.C, a.G, g.S, slots, a.eps, a.scale_shift);
+                                                                    (const float*)a.beta, a.C, a.G, g.S, slots, epg, a.eps, a.scale_shift);
     return check_launch("gn_finalize_kernel");
 }
 

@@ -231,6 +231,76 @@ split_vec_kernel(ImagePtrs imgs, int slot0, int patch0, const int32_t* __restric
     }
 }
 
+// Split (bf16 fast path) that also leaves the moments of every channel behind, for a GroupNorm that reads x next:
+// block = (patch, one of `nch` token chunks, 64 channels); it walks the chunk's 32-token tiles like split_vec_kernel
+// and keeps, per thread, the sums of (x - K) and (x - K)^2 of its eight channels (K = the channel's value in the
+// chunk's first token: nothing is lost when the mean is far from zero).  Per (patch, chunk, channel) it stores the
+// mean and the sum of squared deviations M2 of the chunk's tokens: stats[((p * nch + chunk) * C + c) * 2 + {0, 1}],
+// which the GroupNorm finalize merges (fixed order, no atomics).
+__global__ void __launch_bounds__(256)
+split_stats_kernel(ImagePtrs imgs, int slot0, int patch0, const int32_t* __restrict__ sorted_hw,
+                   const int32_t* __restrict__ owner, const int32_t* __restrict__ rc, int32_t ph, int32_t pw, int32_t C,
+                   int32_t nch, uint16_t* __restrict__ x, float* __restrict__ stats) {
+    __shared__ __attribute__((aligned(16))) uint16_t tile[32][72];      // [token][channel], rows padded to 144 bytes
+    __shared__ float red[2][32][65];
+    __shared__ float kk[64];
+    const int S = ph * pw, tiles = S / 32, tpc = tiles / nch;
+    const int p = patch0 + blockIdx.x / nch, tc = blockIdx.x % nch;
+    const int c0 = blockIdx.y * 64;
+    if (rc[2 * p] < 0) return;                  // a text patch: not part of any image
+    const int s = owner[p];
+    const int H = sorted_hw[2 * s], W = sorted_hw[2 * s + 1];
+    const uint16_t* img = (const uint16_t*)imgs.p[s - slot0];
+    const int tid = threadIdx.x;
+    const int ich = tid >> 2, iq = tid & 3;     // image side: channel ich, 8 pixels starting at token t0 + 8*iq
+    const int ptk = tid >> 3, pq = tid & 7;     // patch side: token t0 + ptk, channels 8*pq .. +8
+    const uint16_t* ibase = img + ((int64_t)(c0 + ich) * H + rc[2 * p] * ph) * W + rc[2 * p + 1] * pw;
+    typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+    float s1[8], s2[8], k0[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { s1[e] = 0.f; s2[e] = 0.f; k0[e] = 0.f; }
+    for (int ti = 0; ti < tpc; ++ti) {
+        const int t0 = (tc * tpc + ti) * 32;
+        const int it = t0 + 8 * iq, iy = it / pw, ix = it - iy * pw;
+        const u32x4 v = *reinterpret_cast<const u32x4*>(ibase + (int64_t)iy * W + ix);
+        if (ti) __syncthreads();                // the previous tile has been read
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            tile[8 * iq + 2 * k][ich] = (uint16_t)(v[k] & 0xFFFFu);
+            tile[8 * iq + 2 * k + 1][ich] = (uint16_t)(v[k] >> 16);
+        }
+        __syncthreads();
+        const u32x4 o = *reinterpret_cast<const u32x4*>(&tile[ptk][8 * pq]);
+        if (ti == 0) {
+            const u32x4 f = *reinterpret_cast<const u32x4*>(&tile[0][8 * pq]);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) { k0[2 * k] = __uint_as_float(f[k] << 16); k0[2 * k + 1] = __uint_as_float(f[k] & 0xFFFF0000u); }
+        }
+        *reinterpret_cast<u32x4*>(x + ((int64_t)p * S + t0 + ptk) * C + c0 + 8 * pq) = o;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float lo = __uint_as_float(o[k] << 16) - k0[2 * k], hi = __uint_as_float(o[k] & 0xFFFF0000u) - k0[2 * k + 1];
+            s1[2 * k] += lo; s2[2 * k] = fmaf(lo, lo, s2[2 * k]);
+            s1[2 * k + 1] += hi; s2[2 * k + 1] = fmaf(hi, hi, s2[2 * k + 1]);
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { red[0][ptk][8 * pq + e] = s1[e]; red[1][ptk][8 * pq + e] = s2[e]; }
+    if (ptk == 0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) kk[8 * pq + e] = k0[e];
+    }
+    __syncthreads();
+    if (tid < 64) {
+        float a = 0.f, b = 0.f;
+        for (int l = 0; l < 32; ++l) { a += red[0][l][tid]; b += red[1][l][tid]; }      // fixed order
+        const float nt = (float)(tpc * 32), inv = 1.f / nt;
+        float* dst = stats + (((int64_t)p * nch + tc) * C + c0 + tid) * 2;
+        dst[0] = kk[tid] + a * inv;
+        dst[1] = fmaxf(b - a * a * inv, 0.f);
+    }
+}
+
 // Text tokens of every request <-> the text patches of the joint token matrix.  One thread per (slot, text row
 // incl. padding, 16-byte vector).  TO_PATCH: text [n][L][C] (caller order) -> x, padding rows zeroed; else x -> text.
 template <bool TO_PATCH>
@@ -297,6 +367,33 @@ static int run_split(const pserve_plan_t* plan, void* const* images, int32_t C, 
     return PSERVE_OK;
 }
 
+
+// pserve_split (bf16 fast path only) that also writes the per-channel moments of x; *done = false (and nothing is
+// written) where the fast path does not apply
+int split_with_stats(const pserve_plan_t* plan, const void* const* images, int32_t C, void* x, float* stats, int32_t nch,
+                     hipStream_t st, bool* done) {
+    *done = false;
+    const auto& ro = plan->h_tab[PSERVE_TAB_REQUEST_OFFSET];
+    const auto& perm = plan->h_tab[PSERVE_TAB_PERM];
+    bool vec = plan->pw % 8 == 0 && plan->S % 32 == 0 && C % 64 == 0 && ((uintptr_t)x & 15) == 0 && nch >= 1 &&
+               (plan->S / 32) % nch == 0 && plan->text_len == 0;
+    for (int i = 0; i < plan->n && vec; ++i)
+        vec = images[i] && plan->h_sorted_hw[2 * i + 1] % 8 == 0 && ((uintptr_t)images[i] & 15) == 0;
+    if (!vec) return PSERVE_OK;
+    for (int s0 = 0; s0 < plan->n; s0 += IMG_CHUNK) {
+        const int s1 = std::min(plan->n, s0 + IMG_CHUNK);
+        ImagePtrs ip;
+        memset(&ip, 0, sizeof(ip));
+        for (int s = s0; s < s1; ++s) ip.p[s - s0] = (void*)images[perm[s]];
+        const int patch0 = ro[s0], npatch = ro[s1] - ro[s0];
+        dim3 grid(npatch * nch, (unsigned)(C / 64));
+        split_stats_kernel<<<grid, 256, 0, st>>>(ip, s0, patch0, plan->d_sorted_hw, plan->d_tab[PSERVE_TAB_PATCH_OWNER],
+                                                 plan->d_tab[PSERVE_TAB_PATCH_RC], plan->ph, plan->pw, C, nch, (uint16_t*)x, stats);
+        PS_TRY(check_launch("split_stats_kernel"));
+    }
+    *done = true;
+    return PSERVE_OK;
+}
 }  // namespace pserve
 
 using namespace pserve;
