@@ -914,6 +914,8 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
         }
         else { ProfScope ps("gn_stats", st); PS_TRY(gn_stats(ga, gm, dt, st)); }
         have_partials = false;
+        // reused patches are not convolved: of them only the border tokens are normalised (the neighbours' rings)
+        ga.rim_only = reuse_mask;
         if (push) {             // normalise + stitch in one pass (push); otherwise the rims are gathered afterwards (pull)
             ProfScope ps("gn_apply_stitch", st);
             PS_TRY(gn_apply(ga, gm, dt, /*silu=*/true, /*padded=*/true, /*stitch=*/true, cache->apad, all, st));

@@ -49,6 +49,7 @@ struct GroupNormArgs {
     const int32_t* request_offset;   // [n+1]
     const int32_t* owner;      // [P]
     const int32_t* neighbour;  // [P][8] (stitching only)
+    const uint8_t* rim_only = nullptr;   // [P] or nullptr; apply pass into the padded layout: only the border tokens of these patches
 };
 int gn_stats(const GroupNormArgs& a, const PatchGeom& g, int dtype, hipStream_t st);
 // second half of gn_stats alone: a.partial already holds [P][slots][G][2] partial sums (filled by a convolution)

@@ -224,15 +224,49 @@ __device__ __forceinline__ void stitch_store(T* __restrict__ out, const int32_t 
         }
 }
 
+// rim_only (padded output): patches with rim_only[p] != 0 are not convolved themselves (their result is reused); only
+// their border tokens are normalised, because the neighbours' rings need them.
 template <typename T, bool SILU, bool PADDED, bool STITCH>
 __global__ void gn_apply_kernel(const T* __restrict__ x, const float* __restrict__ scale_shift,
                                 const int32_t* __restrict__ owner, const int32_t* __restrict__ neighbour, PatchGeom gm,
-                                int32_t C, int32_t nsplit, int32_t TL, ActiveList act, T* __restrict__ out) {
+                                int32_t C, int32_t nsplit, int32_t TL, ActiveList act, const uint8_t* __restrict__ rim_only,
+                                T* __restrict__ out) {
     constexpr int VN = Vec<T>::N;
     int p = blockIdx.x;
     if (act.active) {
         if (p >= *act.count) return;
         p = act.active[p];
+    }
+    if (PADDED && rim_only && rim_only[p]) {
+        // border token b of the patch: top row, bottom row, then left / right column of the rows between
+        const int CVb = C / VN, cvb = threadIdx.x % CVb;
+        const int nb_tok = gm.ph > 1 ? 2 * gm.pw + 2 * (gm.ph - 2) : gm.pw;
+        const int per = (nb_tok + nsplit - 1) / nsplit;
+        const int b0 = blockIdx.y * per, b1 = min(nb_tok, b0 + per);
+        if (b0 >= b1) return;
+        float sc[VN], sh[VN];
+        const float* ss = scale_shift + ((int64_t)owner[p] * C + cvb * VN) * 2;
+#pragma unroll
+        for (int e = 0; e < VN; ++e) { sc[e] = scale_shift ? ss[2 * e] : 1.f; sh[e] = scale_shift ? ss[2 * e + 1] : 0.f; }
+        int32_t nbr[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) nbr[k] = STITCH ? neighbour[8 * p + k] : -1;
+        for (int b = b0 + (int)threadIdx.x / CVb; b < b1; b += TL) {
+            int y, xx;
+            if (b < gm.pw) { y = 0; xx = b; }
+            else if (b < 2 * gm.pw) { y = gm.ph - 1; xx = b - gm.pw; }
+            else { const int r = b - 2 * gm.pw; y = 1 + (r >> 1); xx = (r & 1) ? gm.pw - 1 : 0; }
+            float v[VN];
+            load_vec<T>(x + ((int64_t)p * gm.S + y * gm.pw + xx) * C + cvb * VN, v);
+#pragma unroll
+            for (int e = 0; e < VN; ++e) {
+                v[e] = fmaf(v[e], sc[e], sh[e]);
+                if (SILU) v[e] = silu_f(v[e]);
+            }
+            store_vec<T>(out + ((int64_t)p * gm.pS + (y + 1) * gm.ppw + xx + 1) * C + cvb * VN, v);
+            if (STITCH) stitch_store<T>(out, nbr, gm, p, y, xx, C, cvb * VN, v);
+        }
+        return;
     }
     const int CV = C / VN;
     const int cv = threadIdx.x % CV, tl = threadIdx.x / CV;
@@ -459,7 +493,7 @@ static void launch_apply(const GroupNormArgs& a, const PatchGeom& g, bool silu, 
     const int nt = TL * CV;
 #define PS_APPLY(SI, PA, ST)                                                                                      \
     gn_apply_kernel<T, SI, PA, ST><<<grid, nt, 0, st>>>((const T*)a.x, a.scale_shift, a.owner, a.neighbour, g, a.C, \
-                                                        nsplit, TL, act, (T*)out)
+                                                        nsplit, TL, act, a.rim_only, (T*)out)
     if (silu && padded && stitch) PS_APPLY(true, true, true);
     else if (padded && stitch) PS_APPLY(false, true, true);
     else if (silu && padded) PS_APPLY(true, true, false);
