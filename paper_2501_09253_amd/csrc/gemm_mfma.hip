@@ -87,7 +87,11 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[B
     constexpr int NIT = WM * 4 / 64;
     const bool HAS_RES = !GEGLU && a.res != nullptr;
     const uint16_t* res_row[NIT];
-    u32x4 rres[2][NIT];
+    // residual of the lane's items: with a small wavefront tile all tile columns are fetched at once (every column
+    // otherwise waits out a memory round trip of its own, with one column of work to cover it), else one column ahead
+    constexpr bool RES_ALL = TNO * NIT <= 12;
+    constexpr int RSETS = RES_ALL ? TNO : 2;
+    u32x4 rres[RSETS][NIT];
 #pragma unroll
     for (int t = 0; t < NIT; ++t) {
         const int item = t * 64 + lane;
@@ -96,7 +100,9 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[B
     }
     if (HAS_RES) {
 #pragma unroll
-        for (int t = 0; t < NIT; ++t) rres[0][t] = *reinterpret_cast<const u32x4*>(res_row[t] + n0 + wn * WN);
+        for (int jj = 0; jj < (RES_ALL ? TNO : 1); ++jj)
+#pragma unroll
+            for (int t = 0; t < NIT; ++t) rres[jj][t] = *reinterpret_cast<const u32x4*>(res_row[t] + n0 + wn * WN + jj * 32);
     }
     // per-request bias (time embedding): one value per column when all rows of the wavefront's tile belong to one
     // request (rows are ordered by request, so first == last decides), else looked up per element
@@ -245,7 +251,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[B
             for (int e = 0; e < 16; ++e) ep[(i * 32 + 8 * (e >> 2) + 4 * fh + (e & 3)) * EP_LD + fr] = vals[i][e];
         __builtin_amdgcn_wave_barrier();
         // prefetch the residual of the next tile column while this one is finished
-        if (HAS_RES && j + 1 < TNO) {
+        if (HAS_RES && !RES_ALL && j + 1 < TNO) {
 #pragma unroll
             for (int t = 0; t < NIT; ++t) rres[(j + 1) & 1][t] = *reinterpret_cast<const u32x4*>(res_row[t] + pcol + 32);
         }
@@ -259,7 +265,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, f32x16 (&acc)[B
             const int64_t tk = tok < 0 ? 0 : tok;                   // rows past the end read row 0 and store nothing
             float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
             if (HAS_RES) {
-                const u32x4 r = rres[j & 1][t];
+                const u32x4 r = rres[RES_ALL ? j : (j & 1)][t];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     v[2 * q] += __uint_as_float(r[q] << 16);
@@ -352,7 +358,8 @@ gemm_mfma_kernel(GemmArgs a) {
     const int64_t a_panel = (int64_t)BM * a.K * a.taps * 2;
     const int gm = (int)max((int64_t)1, min((int64_t)mx, (int64_t)(2560 * 1024) / a_panel));
     const int slots = mx * n_tiles, slot_step = gridDim.x >> 3;
-    const int m_limit = (a.tokens_are_rows && a.act.active) ? *a.act.count * a.geom.S : a.M;   // rows that exist
+    const int act_count = (a.tokens_are_rows && a.act.active) ? *a.act.count : 0;              // computed patches
+    const int m_limit = (a.tokens_are_rows && a.act.active) ? act_count * a.geom.S : a.M;      // rows that exist
     // tile of a slot; false when it has no rows
     auto decode = [&](int slot, int& m0, int& n0) -> bool {
         const int grp = slot / (gm * n_tiles), r_in = slot - grp * (gm * n_tiles);
@@ -388,14 +395,22 @@ gemm_mfma_kernel(GemmArgs a) {
     // operand pointers and the row -> token table `tok_tab` of tile (tm0, tn0)
 #define PS_SETUP(tm0, tn0, tok_tab)                                                                               \
     {                                                                                                             \
+        /* the patch ids of all rows first (one memory round trip for the tile, not one per row) */              \
+        int act_p[A_LD];                                                                                          \
+        if (a.tokens_are_rows && a.act.active) {                                                                  \
+            _Pragma("unroll") for (int i = 0; i < A_LD; ++i) {                                                    \
+                const int pi = ((tm0) + lr + i * 32) / a.geom.S;                                                  \
+                act_p[i] = pi < act_count ? a.act.active[pi] : -1;                                                \
+            }                                                                                                     \
+        }                                                                                                         \
         _Pragma("unroll") for (int i = 0; i < A_LD; ++i) {                                                        \
             const int row = lr + i * 32;                                                                          \
             int64_t tok = (tm0) + row;                                                                            \
             bool valid;                                                                                           \
             if (a.tokens_are_rows && a.act.active) {                                                              \
-                const int pi = (int)(tok / a.geom.S);                                                             \
-                valid = pi < *a.act.count;                                                                        \
-                tok = valid ? (int64_t)a.act.active[pi] * a.geom.S + (tok - (int64_t)pi * a.geom.S) : 0;          \
+                const int pi = (int)tok / a.geom.S;                                                               \
+                valid = act_p[i] >= 0;                                                                            \
+                tok = valid ? (int64_t)act_p[i] * a.geom.S + ((int)tok - pi * a.geom.S) : 0;                      \
             } else {                                                                                              \
                 valid = tok < a.M;                                                                                \
                 if (!valid) tok = 0;                                                                              \
@@ -479,6 +494,7 @@ gemm_mfma_kernel(GemmArgs a) {
     constexpr int NR = TM + TN;                     // fragment reads per sub-step
     constexpr int R_PER = (NR + NM - 1) / NM;       // fragment reads slipped in behind one MFMA
     constexpr int L_PER = (LD + NM - 1) / NM;       // loads slipped in behind one MFMA of sub-step 3
+    constexpr bool SKIP_TAIL = NS == 2;
 
     int buf = 0;                                    // token table of the current tile
     PS_SETUP(m0, n0, s_tok2);
@@ -507,6 +523,10 @@ gemm_mfma_kernel(GemmArgs a) {
             PS_OFFSETS(tap, kc);                    // step kt + NS goes into this step's stage
             if (++issued < KT) { if (++kc == kchunks) { kc = 0; ++tap; } } else { issued = KT - 1; }
             u32x4* dst = ring + rd * STAGE_V + wave * 64;
+            // With two stages the barrier waits for ALL loads in flight (vmcnt(0)), so the last steps of a tile need not
+            // keep the count up with loads of steps that do not exist: they issue none, and nothing is in flight when
+            // the tile's epilogue starts (it used to wait out a memory round trip for them).
+            const bool refill = kt + NS < KT;
 #pragma unroll
             for (int ks = 0; ks < BK / 16; ++ks) {
                 if (ks == BK / 16 - 1) {
@@ -526,7 +546,7 @@ gemm_mfma_kernel(GemmArgs a) {
                             if (ks < BK / 16 - 1) { PS_READ_ONE((ks + 1) & 1, cur, ks + 1, q * R_PER + u); }
                             else { PS_READ_ONE(0, nxt, 0, q * R_PER + u); }
                         }
-                        if (ks == BK / 16 - 1) {
+                        if (ks == BK / 16 - 1 && (!SKIP_TAIL || refill)) {
 #pragma unroll
                             for (int u = 0; u < L_PER; ++u) PS_LOAD(dst, a_off, b_off, q * L_PER + u);
                         }
