@@ -63,8 +63,10 @@ def kernel_work(cfg, n_active_tokens, patch=None):
       linear_*     2*Cin*Cout flops per token
       attn_self    4*N_i*C flops per query token of image i
       attn_cross   4*L*C flops per token
-      gn_stats     b*C bytes per token (one read)
-      gn_apply     2*b*C bytes per computed token (read + write); gn_apply_stitch (all tokens) adds b*C*ring per patch (rim writes)
+      gn_stats     b*C bytes per token (one read); gn_finalize = the merge of partial moments alone (where the split pass or
+                   the previous convolution left them behind): no tensor traffic
+      gn_apply     2*b*C bytes per computed token (read + write); gn_apply_stitch: computed tokens plus the border tokens of
+                   reused patches, and b*C*ring per patch (rim writes)
       halo_gather  2*b*C*ring bytes per patch (read + write of the ring)
       reuse_copy   2*b*C bytes per token
       layer_norm   2*b*C bytes per computed token (read + write)
@@ -73,6 +75,7 @@ def kernel_work(cfg, n_active_tokens, patch=None):
     C, T, Ta = cfg.C, cfg.T, n_active_tokens
     ph, pw = patch if patch is not None else cfg.patch
     ring = 2 * (pw + 2) + 2 * ph
+    border = 2 * pw + 2 * (ph - 2) if ph > 1 else pw        # border tokens of a patch
     Pa = Ta // (ph * pw)
     P = T // (ph * pw)
     frac = Ta / T
@@ -96,7 +99,7 @@ def kernel_work(cfg, n_active_tokens, patch=None):
         "attn_cross": (4.0 * cfg.ctx_len * C * Ta, b * 2.0 * C * Ta),
         "gn_stats": (0.0, 1.0 * b * C * T),
         "gn_apply": (0.0, 2.0 * b * C * Ta),
-        "gn_apply_stitch": (0.0, 2.0 * b * C * T + 1.0 * b * C * ring * P),
+        "gn_apply_stitch": (0.0, 2.0 * b * C * (Ta + (P - Pa) * border) + 1.0 * b * C * ring * P),
         "halo_gather": (0.0, 2.0 * b * C * ring * Pa),
         "reuse_copy": (0.0, 2.0 * b * C * T),
         "layer_norm": (0.0, 2.0 * b * C * Ta),
@@ -241,7 +244,9 @@ def measure(cfg_id, steps, warmup, all_kernels=False, events=True, patch=None, p
         us = timed(lambda: run.plan.patch_mse(run.x, y))
         gbs = 2.0 * cfg.T * cfg.C * es / (us * 1e-6) / 1e9
         extras["patch_mse"] = {"avg_us": us, "gbs": gbs, "frac_hbm": gbs / PEAK_HBM_GBS}
-        for name, fn in (("split", lambda: run.plan.split(run.images, out=run.x)), ("reassemble", lambda: run.plan.reassemble(y, outs))):
+        for name, fn in (("split", lambda: run.plan.split(run.images, out=run.x)),
+                         ("split_stats", lambda: run.plan.split(run.images, out=run.x, cache=run.cache)),
+                         ("reassemble", lambda: run.plan.reassemble(y, outs))):
             us = timed(fn)
             gbs = 2.0 * cfg.T * cfg.C * es / (us * 1e-6) / 1e9
             extras[name] = {"avg_us": us, "gbs": gbs, "frac_hbm": gbs / PEAK_HBM_GBS}

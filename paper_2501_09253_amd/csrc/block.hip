@@ -905,11 +905,11 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
     auto norm_conv = [&](const void* in, const StageWeights& w, int ci, const void* res, void* out, bool stats_next,
                          const float* rowbias = nullptr, hipEvent_t rowbias_ready = nullptr) -> int {
         GroupNormArgs ga = gn_args(in, w.gn_g[ci], w.gn_b[ci]);
-        if (have_partials) { ProfScope ps("gn_stats", st); PS_TRY(gn_finalize(ga, gm, dt, plan->S / 64, st)); }
+        if (have_partials) { ProfScope ps("gn_finalize", st); PS_TRY(gn_finalize(ga, gm, dt, plan->S / 64, st)); }
         else if (in_stats && in == x) {             // the block input: its moments came with the split
             GroupNormArgs gi = ga;
             gi.partial = cache->in_partial;
-            ProfScope ps("gn_stats", st);
+            ProfScope ps("gn_finalize", st);
             PS_TRY(gn_finalize(gi, gm, dt, cache->in_nch, st, /*per_channel=*/true));
         }
         else { ProfScope ps("gn_stats", st); PS_TRY(gn_stats(ga, gm, dt, st)); }
@@ -1084,7 +1084,7 @@ int pserve_block_forward_temb(const pserve_plan_t* plan, const void* x, const vo
                 if (in_stats && rin == x) {         // the block input itself (not the slot that mixes in cached patches)
                     GroupNormArgs gi = ga;
                     gi.partial = cache->in_partial;
-                    ProfScope ps("gn_stats", st);
+                    ProfScope ps("gn_finalize", st);
                     PS_TRY(gn_finalize(gi, gm, dt, cache->in_nch, st, /*per_channel=*/true));
                 } else { ProfScope ps("gn_stats", st); PS_TRY(gn_stats(ga, gm, dt, st)); }
                 { ProfScope ps("gn_apply", st); PS_TRY(gn_apply(ga, gm, dt, false, false, false, cache->u, act, st)); }
