@@ -243,7 +243,8 @@ __global__ void gn_apply_kernel(const T* __restrict__ x, const float* __restrict
         // border token b of the patch: top row, bottom row, then left / right column of the rows between
         const int CVb = C / VN, cvb = threadIdx.x % CVb;
         const int nb_tok = gm.ph > 1 ? 2 * gm.pw + 2 * (gm.ph - 2) : gm.pw;
-        const int per = (nb_tok + nsplit - 1) / nsplit;
+        // a few blocks with about four border tokens per thread row (as for whole patches); the others leave at once
+        const int per = max((nb_tok + nsplit - 1) / nsplit, 4 * TL);
         const int b0 = blockIdx.y * per, b1 = min(nb_tok, b0 + per);
         if (b0 >= b1) return;
         float sc[VN], sh[VN];
