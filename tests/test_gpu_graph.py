@@ -14,9 +14,12 @@ from harness import GpuRun, to_dev
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("stages,reuse", [((wl.RES2, wl.SATTN), False), ((wl.LSATTN, wl.LXATTN, wl.LFFN), False),
-                                          ((wl.RES2, wl.SATTN), True)])
-def test_step_replayed_from_a_graph_equals_eager(stages, reuse):
+@pytest.mark.parametrize("stages,reuse,stats", [((wl.RES2, wl.SATTN), False, False), ((wl.LSATTN, wl.LXATTN, wl.LFFN), False, False),
+                                                ((wl.RES2, wl.SATTN), True, False), ((wl.RES2, wl.SATTN), False, True),
+                                                ((wl.RES2, wl.SATTN), True, True)])
+def test_step_replayed_from_a_graph_equals_eager(stages, reuse, stats):
+    """stats: the split that also takes the first norm's moments (pserve_split_stats); the forward call recorded behind
+    it merges them, in the capture as in the eager step."""
     cfg = wl.custom_config([(32, 32), (16, 48), (16, 16)], (16, 16), C=128, G=32, heads=2, stages=stages, dtype="bf16",
                            ctx_len=77, ctx_dim=128, reuse_p=0.4 if reuse else 0.0, seed=71)
     w = wl.make_workload(cfg)
@@ -31,7 +34,7 @@ def test_step_replayed_from_a_graph_equals_eager(stages, reuse):
     outs = [torch.empty_like(im) for im in run.images]
 
     def step():
-        run.plan.split(run.images, out=x)
+        run.plan.split(run.images, out=x, cache=run.cache if stats else None)
         run.cache.forward(x, run.ctx, mask, y=y)
         run.plan.reassemble(y, images=outs)
 
